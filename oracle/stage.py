@@ -1,0 +1,160 @@
+"""One pipeline stage under the V-TiMePReSt / I-TiMePReSt weight rules (fp64).
+
+Follows, in event order:
+  forward   Section "V-TiMePReSt" / "I-TiMePReSt": every micro-batch forward
+            reads the latest weights present at the stage; under the
+            I-policies that version is kept (stashed) for the mini-batch.
+  backward  one pass for the whole mini-batch (Section "Methodology"), on the
+            latest weights (V) or on the intermediate weights built from the
+            stashed version and the degree of staleness (I; Eq. 1-2).  The
+            activations saved in forward are reused as they are; the
+            prescribed weights enter through dx = dz . W_b.
+  retention Section "Memory Overhead": a stale version stays until the last
+            mini-batch that used it in forward has built its intermediate
+            weights; V keeps nothing but the latest version.
+  update    after every mini-batch (Section "Pipeline Parallelism"): SGD with
+            momentum applied to the latest weights, producing the next
+            version.  The paper names no optimiser; the form is
+            m <- mu*m + g, W <- W - lr*m (m starts at zero).
+
+Parameters of a stage are a flat list [W0, b0, W1, b1, ...]; every entry is
+versioned, stashed and blended alike.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional
+
+import numpy as np
+
+from . import layers as L
+from .significance import coefficients
+
+
+class StageError(RuntimeError):
+    pass
+
+
+class Stage:
+    def __init__(self, layer_specs, params: List[np.ndarray], *, policy: str, lam: float,
+                 lr: float, momentum: float, n: int, first_stage: bool = False):
+        self.specs = list(layer_specs)
+        self.policy = policy
+        self.lam = float(lam)
+        self.lr = float(lr)
+        self.mu = float(momentum)
+        self.n = int(n)
+        self.first_stage = first_stage
+        self.latest = 0                                    # number of updates applied
+        self.weights: Dict[int, List[np.ndarray]] = {0: [np.array(p, dtype=np.float64) for p in params]}
+        self.refcnt: Dict[int, int] = {0: 0}               # forward users that have not blended yet
+        self.m = [np.zeros_like(p) for p in self.weights[0]]
+        self.g: Optional[List[np.ndarray]] = None          # gradient of the last backward
+        self.inflight: Dict[int, dict] = {}                # mini-batch -> forward record
+        self.evicted: List[int] = []
+        self.last_W_b: Optional[List[np.ndarray]] = None
+        self.trace: List[tuple] = []                       # (event, mb, v_f, v_now, delta)
+
+    # -- forward ---------------------------------------------------------
+    def forward(self, mb: int, ub: int, x: np.ndarray) -> np.ndarray:
+        rec = self.inflight.get(mb)
+        if rec is None:
+            if ub != 0:
+                raise StageError("micro-batches of a mini-batch must arrive in order")
+            rec = {"v_f": self.latest, "saved": [], "versions": []}
+            self.inflight[mb] = rec
+            if self.policy != "latest":
+                self.refcnt[self.latest] += 1              # stash: one user per mini-batch
+        if ub != len(rec["saved"]) or ub >= self.n:
+            raise StageError("micro-batch index out of order")
+        if self.policy != "latest" and rec["v_f"] != self.latest:
+            raise StageError("update landed between micro-batches of one mini-batch")
+        W = self.weights[self.latest]
+        rec["versions"].append(self.latest)
+        saved = []
+        a = np.asarray(x, dtype=np.float64)
+        for li, spec in enumerate(self.specs):
+            z = L.dense_forward(a, W[2 * li], W[2 * li + 1])
+            saved.append((a, z))
+            a = L.act_forward(z, spec.act)
+        rec["saved"].append(saved)
+        return a
+
+    # -- backward weights ------------------------------------------------
+    def backward_weights(self, mb: int):
+        """W_b for mini-batch mb and the (v_f, v_now, delta) triple behind it."""
+        rec = self.inflight[mb]
+        v_now = self.latest
+        if self.policy == "latest":
+            return self.weights[v_now], (rec["versions"][0], v_now, 0)
+        v_f = rec["v_f"]
+        if v_f not in self.weights:
+            raise StageError(f"version {v_f} is no longer stashed")
+        delta = v_now - v_f
+        alpha, beta = coefficients(self.policy, delta, self.lam)
+        stale, latest = self.weights[v_f], self.weights[v_now]
+        if delta == 0:
+            W_b = [s.copy() for s in stale]                # no staleness: stale = latest = intermediate
+        else:
+            W_b = [alpha * s + beta * l for s, l in zip(stale, latest)]
+        return W_b, (v_f, v_now, delta)
+
+    # -- backward --------------------------------------------------------
+    def backward(self, mb: int, dy: np.ndarray) -> Optional[np.ndarray]:
+        rec = self.inflight.get(mb)
+        if rec is None or len(rec["saved"]) != self.n:
+            raise StageError("backward needs all n micro-batch forwards of the mini-batch")
+        W_b, (v_f, v_now, delta) = self.backward_weights(mb)
+        self.last_W_b = W_b
+        self.trace.append(("B", mb, v_f, v_now, delta))
+        dy = np.asarray(dy, dtype=np.float64)
+        rows = dy.shape[0] // self.n
+        g = [np.zeros_like(p) for p in self.weights[self.latest]]
+        dx_parts = []
+        for ub in range(self.n):                           # one backward, all micro-batches
+            da = dy[ub * rows:(ub + 1) * rows]
+            saved = rec["saved"][ub]
+            for li in reversed(range(len(self.specs))):
+                x_in, z = saved[li]
+                dz = da * L.act_derivative(z, self.specs[li].act)
+                dW, db, da = L.dense_backward(dz, x_in, W_b[2 * li])
+                g[2 * li] += dW
+                g[2 * li + 1] += db
+            dx_parts.append(da)
+        self.g = g
+        # the intermediate weights are built: this mini-batch no longer needs its stale version
+        if self.policy != "latest":
+            self.refcnt[rec["v_f"]] -= 1
+            self._evict_if_unused(rec["v_f"])
+        del self.inflight[mb]
+        return None if self.first_stage else np.concatenate(dx_parts, axis=0)
+
+    # -- update ----------------------------------------------------------
+    def update(self, mb: int) -> int:
+        if self.g is None:
+            raise StageError("update without a gradient")
+        old = self.latest
+        W = self.weights[old]
+        new = []
+        for i, (w, g) in enumerate(zip(W, self.g)):
+            self.m[i] = self.mu * self.m[i] + g
+            new.append(w - self.lr * self.m[i])
+        self.latest = old + 1
+        self.weights[self.latest] = new
+        self.refcnt[self.latest] = 0
+        self.g = None
+        self.trace.append(("U", mb, old, self.latest, 0))
+        self._evict_if_unused(old)                         # V: always; I: unless still stashed
+        return self.latest
+
+    def _evict_if_unused(self, v: int) -> None:
+        if v != self.latest and v in self.weights and self.refcnt.get(v, 0) == 0:
+            del self.weights[v]
+            del self.refcnt[v]
+            self.evicted.append(v)
+
+    # -- inspection ------------------------------------------------------
+    def live_versions(self) -> List[int]:
+        return sorted(self.weights)
+
+    def flat(self, plist: List[np.ndarray]) -> np.ndarray:
+        return np.concatenate([p.reshape(-1) for p in plist])

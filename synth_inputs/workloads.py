@@ -1,0 +1,141 @@
+"""Shapes and seeded tensors of the synthetic workloads.
+
+Each workload is a chain of layers cut into K pipeline stages, plus the batch
+geometry (n micro-batches of `mb` samples per mini-batch) and the optimiser
+constants.  Nothing here computes anything of the method: the functions only
+describe shapes and draw seeded tensors (inputs, labels, initial parameters,
+upstream gradients for a stage timed on its own).
+
+The image workloads stand in for CIFAR-100 / Tiny-ImageNet-200 shaped data:
+pixels are N(0,1) draws and labels are uniform; no record of either dataset is
+used or reproduced.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field, replace
+from typing import List, Tuple
+
+import numpy as np
+
+from . import GLOBAL_SEED, labels as _labels, normal as _normal, round_bf16, round_f32
+
+
+@dataclass(frozen=True)
+class Dense:
+    in_features: int
+    out_features: int
+    act: str  # "relu" | "gelu" | "none"
+    kind: str = "dense"
+
+    def param_shapes(self):
+        return [(self.out_features, self.in_features), (self.out_features,)]
+
+    def out_dim(self):
+        return self.out_features
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    dtype: str                     # "f32" or "bf16" (bf16 storage, fp32 master weights)
+    stages: Tuple[Tuple[Dense, ...], ...]
+    mb: int                        # samples per micro-batch
+    n: int                         # micro-batches per mini-batch
+    classes: int
+    lr: float = 0.01
+    momentum: float = 0.9
+    lam: float = 0.1               # lambda of the significance function
+    seed: int = GLOBAL_SEED
+
+    @property
+    def K(self) -> int:
+        return len(self.stages)
+
+    @property
+    def in_dim(self) -> int:
+        return self.stages[0][0].in_features
+
+    def stage_in_dim(self, s: int) -> int:
+        return self.stages[s][0].in_features
+
+    def stage_out_dim(self, s: int) -> int:
+        return self.stages[s][-1].out_dim()
+
+    def param_count(self, s: int) -> int:
+        return sum(int(np.prod(sh)) for l in self.stages[s] for sh in l.param_shapes())
+
+    def cast(self, x: np.ndarray) -> np.ndarray:
+        """Round to the workload's activation storage type; values stay fp64."""
+        return round_bf16(x) if self.dtype == "bf16" else round_f32(x)
+
+
+def mlp_small() -> Workload:
+    """2-stage pipeline of an fp32 MLP 256-512-512-10 (ReLU), stage 0 = first two layers."""
+    return Workload(
+        name="mlp256_f32_k2", dtype="f32",
+        stages=((Dense(256, 512, "relu"), Dense(512, 512, "relu")),
+                (Dense(512, 10, "none"),)),
+        mb=32, n=4, classes=10)
+
+
+def mlp_wide(width: int = 4096, mb: int = 256, n: int = 8, classes: int = 1000,
+             dtype: str = "bf16") -> Workload:
+    """4-stage pipeline of an 8-layer GELU MLP, two layers per stage.
+
+    Layers 1-7 are width->width with GELU, layer 8 is width->classes (logits).
+    Reduced copies (smaller width / batch) keep the same structure for parity
+    runs the CPU oracle can finish in seconds.
+    """
+    hidden = Dense(width, width, "gelu")
+    stages = ((hidden, hidden), (hidden, hidden), (hidden, hidden),
+              (hidden, Dense(width, classes, "none")))
+    return Workload(name=f"mlp{width}_{dtype}_k4", dtype=dtype, stages=stages,
+                    mb=mb, n=n, classes=classes)
+
+
+def with_lambda(w: Workload, lam: float) -> Workload:
+    return replace(w, lam=lam)
+
+
+# ---------------------------------------------------------------------------
+# seeded tensors
+# ---------------------------------------------------------------------------
+
+def init_params(w: Workload, s: int) -> List[np.ndarray]:
+    """Initial parameters of stage s as a flat list [W0, b0, W1, b1, ...].
+
+    Weights are Kaiming-normal on fan-in with gain sqrt(2): N(0, 2/fan_in);
+    biases start at zero.  Values are rounded to fp32 (the master precision on
+    the GPU) and returned as fp64 arrays holding those fp32 values.
+    """
+    out = []
+    for li, layer in enumerate(w.stages[s]):
+        wshape, bshape = layer.param_shapes()
+        fan_in = int(np.prod(wshape[1:]))
+        W = _normal(f"{w.name}/s{s}/l{li}/W", wshape, std=float(np.sqrt(2.0 / fan_in)), seed=w.seed)
+        out.append(round_f32(W))
+        out.append(np.zeros(bshape, dtype=np.float64))
+    return out
+
+
+def minibatch_input(w: Workload, j: int) -> np.ndarray:
+    """Network input of mini-batch j: [n*mb, in_dim], N(0,1), cast to storage type."""
+    x = _normal(f"{w.name}/x/{j}", (w.n * w.mb, w.in_dim), seed=w.seed)
+    return w.cast(x)
+
+
+def minibatch_labels(w: Workload, j: int) -> np.ndarray:
+    return _labels(f"{w.name}/y/{j}", w.n * w.mb, w.classes, seed=w.seed)
+
+
+def stage_input(w: Workload, s: int, j: int) -> np.ndarray:
+    """Synthetic input of an interior stage timed on its own: N(0,1)."""
+    x = _normal(f"{w.name}/s{s}/x/{j}", (w.n * w.mb, w.stage_in_dim(s)), seed=w.seed)
+    return w.cast(x)
+
+
+def stage_upstream_grad(w: Workload, s: int, j: int) -> np.ndarray:
+    """Synthetic gradient w.r.t. the output of stage s: N(0,1)/sqrt(out_dim)."""
+    d = w.stage_out_dim(s)
+    g = _normal(f"{w.name}/s{s}/dy/{j}", (w.n * w.mb, d), std=float(1.0 / np.sqrt(d)), seed=w.seed)
+    return w.cast(g)
