@@ -1,0 +1,251 @@
+/*
+ * timeprest_stage.h -- C ABI of the MI355X stage library for V-TiMePReSt / I-TiMePReSt.
+ *
+ * One `tp_stage` is one pipeline stage (a run of consecutive layers, Section
+ * "Pipeline Parallelism") living on one GPU.  The calls follow the paper's own
+ * statement of the method:
+ *   - every mini-batch is split into n micro-batches; the n forward passes run one
+ *     after the other and ONE backward pass serves the whole mini-batch (nF1B,
+ *     Section "Methodology");
+ *   - the weights are updated after every mini-batch (Section "Pipeline Parallelism");
+ *     a weight version is named by the number of updates applied so far;
+ *   - V-TiMePReSt: forward and backward always read the latest version, nothing is
+ *     stashed (Section "V-TiMePReSt");
+ *   - I-TiMePReSt: the forward version is stashed; the backward pass runs on an
+ *     intermediate weight built from the stashed version and the degree of staleness
+ *     delta through the significance f(delta) = exp(-lambda*delta) (Section
+ *     "I-TiMePReSt", Eq. 1-2, Appendix A.1-A.2); a stashed version is kept until the
+ *     last mini-batch that used it in forward has built its intermediate weights
+ *     (Section "Memory Overhead").
+ *
+ * Conventions
+ *   - Every function returns 0 (TP_OK) or a negative tp_status; none throws, aborts or
+ *     synchronises the device.  tp_last_error() gives the text of the last failure on
+ *     the calling thread.
+ *   - Pointers named *_dev are DEVICE pointers; everything else is HOST memory.
+ *   - The caller owns every device buffer (ring arena, momentum, gradient, compute
+ *     copies, activation workspace, scratch) and passes them in tp_buffers; sizes come
+ *     from stage_workspace_query.  The library allocates no device memory, creates no
+ *     stream, and enqueues work only on the stream given to stage_init.  Buffers must
+ *     stay alive, and must not be written by the caller, until stage_destroy -- except
+ *     ring slot 0, which the caller fills with the initial weights (version 0), and the
+ *     momentum buffer, which the caller zeroes, both before stage_init.
+ *   - Version ids, slot indices, reference counts and delta are integers computed on
+ *     the host inside the call; they are returned through out-parameters.
+ *   - Matrices are row-major.  Activations are [rows x features]; a mini-batch is the
+ *     n micro-batches stacked in order, [n*mb x features].  In TP_BF16 mode activations,
+ *     incoming/outgoing gradients and the compute copies of the weights are bfloat16,
+ *     while ring, momentum and gradient stay fp32; in TP_F32 mode everything is fp32.
+ *   - Parameter arena: per layer the weight matrix W[out x in] followed by the bias
+ *     b[out]; each tensor starts at a multiple of 64 elements (offsets are reported by
+ *     stage_workspace_query; padding elements are zero and stay zero).
+ */
+#ifndef TIMEPREST_STAGE_H
+#define TIMEPREST_STAGE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum tp_status {
+  TP_OK = 0,
+  TP_EINVAL = -1,     /* null pointer, bad shape, unknown enum value                      */
+  TP_ESTATE = -2,     /* call out of order (backward before n forwards, twice, ...)       */
+  TP_ENOVERSION = -3, /* a version that is not (or no longer) held in the ring            */
+  TP_EFULL = -4,      /* the ring slot the new version needs is still occupied            */
+  TP_EBUSY = -5,      /* evict: version still has users or is the latest -- not freed     */
+  TP_EHIP = -6        /* a HIP call or kernel launch failed                               */
+};
+
+/* Which weights the backward pass runs on: W_b = alpha * W[v_f] + beta * W[latest]. */
+enum tp_policy {
+  TP_LATEST = 0,              /* V-TiMePReSt: alpha=0, beta=1; nothing stashed                */
+  TP_INTERMEDIATE_EQ1 = 1,    /* I-TiMePReSt as printed in Eq. 1: alpha = 2 - 1/f, beta = 0   */
+  TP_INTERMEDIATE_CONVEX = 2, /* I-TiMePReSt read as a blend (Appendix A.2: the stale weight
+                                 scaled by f, the rest 1-f to the latest): alpha=f, beta=1-f */
+  TP_STASHED = 3              /* backward on the forward's own version: alpha=1, beta=0      */
+};
+
+enum tp_dtype { TP_F32 = 0, TP_BF16 = 1 };
+enum tp_act { TP_ACT_NONE = 0, TP_ACT_RELU = 1, TP_ACT_GELU = 2 /* exact erf form */ };
+enum tp_layer_type { TP_LAYER_DENSE = 0 /* z = x W^T + b, a = act(z) */ };
+
+#define TP_MAX_LAYERS 32
+#define TP_NONE UINT64_MAX /* "no mini-batch" for stage_blend_update */
+
+typedef struct tp_layer_desc {
+  int32_t type;         /* tp_layer_type */
+  int32_t act;          /* tp_act */
+  int32_t in_features;  /* columns of the layer input  */
+  int32_t out_features; /* columns of the layer output */
+  int32_t reserved[12]; /* must be zero */
+} tp_layer_desc;
+
+typedef struct tp_stage_desc {
+  int32_t num_layers;
+  int32_t dtype;         /* tp_dtype */
+  int32_t mb;            /* samples per micro-batch */
+  int32_t n;             /* micro-batches per mini-batch */
+  int32_t stage_index;   /* s, 0-based */
+  int32_t num_stages;    /* K */
+  int32_t ring_capacity; /* C: weight versions the ring can hold (K - s covers the nF1B
+                            schedule under the stashing policies; 1 suffices for TP_LATEST) */
+  int32_t max_in_flight; /* mini-batches between forward and backward whose activations are
+                            saved at once (K - s for the nF1B schedule) */
+  int32_t policy;        /* tp_policy */
+  int32_t needs_dx;      /* 0: the stage has no predecessor, no input gradient is formed */
+  double lambda;         /* constant of the significance function, > 0 */
+  double lr;             /* learning rate */
+  double momentum;       /* mu of m <- mu*m + g; W <- W - lr*m */
+  tp_layer_desc layers[TP_MAX_LAYERS];
+} tp_stage_desc;
+
+typedef struct tp_sizes {
+  uint64_t param_count;  /* P: elements of one weight version, padding included */
+  uint64_t ring_bytes;   /* ring_capacity * P * 4 */
+  uint64_t momentum_bytes;
+  uint64_t grad_bytes;
+  uint64_t wfwd_bytes;   /* bf16 copy of the latest version (0 in TP_F32 mode) */
+  uint64_t wbwd_bytes;   /* W_b compute copy, P elements of the activation type */
+  uint64_t act_bytes;    /* saved activations of max_in_flight mini-batches */
+  uint64_t scratch_bytes;/* backward temporaries and reduction partials */
+  uint64_t diag_bytes;   /* TP_DIAG_COUNT doubles written by stage_blend_update */
+  uint64_t w_offset[TP_MAX_LAYERS]; /* element offset of W of layer l inside a version */
+  uint64_t b_offset[TP_MAX_LAYERS]; /* element offset of b of layer l */
+} tp_sizes;
+
+/* Diagnostics the update kernel reduces on the fly (doubles in tp_buffers.diag_dev). */
+enum {
+  TP_DIAG_GRAD_SQ = 0,   /* sum g^2                                   */
+  TP_DIAG_WEIGHT_SQ = 1, /* sum W[v+1]^2                              */
+  TP_DIAG_DRIFT_SQ = 2,  /* sum (W[v+1] - W[v_f])^2, 0 when no blend  */
+  TP_DIAG_WB_SQ = 3,     /* sum W_b^2, 0 when no blend                */
+  TP_DIAG_COUNT = 4
+};
+
+typedef struct tp_buffers {
+  void* ring_dev;
+  void* momentum_dev;
+  void* grad_dev;
+  void* wfwd_dev;
+  void* wbwd_dev;
+  void* act_dev;
+  void* scratch_dev;
+  void* diag_dev;
+} tp_buffers;
+
+#define TP_MAX_SLOTS 16
+#define TP_MAX_IN_FLIGHT 16
+
+typedef struct tp_state {
+  uint64_t latest_version;
+  int32_t ring_capacity;
+  int32_t slot_occupied[TP_MAX_SLOTS];
+  uint64_t slot_version[TP_MAX_SLOTS];
+  uint32_t slot_refcnt[TP_MAX_SLOTS];
+  int32_t num_in_flight;
+  uint64_t in_flight_mb[TP_MAX_IN_FLIGHT];
+  uint64_t in_flight_vf[TP_MAX_IN_FLIGHT];
+  uint32_t in_flight_forwards[TP_MAX_IN_FLIGHT]; /* micro-batch forwards seen so far */
+  uint64_t wb_ready_mb; /* mini-batch whose W_b is already built by the fused update, or TP_NONE */
+} tp_state;
+
+typedef struct tp_stage tp_stage; /* opaque; host memory owned by the library */
+
+/* Sizes and arena offsets for a stage description.  Host only, no GPU needed. */
+int stage_workspace_query(const tp_stage_desc* desc, tp_sizes* out);
+
+/* Create a stage.  `bufs` holds device pointers of at least the queried sizes;
+ * `hip_stream` is a hipStream_t (NULL = the default stream).  Ring slot 0 must hold the
+ * initial weights and momentum_dev must be zero.  In TP_BF16 mode the call enqueues the
+ * conversion of version 0 into wfwd_dev. */
+int stage_init(const tp_stage_desc* desc, const tp_buffers* bufs, void* hip_stream, tp_stage** out);
+int stage_destroy(tp_stage* st);
+
+/* Forward of micro-batch `ub_idx` (0..n-1, in order) of mini-batch `mb_id` on the latest
+ * weights at the stage at the time of the call (Sections "V-TiMePReSt", "I-TiMePReSt").
+ * x_dev: [mb x in] input; y_dev: [mb x out] output.  The stage keeps what the backward
+ * needs in its activation workspace; x_dev may be the pointer returned by
+ * stage_input_ptr (then no copy is made).  On the first micro-batch of a mini-batch the
+ * version is recorded and, under the stashing policies, pinned in the ring.
+ * version_used (optional) receives the version read.
+ * TP_ESTATE: ub_idx out of order, more than max_in_flight mini-batches in flight, or (stashing
+ * policies) an update landed between two micro-batches of the same mini-batch. */
+int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_dev, void* y_dev,
+                  uint64_t* version_used);
+
+/* Where the stage wants the input of (mb_id, ub_idx) to be written so that
+ * stage_forward needs no copy.  Valid for the mini-batch's first micro-batch onwards. */
+int stage_input_ptr(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, void** x_dev);
+
+/* Softmax cross-entropy of a whole mini-batch at the last stage (Section "Methodology":
+ * the loss is taken at the last node and starts the backward pass), mean over the n*mb
+ * rows.  logits_dev: [n*mb x classes] in the activation type, labels_dev: int32[n*mb],
+ * dlogits_dev: [n*mb x classes] = (softmax - onehot)/(n*mb), loss_dev: one float.
+ * classes = out_features of the stage's last layer. */
+int stage_loss_softmax_ce(tp_stage* st, uint64_t mb_id, const void* logits_dev,
+                          const int32_t* labels_dev, void* dlogits_dev, float* loss_dev);
+
+/* The one backward pass of mini-batch `mb_id` over all its n micro-batches (Section
+ * "Methodology"), on W_b = alpha(delta) W[v_f] + beta(delta) W[latest] with
+ * delta = latest - v_f (Eq. 1-2).  dy_dev: [n*mb x out]; dx_dev: [n*mb x in] or NULL when
+ * needs_dx = 0.  Writes the gradient of every parameter into grad_dev (overwriting it).
+ * If the fused update already built W_b for this mini-batch it is used, otherwise the
+ * blend is enqueued first.  Afterwards the mini-batch's stashed version loses one user and
+ * is evicted when unused (Section "Memory Overhead").  delta_used (optional) receives delta.
+ * TP_ESTATE: unknown mini-batch or not all n forwards seen; TP_ENOVERSION: its forward
+ * version is no longer in the ring. */
+int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev,
+                   uint32_t* delta_used);
+
+/* Update after mini-batch `mb_id_done` (its backward must be the last one run):
+ * m <- mu*m + g, W[v+1] = W[v] - lr*m written into ring slot (v+1) mod C, plus the bf16
+ * compute copy in TP_BF16 mode.  If mb_id_next_bwd is not TP_NONE, the same pass over the
+ * parameters also builds W_b for that mini-batch's coming backward, with W[v+1] as the
+ * latest weights (valid as long as no other update happens before that backward; the
+ * backward re-checks).  new_version (optional) receives v+1.
+ * TP_EFULL: slot (v+1) mod C still holds a live version; TP_ESTATE: no gradient pending. */
+int stage_blend_update(tp_stage* st, uint64_t mb_id_done, uint64_t mb_id_next_bwd,
+                       uint64_t* new_version);
+
+/* Pin `version` for one more forward user (refcount + 1); slot (optional) receives its
+ * ring slot.  TP_ENOVERSION if the ring does not hold it. */
+int stash_push(tp_stage* st, uint64_t version, uint32_t* slot);
+
+/* Drop one user of `version`; the slot is freed when no user is left and the version is
+ * not the latest, else TP_EBUSY is returned (the count has still been decremented if it
+ * was positive).  TP_ENOVERSION if the ring does not hold it. */
+int stash_evict(tp_stage* st, uint64_t version);
+
+/* Snapshot of the host bookkeeping. */
+int stage_query(const tp_stage* st, tp_state* out);
+
+/* Copy the fp32 master of `version` (P floats) to dst_dev on the stage's stream. */
+int stage_export_params(tp_stage* st, uint64_t version, void* dst_dev);
+
+/* (alpha, beta) for a policy and degree of staleness, in double (Eq. 1-2). Host only. */
+int tp_blend_coefficients(int32_t policy, uint32_t delta, double lambda, double* alpha,
+                          double* beta);
+
+/* nF1B event order of a K-stage pipeline at mini-batch granularity (Section
+ * "Methodology"): stage s takes in K-s mini-batches, then alternates backward+update and
+ * forward.  Writes up to `capacity` events, returns the total number in *count.
+ * kind: 0 = forward of all n micro-batches, 1 = backward followed by update. Host only. */
+typedef struct tp_event {
+  int32_t t;
+  int32_t kind;
+  int32_t stage;
+  int32_t reserved;
+  uint64_t mb_id;
+} tp_event;
+int tp_schedule_events(int32_t num_stages, uint64_t num_minibatches, tp_event* out,
+                       uint64_t capacity, uint64_t* count);
+
+const char* tp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TIMEPREST_STAGE_H */

@@ -1,0 +1,67 @@
+// Internal launch interface between the C ABI (stage_api.cpp) and the HIP kernels.
+// Everything here enqueues on the given stream and returns the launch status; nothing
+// synchronises.  "elt" is the activation element type: 0 = fp32, 1 = bf16 (raw uint16).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tp {
+
+enum Elt : int { ELT_F32 = 0, ELT_BF16 = 1 };
+enum Act : int { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
+
+// z = x W^T + bias ; a = act(z).   x:[M x K] W:[N x K] (elt), bias: fp32[N].
+// z_out may be null (not saved); a_out is always written.  Both [M x N] in elt.
+hipError_t launch_fprop(hipStream_t s, int elt, int M, int N, int K, const void* x, const void* W,
+                        const float* bias, int act, void* z_out, void* a_out);
+
+// out = (dz W_b) (.) act'(z_prev)   dz:[M x N] W_b:[N x K] z_prev:[M x K] or null (act none).
+hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* Wb,
+                        const void* z_prev, int act_prev, void* out);
+
+// gW = dz^T x  (fp32 [N x K]);  gb = column sums of dz (fp32 [N]).
+// partials: scratch of at least wgrad_scratch_floats(M, N) floats.
+hipError_t launch_wgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* x,
+                        float* gW, float* gb, float* partials);
+size_t wgrad_scratch_floats(int M, int N);
+
+// dz = dy (.) act'(z)    all [rows x cols] in elt.
+hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* z,
+                               int act, void* dz);
+
+// Softmax cross-entropy over `rows` rows of `classes` logits; dlogits = (softmax-onehot)/rows,
+// *loss = mean of the row losses.  row_loss: scratch of `rows` floats.
+hipError_t launch_softmax_ce(hipStream_t s, int elt, int rows, int classes, const void* logits,
+                             const int32_t* labels, void* dlogits, float* row_loss, float* loss);
+
+// fp32 -> elt conversion of `count` elements (compute copy of a weight version).
+hipError_t launch_convert(hipStream_t s, int elt, size_t count, const float* src, void* dst);
+
+// W_b = alpha * W_stale + beta * W_latest  (fp32 in, elt out).
+hipError_t launch_blend(hipStream_t s, int elt, size_t count, const float* w_stale,
+                        const float* w_latest, float alpha, float beta, void* wb);
+
+// The fused pass over the parameters of a stage:
+//   m      <- mu*m + g
+//   w_new  <- w_old - lr*m          (w_new may alias w_old)
+//   wfwd   <- elt(w_new)            (skipped when wfwd == null)
+//   wb     <- elt(alpha*w_stale + beta*w_new)   (skipped when wb == null)
+// and the reductions TP_DIAG_* written as doubles to diag[0..3].
+// partials: scratch of at least update_scratch_floats() floats.
+struct UpdateArgs {
+  size_t count;
+  const float* g;
+  float* m;
+  const float* w_old;
+  float* w_new;
+  const float* w_stale;  // null => no blend
+  void* wfwd;
+  void* wb;
+  float lr, mu, alpha, beta;
+  float* partials;
+  double* diag;
+};
+hipError_t launch_update(hipStream_t s, int elt, const UpdateArgs& a);
+size_t update_scratch_floats();
+
+}  // namespace tp

@@ -1,0 +1,288 @@
+// Elementwise and reduction kernels of the stage library for gfx950 (wave64).
+//
+//   update_kernel   the fused pass over the parameters: momentum, weight update into the next
+//                   ring slot, bf16 compute copy, intermediate weights for the next backward
+//                   (Eq. 1-2) and on-the-fly diagnostics.  Pure HBM streaming.
+//   blend_kernel    the intermediate weights on their own (when the fused pass did not build them)
+//   convert_kernel  fp32 -> bf16 compute copy
+//   act_backward    dz = dy (.) act'(z)
+//   softmax_ce      loss and its gradient at the last stage
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace tp {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUpdateBlocks = 2048;  // 8 blocks per CU on 256 CUs; grid-stride beyond that
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// Sum `NV` values over the block; result valid in thread 0.  Fixed order => deterministic.
+template <int NV>
+__device__ __forceinline__ void block_sum(float (&v)[NV], float* smem /* [NV][4] */) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    v[i] = wave_sum(v[i]);
+    if (lane == 0) smem[i * 4 + wave] = v[i];
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) v[i] = (smem[i * 4 + 0] + smem[i * 4 + 1]) + (smem[i * 4 + 2] + smem[i * 4 + 3]);
+  }
+}
+
+template <typename T>
+struct Store4;
+template <>
+struct Store4<float> {
+  static __device__ __forceinline__ void st(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+};
+template <>
+struct Store4<uint16_t> {
+  static __device__ __forceinline__ void st(uint16_t* p, float4 v) {
+    uint2 o;
+    o.x = pack_bf16x2(v.x, v.y);
+    o.y = pack_bf16x2(v.z, v.w);
+    *reinterpret_cast<uint2*>(p) = o;
+  }
+};
+
+// One float4 per thread per iteration; all streams are read/written exactly once.
+template <typename T, bool BLEND, bool WFWD>
+__global__ __launch_bounds__(kThreads) void update_kernel(size_t n4, const float4* __restrict__ g,
+                                                          float4* __restrict__ m, const float4* w_old,
+                                                          float4* w_new, const float4* __restrict__ w_stale,
+                                                          T* __restrict__ wfwd, T* __restrict__ wb, float lr,
+                                                          float mu, float alpha, float beta,
+                                                          float* __restrict__ partials) {
+  __shared__ float red[4 * 4];
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};  // g^2, w^2, drift^2, wb^2
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += stride) {
+    const float4 gv = g[i];
+    const float4 mv = m[i];
+    const float4 wv = w_old[i];
+    float4 sv;
+    if (BLEND) sv = w_stale[i];
+    float4 mn, wn;
+    mn.x = fmaf(mu, mv.x, gv.x); mn.y = fmaf(mu, mv.y, gv.y);
+    mn.z = fmaf(mu, mv.z, gv.z); mn.w = fmaf(mu, mv.w, gv.w);
+    wn.x = fmaf(-lr, mn.x, wv.x); wn.y = fmaf(-lr, mn.y, wv.y);
+    wn.z = fmaf(-lr, mn.z, wv.z); wn.w = fmaf(-lr, mn.w, wv.w);
+    m[i] = mn;
+    w_new[i] = wn;
+    if (WFWD) Store4<T>::st(wfwd + 4 * i, wn);
+    acc[0] += gv.x * gv.x + gv.y * gv.y + gv.z * gv.z + gv.w * gv.w;
+    acc[1] += wn.x * wn.x + wn.y * wn.y + wn.z * wn.z + wn.w * wn.w;
+    if (BLEND) {
+      float4 b;
+      b.x = fmaf(alpha, sv.x, beta * wn.x); b.y = fmaf(alpha, sv.y, beta * wn.y);
+      b.z = fmaf(alpha, sv.z, beta * wn.z); b.w = fmaf(alpha, sv.w, beta * wn.w);
+      Store4<T>::st(wb + 4 * i, b);
+      const float dx = wn.x - sv.x, dy = wn.y - sv.y, dz = wn.z - sv.z, dw = wn.w - sv.w;
+      acc[2] += dx * dx + dy * dy + dz * dz + dw * dw;
+      acc[3] += b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
+    }
+  }
+  block_sum<4>(acc, red);
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) partials[k * kUpdateBlocks + blockIdx.x] = acc[k];
+  }
+}
+
+// Final, fixed-order reduction of the per-block partials into doubles.
+__global__ __launch_bounds__(kThreads) void diag_reduce_kernel(const float* __restrict__ partials, int nblocks,
+                                                               double* __restrict__ diag) {
+  __shared__ double sm[kThreads];
+  for (int k = 0; k < 4; ++k) {
+    double s = 0.0;
+    for (int i = threadIdx.x; i < nblocks; i += kThreads) s += (double)partials[k * kUpdateBlocks + i];
+    sm[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = kThreads / 2; w > 0; w >>= 1) {
+      if (threadIdx.x < w) sm[threadIdx.x] += sm[threadIdx.x + w];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) diag[k] = sm[0];
+    __syncthreads();
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void blend_kernel(size_t n4, const float4* __restrict__ ws,
+                                                         const float4* __restrict__ wl, float alpha, float beta,
+                                                         T* __restrict__ wb) {
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += stride) {
+    const float4 s = ws[i], l = wl[i];
+    float4 b;
+    b.x = fmaf(alpha, s.x, beta * l.x); b.y = fmaf(alpha, s.y, beta * l.y);
+    b.z = fmaf(alpha, s.z, beta * l.z); b.w = fmaf(alpha, s.w, beta * l.w);
+    Store4<T>::st(wb + 4 * i, b);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void convert_kernel(size_t n4, const float4* __restrict__ src,
+                                                           T* __restrict__ dst) {
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += stride)
+    Store4<T>::st(dst + 4 * i, src[i]);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void act_backward_kernel(size_t count, const T* __restrict__ dy,
+                                                                const T* __restrict__ z, int act,
+                                                                T* __restrict__ dz) {
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < count; i += stride) {
+    const float d = to_float(dy[i]) * act_derivative(to_float(z[i]), act);
+    dz[i] = from_float<T>(d);
+  }
+}
+
+// One wave per row.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void softmax_ce_kernel(int rows, int classes, const T* __restrict__ logits,
+                                                              const int32_t* __restrict__ labels,
+                                                              T* __restrict__ dlogits, float* __restrict__ row_loss) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const T* lg = logits + (size_t)row * classes;
+  float mx = -INFINITY;
+  for (int c = lane; c < classes; c += 64) mx = fmaxf(mx, to_float(lg[c]));
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+  float sum = 0.f;
+  for (int c = lane; c < classes; c += 64) sum += expf(to_float(lg[c]) - mx);
+  sum = wave_sum(sum);
+  const float lse = logf(sum);
+  const int label = labels[row];
+  const float inv_rows = 1.0f / (float)rows;
+  T* dl = dlogits + (size_t)row * classes;
+  for (int c = lane; c < classes; c += 64) {
+    const float p = expf(to_float(lg[c]) - mx - lse);
+    dl[c] = from_float<T>((p - (c == label ? 1.f : 0.f)) * inv_rows);
+  }
+  if (lane == 0) row_loss[row] = -(to_float(lg[label]) - mx - lse);
+}
+
+__global__ __launch_bounds__(kThreads) void mean_kernel(const float* __restrict__ v, int count, float* __restrict__ out) {
+  __shared__ double sm[kThreads];
+  double s = 0.0;
+  for (int i = threadIdx.x; i < count; i += kThreads) s += (double)v[i];
+  sm[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = kThreads / 2; w > 0; w >>= 1) {
+    if (threadIdx.x < w) sm[threadIdx.x] += sm[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *out = (float)(sm[0] / (double)count);
+}
+
+inline int stream_blocks(size_t work_items, int max_blocks) {
+  size_t b = (work_items + kThreads - 1) / kThreads;
+  if (b < 1) b = 1;
+  return (int)(b < (size_t)max_blocks ? b : (size_t)max_blocks);
+}
+
+template <typename T>
+hipError_t update_dispatch(hipStream_t s, const UpdateArgs& a) {
+  const size_t n4 = a.count / 4;
+  const int blocks = stream_blocks(n4, kUpdateBlocks);
+  const float4* g = (const float4*)a.g;
+  float4* m = (float4*)a.m;
+  const float4* wo = (const float4*)a.w_old;
+  float4* wn = (float4*)a.w_new;
+  const float4* ws = (const float4*)a.w_stale;
+  T* wf = (T*)a.wfwd;
+  T* wb = (T*)a.wb;
+  const bool blend = a.w_stale != nullptr && a.wb != nullptr;
+  const bool wfwd = a.wfwd != nullptr;
+#define TP_LAUNCH_UPDATE(B, F) \
+  hipLaunchKernelGGL((update_kernel<T, B, F>), dim3(blocks), dim3(kThreads), 0, s, n4, g, m, wo, wn, ws, wf, wb, a.lr, a.mu, a.alpha, a.beta, a.partials)
+  if (blend && wfwd) TP_LAUNCH_UPDATE(true, true);
+  else if (blend) TP_LAUNCH_UPDATE(true, false);
+  else if (wfwd) TP_LAUNCH_UPDATE(false, true);
+  else TP_LAUNCH_UPDATE(false, false);
+#undef TP_LAUNCH_UPDATE
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(diag_reduce_kernel, dim3(1), dim3(kThreads), 0, s, a.partials, blocks, a.diag);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+size_t update_scratch_floats() { return 4 * (size_t)kUpdateBlocks; }
+
+hipError_t launch_update(hipStream_t s, int elt, const UpdateArgs& a) {
+  if (a.count % 4 != 0) return hipErrorInvalidValue;
+  return elt == ELT_BF16 ? update_dispatch<uint16_t>(s, a) : update_dispatch<float>(s, a);
+}
+
+hipError_t launch_blend(hipStream_t s, int elt, size_t count, const float* w_stale, const float* w_latest,
+                        float alpha, float beta, void* wb) {
+  if (count % 4 != 0) return hipErrorInvalidValue;
+  const size_t n4 = count / 4;
+  const int blocks = stream_blocks(n4, kUpdateBlocks);
+  if (elt == ELT_BF16)
+    hipLaunchKernelGGL(blend_kernel<uint16_t>, dim3(blocks), dim3(kThreads), 0, s, n4, (const float4*)w_stale,
+                       (const float4*)w_latest, alpha, beta, (uint16_t*)wb);
+  else
+    hipLaunchKernelGGL(blend_kernel<float>, dim3(blocks), dim3(kThreads), 0, s, n4, (const float4*)w_stale,
+                       (const float4*)w_latest, alpha, beta, (float*)wb);
+  return hipGetLastError();
+}
+
+hipError_t launch_convert(hipStream_t s, int elt, size_t count, const float* src, void* dst) {
+  if (count % 4 != 0) return hipErrorInvalidValue;
+  const size_t n4 = count / 4;
+  const int blocks = stream_blocks(n4, kUpdateBlocks);
+  if (elt == ELT_BF16)
+    hipLaunchKernelGGL(convert_kernel<uint16_t>, dim3(blocks), dim3(kThreads), 0, s, n4, (const float4*)src, (uint16_t*)dst);
+  else
+    hipLaunchKernelGGL(convert_kernel<float>, dim3(blocks), dim3(kThreads), 0, s, n4, (const float4*)src, (float*)dst);
+  return hipGetLastError();
+}
+
+hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* z, int act, void* dz) {
+  const int blocks = stream_blocks(count, 4096);
+  if (elt == ELT_BF16)
+    hipLaunchKernelGGL(act_backward_kernel<uint16_t>, dim3(blocks), dim3(kThreads), 0, s, count, (const uint16_t*)dy,
+                       (const uint16_t*)z, act, (uint16_t*)dz);
+  else
+    hipLaunchKernelGGL(act_backward_kernel<float>, dim3(blocks), dim3(kThreads), 0, s, count, (const float*)dy,
+                       (const float*)z, act, (float*)dz);
+  return hipGetLastError();
+}
+
+hipError_t launch_softmax_ce(hipStream_t s, int elt, int rows, int classes, const void* logits, const int32_t* labels,
+                             void* dlogits, float* row_loss, float* loss) {
+  const int blocks = (rows + 3) / 4;
+  if (elt == ELT_BF16)
+    hipLaunchKernelGGL(softmax_ce_kernel<uint16_t>, dim3(blocks), dim3(kThreads), 0, s, rows, classes,
+                       (const uint16_t*)logits, labels, (uint16_t*)dlogits, row_loss);
+  else
+    hipLaunchKernelGGL(softmax_ce_kernel<float>, dim3(blocks), dim3(kThreads), 0, s, rows, classes,
+                       (const float*)logits, labels, (float*)dlogits, row_loss);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(kThreads), 0, s, row_loss, rows, loss);
+  return hipGetLastError();
+}
+
+}  // namespace tp

@@ -1,0 +1,184 @@
+// GEMM launchers of a stage: fprop (z = x W^T + b, a = act(z)), dgrad (dx = dz W_b, fused with
+// the previous layer's activation derivative) and wgrad (dW = dz^T x, db = column sums of dz).
+//
+// This file holds the shape-generic, bounds-checked SIMT kernel (fp32 FMA, LDS-tiled) that
+// serves the fp32 mode and any bf16 shape the MFMA kernels do not take, and the dispatch
+// between the two.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "device_utils.h"
+#include "gemm_mfma.h"
+#include "kernels.h"
+
+namespace tp {
+
+namespace {
+
+constexpr int BM = 64, BN = 64, BK = 16, kThreads = 256;
+
+enum Epi : int { EPI_STORE_F32 = 0, EPI_FPROP = 1, EPI_DGRAD = 2 };
+
+struct EpiArgs {
+  float* c_f32;        // EPI_STORE_F32: [M x N] fp32
+  const float* bias;   // EPI_FPROP
+  void* z_out;         // EPI_FPROP: optional pre-activation
+  void* a_out;         // EPI_FPROP: activation; EPI_DGRAD: output
+  const void* z_prev;  // EPI_DGRAD: optional pre-activation of the previous layer
+  int act;
+};
+
+// C(m,n) = sum_k A[m*sam + k*sak] * B[k*sbk + n*sbn], 64x64 tile per block, 4x4 per thread.
+template <typename T, int EPI>
+__global__ __launch_bounds__(kThreads) void gemm_simt_kernel(int M, int N, int K, const T* __restrict__ A, long sam,
+                                                             long sak, const T* __restrict__ B, long sbk, long sbn,
+                                                             EpiArgs e) {
+  __shared__ float As[BK][BM + 4];
+  __shared__ float Bs[BK][BN + 4];
+  const int t = threadIdx.x;
+  const int tx = t & 15, ty = t >> 4;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  float acc[4][4] = {};
+  const bool a_kfast = sak == 1, b_kfast = sbk == 1;
+  for (int k0 = 0; k0 < K; k0 += BK) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int el = t + i * kThreads;
+      int m, k;
+      if (a_kfast) { k = el & (BK - 1); m = el >> 4; } else { m = el & (BM - 1); k = el >> 6; }
+      float v = 0.f;
+      if (m0 + m < M && k0 + k < K) v = to_float(A[(long)(m0 + m) * sam + (long)(k0 + k) * sak]);
+      As[k][m] = v;
+      int n, kb;
+      if (b_kfast) { kb = el & (BK - 1); n = el >> 4; } else { n = el & (BN - 1); kb = el >> 6; }
+      float w = 0.f;
+      if (n0 + n < N && k0 + kb < K) w = to_float(B[(long)(k0 + kb) * sbk + (long)(n0 + n) * sbn]);
+      Bs[kb][n] = w;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < BK; ++k) {
+      const float4 a = *reinterpret_cast<const float4*>(&As[k][ty * 4]);
+      const float4 b = *reinterpret_cast<const float4*>(&Bs[k][tx * 4]);
+      const float av[4] = {a.x, a.y, a.z, a.w};
+      const float bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + ty * 4 + i;
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + tx * 4 + j;
+      if (n >= N) continue;
+      const size_t idx = (size_t)m * N + n;
+      float v = acc[i][j];
+      if (EPI == EPI_STORE_F32) {
+        e.c_f32[idx] = v;
+      } else if (EPI == EPI_FPROP) {
+        v += e.bias[n];
+        if (e.z_out) ((T*)e.z_out)[idx] = from_float<T>(v);
+        ((T*)e.a_out)[idx] = from_float<T>(act_forward(v, e.act));
+      } else {
+        if (e.z_prev) v *= act_derivative(to_float(((const T*)e.z_prev)[idx]), e.act);
+        ((T*)e.a_out)[idx] = from_float<T>(v);
+      }
+    }
+  }
+}
+
+template <int EPI>
+hipError_t simt(hipStream_t s, int elt, int M, int N, int K, const void* A, long sam, long sak, const void* B, long sbk,
+                long sbn, const EpiArgs& e) {
+  dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM);
+  if (elt == ELT_BF16)
+    hipLaunchKernelGGL((gemm_simt_kernel<uint16_t, EPI>), grid, dim3(kThreads), 0, s, M, N, K, (const uint16_t*)A, sam,
+                       sak, (const uint16_t*)B, sbk, sbn, e);
+  else
+    hipLaunchKernelGGL((gemm_simt_kernel<float, EPI>), grid, dim3(kThreads), 0, s, M, N, K, (const float*)A, sam, sak,
+                       (const float*)B, sbk, sbn, e);
+  return hipGetLastError();
+}
+
+// Column sums of dz[M x N] in two fixed-order steps: row chunks -> partials[chunk][N] -> gb[N].
+constexpr int kColChunkRows = 128;
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void colsum_partial_kernel(int M, int N, const T* __restrict__ dz,
+                                                                  float* __restrict__ partials) {
+  __shared__ float sm[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = blockIdx.x * 64 + lane;
+  const int r0 = blockIdx.y * kColChunkRows;
+  const int r1 = min(M, r0 + kColChunkRows);
+  float s = 0.f;
+  if (col < N)
+    for (int r = r0 + wave; r < r1; r += 4) s += to_float(dz[(size_t)r * N + col]);
+  sm[wave][lane] = s;
+  __syncthreads();
+  if (wave == 0 && col < N)
+    partials[(size_t)blockIdx.y * N + col] = (sm[0][lane] + sm[1][lane]) + (sm[2][lane] + sm[3][lane]);
+}
+
+__global__ __launch_bounds__(kThreads) void colsum_final_kernel(int chunks, int N, const float* __restrict__ partials,
+                                                                float* __restrict__ gb) {
+  const int col = blockIdx.x * kThreads + threadIdx.x;
+  if (col >= N) return;
+  float s = 0.f;
+  for (int c = 0; c < chunks; ++c) s += partials[(size_t)c * N + col];
+  gb[col] = s;
+}
+
+}  // namespace
+
+size_t wgrad_scratch_floats(int M, int N) {
+  return (size_t)((M + kColChunkRows - 1) / kColChunkRows) * (size_t)N;
+}
+
+hipError_t launch_fprop(hipStream_t s, int elt, int M, int N, int K, const void* x, const void* W, const float* bias,
+                        int act, void* z_out, void* a_out) {
+  if (elt == ELT_BF16 && mfma_fprop_supported(M, N, K))
+    return mfma_fprop(s, M, N, K, (const uint16_t*)x, (const uint16_t*)W, bias, act, (uint16_t*)z_out, (uint16_t*)a_out);
+  EpiArgs e{};
+  e.bias = bias; e.z_out = z_out; e.a_out = a_out; e.act = act;
+  return simt<EPI_FPROP>(s, elt, M, N, K, x, K, 1, W, 1, K, e);
+}
+
+hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* Wb, const void* z_prev,
+                        int act_prev, void* out) {
+  if (elt == ELT_BF16 && mfma_dgrad_supported(M, N, K))
+    return mfma_dgrad(s, M, N, K, (const uint16_t*)dz, (const uint16_t*)Wb, (const uint16_t*)z_prev, act_prev, (uint16_t*)out);
+  EpiArgs e{};
+  e.a_out = out; e.z_prev = z_prev; e.act = act_prev;
+  // out[M x K] = dz[M x N] . Wb[N x K]: contraction over N
+  return simt<EPI_DGRAD>(s, elt, M, K, N, dz, N, 1, Wb, K, 1, e);
+}
+
+hipError_t launch_wgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* x, float* gW, float* gb,
+                        float* partials) {
+  const int chunks = (M + kColChunkRows - 1) / kColChunkRows;
+  dim3 g1((N + 63) / 64, chunks);
+  if (elt == ELT_BF16)
+    hipLaunchKernelGGL(colsum_partial_kernel<uint16_t>, g1, dim3(kThreads), 0, s, M, N, (const uint16_t*)dz, partials);
+  else
+    hipLaunchKernelGGL(colsum_partial_kernel<float>, g1, dim3(kThreads), 0, s, M, N, (const float*)dz, partials);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  hipLaunchKernelGGL(colsum_final_kernel, dim3((N + kThreads - 1) / kThreads), dim3(kThreads), 0, s, chunks, N, partials, gb);
+  err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  if (elt == ELT_BF16 && mfma_wgrad_supported(M, N, K))
+    return mfma_wgrad(s, M, N, K, (const uint16_t*)dz, (const uint16_t*)x, gW);
+  EpiArgs e{};
+  e.c_f32 = gW;
+  // gW[N x K] = dz^T[N x M] . x[M x K]: contraction over M
+  return simt<EPI_STORE_F32>(s, elt, N, K, M, dz, 1, N, x, K, 1, e);
+}
+
+}  // namespace tp

@@ -1,0 +1,589 @@
+// C ABI of the stage library: host-side bookkeeping of weight versions, the stash ring and
+// the in-flight mini-batches, and the order in which the kernels of a stage are enqueued.
+//
+// The weight rules follow Sections "V-TiMePReSt" and "I-TiMePReSt" (Eq. 1-2), the retention
+// rule follows Section "Memory Overhead", the nF1B order follows Section "Methodology".
+#include "../../include/timeprest_stage.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+inline uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+struct LayerPlan {
+  tp_layer_desc d;
+  uint64_t w_off, b_off;  // elements inside one weight version
+  uint64_t x_off, z_off;  // bytes inside one activation slot (z_off == UINT64_MAX: not saved)
+};
+
+struct Slot {
+  bool occupied = false;
+  uint64_t version = 0;
+  uint32_t refcnt = 0;
+};
+
+struct InFlight {
+  uint64_t mb_id;
+  uint64_t v_f;           // version of the first micro-batch forward (pinned under stashing)
+  uint32_t forwards;      // micro-batch forwards seen
+  int act_slot;
+  bool pinned;
+};
+
+struct Plan {
+  std::vector<LayerPlan> layers;
+  tp_sizes sizes;
+  uint64_t act_slot_bytes = 0;
+  uint64_t dz_bytes = 0;       // one backward temporary
+  uint64_t partial_floats = 0; // reduction partials
+  size_t elt_size = 4;
+};
+
+int check_desc(const tp_stage_desc* d) {
+  if (!d) return fail(TP_EINVAL, "null stage description");
+  if (d->num_layers < 1 || d->num_layers > TP_MAX_LAYERS)
+    return fail(TP_EINVAL, "num_layers %d outside 1..%d", d->num_layers, TP_MAX_LAYERS);
+  if (d->dtype != TP_F32 && d->dtype != TP_BF16) return fail(TP_EINVAL, "unknown dtype %d", d->dtype);
+  if (d->mb < 1 || d->n < 1) return fail(TP_EINVAL, "mb and n must be positive");
+  if ((int64_t)d->mb * d->n > (1 << 24)) return fail(TP_EINVAL, "mini-batch too large");
+  if (d->num_stages < 1 || d->stage_index < 0 || d->stage_index >= d->num_stages)
+    return fail(TP_EINVAL, "stage_index %d outside 0..%d", d->stage_index, d->num_stages - 1);
+  if (d->ring_capacity < 1 || d->ring_capacity > TP_MAX_SLOTS)
+    return fail(TP_EINVAL, "ring_capacity %d outside 1..%d", d->ring_capacity, TP_MAX_SLOTS);
+  if (d->max_in_flight < 1 || d->max_in_flight > TP_MAX_IN_FLIGHT)
+    return fail(TP_EINVAL, "max_in_flight %d outside 1..%d", d->max_in_flight, TP_MAX_IN_FLIGHT);
+  if (d->policy < TP_LATEST || d->policy > TP_STASHED) return fail(TP_EINVAL, "unknown policy %d", d->policy);
+  if (!(d->lambda > 0.0) || !std::isfinite(d->lambda)) return fail(TP_EINVAL, "lambda must be > 0");
+  if (!std::isfinite(d->lr) || !std::isfinite(d->momentum)) return fail(TP_EINVAL, "lr/momentum not finite");
+  for (int l = 0; l < d->num_layers; ++l) {
+    const tp_layer_desc& L = d->layers[l];
+    if (L.type != TP_LAYER_DENSE) return fail(TP_EINVAL, "layer %d: unknown type %d", l, L.type);
+    if (L.act < TP_ACT_NONE || L.act > TP_ACT_GELU) return fail(TP_EINVAL, "layer %d: unknown activation", l);
+    if (L.in_features < 1 || L.out_features < 1) return fail(TP_EINVAL, "layer %d: empty shape", l);
+    if (l > 0 && d->layers[l - 1].out_features != L.in_features)
+      return fail(TP_EINVAL, "layer %d: input %d does not match previous output %d", l, L.in_features,
+                  d->layers[l - 1].out_features);
+    for (int r = 0; r < 12; ++r)
+      if (L.reserved[r] != 0) return fail(TP_EINVAL, "layer %d: reserved fields must be zero", l);
+  }
+  return TP_OK;
+}
+
+int make_plan(const tp_stage_desc* d, Plan* p) {
+  int rc = check_desc(d);
+  if (rc) return rc;
+  p->elt_size = d->dtype == TP_BF16 ? 2 : 4;
+  const uint64_t rows = (uint64_t)d->mb * d->n;
+  std::memset(&p->sizes, 0, sizeof(p->sizes));
+  uint64_t off = 0, act = 0, max_feat = 0;
+  for (int l = 0; l < d->num_layers; ++l) {
+    LayerPlan lp;
+    lp.d = d->layers[l];
+    lp.w_off = off;
+    off += round_up((uint64_t)lp.d.in_features * lp.d.out_features, 64);
+    lp.b_off = off;
+    off += round_up((uint64_t)lp.d.out_features, 64);
+    lp.x_off = act;
+    act += round_up(rows * lp.d.in_features * p->elt_size, 256);
+    if (lp.d.act != TP_ACT_NONE) {
+      lp.z_off = act;
+      act += round_up(rows * lp.d.out_features * p->elt_size, 256);
+    } else {
+      lp.z_off = UINT64_MAX;
+    }
+    max_feat = std::max<uint64_t>(max_feat, std::max(lp.d.in_features, lp.d.out_features));
+    p->sizes.w_offset[l] = lp.w_off;
+    p->sizes.b_offset[l] = lp.b_off;
+    p->layers.push_back(lp);
+  }
+  const uint64_t P = off;
+  p->act_slot_bytes = act;
+  p->dz_bytes = round_up(rows * max_feat * p->elt_size, 256);
+  uint64_t wg = 0;
+  for (const LayerPlan& lp : p->layers)
+    wg = std::max<uint64_t>(wg, tp::wgrad_scratch_floats((int)rows, lp.d.out_features));
+  p->partial_floats = round_up(std::max<uint64_t>({wg, tp::update_scratch_floats(), rows}), 64);
+  tp_sizes& s = p->sizes;
+  s.param_count = P;
+  s.ring_bytes = (uint64_t)d->ring_capacity * P * 4;
+  s.momentum_bytes = P * 4;
+  s.grad_bytes = P * 4;
+  s.wfwd_bytes = d->dtype == TP_BF16 ? P * 2 : 0;
+  s.wbwd_bytes = P * p->elt_size;
+  s.act_bytes = (uint64_t)d->max_in_flight * act;
+  s.scratch_bytes = 2 * p->dz_bytes + p->partial_floats * 4;
+  s.diag_bytes = TP_DIAG_COUNT * sizeof(double);
+  return TP_OK;
+}
+
+bool stashing(int policy) { return policy != TP_LATEST; }
+
+}  // namespace
+
+struct tp_stage {
+  tp_stage_desc desc;
+  Plan plan;
+  tp_buffers bufs;
+  hipStream_t stream;
+  bool dry;                     // no device buffers given: bookkeeping only, nothing is launched
+  uint64_t latest = 0;
+  Slot slots[TP_MAX_SLOTS];
+  std::vector<InFlight> inflight;
+  bool act_used[TP_MAX_IN_FLIGHT] = {};
+  bool grad_pending = false;
+  uint64_t grad_mb = 0;
+  // W_b prepared ahead by the fused update
+  bool wb_valid = false;
+  uint64_t wb_mb = TP_NONE, wb_vf = 0, wb_vnow = 0;
+
+  int find_slot(uint64_t v) const {
+    const Slot& s = slots[v % desc.ring_capacity];
+    return (s.occupied && s.version == v) ? (int)(v % desc.ring_capacity) : -1;
+  }
+  InFlight* find_mb(uint64_t mb) {
+    for (InFlight& f : inflight)
+      if (f.mb_id == mb) return &f;
+    return nullptr;
+  }
+  float* ring(int slot) const { return (float*)bufs.ring_dev + (uint64_t)slot * plan.sizes.param_count; }
+  char* act_slot(int q) const { return (char*)bufs.act_dev + (uint64_t)q * plan.act_slot_bytes; }
+  char* dz_buf(int i) const { return (char*)bufs.scratch_dev + (uint64_t)i * plan.dz_bytes; }
+  float* partials() const { return (float*)((char*)bufs.scratch_dev + 2 * plan.dz_bytes); }
+  // drop a version that nobody needs any more
+  void evict_if_unused(uint64_t v) {
+    int s = find_slot(v);
+    if (s >= 0 && v != latest && slots[s].refcnt == 0) slots[s].occupied = false;
+  }
+};
+
+#define HIP_TRY(expr)                                                                     \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess) return fail(TP_EHIP, "%s: %s", #expr, hipGetErrorString(e_));   \
+  } while (0)
+
+extern "C" {
+
+const char* tp_last_error(void) { return g_err; }
+
+int tp_blend_coefficients(int32_t policy, uint32_t delta, double lambda, double* alpha, double* beta) {
+  if (!alpha || !beta) return fail(TP_EINVAL, "null output");
+  if (!(lambda > 0.0)) return fail(TP_EINVAL, "lambda must be > 0");
+  // Eq. 2: significance of weights that are `delta` updates old.
+  const double f = std::exp(-lambda * (double)delta);
+  switch (policy) {
+    case TP_LATEST: *alpha = 0.0; *beta = 1.0; break;
+    case TP_STASHED: *alpha = 1.0; *beta = 0.0; break;
+    case TP_INTERMEDIATE_EQ1: *alpha = 2.0 - 1.0 / f; *beta = 0.0; break;          // Eq. 1
+    case TP_INTERMEDIATE_CONVEX: *alpha = f; *beta = 1.0 - f; break;               // Appendix A.2
+    default: return fail(TP_EINVAL, "unknown policy %d", policy);
+  }
+  return TP_OK;
+}
+
+int tp_schedule_events(int32_t K, uint64_t num_mb, tp_event* out, uint64_t capacity, uint64_t* count) {
+  if (K < 1 || K > 1024 || !count) return fail(TP_EINVAL, "bad schedule arguments");
+  // Per-stage programme: K-s forwards, then backward/forward alternating.  The clock
+  // advances one operation per stage per tick; an operation runs once its producer has
+  // finished on an earlier tick.  Within a tick: backwards from the last stage down, then
+  // forwards from the first stage up.
+  struct Cursor { uint64_t next_f = 0, next_b = 0; };
+  std::vector<Cursor> cur(K);
+  std::vector<std::vector<int64_t>> f_done(K), b_done(K);
+  for (int s = 0; s < K; ++s) { f_done[s].assign(num_mb, -1); b_done[s].assign(num_mb, -1); }
+  uint64_t emitted = 0;
+  const uint64_t total = 2ull * K * num_mb;
+  for (int64_t t = 0; emitted < total; ++t) {
+    if (t > (int64_t)(4 * total + 16)) return fail(TP_ESTATE, "schedule did not terminate");
+    std::vector<int> run_b, run_f;
+    for (int s = 0; s < K; ++s) {
+      Cursor& c = cur[s];
+      if (c.next_b >= num_mb) continue;
+      const uint64_t warm = std::min<uint64_t>(K - s, num_mb);
+      // the stage's next operation: forward while warming up or right after a backward
+      const bool want_f = c.next_f < num_mb && (c.next_f < warm || c.next_f < c.next_b + warm);
+      if (want_f) {
+        const uint64_t j = c.next_f;
+        if (s == 0 || (f_done[s - 1][j] >= 0 && f_done[s - 1][j] < t)) run_f.push_back(s);
+      } else {
+        const uint64_t j = c.next_b;
+        const int64_t dep = (s == K - 1) ? f_done[s][j] : b_done[s + 1][j];
+        if (dep >= 0 && dep < t) run_b.push_back(s);
+      }
+    }
+    for (auto it = run_b.rbegin(); it != run_b.rend(); ++it) {
+      const int s = *it;
+      const uint64_t j = cur[s].next_b++;
+      b_done[s][j] = t;
+      if (out && emitted < capacity) out[emitted] = tp_event{(int32_t)t, 1, s, 0, j};
+      ++emitted;
+    }
+    for (int s : run_f) {
+      const uint64_t j = cur[s].next_f++;
+      f_done[s][j] = t;
+      if (out && emitted < capacity) out[emitted] = tp_event{(int32_t)t, 0, s, 0, j};
+      ++emitted;
+    }
+  }
+  *count = emitted;
+  return TP_OK;
+}
+
+int stage_workspace_query(const tp_stage_desc* desc, tp_sizes* out) {
+  if (!out) return fail(TP_EINVAL, "null output");
+  Plan p;
+  int rc = make_plan(desc, &p);
+  if (rc) return rc;
+  *out = p.sizes;
+  return TP_OK;
+}
+
+int stage_init(const tp_stage_desc* desc, const tp_buffers* bufs, void* hip_stream, tp_stage** out) {
+  if (!out) return fail(TP_EINVAL, "null output");
+  *out = nullptr;
+  tp_stage* st = new (std::nothrow) tp_stage();
+  if (!st) return fail(TP_EINVAL, "out of host memory");
+  int rc = make_plan(desc, &st->plan);
+  if (rc) { delete st; return rc; }
+  st->desc = *desc;
+  st->stream = (hipStream_t)hip_stream;
+  // bufs == NULL: bookkeeping only (host tests of versions, slots and reference counts);
+  // no kernel is ever launched on such a stage.
+  st->dry = bufs == nullptr;
+  if (bufs) {
+    st->bufs = *bufs;
+    const bool bf = desc->dtype == TP_BF16;
+    if (!bufs->ring_dev || !bufs->momentum_dev || !bufs->grad_dev || !bufs->wbwd_dev || !bufs->act_dev ||
+        !bufs->scratch_dev || !bufs->diag_dev || (bf && !bufs->wfwd_dev)) {
+      delete st;
+      return fail(TP_EINVAL, "null device buffer");
+    }
+    if (bf) {
+      hipError_t e = tp::launch_convert(st->stream, tp::ELT_BF16, st->plan.sizes.param_count, st->ring(0),
+                                        bufs->wfwd_dev);
+      if (e != hipSuccess) { delete st; return fail(TP_EHIP, "convert: %s", hipGetErrorString(e)); }
+    }
+  } else {
+    std::memset(&st->bufs, 0, sizeof(st->bufs));
+  }
+  st->slots[0].occupied = true;
+  st->slots[0].version = 0;
+  st->slots[0].refcnt = 0;
+  *out = st;
+  return TP_OK;
+}
+
+int stage_destroy(tp_stage* st) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  delete st;
+  return TP_OK;
+}
+
+int stash_push(tp_stage* st, uint64_t version, uint32_t* slot) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  int s = st->find_slot(version);
+  if (s < 0) return fail(TP_ENOVERSION, "version %llu is not in the ring", (unsigned long long)version);
+  st->slots[s].refcnt++;
+  if (slot) *slot = (uint32_t)s;
+  return TP_OK;
+}
+
+int stash_evict(tp_stage* st, uint64_t version) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  int s = st->find_slot(version);
+  if (s < 0) return fail(TP_ENOVERSION, "version %llu is not in the ring", (unsigned long long)version);
+  Slot& sl = st->slots[s];
+  if (sl.refcnt > 0) sl.refcnt--;
+  if (sl.refcnt > 0) return fail(TP_EBUSY, "version %llu still has %u users", (unsigned long long)version, sl.refcnt);
+  if (version == st->latest) return fail(TP_EBUSY, "version %llu is the latest", (unsigned long long)version);
+  sl.occupied = false;
+  return TP_OK;
+}
+
+int stage_input_ptr(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, void** x_dev) {
+  if (!st || !x_dev) return fail(TP_EINVAL, "null argument");
+  if (ub_idx >= (uint32_t)st->desc.n) return fail(TP_EINVAL, "micro-batch index %u out of range", ub_idx);
+  InFlight* f = st->find_mb(mb_id);
+  int q;
+  if (f) {
+    q = f->act_slot;
+  } else {
+    // the slot the mini-batch will get when its first forward arrives
+    q = -1;
+    for (int i = 0; i < st->desc.max_in_flight; ++i)
+      if (!st->act_used[i]) { q = i; break; }
+    if (q < 0) return fail(TP_ESTATE, "more than %d mini-batches in flight", st->desc.max_in_flight);
+  }
+  const LayerPlan& l0 = st->plan.layers[0];
+  *x_dev = st->dry ? nullptr
+                   : st->act_slot(q) + l0.x_off + (uint64_t)ub_idx * st->desc.mb * l0.d.in_features * st->plan.elt_size;
+  return TP_OK;
+}
+
+int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_dev, void* y_dev,
+                  uint64_t* version_used) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  if (!st->dry && (!x_dev || !y_dev)) return fail(TP_EINVAL, "null activation pointer");
+  if (mb_id == TP_NONE) return fail(TP_EINVAL, "reserved mini-batch id");
+  const tp_stage_desc& d = st->desc;
+  InFlight* f = st->find_mb(mb_id);
+  if (!f) {
+    if (ub_idx != 0) return fail(TP_ESTATE, "mini-batch %llu: first forward must be micro-batch 0", (unsigned long long)mb_id);
+    int q = -1;
+    for (int i = 0; i < d.max_in_flight; ++i)
+      if (!st->act_used[i]) { q = i; break; }
+    if (q < 0) return fail(TP_ESTATE, "more than %d mini-batches in flight", d.max_in_flight);
+    InFlight nf{mb_id, st->latest, 0, q, false};
+    if (stashing(d.policy)) {
+      int rc = stash_push(st, st->latest, nullptr);   // the forward version stays until blended
+      if (rc) return rc;
+      nf.pinned = true;
+    }
+    st->act_used[q] = true;
+    st->inflight.push_back(nf);
+    f = &st->inflight.back();
+  }
+  if (ub_idx != f->forwards || ub_idx >= (uint32_t)d.n)
+    return fail(TP_ESTATE, "mini-batch %llu: expected micro-batch %u, got %u", (unsigned long long)mb_id, f->forwards, ub_idx);
+  if (stashing(d.policy) && f->v_f != st->latest)
+    return fail(TP_ESTATE, "an update landed between micro-batches of mini-batch %llu", (unsigned long long)mb_id);
+  const uint64_t v = st->latest;                       // always the latest weights at the stage
+  if (version_used) *version_used = v;
+  f->forwards++;
+  if (st->dry) return TP_OK;
+
+  const int slot = st->find_slot(v);
+  const size_t es = st->plan.elt_size;
+  const float* master = st->ring(slot);
+  const char* wcopy = d.dtype == TP_BF16 ? (const char*)st->bufs.wfwd_dev : (const char*)master;
+  char* aslot = st->act_slot(f->act_slot);
+  const uint64_t row0 = (uint64_t)ub_idx * d.mb;
+  const int L = d.num_layers;
+  for (int l = 0; l < L; ++l) {
+    const LayerPlan& lp = st->plan.layers[l];
+    char* x_saved = aslot + lp.x_off + row0 * lp.d.in_features * es;
+    if (l == 0 && x_dev != (const void*)x_saved)
+      HIP_TRY(hipMemcpyAsync(x_saved, x_dev, (size_t)d.mb * lp.d.in_features * es, hipMemcpyDeviceToDevice, st->stream));
+    void* z_out = lp.z_off == UINT64_MAX ? nullptr : aslot + lp.z_off + row0 * lp.d.out_features * es;
+    void* a_out = (l == L - 1) ? y_dev
+                               : (void*)(aslot + st->plan.layers[l + 1].x_off + row0 * lp.d.out_features * es);
+    HIP_TRY(tp::launch_fprop(st->stream, d.dtype, d.mb, lp.d.out_features, lp.d.in_features, x_saved,
+                             wcopy + lp.w_off * es, master + lp.b_off, lp.d.act, z_out, a_out));
+  }
+  return TP_OK;
+}
+
+int stage_loss_softmax_ce(tp_stage* st, uint64_t mb_id, const void* logits_dev, const int32_t* labels_dev,
+                          void* dlogits_dev, float* loss_dev) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  InFlight* f = st->find_mb(mb_id);
+  if (!f || f->forwards != (uint32_t)st->desc.n)
+    return fail(TP_ESTATE, "loss of mini-batch %llu needs all %d forwards", (unsigned long long)mb_id, st->desc.n);
+  if (st->dry) return TP_OK;
+  if (!logits_dev || !labels_dev || !dlogits_dev || !loss_dev) return fail(TP_EINVAL, "null pointer");
+  const int rows = st->desc.mb * st->desc.n;
+  const int classes = st->plan.layers.back().d.out_features;
+  HIP_TRY(tp::launch_softmax_ce(st->stream, st->desc.dtype, rows, classes, logits_dev, labels_dev, dlogits_dev,
+                                st->partials(), loss_dev));
+  return TP_OK;
+}
+
+int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev, uint32_t* delta_used) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  const tp_stage_desc& d = st->desc;
+  InFlight* f = st->find_mb(mb_id);
+  if (!f) return fail(TP_ESTATE, "mini-batch %llu is not in flight", (unsigned long long)mb_id);
+  if (f->forwards != (uint32_t)d.n)
+    return fail(TP_ESTATE, "mini-batch %llu: %u of %d forwards seen", (unsigned long long)mb_id, f->forwards, d.n);
+  if (st->grad_pending) return fail(TP_ESTATE, "gradient of mini-batch %llu has not been applied yet", (unsigned long long)st->grad_mb);
+  if (!st->dry && (!dy_dev || (d.needs_dx && !dx_dev))) return fail(TP_EINVAL, "null gradient pointer");
+
+  // Which weights: V reads the latest; I blends the stashed forward version towards it.
+  const uint64_t v_now = st->latest;
+  const uint64_t v_f = stashing(d.policy) ? f->v_f : v_now;
+  const uint32_t delta = (uint32_t)(v_now - v_f);
+  const int slot_now = st->find_slot(v_now);
+  const int slot_f = st->find_slot(v_f);
+  if (slot_f < 0) return fail(TP_ENOVERSION, "forward version %llu of mini-batch %llu is no longer stashed", (unsigned long long)v_f, (unsigned long long)mb_id);
+  if (delta_used) *delta_used = delta;
+
+  if (!st->dry) {
+    const size_t es = st->plan.elt_size;
+    const uint64_t P = st->plan.sizes.param_count;
+    const char* wb;
+    if (delta == 0) {
+      // no staleness: intermediate = stale = latest (bit for bit)
+      wb = d.dtype == TP_BF16 ? (const char*)st->bufs.wfwd_dev : (const char*)st->ring(slot_now);
+    } else if (st->wb_valid && st->wb_mb == mb_id && st->wb_vf == v_f && st->wb_vnow == v_now) {
+      wb = (const char*)st->bufs.wbwd_dev;            // built by the fused update
+    } else {
+      double a, b;
+      int rc = tp_blend_coefficients(d.policy, delta, d.lambda, &a, &b);
+      if (rc) return rc;
+      HIP_TRY(tp::launch_blend(st->stream, d.dtype, P, st->ring(slot_f), st->ring(slot_now), (float)a, (float)b, st->bufs.wbwd_dev));
+      wb = (const char*)st->bufs.wbwd_dev;
+    }
+
+    const int rows = d.mb * d.n;
+    const int L = d.num_layers;
+    char* aslot = st->act_slot(f->act_slot);
+    float* g = (float*)st->bufs.grad_dev;
+    const void* dz = nullptr;
+    int pp = 0;
+    {
+      const LayerPlan& last = st->plan.layers[L - 1];
+      if (last.d.act == TP_ACT_NONE) {
+        dz = dy_dev;
+      } else {
+        HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * last.d.out_features, dy_dev, aslot + last.z_off, last.d.act, st->dz_buf(pp)));
+        dz = st->dz_buf(pp);
+        pp ^= 1;
+      }
+    }
+    for (int l = L - 1; l >= 0; --l) {
+      const LayerPlan& lp = st->plan.layers[l];
+      HIP_TRY(tp::launch_wgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, aslot + lp.x_off,
+                               g + lp.w_off, g + lp.b_off, st->partials()));
+      if (l > 0) {
+        const LayerPlan& prev = st->plan.layers[l - 1];
+        const void* zprev = prev.z_off == UINT64_MAX ? nullptr : aslot + prev.z_off;
+        HIP_TRY(tp::launch_dgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, wb + lp.w_off * es,
+                                 zprev, prev.d.act, st->dz_buf(pp)));
+        dz = st->dz_buf(pp);
+        pp ^= 1;
+      } else if (d.needs_dx) {
+        HIP_TRY(tp::launch_dgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, wb + lp.w_off * es,
+                                 nullptr, TP_ACT_NONE, dx_dev));
+      }
+    }
+  }
+
+  st->wb_valid = false;
+  // The intermediate weights are built: the mini-batch no longer needs its stashed version.
+  if (f->pinned) {
+    Slot& sl = st->slots[slot_f];
+    if (sl.refcnt > 0) sl.refcnt--;
+    st->evict_if_unused(v_f);
+  }
+  st->act_used[f->act_slot] = false;
+  st->inflight.erase(st->inflight.begin() + (f - st->inflight.data()));
+  st->grad_pending = true;
+  st->grad_mb = mb_id;
+  return TP_OK;
+}
+
+int stage_blend_update(tp_stage* st, uint64_t mb_id_done, uint64_t mb_id_next_bwd, uint64_t* new_version) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  const tp_stage_desc& d = st->desc;
+  if (!st->grad_pending || st->grad_mb != mb_id_done)
+    return fail(TP_ESTATE, "no gradient of mini-batch %llu is pending", (unsigned long long)mb_id_done);
+  const uint64_t v = st->latest;
+  const int C = d.ring_capacity;
+  const int slot_old = (int)(v % C), slot_new = (int)((v + 1) % C);
+  if (slot_new == slot_old) {
+    if (st->slots[slot_old].refcnt != 0)
+      return fail(TP_EFULL, "ring of capacity %d cannot keep version %llu for its %u users", C, (unsigned long long)v, st->slots[slot_old].refcnt);
+  } else if (st->slots[slot_new].occupied) {
+    return fail(TP_EFULL, "ring slot %d still holds version %llu", slot_new, (unsigned long long)st->slots[slot_new].version);
+  }
+  // Optional look-ahead: W_b of the next backward, with W[v+1] as the latest weights.
+  bool blend = false;
+  uint64_t vf_next = 0;
+  double a = 0.0, b = 1.0;
+  int slot_stale = -1;
+  if (mb_id_next_bwd != TP_NONE && stashing(d.policy)) {
+    InFlight* nx = st->find_mb(mb_id_next_bwd);
+    if (!nx) return fail(TP_ESTATE, "mini-batch %llu is not in flight", (unsigned long long)mb_id_next_bwd);
+    vf_next = nx->v_f;
+    slot_stale = st->find_slot(vf_next);
+    if (slot_stale < 0) return fail(TP_ENOVERSION, "version %llu is not in the ring", (unsigned long long)vf_next);
+    const uint32_t delta = (uint32_t)(v + 1 - vf_next);
+    int rc = tp_blend_coefficients(d.policy, delta, d.lambda, &a, &b);
+    if (rc) return rc;
+    blend = slot_stale != slot_new;                    // never read the slot being overwritten
+  }
+  if (!st->dry) {
+    tp::UpdateArgs u;
+    u.count = st->plan.sizes.param_count;
+    u.g = (const float*)st->bufs.grad_dev;
+    u.m = (float*)st->bufs.momentum_dev;
+    u.w_old = st->ring(slot_old);
+    u.w_new = st->ring(slot_new);
+    u.w_stale = blend ? st->ring(slot_stale) : nullptr;
+    u.wfwd = d.dtype == TP_BF16 ? st->bufs.wfwd_dev : nullptr;
+    u.wb = blend ? st->bufs.wbwd_dev : nullptr;
+    u.lr = (float)d.lr;
+    u.mu = (float)d.momentum;
+    u.alpha = (float)a;
+    u.beta = (float)b;
+    u.partials = st->partials();
+    u.diag = (double*)st->bufs.diag_dev;
+    HIP_TRY(tp::launch_update(st->stream, d.dtype, u));
+  }
+  st->wb_valid = blend;
+  st->wb_mb = blend ? mb_id_next_bwd : TP_NONE;
+  st->wb_vf = vf_next;
+  st->wb_vnow = v + 1;
+  // bookkeeping: the new version takes its slot; the old one goes unless still stashed
+  st->slots[slot_new].occupied = true;
+  st->slots[slot_new].version = v + 1;
+  st->slots[slot_new].refcnt = 0;
+  st->latest = v + 1;
+  if (slot_new != slot_old) st->evict_if_unused(v);
+  st->grad_pending = false;
+  if (new_version) *new_version = v + 1;
+  return TP_OK;
+}
+
+int stage_query(const tp_stage* st, tp_state* out) {
+  if (!st || !out) return fail(TP_EINVAL, "null argument");
+  std::memset(out, 0, sizeof(*out));
+  out->latest_version = st->latest;
+  out->ring_capacity = st->desc.ring_capacity;
+  for (int i = 0; i < st->desc.ring_capacity; ++i) {
+    out->slot_occupied[i] = st->slots[i].occupied ? 1 : 0;
+    out->slot_version[i] = st->slots[i].version;
+    out->slot_refcnt[i] = st->slots[i].refcnt;
+  }
+  out->num_in_flight = (int32_t)st->inflight.size();
+  for (size_t i = 0; i < st->inflight.size() && i < TP_MAX_IN_FLIGHT; ++i) {
+    out->in_flight_mb[i] = st->inflight[i].mb_id;
+    out->in_flight_vf[i] = st->inflight[i].v_f;
+    out->in_flight_forwards[i] = st->inflight[i].forwards;
+  }
+  out->wb_ready_mb = st->wb_valid ? st->wb_mb : TP_NONE;
+  return TP_OK;
+}
+
+int stage_export_params(tp_stage* st, uint64_t version, void* dst_dev) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  int s = st->find_slot(version);
+  if (s < 0) return fail(TP_ENOVERSION, "version %llu is not in the ring", (unsigned long long)version);
+  if (st->dry) return TP_OK;
+  if (!dst_dev) return fail(TP_EINVAL, "null destination");
+  HIP_TRY(hipMemcpyAsync(dst_dev, st->ring(s), st->plan.sizes.param_count * 4, hipMemcpyDeviceToDevice, st->stream));
+  return TP_OK;
+}
+
+}  // extern "C"

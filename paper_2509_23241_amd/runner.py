@@ -1,0 +1,211 @@
+"""Torch-side plumbing around the C ABI: device buffers, streams, and the one-GPU emulation of
+the K-stage nF1B schedule.  No arithmetic of the method happens here -- every step runs in the
+library's kernels; this module only allocates memory, uploads inputs and calls the ABI in the
+order the library's own schedule generator gives.
+"""
+from __future__ import annotations
+
+from typing import Callable, Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def _torch_dtype(dtype: str):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+class GpuStage:
+    """One pipeline stage on the current device; owns the torch tensors the library works in."""
+
+    def __init__(self, layers: Sequence[tuple], params: Optional[List[np.ndarray]], *, dtype: str, mb: int, n: int,
+                 stage_index: int, num_stages: int, policy: str, lam: float, lr: float, momentum: float,
+                 ring_capacity: Optional[int] = None, max_in_flight: Optional[int] = None,
+                 needs_dx: Optional[bool] = None, device="cuda:0", stream: Optional[torch.cuda.Stream] = None):
+        self.layers = [tuple(l) for l in layers]
+        self.dtype, self.mb, self.n = dtype, mb, n
+        self.s, self.K = stage_index, num_stages
+        depth = num_stages - stage_index
+        if ring_capacity is None:
+            ring_capacity = 1 if policy == "latest" else depth
+        if max_in_flight is None:
+            max_in_flight = depth
+        if needs_dx is None:
+            needs_dx = stage_index > 0
+        self.needs_dx = needs_dx
+        self.desc = B.make_desc(self.layers, dtype=dtype, mb=mb, n=n, stage_index=stage_index,
+                                num_stages=num_stages, ring_capacity=ring_capacity, max_in_flight=max_in_flight,
+                                policy=policy, needs_dx=needs_dx, lam=lam, lr=lr, momentum=momentum)
+        self.sizes = B.stage_workspace_query(self.desc)
+        self.P = self.sizes.param_count
+        self.C = ring_capacity
+        self.device = torch.device(device)
+        self.tdtype = _torch_dtype(dtype)
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        dev = self.device
+
+        def raw(nbytes):
+            return torch.zeros(max(int(nbytes), 256), dtype=torch.uint8, device=dev)
+
+        self.ring = torch.zeros(self.C * self.P, dtype=torch.float32, device=dev)
+        self.momentum = torch.zeros(self.P, dtype=torch.float32, device=dev)
+        self.grad = torch.zeros(self.P, dtype=torch.float32, device=dev)
+        self.wfwd = torch.zeros(self.P if dtype == "bf16" else 64, dtype=torch.bfloat16, device=dev)
+        self.wbwd = torch.zeros(self.P, dtype=self.tdtype, device=dev)
+        self.act = raw(self.sizes.act_bytes)
+        self.scratch = raw(self.sizes.scratch_bytes)
+        self.diag = torch.zeros(B.TP_DIAG_COUNT, dtype=torch.float64, device=dev)
+        if params is not None:
+            self.ring[: self.P].copy_(torch.from_numpy(self.pack(params)).to(dev))
+        bufs = B.tp_buffers(self.ring.data_ptr(), self.momentum.data_ptr(), self.grad.data_ptr(),
+                            self.wfwd.data_ptr(), self.wbwd.data_ptr(), self.act.data_ptr(),
+                            self.scratch.data_ptr(), self.diag.data_ptr())
+        with torch.cuda.stream(self.stream):
+            self.handle = B.stage_init(self.desc, bufs, self.stream.cuda_stream)
+
+    # -- parameter arena <-> per-layer arrays (pure indexing) -----------------
+    def pack(self, params: List[np.ndarray]) -> np.ndarray:
+        flat = np.zeros(self.P, dtype=np.float32)
+        for l, (fin, fout, _) in enumerate(self.layers):
+            wo, bo = self.sizes.w_offset[l], self.sizes.b_offset[l]
+            flat[wo: wo + fin * fout] = np.asarray(params[2 * l], dtype=np.float32).reshape(-1)
+            flat[bo: bo + fout] = np.asarray(params[2 * l + 1], dtype=np.float32).reshape(-1)
+        return flat
+
+    def unpack(self, flat) -> List[np.ndarray]:
+        flat = np.asarray(flat)
+        out = []
+        for l, (fin, fout, _) in enumerate(self.layers):
+            wo, bo = self.sizes.w_offset[l], self.sizes.b_offset[l]
+            out.append(flat[wo: wo + fin * fout].reshape(fout, fin))
+            out.append(flat[bo: bo + fout])
+        return out
+
+    # -- calls ----------------------------------------------------------------
+    def forward(self, mb_id: int, ub: int, x: torch.Tensor, y: Optional[torch.Tensor] = None):
+        if y is None:
+            y = torch.empty(self.mb, self.layers[-1][1], dtype=self.tdtype, device=self.device)
+        assert x.is_contiguous() and y.is_contiguous() and x.dtype == self.tdtype and y.dtype == self.tdtype
+        assert x.shape == (self.mb, self.layers[0][0]) and y.shape == (self.mb, self.layers[-1][1])
+        v = B.stage_forward(self.handle, mb_id, ub, x.data_ptr(), y.data_ptr())
+        return y, v
+
+    def input_view(self, mb_id: int, ub: int) -> torch.Tensor:
+        """Tensor view of the workspace rows where the input of (mb_id, ub) belongs."""
+        ptr = B.stage_input_ptr(self.handle, mb_id, ub)
+        off = ptr - self.act.data_ptr()
+        nbytes = self.mb * self.layers[0][0] * self.act_elt()
+        return self.act[off: off + nbytes].view(self.tdtype).view(self.mb, self.layers[0][0])
+
+    def act_elt(self) -> int:
+        return 2 if self.dtype == "bf16" else 4
+
+    def loss(self, mb_id: int, logits: torch.Tensor, labels: torch.Tensor):
+        rows = self.mb * self.n
+        assert logits.shape == (rows, self.layers[-1][1]) and logits.is_contiguous() and logits.dtype == self.tdtype
+        assert labels.dtype == torch.int32 and labels.shape == (rows,)
+        dlogits = torch.empty_like(logits)
+        loss = torch.empty(1, dtype=torch.float32, device=self.device)
+        B.stage_loss_softmax_ce(self.handle, mb_id, logits.data_ptr(), labels.data_ptr(), dlogits.data_ptr(),
+                                loss.data_ptr())
+        return loss, dlogits
+
+    def backward(self, mb_id: int, dy: torch.Tensor, dx: Optional[torch.Tensor] = None):
+        rows = self.mb * self.n
+        assert dy.shape == (rows, self.layers[-1][1]) and dy.is_contiguous() and dy.dtype == self.tdtype
+        if self.needs_dx and dx is None:
+            dx = torch.empty(rows, self.layers[0][0], dtype=self.tdtype, device=self.device)
+        if dx is not None:
+            assert dx.shape == (rows, self.layers[0][0]) and dx.is_contiguous() and dx.dtype == self.tdtype
+        delta = B.stage_backward(self.handle, mb_id, dy.data_ptr(), dx.data_ptr() if dx is not None else 0)
+        return dx, delta
+
+    def blend_update(self, mb_done: int, mb_next: int = B.TP_NONE) -> int:
+        return B.stage_blend_update(self.handle, mb_done, mb_next)
+
+    def query(self):
+        return B.stage_query(self.handle)
+
+    def export(self, version: int) -> torch.Tensor:
+        out = torch.empty(self.P, dtype=torch.float32, device=self.device)
+        B.stage_export_params(self.handle, version, out.data_ptr())
+        return out
+
+    def close(self):
+        if self.handle is not None:
+            torch.cuda.synchronize(self.device)
+            B.stage_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class GpuPipeline:
+    """K stages on one GPU driven through the library's own nF1B event list."""
+
+    def __init__(self, workload, stage_params: List[List[np.ndarray]], *, policy: str, device="cuda:0",
+                 fuse_next_blend: bool = True):
+        self.w = workload
+        self.K = workload.K
+        self.fuse = fuse_next_blend
+        self.stages = [GpuStage([(l.in_features, l.out_features, l.act) for l in workload.stages[s]], stage_params[s],
+                                dtype=workload.dtype, mb=workload.mb, n=workload.n, stage_index=s, num_stages=self.K,
+                                policy=policy, lam=workload.lam, lr=workload.lr, momentum=workload.momentum,
+                                device=device) for s in range(self.K)]
+        self.device = torch.device(device)
+
+    def run(self, num_mb: int, get_input: Callable[[int], torch.Tensor], get_labels: Callable[[int], torch.Tensor],
+            on_event=None):
+        w = self.w
+        events = B.tp_schedule_events(self.K, num_mb)
+        # per stage: mini-batches in backward order, to name the next backward for the fused update
+        acts: Dict[tuple, torch.Tensor] = {}
+        grads: Dict[tuple, torch.Tensor] = {}
+        losses: Dict[int, torch.Tensor] = {}
+        rows = w.n * w.mb
+        for (t, kind, s, j) in events:
+            st = self.stages[s]
+            info = {}
+            if kind == "F":
+                x = get_input(j) if s == 0 else acts.pop((s - 1, j))
+                y = torch.empty(rows, st.layers[-1][1], dtype=st.tdtype, device=self.device)
+                for ub in range(w.n):
+                    _, v = st.forward(j, ub, x[ub * w.mb:(ub + 1) * w.mb], y[ub * w.mb:(ub + 1) * w.mb])
+                acts[(s, j)] = y
+                info.update(y=y, v_f=v)
+            else:
+                if s == self.K - 1:
+                    logits = acts.pop((s, j))
+                    loss, dy = st.loss(j, logits, get_labels(j))
+                    losses[j] = loss
+                    info["loss"] = loss
+                else:
+                    dy = grads.pop((s + 1, j))
+                info["dy"] = dy
+                info["latest_before"] = st.query().latest_version
+                dx, delta = st.backward(j, dy)
+                if s > 0:
+                    grads[(s, j)] = dx
+                nxt = j + 1 if (self.fuse and j + 1 < num_mb) else B.TP_NONE
+                if nxt != B.TP_NONE:
+                    q = st.query()
+                    known = [q.in_flight_mb[i] for i in range(q.num_in_flight)]
+                    if nxt not in known:
+                        nxt = B.TP_NONE
+                info.update(dx=dx, delta=delta)
+                if on_event is not None:
+                    on_event("pre_update", (t, kind, s, j), self, info)
+                info["new_version"] = st.blend_update(j, nxt)
+            if on_event is not None:
+                on_event("done", (t, kind, s, j), self, info)
+        return events, losses
+
+    def close(self):
+        for st in self.stages:
+            st.close()

@@ -1,0 +1,211 @@
+"""Host-side checks of the HIP library that need no GPU: it loads, exports every symbol the
+header declares, and its integer bookkeeping (schedule, versions, ring slots, reference
+counts, delta, coefficients, error codes) equals the oracle's bit for bit.  Stages are created
+without device buffers, a mode in which the library launches nothing."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle.pipeline import Pipeline
+from oracle.schedule import closed_form, simulate
+from oracle.significance import POLICIES, coefficients
+from paper_2509_23241_amd import binding as B
+from synth_inputs.workloads import Dense
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "timeprest_stage.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:const\s+char\s*\*|int)\s+(\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert len(names) >= 15
+    assert sorted(B.EXPORTS) == names
+    for name in names:
+        assert hasattr(B.lib, name), name
+
+
+def test_struct_sizes_match_header_layout():
+    import ctypes as C
+    assert C.sizeof(B.tp_layer_desc) == 64
+    assert C.sizeof(B.tp_stage_desc) == 10 * 4 + 3 * 8 + 32 * 64
+    assert C.sizeof(B.tp_event) == 24
+
+
+@pytest.mark.parametrize("K,num", [(1, 5), (2, 8), (3, 7), (4, 12), (6, 9), (4, 2)])
+def test_schedule_events_equal_oracle(K, num):
+    ref = [(e.t, e.kind, e.s, e.j) for e in simulate(K, num)[0]]
+    assert B.tp_schedule_events(K, num) == ref
+
+
+def test_blend_coefficients_equal_oracle():
+    for policy in POLICIES:
+        for lam in (0.01, 0.1, float(np.log(2)), 1.0):
+            for delta in range(0, 6):
+                got = B.tp_blend_coefficients(policy, delta, lam)
+                ref = coefficients(policy, delta, lam)
+                assert np.allclose(got, ref, rtol=1e-15, atol=1e-16), (policy, lam, delta)
+    assert B.tp_blend_coefficients("eq1", 0, 0.3) == (1.0, 0.0)
+    assert B.tp_blend_coefficients("convex", 0, 0.3) == (1.0, 0.0)
+
+
+def _dry_stage(K, s, policy, n=2, C=None, in_flight=None):
+    depth = K - s
+    d = B.make_desc([(5, 5, "relu")], dtype="f32", mb=2, n=n, stage_index=s, num_stages=K,
+                    ring_capacity=C if C is not None else (1 if policy == "latest" else depth),
+                    max_in_flight=in_flight if in_flight is not None else depth, policy=policy,
+                    needs_dx=s > 0, lam=0.1, lr=0.01, momentum=0.9)
+    return B.stage_init(d, None, 0)
+
+
+def _live(q):
+    return {q.slot_version[i]: q.slot_refcnt[i] for i in range(q.ring_capacity) if q.slot_occupied[i]}
+
+
+@pytest.mark.parametrize("policy", POLICIES)
+@pytest.mark.parametrize("K", [1, 2, 4])
+def test_bookkeeping_equals_oracle_under_full_schedule(policy, K):
+    n, num = 2, 11
+    specs = tuple((Dense(5, 5, "relu"),) for _ in range(K - 1)) + ((Dense(5, 3, "none"),),)
+    rng = np.random.default_rng(3)
+    params = [[rng.standard_normal((l.out_features, l.in_features)) * 0.3, np.zeros(l.out_features)]
+              for st in specs for l in st]
+    pipe = Pipeline(specs, [params[s] for s in range(K)], policy=policy, lam=0.1, lr=0.01, momentum=0.9, n=n, mb=2)
+    handles = [_dry_stage(K, s, policy, n=n) for s in range(K)]
+    checked = []
+
+    def on_event(ev, p, info):
+        h, ost = handles[ev.s], p.stages[ev.s]
+        if ev.kind == "F":
+            for ub in range(n):
+                v = B.stage_forward(h, ev.j, ub, 0, 0)
+                assert v == info["v_f"]
+        else:
+            delta = B.stage_backward(h, ev.j, 0, 0)
+            _, _, v_f, v_now, d_ref = info["trace"]
+            assert delta == d_ref
+            assert delta == (0 if policy == "latest" else closed_form(K, ev.s, ev.j)[2])
+            new_v = B.stage_blend_update(h, ev.j, B.TP_NONE)
+            assert new_v == ost.latest
+        q = B.stage_query(h)
+        assert q.latest_version == ost.latest
+        live = _live(q)
+        assert sorted(live) == ost.live_versions()
+        for v, rc in live.items():
+            assert rc == ost.refcnt[v]
+            assert q.slot_version[v % q.ring_capacity] == v        # slot = version mod C
+        assert sorted(q.in_flight_mb[i] for i in range(q.num_in_flight)) == sorted(ost.inflight)
+        for i in range(q.num_in_flight):
+            assert q.in_flight_vf[i] == ost.inflight[q.in_flight_mb[i]]["v_f"]
+        checked.append(ev)
+
+    pipe.run(num, lambda j: np.zeros((2 * n, 5)), lambda j: np.zeros(2 * n, dtype=int), on_event=on_event)
+    assert len(checked) == 2 * K * num
+    for h in handles:
+        B.stage_destroy(h)
+
+
+def test_fused_lookahead_marks_the_next_backward():
+    K, s = 4, 1                                  # paper's example: machine 2 of 4
+    h = _dry_stage(K, s, "eq1")
+    for j in range(3):                           # K - s = 3 mini-batches enter
+        for ub in range(2):
+            B.stage_forward(h, j, ub, 0, 0)
+    assert B.stage_backward(h, 0, 0, 0) == 0
+    assert B.stage_blend_update(h, 0, 1) == 1    # builds W_b for mini-batch 1 on the fly
+    assert B.stage_query(h).wb_ready_mb == 1
+    for ub in range(2):
+        B.stage_forward(h, 3, ub, 0, 0)          # mini-batch 4 (1-indexed) forwards on version 1
+    assert B.stage_backward(h, 1, 0, 0) == 1
+    assert B.stage_query(h).wb_ready_mb == B.TP_NONE
+    B.stage_blend_update(h, 1, 2)
+    assert B.stage_backward(h, 2, 0, 0) == 2
+    B.stage_blend_update(h, 2, 3)
+    q = B.stage_query(h)
+    assert q.latest_version == 3 and _live(q) == {1: 1, 3: 0}
+    assert B.stage_backward(h, 3, 0, 0) == 2     # W_2(1|3): stale 1, latest 3, delta 2
+    B.stage_destroy(h)
+
+
+def test_error_codes():
+    h = _dry_stage(2, 0, "eq1")
+    def code(fn, *a):
+        with pytest.raises(B.StageLibError) as ei:
+            fn(*a)
+        return ei.value.code
+    assert code(B.stage_forward, h, 0, 1, 0, 0) == B.TP_ESTATE            # first forward must be ub 0
+    B.stage_forward(h, 0, 0, 0, 0)
+    assert code(B.stage_forward, h, 0, 0, 0, 0) == B.TP_ESTATE            # repeated micro-batch
+    assert code(B.stage_backward, h, 0, 0, 0) == B.TP_ESTATE              # not all forwards seen
+    assert code(B.stage_backward, h, 7, 0, 0) == B.TP_ESTATE              # unknown mini-batch
+    assert code(B.stage_blend_update, h, 0, B.TP_NONE) == B.TP_ESTATE     # no gradient pending
+    B.stage_forward(h, 0, 1, 0, 0)
+    B.stage_forward(h, 1, 0, 0, 0)
+    B.stage_forward(h, 1, 1, 0, 0)
+    assert code(B.stage_forward, h, 2, 0, 0, 0) == B.TP_ESTATE            # more than K-s in flight
+    B.stage_backward(h, 0, 0, 0)
+    assert code(B.stage_backward, h, 1, 0, 0) == B.TP_ESTATE              # previous gradient not applied
+    assert code(B.stage_blend_update, h, 0, 5) == B.TP_ESTATE             # look-ahead for unknown mini-batch
+    B.stage_blend_update(h, 0, 1)
+    assert code(B.stash_push, h, 9) == B.TP_ENOVERSION
+    assert code(B.stash_evict, h, 9) == B.TP_ENOVERSION
+    assert code(B.stage_export_params, h, 9, 0) == B.TP_ENOVERSION
+    assert B.stash_evict(h, 1) == B.TP_EBUSY                              # the latest version stays
+    assert B.stash_push(h, 0) == 0                                        # version 0 sits in slot 0
+    assert B.stash_evict(h, 0) == B.TP_EBUSY                              # still used by mini-batch 1
+    assert "users" in B.tp_last_error()
+    B.stage_destroy(h)
+    # an update with the forward version still pinned and nowhere to keep it
+    h = _dry_stage(2, 0, "stashed", C=1, in_flight=2)
+    for j in range(2):
+        for ub in range(2):
+            B.stage_forward(h, j, ub, 0, 0)
+    B.stage_backward(h, 0, 0, 0)
+    assert code(B.stage_blend_update, h, 0, B.TP_NONE) == B.TP_EFULL
+    B.stage_destroy(h)
+    # caller-driven eviction makes a later backward fail with TP_ENOVERSION
+    h = _dry_stage(2, 0, "eq1", C=2)
+    for ub in range(2):
+        B.stage_forward(h, 0, ub, 0, 0)
+    for ub in range(2):
+        B.stage_forward(h, 1, ub, 0, 0)
+    B.stage_backward(h, 0, 0, 0)
+    B.stage_blend_update(h, 0, B.TP_NONE)
+    assert B.stash_evict(h, 0) == B.TP_OK                                 # drops mini-batch 1's pin, frees slot
+    assert code(B.stage_backward, h, 1, 0, 0) == B.TP_ENOVERSION
+    B.stage_destroy(h)
+
+
+def test_invalid_descriptions():
+    good = dict(dtype="f32", mb=2, n=2, stage_index=0, num_stages=2, ring_capacity=2, max_in_flight=2,
+                policy="eq1", needs_dx=False, lam=0.1, lr=0.01, momentum=0.9)
+    for bad in (dict(lam=0.0), dict(mb=0), dict(ring_capacity=0), dict(ring_capacity=17), dict(stage_index=2),
+                dict(policy=9), dict(dtype=5), dict(max_in_flight=0)):
+        d = B.make_desc([(4, 4, "relu")], **{**good, **bad})
+        with pytest.raises(B.StageLibError) as ei:
+            B.stage_workspace_query(d)
+        assert ei.value.code == B.TP_EINVAL
+    d = B.make_desc([(4, 8, "relu"), (4, 4, "none")], **good)             # layer shapes do not chain
+    with pytest.raises(B.StageLibError):
+        B.stage_workspace_query(d)
+    d = B.make_desc([], **good)
+    with pytest.raises(B.StageLibError):
+        B.stage_workspace_query(d)
+
+
+def test_workspace_layout():
+    d = B.make_desc([(256, 512, "relu"), (512, 10, "none")], dtype="bf16", mb=32, n=4, stage_index=0, num_stages=2,
+                    ring_capacity=2, max_in_flight=2, policy="convex", needs_dx=False, lam=0.1, lr=0.01, momentum=0.9)
+    s = B.stage_workspace_query(d)
+    assert s.w_offset[0] == 0 and s.b_offset[0] == 256 * 512
+    assert s.w_offset[1] == 256 * 512 + 512 and s.b_offset[1] == s.w_offset[1] + 5120
+    assert s.param_count == s.b_offset[1] + 64 and s.param_count % 64 == 0
+    assert s.ring_bytes == 2 * s.param_count * 4 and s.wfwd_bytes == 2 * s.param_count
+    assert s.momentum_bytes == s.grad_bytes == 4 * s.param_count
