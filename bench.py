@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the stage hot path on one MI355X.
+
+One "step" is one steady-state mini-batch at a pipeline stage: the backward pass of the oldest
+mini-batch in flight (dgrad + wgrad on the prescribed weights), the fused update that also builds
+the intermediate weights of the next backward and writes the new version into the stash ring, and
+the n micro-batch forwards of the mini-batch that enters.  The workload is the interior stage
+(stage 1 of 4) of the 8-layer GELU MLP of width 4096, bf16 activations with fp32 master weights,
+micro-batch 256 x 8, I-TiMePReSt blend, staleness 2 in steady state.  Inputs are seeded synthetic
+tensors resident in HBM before the timed region.
+
+Prints ONE JSON line: stage throughput in samples/s, the roofline of the dominant kernel (timed
+with HIP events inside the timed region) and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--policy", default="convex", choices=["latest", "eq1", "convex", "stashed"])
+    ap.add_argument("--stage", type=int, default=1)
+    ap.add_argument("--width", type=int, default=4096)
+    ap.add_argument("--mb", type=int, default=256)
+    ap.add_argument("--n", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-minibatches", type=int, default=3)
+    return ap.parse_args()
+
+
+def kernel_work(cls, w, s):
+    """Algorithmic work of ONE launch of a kernel class at stage s: (flops, bytes)."""
+    layers = w.stages[s]
+    rows = w.n * w.mb
+    P = sum(l.in_features * l.out_features + l.out_features for l in layers)
+    L = layers[0]                      # the timed stages have equal layers
+    fin, fout = L.in_features, L.out_features
+    if cls == "fprop":                 # one micro-batch, one layer: x, W in; z, a out
+        return 2.0 * w.mb * fin * fout, 2.0 * (w.mb * fin + fin * fout + 2 * w.mb * fout)
+    if cls == "dgrad":                 # dz, W_b, z_prev in; dz_prev out
+        return 2.0 * rows * fin * fout, 2.0 * (rows * fout + fin * fout + 2 * rows * fin)
+    if cls == "wgrad":                 # dz, x in; dW (fp32) out
+        return 2.0 * rows * fin * fout, 2.0 * (rows * fout + rows * fin) + 4.0 * fin * fout
+    if cls == "update":                # g, m, W[v], W[v_f] in; m, W[v+1] fp32 + two bf16 copies out
+        return 8.0 * P, 28.0 * P
+    if cls == "act_bwd":
+        return 0.0, 3 * 2.0 * rows * fout
+    if cls == "colsum":
+        return 0.0, 2.0 * rows * fout
+    return 0.0, 0.0
+
+
+def cpu_baseline(w, s, policy, minibatches):
+    """The oracle as it stands, timed on the host: the same stage, the same step, fp64 numpy."""
+    import numpy as np
+    from oracle.stage import Stage
+    from synth_inputs import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    params = W.init_params(w, s)
+    st = Stage(w.stages[s], params, policy=policy, lam=w.lam, lr=w.lr, momentum=w.momentum, n=w.n,
+               first_stage=(s == 0))
+    depth = w.K - s
+    xs = [W.stage_input(w, s, j) for j in range(2)]
+    dys = [W.stage_upstream_grad(w, s, j) for j in range(2)]
+
+    def fwd(j):
+        x = xs[j % 2]
+        for ub in range(w.n):
+            st.forward(j, ub, x[ub * w.mb:(ub + 1) * w.mb])
+
+    for j in range(depth):
+        fwd(j)
+    t0 = time.perf_counter()
+    for j in range(minibatches):
+        st.backward(j, dys[j % 2])
+        st.update(j)
+        fwd(j + depth)
+    dt = time.perf_counter() - t0
+    return {"value": minibatches * w.n * w.mb / dt, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{minibatches} steady-state mini-batches ({minibatches * w.n * w.mb} samples) of the same stage, "
+                      f"numpy fp64, {dt:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (one pipeline stage per GPU; no collectives are part "
+              "of it); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2509_23241_amd import binding as B
+    from paper_2509_23241_amd.runner import GpuStage
+    from synth_inputs import workloads as W
+
+    w = W.mlp_wide(width=args.width, mb=args.mb, n=args.n)
+    s = args.stage
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    depth = w.K - s
+    layers = [(l.in_features, l.out_features, l.act) for l in w.stages[s]]
+    st = GpuStage(layers, W.init_params(w, s), dtype=w.dtype, mb=w.mb, n=w.n, stage_index=s, num_stages=w.K,
+                  policy=args.policy, lam=w.lam, lr=w.lr, momentum=w.momentum, device=dev)
+    tdt = st.tdtype
+    rows = w.n * w.mb
+    nbuf = 2                                       # distinct synthetic mini-batches, resident in HBM
+    xs = [torch.from_numpy(W.stage_input(w, s, j)).to(dev).to(tdt) for j in range(nbuf)]
+    dys = [torch.from_numpy(W.stage_upstream_grad(w, s, j)).to(dev).to(tdt) for j in range(nbuf)]
+    y = torch.empty(rows, layers[-1][1], dtype=tdt, device=dev)
+    dx = torch.empty(rows, layers[0][0], dtype=tdt, device=dev) if st.needs_dx else None
+
+    def forward(j):
+        x = xs[j % nbuf]
+        for ub in range(w.n):
+            st.forward(j, ub, x[ub * w.mb:(ub + 1) * w.mb], y[ub * w.mb:(ub + 1) * w.mb])
+
+    def step(j):
+        st.backward(j, dys[j % nbuf], dx)
+        st.blend_update(j, j + 1 if depth > 1 else B.TP_NONE)
+        forward(j + depth)
+
+    for j in range(depth):                         # fill the stage: K - s mini-batches in flight
+        forward(j)
+    j = 0
+    for _ in range(args.warmup):
+        step(j)
+        j += 1
+    torch.cuda.synchronize()
+    B.stage_profile_begin(st.handle, args.steps * (8 + 2 * len(layers) * (w.n + 2)) + 64)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(j)
+        j += 1
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = B.stage_profile_end(st.handle)
+    q = st.query()
+    delta_steady = min(depth - 1, int(q.latest_version))
+
+    ms_per_step = dt / args.steps * 1e3
+    value = rows / (dt / args.steps)
+    kernels = {}
+    for cls in B.KERNEL_CLASSES:
+        launches, ms = prof[cls]
+        if launches == 0:
+            continue
+        flops, nbytes = kernel_work(cls, w, s)
+        avg_us = ms / launches * 1e3
+        kernels[cls] = {"launches_per_step": launches / args.steps, "avg_us": round(avg_us, 2),
+                        "share_of_step": round(ms / args.steps / ms_per_step, 4),
+                        "tflops": round(flops / (avg_us * 1e-6) / 1e12, 2) if flops else None,
+                        "gbs": round(nbytes / (avg_us * 1e-6) / 1e9, 1) if nbytes else None}
+    dominant = max(kernels, key=lambda c: kernels[c]["share_of_step"])
+    dk = kernels[dominant]
+    if dominant in ("fprop", "dgrad", "wgrad"):
+        flops, _ = kernel_work(dominant, w, s)
+        achieved = flops / (dk["avg_us"] * 1e-6) / 1e12
+        roofline = {"kernel": dominant, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None}
+    else:
+        _, nbytes = kernel_work(dominant, w, s)
+        achieved = nbytes / (dk["avg_us"] * 1e-6) / 1e9
+        roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
+    out = {
+        "metric": "stage fwd+bwd samples/s on 1 MI355X; MFMA util %; blend/update HBM GB/s",
+        "value": round(value, 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"stage {s} of the 4-stage 8-layer GELU MLP width {args.width}: bf16 activations, "
+                               f"fp32 master weights, micro-batch {w.mb} x {w.n}, policy {args.policy}, "
+                               f"lambda {w.lam}, staleness {delta_steady}, one step = 1 backward + 1 fused update/blend "
+                               f"+ {w.n} micro-batch forwards",
+                   "params_per_stage": int(st.P), "ring_slots": int(st.C)},
+        "roofline": roofline,
+        "kernels": kernels,
+        "mfma_util_pct": {c: round(100 * kernels[c]["tflops"] / PEAK_BF16_TFLOPS, 2)
+                          for c in ("fprop", "dgrad", "wgrad") if c in kernels},
+        "update_hbm_gbs": kernels.get("update", {}).get("gbs"),
+        "profile_dropped": prof["dropped"],
+    }
+    st.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, s, args.policy, args.cpu_minibatches)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

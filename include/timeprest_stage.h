@@ -243,6 +243,31 @@ typedef struct tp_event {
 int tp_schedule_events(int32_t num_stages, uint64_t num_minibatches, tp_event* out,
                        uint64_t capacity, uint64_t* count);
 
+/* Measurement hooks (not part of the method): while profiling is on, every kernel the stage
+ * enqueues is bracketed by a pair of HIP events on the stage's stream.  stage_profile_end waits
+ * for the stream (the only call of this library that synchronises), adds up the elapsed time
+ * per kernel class and switches profiling off.  max_launches bounds the number of event pairs;
+ * launches beyond it are counted in `dropped` and not timed. */
+enum tp_kernel_class {
+  TP_K_FPROP = 0,    /* z = x W^T + b, a = act(z)                    */
+  TP_K_DGRAD = 1,    /* dx = dz W_b (.) act'                         */
+  TP_K_WGRAD = 2,    /* dW = dz^T x                                  */
+  TP_K_COLSUM = 3,   /* db = column sums of dz                       */
+  TP_K_ACT_BWD = 4,  /* dz = dy (.) act'(z)                          */
+  TP_K_UPDATE = 5,   /* fused momentum + update + copies + blend     */
+  TP_K_BLEND = 6,    /* intermediate weights on their own            */
+  TP_K_LOSS = 7,     /* softmax cross-entropy                        */
+  TP_K_COPY = 8,     /* device-to-device copies and conversions      */
+  TP_K_CLASSES = 9
+};
+typedef struct tp_profile {
+  uint64_t launches[TP_K_CLASSES];
+  double ms[TP_K_CLASSES];
+  uint64_t dropped;
+} tp_profile;
+int stage_profile_begin(tp_stage* st, uint32_t max_launches);
+int stage_profile_end(tp_stage* st, tp_profile* out);
+
 const char* tp_last_error(void);
 
 #ifdef __cplusplus

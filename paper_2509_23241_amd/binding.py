@@ -21,7 +21,8 @@ DTYPE = {"f32": TP_F32, "bf16": TP_BF16}
 
 EXPORTS = ["stage_workspace_query", "stage_init", "stage_destroy", "stage_forward", "stage_input_ptr",
            "stage_loss_softmax_ce", "stage_backward", "stage_blend_update", "stash_push", "stash_evict",
-           "stage_query", "stage_export_params", "tp_blend_coefficients", "tp_schedule_events", "tp_last_error"]
+           "stage_query", "stage_export_params", "tp_blend_coefficients", "tp_schedule_events",
+           "stage_profile_begin", "stage_profile_end", "tp_last_error"]
 
 
 class tp_layer_desc(C.Structure):
@@ -62,6 +63,13 @@ class tp_event(C.Structure):
                 ("mb_id", C.c_uint64)]
 
 
+KERNEL_CLASSES = ["fprop", "dgrad", "wgrad", "colsum", "act_bwd", "update", "blend", "loss", "copy"]
+
+
+class tp_profile(C.Structure):
+    _fields_ = [("launches", C.c_uint64 * 9), ("ms", C.c_double * 9), ("dropped", C.c_uint64)]
+
+
 class StageLibError(RuntimeError):
     def __init__(self, code, text):
         super().__init__(f"timeprest_stage error {code}: {text}")
@@ -69,6 +77,10 @@ class StageLibError(RuntimeError):
 
 
 def _load():
+    # The library must share the HIP runtime of the process that owns the device memory and the
+    # streams it is handed.  torch ships its own libamdhip64 (same soname); importing torch first
+    # makes the dynamic loader resolve the library's dependency to that already-loaded runtime.
+    import torch  # noqa: F401
     path = lib_path()
     if not os.path.exists(path):
         raise ImportError(f"{path} is missing: build it first (python -m paper_2509_23241_amd.build); "
@@ -92,6 +104,8 @@ lib.stage_query.argtypes = [_vp, C.POINTER(tp_state)]
 lib.stage_export_params.argtypes = [_vp, _u64, _vp]
 lib.tp_blend_coefficients.argtypes = [_i32, _u32, C.c_double, C.POINTER(C.c_double), C.POINTER(C.c_double)]
 lib.tp_schedule_events.argtypes = [_i32, _u64, C.POINTER(tp_event), _u64, C.POINTER(_u64)]
+lib.stage_profile_begin.argtypes = [_vp, _u32]
+lib.stage_profile_end.argtypes = [_vp, C.POINTER(tp_profile)]
 lib.tp_last_error.restype = C.c_char_p
 for _name in EXPORTS[:-1]:
     getattr(lib, _name).restype = C.c_int
@@ -206,3 +220,16 @@ def tp_schedule_events(num_stages: int, num_minibatches: int):
     cnt = _u64()
     _check(lib.tp_schedule_events(num_stages, num_minibatches, arr, cap, C.byref(cnt)))
     return [(arr[i].t, "FB"[arr[i].kind], arr[i].stage, arr[i].mb_id) for i in range(cnt.value)]
+
+
+def stage_profile_begin(st, max_launches: int):
+    _check(lib.stage_profile_begin(st, max_launches))
+
+
+def stage_profile_end(st) -> dict:
+    """Waits for the stage's stream; returns {class: (launches, total_ms)} plus 'dropped'."""
+    p = tp_profile()
+    _check(lib.stage_profile_end(st, C.byref(p)))
+    out = {name: (p.launches[i], p.ms[i]) for i, name in enumerate(KERNEL_CLASSES)}
+    out["dropped"] = p.dropped
+    return out

@@ -19,11 +19,13 @@ hipError_t launch_fprop(hipStream_t s, int elt, int M, int N, int K, const void*
 hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* Wb,
                         const void* z_prev, int act_prev, void* out);
 
-// gW = dz^T x  (fp32 [N x K]);  gb = column sums of dz (fp32 [N]).
-// partials: scratch of at least wgrad_scratch_floats(M, N) floats.
-hipError_t launch_wgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* x,
-                        float* gW, float* gb, float* partials);
-size_t wgrad_scratch_floats(int M, int N);
+// gW = dz^T x  (fp32 [N x K]).
+hipError_t launch_wgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* x, float* gW);
+
+// gb = column sums of dz[M x N] (fp32 [N]).
+// partials: scratch of at least colsum_scratch_floats(M, N) floats.
+hipError_t launch_colsum(hipStream_t s, int elt, int M, int N, const void* dz, float* gb, float* partials);
+size_t colsum_scratch_floats(int M, int N);
 
 // dz = dy (.) act'(z)    all [rows x cols] in elt.
 hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* z,

@@ -137,7 +137,7 @@ __global__ __launch_bounds__(kThreads) void colsum_final_kernel(int chunks, int 
 
 }  // namespace
 
-size_t wgrad_scratch_floats(int M, int N) {
+size_t colsum_scratch_floats(int M, int N) {
   return (size_t)((M + kColChunkRows - 1) / kColChunkRows) * (size_t)N;
 }
 
@@ -160,8 +160,7 @@ hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void*
   return simt<EPI_DGRAD>(s, elt, M, K, N, dz, N, 1, Wb, K, 1, e);
 }
 
-hipError_t launch_wgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* x, float* gW, float* gb,
-                        float* partials) {
+hipError_t launch_colsum(hipStream_t s, int elt, int M, int N, const void* dz, float* gb, float* partials) {
   const int chunks = (M + kColChunkRows - 1) / kColChunkRows;
   dim3 g1((N + 63) / 64, chunks);
   if (elt == ELT_BF16)
@@ -171,8 +170,10 @@ hipError_t launch_wgrad(hipStream_t s, int elt, int M, int N, int K, const void*
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   hipLaunchKernelGGL(colsum_final_kernel, dim3((N + kThreads - 1) / kThreads), dim3(kThreads), 0, s, chunks, N, partials, gb);
-  err = hipGetLastError();
-  if (err != hipSuccess) return err;
+  return hipGetLastError();
+}
+
+hipError_t launch_wgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* x, float* gW) {
   if (elt == ELT_BF16 && mfma_wgrad_supported(M, N, K))
     return mfma_wgrad(s, M, N, K, (const uint16_t*)dz, (const uint16_t*)x, gW);
   EpiArgs e{};

@@ -122,7 +122,7 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
   p->dz_bytes = round_up(rows * max_feat * p->elt_size, 256);
   uint64_t wg = 0;
   for (const LayerPlan& lp : p->layers)
-    wg = std::max<uint64_t>(wg, tp::wgrad_scratch_floats((int)rows, lp.d.out_features));
+    wg = std::max<uint64_t>(wg, tp::colsum_scratch_floats((int)rows, lp.d.out_features));
   p->partial_floats = round_up(std::max<uint64_t>({wg, tp::update_scratch_floats(), rows}), 64);
   tp_sizes& s = p->sizes;
   s.param_count = P;
@@ -141,8 +141,18 @@ bool stashing(int policy) { return policy != TP_LATEST; }
 
 }  // namespace
 
+struct ProfEntry {
+  int cls;
+  hipEvent_t start, stop;
+};
+
 struct tp_stage {
   tp_stage_desc desc;
+  // profiling: event pairs recorded around each launch while switched on
+  bool prof_on = false;
+  std::vector<ProfEntry> prof_pool;
+  size_t prof_used = 0;
+  uint64_t prof_dropped = 0;
   Plan plan;
   tp_buffers bufs;
   hipStream_t stream;
@@ -174,6 +184,22 @@ struct tp_stage {
   void evict_if_unused(uint64_t v) {
     int s = find_slot(v);
     if (s >= 0 && v != latest && slots[s].refcnt == 0) slots[s].occupied = false;
+  }
+};
+
+// Brackets the launches made during its lifetime with an event pair when profiling is on.
+struct ProfScope {
+  tp_stage* st;
+  ProfEntry* e = nullptr;
+  ProfScope(tp_stage* s, int cls) : st(s) {
+    if (!st->prof_on) return;
+    if (st->prof_used >= st->prof_pool.size()) { st->prof_dropped++; return; }
+    e = &st->prof_pool[st->prof_used++];
+    e->cls = cls;
+    (void)hipEventRecord(e->start, st->stream);
+  }
+  ~ProfScope() {
+    if (e) (void)hipEventRecord(e->stop, st->stream);
   }
 };
 
@@ -296,6 +322,10 @@ int stage_init(const tp_stage_desc* desc, const tp_buffers* bufs, void* hip_stre
 
 int stage_destroy(tp_stage* st) {
   if (!st) return fail(TP_EINVAL, "null stage");
+  for (ProfEntry& e : st->prof_pool) {
+    (void)hipEventDestroy(e.start);
+    (void)hipEventDestroy(e.stop);
+  }
   delete st;
   return TP_OK;
 }
@@ -383,11 +413,14 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
   for (int l = 0; l < L; ++l) {
     const LayerPlan& lp = st->plan.layers[l];
     char* x_saved = aslot + lp.x_off + row0 * lp.d.in_features * es;
-    if (l == 0 && x_dev != (const void*)x_saved)
+    if (l == 0 && x_dev != (const void*)x_saved) {
+      ProfScope ps(st, TP_K_COPY);
       HIP_TRY(hipMemcpyAsync(x_saved, x_dev, (size_t)d.mb * lp.d.in_features * es, hipMemcpyDeviceToDevice, st->stream));
+    }
     void* z_out = lp.z_off == UINT64_MAX ? nullptr : aslot + lp.z_off + row0 * lp.d.out_features * es;
     void* a_out = (l == L - 1) ? y_dev
                                : (void*)(aslot + st->plan.layers[l + 1].x_off + row0 * lp.d.out_features * es);
+    ProfScope ps(st, TP_K_FPROP);
     HIP_TRY(tp::launch_fprop(st->stream, d.dtype, d.mb, lp.d.out_features, lp.d.in_features, x_saved,
                              wcopy + lp.w_off * es, master + lp.b_off, lp.d.act, z_out, a_out));
   }
@@ -404,6 +437,7 @@ int stage_loss_softmax_ce(tp_stage* st, uint64_t mb_id, const void* logits_dev, 
   if (!logits_dev || !labels_dev || !dlogits_dev || !loss_dev) return fail(TP_EINVAL, "null pointer");
   const int rows = st->desc.mb * st->desc.n;
   const int classes = st->plan.layers.back().d.out_features;
+  ProfScope ps(st, TP_K_LOSS);
   HIP_TRY(tp::launch_softmax_ce(st->stream, st->desc.dtype, rows, classes, logits_dev, labels_dev, dlogits_dev,
                                 st->partials(), loss_dev));
   return TP_OK;
@@ -441,6 +475,7 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
       double a, b;
       int rc = tp_blend_coefficients(d.policy, delta, d.lambda, &a, &b);
       if (rc) return rc;
+      ProfScope ps(st, TP_K_BLEND);
       HIP_TRY(tp::launch_blend(st->stream, d.dtype, P, st->ring(slot_f), st->ring(slot_now), (float)a, (float)b, st->bufs.wbwd_dev));
       wb = (const char*)st->bufs.wbwd_dev;
     }
@@ -456,6 +491,7 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
       if (last.d.act == TP_ACT_NONE) {
         dz = dy_dev;
       } else {
+        ProfScope ps(st, TP_K_ACT_BWD);
         HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * last.d.out_features, dy_dev, aslot + last.z_off, last.d.act, st->dz_buf(pp)));
         dz = st->dz_buf(pp);
         pp ^= 1;
@@ -463,16 +499,25 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
     }
     for (int l = L - 1; l >= 0; --l) {
       const LayerPlan& lp = st->plan.layers[l];
-      HIP_TRY(tp::launch_wgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, aslot + lp.x_off,
-                               g + lp.w_off, g + lp.b_off, st->partials()));
+      {
+        ProfScope ps(st, TP_K_COLSUM);
+        HIP_TRY(tp::launch_colsum(st->stream, d.dtype, rows, lp.d.out_features, dz, g + lp.b_off, st->partials()));
+      }
+      {
+        ProfScope ps(st, TP_K_WGRAD);
+        HIP_TRY(tp::launch_wgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, aslot + lp.x_off,
+                                 g + lp.w_off));
+      }
       if (l > 0) {
         const LayerPlan& prev = st->plan.layers[l - 1];
         const void* zprev = prev.z_off == UINT64_MAX ? nullptr : aslot + prev.z_off;
+        ProfScope ps(st, TP_K_DGRAD);
         HIP_TRY(tp::launch_dgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, wb + lp.w_off * es,
                                  zprev, prev.d.act, st->dz_buf(pp)));
         dz = st->dz_buf(pp);
         pp ^= 1;
       } else if (d.needs_dx) {
+        ProfScope ps(st, TP_K_DGRAD);
         HIP_TRY(tp::launch_dgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, wb + lp.w_off * es,
                                  nullptr, TP_ACT_NONE, dx_dev));
       }
@@ -539,6 +584,7 @@ int stage_blend_update(tp_stage* st, uint64_t mb_id_done, uint64_t mb_id_next_bw
     u.beta = (float)b;
     u.partials = st->partials();
     u.diag = (double*)st->bufs.diag_dev;
+    ProfScope ps(st, TP_K_UPDATE);
     HIP_TRY(tp::launch_update(st->stream, d.dtype, u));
   }
   st->wb_valid = blend;
@@ -583,6 +629,40 @@ int stage_export_params(tp_stage* st, uint64_t version, void* dst_dev) {
   if (st->dry) return TP_OK;
   if (!dst_dev) return fail(TP_EINVAL, "null destination");
   HIP_TRY(hipMemcpyAsync(dst_dev, st->ring(s), st->plan.sizes.param_count * 4, hipMemcpyDeviceToDevice, st->stream));
+  return TP_OK;
+}
+
+int stage_profile_begin(tp_stage* st, uint32_t max_launches) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  if (st->dry) return fail(TP_ESTATE, "a stage without device buffers launches nothing");
+  if (st->prof_on) return fail(TP_ESTATE, "profiling is already on");
+  while (st->prof_pool.size() < max_launches) {
+    ProfEntry e{};
+    HIP_TRY(hipEventCreate(&e.start));
+    hipError_t err = hipEventCreate(&e.stop);
+    if (err != hipSuccess) { (void)hipEventDestroy(e.start); return fail(TP_EHIP, "hipEventCreate: %s", hipGetErrorString(err)); }
+    st->prof_pool.push_back(e);
+  }
+  st->prof_used = 0;
+  st->prof_dropped = 0;
+  st->prof_on = true;
+  return TP_OK;
+}
+
+int stage_profile_end(tp_stage* st, tp_profile* out) {
+  if (!st || !out) return fail(TP_EINVAL, "null argument");
+  if (!st->prof_on) return fail(TP_ESTATE, "profiling is not on");
+  st->prof_on = false;
+  std::memset(out, 0, sizeof(*out));
+  HIP_TRY(hipStreamSynchronize(st->stream));
+  for (size_t i = 0; i < st->prof_used; ++i) {
+    const ProfEntry& e = st->prof_pool[i];
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, e.start, e.stop));
+    out->launches[e.cls]++;
+    out->ms[e.cls] += (double)ms;
+  }
+  out->dropped = st->prof_dropped;
   return TP_OK;
 }
 
