@@ -15,8 +15,12 @@ __device__ __forceinline__ uint16_t float_to_bf16(float f) {
   return (uint16_t)(u >> 16);
 }
 
+// two fp32 -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32 on gfx950)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)float_to_bf16(lo) | ((uint32_t)float_to_bf16(hi) << 16);
+  typedef float floatx2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const floatx2_t f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
 }
 
 __device__ __forceinline__ float to_float(float v) { return v; }
@@ -40,6 +44,61 @@ __device__ __forceinline__ float act_derivative(float z, int act) {
   if (act == 1) return z > 0.f ? 1.f : 0.f;
   if (act == 2)
     return 0.5f * (1.f + erff(z * 0.70710678118654752f)) + z * 0.39894228040143268f * __expf(-0.5f * z * z);
+  return 1.f;
+}
+
+// GELU (erf form) and its derivative with one exponential and one reciprocal:
+//   erf(x) = 1 - (a1 t + a2 t^2 + a3 t^3 + a4 t^4 + a5 t^5) exp(-x^2),  t = 1/(1 + p x),  x >= 0
+// (Abramowitz & Stegun 7.1.26, |error| <= 1.5e-7), evaluated at x = |z|/sqrt(2), where
+// exp(-x^2) = exp(-z^2/2) is also the Gaussian factor of the derivative.
+struct GeluParts {
+  float cdf;  // Phi(z) = 0.5 (1 + erf(z/sqrt 2))
+  float pdf;  // phi(z) = exp(-z^2/2)/sqrt(2 pi)
+};
+__device__ __forceinline__ GeluParts gelu_parts(float z) {
+  const float x = fabsf(z) * 0.70710678118654752f;
+  const float t = __frcp_rn(fmaf(0.3275911f, x, 1.0f));
+  const float e = __expf(-0.5f * z * z);
+  float poly = fmaf(1.061405429f, t, -1.453152027f);
+  poly = fmaf(poly, t, 1.421413741f);
+  poly = fmaf(poly, t, -0.284496736f);
+  poly = fmaf(poly, t, 0.254829592f);
+  const float half_erfc = 0.5f * poly * t * e;        // 0.5 * (1 - erf(x))
+  GeluParts g;
+  g.cdf = z >= 0.f ? 1.0f - half_erfc : half_erfc;
+  g.pdf = 0.39894228040143268f * e;
+  return g;
+}
+// act(z) and act'(z) together (they share the exponential and the reciprocal)
+struct ActPair {
+  float a, d;
+};
+__device__ __forceinline__ ActPair act_pair_fast(float z, int act) {
+  ActPair p;
+  if (act == 2) {
+    const GeluParts g = gelu_parts(z);
+    p.a = z * g.cdf;
+    p.d = fmaf(z, g.pdf, g.cdf);
+  } else if (act == 1) {
+    p.a = fmaxf(z, 0.f);
+    p.d = z > 0.f ? 1.f : 0.f;
+  } else {
+    p.a = z;
+    p.d = 1.f;
+  }
+  return p;
+}
+__device__ __forceinline__ float act_forward_fast(float z, int act) {
+  if (act == 1) return fmaxf(z, 0.f);
+  if (act == 2) return z * gelu_parts(z).cdf;
+  return z;
+}
+__device__ __forceinline__ float act_derivative_fast(float z, int act) {
+  if (act == 1) return z > 0.f ? 1.f : 0.f;
+  if (act == 2) {
+    const GeluParts g = gelu_parts(z);
+    return fmaf(z, g.pdf, g.cdf);
+  }
   return 1.f;
 }
 

@@ -10,10 +10,19 @@ bool mfma_fprop_supported(int M, int N, int K);
 bool mfma_dgrad_supported(int M, int N, int K);
 bool mfma_wgrad_supported(int M, int N, int K);
 
+// Tuning hook: force tile configuration `cfg` for product 0 = fprop, 1 = dgrad, 2 = wgrad
+// (-1 = back to the heuristic).
+void mfma_set_config(int product, int cfg);
+// Tuning hook: device pointer to two int64 that receive {shader cycles, 100 MHz ticks} of the main
+// loop of workgroup 0 of the direct-to-LDS kernel (null = off).
+void mfma_set_clock_probe(long long* dev_ptr);
+
+// d_out receives act'(z) (what the backward pass multiplies with), a_out = act(z).
 hipError_t mfma_fprop(hipStream_t s, int M, int N, int K, const uint16_t* x, const uint16_t* W, const float* bias,
-                      int act, uint16_t* z_out, uint16_t* a_out);
+                      int act, uint16_t* d_out, uint16_t* a_out);
+// out = (dz Wb) (.) d_prev, d_prev = saved act'(z) of the previous layer or null.
 hipError_t mfma_dgrad(hipStream_t s, int M, int N, int K, const uint16_t* dz, const uint16_t* Wb,
-                      const uint16_t* z_prev, int act_prev, uint16_t* out);
+                      const uint16_t* d_prev, uint16_t* out);
 hipError_t mfma_wgrad(hipStream_t s, int M, int N, int K, const uint16_t* dz, const uint16_t* x, float* gW);
 
 }  // namespace tp

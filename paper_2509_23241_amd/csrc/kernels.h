@@ -10,14 +10,15 @@ namespace tp {
 enum Elt : int { ELT_F32 = 0, ELT_BF16 = 1 };
 enum Act : int { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
 
-// z = x W^T + bias ; a = act(z).   x:[M x K] W:[N x K] (elt), bias: fp32[N].
-// z_out may be null (not saved); a_out is always written.  Both [M x N] in elt.
+// z = x W^T + bias ; a = act(z) ; d = act'(z).   x:[M x K] W:[N x K] (elt), bias: fp32[N].
+// d_out (what the backward pass multiplies with) may be null; a_out is always written.
+// Both [M x N] in elt.
 hipError_t launch_fprop(hipStream_t s, int elt, int M, int N, int K, const void* x, const void* W,
-                        const float* bias, int act, void* z_out, void* a_out);
+                        const float* bias, int act, void* d_out, void* a_out);
 
-// out = (dz W_b) (.) act'(z_prev)   dz:[M x N] W_b:[N x K] z_prev:[M x K] or null (act none).
+// out = (dz W_b) (.) d_prev   dz:[M x N] W_b:[N x K] d_prev:[M x K] saved act'(z), or null.
 hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* Wb,
-                        const void* z_prev, int act_prev, void* out);
+                        const void* d_prev, void* out);
 
 // gW = dz^T x  (fp32 [N x K]).
 hipError_t launch_wgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* x, float* gW);
@@ -27,9 +28,8 @@ hipError_t launch_wgrad(hipStream_t s, int elt, int M, int N, int K, const void*
 hipError_t launch_colsum(hipStream_t s, int elt, int M, int N, const void* dz, float* gb, float* partials);
 size_t colsum_scratch_floats(int M, int N);
 
-// dz = dy (.) act'(z)    all [rows x cols] in elt.
-hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* z,
-                               int act, void* dz);
+// dz = dy (.) d    all [rows x cols] in elt; d = saved act'(z).
+hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* d, void* dz);
 
 // Softmax cross-entropy over `rows` rows of `classes` logits; dlogits = (softmax-onehot)/rows,
 // *loss = mean of the row losses.  row_loss: scratch of `rows` floats.

@@ -5,7 +5,7 @@
 //                   (Eq. 1-2) and on-the-fly diagnostics.  Pure HBM streaming.
 //   blend_kernel    the intermediate weights on their own (when the fused pass did not build them)
 //   convert_kernel  fp32 -> bf16 compute copy
-//   act_backward    dz = dy (.) act'(z)
+//   act_backward    dz = dy (.) d, d = act'(z) saved by the forward pass
 //   softmax_ce      loss and its gradient at the last stage
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -144,13 +144,10 @@ __global__ __launch_bounds__(kThreads) void convert_kernel(size_t n4, const floa
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void act_backward_kernel(size_t count, const T* __restrict__ dy,
-                                                                const T* __restrict__ z, int act,
-                                                                T* __restrict__ dz) {
+                                                                const T* __restrict__ d, T* __restrict__ dz) {
   const size_t stride = (size_t)gridDim.x * kThreads;
-  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < count; i += stride) {
-    const float d = to_float(dy[i]) * act_derivative(to_float(z[i]), act);
-    dz[i] = from_float<T>(d);
-  }
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < count; i += stride)
+    dz[i] = from_float<T>(to_float(dy[i]) * to_float(d[i]));
 }
 
 // One wave per row.
@@ -259,14 +256,14 @@ hipError_t launch_convert(hipStream_t s, int elt, size_t count, const float* src
   return hipGetLastError();
 }
 
-hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* z, int act, void* dz) {
+hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* d, void* dz) {
   const int blocks = stream_blocks(count, 4096);
   if (elt == ELT_BF16)
     hipLaunchKernelGGL(act_backward_kernel<uint16_t>, dim3(blocks), dim3(kThreads), 0, s, count, (const uint16_t*)dy,
-                       (const uint16_t*)z, act, (uint16_t*)dz);
+                       (const uint16_t*)d, (uint16_t*)dz);
   else
     hipLaunchKernelGGL(act_backward_kernel<float>, dim3(blocks), dim3(kThreads), 0, s, count, (const float*)dy,
-                       (const float*)z, act, (float*)dz);
+                       (const float*)d, (float*)dz);
   return hipGetLastError();
 }
 

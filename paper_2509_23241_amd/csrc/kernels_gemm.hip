@@ -22,9 +22,9 @@ enum Epi : int { EPI_STORE_F32 = 0, EPI_FPROP = 1, EPI_DGRAD = 2 };
 struct EpiArgs {
   float* c_f32;        // EPI_STORE_F32: [M x N] fp32
   const float* bias;   // EPI_FPROP
-  void* z_out;         // EPI_FPROP: optional pre-activation
+  void* d_out;         // EPI_FPROP: optional act'(z)
   void* a_out;         // EPI_FPROP: activation; EPI_DGRAD: output
-  const void* z_prev;  // EPI_DGRAD: optional pre-activation of the previous layer
+  const void* d_prev;  // EPI_DGRAD: optional saved act'(z) of the previous layer
   int act;
 };
 
@@ -83,10 +83,10 @@ __global__ __launch_bounds__(kThreads) void gemm_simt_kernel(int M, int N, int K
         e.c_f32[idx] = v;
       } else if (EPI == EPI_FPROP) {
         v += e.bias[n];
-        if (e.z_out) ((T*)e.z_out)[idx] = from_float<T>(v);
+        if (e.d_out) ((T*)e.d_out)[idx] = from_float<T>(act_derivative(v, e.act));
         ((T*)e.a_out)[idx] = from_float<T>(act_forward(v, e.act));
       } else {
-        if (e.z_prev) v *= act_derivative(to_float(((const T*)e.z_prev)[idx]), e.act);
+        if (e.d_prev) v *= to_float(((const T*)e.d_prev)[idx]);
         ((T*)e.a_out)[idx] = from_float<T>(v);
       }
     }
@@ -142,20 +142,20 @@ size_t colsum_scratch_floats(int M, int N) {
 }
 
 hipError_t launch_fprop(hipStream_t s, int elt, int M, int N, int K, const void* x, const void* W, const float* bias,
-                        int act, void* z_out, void* a_out) {
+                        int act, void* d_out, void* a_out) {
   if (elt == ELT_BF16 && mfma_fprop_supported(M, N, K))
-    return mfma_fprop(s, M, N, K, (const uint16_t*)x, (const uint16_t*)W, bias, act, (uint16_t*)z_out, (uint16_t*)a_out);
+    return mfma_fprop(s, M, N, K, (const uint16_t*)x, (const uint16_t*)W, bias, act, (uint16_t*)d_out, (uint16_t*)a_out);
   EpiArgs e{};
-  e.bias = bias; e.z_out = z_out; e.a_out = a_out; e.act = act;
+  e.bias = bias; e.d_out = d_out; e.a_out = a_out; e.act = act;
   return simt<EPI_FPROP>(s, elt, M, N, K, x, K, 1, W, 1, K, e);
 }
 
-hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* Wb, const void* z_prev,
-                        int act_prev, void* out) {
+hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* Wb, const void* d_prev,
+                        void* out) {
   if (elt == ELT_BF16 && mfma_dgrad_supported(M, N, K))
-    return mfma_dgrad(s, M, N, K, (const uint16_t*)dz, (const uint16_t*)Wb, (const uint16_t*)z_prev, act_prev, (uint16_t*)out);
+    return mfma_dgrad(s, M, N, K, (const uint16_t*)dz, (const uint16_t*)Wb, (const uint16_t*)d_prev, (uint16_t*)out);
   EpiArgs e{};
-  e.a_out = out; e.z_prev = z_prev; e.act = act_prev;
+  e.a_out = out; e.d_prev = d_prev;
   // out[M x K] = dz[M x N] . Wb[N x K]: contraction over N
   return simt<EPI_DGRAD>(s, elt, M, K, N, dz, N, 1, Wb, K, 1, e);
 }

@@ -9,9 +9,15 @@
 // contraction index is the strided one is staged as it lies in memory ([k][row]) and each
 // lane gets its 8 k values through two LDS transpose reads.
 //
-// Block: 256 threads = 4 waves in a 2 x 2 grid, block tile BM x BN, k tile 64, LDS double
-// buffered with one barrier per k tile; global loads of tile t+1 are in flight while the
-// matrix cores work on tile t.
+// Two kernels share the tile and epilogue code:
+//   gemm_bf16_mfma_kernel  any shape whose extents are multiples of 8: global loads go through
+//                          registers, one k tile ahead, LDS double buffered and padded.
+//   gemm_bf16_dma_kernel   contraction extent a multiple of 64: global loads write LDS directly
+//                          (global_load_lds_dwordx4), NS stages deep, no staging registers; LDS is
+//                          unpadded, bank conflicts are avoided by an XOR swizzle of the 16-byte
+//                          chunks, applied on the global side of the copy.
+// Workgroup ids are remapped so that the workgroups of one XCD (ids equal mod 8) cover a
+// compact 2-D patch of output tiles and share their operand panels in that XCD's L2.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -24,80 +30,79 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-constexpr int BK = 64;        // k extent of one LDS tile
-constexpr int kThreads = 256;
-constexpr int ROW_LD = BK + 8;  // bf16 per LDS row of a k-contiguous tile (144 B: conflict-free b128 reads)
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef short shortx8 __attribute__((ext_vector_type(8)));
 
 // ---- staging of one operand tile -------------------------------------------------------------
-// k-contiguous operand: tile [R rows][64 k]; memory element (r, k) at base[r*ld + k].
-template <int R>
+// k-contiguous operand: tile [R rows][BKT k]; memory element (r, k) at base[r*ld + k].
+template <int R, int BKT, int NT>
 struct RowTile {
-  static constexpr int kChunks = R * (BK / 8) / kThreads;  // 16-byte chunks per thread
-  static constexpr int kLdsElems = R * ROW_LD;
-  uint4 regs[kChunks];
+  static constexpr int LD = BKT + 8;             // +16 B per row: conflict-free 128-bit reads
+  static constexpr int kPerRow = BKT / 8;        // 16-byte chunks per row
+  static constexpr int kChunks = R * kPerRow / NT;
+  static constexpr int kRowStep = NT / kPerRow;
+  static constexpr int kLdsElems = R * LD;
+  static_assert(R * kPerRow % NT == 0, "tile does not divide among the threads");
 
-  __device__ __forceinline__ void load(const uint16_t* __restrict__ base, int ld, int r0, int rows, int k0, int K) {
-    const int c = threadIdx.x & 7;
+  static __device__ __forceinline__ void load(uint4 (&regs)[kChunks], const uint16_t* __restrict__ base, int ld, int r0,
+                                              int rows, int k0, int K) {
+    const int c = threadIdx.x % kPerRow;
+    const int k = k0 + c * 8;
 #pragma unroll
     for (int i = 0; i < kChunks; ++i) {
-      const int r = (threadIdx.x >> 3) + 32 * i;
-      const int gr = min(r0 + r, rows - 1);           // clamp: rows past the edge are never stored
-      const int k = k0 + c * 8;
+      const int r = threadIdx.x / kPerRow + kRowStep * i;
+      const int gr = min(r0 + r, rows - 1);  // clamp: rows past the edge are computed but never stored
       regs[i] = k < K ? *reinterpret_cast<const uint4*>(base + (size_t)gr * ld + k) : make_uint4(0, 0, 0, 0);
     }
   }
-  __device__ __forceinline__ void store(uint16_t* lds) const {
-    const int c = threadIdx.x & 7;
+  static __device__ __forceinline__ void store(const uint4 (&regs)[kChunks], uint16_t* lds) {
+    const int c = threadIdx.x % kPerRow;
 #pragma unroll
     for (int i = 0; i < kChunks; ++i) {
-      const int r = (threadIdx.x >> 3) + 32 * i;
-      *reinterpret_cast<uint4*>(lds + r * ROW_LD + c * 8) = regs[i];
+      const int r = threadIdx.x / kPerRow + kRowStep * i;
+      *reinterpret_cast<uint4*>(lds + r * LD + c * 8) = regs[i];
     }
   }
-  // operand rows rbase..rbase+31: lane reads the 8 consecutive k = kk*16 + 8*(lane/32).. of row rbase + lane%32
+  // operand rows rbase..rbase+31: the lane reads k = kk*16 + 8*(lane/32) .. +7 of row rbase + lane%32
   static __device__ __forceinline__ bf16x8 frag(const uint16_t* lds, int rbase, int kk, int lane) {
-    const uint4 v = *reinterpret_cast<const uint4*>(lds + (rbase + (lane & 31)) * ROW_LD + kk * 16 + (lane >> 5) * 8);
+    const uint4 v = *reinterpret_cast<const uint4*>(lds + (rbase + (lane & 31)) * LD + kk * 16 + (lane >> 5) * 8);
     return __builtin_bit_cast(bf16x8, v);
   }
 };
 
-// k-strided operand: tile [64 k][R rows]; memory element (r, k) at base[k*ld + r].
+// k-strided operand: tile [BKT k][R rows]; memory element (r, k) at base[k*ld + r].
 // Fragments come from the LDS transpose read (ds_read_b64_tr_b16): within each group of 16
 // lanes, lane s supplies the address of 4 consecutive bf16 and receives element s%4 of the
 // four lanes 4*j + s/4 (j = 0..3).  With lane s pointing at row k0 + s/4, columns
 // c0 + 4*(s%4) .. +3, lane i of the group ends up with rows k0..k0+3 of column c0 + i: four
 // consecutive k of its own row/column of the MFMA operand.  Two such reads give the 8 k values.
-typedef short shortx4 __attribute__((ext_vector_type(4)));
-typedef short shortx8 __attribute__((ext_vector_type(8)));
-
-template <int R>
+template <int R, int BKT, int NT>
 struct ColTile {
   static constexpr int LD = R + 32;  // row stride = 64 B (mod 256 B): the 4 rows of a transpose read hit distinct banks
-  static constexpr int kChunks = BK * (R / 8) / kThreads;
-  static constexpr int kLdsElems = BK * LD;
-  static constexpr int kChunksPerK = R / 8;
-  uint4 regs[kChunks];
+  static constexpr int kPerK = R / 8;
+  static constexpr int kChunks = BKT * kPerK / NT;
+  static constexpr int kLdsElems = BKT * LD;
+  static_assert(BKT * kPerK % NT == 0, "tile does not divide among the threads");
 
-  __device__ __forceinline__ void load(const uint16_t* __restrict__ base, int ld, int r0, int rows, int k0, int K) {
+  static __device__ __forceinline__ void load(uint4 (&regs)[kChunks], const uint16_t* __restrict__ base, int ld, int r0,
+                                              int rows, int k0, int K) {
 #pragma unroll
     for (int i = 0; i < kChunks; ++i) {
-      const int id = threadIdx.x + kThreads * i;
-      const int c = id % kChunksPerK, k = id / kChunksPerK;
+      const int id = threadIdx.x + NT * i;
+      const int c = id % kPerK, k = id / kPerK;
       const int r = r0 + c * 8;
       const bool ok = (k0 + k < K) && (r + 8 <= rows);
       regs[i] = ok ? *reinterpret_cast<const uint4*>(base + (size_t)(k0 + k) * ld + r) : make_uint4(0, 0, 0, 0);
     }
   }
-  __device__ __forceinline__ void store(uint16_t* lds) const {
+  static __device__ __forceinline__ void store(const uint4 (&regs)[kChunks], uint16_t* lds) {
 #pragma unroll
     for (int i = 0; i < kChunks; ++i) {
-      const int id = threadIdx.x + kThreads * i;
-      const int c = id % kChunksPerK, k = id / kChunksPerK;
+      const int id = threadIdx.x + NT * i;
+      const int c = id % kPerK, k = id / kPerK;
       *reinterpret_cast<uint4*>(lds + k * LD + c * 8) = regs[i];
     }
   }
-  // operand rows rbase..rbase+31, k = kk*16 + 8*(lane/32) .. +7 for row rbase + lane%32
   static __device__ __forceinline__ bf16x8 frag(const uint16_t* lds, int rbase, int kk, int lane) {
     const int g = lane >> 4, s = lane & 15;
     const int k = kk * 16 + 8 * (g >> 1) + (s >> 2);
@@ -111,49 +116,150 @@ struct ColTile {
   }
 };
 
-template <int R, bool COL>
-struct TileSel { using type = RowTile<R>; };
-template <int R>
-struct TileSel<R, true> { using type = ColTile<R>; };
+template <int R, int BKT, int NT, bool COL>
+struct TileSel { using type = RowTile<R, BKT, NT>; };
+template <int R, int BKT, int NT>
+struct TileSel<R, BKT, NT, true> { using type = ColTile<R, BKT, NT>; };
 
-// ---- epilogues: called once per accumulator element with its (m, n) ---------------------------
+// ---- epilogues ---------------------------------------------------------------------------------
+// bf16 outputs: the MFMA operands are swapped (the kernel accumulates the transposed tile), so
+// that each lane ends up with 4 consecutive COLUMNS n..n+3 of one output row m and can load and
+// store 8 contiguous bytes without a trip through LDS.  fp32 output (wgrad) keeps the plain
+// orientation, where the 32 lanes of a half wave already cover 128 contiguous bytes.
 struct EpiFprop {
-  const float* bias; uint16_t* z_out; uint16_t* a_out; int act; int ldc;
-  __device__ __forceinline__ void operator()(int m, int n, float v) const {
-    v += bias[n];
+  const float* bias; uint16_t* d_out; uint16_t* a_out; int act; int ldc;  // d_out: act'(z) for the backward, or null
+  static constexpr bool kSwap = true;
+  __device__ __forceinline__ void quad(int m, int n, int count, float v0, float v1, float v2, float v3) const {
     const size_t i = (size_t)m * ldc + n;
-    if (z_out) z_out[i] = float_to_bf16(v);
-    a_out[i] = float_to_bf16(act_forward(v, act));
+    if (count == 4 && (ldc & 3) == 0) {
+      const float4 b = *reinterpret_cast<const float4*>(bias + n);
+      const ActPair p0 = act_pair_fast(v0 + b.x, act), p1 = act_pair_fast(v1 + b.y, act);
+      const ActPair p2 = act_pair_fast(v2 + b.z, act), p3 = act_pair_fast(v3 + b.w, act);
+      if (d_out) *reinterpret_cast<uint2*>(d_out + i) = make_uint2(pack_bf16x2(p0.d, p1.d), pack_bf16x2(p2.d, p3.d));
+      *reinterpret_cast<uint2*>(a_out + i) = make_uint2(pack_bf16x2(p0.a, p1.a), pack_bf16x2(p2.a, p3.a));
+    } else {
+      const float v[4] = {v0, v1, v2, v3};
+      for (int j = 0; j < count; ++j) {
+        const ActPair p = act_pair_fast(v[j] + bias[n + j], act);
+        if (d_out) d_out[i + j] = float_to_bf16(p.d);
+        a_out[i + j] = float_to_bf16(p.a);
+      }
+    }
   }
 };
 struct EpiDgrad {
-  const uint16_t* z_prev; uint16_t* out; int act; int ldc;
-  __device__ __forceinline__ void operator()(int m, int n, float v) const {
+  const uint16_t* d_prev; uint16_t* out; int ldc;  // d_prev: saved act'(z) of the previous layer, or null
+  static constexpr bool kSwap = true;
+  __device__ __forceinline__ void quad(int m, int n, int count, float v0, float v1, float v2, float v3) const {
     const size_t i = (size_t)m * ldc + n;
-    if (z_prev) v *= act_derivative(bf16_to_float(z_prev[i]), act);
-    out[i] = float_to_bf16(v);
+    if (count == 4 && (ldc & 3) == 0) {
+      if (d_prev) {
+        const uint2 d = *reinterpret_cast<const uint2*>(d_prev + i);
+        v0 *= __uint_as_float(d.x << 16);
+        v1 *= __uint_as_float(d.x & 0xffff0000u);
+        v2 *= __uint_as_float(d.y << 16);
+        v3 *= __uint_as_float(d.y & 0xffff0000u);
+      }
+      *reinterpret_cast<uint2*>(out + i) = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
+    } else {
+      const float v[4] = {v0, v1, v2, v3};
+      for (int j = 0; j < count; ++j) {
+        float d = v[j];
+        if (d_prev) d *= bf16_to_float(d_prev[i + j]);
+        out[i + j] = float_to_bf16(d);
+      }
+    }
   }
 };
 struct EpiWgrad {
   float* out; int ldc;
-  __device__ __forceinline__ void operator()(int m, int n, float v) const { out[(size_t)m * ldc + n] = v; }
+  static constexpr bool kSwap = false;
+  __device__ __forceinline__ void elem(int m, int n, float v) const { out[(size_t)m * ldc + n] = v; }
 };
 
-template <int BM, int BN, bool A_COL, bool B_COL, class Epi>
-__global__ __launch_bounds__(kThreads) void gemm_bf16_mfma_kernel(int M, int N, int K, const uint16_t* __restrict__ A,
-                                                                  int lda, const uint16_t* __restrict__ B, int ldb,
-                                                                  Epi epi) {
-  using ATile = typename TileSel<BM, A_COL>::type;
-  using BTile = typename TileSel<BN, B_COL>::type;
-  constexpr int WM = BM / 2, WN = BN / 2;  // wave tile
+// Accumulator element r of a lane sits at tile row 8*(r/4) + 4*(lane/32) + r%4, tile column
+// lane%32 of what the MFMA computed; with swapped operands that is the transposed output tile.
+template <int TM, int TN, class Epi>
+__device__ __forceinline__ void store_tiles(const floatx16 (&acc)[TM][TN], const Epi& epi, int mbase, int nbase, int M,
+                                            int N, int lane) {
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      if constexpr (Epi::kSwap) {
+        const int m = mbase + i * 32 + (lane & 31);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n = nbase + j * 32 + 8 * g + 4 * (lane >> 5);
+          if (m < M && n < N)
+            epi.quad(m, n, min(4, N - n), acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2],
+                     acc[i][j][4 * g + 3]);
+        }
+      } else {
+        const int n = nbase + j * 32 + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = mbase + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          if (m < M && n < N) epi.elem(m, n, acc[i][j][r]);
+        }
+      }
+    }
+}
+
+// acc += A_frag . B_frag, or its transpose when the epilogue wants columns along the registers
+template <bool SWAP>
+__device__ __forceinline__ floatx16 mma(bf16x8 a, bf16x8 b, floatx16 c) {
+  return SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, c, 0, 0, 0)
+              : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// ---- workgroup id -> output tile, XCD aware ---------------------------------------------------
+// Hardware hands workgroup b to XCD b % 8.  The 8 XCDs are laid out as an xm x xn grid over the
+// tile space; XCD (xi, xj) owns the (tiles_m/xm) x (tiles_n/xn) patch at that position.
+struct TileMap {
+  int tiles_m, tiles_n, xm, xn;  // xm*xn == 8, or xm == 0 for the plain row-major mapping
+  long long* clk;                // tuning probe: workgroup 0 stores {shader cycles, 100 MHz ticks} of its main loop
+  __device__ __forceinline__ void get(int b, int& tm, int& tn) const {
+    if (xm == 0) { tm = b / tiles_n; tn = b % tiles_n; return; }
+    const int xcd = b & 7, i = b >> 3;
+    const int cm = tiles_m / xm, cn = tiles_n / xn;
+    tm = (xcd / xn) * cm + i / cn;
+    tn = (xcd % xn) * cn + i % cn;
+  }
+};
+
+inline TileMap make_tile_map(int tiles_m, int tiles_n) {
+  static const int cand[4][2] = {{2, 4}, {4, 2}, {1, 8}, {8, 1}};
+  TileMap best{tiles_m, tiles_n, 0, 0, nullptr};
+  long best_cost = -1;
+  for (auto& c : cand) {
+    if (tiles_m % c[0] || tiles_n % c[1]) continue;
+    const long cost = tiles_m / c[0] + tiles_n / c[1];  // operand panels one XCD touches
+    if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = TileMap{tiles_m, tiles_n, c[0], c[1], nullptr}; }
+  }
+  return best;
+}
+
+// ---- the kernel --------------------------------------------------------------------------------
+template <int BM, int BN, int WGM, int WGN, int BKT, bool A_COL, bool B_COL, class Epi>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_mfma_kernel(int M, int N, int K,
+                                                                         const uint16_t* __restrict__ A, int lda,
+                                                                         const uint16_t* __restrict__ B, int ldb,
+                                                                         Epi epi, TileMap map) {
+  constexpr int NT = 64 * WGM * WGN;
+  using ATile = typename TileSel<BM, BKT, NT, A_COL>::type;
+  using BTile = typename TileSel<BN, BKT, NT, B_COL>::type;
+  constexpr int WM = BM / WGM, WN = BN / WGN;  // wave tile
   constexpr int TM = WM / 32, TN = WN / 32;
   extern __shared__ __attribute__((aligned(16))) uint16_t lds_raw[];
   auto lds_a = [&](int buf) { return lds_raw + buf * ATile::kLdsElems; };
   auto lds_b = [&](int buf) { return lds_raw + 2 * ATile::kLdsElems + buf * BTile::kLdsElems; };
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
+  int tile_m, tile_n;
+  map.get(blockIdx.x, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -163,71 +269,372 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_mfma_kernel(int M, int N, 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  ATile ta;
-  BTile tb;
-  const int KT = (K + BK - 1) / BK;
-  ta.load(A, lda, m0, M, 0, K);
-  tb.load(B, ldb, n0, N, 0, K);
-  ta.store(lds_a(0));
-  tb.store(lds_b(0));
-  __syncthreads();
-  for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < KT) {
-      ta.load(A, lda, m0, M, (kt + 1) * BK, K);
-      tb.load(B, ldb, n0, N, (kt + 1) * BK, K);
-    }
+  auto compute = [&](int buf) {
+    const uint16_t* la = lds_a(buf);
+    const uint16_t* lb = lds_b(buf);
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
+    for (int kk = 0; kk < BKT / 16; ++kk) {
       bf16x8 af[TM], bfr[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = ATile::frag(lds_a(cur), wm + i * 32, kk, lane);
+      for (int i = 0; i < TM; ++i) af[i] = ATile::frag(la, wm + i * 32, kk, lane);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[j] = BTile::frag(lds_b(cur), wn + j * 32, kk, lane);
+      for (int j = 0; j < TN; ++j) bfr[j] = BTile::frag(lb, wn + j * 32, kk, lane);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = mma<Epi::kSwap>(af[i], bfr[j], acc[i][j]);
     }
+  };
+
+  uint4 ra[ATile::kChunks], rb[BTile::kChunks];
+  const int KT = (K + BKT - 1) / BKT;
+  ATile::load(ra, A, lda, m0, M, 0, K);
+  BTile::load(rb, B, ldb, n0, N, 0, K);
+  ATile::store(ra, lds_a(0));
+  BTile::store(rb, lds_b(0));
+  __syncthreads();
+  for (int kt = 0; kt < KT; ++kt) {
+    const int cur = kt & 1;
     if (kt + 1 < KT) {
-      ta.store(lds_a(cur ^ 1));
-      tb.store(lds_b(cur ^ 1));
+      ATile::load(ra, A, lda, m0, M, (kt + 1) * BKT, K);
+      BTile::load(rb, B, ldb, n0, N, (kt + 1) * BKT, K);
+    }
+    compute(cur);
+    if (kt + 1 < KT) {
+      ATile::store(ra, lds_a(cur ^ 1));
+      BTile::store(rb, lds_b(cur ^ 1));
     }
     __syncthreads();
   }
-  // accumulator element r of a lane: row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = n0 + wn + j * 32 + (lane & 31);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (m < M && n < N) epi(m, n, acc[i][j][r]);
-      }
-    }
+
+  store_tiles<TM, TN>(acc, epi, m0 + wm, n0 + wn, M, N, lane);
 }
 
-template <int BM, int BN, bool A_COL, bool B_COL, class Epi>
+template <int BM, int BN, int WGM, int WGN, int BKT, bool A_COL, bool B_COL, class Epi>
 hipError_t launch(hipStream_t s, int M, int N, int K, const uint16_t* A, int lda, const uint16_t* B, int ldb,
                   const Epi& epi) {
-  using ATile = typename TileSel<BM, A_COL>::type;
-  using BTile = typename TileSel<BN, B_COL>::type;
+  constexpr int NT = 64 * WGM * WGN;
+  using ATile = typename TileSel<BM, BKT, NT, A_COL>::type;
+  using BTile = typename TileSel<BN, BKT, NT, B_COL>::type;
   constexpr size_t lds_bytes = 2 * (ATile::kLdsElems + BTile::kLdsElems) * sizeof(uint16_t);
-  auto kernel = gemm_bf16_mfma_kernel<BM, BN, A_COL, B_COL, Epi>;
+  static_assert(lds_bytes <= 160 * 1024, "tile does not fit the LDS of a CU");
+  auto kernel = gemm_bf16_mfma_kernel<BM, BN, WGM, WGN, BKT, A_COL, B_COL, Epi>;
   if (lds_bytes > 64 * 1024) {
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (attr != hipSuccess) return attr;
   }
-  dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM);
-  hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds_bytes, s, M, N, K, A, lda, B, ldb, epi);
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  const TileMap map = make_tile_map(tiles_m, tiles_n);
+  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n), dim3(NT), lds_bytes, s, M, N, K, A, lda, B, ldb, epi, map);
   return hipGetLastError();
 }
 
+long long* g_clk_probe = nullptr;  // device pointer set through the tuning hook, normally null
+
+// ================================================================================================
+// Direct-to-LDS variant
+// ================================================================================================
+// global_load_lds_dwordx4 copies 16 bytes per lane from global memory to LDS address
+// M0 + 16*lane: one wave instruction fills 1 KB of contiguous LDS, so tiles lie unpadded and
+// bank conflicts are removed by storing chunk c of a row in slot c ^ f(row); the XOR is applied
+// when each lane picks the global chunk it fetches for its (fixed) LDS slot, and again when
+// fragments are read.  The copies do not touch the register file and complete out of band;
+// s_waitcnt vmcnt(n) keeps the NS-1 newest tiles in flight while the oldest is consumed.
+
+constexpr int DBK = 64;  // k extent of one stage
+
+__device__ __forceinline__ void dma16(uint32_t lds_byte_addr, const void* sbase, uint32_t voff_bytes) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_byte_addr), "v"(voff_bytes), "s"(sbase)
+               : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Barrier without the global-memory fence of __syncthreads(): only LDS traffic of this wave is
+// drained, outstanding global->LDS copies of later stages stay in flight.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
+
+// k-contiguous operand, stage = [R rows][64 k] = 128 B per row, 8 chunks; slot = chunk ^ ((row/2)%8).
+template <int R, int NW>
+struct RowDma {
+  static constexpr int kInstr = R / 8;          // wave instructions per stage (8 rows each)
+  static constexpr int kPerWave = kInstr / NW;
+  static constexpr int kBytes = R * DBK * 2;
+  static_assert(kInstr % NW == 0, "rows do not divide among the waves");
+  uint32_t voff[kPerWave];
+
+  __device__ __forceinline__ void init(int ld, int r0, int rows, int wave, int lane) {
+#pragma unroll
+    for (int t = 0; t < kPerWave; ++t) {
+      const int r = 8 * (wave + NW * t) + (lane >> 3);
+      const int c = (lane & 7) ^ ((r >> 1) & 7);
+      voff[t] = (uint32_t)(((size_t)min(r0 + r, rows - 1) * ld + c * 8) * 2);
+    }
+  }
+  // base: operand pointer advanced to the stage's first k
+  __device__ __forceinline__ void issue_one(int t, uint32_t lds_stage, const uint16_t* base, int wave) const {
+    dma16(lds_stage + (wave + NW * t) * 1024, base, voff[t]);
+  }
+  static __device__ __forceinline__ size_t tile_step(int) { return DBK; }  // elements between k tiles
+  static __device__ __forceinline__ bf16x8 frag(const uint16_t* lds, int rbase, int kk, int lane) {
+    const int r = rbase + (lane & 31);
+    const int c = (kk * 2 + (lane >> 5)) ^ ((r >> 1) & 7);
+    const uint4 v = *reinterpret_cast<const uint4*>(lds + r * DBK + c * 8);
+    return __builtin_bit_cast(bf16x8, v);
+  }
+};
+
+// k-strided operand, stage = [64 k][R rows]; R/8 chunks per k row; slot = chunk ^ f(k) so that the
+// four k rows of one transpose read fall into four different 64-byte bank groups.
+template <int R, int NW>
+struct ColDma {
+  static constexpr int kPerK = R / 8;
+  static constexpr int kInstr = DBK * kPerK / 64;
+  static constexpr int kPerWave = kInstr / NW;
+  static constexpr int kBytes = R * DBK * 2;
+  static_assert(kInstr % NW == 0, "rows do not divide among the waves");
+  static_assert(R >= 64, "stage rows shorter than 128 bytes are not laid out");
+  uint32_t voff[kPerWave];
+
+  static __device__ __forceinline__ int swz(int k) { return R >= 128 ? 4 * (k & 3) : 4 * ((k >> 1) & 1); }
+
+  __device__ __forceinline__ void init(int ld, int r0, int rows, int wave, int lane) {
+#pragma unroll
+    for (int t = 0; t < kPerWave; ++t) {
+      const int flat = 64 * (wave + NW * t) + lane;
+      const int k = flat / kPerK;
+      const int c = (flat % kPerK) ^ swz(k);
+      // chunks past the edge re-read the last valid chunk: those columns are never stored
+      voff[t] = (uint32_t)(((size_t)k * ld + min(r0 + c * 8, rows - 8)) * 2);
+    }
+  }
+  __device__ __forceinline__ void issue_one(int t, uint32_t lds_stage, const uint16_t* base, int wave) const {
+    dma16(lds_stage + (wave + NW * t) * 1024, base, voff[t]);
+  }
+  static __device__ __forceinline__ size_t tile_step(int ld) { return (size_t)DBK * ld; }
+  static __device__ __forceinline__ bf16x8 frag(const uint16_t* lds, int rbase, int kk, int lane) {
+    const int g = lane >> 4, s = lane & 15;
+    const int k = kk * 16 + 8 * (g >> 1) + (s >> 2);
+    const int col = rbase + 16 * (g & 1) + 4 * (s & 3);
+    const int slot = (col >> 3) ^ swz(k);
+    typedef __attribute__((address_space(3))) shortx4* lds_ptr;
+    const uint16_t* p = lds + k * R + slot * 8 + (col & 7);
+    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * R));  // k+4: same swizzle
+    const shortx8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+  }
+};
+
+template <int R, int NW, bool COL>
+struct DmaSel { using type = RowDma<R, NW>; };
+template <int R, int NW>
+struct DmaSel<R, NW, true> { using type = ColDma<R, NW>; };
+
+// MODE: 0 = the product; 1 = copies only, 2 = matrix cores only (bandwidth probes for tuning;
+// their results are meaningless and they are reachable only through the tuning hook).
+template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, class Epi, int MODE = 0>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, int N, int K,
+                                                                        const uint16_t* __restrict__ A, int lda,
+                                                                        const uint16_t* __restrict__ B, int ldb,
+                                                                        Epi epi, TileMap map) {
+  constexpr int NW = WGM * WGN;
+  using AT = typename DmaSel<BM, NW, A_COL>::type;
+  using BT = typename DmaSel<BN, NW, B_COL>::type;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int kStageBytes = AT::kBytes + BT::kBytes;
+  constexpr int kLoads = AT::kPerWave + BT::kPerWave;  // copies one wave issues per stage
+  static_assert((NS - 2) * kLoads < 64, "too many copies in flight for vmcnt");
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds_raw[];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
+  int tile_m, tile_n;
+  map.get(blockIdx.x, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const uint32_t lds_base = lds_addr_of(lds_raw);
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  AT ta;
+  BT tb;
+  ta.init(lda, m0, M, wave, lane);
+  tb.init(ldb, n0, N, wave, lane);
+  const int KT = K / DBK;
+  const size_t step_a = AT::tile_step(lda), step_b = BT::tile_step(ldb);
+  constexpr int NM = (DBK / 16) * TM * TN;  // MFMAs of one wave per k tile
+
+  // copy number t (0 .. kLoads-1) of k tile `tile` into stage `st`.  Tiles past the end re-read
+  // the last tile into a stage nobody reads again, which keeps the number of copies per
+  // iteration -- and with it the vmcnt arithmetic -- the same from the first tile to the last.
+  auto issue_copy = [&](int t, int tile, int st) {
+    const int tc = min(tile, KT - 1);
+    const uint32_t dst = lds_base + st * kStageBytes;
+    if (t < AT::kPerWave) ta.issue_one(t, dst, A + tc * step_a, wave);
+    else tb.issue_one(t - AT::kPerWave, dst + AT::kBytes, B + tc * step_b, wave);
+  };
+
+  // prologue: stages 0 .. NS-2
+#pragma unroll
+  for (int st = 0; st < NS - 1; ++st)
+#pragma unroll
+    for (int t = 0; t < kLoads; ++t) issue_copy(t, st, st);
+
+  const long long clk0 = map.clk ? clock64() : 0, wall0 = map.clk ? wall_clock64() : 0;
+  int rd = 0;        // stage holding tile kt
+  int wr = NS - 1;   // stage that receives tile kt + NS - 1
+  for (int kt = 0; kt < KT; ++kt) {
+    // tile kt has landed once at most the NS-2 newer tiles are still in flight
+    wait_vmcnt<(NS - 2) * kLoads>();
+    if (MODE != 4) lds_barrier();  // tile kt visible to all waves; everybody is done reading stage `wr`
+    const uint16_t* la = lds_raw + rd * (kStageBytes / 2);
+    const uint16_t* lb = la + AT::kBytes / 2;
+    if (MODE == 1) {
+#pragma unroll
+      for (int t = 0; t < kLoads; ++t) issue_copy(t, kt + NS - 1, wr);
+    } else if (MODE >= 3) {
+      bf16x8 a0 = AT::frag(lds_raw, wm, 0, lane), b0 = BT::frag(lds_raw, wn, 0, lane);
+#pragma unroll
+      for (int kk = 0; kk < DBK / 16; ++kk)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[i][j], 0, 0, 0);
+    } else {
+      // Fixed schedule per k step: the LDS reads of step kk+1 go out first, then the MFMAs of
+      // step kk with the global->LDS copies of tile kt+NS-1 spread evenly between them, so that
+      // the wave never sits in the memory-instruction queue while its matrix core idles.
+      bf16x8 af[2][TM], bfr[2][TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[0][i] = AT::frag(la, wm + i * 32, 0, lane);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bfr[0][j] = BT::frag(lb, wn + j * 32, 0, lane);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kk = 0; kk < DBK / 16; ++kk) {
+        const int c = kk & 1, nx = c ^ 1;
+        if (kk + 1 < DBK / 16) {
+#pragma unroll
+          for (int i = 0; i < TM; ++i) af[nx][i] = AT::frag(la, wm + i * 32, kk + 1, lane);
+#pragma unroll
+          for (int j = 0; j < TN; ++j) bfr[nx][j] = BT::frag(lb, wn + j * 32, kk + 1, lane);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            acc[i][j] = mma<Epi::kSwap>(af[c][i], bfr[c][j], acc[i][j]);
+            if (MODE == 0) {
+              const int q = (kk * TM + i) * TN + j;  // compile-time after unrolling
+#pragma unroll
+              for (int t = 0; t < kLoads; ++t)
+                if ((t * NM) / kLoads == q) {
+                  __builtin_amdgcn_sched_barrier(0);
+                  issue_copy(t, kt + NS - 1, wr);
+                  __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+          }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    rd = rd + 1 == NS ? 0 : rd + 1;
+    wr = wr + 1 == NS ? 0 : wr + 1;
+  }
+  wait_vmcnt<0>();  // the trailing dummy copies must have landed before LDS is reused
+  lds_barrier();    // all waves are done with the last stage
+  if (map.clk && blockIdx.x == 0 && threadIdx.x == 0) {
+    map.clk[0] = clock64() - clk0;
+    map.clk[1] = wall_clock64() - wall0;
+  }
+
+  store_tiles<TM, TN>(acc, epi, m0 + wm, n0 + wn, M, N, lane);
+}
+
+// Shapes the direct-to-LDS kernel takes: whole 64-wide k tiles, 32-bit byte offsets inside each
+// operand, and at least one 8-wide chunk along the rows of an operand staged [k][row].
+inline bool dma_ok(int M, int N, int K, int lda, int ldb, bool a_col, bool b_col) {
+  if (K < DBK || K % DBK) return false;
+  const size_t a_bytes = (size_t)(a_col ? K : M) * lda * 2, b_bytes = (size_t)(b_col ? K : N) * ldb * 2;
+  if (a_bytes >= (1ull << 31) || b_bytes >= (1ull << 31)) return false;
+  if ((a_col && M < 8) || (b_col && N < 8)) return false;
+  return true;
+}
+
+template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, int MODE = 0, class Epi>
+hipError_t launch_dma(hipStream_t s, int M, int N, int K, const uint16_t* A, int lda, const uint16_t* B, int ldb,
+                      const Epi& epi) {
+  constexpr int NW = WGM * WGN;
+  using AT = typename DmaSel<BM, NW, A_COL>::type;
+  using BT = typename DmaSel<BN, NW, B_COL>::type;
+  constexpr size_t lds_bytes = (size_t)NS * (AT::kBytes + BT::kBytes);
+  static_assert(lds_bytes <= 160 * 1024, "stages do not fit the LDS of a CU");
+  auto kernel = gemm_bf16_dma_kernel<BM, BN, WGM, WGN, NS, A_COL, B_COL, Epi, MODE>;
+  if (lds_bytes > 64 * 1024) {
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (attr != hipSuccess) return attr;
+  }
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  TileMap map = make_tile_map(tiles_m, tiles_n);
+  map.clk = g_clk_probe;
+  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n), dim3(64 * NW), lds_bytes, s, M, N, K, A, lda, B, ldb, epi, map);
+  return hipGetLastError();
+}
+
+int g_cfg[3] = {-1, -1, -1};  // tuning override per product (fprop, dgrad, wgrad); -1 = heuristic
+
+// Tile choice.  The direct-to-LDS kernel is taken whenever the shape allows it: the largest of
+// its tiles that still gives every CU a workgroup (large tiles cut the L2->LDS traffic, which
+// together with the LDS reads is what bounds these kernels).  Ragged shapes go to the
+// register-staged kernel.
+int pick(int rows, int cols, int contraction, int lda, int ldb, bool a_col, bool b_col, int override_cfg) {
+  if (override_cfg >= 0) return override_cfg;
+  auto blocks = [&](int bm, int bn) { return (long)((rows + bm - 1) / bm) * ((cols + bn - 1) / bn); };
+  if (dma_ok(rows, cols, contraction, lda, ldb, a_col, b_col)) {
+    if (blocks(256, 128) >= 256) return 13;
+    if (blocks(128, 128) >= 256) return 12;
+    if (blocks(128, 64) >= 256) return 11;
+    return 10;
+  }
+  if (blocks(128, 128) >= 256) return 2;
+  if (blocks(128, 64) >= 128) return 1;
+  return 0;
+}
+
 }  // namespace
+
+void mfma_set_clock_probe(long long* dev_ptr) { g_clk_probe = dev_ptr; }
+
+void mfma_set_config(int product, int cfg) {
+  if (product >= 0 && product < 3) g_cfg[product] = cfg;
+}
 
 // Contraction extents must be a multiple of 8 (16-byte chunks along k); operands that are staged
 // [k][row] also need their row extent to be a multiple of 8.
@@ -235,26 +642,51 @@ bool mfma_fprop_supported(int M, int N, int K) { return M >= 1 && N >= 1 && K % 
 bool mfma_dgrad_supported(int M, int N, int K) { return M >= 1 && N % 8 == 0 && K % 8 == 0; }
 bool mfma_wgrad_supported(int M, int N, int K) { return M >= 1 && N % 8 == 0 && K % 8 == 0; }
 
+#define TP_GEMM_DISPATCH(cfg, ACOL, BCOL, ...)                                  \
+  switch (cfg) {                                                                \
+    case 10: return launch_dma<64, 64, 2, 2, 4, ACOL, BCOL>(__VA_ARGS__);       \
+    case 11: return launch_dma<128, 64, 2, 2, 4, ACOL, BCOL>(__VA_ARGS__);      \
+    case 12: return launch_dma<128, 128, 2, 2, 3, ACOL, BCOL>(__VA_ARGS__);     \
+    case 13: return launch_dma<256, 128, 2, 2, 3, ACOL, BCOL>(__VA_ARGS__);     \
+    case 14: return launch_dma<128, 256, 2, 2, 3, ACOL, BCOL>(__VA_ARGS__);     \
+    case 15: return launch_dma<256, 256, 2, 2, 2, ACOL, BCOL>(__VA_ARGS__);     \
+    case 16: return launch_dma<128, 128, 2, 2, 4, ACOL, BCOL>(__VA_ARGS__);     \
+    case 17: return launch_dma<64, 64, 2, 2, 8, ACOL, BCOL>(__VA_ARGS__);       \
+    case 23: return launch_dma<256, 128, 2, 2, 3, ACOL, BCOL, 1>(__VA_ARGS__);  \
+    case 33: return launch_dma<256, 128, 2, 2, 3, ACOL, BCOL, 2>(__VA_ARGS__);  \
+    case 25: return launch_dma<256, 256, 2, 2, 2, ACOL, BCOL, 1>(__VA_ARGS__);  \
+    case 35: return launch_dma<256, 256, 2, 2, 2, ACOL, BCOL, 2>(__VA_ARGS__);  \
+    case 22: return launch_dma<128, 128, 2, 2, 3, ACOL, BCOL, 1>(__VA_ARGS__);  \
+    case 43: return launch_dma<256, 128, 2, 2, 3, ACOL, BCOL, 3>(__VA_ARGS__);  \
+    case 53: return launch_dma<256, 128, 2, 2, 3, ACOL, BCOL, 4>(__VA_ARGS__);  \
+    case 45: return launch_dma<256, 256, 2, 2, 2, ACOL, BCOL, 3>(__VA_ARGS__);  \
+    case 55: return launch_dma<256, 256, 2, 2, 2, ACOL, BCOL, 4>(__VA_ARGS__);  \
+    case 32: return launch_dma<128, 128, 2, 2, 3, ACOL, BCOL, 2>(__VA_ARGS__);  \
+    case 5: return launch<128, 256, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);         \
+    case 4: return launch<64, 64, 2, 2, 128, ACOL, BCOL>(__VA_ARGS__);          \
+    case 3: return launch<256, 128, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);         \
+    case 2: return launch<128, 128, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);         \
+    case 1: return launch<128, 64, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);          \
+    default: return launch<64, 64, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);          \
+  }
+
 hipError_t mfma_fprop(hipStream_t s, int M, int N, int K, const uint16_t* x, const uint16_t* W, const float* bias,
-                      int act, uint16_t* z_out, uint16_t* a_out) {
-  EpiFprop e{bias, z_out, a_out, act, N};
-  if (M <= 64) return launch<64, 64, false, false>(s, M, N, K, x, K, W, K, e);
-  return launch<128, 128, false, false>(s, M, N, K, x, K, W, K, e);
+                      int act, uint16_t* d_out, uint16_t* a_out) {
+  EpiFprop e{bias, d_out, a_out, act, N};
+  TP_GEMM_DISPATCH(pick(M, N, K, K, K, false, false, g_cfg[0]), false, false, s, M, N, K, x, K, W, K, e)
 }
 
 hipError_t mfma_dgrad(hipStream_t s, int M, int N, int K, const uint16_t* dz, const uint16_t* Wb,
-                      const uint16_t* z_prev, int act_prev, uint16_t* out) {
+                      const uint16_t* d_prev, uint16_t* out) {
   // out[M x K] = dz[M x N] . Wb[N x K]: GEMM (M, K, contraction N)
-  EpiDgrad e{z_prev, out, act_prev, K};
-  if (M <= 64) return launch<64, 64, false, true>(s, M, K, N, dz, N, Wb, K, e);
-  return launch<128, 128, false, true>(s, M, K, N, dz, N, Wb, K, e);
+  EpiDgrad e{d_prev, out, K};
+  TP_GEMM_DISPATCH(pick(M, K, N, N, K, false, true, g_cfg[1]), false, true, s, M, K, N, dz, N, Wb, K, e)
 }
 
 hipError_t mfma_wgrad(hipStream_t s, int M, int N, int K, const uint16_t* dz, const uint16_t* x, float* gW) {
   // gW[N x K] = dz^T[N x M] . x[M x K]: GEMM (N, K, contraction M)
   EpiWgrad e{gW, K};
-  if (N <= 64 || K <= 64) return launch<64, 64, true, true>(s, N, K, M, dz, N, x, K, e);
-  return launch<128, 128, true, true>(s, N, K, M, dz, N, x, K, e);
+  TP_GEMM_DISPATCH(pick(N, K, M, N, K, true, true, g_cfg[2]), true, true, s, N, K, M, dz, N, x, K, e)
 }
 
 }  // namespace tp

@@ -34,7 +34,7 @@ inline uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 struct LayerPlan {
   tp_layer_desc d;
   uint64_t w_off, b_off;  // elements inside one weight version
-  uint64_t x_off, z_off;  // bytes inside one activation slot (z_off == UINT64_MAX: not saved)
+  uint64_t x_off, z_off;  // bytes inside one activation slot; z_off: saved act'(z) (UINT64_MAX: none)
 };
 
 struct Slot {
@@ -492,7 +492,7 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
         dz = dy_dev;
       } else {
         ProfScope ps(st, TP_K_ACT_BWD);
-        HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * last.d.out_features, dy_dev, aslot + last.z_off, last.d.act, st->dz_buf(pp)));
+        HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * last.d.out_features, dy_dev, aslot + last.z_off, st->dz_buf(pp)));
         dz = st->dz_buf(pp);
         pp ^= 1;
       }
@@ -513,13 +513,13 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
         const void* zprev = prev.z_off == UINT64_MAX ? nullptr : aslot + prev.z_off;
         ProfScope ps(st, TP_K_DGRAD);
         HIP_TRY(tp::launch_dgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, wb + lp.w_off * es,
-                                 zprev, prev.d.act, st->dz_buf(pp)));
+                                 zprev, st->dz_buf(pp)));
         dz = st->dz_buf(pp);
         pp ^= 1;
       } else if (d.needs_dx) {
         ProfScope ps(st, TP_K_DGRAD);
         HIP_TRY(tp::launch_dgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, wb + lp.w_off * es,
-                                 nullptr, TP_ACT_NONE, dx_dev));
+                                 nullptr, dx_dev));
       }
     }
   }
