@@ -13,9 +13,7 @@ bool mfma_wgrad_supported(int M, int N, int K);
 // Tuning hook: force tile configuration `cfg` for product 0 = fprop, 1 = dgrad, 2 = wgrad
 // (-1 = back to the heuristic).
 void mfma_set_config(int product, int cfg);
-// Tuning hook: device pointer to two int64 that receive {shader cycles, 100 MHz ticks} of the main
-// loop of workgroup 0 of the direct-to-LDS kernel (null = off).
-void mfma_set_clock_probe(long long* dev_ptr);
+
 
 // d_out receives act'(z) (what the backward pass multiplies with), a_out = act(z).
 hipError_t mfma_fprop(hipStream_t s, int M, int N, int K, const uint16_t* x, const uint16_t* W, const float* bias,

@@ -31,6 +31,9 @@ size_t colsum_scratch_floats(int M, int N);
 // dz = dy (.) d    all [rows x cols] in elt; d = saved act'(z).
 hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* d, void* dz);
 
+// Device-to-device copy of `bytes` bytes.
+hipError_t launch_copy(hipStream_t s, const void* src, void* dst, size_t bytes);
+
 // Softmax cross-entropy over `rows` rows of `classes` logits; dlogits = (softmax-onehot)/rows,
 // *loss = mean of the row losses.  row_loss: scratch of `rows` floats.
 hipError_t launch_softmax_ce(hipStream_t s, int elt, int rows, int classes, const void* logits,

@@ -18,7 +18,17 @@ namespace tp {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kUpdateBlocks = 2048;  // 8 blocks per CU on 256 CUs; grid-stride beyond that
+// Launch shape of the update kernel (overridable at build time for tuning sweeps).
+#ifndef TP_UPDATE_BLOCKS
+#define TP_UPDATE_BLOCKS 2048  // 8 blocks per CU on 256 CUs; grid-stride beyond that
+#endif
+#ifndef TP_UPDATE_UNROLL
+#define TP_UPDATE_UNROLL 2
+#endif
+#ifndef TP_UPDATE_NT
+#define TP_UPDATE_NT 1  // non-temporal accesses for the streams that are not re-read soon
+#endif
+constexpr int kUpdateBlocks = TP_UPDATE_BLOCKS;
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -58,41 +68,70 @@ struct Store4<uint16_t> {
   }
 };
 
-// One float4 per thread per iteration; all streams are read/written exactly once.
+// Every stream is read or written exactly once.  A block works on contiguous chunks of
+// kThreads*kUnroll float4 per stream and issues all its loads (kUnroll per stream per lane, 16
+// bytes each) before the first dependent instruction, so that each lane keeps up to 16 loads in
+// flight; the fp32 streams that are not re-read soon (momentum, new master weights) bypass the
+// caches with non-temporal accesses.
+constexpr int kUnroll = TP_UPDATE_UNROLL;
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
 template <typename T, bool BLEND, bool WFWD>
-__global__ __launch_bounds__(kThreads) void update_kernel(size_t n4, const float4* __restrict__ g,
-                                                          float4* __restrict__ m, const float4* w_old,
-                                                          float4* w_new, const float4* __restrict__ w_stale,
+__global__ __launch_bounds__(kThreads) void update_kernel(size_t n4, const floatx4* __restrict__ g,
+                                                          floatx4* __restrict__ m, const floatx4* w_old,
+                                                          floatx4* w_new, const floatx4* __restrict__ w_stale,
                                                           T* __restrict__ wfwd, T* __restrict__ wb, float lr,
                                                           float mu, float alpha, float beta,
                                                           float* __restrict__ partials) {
   __shared__ float red[4 * 4];
   float acc[4] = {0.f, 0.f, 0.f, 0.f};  // g^2, w^2, drift^2, wb^2
-  const size_t stride = (size_t)gridDim.x * kThreads;
-  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += stride) {
-    const float4 gv = g[i];
-    const float4 mv = m[i];
-    const float4 wv = w_old[i];
-    float4 sv;
-    if (BLEND) sv = w_stale[i];
-    float4 mn, wn;
-    mn.x = fmaf(mu, mv.x, gv.x); mn.y = fmaf(mu, mv.y, gv.y);
-    mn.z = fmaf(mu, mv.z, gv.z); mn.w = fmaf(mu, mv.w, gv.w);
-    wn.x = fmaf(-lr, mn.x, wv.x); wn.y = fmaf(-lr, mn.y, wv.y);
-    wn.z = fmaf(-lr, mn.z, wv.z); wn.w = fmaf(-lr, mn.w, wv.w);
-    m[i] = mn;
-    w_new[i] = wn;
-    if (WFWD) Store4<T>::st(wfwd + 4 * i, wn);
-    acc[0] += gv.x * gv.x + gv.y * gv.y + gv.z * gv.z + gv.w * gv.w;
-    acc[1] += wn.x * wn.x + wn.y * wn.y + wn.z * wn.z + wn.w * wn.w;
-    if (BLEND) {
-      float4 b;
-      b.x = fmaf(alpha, sv.x, beta * wn.x); b.y = fmaf(alpha, sv.y, beta * wn.y);
-      b.z = fmaf(alpha, sv.z, beta * wn.z); b.w = fmaf(alpha, sv.w, beta * wn.w);
-      Store4<T>::st(wb + 4 * i, b);
-      const float dx = wn.x - sv.x, dy = wn.y - sv.y, dz = wn.z - sv.z, dw = wn.w - sv.w;
-      acc[2] += dx * dx + dy * dy + dz * dz + dw * dw;
-      acc[3] += b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
+  const size_t chunk = (size_t)kThreads * kUnroll;
+  for (size_t base = (size_t)blockIdx.x * chunk; base < n4; base += (size_t)gridDim.x * chunk) {
+    floatx4 gv[kUnroll], mv[kUnroll], wv[kUnroll], sv[kUnroll];
+    bool ok[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const size_t i = base + (size_t)u * kThreads + threadIdx.x;
+      ok[u] = i < n4;
+      if (ok[u]) {
+        gv[u] = TP_UPDATE_NT ? __builtin_nontemporal_load(g + i) : g[i];
+        mv[u] = TP_UPDATE_NT ? __builtin_nontemporal_load(m + i) : m[i];
+        wv[u] = w_old[i];
+        if (BLEND) sv[u] = w_stale[i];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      if (!ok[u]) continue;
+      const size_t i = base + (size_t)u * kThreads + threadIdx.x;
+      floatx4 mn, wn;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        mn[c] = fmaf(mu, mv[u][c], gv[u][c]);
+        wn[c] = fmaf(-lr, mn[c], wv[u][c]);
+        acc[0] = fmaf(gv[u][c], gv[u][c], acc[0]);
+        acc[1] = fmaf(wn[c], wn[c], acc[1]);
+      }
+      if (TP_UPDATE_NT) {
+        __builtin_nontemporal_store(mn, m + i);
+        __builtin_nontemporal_store(wn, w_new + i);
+      } else {
+        m[i] = mn;
+        w_new[i] = wn;
+      }
+      if (WFWD) Store4<T>::st(wfwd + 4 * i, make_float4(wn[0], wn[1], wn[2], wn[3]));
+      if (BLEND) {
+        floatx4 b;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          b[c] = fmaf(alpha, sv[u][c], beta * wn[c]);
+          const float dd = wn[c] - sv[u][c];
+          acc[2] = fmaf(dd, dd, acc[2]);
+          acc[3] = fmaf(b[c], b[c], acc[3]);
+        }
+        Store4<T>::st(wb + 4 * i, make_float4(b[0], b[1], b[2], b[3]));
+      }
     }
   }
   block_sum<4>(acc, red);
@@ -102,22 +141,15 @@ __global__ __launch_bounds__(kThreads) void update_kernel(size_t n4, const float
   }
 }
 
-// Final, fixed-order reduction of the per-block partials into doubles.
+// Final, fixed-order reduction of the per-block partials into doubles: wave k sums quantity k.
 __global__ __launch_bounds__(kThreads) void diag_reduce_kernel(const float* __restrict__ partials, int nblocks,
                                                                double* __restrict__ diag) {
-  __shared__ double sm[kThreads];
-  for (int k = 0; k < 4; ++k) {
-    double s = 0.0;
-    for (int i = threadIdx.x; i < nblocks; i += kThreads) s += (double)partials[k * kUpdateBlocks + i];
-    sm[threadIdx.x] = s;
-    __syncthreads();
-    for (int w = kThreads / 2; w > 0; w >>= 1) {
-      if (threadIdx.x < w) sm[threadIdx.x] += sm[threadIdx.x + w];
-      __syncthreads();
-    }
-    if (threadIdx.x == 0) diag[k] = sm[0];
-    __syncthreads();
-  }
+  const int lane = threadIdx.x & 63, k = threadIdx.x >> 6;
+  double s = 0.0;
+  for (int i = lane; i < nblocks; i += 64) s += (double)partials[k * kUpdateBlocks + i];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+  if (lane == 0) diag[k] = s;
 }
 
 template <typename T>
@@ -142,12 +174,44 @@ __global__ __launch_bounds__(kThreads) void convert_kernel(size_t n4, const floa
     Store4<T>::st(dst + 4 * i, src[i]);
 }
 
+// dz = dy (.) d, 16 bytes per lane per step; `count` elements, the tail element-wise.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void act_backward_kernel(size_t count, const T* __restrict__ dy,
                                                                 const T* __restrict__ d, T* __restrict__ dz) {
+  constexpr int V = 16 / sizeof(T);
+  const size_t nvec = count / V;
   const size_t stride = (size_t)gridDim.x * kThreads;
-  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < count; i += stride)
-    dz[i] = from_float<T>(to_float(dy[i]) * to_float(d[i]));
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  for (size_t i = tid; i < nvec; i += stride) {
+    const uint4 a = reinterpret_cast<const uint4*>(dy)[i];
+    const uint4 b = reinterpret_cast<const uint4*>(d)[i];
+    uint4 o;
+    if (sizeof(T) == 2) {
+      const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+      uint32_t ow[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        ow[j] = pack_bf16x2(__uint_as_float(aw[j] << 16) * __uint_as_float(bw[j] << 16),
+                            __uint_as_float(aw[j] & 0xffff0000u) * __uint_as_float(bw[j] & 0xffff0000u));
+      o = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+    } else {
+      o = make_uint4(__float_as_uint(__uint_as_float(a.x) * __uint_as_float(b.x)),
+                     __float_as_uint(__uint_as_float(a.y) * __uint_as_float(b.y)),
+                     __float_as_uint(__uint_as_float(a.z) * __uint_as_float(b.z)),
+                     __float_as_uint(__uint_as_float(a.w) * __uint_as_float(b.w)));
+    }
+    reinterpret_cast<uint4*>(dz)[i] = o;
+  }
+  for (size_t i = nvec * V + tid; i < count; i += stride) dz[i] = from_float<T>(to_float(dy[i]) * to_float(d[i]));
+}
+
+// Plain 16-byte-per-lane copy (activations handed to a stage that are not yet in its workspace).
+__global__ __launch_bounds__(kThreads) void copy_kernel(size_t nvec, const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                        size_t tail_bytes, const char* tsrc, char* tdst) {
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  for (size_t i = tid; i < nvec; i += stride) dst[i] = src[i];
+  for (size_t i = tid; i < tail_bytes; i += stride) tdst[i] = tsrc[i];
 }
 
 // One wave per row.
@@ -199,12 +263,12 @@ inline int stream_blocks(size_t work_items, int max_blocks) {
 template <typename T>
 hipError_t update_dispatch(hipStream_t s, const UpdateArgs& a) {
   const size_t n4 = a.count / 4;
-  const int blocks = stream_blocks(n4, kUpdateBlocks);
-  const float4* g = (const float4*)a.g;
-  float4* m = (float4*)a.m;
-  const float4* wo = (const float4*)a.w_old;
-  float4* wn = (float4*)a.w_new;
-  const float4* ws = (const float4*)a.w_stale;
+  const int blocks = stream_blocks((n4 + kUnroll - 1) / kUnroll, kUpdateBlocks);
+  const floatx4* g = (const floatx4*)a.g;
+  floatx4* m = (floatx4*)a.m;
+  const floatx4* wo = (const floatx4*)a.w_old;
+  floatx4* wn = (floatx4*)a.w_new;
+  const floatx4* ws = (const floatx4*)a.w_stale;
   T* wf = (T*)a.wfwd;
   T* wb = (T*)a.wb;
   const bool blend = a.w_stale != nullptr && a.wb != nullptr;
@@ -257,13 +321,22 @@ hipError_t launch_convert(hipStream_t s, int elt, size_t count, const float* src
 }
 
 hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* d, void* dz) {
-  const int blocks = stream_blocks(count, 4096);
+  const int blocks = stream_blocks(count / 8 + 1, 4096);
   if (elt == ELT_BF16)
     hipLaunchKernelGGL(act_backward_kernel<uint16_t>, dim3(blocks), dim3(kThreads), 0, s, count, (const uint16_t*)dy,
                        (const uint16_t*)d, (uint16_t*)dz);
   else
     hipLaunchKernelGGL(act_backward_kernel<float>, dim3(blocks), dim3(kThreads), 0, s, count, (const float*)dy,
                        (const float*)d, (float*)dz);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy(hipStream_t s, const void* src, void* dst, size_t bytes) {
+  if (((uintptr_t)src | (uintptr_t)dst) & 15) return hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s);
+  const size_t nvec = bytes / 16, tail = bytes % 16;
+  const int blocks = stream_blocks(nvec, 2048);
+  hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(kThreads), 0, s, nvec, (const uint4*)src, (uint4*)dst, tail,
+                     (const char*)src + nvec * 16, (char*)dst + nvec * 16);
   return hipGetLastError();
 }
 

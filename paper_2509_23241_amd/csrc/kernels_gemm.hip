@@ -107,23 +107,52 @@ hipError_t simt(hipStream_t s, int elt, int M, int N, int K, const void* A, long
 }
 
 // Column sums of dz[M x N] in two fixed-order steps: row chunks -> partials[chunk][N] -> gb[N].
+// A lane owns V = 16/sizeof(T) adjacent columns (one 16-byte load per row); the four waves of a
+// block take every fourth row of the chunk and are combined through LDS in a fixed order.
 constexpr int kColChunkRows = 128;
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(int M, int N, const T* __restrict__ dz,
                                                                   float* __restrict__ partials) {
-  __shared__ float sm[4][64];
+  constexpr int V = 16 / sizeof(T);
+  __shared__ float sm[4][64 * V];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int col = blockIdx.x * 64 + lane;
+  const int col = (blockIdx.x * 64 + lane) * V;
   const int r0 = blockIdx.y * kColChunkRows;
   const int r1 = min(M, r0 + kColChunkRows);
-  float s = 0.f;
-  if (col < N)
-    for (int r = r0 + wave; r < r1; r += 4) s += to_float(dz[(size_t)r * N + col]);
-  sm[wave][lane] = s;
+  float s[V];
+#pragma unroll
+  for (int j = 0; j < V; ++j) s[j] = 0.f;
+  if (col + V <= N && (N % V) == 0) {
+    for (int r = r0 + wave; r < r1; r += 4) {
+      const uint4 v = *reinterpret_cast<const uint4*>(dz + (size_t)r * N + col);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+      if (sizeof(T) == 2) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          s[(2 * j) % V] += __uint_as_float(w[j] << 16);
+          s[(2 * j + 1) % V] += __uint_as_float(w[j] & 0xffff0000u);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s[j % V] += __uint_as_float(w[j]);
+      }
+    }
+  } else {
+    for (int r = r0 + wave; r < r1; r += 4)
+      for (int j = 0; j < V; ++j)
+        if (col + j < N) s[j] += to_float(dz[(size_t)r * N + col + j]);
+  }
+#pragma unroll
+  for (int j = 0; j < V; ++j) sm[wave][lane * V + j] = s[j];
   __syncthreads();
-  if (wave == 0 && col < N)
-    partials[(size_t)blockIdx.y * N + col] = (sm[0][lane] + sm[1][lane]) + (sm[2][lane] + sm[3][lane]);
+  if (wave == 0) {
+    for (int j = 0; j < V; ++j)
+      if (col + j < N) {
+        const int c = lane * V + j;
+        partials[(size_t)blockIdx.y * N + col + j] = (sm[0][c] + sm[1][c]) + (sm[2][c] + sm[3][c]);
+      }
+  }
 }
 
 __global__ __launch_bounds__(kThreads) void colsum_final_kernel(int chunks, int N, const float* __restrict__ partials,
@@ -162,7 +191,8 @@ hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void*
 
 hipError_t launch_colsum(hipStream_t s, int elt, int M, int N, const void* dz, float* gb, float* partials) {
   const int chunks = (M + kColChunkRows - 1) / kColChunkRows;
-  dim3 g1((N + 63) / 64, chunks);
+  const int per_block = 64 * (elt == ELT_BF16 ? 8 : 4);
+  dim3 g1((N + per_block - 1) / per_block, chunks);
   if (elt == ELT_BF16)
     hipLaunchKernelGGL(colsum_partial_kernel<uint16_t>, g1, dim3(kThreads), 0, s, M, N, (const uint16_t*)dz, partials);
   else

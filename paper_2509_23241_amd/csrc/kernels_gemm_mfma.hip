@@ -218,7 +218,6 @@ __device__ __forceinline__ floatx16 mma(bf16x8 a, bf16x8 b, floatx16 c) {
 // tile space; XCD (xi, xj) owns the (tiles_m/xm) x (tiles_n/xn) patch at that position.
 struct TileMap {
   int tiles_m, tiles_n, xm, xn;  // xm*xn == 8, or xm == 0 for the plain row-major mapping
-  long long* clk;                // tuning probe: workgroup 0 stores {shader cycles, 100 MHz ticks} of its main loop
   __device__ __forceinline__ void get(int b, int& tm, int& tn) const {
     if (xm == 0) { tm = b / tiles_n; tn = b % tiles_n; return; }
     const int xcd = b & 7, i = b >> 3;
@@ -230,12 +229,12 @@ struct TileMap {
 
 inline TileMap make_tile_map(int tiles_m, int tiles_n) {
   static const int cand[4][2] = {{2, 4}, {4, 2}, {1, 8}, {8, 1}};
-  TileMap best{tiles_m, tiles_n, 0, 0, nullptr};
+  TileMap best{tiles_m, tiles_n, 0, 0};
   long best_cost = -1;
   for (auto& c : cand) {
     if (tiles_m % c[0] || tiles_n % c[1]) continue;
     const long cost = tiles_m / c[0] + tiles_n / c[1];  // operand panels one XCD touches
-    if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = TileMap{tiles_m, tiles_n, c[0], c[1], nullptr}; }
+    if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = TileMap{tiles_m, tiles_n, c[0], c[1]}; }
   }
   return best;
 }
@@ -330,8 +329,6 @@ hipError_t launch(hipStream_t s, int M, int N, int K, const uint16_t* A, int lda
   hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n), dim3(NT), lds_bytes, s, M, N, K, A, lda, B, ldb, epi, map);
   return hipGetLastError();
 }
-
-long long* g_clk_probe = nullptr;  // device pointer set through the tuning hook, normally null
 
 // ================================================================================================
 // Direct-to-LDS variant
@@ -447,9 +444,7 @@ struct DmaSel { using type = RowDma<R, NW>; };
 template <int R, int NW>
 struct DmaSel<R, NW, true> { using type = ColDma<R, NW>; };
 
-// MODE: 0 = the product; 1 = copies only, 2 = matrix cores only (bandwidth probes for tuning;
-// their results are meaningless and they are reachable only through the tuning hook).
-template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, class Epi, int MODE = 0>
+template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, class Epi>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, int N, int K,
                                                                         const uint16_t* __restrict__ A, int lda,
                                                                         const uint16_t* __restrict__ B, int ldb,
@@ -504,28 +499,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, in
 #pragma unroll
     for (int t = 0; t < kLoads; ++t) issue_copy(t, st, st);
 
-  const long long clk0 = map.clk ? clock64() : 0, wall0 = map.clk ? wall_clock64() : 0;
   int rd = 0;        // stage holding tile kt
   int wr = NS - 1;   // stage that receives tile kt + NS - 1
   for (int kt = 0; kt < KT; ++kt) {
     // tile kt has landed once at most the NS-2 newer tiles are still in flight
     wait_vmcnt<(NS - 2) * kLoads>();
-    if (MODE != 4) lds_barrier();  // tile kt visible to all waves; everybody is done reading stage `wr`
+    lds_barrier();  // tile kt visible to all waves; everybody is done reading stage `wr`
     const uint16_t* la = lds_raw + rd * (kStageBytes / 2);
     const uint16_t* lb = la + AT::kBytes / 2;
-    if (MODE == 1) {
-#pragma unroll
-      for (int t = 0; t < kLoads; ++t) issue_copy(t, kt + NS - 1, wr);
-    } else if (MODE >= 3) {
-      bf16x8 a0 = AT::frag(lds_raw, wm, 0, lane), b0 = BT::frag(lds_raw, wn, 0, lane);
-#pragma unroll
-      for (int kk = 0; kk < DBK / 16; ++kk)
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[i][j], 0, 0, 0);
-    } else {
+    {
       // Fixed schedule per k step: the LDS reads of step kk+1 go out first, then the MFMAs of
       // step kk with the global->LDS copies of tile kt+NS-1 spread evenly between them, so that
       // the wave never sits in the memory-instruction queue while its matrix core idles.
@@ -550,16 +532,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, in
 #pragma unroll
           for (int j = 0; j < TN; ++j) {
             acc[i][j] = mma<Epi::kSwap>(af[c][i], bfr[c][j], acc[i][j]);
-            if (MODE == 0) {
-              const int q = (kk * TM + i) * TN + j;  // compile-time after unrolling
+            const int q = (kk * TM + i) * TN + j;  // compile-time after unrolling
 #pragma unroll
-              for (int t = 0; t < kLoads; ++t)
-                if ((t * NM) / kLoads == q) {
-                  __builtin_amdgcn_sched_barrier(0);
-                  issue_copy(t, kt + NS - 1, wr);
-                  __builtin_amdgcn_sched_barrier(0);
-                }
-            }
+            for (int t = 0; t < kLoads; ++t)
+              if ((t * NM) / kLoads == q) {
+                __builtin_amdgcn_sched_barrier(0);
+                issue_copy(t, kt + NS - 1, wr);
+                __builtin_amdgcn_sched_barrier(0);
+              }
           }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -569,11 +549,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, in
   }
   wait_vmcnt<0>();  // the trailing dummy copies must have landed before LDS is reused
   lds_barrier();    // all waves are done with the last stage
-  if (map.clk && blockIdx.x == 0 && threadIdx.x == 0) {
-    map.clk[0] = clock64() - clk0;
-    map.clk[1] = wall_clock64() - wall0;
-  }
-
   store_tiles<TM, TN>(acc, epi, m0 + wm, n0 + wn, M, N, lane);
 }
 
@@ -587,7 +562,7 @@ inline bool dma_ok(int M, int N, int K, int lda, int ldb, bool a_col, bool b_col
   return true;
 }
 
-template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, int MODE = 0, class Epi>
+template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, class Epi>
 hipError_t launch_dma(hipStream_t s, int M, int N, int K, const uint16_t* A, int lda, const uint16_t* B, int ldb,
                       const Epi& epi) {
   constexpr int NW = WGM * WGN;
@@ -595,15 +570,14 @@ hipError_t launch_dma(hipStream_t s, int M, int N, int K, const uint16_t* A, int
   using BT = typename DmaSel<BN, NW, B_COL>::type;
   constexpr size_t lds_bytes = (size_t)NS * (AT::kBytes + BT::kBytes);
   static_assert(lds_bytes <= 160 * 1024, "stages do not fit the LDS of a CU");
-  auto kernel = gemm_bf16_dma_kernel<BM, BN, WGM, WGN, NS, A_COL, B_COL, Epi, MODE>;
+  auto kernel = gemm_bf16_dma_kernel<BM, BN, WGM, WGN, NS, A_COL, B_COL, Epi>;
   if (lds_bytes > 64 * 1024) {
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (attr != hipSuccess) return attr;
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  TileMap map = make_tile_map(tiles_m, tiles_n);
-  map.clk = g_clk_probe;
+  const TileMap map = make_tile_map(tiles_m, tiles_n);
   hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n), dim3(64 * NW), lds_bytes, s, M, N, K, A, lda, B, ldb, epi, map);
   return hipGetLastError();
 }
@@ -630,8 +604,6 @@ int pick(int rows, int cols, int contraction, int lda, int ldb, bool a_col, bool
 
 }  // namespace
 
-void mfma_set_clock_probe(long long* dev_ptr) { g_clk_probe = dev_ptr; }
-
 void mfma_set_config(int product, int cfg) {
   if (product >= 0 && product < 3) g_cfg[product] = cfg;
 }
@@ -652,16 +624,6 @@ bool mfma_wgrad_supported(int M, int N, int K) { return M >= 1 && N % 8 == 0 && 
     case 15: return launch_dma<256, 256, 2, 2, 2, ACOL, BCOL>(__VA_ARGS__);     \
     case 16: return launch_dma<128, 128, 2, 2, 4, ACOL, BCOL>(__VA_ARGS__);     \
     case 17: return launch_dma<64, 64, 2, 2, 8, ACOL, BCOL>(__VA_ARGS__);       \
-    case 23: return launch_dma<256, 128, 2, 2, 3, ACOL, BCOL, 1>(__VA_ARGS__);  \
-    case 33: return launch_dma<256, 128, 2, 2, 3, ACOL, BCOL, 2>(__VA_ARGS__);  \
-    case 25: return launch_dma<256, 256, 2, 2, 2, ACOL, BCOL, 1>(__VA_ARGS__);  \
-    case 35: return launch_dma<256, 256, 2, 2, 2, ACOL, BCOL, 2>(__VA_ARGS__);  \
-    case 22: return launch_dma<128, 128, 2, 2, 3, ACOL, BCOL, 1>(__VA_ARGS__);  \
-    case 43: return launch_dma<256, 128, 2, 2, 3, ACOL, BCOL, 3>(__VA_ARGS__);  \
-    case 53: return launch_dma<256, 128, 2, 2, 3, ACOL, BCOL, 4>(__VA_ARGS__);  \
-    case 45: return launch_dma<256, 256, 2, 2, 2, ACOL, BCOL, 3>(__VA_ARGS__);  \
-    case 55: return launch_dma<256, 256, 2, 2, 2, ACOL, BCOL, 4>(__VA_ARGS__);  \
-    case 32: return launch_dma<128, 128, 2, 2, 3, ACOL, BCOL, 2>(__VA_ARGS__);  \
     case 5: return launch<128, 256, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);         \
     case 4: return launch<64, 64, 2, 2, 128, ACOL, BCOL>(__VA_ARGS__);          \
     case 3: return launch<256, 128, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);         \

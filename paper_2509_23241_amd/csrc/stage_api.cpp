@@ -415,7 +415,7 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
     char* x_saved = aslot + lp.x_off + row0 * lp.d.in_features * es;
     if (l == 0 && x_dev != (const void*)x_saved) {
       ProfScope ps(st, TP_K_COPY);
-      HIP_TRY(hipMemcpyAsync(x_saved, x_dev, (size_t)d.mb * lp.d.in_features * es, hipMemcpyDeviceToDevice, st->stream));
+      HIP_TRY(tp::launch_copy(st->stream, x_dev, x_saved, (size_t)d.mb * lp.d.in_features * es));
     }
     void* z_out = lp.z_off == UINT64_MAX ? nullptr : aslot + lp.z_off + row0 * lp.d.out_features * es;
     void* a_out = (l == L - 1) ? y_dev
