@@ -12,9 +12,10 @@ enum Act : int { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
 
 // z = x W^T + bias ; a = act(z) ; d = act'(z).   x:[M x K] W:[N x K] (elt), bias: fp32[N].
 // d_out (what the backward pass multiplies with) may be null; a_out is always written.
-// Both [M x N] in elt.
+// Both [M x N] in elt.  If x_copy is not null the launch also leaves a copy of x there (fused
+// into the GEMM where the kernel supports it, a separate copy otherwise).
 hipError_t launch_fprop(hipStream_t s, int elt, int M, int N, int K, const void* x, const void* W,
-                        const float* bias, int act, void* d_out, void* a_out);
+                        const float* bias, int act, void* d_out, void* a_out, void* x_copy);
 
 // out = (dz W_b) (.) d_prev   dz:[M x N] W_b:[N x K] d_prev:[M x K] saved act'(z), or null.
 hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* Wb,

@@ -146,6 +146,7 @@ __global__ __launch_bounds__(kThreads) void diag_reduce_kernel(const float* __re
                                                                double* __restrict__ diag) {
   const int lane = threadIdx.x & 63, k = threadIdx.x >> 6;
   double s = 0.0;
+#pragma unroll 8
   for (int i = lane; i < nblocks; i += 64) s += (double)partials[k * kUpdateBlocks + i];
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);

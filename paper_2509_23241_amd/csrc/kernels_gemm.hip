@@ -109,7 +109,7 @@ hipError_t simt(hipStream_t s, int elt, int M, int N, int K, const void* A, long
 // Column sums of dz[M x N] in two fixed-order steps: row chunks -> partials[chunk][N] -> gb[N].
 // A lane owns V = 16/sizeof(T) adjacent columns (one 16-byte load per row); the four waves of a
 // block take every fourth row of the chunk and are combined through LDS in a fixed order.
-constexpr int kColChunkRows = 128;
+constexpr int kColChunkRows = 32;
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(int M, int N, const T* __restrict__ dz,
@@ -124,6 +124,7 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(int M, int N, 
 #pragma unroll
   for (int j = 0; j < V; ++j) s[j] = 0.f;
   if (col + V <= N && (N % V) == 0) {
+#pragma unroll 8
     for (int r = r0 + wave; r < r1; r += 4) {
       const uint4 v = *reinterpret_cast<const uint4*>(dz + (size_t)r * N + col);
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -160,6 +161,7 @@ __global__ __launch_bounds__(kThreads) void colsum_final_kernel(int chunks, int 
   const int col = blockIdx.x * kThreads + threadIdx.x;
   if (col >= N) return;
   float s = 0.f;
+#pragma unroll 8
   for (int c = 0; c < chunks; ++c) s += partials[(size_t)c * N + col];
   gb[col] = s;
 }
@@ -171,9 +173,18 @@ size_t colsum_scratch_floats(int M, int N) {
 }
 
 hipError_t launch_fprop(hipStream_t s, int elt, int M, int N, int K, const void* x, const void* W, const float* bias,
-                        int act, void* d_out, void* a_out) {
+                        int act, void* d_out, void* a_out, void* x_copy) {
+  const bool aligned = (((uintptr_t)x | (uintptr_t)x_copy) & 15) == 0;
+  if (elt == ELT_BF16 && mfma_fprop_supported(M, N, K) && aligned)
+    return mfma_fprop(s, M, N, K, (const uint16_t*)x, (const uint16_t*)W, bias, act, (uint16_t*)d_out, (uint16_t*)a_out,
+                      (uint16_t*)x_copy);
+  if (x_copy) {
+    hipError_t err = launch_copy(s, x, x_copy, (size_t)M * K * (elt == ELT_BF16 ? 2 : 4));
+    if (err != hipSuccess) return err;
+  }
   if (elt == ELT_BF16 && mfma_fprop_supported(M, N, K))
-    return mfma_fprop(s, M, N, K, (const uint16_t*)x, (const uint16_t*)W, bias, act, (uint16_t*)d_out, (uint16_t*)a_out);
+    return mfma_fprop(s, M, N, K, (const uint16_t*)x, (const uint16_t*)W, bias, act, (uint16_t*)d_out, (uint16_t*)a_out,
+                      nullptr);
   EpiArgs e{};
   e.bias = bias; e.d_out = d_out; e.a_out = a_out; e.act = act;
   return simt<EPI_FPROP>(s, elt, M, N, K, x, K, 1, W, 1, K, e);

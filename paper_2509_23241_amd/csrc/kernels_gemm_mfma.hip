@@ -227,6 +227,14 @@ struct TileMap {
   }
 };
 
+// Optional side job of a forward GEMM: keep a copy of its input (the stage saves the activations a
+// micro-batch arrives with).  The workgroups share the copy evenly, 16 bytes per lane per step.
+struct SideCopy {
+  const uint4* src;
+  uint4* dst;
+  size_t nvec;  // 16-byte units; 0 = nothing to do
+};
+
 inline TileMap make_tile_map(int tiles_m, int tiles_n) {
   static const int cand[4][2] = {{2, 4}, {4, 2}, {1, 8}, {8, 1}};
   TileMap best{tiles_m, tiles_n, 0, 0};
@@ -312,7 +320,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_mfma_kernel(int M, i
 
 template <int BM, int BN, int WGM, int WGN, int BKT, bool A_COL, bool B_COL, class Epi>
 hipError_t launch(hipStream_t s, int M, int N, int K, const uint16_t* A, int lda, const uint16_t* B, int ldb,
-                  const Epi& epi) {
+                  const Epi& epi, SideCopy side = SideCopy{nullptr, nullptr, 0}) {
+  if (side.nvec) {  // this kernel has no side job: a plain copy first
+    hipError_t e = hipMemcpyAsync(side.dst, side.src, side.nvec * 16, hipMemcpyDeviceToDevice, s);
+    if (e != hipSuccess) return e;
+  }
   constexpr int NT = 64 * WGM * WGN;
   using ATile = typename TileSel<BM, BKT, NT, A_COL>::type;
   using BTile = typename TileSel<BN, BKT, NT, B_COL>::type;
@@ -448,7 +460,7 @@ template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, clas
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, int N, int K,
                                                                         const uint16_t* __restrict__ A, int lda,
                                                                         const uint16_t* __restrict__ B, int ldb,
-                                                                        Epi epi, TileMap map) {
+                                                                        Epi epi, TileMap map, SideCopy side) {
   constexpr int NW = WGM * WGN;
   using AT = typename DmaSel<BM, NW, A_COL>::type;
   using BT = typename DmaSel<BN, NW, B_COL>::type;
@@ -474,6 +486,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, in
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  for (size_t i = (size_t)blockIdx.x * (64 * NW) + threadIdx.x; i < side.nvec; i += (size_t)gridDim.x * (64 * NW))
+    side.dst[i] = side.src[i];
 
   AT ta;
   BT tb;
@@ -564,7 +579,7 @@ inline bool dma_ok(int M, int N, int K, int lda, int ldb, bool a_col, bool b_col
 
 template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, class Epi>
 hipError_t launch_dma(hipStream_t s, int M, int N, int K, const uint16_t* A, int lda, const uint16_t* B, int ldb,
-                      const Epi& epi) {
+                      const Epi& epi, SideCopy side = SideCopy{nullptr, nullptr, 0}) {
   constexpr int NW = WGM * WGN;
   using AT = typename DmaSel<BM, NW, A_COL>::type;
   using BT = typename DmaSel<BN, NW, B_COL>::type;
@@ -578,7 +593,8 @@ hipError_t launch_dma(hipStream_t s, int M, int N, int K, const uint16_t* A, int
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const TileMap map = make_tile_map(tiles_m, tiles_n);
-  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n), dim3(64 * NW), lds_bytes, s, M, N, K, A, lda, B, ldb, epi, map);
+  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n), dim3(64 * NW), lds_bytes, s, M, N, K, A, lda, B, ldb, epi, map,
+                     side);
   return hipGetLastError();
 }
 
@@ -592,7 +608,9 @@ int pick(int rows, int cols, int contraction, int lda, int ldb, bool a_col, bool
   if (override_cfg >= 0) return override_cfg;
   auto blocks = [&](int bm, int bn) { return (long)((rows + bm - 1) / bm) * ((cols + bn - 1) / bn); };
   if (dma_ok(rows, cols, contraction, lda, ldb, a_col, b_col)) {
-    if (blocks(256, 128) >= 256) return 13;
+    // 8 waves on the big tiles: two waves per SIMD hide each other's LDS and barrier latency
+    if (a_col && b_col && blocks(256, 256) >= 256) return 18;  // fp32-output product only (register budget)
+    if (blocks(256, 128) >= 256) return 19;
     if (blocks(128, 128) >= 256) return 12;
     if (blocks(128, 64) >= 256) return 11;
     return 10;
@@ -624,6 +642,8 @@ bool mfma_wgrad_supported(int M, int N, int K) { return M >= 1 && N % 8 == 0 && 
     case 15: return launch_dma<256, 256, 2, 2, 2, ACOL, BCOL>(__VA_ARGS__);     \
     case 16: return launch_dma<128, 128, 2, 2, 4, ACOL, BCOL>(__VA_ARGS__);     \
     case 17: return launch_dma<64, 64, 2, 2, 8, ACOL, BCOL>(__VA_ARGS__);       \
+    case 18: return launch_dma<256, 256, 2, 4, 2, ACOL, BCOL>(__VA_ARGS__);     \
+    case 19: return launch_dma<256, 128, 2, 4, 3, ACOL, BCOL>(__VA_ARGS__);     \
     case 5: return launch<128, 256, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);         \
     case 4: return launch<64, 64, 2, 2, 128, ACOL, BCOL>(__VA_ARGS__);          \
     case 3: return launch<256, 128, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);         \
@@ -633,9 +653,11 @@ bool mfma_wgrad_supported(int M, int N, int K) { return M >= 1 && N % 8 == 0 && 
   }
 
 hipError_t mfma_fprop(hipStream_t s, int M, int N, int K, const uint16_t* x, const uint16_t* W, const float* bias,
-                      int act, uint16_t* d_out, uint16_t* a_out) {
+                      int act, uint16_t* d_out, uint16_t* a_out, uint16_t* x_copy) {
   EpiFprop e{bias, d_out, a_out, act, N};
-  TP_GEMM_DISPATCH(pick(M, N, K, K, K, false, false, g_cfg[0]), false, false, s, M, N, K, x, K, W, K, e)
+  // x is [M x K] with K % 8 == 0 and 16-byte aligned rows, so it is a whole number of 16-byte units
+  SideCopy side{(const uint4*)x, (uint4*)x_copy, x_copy ? (size_t)M * K / 8 : 0};
+  TP_GEMM_DISPATCH(pick(M, N, K, K, K, false, false, g_cfg[0]), false, false, s, M, N, K, x, K, W, K, e, side)
 }
 
 hipError_t mfma_dgrad(hipStream_t s, int M, int N, int K, const uint16_t* dz, const uint16_t* Wb,

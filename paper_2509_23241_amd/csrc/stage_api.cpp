@@ -413,16 +413,16 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
   for (int l = 0; l < L; ++l) {
     const LayerPlan& lp = st->plan.layers[l];
     char* x_saved = aslot + lp.x_off + row0 * lp.d.in_features * es;
-    if (l == 0 && x_dev != (const void*)x_saved) {
-      ProfScope ps(st, TP_K_COPY);
-      HIP_TRY(tp::launch_copy(st->stream, x_dev, x_saved, (size_t)d.mb * lp.d.in_features * es));
-    }
+    // a micro-batch that did not arrive in its workspace slot is copied there by its first GEMM
+    const bool need_copy = l == 0 && x_dev != (const void*)x_saved;
+    const void* x_in = need_copy ? x_dev : (const void*)x_saved;
     void* z_out = lp.z_off == UINT64_MAX ? nullptr : aslot + lp.z_off + row0 * lp.d.out_features * es;
     void* a_out = (l == L - 1) ? y_dev
                                : (void*)(aslot + st->plan.layers[l + 1].x_off + row0 * lp.d.out_features * es);
     ProfScope ps(st, TP_K_FPROP);
-    HIP_TRY(tp::launch_fprop(st->stream, d.dtype, d.mb, lp.d.out_features, lp.d.in_features, x_saved,
-                             wcopy + lp.w_off * es, master + lp.b_off, lp.d.act, z_out, a_out));
+    HIP_TRY(tp::launch_fprop(st->stream, d.dtype, d.mb, lp.d.out_features, lp.d.in_features, x_in,
+                             wcopy + lp.w_off * es, master + lp.b_off, lp.d.act, z_out, a_out,
+                             need_copy ? x_saved : nullptr));
   }
   return TP_OK;
 }
