@@ -26,6 +26,12 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
+# HBM-side bytes per launch at the default workload, from two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE) scaled by what the same counters read for a plain 1 GiB copy (FETCH_SIZE reports half the
+# bytes, WRITE_SIZE all of them); commands and raw counts: profiles/bench_mlp4096_stage1_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = {"fprop": 56.1e6, "dgrad": 159.6e6, "wgrad": 168.0e6, "update": 940.1e6,
+                          "act_bwd": 50.4e6, "colsum": 17.9e6}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -39,6 +45,9 @@ def parse():
     ap.add_argument("--n", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-minibatches", type=int, default=3)
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
+                    help="only run a plain device copy of BYTES bytes five times and exit (calibration of the "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -107,6 +116,14 @@ def main():
         sys.exit(2)
     import numpy as np
     import torch
+    if args.copy_probe:
+        src = torch.ones(args.copy_probe // 4, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": args.copy_probe, "copies": 5}))
+        return
     from paper_2509_23241_amd import binding as B
     from paper_2509_23241_amd.runner import GpuStage
     from synth_inputs import workloads as W
@@ -193,6 +210,9 @@ def main():
         achieved = nbytes / (dk["avg_us"] * 1e-6) / 1e9
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
+    default_workload = (args.width, args.mb, args.n, args.stage, args.policy) == (4096, 256, 8, 1, "convex")
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(dominant) if default_workload else None
+    roofline["algorithmic"] = nbytes if roofline["bound"] == "hbm" else flops
     roofline["avg_us"] = dk["avg_us"]
     roofline["launches_per_step"] = dk["launches_per_step"]
     out = {
