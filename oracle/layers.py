@@ -65,3 +65,63 @@ def softmax_cross_entropy(logits, labels, denom):
     d = np.exp(logp)
     d[rows, labels] -= 1.0
     return loss, d / denom
+
+
+# ---------------------------------------------------------------------------
+# convolution and pooling (NHWC activations, weights [Cout][kh][kw][Cin])
+# ---------------------------------------------------------------------------
+
+def conv2d_forward(x, W, b, stride=1, pad=1):
+    """Cross-correlation with zero padding, written as the sum over the kernel offsets:
+    z[n, oh, ow, o] = b[o] + sum_{i,j,c} x[n, oh*stride + i - pad, ow*stride + j - pad, c] * W[o, i, j, c]."""
+    B, H, Wd, _ = x.shape
+    Cout, kh, kw, _ = W.shape
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (Wd + 2 * pad - kw) // stride + 1
+    xp = np.pad(x, ((0, 0), (pad, pad), (pad, pad), (0, 0)))
+    z = np.zeros((B, Ho, Wo, Cout), dtype=np.float64)
+    for i in range(kh):
+        for j in range(kw):
+            patch = xp[:, i:i + stride * Ho:stride, j:j + stride * Wo:stride, :]
+            z += patch @ W[:, i, j, :].T
+    return z + b
+
+
+def conv2d_backward(dz, x, W_b, stride=1, pad=1):
+    """Gradients of conv2d_forward given dz = dL/dz: (dW, db, dx).
+
+    dW[o,i,j,c] = sum_{n,oh,ow} dz[n,oh,ow,o] * x[n, oh*stride+i-pad, ow*stride+j-pad, c]
+    db[o]       = sum_{n,oh,ow} dz[n,oh,ow,o]
+    dx          = the same sum scattered back through W_b (the weights the method prescribes)."""
+    B, H, Wd, Cin = x.shape
+    Cout, kh, kw, _ = W_b.shape
+    _, Ho, Wo, _ = dz.shape
+    xp = np.pad(x, ((0, 0), (pad, pad), (pad, pad), (0, 0)))
+    dxp = np.zeros_like(xp)
+    dW = np.zeros((Cout, kh, kw, Cin), dtype=np.float64)
+    dz2 = dz.reshape(-1, Cout)
+    for i in range(kh):
+        for j in range(kw):
+            patch = xp[:, i:i + stride * Ho:stride, j:j + stride * Wo:stride, :]
+            dW[:, i, j, :] = dz2.T @ patch.reshape(-1, Cin)
+            dxp[:, i:i + stride * Ho:stride, j:j + stride * Wo:stride, :] += dz @ W_b[:, i, j, :]
+    dx = dxp[:, pad:pad + H, pad:pad + Wd, :]
+    return dW, dz2.sum(axis=0), dx
+
+
+def maxpool2_forward(x):
+    """2x2 max pooling, stride 2.  Returns (y, idx) with idx the position of the FIRST maximum in
+    the window in row-major order (0: top-left, 1: top-right, 2: bottom-left, 3: bottom-right)."""
+    B, H, Wd, C = x.shape
+    win = x.reshape(B, H // 2, 2, Wd // 2, 2, C).transpose(0, 1, 3, 2, 4, 5).reshape(B, H // 2, Wd // 2, 4, C)
+    idx = np.argmax(win, axis=3)
+    y = np.take_along_axis(win, idx[:, :, :, None, :], axis=3)[:, :, :, 0, :]
+    return y, idx
+
+
+def maxpool2_backward(dy, idx, in_shape):
+    """Each output gradient goes to the input position that produced the maximum."""
+    B, H, Wd, C = in_shape
+    dwin = np.zeros((B, H // 2, Wd // 2, 4, C), dtype=np.float64)
+    np.put_along_axis(dwin, idx[:, :, :, None, :], dy[:, :, :, None, :], axis=3)
+    return dwin.reshape(B, H // 2, Wd // 2, 2, 2, C).transpose(0, 1, 3, 2, 4, 5).reshape(B, H, Wd, C)

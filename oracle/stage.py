@@ -38,6 +38,14 @@ class Stage:
     def __init__(self, layer_specs, params: List[np.ndarray], *, policy: str, lam: float,
                  lr: float, momentum: float, n: int, first_stage: bool = False):
         self.specs = list(layer_specs)
+        # position of each layer's weight in the flat parameter list (None: layer has no parameters)
+        self.pidx, nxt = [], 0
+        for spec in self.specs:
+            if getattr(spec, "kind", "dense") == "pool":
+                self.pidx.append(None)
+            else:
+                self.pidx.append(nxt)
+                nxt += 2
         self.policy = policy
         self.lam = float(lam)
         self.lr = float(lr)
@@ -73,7 +81,17 @@ class Stage:
         saved = []
         a = np.asarray(x, dtype=np.float64)
         for li, spec in enumerate(self.specs):
-            z = L.dense_forward(a, W[2 * li], W[2 * li + 1])
+            kind = getattr(spec, "kind", "dense")
+            pi = self.pidx[li]
+            if kind == "pool":
+                y, idx = L.maxpool2_forward(a)
+                saved.append((a.shape, idx))
+                a = y
+                continue
+            if kind == "conv":
+                z = L.conv2d_forward(a, W[pi], W[pi + 1], spec.stride, spec.pad)
+            else:
+                z = L.dense_forward(a, W[pi], W[pi + 1])
             saved.append((a, z))
             a = L.act_forward(z, spec.act)
         rec["saved"].append(saved)
@@ -107,18 +125,28 @@ class Stage:
         self.last_W_b = W_b
         self.trace.append(("B", mb, v_f, v_now, delta))
         dy = np.asarray(dy, dtype=np.float64)
-        rows = dy.shape[0] // self.n
+        rows = dy.shape[0] // self.n                       # samples per micro-batch
         g = [np.zeros_like(p) for p in self.weights[self.latest]]
         dx_parts = []
         for ub in range(self.n):                           # one backward, all micro-batches
             da = dy[ub * rows:(ub + 1) * rows]
             saved = rec["saved"][ub]
             for li in reversed(range(len(self.specs))):
+                spec = self.specs[li]
+                kind = getattr(spec, "kind", "dense")
+                pi = self.pidx[li]
+                if kind == "pool":
+                    in_shape, idx = saved[li]
+                    da = L.maxpool2_backward(da, idx, in_shape)
+                    continue
                 x_in, z = saved[li]
-                dz = da * L.act_derivative(z, self.specs[li].act)
-                dW, db, da = L.dense_backward(dz, x_in, W_b[2 * li])
-                g[2 * li] += dW
-                g[2 * li + 1] += db
+                dz = da * L.act_derivative(z, spec.act)
+                if kind == "conv":
+                    dW, db, da = L.conv2d_backward(dz, x_in, W_b[pi], spec.stride, spec.pad)
+                else:
+                    dW, db, da = L.dense_backward(dz, x_in, W_b[pi])
+                g[pi] += dW
+                g[pi + 1] += db
             dx_parts.append(da)
         self.g = g
         # the intermediate weights are built: this mini-batch no longer needs its stale version

@@ -30,15 +30,77 @@ class Dense:
     def param_shapes(self):
         return [(self.out_features, self.in_features), (self.out_features,)]
 
+    def in_shape(self):
+        return (self.in_features,)
+
+    def out_shape(self):
+        return (self.out_features,)
+
     def out_dim(self):
         return self.out_features
+
+
+@dataclass(frozen=True)
+class Conv2d:
+    """3x3-style convolution on NHWC activations, weights [Cout][kh][kw][Cin], plus bias and activation."""
+    cin: int
+    cout: int
+    h: int           # input height
+    w: int           # input width
+    act: str
+    k: int = 3
+    stride: int = 1
+    pad: int = 1
+    kind: str = "conv"
+
+    def param_shapes(self):
+        return [(self.cout, self.k, self.k, self.cin), (self.cout,)]
+
+    @property
+    def ho(self):
+        return (self.h + 2 * self.pad - self.k) // self.stride + 1
+
+    @property
+    def wo(self):
+        return (self.w + 2 * self.pad - self.k) // self.stride + 1
+
+    def in_shape(self):
+        return (self.h, self.w, self.cin)
+
+    def out_shape(self):
+        return (self.ho, self.wo, self.cout)
+
+    def out_dim(self):
+        return self.ho * self.wo * self.cout
+
+
+@dataclass(frozen=True)
+class MaxPool2:
+    """2x2 max pooling with stride 2 on NHWC activations; no parameters."""
+    c: int
+    h: int
+    w: int
+    act: str = "none"
+    kind: str = "pool"
+
+    def param_shapes(self):
+        return []
+
+    def in_shape(self):
+        return (self.h, self.w, self.c)
+
+    def out_shape(self):
+        return (self.h // 2, self.w // 2, self.c)
+
+    def out_dim(self):
+        return (self.h // 2) * (self.w // 2) * self.c
 
 
 @dataclass(frozen=True)
 class Workload:
     name: str
     dtype: str                     # "f32" or "bf16" (bf16 storage, fp32 master weights)
-    stages: Tuple[Tuple[Dense, ...], ...]
+    stages: Tuple[tuple, ...]
     mb: int                        # samples per micro-batch
     n: int                         # micro-batches per mini-batch
     classes: int
@@ -53,10 +115,10 @@ class Workload:
 
     @property
     def in_dim(self) -> int:
-        return self.stages[0][0].in_features
+        return self.stage_in_dim(0)
 
     def stage_in_dim(self, s: int) -> int:
-        return self.stages[s][0].in_features
+        return int(np.prod(self.stages[s][0].in_shape()))
 
     def stage_out_dim(self, s: int) -> int:
         return self.stages[s][-1].out_dim()
@@ -93,6 +155,18 @@ def mlp_wide(width: int = 4096, mb: int = 256, n: int = 8, classes: int = 1000,
                     mb=mb, n=n, classes=classes)
 
 
+def vgg_stage0(mb: int = 64, n: int = 4, size: int = 32, c1: int = 64, c2: int = 128, classes: int = 100,
+               dtype: str = "bf16") -> Workload:
+    """First stage of a VGG-16-style net on size x size x 3 images: conv3-c1, conv3-c1, pool, conv3-c2,
+    conv3-c2, pool (3x3 convolutions, stride 1, pad 1, bias, ReLU), as stage 0 of a 4-stage pipeline.
+    Only this stage is described; the other three are not built, so the workload is used stage-wise."""
+    s0 = (Conv2d(3, c1, size, size, "relu"), Conv2d(c1, c1, size, size, "relu"), MaxPool2(c1, size, size),
+          Conv2d(c1, c2, size // 2, size // 2, "relu"), Conv2d(c2, c2, size // 2, size // 2, "relu"),
+          MaxPool2(c2, size // 2, size // 2))
+    return Workload(name=f"vgg{size}_{c1}_{c2}_{dtype}_s0", dtype=dtype, stages=(s0, (), (), ()), mb=mb, n=n,
+                    classes=classes)
+
+
 def with_lambda(w: Workload, lam: float) -> Workload:
     return replace(w, lam=lam)
 
@@ -110,6 +184,8 @@ def init_params(w: Workload, s: int) -> List[np.ndarray]:
     """
     out = []
     for li, layer in enumerate(w.stages[s]):
+        if not layer.param_shapes():
+            continue
         wshape, bshape = layer.param_shapes()
         fan_in = int(np.prod(wshape[1:]))
         W = _normal(f"{w.name}/s{s}/l{li}/W", wshape, std=float(np.sqrt(2.0 / fan_in)), seed=w.seed)
@@ -130,12 +206,13 @@ def minibatch_labels(w: Workload, j: int) -> np.ndarray:
 
 def stage_input(w: Workload, s: int, j: int) -> np.ndarray:
     """Synthetic input of an interior stage timed on its own: N(0,1)."""
-    x = _normal(f"{w.name}/s{s}/x/{j}", (w.n * w.mb, w.stage_in_dim(s)), seed=w.seed)
+    x = _normal(f"{w.name}/s{s}/x/{j}", (w.n * w.mb,) + tuple(w.stages[s][0].in_shape()), seed=w.seed)
     return w.cast(x)
 
 
 def stage_upstream_grad(w: Workload, s: int, j: int) -> np.ndarray:
     """Synthetic gradient w.r.t. the output of stage s: N(0,1)/sqrt(out_dim)."""
     d = w.stage_out_dim(s)
-    g = _normal(f"{w.name}/s{s}/dy/{j}", (w.n * w.mb, d), std=float(1.0 / np.sqrt(d)), seed=w.seed)
+    g = _normal(f"{w.name}/s{s}/dy/{j}", (w.n * w.mb,) + tuple(w.stages[s][-1].out_shape()),
+                std=float(1.0 / np.sqrt(d)), seed=w.seed)
     return w.cast(g)
