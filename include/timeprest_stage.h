@@ -36,9 +36,11 @@
  *     n micro-batches stacked in order, [n*mb x features].  In TP_BF16 mode activations,
  *     incoming/outgoing gradients and the compute copies of the weights are bfloat16,
  *     while ring, momentum and gradient stay fp32; in TP_F32 mode everything is fp32.
- *   - Parameter arena: per layer the weight matrix W[out x in] followed by the bias
- *     b[out]; each tensor starts at a multiple of 64 elements (offsets are reported by
- *     stage_workspace_query; padding elements are zero and stay zero).
+ *   - Parameter arena: per layer that has parameters the weight tensor (dense W[out x in],
+ *     conv W[Cout][3][3][Cin]) followed by the bias b[out]; each tensor starts at a multiple of
+ *     64 elements (offsets are reported by stage_workspace_query; padding elements are zero
+ *     and stay zero).  Activations of conv/pool layers are NHWC; a row of a mini-batch is one
+ *     sample with all its values.
  */
 #ifndef TIMEPREST_STAGE_H
 #define TIMEPREST_STAGE_H
@@ -70,7 +72,14 @@ enum tp_policy {
 
 enum tp_dtype { TP_F32 = 0, TP_BF16 = 1 };
 enum tp_act { TP_ACT_NONE = 0, TP_ACT_RELU = 1, TP_ACT_GELU = 2 /* exact erf form */ };
-enum tp_layer_type { TP_LAYER_DENSE = 0 /* z = x W^T + b, a = act(z) */ };
+enum tp_layer_type {
+  TP_LAYER_DENSE = 0,    /* z = x W^T + b, a = act(z);  W[out x in]                                   */
+  TP_LAYER_CONV2D = 1,   /* 3x3 convolution, stride 1, zero padding 1, + bias + act, on NHWC activations:
+                            in_features = Cin, out_features = Cout, geom = {H, W, 3, 1, 1};
+                            W[Cout][3][3][Cin], b[Cout]; a sample is H*W*Cin values in, H*W*Cout out     */
+  TP_LAYER_MAXPOOL2 = 2  /* 2x2 max pooling, stride 2, no parameters: in_features = out_features = C,
+                            geom = {H, W} of the input (both even); first maximum wins ties             */
+};
 
 #define TP_MAX_LAYERS 32
 #define TP_NONE UINT64_MAX /* "no mini-batch" for stage_blend_update */
@@ -78,9 +87,10 @@ enum tp_layer_type { TP_LAYER_DENSE = 0 /* z = x W^T + b, a = act(z) */ };
 typedef struct tp_layer_desc {
   int32_t type;         /* tp_layer_type */
   int32_t act;          /* tp_act */
-  int32_t in_features;  /* columns of the layer input  */
-  int32_t out_features; /* columns of the layer output */
-  int32_t reserved[12]; /* must be zero */
+  int32_t in_features;  /* dense: columns of the layer input;  conv/pool: input channels  */
+  int32_t out_features; /* dense: columns of the layer output; conv/pool: output channels */
+  int32_t geom[5];      /* conv: {H, W, kernel, stride, pad}; pool: {H, W, 0, 0, 0}; dense: zeros */
+  int32_t reserved[7];  /* must be zero */
 } tp_layer_desc;
 
 typedef struct tp_stage_desc {
@@ -258,7 +268,8 @@ enum tp_kernel_class {
   TP_K_BLEND = 6,    /* intermediate weights on their own            */
   TP_K_LOSS = 7,     /* softmax cross-entropy                        */
   TP_K_COPY = 8,     /* device-to-device copies and conversions      */
-  TP_K_CLASSES = 9
+  TP_K_POOL = 9,     /* max pooling forward / backward               */
+  TP_K_CLASSES = 10
 };
 typedef struct tp_profile {
   uint64_t launches[TP_K_CLASSES];

@@ -36,7 +36,12 @@ class StageError(RuntimeError):
 
 class Stage:
     def __init__(self, layer_specs, params: List[np.ndarray], *, policy: str, lam: float,
-                 lr: float, momentum: float, n: int, first_stage: bool = False):
+                 lr: float, momentum: float, n: int, first_stage: bool = False, storage=None):
+        """storage: optional rounding (e.g. to bfloat16) applied wherever the workload keeps a tensor
+        in its activation type -- weight compute copies, layer outputs, propagated gradients -- while all
+        arithmetic stays fp64.  It puts decisions that hinge on stored values (which element of a
+        pooling window is the maximum) in the precision the workload prescribes; None keeps pure fp64."""
+        self.q = storage if storage is not None else (lambda a: a)
         self.specs = list(layer_specs)
         # position of each layer's weight in the flat parameter list (None: layer has no parameters)
         self.pidx, nxt = [], 0
@@ -76,7 +81,7 @@ class Stage:
             raise StageError("micro-batch index out of order")
         if self.policy != "latest" and rec["v_f"] != self.latest:
             raise StageError("update landed between micro-batches of one mini-batch")
-        W = self.weights[self.latest]
+        W = [self.q(p) if p.ndim > 1 else p for p in self.weights[self.latest]]   # compute copy
         rec["versions"].append(self.latest)
         saved = []
         a = np.asarray(x, dtype=np.float64)
@@ -93,7 +98,7 @@ class Stage:
             else:
                 z = L.dense_forward(a, W[pi], W[pi + 1])
             saved.append((a, z))
-            a = L.act_forward(z, spec.act)
+            a = self.q(L.act_forward(z, spec.act))
         rec["saved"].append(saved)
         return a
 
@@ -123,6 +128,7 @@ class Stage:
             raise StageError("backward needs all n micro-batch forwards of the mini-batch")
         W_b, (v_f, v_now, delta) = self.backward_weights(mb)
         self.last_W_b = W_b
+        W_b = [self.q(p) if p.ndim > 1 else p for p in W_b]                       # compute copy
         self.trace.append(("B", mb, v_f, v_now, delta))
         dy = np.asarray(dy, dtype=np.float64)
         rows = dy.shape[0] // self.n                       # samples per micro-batch
@@ -140,14 +146,14 @@ class Stage:
                     da = L.maxpool2_backward(da, idx, in_shape)
                     continue
                 x_in, z = saved[li]
-                dz = da * L.act_derivative(z, spec.act)
+                dz = self.q(da * L.act_derivative(z, spec.act))
                 if kind == "conv":
                     dW, db, da = L.conv2d_backward(dz, x_in, W_b[pi], spec.stride, spec.pad)
                 else:
                     dW, db, da = L.dense_backward(dz, x_in, W_b[pi])
                 g[pi] += dW
                 g[pi + 1] += db
-            dx_parts.append(da)
+            dx_parts.append(self.q(da))
         self.g = g
         # the intermediate weights are built: this mini-batch no longer needs its stale version
         if self.policy != "latest":

@@ -10,7 +10,7 @@ TP_OK, TP_EINVAL, TP_ESTATE, TP_ENOVERSION, TP_EFULL, TP_EBUSY, TP_EHIP = 0, -1,
 TP_LATEST, TP_INTERMEDIATE_EQ1, TP_INTERMEDIATE_CONVEX, TP_STASHED = 0, 1, 2, 3
 TP_F32, TP_BF16 = 0, 1
 TP_ACT_NONE, TP_ACT_RELU, TP_ACT_GELU = 0, 1, 2
-TP_LAYER_DENSE = 0
+TP_LAYER_DENSE, TP_LAYER_CONV2D, TP_LAYER_MAXPOOL2 = 0, 1, 2
 TP_MAX_LAYERS, TP_MAX_SLOTS, TP_MAX_IN_FLIGHT = 32, 16, 16
 TP_NONE = (1 << 64) - 1
 TP_DIAG_GRAD_SQ, TP_DIAG_WEIGHT_SQ, TP_DIAG_DRIFT_SQ, TP_DIAG_WB_SQ, TP_DIAG_COUNT = 0, 1, 2, 3, 4
@@ -27,7 +27,7 @@ EXPORTS = ["stage_workspace_query", "stage_init", "stage_destroy", "stage_forwar
 
 class tp_layer_desc(C.Structure):
     _fields_ = [("type", C.c_int32), ("act", C.c_int32), ("in_features", C.c_int32), ("out_features", C.c_int32),
-                ("reserved", C.c_int32 * 12)]
+                ("geom", C.c_int32 * 5), ("reserved", C.c_int32 * 7)]
 
 
 class tp_stage_desc(C.Structure):
@@ -63,11 +63,11 @@ class tp_event(C.Structure):
                 ("mb_id", C.c_uint64)]
 
 
-KERNEL_CLASSES = ["fprop", "dgrad", "wgrad", "colsum", "act_bwd", "update", "blend", "loss", "copy"]
+KERNEL_CLASSES = ["fprop", "dgrad", "wgrad", "colsum", "act_bwd", "update", "blend", "loss", "copy", "pool"]
 
 
 class tp_profile(C.Structure):
-    _fields_ = [("launches", C.c_uint64 * 9), ("ms", C.c_double * 9), ("dropped", C.c_uint64)]
+    _fields_ = [("launches", C.c_uint64 * 10), ("ms", C.c_double * 10), ("dropped", C.c_uint64)]
 
 
 class StageLibError(RuntimeError):
@@ -123,7 +123,8 @@ def _check(rc, soft=()):
 
 def make_desc(layers, *, dtype, mb, n, stage_index, num_stages, ring_capacity, max_in_flight, policy, needs_dx,
               lam, lr, momentum) -> tp_stage_desc:
-    """layers: sequence of (in_features, out_features, act-name)."""
+    """layers: sequence of (in_features, out_features, act-name) for dense layers,
+    ("conv", cin, cout, H, W, act-name) for 3x3/stride 1/pad 1 convolutions, ("pool", C, H, W) for 2x2 pooling."""
     d = tp_stage_desc()
     d.num_layers = len(layers)
     d.dtype = DTYPE[dtype] if isinstance(dtype, str) else dtype
@@ -133,11 +134,47 @@ def make_desc(layers, *, dtype, mb, n, stage_index, num_stages, ring_capacity, m
     d.policy = POLICY[policy] if isinstance(policy, str) else policy
     d.needs_dx = int(bool(needs_dx))
     d.lambda_, d.lr, d.momentum = lam, lr, momentum
-    for i, (fin, fout, act) in enumerate(layers[:TP_MAX_LAYERS]):
-        d.layers[i].type = TP_LAYER_DENSE
-        d.layers[i].act = ACT[act] if isinstance(act, str) else act
-        d.layers[i].in_features, d.layers[i].out_features = fin, fout
+    for i, spec in enumerate(layers[:TP_MAX_LAYERS]):
+        L = d.layers[i]
+        if spec[0] == "conv":
+            _, cin, cout, H, W, act = spec
+            L.type, L.in_features, L.out_features = TP_LAYER_CONV2D, cin, cout
+            L.geom[0], L.geom[1], L.geom[2], L.geom[3], L.geom[4] = H, W, 3, 1, 1
+        elif spec[0] == "pool":
+            _, c, H, W = spec
+            act = "none"
+            L.type, L.in_features, L.out_features = TP_LAYER_MAXPOOL2, c, c
+            L.geom[0], L.geom[1] = H, W
+        else:
+            fin, fout, act = spec
+            L.type, L.in_features, L.out_features = TP_LAYER_DENSE, fin, fout
+        L.act = ACT[act] if isinstance(act, str) else act
     return d
+
+
+def layer_in_elems(spec) -> int:
+    """Values per sample a layer takes in / gives out (same tuple format as make_desc)."""
+    if spec[0] == "conv":
+        return spec[3] * spec[4] * spec[1]
+    if spec[0] == "pool":
+        return spec[2] * spec[3] * spec[1]
+    return spec[0]
+
+
+def layer_out_elems(spec) -> int:
+    if spec[0] == "conv":
+        return spec[3] * spec[4] * spec[2]
+    if spec[0] == "pool":
+        return (spec[2] // 2) * (spec[3] // 2) * spec[1]
+    return spec[1]
+
+
+def layer_param_shapes(spec):
+    if spec[0] == "conv":
+        return [(spec[2], 3, 3, spec[1]), (spec[2],)]
+    if spec[0] == "pool":
+        return []
+    return [(spec[1], spec[0]), (spec[1],)]
 
 
 def stage_workspace_query(desc: tp_stage_desc) -> tp_sizes:

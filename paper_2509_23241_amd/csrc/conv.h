@@ -1,0 +1,29 @@
+// Launch interface of the convolution and pooling kernels (3x3, stride 1, pad 1; 2x2 max pool).
+// elt: 0 = fp32, 1 = bf16.  Activations are NHWC, [imgs*H*W x C] row-major; weights [Cout][3][3][Cin].
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tp {
+
+// a = act(conv(x, W) + bias), d = act'(.) (d_out may be null).  Outputs [imgs*H*W x cout].
+hipError_t launch_conv_fprop(hipStream_t s, int elt, int imgs, int H, int W, int cin, int cout, const void* x,
+                             const void* wgt, const float* bias, int act, void* d_out, void* a_out);
+
+// out = (transposed convolution of dz with W_b) (.) d_prev;  dz:[imgs*H*W x cout], out:[imgs*H*W x cin].
+hipError_t launch_conv_dgrad(hipStream_t s, int elt, int imgs, int H, int W, int cin, int cout, const void* dz,
+                             const void* wb, const void* d_prev, void* out);
+
+// gW[cout][3][3][cin] (fp32) = sum over pixels of dz (x) shifted x.
+// partial: scratch of conv_wgrad_scratch_floats(imgs*H*W, cin, cout) floats.
+hipError_t launch_conv_wgrad(hipStream_t s, int elt, int imgs, int H, int W, int cin, int cout, const void* dz,
+                             const void* x, float* gW, float* partial);
+size_t conv_wgrad_scratch_floats(int pixels, int cin, int cout);
+
+// y[imgs x H/2 x W/2 x C] = 2x2/2 max pooling of x[imgs x H x W x C];  backward recomputes the
+// position of the (first) maximum from the saved input x.
+hipError_t launch_maxpool_fwd(hipStream_t s, int elt, int imgs, int H, int W, int C, const void* x, void* y);
+hipError_t launch_maxpool_bwd(hipStream_t s, int elt, int imgs, int H, int W, int C, const void* x, const void* dy,
+                              void* dx);
+
+}  // namespace tp

@@ -1,0 +1,279 @@
+// 3x3 convolution (stride 1, zero padding 1) on NHWC activations as implicit GEMMs, and 2x2 max
+// pooling.  Weights are [Cout][3][3][Cin], i.e. a row-major [Cout x 9*Cin] matrix whose k index
+// runs over (tap, input channel), tap = 3*kh + kw.
+//
+//   fprop  z[p][co]  = sum_{tap,ci} x[shift(p,+tap)][ci] * W[co][tap][ci]        rows: output pixels
+//   dgrad  dx[p][ci] = sum_{tap,co} dz[shift(p,-tap)][co] * W_b[co][tap][ci]     rows: input pixels
+//   wgrad  dW[co][tap][ci] = sum_p dz[p][co] * x[shift(p,+tap)][ci]              contraction: pixels
+// shift(p, +tap) moves pixel p = (img, h, w) by (kh-1, kw-1); positions outside the image read 0.
+//
+// This file holds the shape-generic, bounds-checked SIMT kernel (fp32 FMA, LDS-tiled), used for
+// the fp32 mode, for channel counts the matrix-core kernels do not take (the 3-channel first
+// layer) and as their reference.  wgrad contracts over all pixels of the mini-batch, so it is
+// split over pixel ranges; a second kernel adds the partial results in a fixed order.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "conv.h"
+#include "device_utils.h"
+
+namespace tp {
+
+namespace {
+
+constexpr int BM = 64, BN = 64, BK = 16, kThreads = 256;
+
+struct ConvGeom {
+  int imgs, H, W, Cin, Cout;
+};
+
+__device__ __forceinline__ void pixel_of(int p, const ConvGeom& g, int& img, int& h, int& w) {
+  w = p % g.W;
+  const int t = p / g.W;
+  h = t % g.H;
+  img = t / g.H;
+}
+
+// PRODUCT: 0 fprop, 1 dgrad, 2 wgrad (partial sums over the pixel range of blockIdx.z)
+template <typename T, int PRODUCT>
+__global__ __launch_bounds__(kThreads) void conv_simt_kernel(ConvGeom g, const T* __restrict__ act_in,
+                                                             const T* __restrict__ wgt_or_dz, const float* __restrict__ bias,
+                                                             int act, const T* __restrict__ d_prev, T* __restrict__ d_out,
+                                                             T* __restrict__ out, float* __restrict__ partial,
+                                                             int pixels_per_split) {
+  __shared__ float As[BK][BM + 4];
+  __shared__ float Bs[BK][BN + 4];
+  const int P = g.imgs * g.H * g.W;
+  const int M = PRODUCT == 2 ? g.Cout : P;
+  const int N = PRODUCT == 0 ? g.Cout : (PRODUCT == 1 ? g.Cin : 9 * g.Cin);
+  const int Kfull = PRODUCT == 0 ? 9 * g.Cin : (PRODUCT == 1 ? 9 * g.Cout : P);
+  const int kbeg = PRODUCT == 2 ? blockIdx.z * pixels_per_split : 0;
+  const int kend = PRODUCT == 2 ? min(P, kbeg + pixels_per_split) : Kfull;
+  const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+
+  // A(m, k) and B(k, n) of the three products
+  auto fetch_a = [&](int m, int k) -> float {
+    if (m >= M || k >= kend) return 0.f;
+    if (PRODUCT == 2) return to_float(wgt_or_dz[(size_t)k * g.Cout + m]);  // dz[p][co]
+    const int C = PRODUCT == 0 ? g.Cin : g.Cout;
+    const int tap = k / C, c = k % C;
+    int img, h, w;
+    pixel_of(m, g, img, h, w);
+    const int dh = tap / 3 - 1, dw = tap % 3 - 1;
+    const int sh = PRODUCT == 0 ? h + dh : h - dh, sw = PRODUCT == 0 ? w + dw : w - dw;
+    if (sh < 0 || sh >= g.H || sw < 0 || sw >= g.W) return 0.f;
+    return to_float(act_in[((size_t)(img * g.H + sh) * g.W + sw) * C + c]);
+  };
+  auto fetch_b = [&](int k, int n) -> float {
+    if (n >= N || k >= kend) return 0.f;
+    if (PRODUCT == 0) return to_float(wgt_or_dz[(size_t)n * (9 * g.Cin) + k]);  // W[co][k]
+    if (PRODUCT == 1) {
+      const int tap = k / g.Cout, co = k % g.Cout;
+      return to_float(wgt_or_dz[(size_t)co * (9 * g.Cin) + tap * g.Cin + n]);   // W_b[co][tap][ci]
+    }
+    const int tap = n / g.Cin, c = n % g.Cin;
+    int img, h, w;
+    pixel_of(k, g, img, h, w);
+    const int sh = h + tap / 3 - 1, sw = w + tap % 3 - 1;
+    if (sh < 0 || sh >= g.H || sw < 0 || sw >= g.W) return 0.f;
+    return to_float(act_in[((size_t)(img * g.H + sh) * g.W + sw) * g.Cin + c]);
+  };
+
+  float acc[4][4] = {};
+  for (int k0 = kbeg; k0 < kend; k0 += BK) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int el = t + i * kThreads;
+      // thread -> element so that consecutive threads read consecutive addresses of each operand
+      int am, ak, bn, bk;
+      if (PRODUCT == 2) { am = el & (BM - 1); ak = el >> 6; } else { ak = el & (BK - 1); am = el >> 4; }
+      if (PRODUCT == 0) { bk = el & (BK - 1); bn = el >> 4; } else { bn = el & (BN - 1); bk = el >> 6; }
+      As[ak][am] = fetch_a(m0 + am, k0 + ak);
+      Bs[bk][bn] = fetch_b(k0 + bk, n0 + bn);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < BK; ++k) {
+      const float4 a = *reinterpret_cast<const float4*>(&As[k][ty * 4]);
+      const float4 b = *reinterpret_cast<const float4*>(&Bs[k][tx * 4]);
+      const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + ty * 4 + i;
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + tx * 4 + j;
+      if (n >= N) continue;
+      const size_t idx = (size_t)m * N + n;
+      float v = acc[i][j];
+      if (PRODUCT == 0) {
+        v += bias[n];
+        if (d_out) d_out[idx] = from_float<T>(act_derivative(v, act));
+        out[idx] = from_float<T>(act_forward(v, act));
+      } else if (PRODUCT == 1) {
+        if (d_prev) v *= to_float(d_prev[idx]);
+        out[idx] = from_float<T>(v);
+      } else {
+        partial[(size_t)blockIdx.z * M * N + idx] = v;
+      }
+    }
+  }
+}
+
+// out[i] = sum over splits of partial[s][i], fixed order
+__global__ __launch_bounds__(kThreads) void split_sum_kernel(size_t count, int splits, const float* __restrict__ partial,
+                                                             float* __restrict__ out) {
+  const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= count) return;
+  float s = 0.f;
+#pragma unroll 8
+  for (int z = 0; z < splits; ++z) s += partial[(size_t)z * count + i];
+  out[i] = s;
+}
+
+// 2x2 max pooling, stride 2, NHWC; first maximum in row-major window order wins ties.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void maxpool_fwd_kernel(int imgs, int H, int W, int C, const T* __restrict__ x,
+                                                               T* __restrict__ y) {
+  const size_t total = (size_t)imgs * (H / 2) * (W / 2) * C;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (size_t)gridDim.x * kThreads) {
+    const int c = i % C;
+    size_t t = i / C;
+    const int ow = t % (W / 2);
+    t /= (W / 2);
+    const int oh = t % (H / 2);
+    const int img = t / (H / 2);
+    const T* p = x + (((size_t)img * H + 2 * oh) * W + 2 * ow) * C + c;
+    float m = to_float(p[0]);
+    m = fmaxf(m, to_float(p[C]));
+    m = fmaxf(m, to_float(p[(size_t)W * C]));
+    m = fmaxf(m, to_float(p[(size_t)W * C + C]));
+    y[i] = from_float<T>(m);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void maxpool_bwd_kernel(int imgs, int H, int W, int C, const T* __restrict__ x,
+                                                               const T* __restrict__ dy, T* __restrict__ dx) {
+  const size_t total = (size_t)imgs * (H / 2) * (W / 2) * C;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (size_t)gridDim.x * kThreads) {
+    const int c = i % C;
+    size_t t = i / C;
+    const int ow = t % (W / 2);
+    t /= (W / 2);
+    const int oh = t % (H / 2);
+    const int img = t / (H / 2);
+    const size_t base = (((size_t)img * H + 2 * oh) * W + 2 * ow) * C + c;
+    const size_t off[4] = {0, (size_t)C, (size_t)W * C, (size_t)W * C + C};
+    float best = to_float(x[base]);
+    int arg = 0;
+#pragma unroll
+    for (int q = 1; q < 4; ++q) {
+      const float v = to_float(x[base + off[q]]);
+      if (v > best) { best = v; arg = q; }
+    }
+    const T g = dy[i], zero = from_float<T>(0.f);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) dx[base + off[q]] = q == arg ? g : zero;
+  }
+}
+
+inline int stream_blocks(size_t items, int max_blocks) {
+  size_t b = (items + kThreads - 1) / kThreads;
+  return (int)(b < 1 ? 1 : (b < (size_t)max_blocks ? b : (size_t)max_blocks));
+}
+
+}  // namespace
+
+int conv_wgrad_splits(int pixels) {
+  // enough pixel ranges to fill the chip even when dW has only a handful of tiles
+  int s = (pixels + 2047) / 2048;
+  return s < 1 ? 1 : (s > 256 ? 256 : s);
+}
+
+size_t conv_wgrad_scratch_floats(int pixels, int cin, int cout) {
+  return (size_t)conv_wgrad_splits(pixels) * cout * 9 * cin;
+}
+
+hipError_t launch_conv_fprop(hipStream_t s, int elt, int imgs, int H, int W, int cin, int cout, const void* x,
+                             const void* wgt, const float* bias, int act, void* d_out, void* a_out) {
+  const ConvGeom g{imgs, H, W, cin, cout};
+  const int P = imgs * H * W;
+  dim3 grid((cout + BN - 1) / BN, (P + BM - 1) / BM);
+  if (elt == 1)
+    hipLaunchKernelGGL((conv_simt_kernel<uint16_t, 0>), grid, dim3(kThreads), 0, s, g, (const uint16_t*)x, (const uint16_t*)wgt,
+                       bias, act, (const uint16_t*)nullptr, (uint16_t*)d_out, (uint16_t*)a_out, (float*)nullptr, 0);
+  else
+    hipLaunchKernelGGL((conv_simt_kernel<float, 0>), grid, dim3(kThreads), 0, s, g, (const float*)x, (const float*)wgt, bias,
+                       act, (const float*)nullptr, (float*)d_out, (float*)a_out, (float*)nullptr, 0);
+  return hipGetLastError();
+}
+
+hipError_t launch_conv_dgrad(hipStream_t s, int elt, int imgs, int H, int W, int cin, int cout, const void* dz,
+                             const void* wb, const void* d_prev, void* out) {
+  const ConvGeom g{imgs, H, W, cin, cout};
+  const int P = imgs * H * W;
+  dim3 grid((cin + BN - 1) / BN, (P + BM - 1) / BM);
+  if (elt == 1)
+    hipLaunchKernelGGL((conv_simt_kernel<uint16_t, 1>), grid, dim3(kThreads), 0, s, g, (const uint16_t*)dz, (const uint16_t*)wb,
+                       (const float*)nullptr, 0, (const uint16_t*)d_prev, (uint16_t*)nullptr, (uint16_t*)out, (float*)nullptr, 0);
+  else
+    hipLaunchKernelGGL((conv_simt_kernel<float, 1>), grid, dim3(kThreads), 0, s, g, (const float*)dz, (const float*)wb,
+                       (const float*)nullptr, 0, (const float*)d_prev, (float*)nullptr, (float*)out, (float*)nullptr, 0);
+  return hipGetLastError();
+}
+
+hipError_t launch_conv_wgrad(hipStream_t s, int elt, int imgs, int H, int W, int cin, int cout, const void* dz,
+                             const void* x, float* gW, float* partial) {
+  const ConvGeom g{imgs, H, W, cin, cout};
+  const int P = imgs * H * W;
+  const int splits = conv_wgrad_splits(P);
+  const int per = ((P + splits - 1) / splits + BK - 1) / BK * BK;
+  dim3 grid((9 * cin + BN - 1) / BN, (cout + BM - 1) / BM, splits);
+  if (elt == 1)
+    hipLaunchKernelGGL((conv_simt_kernel<uint16_t, 2>), grid, dim3(kThreads), 0, s, g, (const uint16_t*)x, (const uint16_t*)dz,
+                       (const float*)nullptr, 0, (const uint16_t*)nullptr, (uint16_t*)nullptr, (uint16_t*)nullptr, partial, per);
+  else
+    hipLaunchKernelGGL((conv_simt_kernel<float, 2>), grid, dim3(kThreads), 0, s, g, (const float*)x, (const float*)dz,
+                       (const float*)nullptr, 0, (const float*)nullptr, (float*)nullptr, (float*)nullptr, partial, per);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const size_t count = (size_t)cout * 9 * cin;
+  hipLaunchKernelGGL(split_sum_kernel, dim3((unsigned)((count + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, count,
+                     splits, partial, gW);
+  return hipGetLastError();
+}
+
+hipError_t launch_maxpool_fwd(hipStream_t s, int elt, int imgs, int H, int W, int C, const void* x, void* y) {
+  const size_t total = (size_t)imgs * (H / 2) * (W / 2) * C;
+  const int blocks = stream_blocks(total, 8192);
+  if (elt == 1)
+    hipLaunchKernelGGL(maxpool_fwd_kernel<uint16_t>, dim3(blocks), dim3(kThreads), 0, s, imgs, H, W, C, (const uint16_t*)x, (uint16_t*)y);
+  else
+    hipLaunchKernelGGL(maxpool_fwd_kernel<float>, dim3(blocks), dim3(kThreads), 0, s, imgs, H, W, C, (const float*)x, (float*)y);
+  return hipGetLastError();
+}
+
+hipError_t launch_maxpool_bwd(hipStream_t s, int elt, int imgs, int H, int W, int C, const void* x, const void* dy,
+                              void* dx) {
+  const size_t total = (size_t)imgs * (H / 2) * (W / 2) * C;
+  const int blocks = stream_blocks(total, 8192);
+  if (elt == 1)
+    hipLaunchKernelGGL(maxpool_bwd_kernel<uint16_t>, dim3(blocks), dim3(kThreads), 0, s, imgs, H, W, C, (const uint16_t*)x,
+                       (const uint16_t*)dy, (uint16_t*)dx);
+  else
+    hipLaunchKernelGGL(maxpool_bwd_kernel<float>, dim3(blocks), dim3(kThreads), 0, s, imgs, H, W, C, (const float*)x,
+                       (const float*)dy, (float*)dx);
+  return hipGetLastError();
+}
+
+}  // namespace tp

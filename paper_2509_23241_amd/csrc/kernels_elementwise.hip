@@ -176,9 +176,10 @@ __global__ __launch_bounds__(kThreads) void convert_kernel(size_t n4, const floa
 }
 
 // dz = dy (.) d, 16 bytes per lane per step; `count` elements, the tail element-wise.
+// dz may be the same buffer as dy (every element is read before it is written by the same lane).
 template <typename T>
-__global__ __launch_bounds__(kThreads) void act_backward_kernel(size_t count, const T* __restrict__ dy,
-                                                                const T* __restrict__ d, T* __restrict__ dz) {
+__global__ __launch_bounds__(kThreads) void act_backward_kernel(size_t count, const T* dy, const T* __restrict__ d,
+                                                                T* dz) {
   constexpr int V = 16 / sizeof(T);
   const size_t nvec = count / V;
   const size_t stride = (size_t)gridDim.x * kThreads;

@@ -7,6 +7,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 #include "device_utils.h"
 #include "gemm_mfma.h"
 #include "kernels.h"
@@ -107,25 +109,44 @@ hipError_t simt(hipStream_t s, int elt, int M, int N, int K, const void* A, long
 }
 
 // Column sums of dz[M x N] in two fixed-order steps: row chunks -> partials[chunk][N] -> gb[N].
-// A lane owns V = 16/sizeof(T) adjacent columns (one 16-byte load per row); the four waves of a
-// block take every fourth row of the chunk and are combined through LDS in a fixed order.
-constexpr int kColChunkRows = 32;
+// A lane owns V = 16/sizeof(T) adjacent columns (one 16-byte load per row).  A block covers up
+// to 64*V columns; when the matrix is narrower, the spare lanes take other rows, so tall and
+// skinny matrices (convolution: rows = all pixels) still use every lane.  The row groups of a
+// block are combined through LDS in a fixed order.
+struct ColsumShape {
+  int lanes_per_row;  // power of two <= 64
+  int rows_per_iter;  // kThreads / lanes_per_row
+  int col_blocks, chunk_rows, chunks;
+};
+
+inline ColsumShape colsum_shape(int M, int N, int V) {
+  ColsumShape c;
+  const int need = (std::min(N, 64 * V) + V - 1) / V;
+  c.lanes_per_row = 1;
+  while (c.lanes_per_row < need) c.lanes_per_row *= 2;
+  c.rows_per_iter = kThreads / c.lanes_per_row;
+  c.col_blocks = (N + c.lanes_per_row * V - 1) / (c.lanes_per_row * V);
+  const int target_chunks = std::max(1, 1024 / c.col_blocks);
+  c.chunk_rows = std::max(c.rows_per_iter * 2, (M + target_chunks - 1) / target_chunks);
+  c.chunks = (M + c.chunk_rows - 1) / c.chunk_rows;
+  return c;
+}
 
 template <typename T>
-__global__ __launch_bounds__(kThreads) void colsum_partial_kernel(int M, int N, const T* __restrict__ dz,
+__global__ __launch_bounds__(kThreads) void colsum_partial_kernel(int M, int N, ColsumShape cs, const T* __restrict__ dz,
                                                                   float* __restrict__ partials) {
   constexpr int V = 16 / sizeof(T);
-  __shared__ float sm[4][64 * V];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int col = (blockIdx.x * 64 + lane) * V;
-  const int r0 = blockIdx.y * kColChunkRows;
-  const int r1 = min(M, r0 + kColChunkRows);
+  __shared__ float sm[kThreads * V];
+  const int lr = threadIdx.x % cs.lanes_per_row, rsub = threadIdx.x / cs.lanes_per_row;
+  const int col = (blockIdx.x * cs.lanes_per_row + lr) * V;
+  const int r0 = blockIdx.y * cs.chunk_rows;
+  const int r1 = min(M, r0 + cs.chunk_rows);
   float s[V];
 #pragma unroll
   for (int j = 0; j < V; ++j) s[j] = 0.f;
   if (col + V <= N && (N % V) == 0) {
-#pragma unroll 8
-    for (int r = r0 + wave; r < r1; r += 4) {
+#pragma unroll 4
+    for (int r = r0 + rsub; r < r1; r += cs.rows_per_iter) {
       const uint4 v = *reinterpret_cast<const uint4*>(dz + (size_t)r * N + col);
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
       if (sizeof(T) == 2) {
@@ -140,19 +161,20 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(int M, int N, 
       }
     }
   } else {
-    for (int r = r0 + wave; r < r1; r += 4)
+    for (int r = r0 + rsub; r < r1; r += cs.rows_per_iter)
       for (int j = 0; j < V; ++j)
         if (col + j < N) s[j] += to_float(dz[(size_t)r * N + col + j]);
   }
 #pragma unroll
-  for (int j = 0; j < V; ++j) sm[wave][lane * V + j] = s[j];
+  for (int j = 0; j < V; ++j) sm[(rsub * cs.lanes_per_row + lr) * V + j] = s[j];
   __syncthreads();
-  if (wave == 0) {
-    for (int j = 0; j < V; ++j)
-      if (col + j < N) {
-        const int c = lane * V + j;
-        partials[(size_t)blockIdx.y * N + col + j] = (sm[0][c] + sm[1][c]) + (sm[2][c] + sm[3][c]);
-      }
+  if (rsub == 0) {
+    for (int j = 0; j < V; ++j) {
+      if (col + j >= N) continue;
+      float t = 0.f;
+      for (int q = 0; q < cs.rows_per_iter; ++q) t += sm[(q * cs.lanes_per_row + lr) * V + j];
+      partials[(size_t)blockIdx.y * N + col + j] = t;
+    }
   }
 }
 
@@ -169,7 +191,8 @@ __global__ __launch_bounds__(kThreads) void colsum_final_kernel(int chunks, int 
 }  // namespace
 
 size_t colsum_scratch_floats(int M, int N) {
-  return (size_t)((M + kColChunkRows - 1) / kColChunkRows) * (size_t)N;
+  // the fp32 shape has the fewer columns per block, hence the more chunks: size for it
+  return (size_t)std::max(colsum_shape(M, N, 4).chunks, colsum_shape(M, N, 8).chunks) * (size_t)N;
 }
 
 hipError_t launch_fprop(hipStream_t s, int elt, int M, int N, int K, const void* x, const void* W, const float* bias,
@@ -201,16 +224,15 @@ hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void*
 }
 
 hipError_t launch_colsum(hipStream_t s, int elt, int M, int N, const void* dz, float* gb, float* partials) {
-  const int chunks = (M + kColChunkRows - 1) / kColChunkRows;
-  const int per_block = 64 * (elt == ELT_BF16 ? 8 : 4);
-  dim3 g1((N + per_block - 1) / per_block, chunks);
+  const ColsumShape cs = colsum_shape(M, N, elt == ELT_BF16 ? 8 : 4);
+  dim3 g1(cs.col_blocks, cs.chunks);
   if (elt == ELT_BF16)
-    hipLaunchKernelGGL(colsum_partial_kernel<uint16_t>, g1, dim3(kThreads), 0, s, M, N, (const uint16_t*)dz, partials);
+    hipLaunchKernelGGL(colsum_partial_kernel<uint16_t>, g1, dim3(kThreads), 0, s, M, N, cs, (const uint16_t*)dz, partials);
   else
-    hipLaunchKernelGGL(colsum_partial_kernel<float>, g1, dim3(kThreads), 0, s, M, N, (const float*)dz, partials);
+    hipLaunchKernelGGL(colsum_partial_kernel<float>, g1, dim3(kThreads), 0, s, M, N, cs, (const float*)dz, partials);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  hipLaunchKernelGGL(colsum_final_kernel, dim3((N + kThreads - 1) / kThreads), dim3(kThreads), 0, s, chunks, N, partials, gb);
+  hipLaunchKernelGGL(colsum_final_kernel, dim3((N + kThreads - 1) / kThreads), dim3(kThreads), 0, s, cs.chunks, N, partials, gb);
   return hipGetLastError();
 }
 

@@ -15,6 +15,7 @@
 #include <new>
 #include <vector>
 
+#include "conv.h"
 #include "kernels.h"
 
 namespace {
@@ -33,6 +34,8 @@ inline uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
 struct LayerPlan {
   tp_layer_desc d;
+  uint64_t in_elems, out_elems;  // values per sample in / out
+  uint64_t w_elems;              // elements of the weight tensor (0: no parameters)
   uint64_t w_off, b_off;  // elements inside one weight version
   uint64_t x_off, z_off;  // bytes inside one activation slot; z_off: saved act'(z) (UINT64_MAX: none)
 };
@@ -76,15 +79,39 @@ int check_desc(const tp_stage_desc* d) {
   if (d->policy < TP_LATEST || d->policy > TP_STASHED) return fail(TP_EINVAL, "unknown policy %d", d->policy);
   if (!(d->lambda > 0.0) || !std::isfinite(d->lambda)) return fail(TP_EINVAL, "lambda must be > 0");
   if (!std::isfinite(d->lr) || !std::isfinite(d->momentum)) return fail(TP_EINVAL, "lr/momentum not finite");
+  uint64_t prev_out = 0;
   for (int l = 0; l < d->num_layers; ++l) {
     const tp_layer_desc& L = d->layers[l];
-    if (L.type != TP_LAYER_DENSE) return fail(TP_EINVAL, "layer %d: unknown type %d", l, L.type);
     if (L.act < TP_ACT_NONE || L.act > TP_ACT_GELU) return fail(TP_EINVAL, "layer %d: unknown activation", l);
     if (L.in_features < 1 || L.out_features < 1) return fail(TP_EINVAL, "layer %d: empty shape", l);
-    if (l > 0 && d->layers[l - 1].out_features != L.in_features)
-      return fail(TP_EINVAL, "layer %d: input %d does not match previous output %d", l, L.in_features,
-                  d->layers[l - 1].out_features);
-    for (int r = 0; r < 12; ++r)
+    uint64_t in_e, out_e;
+    if (L.type == TP_LAYER_DENSE) {
+      for (int r = 0; r < 5; ++r)
+        if (L.geom[r] != 0) return fail(TP_EINVAL, "layer %d: geometry fields must be zero for a dense layer", l);
+      in_e = L.in_features;
+      out_e = L.out_features;
+    } else if (L.type == TP_LAYER_CONV2D) {
+      if (L.geom[0] < 1 || L.geom[1] < 1) return fail(TP_EINVAL, "layer %d: empty image", l);
+      if (L.geom[2] != 3 || L.geom[3] != 1 || L.geom[4] != 1)
+        return fail(TP_EINVAL, "layer %d: only 3x3 / stride 1 / pad 1 convolutions are built", l);
+      in_e = (uint64_t)L.geom[0] * L.geom[1] * L.in_features;
+      out_e = (uint64_t)L.geom[0] * L.geom[1] * L.out_features;
+    } else if (L.type == TP_LAYER_MAXPOOL2) {
+      if (L.geom[0] < 2 || L.geom[1] < 2 || (L.geom[0] & 1) || (L.geom[1] & 1))
+        return fail(TP_EINVAL, "layer %d: pooling needs even height and width", l);
+      if (L.in_features != L.out_features || L.act != TP_ACT_NONE || L.geom[2] || L.geom[3] || L.geom[4])
+        return fail(TP_EINVAL, "layer %d: malformed pooling layer", l);
+      in_e = (uint64_t)L.geom[0] * L.geom[1] * L.in_features;
+      out_e = in_e / 4;
+    } else {
+      return fail(TP_EINVAL, "layer %d: unknown type %d", l, L.type);
+    }
+    if (in_e > (1u << 30) || out_e > (1u << 30)) return fail(TP_EINVAL, "layer %d: sample too large", l);
+    if (l > 0 && prev_out != in_e)
+      return fail(TP_EINVAL, "layer %d: input of %llu values does not match previous output of %llu", l,
+                  (unsigned long long)in_e, (unsigned long long)prev_out);
+    prev_out = out_e;
+    for (int r = 0; r < 7; ++r)
       if (L.reserved[r] != 0) return fail(TP_EINVAL, "layer %d: reserved fields must be zero", l);
   }
   return TP_OK;
@@ -97,22 +124,42 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
   const uint64_t rows = (uint64_t)d->mb * d->n;
   std::memset(&p->sizes, 0, sizeof(p->sizes));
   uint64_t off = 0, act = 0, max_feat = 0;
+  uint64_t conv_scratch = 0;
   for (int l = 0; l < d->num_layers; ++l) {
     LayerPlan lp;
     lp.d = d->layers[l];
+    const tp_layer_desc& L = lp.d;
+    if (L.type == TP_LAYER_DENSE) {
+      lp.in_elems = L.in_features;
+      lp.out_elems = L.out_features;
+      lp.w_elems = (uint64_t)L.in_features * L.out_features;
+    } else if (L.type == TP_LAYER_CONV2D) {
+      lp.in_elems = (uint64_t)L.geom[0] * L.geom[1] * L.in_features;
+      lp.out_elems = (uint64_t)L.geom[0] * L.geom[1] * L.out_features;
+      lp.w_elems = (uint64_t)L.out_features * 9 * L.in_features;
+      conv_scratch = std::max<uint64_t>(conv_scratch, tp::conv_wgrad_scratch_floats((int)(rows * L.geom[0] * L.geom[1]),
+                                                                                    L.in_features, L.out_features));
+    } else {
+      lp.in_elems = (uint64_t)L.geom[0] * L.geom[1] * L.in_features;
+      lp.out_elems = lp.in_elems / 4;
+      lp.w_elems = 0;
+    }
     lp.w_off = off;
-    off += round_up((uint64_t)lp.d.in_features * lp.d.out_features, 64);
     lp.b_off = off;
-    off += round_up((uint64_t)lp.d.out_features, 64);
+    if (lp.w_elems) {
+      off += round_up(lp.w_elems, 64);
+      lp.b_off = off;
+      off += round_up((uint64_t)L.out_features, 64);
+    }
     lp.x_off = act;
-    act += round_up(rows * lp.d.in_features * p->elt_size, 256);
-    if (lp.d.act != TP_ACT_NONE) {
+    act += round_up(rows * lp.in_elems * p->elt_size, 256);
+    if (L.act != TP_ACT_NONE) {
       lp.z_off = act;
-      act += round_up(rows * lp.d.out_features * p->elt_size, 256);
+      act += round_up(rows * lp.out_elems * p->elt_size, 256);
     } else {
       lp.z_off = UINT64_MAX;
     }
-    max_feat = std::max<uint64_t>(max_feat, std::max(lp.d.in_features, lp.d.out_features));
+    max_feat = std::max<uint64_t>(max_feat, std::max(lp.in_elems, lp.out_elems));
     p->sizes.w_offset[l] = lp.w_off;
     p->sizes.b_offset[l] = lp.b_off;
     p->layers.push_back(lp);
@@ -121,9 +168,13 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
   p->act_slot_bytes = act;
   p->dz_bytes = round_up(rows * max_feat * p->elt_size, 256);
   uint64_t wg = 0;
-  for (const LayerPlan& lp : p->layers)
-    wg = std::max<uint64_t>(wg, tp::colsum_scratch_floats((int)rows, lp.d.out_features));
-  p->partial_floats = round_up(std::max<uint64_t>({wg, tp::update_scratch_floats(), rows}), 64);
+  for (const LayerPlan& lp : p->layers) {
+    if (!lp.w_elems) continue;
+    // bias gradients: column sums over rows (dense) or over all pixels (conv)
+    const uint64_t r = lp.d.type == TP_LAYER_CONV2D ? rows * lp.d.geom[0] * lp.d.geom[1] : rows;
+    wg = std::max<uint64_t>(wg, tp::colsum_scratch_floats((int)r, lp.d.out_features));
+  }
+  p->partial_floats = round_up(std::max<uint64_t>({wg, tp::update_scratch_floats(), rows, conv_scratch}), 64);
   tp_sizes& s = p->sizes;
   s.param_count = P;
   s.ring_bytes = (uint64_t)d->ring_capacity * P * 4;
@@ -367,7 +418,7 @@ int stage_input_ptr(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, void** x_dev)
   }
   const LayerPlan& l0 = st->plan.layers[0];
   *x_dev = st->dry ? nullptr
-                   : st->act_slot(q) + l0.x_off + (uint64_t)ub_idx * st->desc.mb * l0.d.in_features * st->plan.elt_size;
+                   : st->act_slot(q) + l0.x_off + (uint64_t)ub_idx * st->desc.mb * l0.in_elems * st->plan.elt_size;
   return TP_OK;
 }
 
@@ -412,17 +463,33 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
   const int L = d.num_layers;
   for (int l = 0; l < L; ++l) {
     const LayerPlan& lp = st->plan.layers[l];
-    char* x_saved = aslot + lp.x_off + row0 * lp.d.in_features * es;
+    char* x_saved = aslot + lp.x_off + row0 * lp.in_elems * es;
     // a micro-batch that did not arrive in its workspace slot is copied there by its first GEMM
     const bool need_copy = l == 0 && x_dev != (const void*)x_saved;
     const void* x_in = need_copy ? x_dev : (const void*)x_saved;
-    void* z_out = lp.z_off == UINT64_MAX ? nullptr : aslot + lp.z_off + row0 * lp.d.out_features * es;
-    void* a_out = (l == L - 1) ? y_dev
-                               : (void*)(aslot + st->plan.layers[l + 1].x_off + row0 * lp.d.out_features * es);
-    ProfScope ps(st, TP_K_FPROP);
-    HIP_TRY(tp::launch_fprop(st->stream, d.dtype, d.mb, lp.d.out_features, lp.d.in_features, x_in,
-                             wcopy + lp.w_off * es, master + lp.b_off, lp.d.act, z_out, a_out,
-                             need_copy ? x_saved : nullptr));
+    void* z_out = lp.z_off == UINT64_MAX ? nullptr : aslot + lp.z_off + row0 * lp.out_elems * es;
+    void* a_out = (l == L - 1) ? y_dev : (void*)(aslot + st->plan.layers[l + 1].x_off + row0 * lp.out_elems * es);
+    if (lp.d.type == TP_LAYER_DENSE) {
+      ProfScope ps(st, TP_K_FPROP);
+      HIP_TRY(tp::launch_fprop(st->stream, d.dtype, d.mb, lp.d.out_features, lp.d.in_features, x_in,
+                               wcopy + lp.w_off * es, master + lp.b_off, lp.d.act, z_out, a_out,
+                               need_copy ? x_saved : nullptr));
+      continue;
+    }
+    if (need_copy) {
+      ProfScope ps(st, TP_K_COPY);
+      HIP_TRY(tp::launch_copy(st->stream, x_dev, x_saved, (size_t)d.mb * lp.in_elems * es));
+    }
+    if (lp.d.type == TP_LAYER_CONV2D) {
+      ProfScope ps(st, TP_K_FPROP);
+      HIP_TRY(tp::launch_conv_fprop(st->stream, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features,
+                                    lp.d.out_features, x_saved, wcopy + lp.w_off * es, master + lp.b_off, lp.d.act,
+                                    z_out, a_out));
+    } else {
+      ProfScope ps(st, TP_K_POOL);
+      HIP_TRY(tp::launch_maxpool_fwd(st->stream, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, x_saved,
+                                     a_out));
+    }
   }
   return TP_OK;
 }
@@ -436,6 +503,7 @@ int stage_loss_softmax_ce(tp_stage* st, uint64_t mb_id, const void* logits_dev, 
   if (st->dry) return TP_OK;
   if (!logits_dev || !labels_dev || !dlogits_dev || !loss_dev) return fail(TP_EINVAL, "null pointer");
   const int rows = st->desc.mb * st->desc.n;
+  if (st->plan.layers.back().d.type != TP_LAYER_DENSE) return fail(TP_EINVAL, "the loss needs a dense last layer");
   const int classes = st->plan.layers.back().d.out_features;
   ProfScope ps(st, TP_K_LOSS);
   HIP_TRY(tp::launch_softmax_ce(st->stream, st->desc.dtype, rows, classes, logits_dev, labels_dev, dlogits_dev,
@@ -484,7 +552,7 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
     const int L = d.num_layers;
     char* aslot = st->act_slot(f->act_slot);
     float* g = (float*)st->bufs.grad_dev;
-    const void* dz = nullptr;
+    const void* dz = nullptr;  // gradient w.r.t. the pre-activation output of layer l (or pooled output)
     int pp = 0;
     {
       const LayerPlan& last = st->plan.layers[L - 1];
@@ -492,35 +560,62 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
         dz = dy_dev;
       } else {
         ProfScope ps(st, TP_K_ACT_BWD);
-        HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * last.d.out_features, dy_dev, aslot + last.z_off, st->dz_buf(pp)));
+        HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * last.out_elems, dy_dev, aslot + last.z_off, st->dz_buf(pp)));
         dz = st->dz_buf(pp);
         pp ^= 1;
       }
     }
     for (int l = L - 1; l >= 0; --l) {
       const LayerPlan& lp = st->plan.layers[l];
+      // where the gradient w.r.t. this layer's input goes, and what it is multiplied with on the way
+      const bool to_caller = l == 0;
+      if (to_caller && !d.needs_dx && lp.d.type == TP_LAYER_MAXPOOL2) break;
+      const void* dprev = nullptr;
+      if (l > 0) {
+        const LayerPlan& prev = st->plan.layers[l - 1];
+        dprev = prev.z_off == UINT64_MAX ? nullptr : aslot + prev.z_off;
+      }
+      void* dst = to_caller ? dx_dev : (void*)st->dz_buf(pp);
+      if (lp.d.type == TP_LAYER_MAXPOOL2) {
+        {
+          ProfScope ps(st, TP_K_POOL);
+          HIP_TRY(tp::launch_maxpool_bwd(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features,
+                                         aslot + lp.x_off, dz, dst));
+        }
+        if (dprev) {  // the layer before the pool has an activation: dz_prev = dx_pool (.) act'
+          ProfScope ps(st, TP_K_ACT_BWD);
+          HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * lp.in_elems, dst, dprev, dst));
+        }
+        dz = dst;
+        if (!to_caller) pp ^= 1;
+        continue;
+      }
+      const int grad_rows = lp.d.type == TP_LAYER_CONV2D ? rows * lp.d.geom[0] * lp.d.geom[1] : rows;
       {
         ProfScope ps(st, TP_K_COLSUM);
-        HIP_TRY(tp::launch_colsum(st->stream, d.dtype, rows, lp.d.out_features, dz, g + lp.b_off, st->partials()));
+        HIP_TRY(tp::launch_colsum(st->stream, d.dtype, grad_rows, lp.d.out_features, dz, g + lp.b_off, st->partials()));
       }
       {
         ProfScope ps(st, TP_K_WGRAD);
-        HIP_TRY(tp::launch_wgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, aslot + lp.x_off,
-                                 g + lp.w_off));
+        if (lp.d.type == TP_LAYER_DENSE)
+          HIP_TRY(tp::launch_wgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, aslot + lp.x_off,
+                                   g + lp.w_off));
+        else
+          HIP_TRY(tp::launch_conv_wgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features,
+                                        lp.d.out_features, dz, aslot + lp.x_off, g + lp.w_off, st->partials()));
       }
-      if (l > 0) {
-        const LayerPlan& prev = st->plan.layers[l - 1];
-        const void* zprev = prev.z_off == UINT64_MAX ? nullptr : aslot + prev.z_off;
+      if (to_caller && !d.needs_dx) break;
+      {
         ProfScope ps(st, TP_K_DGRAD);
-        HIP_TRY(tp::launch_dgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, wb + lp.w_off * es,
-                                 zprev, st->dz_buf(pp)));
-        dz = st->dz_buf(pp);
-        pp ^= 1;
-      } else if (d.needs_dx) {
-        ProfScope ps(st, TP_K_DGRAD);
-        HIP_TRY(tp::launch_dgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, wb + lp.w_off * es,
-                                 nullptr, dx_dev));
+        if (lp.d.type == TP_LAYER_DENSE)
+          HIP_TRY(tp::launch_dgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, wb + lp.w_off * es,
+                                   dprev, dst));
+        else
+          HIP_TRY(tp::launch_conv_dgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features,
+                                        lp.d.out_features, dz, wb + lp.w_off * es, dprev, dst));
       }
+      dz = dst;
+      if (!to_caller) pp ^= 1;
     }
   }
 

@@ -13,6 +13,17 @@ import torch
 from . import binding as B
 
 
+def layer_tuple(spec) -> tuple:
+    """Workload layer description -> the tuple format of binding.make_desc."""
+    kind = getattr(spec, "kind", "dense")
+    if kind == "conv":
+        assert (spec.k, spec.stride, spec.pad) == (3, 1, 1), "only 3x3 / stride 1 / pad 1 convolutions are built"
+        return ("conv", spec.cin, spec.cout, spec.h, spec.w, spec.act)
+    if kind == "pool":
+        return ("pool", spec.c, spec.h, spec.w)
+    return (spec.in_features, spec.out_features, spec.act)
+
+
 def _torch_dtype(dtype: str):
     return torch.bfloat16 if dtype == "bf16" else torch.float32
 
@@ -25,6 +36,8 @@ class GpuStage:
                  ring_capacity: Optional[int] = None, max_in_flight: Optional[int] = None,
                  needs_dx: Optional[bool] = None, device="cuda:0", stream: Optional[torch.cuda.Stream] = None):
         self.layers = [tuple(l) for l in layers]
+        self.in_elems = B.layer_in_elems(self.layers[0])      # values per sample in / out of the stage
+        self.out_elems = B.layer_out_elems(self.layers[-1])
         self.dtype, self.mb, self.n = dtype, mb, n
         self.s, self.K = stage_index, num_stages
         depth = num_stages - stage_index
@@ -67,28 +80,39 @@ class GpuStage:
 
     # -- parameter arena <-> per-layer arrays (pure indexing) -----------------
     def pack(self, params: List[np.ndarray]) -> np.ndarray:
+        """Flat list [W, b, W, b, ...] over the layers that have parameters -> padded arena."""
         flat = np.zeros(self.P, dtype=np.float32)
-        for l, (fin, fout, _) in enumerate(self.layers):
+        pi = 0
+        for l, spec in enumerate(self.layers):
+            shapes = B.layer_param_shapes(spec)
+            if not shapes:
+                continue
             wo, bo = self.sizes.w_offset[l], self.sizes.b_offset[l]
-            flat[wo: wo + fin * fout] = np.asarray(params[2 * l], dtype=np.float32).reshape(-1)
-            flat[bo: bo + fout] = np.asarray(params[2 * l + 1], dtype=np.float32).reshape(-1)
+            nw, nb = int(np.prod(shapes[0])), int(np.prod(shapes[1]))
+            flat[wo: wo + nw] = np.asarray(params[pi], dtype=np.float32).reshape(-1)
+            flat[bo: bo + nb] = np.asarray(params[pi + 1], dtype=np.float32).reshape(-1)
+            pi += 2
         return flat
 
     def unpack(self, flat) -> List[np.ndarray]:
         flat = np.asarray(flat)
         out = []
-        for l, (fin, fout, _) in enumerate(self.layers):
+        for l, spec in enumerate(self.layers):
+            shapes = B.layer_param_shapes(spec)
+            if not shapes:
+                continue
             wo, bo = self.sizes.w_offset[l], self.sizes.b_offset[l]
-            out.append(flat[wo: wo + fin * fout].reshape(fout, fin))
-            out.append(flat[bo: bo + fout])
+            out.append(flat[wo: wo + int(np.prod(shapes[0]))].reshape(shapes[0]))
+            out.append(flat[bo: bo + int(np.prod(shapes[1]))])
         return out
 
     # -- calls ----------------------------------------------------------------
     def forward(self, mb_id: int, ub: int, x: torch.Tensor, y: Optional[torch.Tensor] = None):
         if y is None:
-            y = torch.empty(self.mb, self.layers[-1][1], dtype=self.tdtype, device=self.device)
+            y = torch.empty(self.mb, self.out_elems, dtype=self.tdtype, device=self.device)
         assert x.is_contiguous() and y.is_contiguous() and x.dtype == self.tdtype and y.dtype == self.tdtype
-        assert x.shape == (self.mb, self.layers[0][0]) and y.shape == (self.mb, self.layers[-1][1])
+        assert x.shape[0] == self.mb and x.numel() == self.mb * self.in_elems
+        assert y.shape[0] == self.mb and y.numel() == self.mb * self.out_elems
         v = B.stage_forward(self.handle, mb_id, ub, x.data_ptr(), y.data_ptr())
         return y, v
 
@@ -96,15 +120,15 @@ class GpuStage:
         """Tensor view of the workspace rows where the input of (mb_id, ub) belongs."""
         ptr = B.stage_input_ptr(self.handle, mb_id, ub)
         off = ptr - self.act.data_ptr()
-        nbytes = self.mb * self.layers[0][0] * self.act_elt()
-        return self.act[off: off + nbytes].view(self.tdtype).view(self.mb, self.layers[0][0])
+        nbytes = self.mb * self.in_elems * self.act_elt()
+        return self.act[off: off + nbytes].view(self.tdtype).view(self.mb, self.in_elems)
 
     def act_elt(self) -> int:
         return 2 if self.dtype == "bf16" else 4
 
     def loss(self, mb_id: int, logits: torch.Tensor, labels: torch.Tensor):
         rows = self.mb * self.n
-        assert logits.shape == (rows, self.layers[-1][1]) and logits.is_contiguous() and logits.dtype == self.tdtype
+        assert logits.shape == (rows, self.out_elems) and logits.is_contiguous() and logits.dtype == self.tdtype
         assert labels.dtype == torch.int32 and labels.shape == (rows,)
         dlogits = torch.empty_like(logits)
         loss = torch.empty(1, dtype=torch.float32, device=self.device)
@@ -114,11 +138,12 @@ class GpuStage:
 
     def backward(self, mb_id: int, dy: torch.Tensor, dx: Optional[torch.Tensor] = None):
         rows = self.mb * self.n
-        assert dy.shape == (rows, self.layers[-1][1]) and dy.is_contiguous() and dy.dtype == self.tdtype
+        assert dy.shape[0] == rows and dy.numel() == rows * self.out_elems and dy.is_contiguous()
+        assert dy.dtype == self.tdtype
         if self.needs_dx and dx is None:
-            dx = torch.empty(rows, self.layers[0][0], dtype=self.tdtype, device=self.device)
+            dx = torch.empty(rows, self.in_elems, dtype=self.tdtype, device=self.device)
         if dx is not None:
-            assert dx.shape == (rows, self.layers[0][0]) and dx.is_contiguous() and dx.dtype == self.tdtype
+            assert dx.numel() == rows * self.in_elems and dx.is_contiguous() and dx.dtype == self.tdtype
         delta = B.stage_backward(self.handle, mb_id, dy.data_ptr(), dx.data_ptr() if dx is not None else 0)
         return dx, delta
 
@@ -154,7 +179,7 @@ class GpuPipeline:
         self.w = workload
         self.K = workload.K
         self.fuse = fuse_next_blend
-        self.stages = [GpuStage([(l.in_features, l.out_features, l.act) for l in workload.stages[s]], stage_params[s],
+        self.stages = [GpuStage([layer_tuple(l) for l in workload.stages[s]], stage_params[s],
                                 dtype=workload.dtype, mb=workload.mb, n=workload.n, stage_index=s, num_stages=self.K,
                                 policy=policy, lam=workload.lam, lr=workload.lr, momentum=workload.momentum,
                                 device=device) for s in range(self.K)]
@@ -174,7 +199,7 @@ class GpuPipeline:
             info = {}
             if kind == "F":
                 x = get_input(j) if s == 0 else acts.pop((s - 1, j))
-                y = torch.empty(rows, st.layers[-1][1], dtype=st.tdtype, device=self.device)
+                y = torch.empty(rows, st.out_elems, dtype=st.tdtype, device=self.device)
                 for ub in range(w.n):
                     _, v = st.forward(j, ub, x[ub * w.mb:(ub + 1) * w.mb], y[ub * w.mb:(ub + 1) * w.mb])
                 acts[(s, j)] = y

@@ -52,8 +52,11 @@ def oracle_records(w: W.Workload, policy: str, num_mb: int, params=None):
 
 def oracle_flat_to_arena(stage, flat_oracle: np.ndarray) -> np.ndarray:
     """Oracle's concatenated [W0,b0,W1,b1,...] -> the library's padded arena order."""
+    from paper_2509_23241_amd.binding import layer_param_shapes
     parts, off = [], 0
-    for (fin, fout, _) in stage.layers:
-        parts.append(flat_oracle[off: off + fin * fout].reshape(fout, fin)); off += fin * fout
-        parts.append(flat_oracle[off: off + fout]); off += fout
+    for spec in stage.layers:
+        for shape in layer_param_shapes(spec):
+            n = int(np.prod(shape))
+            parts.append(flat_oracle[off: off + n].reshape(shape))
+            off += n
     return stage.pack(parts).astype(np.float64)
