@@ -39,10 +39,13 @@ def parse():
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--policy", default="convex", choices=["latest", "eq1", "convex", "stashed"])
-    ap.add_argument("--stage", type=int, default=1)
+    ap.add_argument("--workload", default="mlp", choices=["mlp", "vgg"],
+                    help="mlp: interior stage of the width-4096 GELU MLP (the configuration the metric is quoted on); "
+                         "vgg: stage 0 of the VGG-16-style net on 32x32x3 images (implicit-GEMM convolutions)")
+    ap.add_argument("--stage", type=int, default=None)
     ap.add_argument("--width", type=int, default=4096)
-    ap.add_argument("--mb", type=int, default=256)
-    ap.add_argument("--n", type=int, default=8)
+    ap.add_argument("--mb", type=int, default=None, help="micro-batch size (default 256 mlp, 64 vgg)")
+    ap.add_argument("--n", type=int, default=None, help="micro-batches per mini-batch (default 8 mlp, 4 vgg)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-minibatches", type=int, default=3)
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
@@ -51,26 +54,68 @@ def parse():
     return ap.parse_args()
 
 
-def kernel_work(cls, w, s):
-    """Algorithmic work of ONE launch of a kernel class at stage s: (flops, bytes)."""
+def layer_work(cls, layer, rows, mb):
+    """Algorithmic (flops, bytes) of ONE launch of kernel class `cls` for one layer; rows = samples of a
+    mini-batch (backward kernels), mb = samples of a micro-batch (forward kernels)."""
+    if layer.kind == "pool":
+        return 0.0, 0.0
+    px = layer.h * layer.w if layer.kind == "conv" else 1        # GEMM rows per sample
+    fin = (9 * layer.cin) if layer.kind == "conv" else layer.in_features
+    cin = layer.cin if layer.kind == "conv" else layer.in_features
+    fout = layer.cout if layer.kind == "conv" else layer.out_features
+    if cls == "fprop":                 # x, W in; act'(z), a out
+        return 2.0 * mb * px * fin * fout, 2.0 * (mb * px * cin + fin * fout + 2 * mb * px * fout)
+    if cls == "dgrad":                 # dz, W_b, act'(z_prev) in; dz_prev out
+        return 2.0 * rows * px * fin * fout, 2.0 * (rows * px * fout + fin * fout + 2 * rows * px * cin)
+    if cls == "wgrad":                 # dz, x in; dW (fp32) out
+        return 2.0 * rows * px * fin * fout, 2.0 * (rows * px * fout + rows * px * cin) + 4.0 * fin * fout
+    if cls == "colsum":
+        return 0.0, 2.0 * rows * px * fout
+    return 0.0, 0.0
+
+
+def kernel_work(cls, w, s, needs_dx):
+    """Algorithmic work of one STEP in kernel class cls at stage s: (flops, bytes), summed over the
+    launches of the step; divided by the launches it is the per-launch figure."""
     layers = w.stages[s]
     rows = w.n * w.mb
-    P = sum(l.in_features * l.out_features + l.out_features for l in layers)
-    L = layers[0]                      # the timed stages have equal layers
-    fin, fout = L.in_features, L.out_features
-    if cls == "fprop":                 # one micro-batch, one layer: x, W in; z, a out
-        return 2.0 * w.mb * fin * fout, 2.0 * (w.mb * fin + fin * fout + 2 * w.mb * fout)
-    if cls == "dgrad":                 # dz, W_b, z_prev in; dz_prev out
-        return 2.0 * rows * fin * fout, 2.0 * (rows * fout + fin * fout + 2 * rows * fin)
-    if cls == "wgrad":                 # dz, x in; dW (fp32) out
-        return 2.0 * rows * fin * fout, 2.0 * (rows * fout + rows * fin) + 4.0 * fin * fout
+    P = sum(int(np_prod(sh)) for l in layers for sh in l.param_shapes())
     if cls == "update":                # g, m, W[v], W[v_f] in; m, W[v+1] fp32 + two bf16 copies out
         return 8.0 * P, 28.0 * P
-    if cls == "act_bwd":
-        return 0.0, 3 * 2.0 * rows * fout
-    if cls == "colsum":
-        return 0.0, 2.0 * rows * fout
-    return 0.0, 0.0
+    if cls == "act_bwd":               # dy (.) act'(z) at the stage output and behind every pool
+        tot = 0.0
+        for i, l in enumerate(layers):
+            if l.kind != "pool" and (i == len(layers) - 1 or layers[i + 1].kind == "pool") and l.act != "none":
+                tot += 3 * 2.0 * rows * l.out_dim()
+        return 0.0, tot
+    if cls == "pool":                  # forward: in + out; backward: in, out, dy in, dx out
+        tot = 0.0
+        for l in layers:
+            if l.kind == "pool":
+                e = l.c * l.h * l.w
+                tot += 2.0 * rows * (e + e / 4) + 2.0 * rows * (2 * e + 2 * e / 4)
+        return 0.0, tot
+    if cls == "copy":                  # stage input saved for the backward where no GEMM can fuse it
+        l = layers[0]
+        return 0.0, (2 * 2.0 * rows * np_prod(l.in_shape())) if l.kind == "conv" else 0.0
+    flops = nbytes = 0.0
+    for i, l in enumerate(layers):
+        if l.kind == "pool":
+            continue
+        if cls == "dgrad" and i == 0 and not needs_dx:
+            continue
+        f, b = layer_work(cls, l, rows, w.mb)
+        mult = w.n if cls == "fprop" else 1
+        flops += mult * f
+        nbytes += mult * b
+    return flops, nbytes
+
+
+def np_prod(shape):
+    out = 1
+    for v in shape:
+        out *= int(v)
+    return out
 
 
 def cpu_baseline(w, s, policy, minibatches):
@@ -125,24 +170,33 @@ def main():
         print(json.dumps({"copy_probe_bytes": args.copy_probe, "copies": 5}))
         return
     from paper_2509_23241_amd import binding as B
-    from paper_2509_23241_amd.runner import GpuStage
+    from paper_2509_23241_amd.runner import GpuStage, layer_tuple
     from synth_inputs import workloads as W
 
-    w = W.mlp_wide(width=args.width, mb=args.mb, n=args.n)
-    s = args.stage
+    if args.workload == "mlp":
+        w = W.mlp_wide(width=args.width, mb=args.mb or 256, n=args.n or 8)
+        s = 1 if args.stage is None else args.stage
+        what = f"stage {s} of the 4-stage 8-layer GELU MLP width {args.width}"
+    else:
+        w = W.vgg_stage0(mb=args.mb or 64, n=args.n or 4)
+        s = 0
+        if args.stage not in (None, 0):
+            sys.exit("bench.py: the vgg workload describes stage 0 only")
+        what = ("stage 0 (conv3-64, conv3-64, pool, conv3-128, conv3-128, pool; ReLU) of the 4-stage VGG-16-style "
+                "net on 32x32x3 images")
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     depth = w.K - s
-    layers = [(l.in_features, l.out_features, l.act) for l in w.stages[s]]
+    layers = [layer_tuple(l) for l in w.stages[s]]
     st = GpuStage(layers, W.init_params(w, s), dtype=w.dtype, mb=w.mb, n=w.n, stage_index=s, num_stages=w.K,
-                  policy=args.policy, lam=w.lam, lr=w.lr, momentum=w.momentum, device=dev)
+                  policy=args.policy, lam=w.lam, lr=w.lr, momentum=w.momentum, needs_dx=(s > 0), device=dev)
     tdt = st.tdtype
     rows = w.n * w.mb
     nbuf = 2                                       # distinct synthetic mini-batches, resident in HBM
-    xs = [torch.from_numpy(W.stage_input(w, s, j)).to(dev).to(tdt) for j in range(nbuf)]
-    dys = [torch.from_numpy(W.stage_upstream_grad(w, s, j)).to(dev).to(tdt) for j in range(nbuf)]
-    y = torch.empty(rows, layers[-1][1], dtype=tdt, device=dev)
-    dx = torch.empty(rows, layers[0][0], dtype=tdt, device=dev) if st.needs_dx else None
+    xs = [torch.from_numpy(W.stage_input(w, s, j).reshape(rows, -1)).to(dev).to(tdt) for j in range(nbuf)]
+    dys = [torch.from_numpy(W.stage_upstream_grad(w, s, j).reshape(rows, -1)).to(dev).to(tdt) for j in range(nbuf)]
+    y = torch.empty(rows, st.out_elems, dtype=tdt, device=dev)
+    dx = torch.empty(rows, st.in_elems, dtype=tdt, device=dev) if st.needs_dx else None
 
     def forward(j):
         x = xs[j % nbuf]
@@ -190,7 +244,8 @@ def main():
         launches, ms = prof[cls]
         if launches == 0:
             continue
-        flops, nbytes = kernel_work(cls, w, s)
+        per_step = launches / args.steps
+        flops, nbytes = (v / per_step for v in kernel_work(cls, w, s, st.needs_dx))
         avg_us = ms / launches * 1e3
         kernels[cls] = {"launches_per_step": launches / args.steps, "avg_us": round(avg_us, 2),
                         "share_of_step": round(ms / args.steps / (dt_prof / args.steps * 1e3), 4),
@@ -198,7 +253,7 @@ def main():
                         "gbs": round(nbytes / (avg_us * 1e-6) / 1e9, 1) if nbytes else None}
     dominant = max(kernels, key=lambda c: kernels[c]["share_of_step"])
     dk = kernels[dominant]
-    flops, nbytes = kernel_work(dominant, w, s)
+    flops, nbytes = (v / dk["launches_per_step"] for v in kernel_work(dominant, w, s, st.needs_dx))
     # the roofline that bounds one launch: matrix cores or HBM, whichever takes longer at peak
     t_mfma = flops / (PEAK_BF16_TFLOPS * 1e12)
     t_hbm = nbytes / (PEAK_HBM_GBS * 1e9)
@@ -210,7 +265,7 @@ def main():
         achieved = nbytes / (dk["avg_us"] * 1e-6) / 1e9
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
-    default_workload = (args.width, args.mb, args.n, args.stage, args.policy) == (4096, 256, 8, 1, "convex")
+    default_workload = (args.workload, args.width, w.mb, w.n, s, args.policy) == ("mlp", 4096, 256, 8, 1, "convex")
     roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(dominant) if default_workload else None
     roofline["algorithmic"] = nbytes if roofline["bound"] == "hbm" else flops
     roofline["avg_us"] = dk["avg_us"]
@@ -221,7 +276,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "ms_per_step_with_events": round(dt_prof / args.steps * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"stage {s} of the 4-stage 8-layer GELU MLP width {args.width}: bf16 activations, "
+        "config": {"workload": f"{what}: bf16 activations, "
                                f"fp32 master weights, micro-batch {w.mb} x {w.n}, policy {args.policy}, "
                                f"lambda {w.lam}, staleness {delta_steady}, one step = 1 backward + 1 fused update/blend "
                                f"+ {w.n} micro-batch forwards",

@@ -14,6 +14,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 #include "conv.h"
 #include "device_utils.h"
 
@@ -201,11 +203,15 @@ int conv_wgrad_splits(int pixels) {
 }
 
 size_t conv_wgrad_scratch_floats(int pixels, int cin, int cout) {
-  return (size_t)conv_wgrad_splits(pixels) * cout * 9 * cin;
+  const int splits = std::max(conv_wgrad_splits(pixels), conv_mfma_wgrad_splits(pixels, cin, cout));
+  return (size_t)splits * cout * 9 * cin;
 }
 
 hipError_t launch_conv_fprop(hipStream_t s, int elt, int imgs, int H, int W, int cin, int cout, const void* x,
-                             const void* wgt, const float* bias, int act, void* d_out, void* a_out) {
+                             const void* wgt, const float* bias, int act, void* d_out, void* a_out, const void* zeros) {
+  if (elt == 1 && zeros && conv_mfma_supported(imgs, H, W, cin, cout))
+    return conv_mfma_fprop(s, imgs, H, W, cin, cout, (const uint16_t*)x, (const uint16_t*)wgt, bias, act, (uint16_t*)d_out,
+                           (uint16_t*)a_out, (const uint16_t*)zeros);
   const ConvGeom g{imgs, H, W, cin, cout};
   const int P = imgs * H * W;
   dim3 grid((cout + BN - 1) / BN, (P + BM - 1) / BM);
@@ -219,7 +225,10 @@ hipError_t launch_conv_fprop(hipStream_t s, int elt, int imgs, int H, int W, int
 }
 
 hipError_t launch_conv_dgrad(hipStream_t s, int elt, int imgs, int H, int W, int cin, int cout, const void* dz,
-                             const void* wb, const void* d_prev, void* out) {
+                             const void* wb, const void* d_prev, void* out, const void* zeros) {
+  if (elt == 1 && zeros && conv_mfma_supported(imgs, H, W, cin, cout))
+    return conv_mfma_dgrad(s, imgs, H, W, cin, cout, (const uint16_t*)dz, (const uint16_t*)wb, (const uint16_t*)d_prev,
+                           (uint16_t*)out, (const uint16_t*)zeros);
   const ConvGeom g{imgs, H, W, cin, cout};
   const int P = imgs * H * W;
   dim3 grid((cin + BN - 1) / BN, (P + BM - 1) / BM);
@@ -233,7 +242,10 @@ hipError_t launch_conv_dgrad(hipStream_t s, int elt, int imgs, int H, int W, int
 }
 
 hipError_t launch_conv_wgrad(hipStream_t s, int elt, int imgs, int H, int W, int cin, int cout, const void* dz,
-                             const void* x, float* gW, float* partial) {
+                             const void* x, float* gW, float* partial, const void* zeros) {
+  if (elt == 1 && zeros && conv_mfma_supported(imgs, H, W, cin, cout))
+    return conv_mfma_wgrad(s, imgs, H, W, cin, cout, (const uint16_t*)dz, (const uint16_t*)x, gW, partial,
+                           (const uint16_t*)zeros);
   const ConvGeom g{imgs, H, W, cin, cout};
   const int P = imgs * H * W;
   const int splits = conv_wgrad_splits(P);

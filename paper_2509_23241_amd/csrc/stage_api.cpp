@@ -183,7 +183,7 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
   s.wfwd_bytes = d->dtype == TP_BF16 ? P * 2 : 0;
   s.wbwd_bytes = P * p->elt_size;
   s.act_bytes = (uint64_t)d->max_in_flight * act;
-  s.scratch_bytes = 2 * p->dz_bytes + p->partial_floats * 4;
+  s.scratch_bytes = 2 * p->dz_bytes + p->partial_floats * 4 + 512;  // + an aligned block of 256 zero bytes (conv padding)
   s.diag_bytes = TP_DIAG_COUNT * sizeof(double);
   return TP_OK;
 }
@@ -231,6 +231,10 @@ struct tp_stage {
   char* act_slot(int q) const { return (char*)bufs.act_dev + (uint64_t)q * plan.act_slot_bytes; }
   char* dz_buf(int i) const { return (char*)bufs.scratch_dev + (uint64_t)i * plan.dz_bytes; }
   float* partials() const { return (float*)((char*)bufs.scratch_dev + 2 * plan.dz_bytes); }
+  const void* zeros() const {  // 256-byte aligned, behind the partial sums
+    const uintptr_t p = (uintptr_t)bufs.scratch_dev + 2 * plan.dz_bytes + plan.partial_floats * 4;
+    return (const void*)((p + 255) & ~(uintptr_t)255);
+  }
   // drop a version that nobody needs any more
   void evict_if_unused(uint64_t v) {
     int s = find_slot(v);
@@ -355,6 +359,10 @@ int stage_init(const tp_stage_desc* desc, const tp_buffers* bufs, void* hip_stre
         !bufs->scratch_dev || !bufs->diag_dev || (bf && !bufs->wfwd_dev)) {
       delete st;
       return fail(TP_EINVAL, "null device buffer");
+    }
+    {  // the block of zeros that convolution padding reads
+      hipError_t e = hipMemsetAsync((void*)st->zeros(), 0, 256, st->stream);
+      if (e != hipSuccess) { delete st; return fail(TP_EHIP, "memset: %s", hipGetErrorString(e)); }
     }
     if (bf) {
       hipError_t e = tp::launch_convert(st->stream, tp::ELT_BF16, st->plan.sizes.param_count, st->ring(0),
@@ -484,7 +492,7 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
       ProfScope ps(st, TP_K_FPROP);
       HIP_TRY(tp::launch_conv_fprop(st->stream, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features,
                                     lp.d.out_features, x_saved, wcopy + lp.w_off * es, master + lp.b_off, lp.d.act,
-                                    z_out, a_out));
+                                    z_out, a_out, st->zeros()));
     } else {
       ProfScope ps(st, TP_K_POOL);
       HIP_TRY(tp::launch_maxpool_fwd(st->stream, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, x_saved,
@@ -602,7 +610,8 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
                                    g + lp.w_off));
         else
           HIP_TRY(tp::launch_conv_wgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features,
-                                        lp.d.out_features, dz, aslot + lp.x_off, g + lp.w_off, st->partials()));
+                                        lp.d.out_features, dz, aslot + lp.x_off, g + lp.w_off, st->partials(),
+                                        st->zeros()));
       }
       if (to_caller && !d.needs_dx) break;
       {
@@ -612,7 +621,7 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
                                    dprev, dst));
         else
           HIP_TRY(tp::launch_conv_dgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features,
-                                        lp.d.out_features, dz, wb + lp.w_off * es, dprev, dst));
+                                        lp.d.out_features, dz, wb + lp.w_off * es, dprev, dst, st->zeros()));
       }
       dz = dst;
       if (!to_caller) pp ^= 1;

@@ -115,6 +115,13 @@ def test_conv_channels_multiple_of_64(dtype):
     print(dtype, _run_stage(specs, f"conv64_{dtype}", dtype, mb=4, n=2, depth=3, minibatches=4))
 
 
+def test_conv_matrix_core_tile_variants():
+    # non-square power-of-two image, channel counts that are multiples of 64 but not of 128 (the
+    # narrower tiles), 768 pixels per mini-batch = six row tiles, no pooling: normal tolerance throughout
+    specs = (W.Conv2d(128, 192, 4, 16, "gelu"), W.Conv2d(192, 64, 4, 16, "gelu"), W.Conv2d(64, 128, 4, 16, "none"))
+    print(_run_stage(specs, "convtiles_bf16", "bf16", mb=6, n=2, depth=2, minibatches=3))
+
+
 def test_vgg_first_stage_reduced_bf16():
     # the VGG-style stage 0 (conv3-64, conv3-64, pool, conv3-128, conv3-128, pool) on 16x16 images,
     # micro-batch 4 x 2; GELU instead of ReLU keeps the bf16 comparison away from the ReLU kink
