@@ -38,19 +38,19 @@ def _run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, dept
     tol = TOL[dtype]
     worst = {}
     failures = []
-    # Pooling picks one element per window.  Once the two sides have taken an update, their bf16
-    # weight copies differ in the last bit for ~1 % of the weights, activations differ in the last bit
-    # here and there, and a window whose two largest values are a bf16 ulp apart may route its
-    # gradient to the other element.  The totals are unaffected (bias gradients, outputs, updated
-    # weights stay within the normal tolerance) but tensors that see the position of the routed
-    # gradient -- dx and the weight gradients of layers in front of a pool -- move by sqrt(2 * fraction
-    # of such windows), a few percent.  They are held to the normal tolerance while both sides still
-    # run on identical weights (mini-batches whose forward preceded the first update, and everything
-    # in fp32) and to ROUTED_TOL afterwards.
+    # Pooling picks one element per window and ReLU one side of its kink.  Once the two sides have
+    # taken an update, their bf16 weight copies differ in the last bit for ~1 % of the weights,
+    # activations differ in the last bit here and there, and a window whose two largest values are a
+    # bf16 ulp apart may route its gradient to the other element (a pre-activation next to zero may
+    # switch its gradient on or off).  Forward outputs and updated weights are unaffected and stay
+    # within the normal tolerance.  Gradients are sums of terms of random sign (the synthetic
+    # upstream gradient has no preferred sign), so a fraction e of re-routed terms moves a sum by
+    # sqrt(e) of its size: a few percent for e ~ 1e-3.  Gradient tensors of stages with a pool or a
+    # ReLU are therefore held to the normal tolerance while both sides still run on identical
+    # weights (mini-batches whose forward preceded the first update -- these cover every staleness
+    # the schedule produces -- and everything in fp32) and to ROUTED_TOL afterwards.
     ROUTED_TOL = 0.15
-    pools = [i for i, l in enumerate(specs) if l.kind == "pool"]
-    last_pool = max(pools) if pools else -1
-    param_layer = [i for i, l in enumerate(specs) if l.kind != "pool" for _ in (0, 1)]
+    nonsmooth = any(l.kind == "pool" or getattr(l, "act", "") == "relu" for l in specs)
     diverged = [False]
 
     def note(k, e, routed=False):
@@ -80,11 +80,10 @@ def _run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, dept
         print(f"  mini-batch {j}: delta {delta}", {k: f"{v:.1e}" for k, v in worst.items()}, flush=True)
         diverged[0] = j >= depth                     # this mini-batch's forward ran after an update
         if needs_dx:
-            note("dx", rel_err(to_np(dx), dx_ref.reshape(n * mb, -1)), routed=last_pool >= 0)
-        note("g", rel_err(to_np(st.grad), oracle_flat_to_arena(st, ost.flat(ost.g))), routed=last_pool >= 0)
+            note("dx", rel_err(to_np(dx), dx_ref.reshape(n * mb, -1)), routed=nonsmooth)
+        note("g", rel_err(to_np(st.grad), oracle_flat_to_arena(st, ost.flat(ost.g))), routed=nonsmooth)
         for pi, (got, ref) in enumerate(zip(st.unpack(to_np(st.grad)), ost.g)):
-            is_weight = pi % 2 == 0
-            note(f"g[{pi}]", rel_err(got, ref), routed=is_weight and param_layer[pi] < last_pool)
+            note(f"g[{pi}]", rel_err(got, ref), routed=nonsmooth)
         ost.update(j)
         assert st.blend_update(j, j + 1) == ost.latest
         note("W_new", rel_err(to_np(st.export(ost.latest)), oracle_flat_to_arena(st, ost.flat(ost.weights[ost.latest]))))
