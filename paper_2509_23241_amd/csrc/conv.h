@@ -31,6 +31,7 @@ hipError_t launch_maxpool_bwd(hipStream_t s, int elt, int imgs, int H, int W, in
 // bf16 matrix-core versions (kernels_conv_mfma.hip) and the shapes they take
 bool conv_mfma_supported(int imgs, int H, int W, int cin, int cout);
 int conv_mfma_wgrad_splits(int pixels, int cin, int cout);
+int conv_mfma_wgrad_max_splits(int pixels, int cin, int cout);
 hipError_t conv_mfma_fprop(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* x,
                            const uint16_t* wgt, const float* bias, int act, uint16_t* d_out, uint16_t* a_out,
                            const uint16_t* zeros);

@@ -196,14 +196,16 @@ inline int stream_blocks(size_t items, int max_blocks) {
 
 }  // namespace
 
-int conv_wgrad_splits(int pixels) {
-  // enough pixel ranges to fill the chip even when dW has only a handful of tiles
-  int s = (pixels + 2047) / 2048;
-  return s < 1 ? 1 : (s > 256 ? 256 : s);
+int conv_wgrad_splits(int pixels, int cin, int cout) {
+  // enough pixel ranges to put ~1024 workgroups on the chip even when dW has only a handful of
+  // tiles (the 3-channel first layer has one), at least 256 pixels each
+  const int tiles = ((9 * cin + BN - 1) / BN) * ((cout + BM - 1) / BM);
+  int s = std::min((1024 + tiles - 1) / tiles, (pixels + 255) / 256);
+  return s < 1 ? 1 : (s > 1024 ? 1024 : s);
 }
 
 size_t conv_wgrad_scratch_floats(int pixels, int cin, int cout) {
-  const int splits = std::max(conv_wgrad_splits(pixels), conv_mfma_wgrad_splits(pixels, cin, cout));
+  const int splits = std::max(conv_wgrad_splits(pixels, cin, cout), conv_mfma_wgrad_max_splits(pixels, cin, cout));
   return (size_t)splits * cout * 9 * cin;
 }
 
@@ -248,7 +250,7 @@ hipError_t launch_conv_wgrad(hipStream_t s, int elt, int imgs, int H, int W, int
                            (const uint16_t*)zeros);
   const ConvGeom g{imgs, H, W, cin, cout};
   const int P = imgs * H * W;
-  const int splits = conv_wgrad_splits(P);
+  const int splits = conv_wgrad_splits(P, cin, cout);
   const int per = ((P + splits - 1) / splits + BK - 1) / BK * BK;
   dim3 grid((9 * cin + BN - 1) / BN, (cout + BM - 1) / BM, splits);
   if (elt == 1)

@@ -19,6 +19,7 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <cstdlib>
 
 #include "conv.h"
 #include "device_utils.h"
@@ -258,13 +259,22 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_bf16_dma_kernel(int M, in
   }
   wait_vmcnt<0>();
   lds_barrier();
+  if constexpr (Epi::kSwap) {
+    if (m0 + wm + WM <= M && n0 + wn + WN <= N && (N & 7) == 0) {
+      float* wave_lds = reinterpret_cast<float*>(lds_raw) + wave * (wave_epilogue_bytes<TM, TN>() / 4);
+      store_tiles_coalesced<TM, TN>(acc, epi_at(epi, batch, split), m0 + wm, n0 + wn, lane, wave_lds);
+      return;
+    }
+  }
   store_tiles<TM, TN>(acc, epi_at(epi, batch, split), m0 + wm, n0 + wn, M, N, lane);
 }
 
 template <int BM, int BN, int NS, class AL, class BL, class Epi>
 hipError_t launch_conv(hipStream_t s, int M, int N, int KT, int batches, int splits, const typename AL::Desc& ad,
                        const typename BL::Desc& bd, const Epi& epi) {
-  constexpr size_t lds_bytes = (size_t)NS * (AL::kBytes + BL::kBytes);
+  constexpr size_t stage_bytes = (size_t)NS * (AL::kBytes + BL::kBytes);
+  constexpr size_t epi_bytes = (size_t)4 * wave_epilogue_bytes<BM / 64, BN / 64>();
+  constexpr size_t lds_bytes = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
   static_assert(lds_bytes <= 160 * 1024, "stages do not fit the LDS of a CU");
   auto kernel = conv_bf16_dma_kernel<BM, BN, 2, 2, NS, AL, BL, Epi>;
   if (lds_bytes > 32 * 1024) {
@@ -276,6 +286,270 @@ hipError_t launch_conv(hipStream_t s, int M, int N, int KT, int batches, int spl
   const TileMap map = make_tile_map(tiles_m, tiles_n);
   hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n, batches, splits), dim3(256), lds_bytes, s, M, N, KT, ad, bd, epi, map);
   return hipGetLastError();
+}
+
+// ================================================================================================
+// Patch kernels: the input tile lives in LDS once, with its halo
+// ================================================================================================
+// A tile of BM output pixels = BM/W whole image rows.  The (BM/W + 2) x (W + 2) input pixels it
+// needs (zero outside the image) are copied to LDS once, [patch pixel][channel]; the nine taps
+// then read the same LDS data at shifted pixel positions.  Compared with gathering every
+// (tap, channel block) k tile from L2 this cuts the activation traffic into the CU ninefold.
+
+struct PatchDesc {
+  const uint16_t* base;   // [P][C]
+  const uint16_t* zeros;  // >= 128 zero bytes
+  int H, W, lw;           // image size, log2(W)
+  int C;                  // channels of `base` (pixel pitch in elements)
+  int c0;                 // first channel staged
+  int CB;                 // 16-byte chunks staged per pixel (channels staged / 8)
+  int tr;                 // 1: layout for transposed reads (pixels are the contraction index)
+  long long* prof = nullptr;
+};
+
+// chunk c of patch pixel pp is stored in slot c ^ patch_swz(pp)
+__device__ __forceinline__ int patch_swz(int pp, int CB, int tr) {
+  if (tr) return 4 * ((pp >> 1) & 1);             // as the [k][64] stages of the dense kernels
+  return (CB & 15) ? ((pp >> 1) & 7) : (pp & 15);  // 128-byte pixels: 8 slots over same-parity pixels; wider: 16
+}
+
+// All waves of the workgroup copy the patch of the tile whose first pixel is p0 (a multiple of BM)
+template <int BM, int NW>
+__device__ __forceinline__ void issue_patch(const PatchDesc& d, uint32_t lds_patch, int p0, int wave, int lane) {
+  const int PC = d.W + 2, NPIX = (BM / d.W + 2) * PC;
+  const int img_px = d.H * d.W;
+  const int img = p0 / img_px, h0 = (p0 - img * img_px) >> d.lw;
+  const int px_bytes = d.CB * 16;
+  const int instrs = (NPIX * px_bytes + 1023) / 1024;
+  for (int i = wave; i < instrs; i += NW) {
+    const int off = i * 1024 + lane * 16;
+    const int pp = off / px_bytes, slot = (off - pp * px_bytes) >> 4;
+    const int chunk = slot ^ patch_swz(pp, d.CB, d.tr);
+    const int pr = pp / PC, pc = pp - pr * PC;
+    const int h = h0 + pr - 1, w = pc - 1;
+    const bool valid = pp < NPIX && (unsigned)h < (unsigned)d.H && (unsigned)w < (unsigned)d.W;
+    const long src = (((long)img * d.H + h) * d.W + w) * d.C + d.c0 + chunk * 8;
+    const uint16_t* ptr = valid ? d.base + src : d.zeros + (lane & 7) * 8;
+    dma16_addr(lds_patch + i * 1024, ptr);
+  }
+}
+__host__ __device__ inline int patch_bytes(int BM, int W, int CB) {
+  return (((BM / W + 2) * (W + 2) * CB * 16 + 1023) / 1024) * 1024;
+}
+
+// fprop (BWD = false) and dgrad (BWD = true): out[p][n] = sum_{tap, c} in[p shifted by tap][c] * B[(tap, c)][n]
+template <int BM, int BN, int WGM, int WGN, int NS, bool BWD, class BL, class Epi>
+__global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(int P, int N, PatchDesc pd, typename BL::Desc bd, Epi epi,
+                                                                     int tiles_n) {
+  constexpr int NW = WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int kLoads = BL::kPerWave;
+  constexpr int NM = (DBK / 16) * TM * TN;
+  static_assert((NS - 2) * kLoads < 64, "too many copies in flight for vmcnt");
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds_raw[];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
+  const int tile_p = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_p * tiles_n;
+  const int m0 = tile_p * BM, n0 = tile_n * BN;
+  const uint32_t lds_base = lds_addr_of(lds_raw);
+  const int pbytes = patch_bytes(BM, pd.W, pd.CB);
+  const uint32_t lds_stage0 = lds_base + pbytes;
+  const uint16_t* stage0 = lds_raw + pbytes / 2;
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  long long t0 = 0, t1 = 0, t2 = 0, t3 = 0;
+  if (pd.prof) t0 = wall_clock64();
+  issue_patch<BM, NW>(pd, lds_base, m0, wave, lane);
+  BL tb;
+  tb.init(bd, n0, wave, lane, 0);
+  const int cbs = pd.C / DBK;  // 64-channel blocks per tap
+  const int KT = 9 * cbs;
+  auto issue_copy = [&](int t, int tile, int st) {
+    tb.issue_one(t, lds_stage0 + st * BL::kBytes, min(tile, KT - 1), wave);
+  };
+#pragma unroll
+  for (int st = 0; st < NS - 1; ++st)
+#pragma unroll
+    for (int t = 0; t < kLoads; ++t) issue_copy(t, st, st);
+
+  // centre patch pixel of the lane's row in each of its MFMA row tiles
+  const int PC = pd.W + 2;
+  int ppc[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int q = wm + i * 32 + (lane & 31);
+    ppc[i] = ((q >> pd.lw) + 1) * PC + (q & (pd.W - 1)) + 1;
+  }
+  const int khalf = lane >> 5;
+
+  int rd = 0, wr = NS - 1;
+  int tap = 0, cb = 0;
+  for (int kt = 0; kt < KT; ++kt) {
+    wait_vmcnt<(NS - 2) * kLoads>();  // the patch copies are older than any stage: they have landed too
+    lds_barrier();
+    if (pd.prof && kt == 0) t1 = wall_clock64();
+    const uint16_t* lb = stage0 + rd * (BL::kBytes / 2);
+    int dh = tap / 3 - 1, dw = tap - (tap / 3) * 3 - 1;
+    if (BWD) { dh = -dh; dw = -dw; }
+    const int tapoff = dh * PC + dw;
+    uint32_t prow[TM];  // element offset of the lane's shifted pixel
+    int psw[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int ppt = ppc[i] + tapoff;
+      prow[i] = (uint32_t)ppt * pd.CB * 8;
+      psw[i] = patch_swz(ppt, pd.CB, 0);
+    }
+    auto afrag = [&](int i, int kk) {
+      const int chunk = cb * 8 + kk * 2 + khalf;
+      const uint4 v = *reinterpret_cast<const uint4*>(lds_raw + prow[i] + ((chunk ^ psw[i]) << 3));
+      return __builtin_bit_cast(bf16x8, v);
+    };
+    bf16x8 af[2][TM], bfr[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[0][i] = afrag(i, 0);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bfr[0][j] = BL::frag(lb, wn + j * 32, 0, lane);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < DBK / 16; ++kk) {
+      const int c = kk & 1, nx = c ^ 1;
+      if (kk + 1 < DBK / 16) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[nx][i] = afrag(i, kk + 1);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[nx][j] = BL::frag(lb, wn + j * 32, kk + 1, lane);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          acc[i][j] = mma<Epi::kSwap>(af[c][i], bfr[c][j], acc[i][j]);
+          const int q = (kk * TM + i) * TN + j;
+#pragma unroll
+          for (int t = 0; t < kLoads; ++t)
+            if ((t * NM) / kLoads == q) {
+              __builtin_amdgcn_sched_barrier(0);
+              issue_copy(t, kt + NS - 1, wr);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    rd = rd + 1 == NS ? 0 : rd + 1;
+    wr = wr + 1 == NS ? 0 : wr + 1;
+    if (++cb == cbs) { cb = 0; ++tap; }
+  }
+  wait_vmcnt<0>();
+  lds_barrier();
+  if (pd.prof) t2 = wall_clock64();
+  if (n0 + wn + WN <= N && (N & 7) == 0) {  // pixel tiles are always whole
+    float* wave_lds = reinterpret_cast<float*>(lds_raw) + wave * (wave_epilogue_bytes<TM, TN>() / 4);
+    store_tiles_coalesced<TM, TN>(acc, epi, m0 + wm, n0 + wn, lane, wave_lds);
+  } else {
+    store_tiles<TM, TN>(acc, epi, m0 + wm, n0 + wn, P, N, lane);
+  }
+  if (pd.prof) {
+    wait_vmcnt<0>();
+    t3 = wall_clock64();
+    if (threadIdx.x == 0) {
+      long long* o = pd.prof + 4 * (size_t)blockIdx.x;
+      o[0] = t0; o[1] = t1; o[2] = t2; o[3] = t3;
+    }
+  }
+}
+
+// wgrad: dW[co][tap][ci] = sum_p dz[p][co] * x[p shifted by tap][ci] for one block of 64 output and 64
+// input channels and all nine taps; the workgroup walks over pixel tiles split, split + splits, ...,
+// double buffered: the copies of the next tile fly while the current one is multiplied.
+template <int BM>
+__global__ __launch_bounds__(256) void conv_wgrad_patch_kernel(PatchDesc xd, const uint16_t* __restrict__ dz, int cout,
+                                                               int px_tiles, int ci_blocks, float* __restrict__ out) {
+  constexpr int NW = 4;
+  using DZ = ColDma<64, NW>;  // stage [pixel][64 output channels]; k index = pixel
+  constexpr int kDzInstr = BM * 8 / 64 / NW;
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds_raw[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int cob = blockIdx.x / ci_blocks, cib = blockIdx.x - cob * ci_blocks;
+  const int split = blockIdx.y, splits = gridDim.y;
+  const int cin = xd.C;
+  xd.c0 = cib * 64;
+  const int pbytes = patch_bytes(BM, xd.W, 8);
+  const int buf_bytes = pbytes + BM * 128;
+  const uint32_t lds_base = lds_addr_of(lds_raw);
+  const int rb_co = (wave >> 1) * 32, rb_ci = (wave & 1) * 32;
+  const int PC = xd.W + 2;
+
+  floatx16 acc[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+  // per-lane source offsets of the dz tile (the same in every tile, relative to its first pixel)
+  uint32_t dzoff[kDzInstr];
+#pragma unroll
+  for (int i = 0; i < kDzInstr; ++i) {
+    const int flat = 64 * (wave + NW * i) + lane;
+    const int k = flat >> 3, c = (flat & 7) ^ DZ::swz(k);
+    dzoff[i] = (uint32_t)(((size_t)k * cout + cob * 64 + c * 8) * 2);
+  }
+  auto issue_tile = [&](int tile, int buf) {
+    const uint32_t dst = lds_base + buf * buf_bytes;
+    issue_patch<BM, NW>(xd, dst, tile * BM, wave, lane);
+    const uint16_t* src = dz + (size_t)tile * BM * cout;
+#pragma unroll
+    for (int i = 0; i < kDzInstr; ++i) dma16(dst + pbytes + (wave + NW * i) * 1024, src, dzoff[i]);
+  };
+
+  if (split < px_tiles) issue_tile(split, 0);
+  int buf = 0;
+  for (int tile = split; tile < px_tiles; tile += splits) {
+    wait_vmcnt<0>();  // this tile has landed (nothing else is in flight)
+    lds_barrier();    // ... for every wave, and every wave is done with the other buffer
+    if (tile + splits < px_tiles) issue_tile(tile + splits, buf ^ 1);
+    const uint16_t* lp = lds_raw + buf * (buf_bytes / 2);
+    const uint16_t* ldz = lp + pbytes / 2;
+    const int g = lane >> 4, s = lane & 15;
+    const int col = rb_ci + 16 * (g & 1) + 4 * (s & 3);
+#pragma unroll 2
+    for (int kk = 0; kk < BM / 16; ++kk) {
+      const bf16x8 a = DZ::frag(ldz, rb_co, kk, lane);
+      const int kq = kk * 16 + 8 * (g >> 1) + (s >> 2);
+      const int ppc = ((kq >> xd.lw) + 1) * PC + (kq & (xd.W - 1)) + 1;
+#pragma unroll
+      for (int t = 0; t < 9; ++t) {
+        const int ppt = ppc + (t / 3 - 1) * PC + (t % 3 - 1);
+        const int slot = (col >> 3) ^ patch_swz(ppt, 8, 1);
+        typedef __attribute__((address_space(3))) shortx4* lds_ptr;
+        const uint16_t* p = lp + ppt * 64 + slot * 8 + (col & 7);
+        const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+        const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * 64));
+        const shortx8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        acc[t] = mma<false>(a, __builtin_bit_cast(bf16x8, v), acc[t]);
+      }
+    }
+    buf ^= 1;
+  }
+  float* o = out + (size_t)split * cout * 9 * cin;
+#pragma unroll
+  for (int t = 0; t < 9; ++t) {
+    floatx16 one[1][1];
+    one[0][0] = acc[t];
+    store_tiles<1, 1>(one, EpiWgrad{o + (size_t)t * cin, 9 * cin}, cob * 64 + rb_co, cib * 64 + rb_ci, cout, cin, lane);
+  }
 }
 
 inline bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
@@ -293,10 +567,88 @@ __global__ __launch_bounds__(256) void split_sum_mfma_kernel(size_t count, int s
 
 }  // namespace
 
+constexpr int kMaxLds = 160 * 1024;
+
+inline bool patch_shape_ok(int H, int W, int BM) {
+  return pow2(H) && pow2(W) && W >= 8 && BM % W == 0 && (H * W) % BM == 0;
+}
+
+template <int BM, int BN, int WGM, int WGN, int NS, bool BWD, class Epi>
+struct PatchCfg {
+  using BL = Plain<BN, WGM * WGN, BWD>;
+  static size_t lds(int W, int CB) {
+    const size_t loop = (size_t)patch_bytes(BM, W, CB) + (size_t)NS * BL::kBytes;
+    const size_t epi = (size_t)WGM * WGN * wave_epilogue_bytes<BM / WGM / 32, BN / WGN / 32>();
+    return std::max(loop, epi);
+  }
+  static bool ok(int H, int W, int C) { return patch_shape_ok(H, W, BM) && lds(W, C / 8) <= kMaxLds; }
+  static long tiles(long P, int N) { return (P / BM) * ((N + BN - 1) / BN); }
+  static hipError_t launch(hipStream_t s, int P, int N, const PatchDesc& pd, const PlainDesc& bd, const Epi& e) {
+    auto kernel = conv_patch_kernel<BM, BN, WGM, WGN, NS, BWD, BL, Epi>;
+    static hipError_t attr =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
+    if (attr != hipSuccess) return attr;
+    const int tiles_n = (N + BN - 1) / BN;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(P / BM * tiles_n)), dim3(64 * WGM * WGN), lds(pd.W, pd.CB), s, P, N, pd, bd, e,
+                       tiles_n);
+    return hipGetLastError();
+  }
+};
+
+// The largest tile that still gives every CU a workgroup; failing that, the one with the most
+// workgroups.  Returns hipErrorNotSupported when no patch tile fits the shape.
+template <bool BWD, class Epi>
+hipError_t launch_patch_conv(hipStream_t s, int P, int H, int W, int C, int N, const PatchDesc& pd, const PlainDesc& bd,
+                             const Epi& e) {
+  using A = PatchCfg<256, 128, 4, 2, 3, BWD, Epi>;
+  using B = PatchCfg<256, 64, 4, 2, 3, BWD, Epi>;
+  using Cc = PatchCfg<128, 128, 2, 2, 3, BWD, Epi>;
+  using D = PatchCfg<128, 64, 2, 2, 4, BWD, Epi>;
+  using E = PatchCfg<128, 64, 2, 2, 3, BWD, Epi>;
+  using F = PatchCfg<128, 64, 2, 2, 2, BWD, Epi>;
+  using G = PatchCfg<128, 128, 2, 2, 2, BWD, Epi>;
+  const bool wide = N % 128 == 0;
+  const bool ok[4] = {wide && A::ok(H, W, C), B::ok(H, W, C), wide && Cc::ok(H, W, C), D::ok(H, W, C)};
+  const long tiles[4] = {A::tiles(P, N), B::tiles(P, N), Cc::tiles(P, N), D::tiles(P, N)};
+  int pick = -1;
+  for (int i = 0; i < 4 && pick < 0; ++i)
+    if (ok[i] && tiles[i] >= 256) pick = i;
+  if (pick < 0)
+    for (int i = 0; i < 4; ++i)
+      if (ok[i] && (pick < 0 || tiles[i] > tiles[pick])) pick = i;
+  static const int forced = getenv("TP_CONV_TILE") ? atoi(getenv("TP_CONV_TILE")) : -1;
+  if (forced >= 0) pick = forced;
+  if (pick == 4) return E::launch(s, P, N, pd, bd, e);
+  if (pick == 5) return F::launch(s, P, N, pd, bd, e);
+  if (pick == 6) return G::launch(s, P, N, pd, bd, e);
+  switch (pick) {
+    case 0: return A::launch(s, P, N, pd, bd, e);
+    case 1: return B::launch(s, P, N, pd, bd, e);
+    case 2: return Cc::launch(s, P, N, pd, bd, e);
+    case 3: return D::launch(s, P, N, pd, bd, e);
+    default: return hipErrorNotSupported;
+  }
+}
+
+constexpr int kWgradBM = 128;
+inline size_t wgrad_patch_lds(int W) { return 2 * ((size_t)patch_bytes(kWgradBM, W, 8) + kWgradBM * 128); }
+inline bool wgrad_patch_ok(int H, int W) { return patch_shape_ok(H, W, kWgradBM) && wgrad_patch_lds(W) <= kMaxLds; }
+inline int wgrad_patch_splits(long px_tiles, int cin, int cout) {
+  const long blocks = std::max(1l, (long)(cin / 64) * (cout / 64));
+  return (int)std::max(1l, std::min(px_tiles, 256 / blocks));
+}
+
+long long* g_conv_prof = nullptr;
+
 bool conv_mfma_supported(int imgs, int H, int W, int cin, int cout) {
   const long P = (long)imgs * H * W;
   return pow2(H) && pow2(W) && H <= 32768 && W <= 32768 && cin % 64 == 0 && cout % 64 == 0 && P % 64 == 0 &&
          P * std::max(cin, cout) * 2 < (1l << 31);
+}
+
+// most partial sums either matrix-core wgrad kernel may write for this layer
+int conv_mfma_wgrad_max_splits(int pixels, int cin, int cout) {
+  return std::max(conv_mfma_wgrad_splits(pixels, cin, cout), wgrad_patch_splits(pixels / kWgradBM, cin, cout));
 }
 
 // pixel ranges for wgrad: enough workgroups to fill the chip, at least 4 k tiles each
@@ -312,9 +664,15 @@ hipError_t conv_mfma_fprop(hipStream_t s, int imgs, int H, int W, int cin, int c
                            const uint16_t* wgt, const float* bias, int act, uint16_t* d_out, uint16_t* a_out,
                            const uint16_t* zeros) {
   const int P = imgs * H * W;
-  GatherDesc ad{x, zeros, P, H, W, ilog2(W), cin};
   PlainDesc bd{wgt, 9 * cin, cout, 1 << 30, DBK, 0};
   EpiFprop e{bias, d_out, a_out, act, cout};
+  {
+    PatchDesc pd{x, zeros, H, W, ilog2(W), cin, 0, cin / 8, 0};
+    pd.prof = g_conv_prof;
+    const hipError_t err = launch_patch_conv<false>(s, P, H, W, cin, cout, pd, bd, e);
+    if (err != hipErrorNotSupported) return err;
+  }
+  GatherDesc ad{x, zeros, P, H, W, ilog2(W), cin};
   const int KT = 9 * cin / DBK;
   if (cout % 128 == 0)
     return launch_conv<128, 128, 3, RowGather<128, 4, false>, Plain<128, 4, false>>(s, P, cout, KT, 1, 1, ad, bd, e);
@@ -324,10 +682,16 @@ hipError_t conv_mfma_fprop(hipStream_t s, int imgs, int H, int W, int cin, int c
 hipError_t conv_mfma_dgrad(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* dz,
                            const uint16_t* wb, const uint16_t* d_prev, uint16_t* out, const uint16_t* zeros) {
   const int P = imgs * H * W;
-  GatherDesc ad{dz, zeros, P, H, W, ilog2(W), cout};
   // k tile -> (tap, block of 64 output channels): rows co0.. of W_b, columns tap*Cin..
   PlainDesc bd{wb, 9 * cin, cin, cout / DBK, (long)DBK * 9 * cin, cin};
   EpiDgrad e{d_prev, out, cin};
+  {
+    PatchDesc pd{dz, zeros, H, W, ilog2(W), cout, 0, cout / 8, 0};
+    pd.prof = g_conv_prof;
+    const hipError_t err = launch_patch_conv<true>(s, P, H, W, cout, cin, pd, bd, e);
+    if (err != hipErrorNotSupported) return err;
+  }
+  GatherDesc ad{dz, zeros, P, H, W, ilog2(W), cout};
   const int KT = 9 * cout / DBK;
   if (cin % 128 == 0)
     return launch_conv<128, 128, 3, RowGather<128, 4, true>, Plain<128, 4, true>>(s, P, cin, KT, 1, 1, ad, bd, e);
@@ -337,6 +701,22 @@ hipError_t conv_mfma_dgrad(hipStream_t s, int imgs, int H, int W, int cin, int c
 hipError_t conv_mfma_wgrad(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* dz,
                            const uint16_t* x, float* gW, float* partial, const uint16_t* zeros) {
   const int P = imgs * H * W;
+  const size_t count = (size_t)cout * 9 * cin;
+  if (wgrad_patch_ok(H, W)) {
+    const int px_tiles = P / kWgradBM;
+    const int splits = wgrad_patch_splits(px_tiles, cin, cout);
+    const PatchDesc xd{x, zeros, H, W, ilog2(W), cin, 0, 8, 1};
+    auto kernel = conv_wgrad_patch_kernel<kWgradBM>;
+    static hipError_t attr =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL(kernel, dim3((cin / 64) * (cout / 64), splits), dim3(256), wgrad_patch_lds(W), s, xd, dz, cout, px_tiles,
+                       cin / 64, splits > 1 ? partial : gW);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess || splits == 1) return err;
+    hipLaunchKernelGGL(split_sum_mfma_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, count, splits, partial, gW);
+    return hipGetLastError();
+  }
   const int splits = conv_mfma_wgrad_splits(P, cin, cout);
   const int KT = P / DBK / splits;
   PlainDesc ad{dz, cout, cout, 1 << 30, (long)DBK * cout, 0};
@@ -348,7 +728,6 @@ hipError_t conv_mfma_wgrad(hipStream_t s, int imgs, int H, int W, int cin, int c
   else
     err = launch_conv<64, 64, 4, Plain<64, 4, true>, ColGather<64, 4>>(s, cout, cin, KT, 9, splits, ad, bd, e);
   if (err != hipSuccess || splits == 1) return err;
-  const size_t count = (size_t)cout * 9 * cin;
   hipLaunchKernelGGL(split_sum_mfma_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, count, splits, partial, gW);
   return hipGetLastError();
 }

@@ -178,14 +178,24 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(int M, int N, 
   }
 }
 
+// 16 columns per block; 16 threads share a column (chunks c = q, q+16, ...) and are combined in a
+// fixed order, so that narrow matrices with many chunks do not end in one long serial sum.
 __global__ __launch_bounds__(kThreads) void colsum_final_kernel(int chunks, int N, const float* __restrict__ partials,
                                                                 float* __restrict__ gb) {
-  const int col = blockIdx.x * kThreads + threadIdx.x;
-  if (col >= N) return;
+  __shared__ float sm[16][17];
+  const int cl = threadIdx.x & 15, q = threadIdx.x >> 4;
+  const int col = blockIdx.x * 16 + cl;
   float s = 0.f;
-#pragma unroll 8
-  for (int c = 0; c < chunks; ++c) s += partials[(size_t)c * N + col];
-  gb[col] = s;
+  if (col < N)
+    for (int c = q; c < chunks; c += 16) s += partials[(size_t)c * N + col];
+  sm[q][cl] = s;
+  __syncthreads();
+  if (q == 0 && col < N) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t += sm[i][cl];
+    gb[col] = t;
+  }
 }
 
 }  // namespace
@@ -232,7 +242,7 @@ hipError_t launch_colsum(hipStream_t s, int elt, int M, int N, const void* dz, f
     hipLaunchKernelGGL(colsum_partial_kernel<float>, g1, dim3(kThreads), 0, s, M, N, cs, (const float*)dz, partials);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  hipLaunchKernelGGL(colsum_final_kernel, dim3((N + kThreads - 1) / kThreads), dim3(kThreads), 0, s, cs.chunks, N, partials, gb);
+  hipLaunchKernelGGL(colsum_final_kernel, dim3((N + 15) / 16), dim3(kThreads), 0, s, cs.chunks, N, partials, gb);
   return hipGetLastError();
 }
 

@@ -323,6 +323,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, in
   }
   wait_vmcnt<0>();  // the trailing dummy copies must have landed before LDS is reused
   lds_barrier();    // all waves are done with the last stage
+  if constexpr (Epi::kSwap && NW * wave_epilogue_bytes<TM, TN>() <= 160 * 1024) {
+    if (m0 + wm + WM <= M && n0 + wn + WN <= N && (N & 7) == 0) {
+      float* wave_lds = reinterpret_cast<float*>(lds_raw) + wave * (wave_epilogue_bytes<TM, TN>() / 4);
+      store_tiles_coalesced<TM, TN>(acc, epi, m0 + wm, n0 + wn, lane, wave_lds);
+      return;
+    }
+  }
   store_tiles<TM, TN>(acc, epi, m0 + wm, n0 + wn, M, N, lane);
 }
 
@@ -342,7 +349,10 @@ hipError_t launch_dma(hipStream_t s, int M, int N, int K, const uint16_t* A, int
   constexpr int NW = WGM * WGN;
   using AT = typename DmaSel<BM, NW, A_COL>::type;
   using BT = typename DmaSel<BN, NW, B_COL>::type;
-  constexpr size_t lds_bytes = (size_t)NS * (AT::kBytes + BT::kBytes);
+  constexpr size_t stage_bytes = (size_t)NS * (AT::kBytes + BT::kBytes);
+  constexpr size_t epi_all = (size_t)NW * wave_epilogue_bytes<BM / WGM / 32, BN / WGN / 32>();
+  constexpr size_t epi_bytes = Epi::kSwap && epi_all <= 160 * 1024 ? epi_all : 0;  // wave tiles turned through LDS
+  constexpr size_t lds_bytes = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
   static_assert(lds_bytes <= 160 * 1024, "stages do not fit the LDS of a CU");
   auto kernel = gemm_bf16_dma_kernel<BM, BN, WGM, WGN, NS, A_COL, B_COL, Epi>;
   if (lds_bytes > 64 * 1024) {

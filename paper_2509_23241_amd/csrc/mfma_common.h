@@ -25,6 +25,24 @@ typedef short shortx8 __attribute__((ext_vector_type(8)));
 struct EpiFprop {
   const float* bias; uint16_t* d_out; uint16_t* a_out; int act; int ldc;  // d_out: act'(z) for the backward, or null
   static constexpr bool kSwap = true;
+  // 8 consecutive columns n..n+7 of row m (n and ldc multiples of 8)
+  __device__ __forceinline__ void row8(int m, int n, float (&v)[8]) const {
+    const size_t i = (size_t)m * ldc + n;
+    const float4 b0 = *reinterpret_cast<const float4*>(bias + n), b1 = *reinterpret_cast<const float4*>(bias + n + 4);
+    const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+    float a[8], d[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const ActPair p = act_pair_fast(v[j] + b[j], act);
+      a[j] = p.a;
+      d[j] = p.d;
+    }
+    if (d_out)
+      *reinterpret_cast<uint4*>(d_out + i) =
+          make_uint4(pack_bf16x2(d[0], d[1]), pack_bf16x2(d[2], d[3]), pack_bf16x2(d[4], d[5]), pack_bf16x2(d[6], d[7]));
+    *reinterpret_cast<uint4*>(a_out + i) =
+        make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(a[4], a[5]), pack_bf16x2(a[6], a[7]));
+  }
   __device__ __forceinline__ void quad(int m, int n, int count, float v0, float v1, float v2, float v3) const {
     const size_t i = (size_t)m * ldc + n;
     if (count == 4 && (ldc & 3) == 0) {
@@ -46,6 +64,21 @@ struct EpiFprop {
 struct EpiDgrad {
   const uint16_t* d_prev; uint16_t* out; int ldc;  // d_prev: saved act'(z) of the previous layer, or null
   static constexpr bool kSwap = true;
+  // 8 consecutive columns n..n+7 of row m (n and ldc multiples of 8)
+  __device__ __forceinline__ void row8(int m, int n, float (&v)[8]) const {
+    const size_t i = (size_t)m * ldc + n;
+    if (d_prev) {
+      const uint4 d = *reinterpret_cast<const uint4*>(d_prev + i);
+      const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        v[2 * j] *= __uint_as_float(w[j] << 16);
+        v[2 * j + 1] *= __uint_as_float(w[j] & 0xffff0000u);
+      }
+    }
+    *reinterpret_cast<uint4*>(out + i) =
+        make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+  }
   __device__ __forceinline__ void quad(int m, int n, int count, float v0, float v1, float v2, float v3) const {
     const size_t i = (size_t)m * ldc + n;
     if (count == 4 && (ldc & 3) == 0) {
@@ -100,6 +133,48 @@ __device__ __forceinline__ void store_tiles(const floatx16 (&acc)[TM][TN], const
         }
       }
     }
+}
+
+// bf16 outputs, coalesced.  Straight from the accumulators a lane owns 4 columns of one row, so
+// a store instruction would touch 32 rows with 16 bytes each, and the memory pipeline takes one
+// partial cache line per row: at 64 k tiles per workgroup that is tolerable, for short
+// contractions (convolutions) it costs more than the multiplications.  Here each wave turns its
+// (32*TM) x (32*TN) fp32 tile through a private LDS region (row pitch 32*TN + 4 floats: writes
+// and reads are bank-conflict free) and then walks it row-wise: a lane takes 8 consecutive
+// columns, applies the epilogue and stores 16 bytes, 4*TN lanes per row.  Needs the whole wave
+// tile inside the matrix and N a multiple of 8; the caller falls back to store_tiles otherwise.
+template <int TM, int TN>
+constexpr int wave_epilogue_bytes() { return 32 * TM * (32 * TN + 4) * 4; }
+
+template <int TM, int TN, class Epi>
+__device__ __forceinline__ void store_tiles_coalesced(const floatx16 (&acc)[TM][TN], const Epi& epi, int mbase, int nbase,
+                                                      int lane, float* wave_lds) {
+  constexpr int PITCH = 32 * TN + 4;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float* p = wave_lds + (i * 32 + (lane & 31)) * PITCH + j * 32 + 8 * g + 4 * (lane >> 5);
+        *reinterpret_cast<float4*>(p) =
+            make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+      }
+  // same wave on both sides: LDS operations of a wave complete in order
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  constexpr int kLanesPerRow = 4 * TN;            // 8 columns each
+  constexpr int kRowsPerPass = 64 / kLanesPerRow;
+  const int rsub = lane / kLanesPerRow, c8 = (lane % kLanesPerRow) * 8;
+#pragma unroll
+  for (int r0 = 0; r0 < 32 * TM; r0 += kRowsPerPass) {
+    const int r = r0 + rsub;
+    const float* p = wave_lds + r * PITCH + c8;
+    const float4 lo = *reinterpret_cast<const float4*>(p), hi = *reinterpret_cast<const float4*>(p + 4);
+    float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    epi.row8(mbase + r, nbase + c8, v);
+  }
 }
 
 // acc += A_frag . B_frag, or its transpose when the epilogue wants columns along the registers
