@@ -40,4 +40,12 @@ hipError_t conv_mfma_dgrad(hipStream_t s, int imgs, int H, int W, int cin, int c
 hipError_t conv_mfma_wgrad(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* dz,
                            const uint16_t* x, float* gW, float* partial, const uint16_t* zeros);
 
+// First layer of an image net (cin <= 8, bf16) on a zero-padded [pixel][8 channels] copy x8 of its input.
+bool conv_c8_supported(int imgs, int H, int W, int cin, int cout);
+hipError_t conv_c8_pad(hipStream_t s, size_t pixels, int cin, const uint16_t* x, uint16_t* x8);
+hipError_t conv_c8_fprop(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* x8, const uint16_t* wgt,
+                         const float* bias, int act, uint16_t* d_out, uint16_t* a_out, const uint16_t* zeros);
+hipError_t conv_c8_wgrad(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* dz, const uint16_t* x8,
+                         float* gW, float* partial, const uint16_t* zeros);
+
 }  // namespace tp

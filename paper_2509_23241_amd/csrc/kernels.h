@@ -28,6 +28,8 @@ hipError_t launch_wgrad(hipStream_t s, int elt, int M, int N, int K, const void*
 // partials: scratch of at least colsum_scratch_floats(M, N) floats.
 hipError_t launch_colsum(hipStream_t s, int elt, int M, int N, const void* dz, float* gb, float* partials);
 size_t colsum_scratch_floats(int M, int N);
+// out[i] = sum over z < splits of partial[z*count + i], i < count; fixed summation order.
+hipError_t launch_sum_partials(hipStream_t s, size_t count, int splits, const float* partial, float* out);
 
 // dz = dy (.) d    all [rows x cols] in elt; d = saved act'(z).
 hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* d, void* dz);

@@ -17,6 +17,7 @@
 #include <algorithm>
 
 #include "conv.h"
+#include "kernels.h"
 #include "device_utils.h"
 
 namespace tp {
@@ -129,17 +130,6 @@ __global__ __launch_bounds__(kThreads) void conv_simt_kernel(ConvGeom g, const T
       }
     }
   }
-}
-
-// out[i] = sum over splits of partial[s][i], fixed order
-__global__ __launch_bounds__(kThreads) void split_sum_kernel(size_t count, int splits, const float* __restrict__ partial,
-                                                             float* __restrict__ out) {
-  const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
-  if (i >= count) return;
-  float s = 0.f;
-#pragma unroll 8
-  for (int z = 0; z < splits; ++z) s += partial[(size_t)z * count + i];
-  out[i] = s;
 }
 
 // 2x2 max pooling, stride 2, NHWC; first maximum in row-major window order wins ties.
@@ -262,9 +252,7 @@ hipError_t launch_conv_wgrad(hipStream_t s, int elt, int imgs, int H, int W, int
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const size_t count = (size_t)cout * 9 * cin;
-  hipLaunchKernelGGL(split_sum_kernel, dim3((unsigned)((count + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, count,
-                     splits, partial, gW);
-  return hipGetLastError();
+  return launch_sum_partials(s, count, splits, partial, gW);
 }
 
 hipError_t launch_maxpool_fwd(hipStream_t s, int elt, int imgs, int H, int W, int C, const void* x, void* y) {

@@ -19,9 +19,9 @@
 #include <stdint.h>
 
 #include <algorithm>
-#include <cstdlib>
 
 #include "conv.h"
+#include "kernels.h"
 #include "device_utils.h"
 #include "mfma_common.h"
 
@@ -304,7 +304,6 @@ struct PatchDesc {
   int c0;                 // first channel staged
   int CB;                 // 16-byte chunks staged per pixel (channels staged / 8)
   int tr;                 // 1: layout for transposed reads (pixels are the contraction index)
-  long long* prof = nullptr;
 };
 
 // chunk c of patch pixel pp is stored in slot c ^ patch_swz(pp)
@@ -367,8 +366,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(int P, int N
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  long long t0 = 0, t1 = 0, t2 = 0, t3 = 0;
-  if (pd.prof) t0 = wall_clock64();
   issue_patch<BM, NW>(pd, lds_base, m0, wave, lane);
   BL tb;
   tb.init(bd, n0, wave, lane, 0);
@@ -397,7 +394,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(int P, int N
   for (int kt = 0; kt < KT; ++kt) {
     wait_vmcnt<(NS - 2) * kLoads>();  // the patch copies are older than any stage: they have landed too
     lds_barrier();
-    if (pd.prof && kt == 0) t1 = wall_clock64();
     const uint16_t* lb = stage0 + rd * (BL::kBytes / 2);
     int dh = tap / 3 - 1, dw = tap - (tap / 3) * 3 - 1;
     if (BWD) { dh = -dh; dw = -dw; }
@@ -453,20 +449,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_patch_kernel(int P, int N
   }
   wait_vmcnt<0>();
   lds_barrier();
-  if (pd.prof) t2 = wall_clock64();
   if (n0 + wn + WN <= N && (N & 7) == 0) {  // pixel tiles are always whole
     float* wave_lds = reinterpret_cast<float*>(lds_raw) + wave * (wave_epilogue_bytes<TM, TN>() / 4);
     store_tiles_coalesced<TM, TN>(acc, epi, m0 + wm, n0 + wn, lane, wave_lds);
   } else {
     store_tiles<TM, TN>(acc, epi, m0 + wm, n0 + wn, P, N, lane);
-  }
-  if (pd.prof) {
-    wait_vmcnt<0>();
-    t3 = wall_clock64();
-    if (threadIdx.x == 0) {
-      long long* o = pd.prof + 4 * (size_t)blockIdx.x;
-      o[0] = t0; o[1] = t1; o[2] = t2; o[3] = t3;
-    }
   }
 }
 
@@ -552,18 +539,208 @@ __global__ __launch_bounds__(256) void conv_wgrad_patch_kernel(PatchDesc xd, con
   }
 }
 
+// ================================================================================================
+// First layer of an image net: a handful of input channels (3), padded to 8
+// ================================================================================================
+// With the input stored [pixel][8 channels] (16 bytes per pixel, channels >= Cin zero), one k step
+// of the MFMA (16 values) is two taps x 8 channels: the lane half that holds k 0..7 reads tap
+// 2*kk, the other tap 2*kk + 1, each one 16-byte LDS read of the patch at its shifted pixel.
+// Nine taps fill 4.5 steps; a tenth tap reads a zero pixel.  The whole contraction is 5 steps, so
+// the weights of 64 output channels sit in registers and nothing is streamed: the kernels are
+// bound by writing the outputs (fprop) and by reading dz (wgrad).
+
+constexpr int kC8 = 8;
+
+// patch of [pixel][8] plus one zero pixel behind it; returns its size in bytes (multiple of 1 KB)
+template <int BM, int NW>
+__device__ __forceinline__ int issue_patch_c8(const uint16_t* x8, const uint16_t* zeros, int H, int W, int lw, uint32_t lds_patch,
+                                              int p0, int wave, int lane) {
+  const int PC = W + 2, NPIX = (BM / W + 2) * PC;
+  const int img_px = H * W;
+  const int img = p0 / img_px, h0 = (p0 - img * img_px) >> lw;
+  const int instrs = ((NPIX + 1) * 16 + 1023) / 1024;
+  for (int i = wave; i < instrs; i += NW) {
+    const int pp = i * 64 + lane;
+    const int pr = pp / PC, pc = pp - pr * PC;
+    const int h = h0 + pr - 1, w = pc - 1;
+    const bool valid = pp < NPIX && (unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W;
+    const uint16_t* ptr = valid ? x8 + ((((long)img * H + h) * W + w) << 3) : zeros;
+    dma16_addr(lds_patch + i * 1024, ptr);
+  }
+  return instrs * 1024;
+}
+__host__ __device__ inline int patch_c8_bytes(int BM, int W) { return ((((BM / W + 2) * (W + 2) + 1) * 16 + 1023) / 1024) * 1024; }
+
+// out[p][co0 .. co0+63]: 256 pixels per workgroup, 4 waves x (64 pixels x 64 channels)
+__global__ __launch_bounds__(256) void conv_c8_fprop_kernel(int P, int H, int W, int lw, int cin, int cout,
+                                                           const uint16_t* __restrict__ x8, const uint16_t* __restrict__ zeros,
+                                                           const uint16_t* __restrict__ wgt, EpiFprop epi) {
+  constexpr int BM = 256;
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds_raw[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * 64;
+  issue_patch_c8<BM, 4>(x8, zeros, H, W, lw, lds_addr_of(lds_raw), m0, wave, lane);
+
+  // weights: fragment (kk, j) = channels n0 + 32*j + lane%32, tap 2*kk + lane/32, 8 channel slots
+  bf16x8 bfr[5][2];
+  const int khalf = lane >> 5;
+#pragma unroll
+  for (int kk = 0; kk < 5; ++kk)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int co = n0 + 32 * j + (lane & 31), tap = 2 * kk + khalf;
+      shortx8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (tap < 9 && co < cout) {
+        const uint16_t* wp = wgt + ((size_t)co * 9 + tap) * cin;
+#pragma unroll
+        for (int c = 0; c < kC8; ++c)
+          if (c < cin) v[c] = (short)wp[c];
+      }
+      bfr[kk][j] = __builtin_bit_cast(bf16x8, v);
+    }
+
+  const int PC = W + 2, NPIX = (BM / W + 2) * PC;
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  int ppc[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int q = wave * 64 + i * 32 + (lane & 31);
+    ppc[i] = ((q >> lw) + 1) * PC + (q & (W - 1)) + 1;
+  }
+  wait_vmcnt<0>();
+  __syncthreads();
+#pragma unroll
+  for (int kk = 0; kk < 5; ++kk) {
+    const int tap = 2 * kk + khalf;
+    const int tapoff = (tap / 3 - 1) * PC + (tap % 3 - 1);
+    bf16x8 af[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int pp = tap < 9 ? ppc[i] + tapoff : NPIX;  // the zero pixel behind the patch
+      af[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(lds_raw + pp * 8));
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) acc[i][j] = mma<true>(af[i], bfr[kk][j], acc[i][j]);
+  }
+  __syncthreads();  // the patch is dead: its LDS is reused for the output tiles
+  if (n0 + 64 <= cout && (cout & 7) == 0) {
+    float* wave_lds = reinterpret_cast<float*>(lds_raw) + wave * (wave_epilogue_bytes<2, 2>() / 4);
+    store_tiles_coalesced<2, 2>(acc, epi, m0 + wave * 64, n0, lane, wave_lds);
+  } else {
+    store_tiles<2, 2>(acc, epi, m0 + wave * 64, n0, P, cout, lane);
+  }
+}
+
+// partial dW[co0..co0+63][tap][c] over the pixel tiles split, split + splits, ...; 128 pixels per tile.
+// Wave w: output channels 32*(w&1).., columns (tap, c) 0..63 (w < 2) or 64..95 (w >= 2; taps 8..11,
+// of which only tap 8 exists).
+__global__ __launch_bounds__(256) void conv_c8_wgrad_kernel(int H, int W, int lw, int cin, int cout, int px_tiles,
+                                                           const uint16_t* __restrict__ x8, const uint16_t* __restrict__ zeros,
+                                                           const uint16_t* __restrict__ dz, float* __restrict__ out) {
+  constexpr int BM = 128, NW = 4;
+  using DZ = ColDma<64, NW>;
+  constexpr int kDzInstr = BM * 8 / 64 / NW;
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds_raw[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int cob = blockIdx.x, split = blockIdx.y, splits = gridDim.y;
+  const int pbytes = patch_c8_bytes(BM, W);
+  const int buf_bytes = pbytes + BM * 128;
+  const uint32_t lds_base = lds_addr_of(lds_raw);
+  const int PC = W + 2, NPIX = (BM / W + 2) * PC;
+  const int rb_co = (wave & 1) * 32;
+  const int ntile0 = wave < 2 ? 0 : 2, ntiles = wave < 2 ? 2 : 1;
+
+  floatx16 acc[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+  uint32_t dzoff[kDzInstr];
+#pragma unroll
+  for (int i = 0; i < kDzInstr; ++i) {
+    const int flat = 64 * (wave + NW * i) + lane;
+    const int k = flat >> 3, c = (flat & 7) ^ DZ::swz(k);
+    dzoff[i] = (uint32_t)(((size_t)k * cout + cob * 64 + c * 8) * 2);
+  }
+  auto issue_tile = [&](int tile, int buf) {
+    const uint32_t dst = lds_base + buf * buf_bytes;
+    issue_patch_c8<BM, NW>(x8, zeros, H, W, lw, dst, tile * BM, wave, lane);
+    const uint16_t* src = dz + (size_t)tile * BM * cout;
+#pragma unroll
+    for (int i = 0; i < kDzInstr; ++i) dma16(dst + pbytes + (wave + NW * i) * 1024, src, dzoff[i]);
+  };
+  if (split < px_tiles) issue_tile(split, 0);
+  int buf = 0;
+  const int g = lane >> 4, s = lane & 15;
+  for (int tile = split; tile < px_tiles; tile += splits) {
+    wait_vmcnt<0>();
+    lds_barrier();
+    if (tile + splits < px_tiles) issue_tile(tile + splits, buf ^ 1);
+    const uint16_t* lp = lds_raw + buf * (buf_bytes / 2);
+    const uint16_t* ldz = lp + pbytes / 2;
+#pragma unroll 2
+    for (int kk = 0; kk < BM / 16; ++kk) {
+      const bf16x8 a = DZ::frag(ldz, rb_co, kk, lane);
+      const int kq = kk * 16 + 8 * (g >> 1) + (s >> 2);
+      const int ppc = ((kq >> lw) + 1) * PC + (kq & (W - 1)) + 1;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        if (t < ntiles) {
+          const int col = (ntile0 + t) * 32 + 16 * (g & 1) + 4 * (s & 3);
+          const int tap = col >> 3;
+          const int tapoff = (tap / 3 - 1) * PC + (tap % 3 - 1);
+          typedef __attribute__((address_space(3))) shortx4* lds_ptr;
+          // rows kq and kq + 4 of the lane's 4 columns; taps past the ninth read the zero pixel
+          const uint16_t* p0 = lp + (tap < 9 ? ppc + tapoff : NPIX) * 8 + (col & 4);
+          const uint16_t* p1 = lp + (tap < 9 ? ppc + 4 + tapoff : NPIX) * 8 + (col & 4);
+          const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0));
+          const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p1));
+          const shortx8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          acc[t] = mma<false>(a, __builtin_bit_cast(bf16x8, v), acc[t]);
+        }
+      }
+    }
+    buf ^= 1;
+  }
+  // accumulator element r: row co = rb_co + 8*(r/4) + 4*(lane/32) + r%4, column lane%32 of the tile
+  float* o = out + (size_t)split * cout * 9 * cin;
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    if (t >= ntiles) continue;
+    const int col = (ntile0 + t) * 32 + (lane & 31);
+    const int tap = col >> 3, c = col & 7;
+    if (tap >= 9 || c >= cin) continue;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int co = cob * 64 + rb_co + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      if (co < cout) o[((size_t)co * 9 + tap) * cin + c] = acc[t][r];
+    }
+  }
+}
+
+// x[P][cin] -> x8[P][8], channels >= cin zero
+__global__ __launch_bounds__(256) void pad_channels_kernel(size_t pixels, int cin, const uint16_t* __restrict__ x,
+                                                           uint16_t* __restrict__ x8) {
+  for (size_t p = (size_t)blockIdx.x * 256 + threadIdx.x; p < pixels; p += (size_t)gridDim.x * 256) {
+    shortx8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int c = 0; c < kC8; ++c)
+      if (c < cin) v[c] = (short)x[p * cin + c];
+    *reinterpret_cast<shortx8*>(x8 + p * 8) = v;
+  }
+}
+
 inline bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 inline int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
-
-__global__ __launch_bounds__(256) void split_sum_mfma_kernel(size_t count, int splits, const float* __restrict__ partial,
-                                                             float* __restrict__ out) {
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= count) return;
-  float s = 0.f;
-#pragma unroll 8
-  for (int z = 0; z < splits; ++z) s += partial[(size_t)z * count + i];
-  out[i] = s;
-}
 
 }  // namespace
 
@@ -604,9 +781,6 @@ hipError_t launch_patch_conv(hipStream_t s, int P, int H, int W, int C, int N, c
   using B = PatchCfg<256, 64, 4, 2, 3, BWD, Epi>;
   using Cc = PatchCfg<128, 128, 2, 2, 3, BWD, Epi>;
   using D = PatchCfg<128, 64, 2, 2, 4, BWD, Epi>;
-  using E = PatchCfg<128, 64, 2, 2, 3, BWD, Epi>;
-  using F = PatchCfg<128, 64, 2, 2, 2, BWD, Epi>;
-  using G = PatchCfg<128, 128, 2, 2, 2, BWD, Epi>;
   const bool wide = N % 128 == 0;
   const bool ok[4] = {wide && A::ok(H, W, C), B::ok(H, W, C), wide && Cc::ok(H, W, C), D::ok(H, W, C)};
   const long tiles[4] = {A::tiles(P, N), B::tiles(P, N), Cc::tiles(P, N), D::tiles(P, N)};
@@ -616,11 +790,6 @@ hipError_t launch_patch_conv(hipStream_t s, int P, int H, int W, int C, int N, c
   if (pick < 0)
     for (int i = 0; i < 4; ++i)
       if (ok[i] && (pick < 0 || tiles[i] > tiles[pick])) pick = i;
-  static const int forced = getenv("TP_CONV_TILE") ? atoi(getenv("TP_CONV_TILE")) : -1;
-  if (forced >= 0) pick = forced;
-  if (pick == 4) return E::launch(s, P, N, pd, bd, e);
-  if (pick == 5) return F::launch(s, P, N, pd, bd, e);
-  if (pick == 6) return G::launch(s, P, N, pd, bd, e);
   switch (pick) {
     case 0: return A::launch(s, P, N, pd, bd, e);
     case 1: return B::launch(s, P, N, pd, bd, e);
@@ -638,8 +807,6 @@ inline int wgrad_patch_splits(long px_tiles, int cin, int cout) {
   return (int)std::max(1l, std::min(px_tiles, 256 / blocks));
 }
 
-long long* g_conv_prof = nullptr;
-
 bool conv_mfma_supported(int imgs, int H, int W, int cin, int cout) {
   const long P = (long)imgs * H * W;
   return pow2(H) && pow2(W) && H <= 32768 && W <= 32768 && cin % 64 == 0 && cout % 64 == 0 && P % 64 == 0 &&
@@ -648,7 +815,8 @@ bool conv_mfma_supported(int imgs, int H, int W, int cin, int cout) {
 
 // most partial sums either matrix-core wgrad kernel may write for this layer
 int conv_mfma_wgrad_max_splits(int pixels, int cin, int cout) {
-  return std::max(conv_mfma_wgrad_splits(pixels, cin, cout), wgrad_patch_splits(pixels / kWgradBM, cin, cout));
+  const int c8 = cin <= 8 && cout % 64 == 0 ? std::max(1, std::min(pixels / 128, 512 / (cout / 64))) : 1;
+  return std::max({conv_mfma_wgrad_splits(pixels, cin, cout), wgrad_patch_splits(pixels / kWgradBM, cin, cout), c8});
 }
 
 // pixel ranges for wgrad: enough workgroups to fill the chip, at least 4 k tiles each
@@ -667,8 +835,7 @@ hipError_t conv_mfma_fprop(hipStream_t s, int imgs, int H, int W, int cin, int c
   PlainDesc bd{wgt, 9 * cin, cout, 1 << 30, DBK, 0};
   EpiFprop e{bias, d_out, a_out, act, cout};
   {
-    PatchDesc pd{x, zeros, H, W, ilog2(W), cin, 0, cin / 8, 0};
-    pd.prof = g_conv_prof;
+    const PatchDesc pd{x, zeros, H, W, ilog2(W), cin, 0, cin / 8, 0};
     const hipError_t err = launch_patch_conv<false>(s, P, H, W, cin, cout, pd, bd, e);
     if (err != hipErrorNotSupported) return err;
   }
@@ -686,8 +853,7 @@ hipError_t conv_mfma_dgrad(hipStream_t s, int imgs, int H, int W, int cin, int c
   PlainDesc bd{wb, 9 * cin, cin, cout / DBK, (long)DBK * 9 * cin, cin};
   EpiDgrad e{d_prev, out, cin};
   {
-    PatchDesc pd{dz, zeros, H, W, ilog2(W), cout, 0, cout / 8, 0};
-    pd.prof = g_conv_prof;
+    const PatchDesc pd{dz, zeros, H, W, ilog2(W), cout, 0, cout / 8, 0};
     const hipError_t err = launch_patch_conv<true>(s, P, H, W, cout, cin, pd, bd, e);
     if (err != hipErrorNotSupported) return err;
   }
@@ -714,8 +880,7 @@ hipError_t conv_mfma_wgrad(hipStream_t s, int imgs, int H, int W, int cin, int c
                        cin / 64, splits > 1 ? partial : gW);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || splits == 1) return err;
-    hipLaunchKernelGGL(split_sum_mfma_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, count, splits, partial, gW);
-    return hipGetLastError();
+    return launch_sum_partials(s, count, splits, partial, gW);
   }
   const int splits = conv_mfma_wgrad_splits(P, cin, cout);
   const int KT = P / DBK / splits;
@@ -728,8 +893,53 @@ hipError_t conv_mfma_wgrad(hipStream_t s, int imgs, int H, int W, int cin, int c
   else
     err = launch_conv<64, 64, 4, Plain<64, 4, true>, ColGather<64, 4>>(s, cout, cin, KT, 9, splits, ad, bd, e);
   if (err != hipSuccess || splits == 1) return err;
-  hipLaunchKernelGGL(split_sum_mfma_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, count, splits, partial, gW);
+  return launch_sum_partials(s, count, splits, partial, gW);
+}
+
+// ---- first layer (cin <= 8) on a padded [pixel][8] copy of the input -------------------------
+bool conv_c8_supported(int imgs, int H, int W, int cin, int cout) {
+  const long P = (long)imgs * H * W;
+  return cin >= 1 && cin <= kC8 && cout % 64 == 0 && patch_shape_ok(H, W, 256) && patch_shape_ok(H, W, 128) &&
+         P * 16 < (1l << 31) &&
+         P * cout * 2 < (1l << 31);
+}
+
+hipError_t conv_c8_pad(hipStream_t s, size_t pixels, int cin, const uint16_t* x, uint16_t* x8) {
+  const unsigned blocks = (unsigned)std::min<size_t>((pixels + 255) / 256, 4096);
+  hipLaunchKernelGGL(pad_channels_kernel, dim3(blocks), dim3(256), 0, s, pixels, cin, x, x8);
   return hipGetLastError();
+}
+
+hipError_t conv_c8_fprop(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* x8, const uint16_t* wgt,
+                         const float* bias, int act, uint16_t* d_out, uint16_t* a_out, const uint16_t* zeros) {
+  const int P = imgs * H * W;
+  const size_t lds = std::max<size_t>(patch_c8_bytes(256, W), 4 * wave_epilogue_bytes<2, 2>());
+  static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_c8_fprop_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
+  if (attr != hipSuccess) return attr;
+  if (lds > (size_t)kMaxLds) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(conv_c8_fprop_kernel, dim3(P / 256, cout / 64), dim3(256), lds, s, P, H, W, ilog2(W), cin, cout, x8, zeros,
+                     wgt, EpiFprop{bias, d_out, a_out, act, cout});
+  return hipGetLastError();
+}
+
+int conv_c8_wgrad_splits(int pixels, int cout) { return std::max(1, std::min(pixels / 128, 512 / (cout / 64))); }
+
+hipError_t conv_c8_wgrad(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* dz, const uint16_t* x8,
+                         float* gW, float* partial, const uint16_t* zeros) {
+  const int P = imgs * H * W;
+  const int px_tiles = P / 128;
+  const int splits = conv_c8_wgrad_splits(P, cout);
+  const size_t lds = 2 * ((size_t)patch_c8_bytes(128, W) + 128 * 128);
+  static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_c8_wgrad_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
+  if (attr != hipSuccess) return attr;
+  if (lds > (size_t)kMaxLds) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(conv_c8_wgrad_kernel, dim3(cout / 64, splits), dim3(256), lds, s, H, W, ilog2(W), cin, cout, px_tiles, x8,
+                     zeros, dz, splits > 1 ? partial : gW);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess || splits == 1) return err;
+  return launch_sum_partials(s, (size_t)cout * 9 * cin, splits, partial, gW);
 }
 
 }  // namespace tp

@@ -178,23 +178,34 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(int M, int N, 
   }
 }
 
-// 16 columns per block; 16 threads share a column (chunks c = q, q+16, ...) and are combined in a
-// fixed order, so that narrow matrices with many chunks do not end in one long serial sum.
-__global__ __launch_bounds__(kThreads) void colsum_final_kernel(int chunks, int N, const float* __restrict__ partials,
-                                                                float* __restrict__ gb) {
-  __shared__ float sm[16][17];
-  const int cl = threadIdx.x & 15, q = threadIdx.x >> 4;
-  const int col = blockIdx.x * 16 + cl;
-  float s = 0.f;
-  if (col < N)
-    for (int c = q; c < chunks; c += 16) s += partials[(size_t)c * N + col];
-  sm[q][cl] = s;
+// Sum of partial results.  A block covers IL = 256/ZG consecutive outputs with ZG threads each:
+// thread (zg, il) adds partials zg, zg + ZG, ... of output il, the ZG sums are combined through LDS
+// in a fixed order.  Large outputs take few threads per output (whole cache lines per partial
+// row, enough blocks anyway); small ones take many, so that a thousand partials do not end up
+// as one long chain of dependent loads.
+template <int ZG>
+__global__ __launch_bounds__(kThreads) void sum_partials_kernel(size_t count, int splits, const float* __restrict__ partial,
+                                                                float* __restrict__ out) {
+  constexpr int IL = kThreads / ZG;
+  __shared__ float sm[ZG][IL + 1];
+  const int il = threadIdx.x % IL, zg = threadIdx.x / IL;
+  const size_t i = (size_t)blockIdx.x * IL + il;
+  float s0 = 0.f, s1 = 0.f;
+  if (i < count) {
+    int z = zg;
+    for (; z + ZG < splits; z += 2 * ZG) {  // two independent chains
+      s0 += partial[(size_t)z * count + i];
+      s1 += partial[(size_t)(z + ZG) * count + i];
+    }
+    if (z < splits) s0 += partial[(size_t)z * count + i];
+  }
+  sm[zg][il] = s0 + s1;
   __syncthreads();
-  if (q == 0 && col < N) {
+  if (zg == 0 && i < count) {
     float t = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) t += sm[i][cl];
-    gb[col] = t;
+    for (int k = 0; k < ZG; ++k) t += sm[k][il];
+    out[i] = t;
   }
 }
 
@@ -233,6 +244,17 @@ hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void*
   return simt<EPI_DGRAD>(s, elt, M, K, N, dz, N, 1, Wb, K, 1, e);
 }
 
+hipError_t launch_sum_partials(hipStream_t s, size_t count, int splits, const float* partial, float* out) {
+  auto blocks = [&](int il) { return dim3((unsigned)((count + il - 1) / il)); };
+  if (count >= 512 * 64 || splits <= 8)
+    hipLaunchKernelGGL(sum_partials_kernel<4>, blocks(64), dim3(kThreads), 0, s, count, splits, partial, out);
+  else if (count >= 512 * 16)
+    hipLaunchKernelGGL(sum_partials_kernel<16>, blocks(16), dim3(kThreads), 0, s, count, splits, partial, out);
+  else
+    hipLaunchKernelGGL(sum_partials_kernel<64>, blocks(4), dim3(kThreads), 0, s, count, splits, partial, out);
+  return hipGetLastError();
+}
+
 hipError_t launch_colsum(hipStream_t s, int elt, int M, int N, const void* dz, float* gb, float* partials) {
   const ColsumShape cs = colsum_shape(M, N, elt == ELT_BF16 ? 8 : 4);
   dim3 g1(cs.col_blocks, cs.chunks);
@@ -242,8 +264,7 @@ hipError_t launch_colsum(hipStream_t s, int elt, int M, int N, const void* dz, f
     hipLaunchKernelGGL(colsum_partial_kernel<float>, g1, dim3(kThreads), 0, s, M, N, cs, (const float*)dz, partials);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  hipLaunchKernelGGL(colsum_final_kernel, dim3((N + 15) / 16), dim3(kThreads), 0, s, cs.chunks, N, partials, gb);
-  return hipGetLastError();
+  return launch_sum_partials(s, (size_t)N, cs.chunks, partials, gb);
 }
 
 hipError_t launch_wgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* x, float* gW) {

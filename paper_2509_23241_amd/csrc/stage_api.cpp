@@ -38,6 +38,7 @@ struct LayerPlan {
   uint64_t w_elems;              // elements of the weight tensor (0: no parameters)
   uint64_t w_off, b_off;  // elements inside one weight version
   uint64_t x_off, z_off;  // bytes inside one activation slot; z_off: saved act'(z) (UINT64_MAX: none)
+  uint64_t xpad_off = UINT64_MAX;  // first image layer in bf16: the input again, padded to 8 channels per pixel
 };
 
 struct Slot {
@@ -158,6 +159,12 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
       act += round_up(rows * lp.out_elems * p->elt_size, 256);
     } else {
       lp.z_off = UINT64_MAX;
+    }
+    if (l == 0 && L.type == TP_LAYER_CONV2D && d->dtype == TP_BF16 &&
+        tp::conv_c8_supported((int)rows, L.geom[0], L.geom[1], L.in_features, L.out_features) &&
+        tp::conv_c8_supported(d->mb, L.geom[0], L.geom[1], L.in_features, L.out_features)) {
+      lp.xpad_off = act;
+      act += round_up(rows * L.geom[0] * L.geom[1] * 8 * p->elt_size, 256);
     }
     max_feat = std::max<uint64_t>(max_feat, std::max(lp.in_elems, lp.out_elems));
     p->sizes.w_offset[l] = lp.w_off;
@@ -484,6 +491,20 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
                                need_copy ? x_saved : nullptr));
       continue;
     }
+    if (lp.xpad_off != UINT64_MAX) {
+      // few-channel first layer: what is kept for the backward pass is the 8-channel padded input
+      const size_t px = (size_t)lp.d.geom[0] * lp.d.geom[1];
+      uint16_t* x8 = (uint16_t*)(aslot + lp.xpad_off) + row0 * px * 8;
+      {
+        ProfScope ps(st, TP_K_COPY);
+        HIP_TRY(tp::conv_c8_pad(st->stream, d.mb * px, lp.d.in_features, (const uint16_t*)x_in, x8));
+      }
+      ProfScope ps(st, TP_K_FPROP);
+      HIP_TRY(tp::conv_c8_fprop(st->stream, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, lp.d.out_features, x8,
+                                (const uint16_t*)(wcopy + lp.w_off * es), master + lp.b_off, lp.d.act, (uint16_t*)z_out,
+                                (uint16_t*)a_out, (const uint16_t*)st->zeros()));
+      continue;
+    }
     if (need_copy) {
       ProfScope ps(st, TP_K_COPY);
       HIP_TRY(tp::launch_copy(st->stream, x_dev, x_saved, (size_t)d.mb * lp.in_elems * es));
@@ -608,6 +629,10 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
         if (lp.d.type == TP_LAYER_DENSE)
           HIP_TRY(tp::launch_wgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, aslot + lp.x_off,
                                    g + lp.w_off));
+        else if (lp.xpad_off != UINT64_MAX)
+          HIP_TRY(tp::conv_c8_wgrad(st->stream, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, lp.d.out_features,
+                                    (const uint16_t*)dz, (const uint16_t*)(aslot + lp.xpad_off), g + lp.w_off, st->partials(),
+                                    (const uint16_t*)st->zeros()));
         else
           HIP_TRY(tp::launch_conv_wgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features,
                                         lp.d.out_features, dz, aslot + lp.x_off, g + lp.w_off, st->partials(),

@@ -121,6 +121,14 @@ def test_conv_matrix_core_tile_variants():
     print(_run_stage(specs, "convtiles_bf16", "bf16", mb=6, n=2, depth=2, minibatches=3))
 
 
+def test_first_layer_few_channels_bf16():
+    # a first layer with 5 input channels (padded to 8 inside the stage), 128 output channels = two
+    # channel blocks, input gradient requested: the few-channel forward and weight-gradient kernels next
+    # to the generic input-gradient kernel
+    specs = (W.Conv2d(5, 128, 16, 16, "gelu"), W.Conv2d(128, 64, 16, 16, "none"))
+    print(_run_stage(specs, "conv5ch_bf16", "bf16", mb=2, n=2, depth=2, minibatches=3, needs_dx=True))
+
+
 def test_vgg_first_stage_reduced_bf16():
     # the VGG-style stage 0 (conv3-64, conv3-64, pool, conv3-128, conv3-128, pool) on 16x16 images,
     # micro-batch 4 x 2; GELU instead of ReLU keeps the bf16 comparison away from the ReLU kink
