@@ -46,8 +46,10 @@ def dense_backward(dz, x, W_b):
     db[o]    = sum_i dz[i, o]
     dx[i, k] = sum_o dz[i, o] * W_b[o, k] (W_b: the weights the method
                                            prescribes for the backward pass)
+    i runs over every leading index (samples, and token positions if there are any).
     """
-    return dz.T @ x, dz.sum(axis=0), dz @ W_b
+    dz2, x2 = dz.reshape(-1, dz.shape[-1]), x.reshape(-1, x.shape[-1])
+    return dz2.T @ x2, dz2.sum(axis=0), dz @ W_b
 
 
 def softmax_cross_entropy(logits, labels, denom):
@@ -125,3 +127,76 @@ def maxpool2_backward(dy, idx, in_shape):
     dwin = np.zeros((B, H // 2, Wd // 2, 4, C), dtype=np.float64)
     np.put_along_axis(dwin, idx[:, :, :, None, :], dy[:, :, :, None, :], axis=3)
     return dwin.reshape(B, H // 2, Wd // 2, 2, 2, C).transpose(0, 1, 3, 2, 4, 5).reshape(B, H, Wd, C)
+
+
+# ---------------------------------------------------------------------------
+# Layers of the transformer-shaped workload (layer normalisation, causal
+# multi-head self-attention); standard definitions, the paper prescribes none.
+# ---------------------------------------------------------------------------
+
+LN_EPS = 1e-5
+
+
+def layernorm_forward(x, gamma, beta, eps=LN_EPS):
+    """y[..., d] = gamma[d] * (x[..., d] - mean) / sqrt(var + eps) + beta[d], mean/var over the last axis.
+    Returns y and what the backward pass needs: the normalised values and 1/sqrt(var + eps)."""
+    mu = x.mean(axis=-1, keepdims=True)
+    xc = x - mu
+    var = (xc * xc).mean(axis=-1, keepdims=True)
+    rstd = 1.0 / np.sqrt(var + eps)
+    xhat = xc * rstd
+    return xhat * gamma + beta, xhat, rstd
+
+
+def layernorm_backward(dy, xhat, rstd, gamma_b):
+    """Gradients of layernorm_forward; gamma_b is the scale the backward pass is told to use."""
+    D = dy.shape[-1]
+    dgamma = (dy * xhat).reshape(-1, D).sum(axis=0)
+    dbeta = dy.reshape(-1, D).sum(axis=0)
+    dxhat = dy * gamma_b
+    dx = rstd * (dxhat - dxhat.mean(axis=-1, keepdims=True) - xhat * (dxhat * xhat).mean(axis=-1, keepdims=True))
+    return dgamma, dbeta, dx
+
+
+def _split_heads(qkv, heads):
+    B, S, D3 = qkv.shape
+    D = D3 // 3
+    dh = D // heads
+    q, k, v = (qkv[:, :, i * D:(i + 1) * D].reshape(B, S, heads, dh).transpose(0, 2, 1, 3) for i in range(3))
+    return q, k, v, dh
+
+
+def attention_probabilities(qkv, heads):
+    """softmax over keys j <= i of q_i . k_j / sqrt(head dim), per sequence and head: [B, heads, S, S]."""
+    q, k, _, dh = _split_heads(qkv, heads)
+    S = qkv.shape[1]
+    s = q @ k.transpose(0, 1, 3, 2) / np.sqrt(dh)
+    s = np.where(np.tril(np.ones((S, S), dtype=bool)), s, -np.inf)
+    s = s - s.max(axis=-1, keepdims=True)
+    e = np.exp(s)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def attention_forward(qkv, heads):
+    """Causal multi-head self-attention.  qkv: [B, S, 3*D] = (queries | keys | values), each D = heads * dh
+    wide with head h in columns h*dh .. (h+1)*dh - 1.  Returns [B, S, D]."""
+    B, S, D3 = qkv.shape
+    _, _, v, _ = _split_heads(qkv, heads)
+    p = attention_probabilities(qkv, heads)
+    return (p @ v).transpose(0, 2, 1, 3).reshape(B, S, D3 // 3)
+
+
+def attention_backward(dout, qkv, heads):
+    """Gradient of attention_forward with respect to qkv."""
+    B, S, D3 = qkv.shape
+    D = D3 // 3
+    q, k, v, dh = _split_heads(qkv, heads)
+    p = attention_probabilities(qkv, heads)
+    do = dout.reshape(B, S, heads, dh).transpose(0, 2, 1, 3)
+    dv = p.transpose(0, 1, 3, 2) @ do
+    dp = do @ v.transpose(0, 1, 3, 2)
+    ds = p * (dp - (dp * p).sum(axis=-1, keepdims=True))
+    dq = ds @ k / np.sqrt(dh)
+    dk = ds.transpose(0, 1, 3, 2) @ q / np.sqrt(dh)
+    back = lambda t: t.transpose(0, 2, 1, 3).reshape(B, S, D)
+    return np.concatenate([back(dq), back(dk), back(dv)], axis=-1)

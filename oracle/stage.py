@@ -46,7 +46,7 @@ class Stage:
         # position of each layer's weight in the flat parameter list (None: layer has no parameters)
         self.pidx, nxt = [], 0
         for spec in self.specs:
-            if getattr(spec, "kind", "dense") == "pool":
+            if getattr(spec, "kind", "dense") in ("pool", "attn", "res"):
                 self.pidx.append(None)
             else:
                 self.pidx.append(nxt)
@@ -85,6 +85,7 @@ class Stage:
         rec["versions"].append(self.latest)
         saved = []
         a = np.asarray(x, dtype=np.float64)
+        skip = None                                        # activation remembered by a residual "begin"
         for li, spec in enumerate(self.specs):
             kind = getattr(spec, "kind", "dense")
             pi = self.pidx[li]
@@ -92,6 +93,22 @@ class Stage:
                 y, idx = L.maxpool2_forward(a)
                 saved.append((a.shape, idx))
                 a = y
+                continue
+            if kind == "res":
+                if spec.mark == "begin":
+                    skip = a
+                else:
+                    a = self.q(a + skip)
+                saved.append(None)
+                continue
+            if kind == "ln":
+                y, xhat, rstd = L.layernorm_forward(a, W[pi], W[pi + 1])
+                saved.append((xhat, rstd))
+                a = self.q(y)
+                continue
+            if kind == "attn":
+                saved.append((a,))
+                a = self.q(L.attention_forward(a, spec.heads))
                 continue
             if kind == "conv":
                 z = L.conv2d_forward(a, W[pi], W[pi + 1], spec.stride, spec.pad)
@@ -137,6 +154,7 @@ class Stage:
         for ub in range(self.n):                           # one backward, all micro-batches
             da = dy[ub * rows:(ub + 1) * rows]
             saved = rec["saved"][ub]
+            dskip = None                                   # gradient that flows around a residual branch
             for li in reversed(range(len(self.specs))):
                 spec = self.specs[li]
                 kind = getattr(spec, "kind", "dense")
@@ -144,6 +162,22 @@ class Stage:
                 if kind == "pool":
                     in_shape, idx = saved[li]
                     da = L.maxpool2_backward(da, idx, in_shape)
+                    continue
+                if kind == "res":
+                    if spec.mark == "add":
+                        dskip = da
+                    else:
+                        da = self.q(da + dskip)
+                    continue
+                if kind == "ln":
+                    xhat, rstd = saved[li]
+                    dgamma, dbeta, da = L.layernorm_backward(da, xhat, rstd, W_b[pi])
+                    g[pi] += dgamma
+                    g[pi + 1] += dbeta
+                    da = self.q(da)
+                    continue
+                if kind == "attn":
+                    da = self.q(L.attention_backward(da, saved[li][0], spec.heads))
                     continue
                 x_in, z = saved[li]
                 dz = self.q(da * L.act_derivative(z, spec.act))

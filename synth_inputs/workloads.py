@@ -22,22 +22,90 @@ from . import GLOBAL_SEED, labels as _labels, normal as _normal, round_bf16, rou
 
 @dataclass(frozen=True)
 class Dense:
+    """Fully connected layer; with tokens > 1 it is applied to every one of `tokens` positions of a sample
+    (activations [tokens, features] per sample)."""
     in_features: int
     out_features: int
     act: str  # "relu" | "gelu" | "none"
     kind: str = "dense"
+    tokens: int = 1
 
     def param_shapes(self):
         return [(self.out_features, self.in_features), (self.out_features,)]
 
     def in_shape(self):
-        return (self.in_features,)
+        return (self.in_features,) if self.tokens == 1 else (self.tokens, self.in_features)
 
     def out_shape(self):
-        return (self.out_features,)
+        return (self.out_features,) if self.tokens == 1 else (self.tokens, self.out_features)
 
     def out_dim(self):
-        return self.out_features
+        return self.tokens * self.out_features
+
+
+@dataclass(frozen=True)
+class LayerNorm:
+    """Layer normalisation over the feature axis of [tokens, d] samples; parameters scale and shift."""
+    d: int
+    tokens: int
+    kind: str = "ln"
+    act: str = "none"
+
+    def param_shapes(self):
+        return [(self.d,), (self.d,)]
+
+    def in_shape(self):
+        return (self.tokens, self.d)
+
+    def out_shape(self):
+        return (self.tokens, self.d)
+
+    def out_dim(self):
+        return self.tokens * self.d
+
+
+@dataclass(frozen=True)
+class Attention:
+    """Causal multi-head self-attention on [tokens, 3*d] (queries | keys | values) -> [tokens, d]; no parameters."""
+    d: int
+    heads: int
+    tokens: int
+    kind: str = "attn"
+    act: str = "none"
+
+    def param_shapes(self):
+        return []
+
+    def in_shape(self):
+        return (self.tokens, 3 * self.d)
+
+    def out_shape(self):
+        return (self.tokens, self.d)
+
+    def out_dim(self):
+        return self.tokens * self.d
+
+
+@dataclass(frozen=True)
+class Residual:
+    """mark = "begin": remember the current activation; mark = "add": add the remembered one. No parameters."""
+    d: int
+    tokens: int
+    mark: str
+    kind: str = "res"
+    act: str = "none"
+
+    def param_shapes(self):
+        return []
+
+    def in_shape(self):
+        return (self.tokens, self.d)
+
+    def out_shape(self):
+        return (self.tokens, self.d)
+
+    def out_dim(self):
+        return self.tokens * self.d
 
 
 @dataclass(frozen=True)
@@ -167,6 +235,22 @@ def vgg_stage0(mb: int = 64, n: int = 4, size: int = 32, c1: int = 64, c2: int =
                     classes=classes)
 
 
+def transformer_block(d: int, heads: int, ffn: int, tokens: int) -> tuple:
+    """Pre-norm decoder block: x + proj(attn(qkv(LN(x)))), then x + ffn2(gelu(ffn1(LN(x))))."""
+    return (Residual(d, tokens, "begin"), LayerNorm(d, tokens), Dense(d, 3 * d, "none", tokens=tokens),
+            Attention(d, heads, tokens), Dense(d, d, "none", tokens=tokens), Residual(d, tokens, "add"),
+            Residual(d, tokens, "begin"), LayerNorm(d, tokens), Dense(d, ffn, "gelu", tokens=tokens),
+            Dense(ffn, d, "none", tokens=tokens), Residual(d, tokens, "add"))
+
+
+def transformer_stage(d: int = 2048, heads: int = 16, ffn: int = 8192, tokens: int = 1024, layers: int = 4, mb: int = 8,
+                      n: int = 4, dtype: str = "bf16") -> Workload:
+    """An interior stage of a decoder-only transformer: `layers` blocks on [tokens, d] hidden states, as stage 1
+    of a 4-stage pipeline.  Only this stage is described."""
+    blocks = tuple(l for _ in range(layers) for l in transformer_block(d, heads, ffn, tokens))
+    return Workload(name=f"tfm{d}x{layers}_{dtype}_s1", dtype=dtype, stages=((), blocks, (), ()), mb=mb, n=n, classes=2)
+
+
 def with_lambda(w: Workload, lam: float) -> Workload:
     return replace(w, lam=lam)
 
@@ -187,6 +271,10 @@ def init_params(w: Workload, s: int) -> List[np.ndarray]:
         if not layer.param_shapes():
             continue
         wshape, bshape = layer.param_shapes()
+        if layer.kind == "ln":                               # scale 1, shift 0
+            out.append(np.ones(wshape, dtype=np.float64))
+            out.append(np.zeros(bshape, dtype=np.float64))
+            continue
         fan_in = int(np.prod(wshape[1:]))
         W = _normal(f"{w.name}/s{s}/l{li}/W", wshape, std=float(np.sqrt(2.0 / fan_in)), seed=w.seed)
         out.append(round_f32(W))
