@@ -73,23 +73,36 @@ enum tp_policy {
 enum tp_dtype { TP_F32 = 0, TP_BF16 = 1 };
 enum tp_act { TP_ACT_NONE = 0, TP_ACT_RELU = 1, TP_ACT_GELU = 2 /* exact erf form */ };
 enum tp_layer_type {
-  TP_LAYER_DENSE = 0,    /* z = x W^T + b, a = act(z);  W[out x in]                                   */
+  TP_LAYER_DENSE = 0,    /* z = x W^T + b, a = act(z);  W[out x in].  geom[0] = token positions per sample
+                            (0 or 1: one): the layer is applied to every position of a [tokens x in] sample */
   TP_LAYER_CONV2D = 1,   /* 3x3 convolution, stride 1, zero padding 1, + bias + act, on NHWC activations:
                             in_features = Cin, out_features = Cout, geom = {H, W, 3, 1, 1};
                             W[Cout][3][3][Cin], b[Cout]; a sample is H*W*Cin values in, H*W*Cout out     */
-  TP_LAYER_MAXPOOL2 = 2  /* 2x2 max pooling, stride 2, no parameters: in_features = out_features = C,
+  TP_LAYER_MAXPOOL2 = 2, /* 2x2 max pooling, stride 2, no parameters: in_features = out_features = C,
                             geom = {H, W} of the input (both even); first maximum wins ties             */
+  /* Layers of a transformer-shaped stage; samples are [tokens x features] (BASELINE configuration 5; the
+     paper prescribes no layer formulas, these are the standard ones). */
+  TP_LAYER_LAYERNORM = 3, /* y = gamma (x - mean)/sqrt(var + 1e-5) + beta over the features of each token;
+                             in_features = out_features = D, geom = {tokens}; parameters gamma[D] (stored where a
+                             dense layer keeps W) and beta[D] (where it keeps b), both fp32 in every mode   */
+  TP_LAYER_ATTENTION = 4, /* causal multi-head self-attention, no parameters: in_features = 3*D (queries | keys |
+                             values, head h in columns h*D/heads ..), out_features = D, geom = {tokens, heads};
+                             must not be the last layer of a stage (its output is kept for the backward pass) */
+  TP_LAYER_RESIDUAL = 5   /* skip connection, no parameters: in_features = out_features = D, geom = {tokens, mark};
+                             mark 0 remembers the activation at this point, mark 1 adds the remembered one to
+                             the activation at this point; marks alternate 0, 1, 0, 1, ... within a stage    */
 };
 
-#define TP_MAX_LAYERS 32
+#define TP_MAX_LAYERS 64
 #define TP_NONE UINT64_MAX /* "no mini-batch" for stage_blend_update */
 
 typedef struct tp_layer_desc {
   int32_t type;         /* tp_layer_type */
   int32_t act;          /* tp_act */
-  int32_t in_features;  /* dense: columns of the layer input;  conv/pool: input channels  */
-  int32_t out_features; /* dense: columns of the layer output; conv/pool: output channels */
-  int32_t geom[5];      /* conv: {H, W, kernel, stride, pad}; pool: {H, W, 0, 0, 0}; dense: zeros */
+  int32_t in_features;  /* dense: columns of the layer input;  conv/pool: input channels;  others: see the type */
+  int32_t out_features; /* dense: columns of the layer output; conv/pool: output channels; others: see the type */
+  int32_t geom[5];      /* conv: {H, W, kernel, stride, pad}; pool: {H, W, 0, 0, 0}; dense, layer norm: {tokens};
+                           attention: {tokens, heads}; residual: {tokens, mark}; unused entries zero */
   int32_t reserved[7];  /* must be zero */
 } tp_layer_desc;
 
@@ -269,7 +282,10 @@ enum tp_kernel_class {
   TP_K_LOSS = 7,     /* softmax cross-entropy                        */
   TP_K_COPY = 8,     /* device-to-device copies and conversions      */
   TP_K_POOL = 9,     /* max pooling forward / backward               */
-  TP_K_CLASSES = 10
+  TP_K_NORM = 10,    /* layer normalisation forward / backward       */
+  TP_K_ATTN = 11,    /* attention forward / backward                 */
+  TP_K_ADD = 12,     /* residual additions                           */
+  TP_K_CLASSES = 13
 };
 typedef struct tp_profile {
   uint64_t launches[TP_K_CLASSES];

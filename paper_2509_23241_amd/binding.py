@@ -10,8 +10,8 @@ TP_OK, TP_EINVAL, TP_ESTATE, TP_ENOVERSION, TP_EFULL, TP_EBUSY, TP_EHIP = 0, -1,
 TP_LATEST, TP_INTERMEDIATE_EQ1, TP_INTERMEDIATE_CONVEX, TP_STASHED = 0, 1, 2, 3
 TP_F32, TP_BF16 = 0, 1
 TP_ACT_NONE, TP_ACT_RELU, TP_ACT_GELU = 0, 1, 2
-TP_LAYER_DENSE, TP_LAYER_CONV2D, TP_LAYER_MAXPOOL2 = 0, 1, 2
-TP_MAX_LAYERS, TP_MAX_SLOTS, TP_MAX_IN_FLIGHT = 32, 16, 16
+TP_LAYER_DENSE, TP_LAYER_CONV2D, TP_LAYER_MAXPOOL2, TP_LAYER_LAYERNORM, TP_LAYER_ATTENTION, TP_LAYER_RESIDUAL = 0, 1, 2, 3, 4, 5
+TP_MAX_LAYERS, TP_MAX_SLOTS, TP_MAX_IN_FLIGHT = 64, 16, 16
 TP_NONE = (1 << 64) - 1
 TP_DIAG_GRAD_SQ, TP_DIAG_WEIGHT_SQ, TP_DIAG_DRIFT_SQ, TP_DIAG_WB_SQ, TP_DIAG_COUNT = 0, 1, 2, 3, 4
 
@@ -63,11 +63,12 @@ class tp_event(C.Structure):
                 ("mb_id", C.c_uint64)]
 
 
-KERNEL_CLASSES = ["fprop", "dgrad", "wgrad", "colsum", "act_bwd", "update", "blend", "loss", "copy", "pool"]
+KERNEL_CLASSES = ["fprop", "dgrad", "wgrad", "colsum", "act_bwd", "update", "blend", "loss", "copy", "pool", "norm", "attn",
+                  "add"]
 
 
 class tp_profile(C.Structure):
-    _fields_ = [("launches", C.c_uint64 * 10), ("ms", C.c_double * 10), ("dropped", C.c_uint64)]
+    _fields_ = [("launches", C.c_uint64 * 13), ("ms", C.c_double * 13), ("dropped", C.c_uint64)]
 
 
 class StageLibError(RuntimeError):
@@ -123,8 +124,11 @@ def _check(rc, soft=()):
 
 def make_desc(layers, *, dtype, mb, n, stage_index, num_stages, ring_capacity, max_in_flight, policy, needs_dx,
               lam, lr, momentum) -> tp_stage_desc:
-    """layers: sequence of (in_features, out_features, act-name) for dense layers,
-    ("conv", cin, cout, H, W, act-name) for 3x3/stride 1/pad 1 convolutions, ("pool", C, H, W) for 2x2 pooling."""
+    """layers: sequence of (in_features, out_features, act-name[, tokens]) for dense layers,
+    ("conv", cin, cout, H, W, act-name) for 3x3/stride 1/pad 1 convolutions, ("pool", C, H, W) for 2x2 pooling,
+    ("ln", D, tokens), ("attn", D, heads, tokens), ("res", D, tokens, "begin" | "add")."""
+    if len(layers) > TP_MAX_LAYERS:
+        raise ValueError(f"{len(layers)} layers: a stage takes at most {TP_MAX_LAYERS}")
     d = tp_stage_desc()
     d.num_layers = len(layers)
     d.dtype = DTYPE[dtype] if isinstance(dtype, str) else dtype
@@ -145,9 +149,25 @@ def make_desc(layers, *, dtype, mb, n, stage_index, num_stages, ring_capacity, m
             act = "none"
             L.type, L.in_features, L.out_features = TP_LAYER_MAXPOOL2, c, c
             L.geom[0], L.geom[1] = H, W
+        elif spec[0] == "ln":
+            _, dm, tokens = spec
+            act = "none"
+            L.type, L.in_features, L.out_features = TP_LAYER_LAYERNORM, dm, dm
+            L.geom[0] = tokens
+        elif spec[0] == "attn":
+            _, dm, heads, tokens = spec
+            act = "none"
+            L.type, L.in_features, L.out_features = TP_LAYER_ATTENTION, 3 * dm, dm
+            L.geom[0], L.geom[1] = tokens, heads
+        elif spec[0] == "res":
+            _, dm, tokens, mark = spec
+            act = "none"
+            L.type, L.in_features, L.out_features = TP_LAYER_RESIDUAL, dm, dm
+            L.geom[0], L.geom[1] = tokens, {"begin": 0, "add": 1}[mark]
         else:
-            fin, fout, act = spec
+            fin, fout, act = spec[:3]
             L.type, L.in_features, L.out_features = TP_LAYER_DENSE, fin, fout
+            L.geom[0] = spec[3] if len(spec) > 3 and spec[3] > 1 else 0
         L.act = ACT[act] if isinstance(act, str) else act
     return d
 
@@ -158,7 +178,13 @@ def layer_in_elems(spec) -> int:
         return spec[3] * spec[4] * spec[1]
     if spec[0] == "pool":
         return spec[2] * spec[3] * spec[1]
-    return spec[0]
+    if spec[0] == "ln":
+        return spec[1] * spec[2]
+    if spec[0] == "attn":
+        return 3 * spec[1] * spec[3]
+    if spec[0] == "res":
+        return spec[1] * spec[2]
+    return spec[0] * (spec[3] if len(spec) > 3 else 1)
 
 
 def layer_out_elems(spec) -> int:
@@ -166,14 +192,22 @@ def layer_out_elems(spec) -> int:
         return spec[3] * spec[4] * spec[2]
     if spec[0] == "pool":
         return (spec[2] // 2) * (spec[3] // 2) * spec[1]
-    return spec[1]
+    if spec[0] == "ln":
+        return spec[1] * spec[2]
+    if spec[0] == "attn":
+        return spec[1] * spec[3]
+    if spec[0] == "res":
+        return spec[1] * spec[2]
+    return spec[1] * (spec[3] if len(spec) > 3 else 1)
 
 
 def layer_param_shapes(spec):
     if spec[0] == "conv":
         return [(spec[2], 3, 3, spec[1]), (spec[2],)]
-    if spec[0] == "pool":
+    if spec[0] in ("pool", "attn", "res"):
         return []
+    if spec[0] == "ln":
+        return [(spec[1],), (spec[1],)]
     return [(spec[1], spec[0]), (spec[1],)]
 
 

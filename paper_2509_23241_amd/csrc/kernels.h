@@ -30,6 +30,9 @@ hipError_t launch_colsum(hipStream_t s, int elt, int M, int N, const void* dz, f
 size_t colsum_scratch_floats(int M, int N);
 // out[i] = sum over z < splits of partial[z*count + i], i < count; fixed summation order.
 hipError_t launch_sum_partials(hipStream_t s, size_t count, int splits, const float* partial, float* out);
+// the same with partial row z starting at partial + z*stride
+hipError_t launch_sum_partials_strided(hipStream_t s, size_t count, int splits, const float* partial, size_t stride,
+                                       float* out);
 
 // dz = dy (.) d    all [rows x cols] in elt; d = saved act'(z).
 hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* d, void* dz);

@@ -184,8 +184,8 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(int M, int N, 
 // row, enough blocks anyway); small ones take many, so that a thousand partials do not end up
 // as one long chain of dependent loads.
 template <int ZG>
-__global__ __launch_bounds__(kThreads) void sum_partials_kernel(size_t count, int splits, const float* __restrict__ partial,
-                                                                float* __restrict__ out) {
+__global__ __launch_bounds__(kThreads) void sum_partials_kernel(size_t count, int splits, size_t stride,
+                                                                const float* __restrict__ partial, float* __restrict__ out) {
   constexpr int IL = kThreads / ZG;
   __shared__ float sm[ZG][IL + 1];
   const int il = threadIdx.x % IL, zg = threadIdx.x / IL;
@@ -194,10 +194,10 @@ __global__ __launch_bounds__(kThreads) void sum_partials_kernel(size_t count, in
   if (i < count) {
     int z = zg;
     for (; z + ZG < splits; z += 2 * ZG) {  // two independent chains
-      s0 += partial[(size_t)z * count + i];
-      s1 += partial[(size_t)(z + ZG) * count + i];
+      s0 += partial[(size_t)z * stride + i];
+      s1 += partial[(size_t)(z + ZG) * stride + i];
     }
-    if (z < splits) s0 += partial[(size_t)z * count + i];
+    if (z < splits) s0 += partial[(size_t)z * stride + i];
   }
   sm[zg][il] = s0 + s1;
   __syncthreads();
@@ -244,15 +244,20 @@ hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void*
   return simt<EPI_DGRAD>(s, elt, M, K, N, dz, N, 1, Wb, K, 1, e);
 }
 
-hipError_t launch_sum_partials(hipStream_t s, size_t count, int splits, const float* partial, float* out) {
+hipError_t launch_sum_partials_strided(hipStream_t s, size_t count, int splits, const float* partial, size_t stride,
+                                       float* out) {
   auto blocks = [&](int il) { return dim3((unsigned)((count + il - 1) / il)); };
   if (count >= 512 * 64 || splits <= 8)
-    hipLaunchKernelGGL(sum_partials_kernel<4>, blocks(64), dim3(kThreads), 0, s, count, splits, partial, out);
+    hipLaunchKernelGGL(sum_partials_kernel<4>, blocks(64), dim3(kThreads), 0, s, count, splits, stride, partial, out);
   else if (count >= 512 * 16)
-    hipLaunchKernelGGL(sum_partials_kernel<16>, blocks(16), dim3(kThreads), 0, s, count, splits, partial, out);
+    hipLaunchKernelGGL(sum_partials_kernel<16>, blocks(16), dim3(kThreads), 0, s, count, splits, stride, partial, out);
   else
-    hipLaunchKernelGGL(sum_partials_kernel<64>, blocks(4), dim3(kThreads), 0, s, count, splits, partial, out);
+    hipLaunchKernelGGL(sum_partials_kernel<64>, blocks(4), dim3(kThreads), 0, s, count, splits, stride, partial, out);
   return hipGetLastError();
+}
+
+hipError_t launch_sum_partials(hipStream_t s, size_t count, int splits, const float* partial, float* out) {
+  return launch_sum_partials_strided(s, count, splits, partial, count, out);
 }
 
 hipError_t launch_colsum(hipStream_t s, int elt, int M, int N, const void* dz, float* gb, float* partials) {

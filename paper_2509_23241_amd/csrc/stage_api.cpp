@@ -16,6 +16,7 @@
 #include <vector>
 
 #include "conv.h"
+#include "transformer.h"
 #include "kernels.h"
 
 namespace {
@@ -39,6 +40,10 @@ struct LayerPlan {
   uint64_t w_off, b_off;  // elements inside one weight version
   uint64_t x_off, z_off;  // bytes inside one activation slot; z_off: saved act'(z) (UINT64_MAX: none)
   uint64_t xpad_off = UINT64_MAX;  // first image layer in bf16: the input again, padded to 8 channels per pixel
+  uint64_t stat_off = UINT64_MAX;  // layer norm: mean and 1/std per token; attention: log-sum-exp per (head, query)
+  uint64_t stat_elems = 0;         // floats per sample behind stat_off
+  int tokens = 1;                  // positions per sample (rows of the layer's matrices per sample)
+  int skip_layer = -1;             // residual add: index of the layer that remembered the skip activation
 };
 
 struct Slot {
@@ -81,16 +86,48 @@ int check_desc(const tp_stage_desc* d) {
   if (!(d->lambda > 0.0) || !std::isfinite(d->lambda)) return fail(TP_EINVAL, "lambda must be > 0");
   if (!std::isfinite(d->lr) || !std::isfinite(d->momentum)) return fail(TP_EINVAL, "lr/momentum not finite");
   uint64_t prev_out = 0;
+  int open_skip = -1;  // layer of a residual begin that has not met its add yet
   for (int l = 0; l < d->num_layers; ++l) {
     const tp_layer_desc& L = d->layers[l];
     if (L.act < TP_ACT_NONE || L.act > TP_ACT_GELU) return fail(TP_EINVAL, "layer %d: unknown activation", l);
     if (L.in_features < 1 || L.out_features < 1) return fail(TP_EINVAL, "layer %d: empty shape", l);
     uint64_t in_e, out_e;
     if (L.type == TP_LAYER_DENSE) {
-      for (int r = 0; r < 5; ++r)
-        if (L.geom[r] != 0) return fail(TP_EINVAL, "layer %d: geometry fields must be zero for a dense layer", l);
-      in_e = L.in_features;
-      out_e = L.out_features;
+      for (int r = 1; r < 5; ++r)
+        if (L.geom[r] != 0) return fail(TP_EINVAL, "layer %d: geometry fields 1..4 must be zero for a dense layer", l);
+      if (L.geom[0] < 0) return fail(TP_EINVAL, "layer %d: negative token count", l);
+      const uint64_t T = L.geom[0] > 1 ? L.geom[0] : 1;
+      in_e = T * L.in_features;
+      out_e = T * L.out_features;
+    } else if (L.type == TP_LAYER_LAYERNORM || L.type == TP_LAYER_RESIDUAL) {
+      if (L.geom[0] < 1 || L.in_features != L.out_features || L.act != TP_ACT_NONE || L.geom[2] || L.geom[3] || L.geom[4])
+        return fail(TP_EINVAL, "layer %d: malformed %s layer", l, L.type == TP_LAYER_LAYERNORM ? "normalisation" : "residual");
+      if (L.type == TP_LAYER_LAYERNORM && (L.geom[1] != 0 || L.in_features > 20480))
+        return fail(TP_EINVAL, "layer %d: malformed normalisation layer", l);
+      if (L.type == TP_LAYER_RESIDUAL) {
+        if (L.geom[1] != 0 && L.geom[1] != 1) return fail(TP_EINVAL, "layer %d: residual mark must be 0 or 1", l);
+        if (L.geom[1] != (open_skip >= 0 ? 1 : 0))
+          return fail(TP_EINVAL, "layer %d: residual marks must alternate begin, add", l);
+        if (L.geom[1] == 0) {
+          open_skip = l;
+        } else {
+          const tp_layer_desc& B = d->layers[open_skip];
+          if (B.in_features != L.in_features || B.geom[0] != L.geom[0])
+            return fail(TP_EINVAL, "layer %d: residual add does not match the shape remembered at layer %d", l, open_skip);
+          open_skip = -1;
+        }
+      }
+      in_e = out_e = (uint64_t)L.geom[0] * L.in_features;
+    } else if (L.type == TP_LAYER_ATTENTION) {
+      if (L.geom[0] < 1 || L.geom[1] < 1 || L.act != TP_ACT_NONE || L.geom[2] || L.geom[3] || L.geom[4] ||
+          L.in_features != 3 * L.out_features || L.out_features % L.geom[1] != 0)
+        return fail(TP_EINVAL, "layer %d: malformed attention layer", l);
+      if (!tp::attention_supported(L.geom[0], L.geom[1], L.out_features / L.geom[1]))
+        return fail(TP_EINVAL, "layer %d: head width %d is outside what the attention kernels take", l,
+                    L.out_features / L.geom[1]);
+      if (l == d->num_layers - 1) return fail(TP_EINVAL, "layer %d: attention must not be the last layer of a stage", l);
+      in_e = (uint64_t)L.geom[0] * L.in_features;
+      out_e = (uint64_t)L.geom[0] * L.out_features;
     } else if (L.type == TP_LAYER_CONV2D) {
       if (L.geom[0] < 1 || L.geom[1] < 1) return fail(TP_EINVAL, "layer %d: empty image", l);
       if (L.geom[2] != 3 || L.geom[3] != 1 || L.geom[4] != 1)
@@ -115,6 +152,7 @@ int check_desc(const tp_stage_desc* d) {
     for (int r = 0; r < 7; ++r)
       if (L.reserved[r] != 0) return fail(TP_EINVAL, "layer %d: reserved fields must be zero", l);
   }
+  if (open_skip >= 0) return fail(TP_EINVAL, "layer %d: residual begin without an add", open_skip);
   return TP_OK;
 }
 
@@ -125,15 +163,35 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
   const uint64_t rows = (uint64_t)d->mb * d->n;
   std::memset(&p->sizes, 0, sizeof(p->sizes));
   uint64_t off = 0, act = 0, max_feat = 0;
-  uint64_t conv_scratch = 0;
+  uint64_t conv_scratch = 0, norm_scratch = 0;
+  int open_skip = -1;
+  bool alias_prev = false;  // the previous layer was a residual begin: this layer reads the same tensor
   for (int l = 0; l < d->num_layers; ++l) {
     LayerPlan lp;
     lp.d = d->layers[l];
     const tp_layer_desc& L = lp.d;
     if (L.type == TP_LAYER_DENSE) {
-      lp.in_elems = L.in_features;
-      lp.out_elems = L.out_features;
+      lp.tokens = L.geom[0] > 1 ? L.geom[0] : 1;
+      lp.in_elems = (uint64_t)lp.tokens * L.in_features;
+      lp.out_elems = (uint64_t)lp.tokens * L.out_features;
       lp.w_elems = (uint64_t)L.in_features * L.out_features;
+    } else if (L.type == TP_LAYER_LAYERNORM) {
+      lp.tokens = L.geom[0];
+      lp.in_elems = lp.out_elems = (uint64_t)lp.tokens * L.in_features;
+      lp.w_elems = L.in_features;                      // gamma; beta sits where a dense layer keeps its bias
+      lp.stat_elems = 2 * (uint64_t)lp.tokens;
+      norm_scratch = std::max<uint64_t>(norm_scratch, tp::layernorm_scratch_floats(rows * lp.tokens, L.in_features));
+    } else if (L.type == TP_LAYER_ATTENTION) {
+      lp.tokens = L.geom[0];
+      lp.in_elems = (uint64_t)lp.tokens * L.in_features;
+      lp.out_elems = (uint64_t)lp.tokens * L.out_features;
+      lp.w_elems = 0;
+      lp.stat_elems = (uint64_t)lp.tokens * L.geom[1];
+    } else if (L.type == TP_LAYER_RESIDUAL) {
+      lp.tokens = L.geom[0];
+      lp.in_elems = lp.out_elems = (uint64_t)lp.tokens * L.in_features;
+      lp.w_elems = 0;
+      if (L.geom[1] == 0) open_skip = l; else lp.skip_layer = open_skip;
     } else if (L.type == TP_LAYER_CONV2D) {
       lp.in_elems = (uint64_t)L.geom[0] * L.geom[1] * L.in_features;
       lp.out_elems = (uint64_t)L.geom[0] * L.geom[1] * L.out_features;
@@ -152,8 +210,17 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
       lp.b_off = off;
       off += round_up((uint64_t)L.out_features, 64);
     }
-    lp.x_off = act;
-    act += round_up(rows * lp.in_elems * p->elt_size, 256);
+    if (alias_prev) {
+      lp.x_off = p->layers.back().x_off;
+    } else {
+      lp.x_off = act;
+      act += round_up(rows * lp.in_elems * p->elt_size, 256);
+    }
+    alias_prev = L.type == TP_LAYER_RESIDUAL && L.geom[1] == 0;
+    if (lp.stat_elems) {
+      lp.stat_off = act;
+      act += round_up(rows * lp.stat_elems * 4, 256);
+    }
     if (L.act != TP_ACT_NONE) {
       lp.z_off = act;
       act += round_up(rows * lp.out_elems * p->elt_size, 256);
@@ -178,10 +245,11 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
   for (const LayerPlan& lp : p->layers) {
     if (!lp.w_elems) continue;
     // bias gradients: column sums over rows (dense) or over all pixels (conv)
-    const uint64_t r = lp.d.type == TP_LAYER_CONV2D ? rows * lp.d.geom[0] * lp.d.geom[1] : rows;
+    if (lp.d.type == TP_LAYER_LAYERNORM) continue;
+    const uint64_t r = lp.d.type == TP_LAYER_CONV2D ? rows * lp.d.geom[0] * lp.d.geom[1] : rows * lp.tokens;
     wg = std::max<uint64_t>(wg, tp::colsum_scratch_floats((int)r, lp.d.out_features));
   }
-  p->partial_floats = round_up(std::max<uint64_t>({wg, tp::update_scratch_floats(), rows, conv_scratch}), 64);
+  p->partial_floats = round_up(std::max<uint64_t>({wg, tp::update_scratch_floats(), rows, conv_scratch, norm_scratch}), 64);
   tp_sizes& s = p->sizes;
   s.param_count = P;
   s.ring_bytes = (uint64_t)d->ring_capacity * P * 4;
@@ -190,7 +258,7 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
   s.wfwd_bytes = d->dtype == TP_BF16 ? P * 2 : 0;
   s.wbwd_bytes = P * p->elt_size;
   s.act_bytes = (uint64_t)d->max_in_flight * act;
-  s.scratch_bytes = 2 * p->dz_bytes + p->partial_floats * 4 + 512;  // + an aligned block of 256 zero bytes (conv padding)
+  s.scratch_bytes = 3 * p->dz_bytes + p->partial_floats * 4 + 512;  // + an aligned block of 256 zero bytes (conv padding)
   s.diag_bytes = TP_DIAG_COUNT * sizeof(double);
   return TP_OK;
 }
@@ -237,9 +305,9 @@ struct tp_stage {
   float* ring(int slot) const { return (float*)bufs.ring_dev + (uint64_t)slot * plan.sizes.param_count; }
   char* act_slot(int q) const { return (char*)bufs.act_dev + (uint64_t)q * plan.act_slot_bytes; }
   char* dz_buf(int i) const { return (char*)bufs.scratch_dev + (uint64_t)i * plan.dz_bytes; }
-  float* partials() const { return (float*)((char*)bufs.scratch_dev + 2 * plan.dz_bytes); }
+  float* partials() const { return (float*)((char*)bufs.scratch_dev + 3 * plan.dz_bytes); }
   const void* zeros() const {  // 256-byte aligned, behind the partial sums
-    const uintptr_t p = (uintptr_t)bufs.scratch_dev + 2 * plan.dz_bytes + plan.partial_floats * 4;
+    const uintptr_t p = (uintptr_t)bufs.scratch_dev + 3 * plan.dz_bytes + plan.partial_floats * 4;
     return (const void*)((p + 255) & ~(uintptr_t)255);
   }
   // drop a version that nobody needs any more
@@ -486,7 +554,7 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
     void* a_out = (l == L - 1) ? y_dev : (void*)(aslot + st->plan.layers[l + 1].x_off + row0 * lp.out_elems * es);
     if (lp.d.type == TP_LAYER_DENSE) {
       ProfScope ps(st, TP_K_FPROP);
-      HIP_TRY(tp::launch_fprop(st->stream, d.dtype, d.mb, lp.d.out_features, lp.d.in_features, x_in,
+      HIP_TRY(tp::launch_fprop(st->stream, d.dtype, d.mb * lp.tokens, lp.d.out_features, lp.d.in_features, x_in,
                                wcopy + lp.w_off * es, master + lp.b_off, lp.d.act, z_out, a_out,
                                need_copy ? x_saved : nullptr));
       continue;
@@ -508,6 +576,28 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
     if (need_copy) {
       ProfScope ps(st, TP_K_COPY);
       HIP_TRY(tp::launch_copy(st->stream, x_dev, x_saved, (size_t)d.mb * lp.in_elems * es));
+    }
+    if (lp.d.type == TP_LAYER_LAYERNORM) {
+      ProfScope ps(st, TP_K_NORM);
+      float* stats = (float*)(aslot + lp.stat_off) + row0 * lp.stat_elems;
+      HIP_TRY(tp::launch_layernorm_fwd(st->stream, d.dtype, (size_t)d.mb * lp.tokens, lp.d.in_features, x_saved,
+                                       master + lp.w_off, master + lp.b_off, a_out, stats));
+      continue;
+    }
+    if (lp.d.type == TP_LAYER_ATTENTION) {
+      ProfScope ps(st, TP_K_ATTN);
+      float* lse = (float*)(aslot + lp.stat_off) + row0 * lp.stat_elems;
+      const int heads = lp.d.geom[1];
+      HIP_TRY(tp::launch_attention_fwd(st->stream, d.dtype, d.mb, lp.tokens, heads, lp.d.out_features / heads, x_saved, a_out,
+                                       lse));
+      continue;
+    }
+    if (lp.d.type == TP_LAYER_RESIDUAL) {
+      if (lp.skip_layer < 0) continue;  // begin: the next layer reads this layer's input in place
+      ProfScope ps(st, TP_K_ADD);
+      const char* skip = aslot + st->plan.layers[lp.skip_layer].x_off + row0 * lp.in_elems * es;
+      HIP_TRY(tp::launch_add(st->stream, d.dtype, (size_t)d.mb * lp.in_elems, x_saved, skip, a_out));
+      continue;
     }
     if (lp.d.type == TP_LAYER_CONV2D) {
       ProfScope ps(st, TP_K_FPROP);
@@ -582,44 +672,106 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
     char* aslot = st->act_slot(f->act_slot);
     float* g = (float*)st->bufs.grad_dev;
     const void* dz = nullptr;  // gradient w.r.t. the pre-activation output of layer l (or pooled output)
-    int pp = 0;
+    // Three temporaries: the gradient in hand, the one being formed, and the one a residual add has
+    // set aside for the matching begin.
+    const void* pinned = nullptr;
+    auto scratch_for = [&](const void* cur) -> void* {
+      for (int i = 0; i < 3; ++i)
+        if (st->dz_buf(i) != cur && st->dz_buf(i) != pinned) return st->dz_buf(i);
+      return nullptr;
+    };
+    // scale of a layer normalisation in the backward pass: the intermediate weight, formed in fp32
+    double ca = 1.0, cb = 0.0;
+    if (delta != 0) {
+      int rc = tp_blend_coefficients(d.policy, delta, d.lambda, &ca, &cb);
+      if (rc) return rc;
+    }
     {
       const LayerPlan& last = st->plan.layers[L - 1];
       if (last.d.act == TP_ACT_NONE) {
         dz = dy_dev;
       } else {
         ProfScope ps(st, TP_K_ACT_BWD);
-        HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * last.out_elems, dy_dev, aslot + last.z_off, st->dz_buf(pp)));
-        dz = st->dz_buf(pp);
-        pp ^= 1;
+        void* buf = scratch_for(nullptr);
+        HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * last.out_elems, dy_dev, aslot + last.z_off, buf));
+        dz = buf;
       }
     }
     for (int l = L - 1; l >= 0; --l) {
       const LayerPlan& lp = st->plan.layers[l];
       // where the gradient w.r.t. this layer's input goes, and what it is multiplied with on the way
       const bool to_caller = l == 0;
-      if (to_caller && !d.needs_dx && lp.d.type == TP_LAYER_MAXPOOL2) break;
+      const bool no_dx = to_caller && !d.needs_dx;
+      if (no_dx && (lp.d.type == TP_LAYER_MAXPOOL2 || lp.d.type == TP_LAYER_ATTENTION)) break;
       const void* dprev = nullptr;
       if (l > 0) {
         const LayerPlan& prev = st->plan.layers[l - 1];
         dprev = prev.z_off == UINT64_MAX ? nullptr : aslot + prev.z_off;
       }
-      void* dst = to_caller ? dx_dev : (void*)st->dz_buf(pp);
+      void* dst = to_caller && !no_dx ? dx_dev : scratch_for(dz);
+      auto through_activation = [&](void* grad) -> int {  // dz_prev = dx (.) act'(z_prev), in place
+        if (!dprev) return TP_OK;
+        ProfScope ps(st, TP_K_ACT_BWD);
+        HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * lp.in_elems, grad, dprev, grad));
+        return TP_OK;
+      };
       if (lp.d.type == TP_LAYER_MAXPOOL2) {
         {
           ProfScope ps(st, TP_K_POOL);
           HIP_TRY(tp::launch_maxpool_bwd(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features,
                                          aslot + lp.x_off, dz, dst));
         }
-        if (dprev) {  // the layer before the pool has an activation: dz_prev = dx_pool (.) act'
-          ProfScope ps(st, TP_K_ACT_BWD);
-          HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * lp.in_elems, dst, dprev, dst));
-        }
+        if (int rc = through_activation(dst)) return rc;
         dz = dst;
-        if (!to_caller) pp ^= 1;
         continue;
       }
-      const int grad_rows = lp.d.type == TP_LAYER_CONV2D ? rows * lp.d.geom[0] * lp.d.geom[1] : rows;
+      if (lp.d.type == TP_LAYER_RESIDUAL) {
+        if (lp.skip_layer >= 0) {  // add: the gradient goes on unchanged and is set aside for the begin
+          pinned = dz;
+          if (dprev) {
+            ProfScope ps(st, TP_K_ACT_BWD);
+            HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * lp.in_elems, dz, dprev, dst));
+            dz = dst;
+          }
+          continue;
+        }
+        if (no_dx) break;
+        {
+          ProfScope ps(st, TP_K_ADD);
+          HIP_TRY(tp::launch_add(st->stream, d.dtype, (size_t)rows * lp.in_elems, dz, pinned, dst));
+        }
+        pinned = nullptr;
+        if (int rc = through_activation(dst)) return rc;
+        dz = dst;
+        continue;
+      }
+      if (lp.d.type == TP_LAYER_LAYERNORM) {
+        const float* gl = st->ring(slot_now) + lp.w_off;
+        const float* gs = delta != 0 ? st->ring(slot_f) + lp.w_off : gl;
+        {
+          ProfScope ps(st, TP_K_NORM);
+          HIP_TRY(tp::launch_layernorm_bwd(st->stream, d.dtype, (size_t)rows * lp.tokens, lp.d.in_features, dz, aslot + lp.x_off,
+                                           (const float*)(aslot + lp.stat_off), gs, gl, (float)ca, (float)cb, dst,
+                                           g + lp.w_off, g + lp.b_off, st->partials()));
+        }
+        if (no_dx) break;
+        if (int rc = through_activation(dst)) return rc;
+        dz = dst;
+        continue;
+      }
+      if (lp.d.type == TP_LAYER_ATTENTION) {
+        const int heads = lp.d.geom[1];
+        {
+          ProfScope ps(st, TP_K_ATTN);
+          HIP_TRY(tp::launch_attention_bwd(st->stream, d.dtype, rows, lp.tokens, heads, lp.d.out_features / heads,
+                                           aslot + lp.x_off, aslot + st->plan.layers[l + 1].x_off, dz,
+                                           (const float*)(aslot + lp.stat_off), dst));
+        }
+        if (int rc = through_activation(dst)) return rc;
+        dz = dst;
+        continue;
+      }
+      const int grad_rows = lp.d.type == TP_LAYER_CONV2D ? rows * lp.d.geom[0] * lp.d.geom[1] : rows * lp.tokens;
       {
         ProfScope ps(st, TP_K_COLSUM);
         HIP_TRY(tp::launch_colsum(st->stream, d.dtype, grad_rows, lp.d.out_features, dz, g + lp.b_off, st->partials()));
@@ -627,7 +779,7 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
       {
         ProfScope ps(st, TP_K_WGRAD);
         if (lp.d.type == TP_LAYER_DENSE)
-          HIP_TRY(tp::launch_wgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, aslot + lp.x_off,
+          HIP_TRY(tp::launch_wgrad(st->stream, d.dtype, grad_rows, lp.d.out_features, lp.d.in_features, dz, aslot + lp.x_off,
                                    g + lp.w_off));
         else if (lp.xpad_off != UINT64_MAX)
           HIP_TRY(tp::conv_c8_wgrad(st->stream, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, lp.d.out_features,
@@ -638,18 +790,17 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
                                         lp.d.out_features, dz, aslot + lp.x_off, g + lp.w_off, st->partials(),
                                         st->zeros()));
       }
-      if (to_caller && !d.needs_dx) break;
+      if (no_dx) break;
       {
         ProfScope ps(st, TP_K_DGRAD);
         if (lp.d.type == TP_LAYER_DENSE)
-          HIP_TRY(tp::launch_dgrad(st->stream, d.dtype, rows, lp.d.out_features, lp.d.in_features, dz, wb + lp.w_off * es,
+          HIP_TRY(tp::launch_dgrad(st->stream, d.dtype, grad_rows, lp.d.out_features, lp.d.in_features, dz, wb + lp.w_off * es,
                                    dprev, dst));
         else
           HIP_TRY(tp::launch_conv_dgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features,
                                         lp.d.out_features, dz, wb + lp.w_off * es, dprev, dst, st->zeros()));
       }
       dz = dst;
-      if (!to_caller) pp ^= 1;
     }
   }
 

@@ -1,0 +1,35 @@
+// Layers of the transformer-shaped stage: layer normalisation, causal multi-head self-attention and
+// the residual add.  Activations are [rows x D] matrices (row = one token) in the stage's activation
+// type (elt: 0 fp32, 1 bf16); statistics and parameter gradients are fp32.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace tp {
+
+// y = gamma * (x - mean) / sqrt(var + eps) + beta per row; stats[2*r] = mean, stats[2*r+1] = 1/sqrt(var+eps).
+hipError_t launch_layernorm_fwd(hipStream_t s, int elt, size_t rows, int D, const void* x, const float* gamma,
+                                const float* beta, void* y, float* stats);
+// dx, dgamma, dbeta of the above.  The scale the backward pass uses is alpha*gamma_s + beta_c*gamma_l
+// (the intermediate weight of the method, formed on the fly in fp32; pass gamma_l twice with 1, 0 for
+// the plain case).  partials: scratch of layernorm_scratch_floats(rows, D) floats.
+hipError_t launch_layernorm_bwd(hipStream_t s, int elt, size_t rows, int D, const void* dy, const void* x,
+                                const float* stats, const float* gamma_s, const float* gamma_l, float alpha, float beta_c,
+                                void* dx, float* dgamma, float* dbeta, float* partials);
+size_t layernorm_scratch_floats(size_t rows, int D);
+
+// out = a + b, elementwise (out may alias a or b)
+hipError_t launch_add(hipStream_t s, int elt, size_t count, const void* a, const void* b, void* out);
+
+// qkv: [seqs*S x 3*D] (queries | keys | values, head h in columns h*dh..), out: [seqs*S x D],
+// lse: [seqs*heads*S] log-sum-exp of the scaled scores of each query (kept for the backward pass).
+hipError_t launch_attention_fwd(hipStream_t s, int elt, int seqs, int S, int heads, int dh, const void* qkv, void* out,
+                                float* lse);
+// dqkv: [seqs*S x 3*D] from dout, the saved qkv, the saved output and lse.
+hipError_t launch_attention_bwd(hipStream_t s, int elt, int seqs, int S, int heads, int dh, const void* qkv, const void* out,
+                                const void* dout, const float* lse, void* dqkv);
+// head widths the attention kernels take
+bool attention_supported(int S, int heads, int dh);
+
+}  // namespace tp

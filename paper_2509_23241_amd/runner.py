@@ -21,7 +21,13 @@ def layer_tuple(spec) -> tuple:
         return ("conv", spec.cin, spec.cout, spec.h, spec.w, spec.act)
     if kind == "pool":
         return ("pool", spec.c, spec.h, spec.w)
-    return (spec.in_features, spec.out_features, spec.act)
+    if kind == "ln":
+        return ("ln", spec.d, spec.tokens)
+    if kind == "attn":
+        return ("attn", spec.d, spec.heads, spec.tokens)
+    if kind == "res":
+        return ("res", spec.d, spec.tokens, spec.mark)
+    return (spec.in_features, spec.out_features, spec.act, getattr(spec, "tokens", 1))
 
 
 def _torch_dtype(dtype: str):

@@ -1,0 +1,49 @@
+"""GPU parity of transformer-shaped stages against the fp64 oracle: layer normalisation, per-token dense
+layers, causal multi-head attention and residual connections, driven like the other single-stage tests
+(forward, backward with real staleness under the blend, update), in both precisions."""
+import pytest
+
+from synth_inputs import workloads as W
+from test_gpu_conv_stage import _run_stage
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_layernorm_and_per_token_dense(dtype):
+    # 7 tokens x 24 features (no multiple of anything), LN -> dense+GELU -> LN -> dense
+    specs = (W.LayerNorm(24, 7), W.Dense(24, 40, "gelu", tokens=7), W.LayerNorm(40, 7), W.Dense(40, 16, "none", tokens=7))
+    print(dtype, _run_stage(specs, f"ln_{dtype}", dtype, mb=3, n=2))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_attention_alone(dtype):
+    # qkv projection -> attention -> output projection; 21 tokens: ragged against the 16-row / 64-key tiles
+    specs = (W.Dense(16, 48, "none", tokens=21), W.Attention(16, 2, 21), W.Dense(16, 16, "none", tokens=21))
+    print(dtype, _run_stage(specs, f"attn_{dtype}", dtype, mb=2, n=2))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_residual_around_gelu_dense(dtype):
+    # the residual add follows an activation and the begin follows one too
+    specs = (W.Dense(16, 16, "gelu", tokens=4), W.Residual(16, 4, "begin"), W.Dense(16, 16, "gelu", tokens=4),
+             W.Residual(16, 4, "add"), W.Dense(16, 8, "none", tokens=4))
+    print(dtype, _run_stage(specs, f"res_{dtype}", dtype, mb=3, n=2))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_two_transformer_blocks(dtype):
+    # two pre-norm decoder blocks, 80 tokens (two key tiles), 4 heads of 8, depth 3: staleness 0, 1, 2
+    specs = W.transformer_block(32, 4, 64, 80) + W.transformer_block(32, 4, 64, 80)
+    print(dtype, _run_stage(specs, f"tfm2_{dtype}", dtype, mb=2, n=2, depth=3, minibatches=4))
+
+
+def test_transformer_block_first_stage_no_input_gradient():
+    specs = W.transformer_block(32, 2, 64, 16)
+    print(_run_stage(specs, "tfm_first", "f32", mb=2, n=2, needs_dx=False))
+
+
+def test_transformer_block_wide_heads_bf16():
+    # head width 128 (two output columns per lane in the attention kernels), 128-wide model, 64 tokens
+    specs = W.transformer_block(128, 1, 256, 64)
+    print(_run_stage(specs, "tfm_wide", "bf16", mb=2, n=2))

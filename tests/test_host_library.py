@@ -35,7 +35,9 @@ def test_library_exports_every_declared_symbol():
 def test_struct_sizes_match_header_layout():
     import ctypes as C
     assert C.sizeof(B.tp_layer_desc) == 64
-    assert C.sizeof(B.tp_stage_desc) == 10 * 4 + 3 * 8 + 32 * 64
+    assert C.sizeof(B.tp_stage_desc) == 10 * 4 + 3 * 8 + B.TP_MAX_LAYERS * 64
+    assert B.TP_MAX_LAYERS == int(re.search(r"#define TP_MAX_LAYERS (\d+)", open(HEADER).read()).group(1))
+    assert C.sizeof(B.tp_profile) == len(B.KERNEL_CLASSES) * 16 + 8
     assert C.sizeof(B.tp_event) == 24
 
 
@@ -198,6 +200,35 @@ def test_invalid_descriptions():
     d = B.make_desc([], **good)
     with pytest.raises(B.StageLibError):
         B.stage_workspace_query(d)
+
+
+def test_transformer_layer_descriptions():
+    good = dict(dtype="bf16", mb=2, n=2, stage_index=1, num_stages=4, ring_capacity=3, max_in_flight=3,
+                policy="convex", needs_dx=True, lam=0.1, lr=0.01, momentum=0.9)
+    D, T = 32, 8
+    block = [("res", D, T, "begin"), ("ln", D, T), (D, 3 * D, "none", T), ("attn", D, 4, T), (D, D, "none", T),
+             ("res", D, T, "add")]
+    s = B.stage_workspace_query(B.make_desc(block, **good))
+    # parameters: gamma/beta of the norm, then W/b of the two dense layers, each padded to 64 elements
+    assert s.w_offset[1] == 0 and s.b_offset[1] == 64
+    assert s.w_offset[2] == 128 and s.b_offset[2] == 128 + 3 * D * D
+    assert s.param_count == 128 + 3 * D * D + 128 + D * D + 64
+    bad_cases = [
+        block[:4],                                                            # attention last, skip left open
+        [("res", D, T, "begin"), ("ln", D, T)],                               # begin without add
+        [("ln", D, T), ("res", D, T, "add")],                                 # add without begin
+        [("res", D, T, "begin"), ("res", D, T, "begin"), ("res", D, T, "add"), ("res", D, T, "add")],   # nested
+        [("res", D, T, "begin"), (D, 2 * D, "none", T), ("res", 2 * D, T, "add")],                     # shapes differ
+        [(D, 3 * D, "none", T), ("attn", D, 5, T), (D, D, "none", T)],        # heads do not divide the width
+        [(D, 3 * D, "none", T), ("attn", D, 4, T + 1), (D, D, "none", T)],    # token counts do not chain
+        [(D, 3 * D, "none", T), ("attn", D, 4, T)],                           # attention as the last layer
+    ]
+    for layers in bad_cases:
+        with pytest.raises(B.StageLibError) as ei:
+            B.stage_workspace_query(B.make_desc(layers, **good))
+        assert ei.value.code == B.TP_EINVAL, layers
+    with pytest.raises(ValueError):
+        B.make_desc([(4, 4, "none")] * (B.TP_MAX_LAYERS + 1), **good)
 
 
 def test_workspace_layout():
