@@ -47,3 +47,10 @@ def test_transformer_block_wide_heads_bf16():
     # head width 128 (two output columns per lane in the attention kernels), 128-wide model, 64 tokens
     specs = W.transformer_block(128, 1, 256, 64)
     print(_run_stage(specs, "tfm_wide", "bf16", mb=2, n=2))
+
+
+def test_transformer_stage_reduced_bf16():
+    # the decoder stage of the transformer workload at reduced size: 4 blocks (44 layers), d_model 256,
+    # 4 heads of 64, FFN 1024, 128 tokens, micro-batch 2 x 2, depth 3 (staleness 0, 1, 2)
+    w = W.transformer_stage(d=256, heads=4, ffn=1024, tokens=128, layers=4, mb=2, n=2)
+    print(_run_stage(w.stages[1], "tfm_reduced", "bf16", mb=2, n=2, depth=3, minibatches=3))
