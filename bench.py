@@ -39,13 +39,15 @@ def parse():
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--policy", default="convex", choices=["latest", "eq1", "convex", "stashed"])
-    ap.add_argument("--workload", default="mlp", choices=["mlp", "vgg"],
+    ap.add_argument("--workload", default="mlp", choices=["mlp", "vgg", "tfm"],
                     help="mlp: interior stage of the width-4096 GELU MLP (the configuration the metric is quoted on); "
-                         "vgg: stage 0 of the VGG-16-style net on 32x32x3 images (implicit-GEMM convolutions)")
+                         "vgg: stage 0 of the VGG-16-style net on 32x32x3 images (implicit-GEMM convolutions); "
+                         "tfm: interior stage of the decoder-only transformer (4 blocks, d_model 2048, 1024 tokens)")
+    ap.add_argument("--blocks", type=int, default=4, help="transformer blocks in the tfm stage")
     ap.add_argument("--stage", type=int, default=None)
     ap.add_argument("--width", type=int, default=4096)
-    ap.add_argument("--mb", type=int, default=None, help="micro-batch size (default 256 mlp, 64 vgg)")
-    ap.add_argument("--n", type=int, default=None, help="micro-batches per mini-batch (default 8 mlp, 4 vgg)")
+    ap.add_argument("--mb", type=int, default=None, help="micro-batch size (default 256 mlp, 64 vgg, 8 tfm)")
+    ap.add_argument("--n", type=int, default=None, help="micro-batches per mini-batch (default 8 mlp, 4 vgg, 4 tfm)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-minibatches", type=int, default=3)
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
@@ -59,7 +61,9 @@ def layer_work(cls, layer, rows, mb):
     mini-batch (backward kernels), mb = samples of a micro-batch (forward kernels)."""
     if layer.kind == "pool":
         return 0.0, 0.0
-    px = layer.h * layer.w if layer.kind == "conv" else 1        # GEMM rows per sample
+    if layer.kind in ("ln", "attn", "res"):
+        return 0.0, 0.0
+    px = layer.h * layer.w if layer.kind == "conv" else getattr(layer, "tokens", 1)   # GEMM rows per sample
     fin = (9 * layer.cin) if layer.kind == "conv" else layer.in_features
     cin = layer.cin if layer.kind == "conv" else layer.in_features
     fout = layer.cout if layer.kind == "conv" else layer.out_features
@@ -85,7 +89,8 @@ def kernel_work(cls, w, s, needs_dx):
     if cls == "act_bwd":               # dy (.) act'(z) at the stage output and behind every pool
         tot = 0.0
         for i, l in enumerate(layers):
-            if l.kind != "pool" and (i == len(layers) - 1 or layers[i + 1].kind == "pool") and l.act != "none":
+            if l.kind in ("dense", "conv") and (i == len(layers) - 1 or layers[i + 1].kind != "dense" and
+                                                 layers[i + 1].kind != "conv") and l.act != "none":
                 tot += 3 * 2.0 * rows * l.out_dim()
         return 0.0, tot
     if cls == "pool":                  # forward: in + out; backward: in, out, dy in, dx out
@@ -95,12 +100,25 @@ def kernel_work(cls, w, s, needs_dx):
                 e = l.c * l.h * l.w
                 tot += 2.0 * rows * (e + e / 4) + 2.0 * rows * (2 * e + 2 * e / 4)
         return 0.0, tot
+    if cls == "norm":                  # forward: x in, y out; backward: dy, x in, dx out
+        tot = sum(2.0 * rows * l.out_dim() * 5 for l in layers if l.kind == "ln")
+        return 0.0, tot
+    if cls == "add":                   # forward a + b -> out; backward the same on gradients
+        tot = sum(2.0 * rows * l.out_dim() * 3 * 2 for l in layers if l.kind == "res" and l.mark == "add")
+        return 0.0, tot
+    if cls == "attn":                  # causal: half of the S x S scores; QK^T and PV forward, five products backward
+        fl = by = 0.0
+        for l in layers:
+            if l.kind == "attn":
+                fl += rows * 7 * 2.0 * l.tokens * l.tokens * l.d / 2
+                by += 2.0 * rows * l.tokens * l.d * (4 + 8)
+        return fl, by
     if cls == "copy":                  # stage input saved for the backward where no GEMM can fuse it
         l = layers[0]
-        return 0.0, (2 * 2.0 * rows * np_prod(l.in_shape())) if l.kind == "conv" else 0.0
+        return 0.0, (2 * 2.0 * rows * np_prod(l.in_shape())) if l.kind in ("conv", "res", "ln") else 0.0
     flops = nbytes = 0.0
     for i, l in enumerate(layers):
-        if l.kind == "pool":
+        if l.kind in ("pool", "ln", "attn", "res"):
             continue
         if cls == "dgrad" and i == 0 and not needs_dx:
             continue
@@ -119,7 +137,12 @@ def np_prod(shape):
 
 
 def cpu_baseline(w, s, policy, minibatches):
-    """The oracle as it stands, timed on the host: the same stage, the same step, fp64 numpy."""
+    """The oracle as it stands, timed on the host: the same stage, the same step, fp64 numpy.  The transformer
+    stage is timed on mini-batches of one sequence (the oracle's cost is linear in the number of sequences)."""
+    from dataclasses import replace
+    if w.name.startswith("tfm"):
+        w = replace(w, mb=1, n=1)
+        minibatches = 1
     import numpy as np
     from oracle.stage import Stage
     from synth_inputs import workloads as W
@@ -149,8 +172,8 @@ def cpu_baseline(w, s, policy, minibatches):
         fwd(j + depth)
     dt = time.perf_counter() - t0
     return {"value": minibatches * w.n * w.mb / dt, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{minibatches} steady-state mini-batches ({minibatches * w.n * w.mb} samples) of the same stage, "
-                      f"numpy fp64, {dt:.1f} s"}
+            "sample": f"{minibatches} steady-state mini-batches of {w.n} x {w.mb} samples ({minibatches * w.n * w.mb} samples) "
+                      f"of the same stage, numpy fp64, {dt:.1f} s"}
 
 
 def main():
@@ -177,13 +200,20 @@ def main():
         w = W.mlp_wide(width=args.width, mb=args.mb or 256, n=args.n or 8)
         s = 1 if args.stage is None else args.stage
         what = f"stage {s} of the 4-stage 8-layer GELU MLP width {args.width}"
-    else:
+    elif args.workload == "vgg":
         w = W.vgg_stage0(mb=args.mb or 64, n=args.n or 4)
         s = 0
         if args.stage not in (None, 0):
             sys.exit("bench.py: the vgg workload describes stage 0 only")
         what = ("stage 0 (conv3-64, conv3-64, pool, conv3-128, conv3-128, pool; ReLU) of the 4-stage VGG-16-style "
                 "net on 32x32x3 images")
+    else:
+        w = W.transformer_stage(layers=args.blocks, mb=args.mb or 8, n=args.n or 4)
+        s = 1
+        if args.stage not in (None, 1):
+            sys.exit("bench.py: the tfm workload describes stage 1 only")
+        what = (f"stage 1 ({args.blocks} pre-norm decoder blocks, d_model 2048, 16 heads, FFN 8192, 1024 tokens; a sample "
+                "is one sequence) of the 4-stage decoder-only transformer")
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     depth = w.K - s
