@@ -449,9 +449,16 @@ bool attention_supported(int S, int heads, int dh) {
   return S >= 1 && heads >= 1 && heads <= 65535 && dh >= 1 && dh <= kMaxDh;
 }
 
+size_t attention_scratch_bytes(int elt, int seqs, int S, int heads, int dh) {
+  return elt == ELT_BF16 && attention_mfma_supported(S, heads, dh) ? attention_mfma_scratch_bytes(seqs, S, heads) : 0;
+}
+
 hipError_t launch_attention_fwd(hipStream_t s, int elt, int seqs, int S, int heads, int dh, const void* qkv, void* out,
-                                float* lse) {
+                                float* lse, void* scratch, size_t scratch_bytes) {
   if (!attention_supported(S, heads, dh) || seqs > 65535) return hipErrorInvalidValue;
+  if (elt == ELT_BF16 && scratch && attention_mfma_supported(S, heads, dh) &&
+      scratch_bytes >= attention_mfma_scratch_bytes(1, S, heads))
+    return attention_mfma_fwd(s, seqs, S, heads, dh, (const uint16_t*)qkv, (uint16_t*)out, lse, scratch, scratch_bytes);
   const float scale = 1.0f / sqrtf((float)dh);
   const dim3 grid((S + kRows - 1) / kRows, heads, seqs);
   const size_t lds = (size_t)(kRows + 2 * kTile) * (dh + 1) * sizeof(float);
@@ -492,8 +499,12 @@ static hipError_t attention_bwd_typed(hipStream_t s, int seqs, int S, int heads,
 }
 
 hipError_t launch_attention_bwd(hipStream_t s, int elt, int seqs, int S, int heads, int dh, const void* qkv, const void* out,
-                                const void* dout, const float* lse, void* dqkv) {
+                                const void* dout, const float* lse, void* dqkv, void* scratch, size_t scratch_bytes) {
   if (!attention_supported(S, heads, dh) || seqs > 65535) return hipErrorInvalidValue;
+  if (elt == ELT_BF16 && scratch && attention_mfma_supported(S, heads, dh) &&
+      scratch_bytes >= attention_mfma_scratch_bytes(1, S, heads))
+    return attention_mfma_bwd(s, seqs, S, heads, dh, (const uint16_t*)qkv, (const uint16_t*)dout, lse, (uint16_t*)dqkv, scratch,
+                              scratch_bytes);
   if (elt == ELT_BF16)
     return attention_bwd_typed<uint16_t>(s, seqs, S, heads, dh, (const uint16_t*)qkv, (const uint16_t*)out, (const uint16_t*)dout,
                                          lse, (uint16_t*)dqkv);

@@ -66,6 +66,7 @@ struct Plan {
   uint64_t act_slot_bytes = 0;
   uint64_t dz_bytes = 0;       // one backward temporary
   uint64_t partial_floats = 0; // reduction partials
+  uint64_t attn_scratch_bytes = 0;  // transient score matrices of the matrix-core attention
   size_t elt_size = 4;
 };
 
@@ -187,6 +188,9 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
       lp.out_elems = (uint64_t)lp.tokens * L.out_features;
       lp.w_elems = 0;
       lp.stat_elems = (uint64_t)lp.tokens * L.geom[1];
+      p->attn_scratch_bytes = std::max<uint64_t>(
+          p->attn_scratch_bytes,
+          tp::attention_scratch_bytes(d->dtype, (int)rows, lp.tokens, L.geom[1], L.out_features / L.geom[1]));
     } else if (L.type == TP_LAYER_RESIDUAL) {
       lp.tokens = L.geom[0];
       lp.in_elems = lp.out_elems = (uint64_t)lp.tokens * L.in_features;
@@ -258,7 +262,7 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
   s.wfwd_bytes = d->dtype == TP_BF16 ? P * 2 : 0;
   s.wbwd_bytes = P * p->elt_size;
   s.act_bytes = (uint64_t)d->max_in_flight * act;
-  s.scratch_bytes = 3 * p->dz_bytes + p->partial_floats * 4 + 512;  // + an aligned block of 256 zero bytes (conv padding)
+  s.scratch_bytes = 3 * p->dz_bytes + p->partial_floats * 4 + 512 + p->attn_scratch_bytes;  // + an aligned block of 256 zero bytes (conv padding)
   s.diag_bytes = TP_DIAG_COUNT * sizeof(double);
   return TP_OK;
 }
@@ -310,6 +314,7 @@ struct tp_stage {
     const uintptr_t p = (uintptr_t)bufs.scratch_dev + 3 * plan.dz_bytes + plan.partial_floats * 4;
     return (const void*)((p + 255) & ~(uintptr_t)255);
   }
+  void* attn_scratch() const { return plan.attn_scratch_bytes ? (char*)zeros() + 256 : nullptr; }
   // drop a version that nobody needs any more
   void evict_if_unused(uint64_t v) {
     int s = find_slot(v);
@@ -589,7 +594,7 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
       float* lse = (float*)(aslot + lp.stat_off) + row0 * lp.stat_elems;
       const int heads = lp.d.geom[1];
       HIP_TRY(tp::launch_attention_fwd(st->stream, d.dtype, d.mb, lp.tokens, heads, lp.d.out_features / heads, x_saved, a_out,
-                                       lse));
+                                       lse, st->attn_scratch(), st->plan.attn_scratch_bytes));
       continue;
     }
     if (lp.d.type == TP_LAYER_RESIDUAL) {
@@ -765,7 +770,8 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
           ProfScope ps(st, TP_K_ATTN);
           HIP_TRY(tp::launch_attention_bwd(st->stream, d.dtype, rows, lp.tokens, heads, lp.d.out_features / heads,
                                            aslot + lp.x_off, aslot + st->plan.layers[l + 1].x_off, dz,
-                                           (const float*)(aslot + lp.stat_off), dst));
+                                           (const float*)(aslot + lp.stat_off), dst, st->attn_scratch(),
+                                           st->plan.attn_scratch_bytes));
         }
         if (int rc = through_activation(dst)) return rc;
         dz = dst;

@@ -24,12 +24,25 @@ hipError_t launch_add(hipStream_t s, int elt, size_t count, const void* a, const
 
 // qkv: [seqs*S x 3*D] (queries | keys | values, head h in columns h*dh..), out: [seqs*S x D],
 // lse: [seqs*heads*S] log-sum-exp of the scaled scores of each query (kept for the backward pass).
+// scratch (may be null): attention_scratch_bytes(elt, seqs, S, heads, dh) bytes let bf16 shapes the matrix-core
+// kernels take run there; without it, and for every other shape, the wavefront kernels run.
 hipError_t launch_attention_fwd(hipStream_t s, int elt, int seqs, int S, int heads, int dh, const void* qkv, void* out,
-                                float* lse);
+                                float* lse, void* scratch, size_t scratch_bytes);
+size_t attention_scratch_bytes(int elt, int seqs, int S, int heads, int dh);
 // dqkv: [seqs*S x 3*D] from dout, the saved qkv, the saved output and lse.
 hipError_t launch_attention_bwd(hipStream_t s, int elt, int seqs, int S, int heads, int dh, const void* qkv, const void* out,
-                                const void* dout, const float* lse, void* dqkv);
+                                const void* dout, const float* lse, void* dqkv, void* scratch, size_t scratch_bytes);
 // head widths the attention kernels take
 bool attention_supported(int S, int heads, int dh);
+
+// Matrix-core attention (bf16; kernels_attention_mfma.hip): same arguments and results as the two
+// launchers above, plus scratch for the transient score matrices (attention_mfma_scratch_bytes for the
+// largest number of sequences a call will see; a smaller scratch makes the call work in smaller chunks).
+bool attention_mfma_supported(int S, int heads, int dh);
+size_t attention_mfma_scratch_bytes(int seqs, int S, int heads);
+hipError_t attention_mfma_fwd(hipStream_t s, int seqs, int S, int heads, int dh, const uint16_t* qkv, uint16_t* out, float* lse,
+                              void* scratch, size_t scratch_bytes);
+hipError_t attention_mfma_bwd(hipStream_t s, int seqs, int S, int heads, int dh, const uint16_t* qkv, const uint16_t* dout,
+                              const float* lse, uint16_t* dqkv, void* scratch, size_t scratch_bytes);
 
 }  // namespace tp

@@ -49,6 +49,13 @@ def test_transformer_block_wide_heads_bf16():
     print(_run_stage(specs, "tfm_wide", "bf16", mb=2, n=2))
 
 
+def test_attention_matrix_core_ragged_tiles_bf16():
+    # 192 tokens (one and a half 128-row tiles), 3 heads of 64: the matrix-core attention with a ragged
+    # last tile, causal tile skipping and both contraction shortcuts; projections around it
+    specs = (W.Dense(64, 3 * 192, "none", tokens=192), W.Attention(192, 3, 192), W.Dense(192, 64, "none", tokens=192))
+    print(_run_stage(specs, "attn_mfma", "bf16", mb=2, n=2))
+
+
 def test_transformer_stage_reduced_bf16():
     # the decoder stage of the transformer workload at reduced size: 4 blocks (44 layers), d_model 256,
     # 4 heads of 64, FFN 1024, 128 tokens, micro-batch 2 x 2, depth 3 (staleness 0, 1, 2)
