@@ -108,6 +108,127 @@ __global__ __launch_bounds__(kThreads) void layernorm_bwd_kernel(size_t rows, in
     partial[(size_t)blockIdx.x * 2 * D + d] = sm[d] + sm[2 * D + d] + sm[4 * D + d] + sm[6 * D + d];
 }
 
+// bf16 rows whose width is NG * 512 (NG <= 8): every lane owns NG groups of 8 consecutive features,
+// reads them with 16-byte loads, keeps the row in registers between the two passes, and carries its
+// share of dgamma / dbeta in registers across the rows of the workgroup.
+__device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    f[2 * j] = __uint_as_float(w[j] << 16);
+    f[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
+  return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+}
+
+template <int NG>
+__global__ __launch_bounds__(kThreads) void layernorm_fwd_bf16_kernel(size_t rows, const uint16_t* __restrict__ x,
+                                                                      const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                                      uint16_t* __restrict__ y, float* __restrict__ stats) {
+  constexpr int D = NG * 512;
+  const int lane = threadIdx.x & 63;
+  const size_t r = (size_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  float v[NG][8];
+  float s = 0.f;
+#pragma unroll
+  for (int k = 0; k < NG; ++k) {
+    unpack8(*reinterpret_cast<const uint4*>(x + r * D + (lane + 64 * k) * 8), v[k]);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s += v[k][j];
+  }
+  const float mean = wave_sum(s) / D;
+  float q = 0.f;
+#pragma unroll
+  for (int k = 0; k < NG; ++k)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      v[k][j] -= mean;
+      q += v[k][j] * v[k][j];
+    }
+  const float rstd = rsqrtf(wave_sum(q) / D + kLnEps);
+#pragma unroll
+  for (int k = 0; k < NG; ++k) {
+    const int d0 = (lane + 64 * k) * 8;
+    const float4 g0 = *reinterpret_cast<const float4*>(gamma + d0), g1 = *reinterpret_cast<const float4*>(gamma + d0 + 4);
+    const float4 b0 = *reinterpret_cast<const float4*>(beta + d0), b1 = *reinterpret_cast<const float4*>(beta + d0 + 4);
+    const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w}, b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+    float o[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = fmaf(v[k][j] * rstd, g[j], b[j]);
+    *reinterpret_cast<uint4*>(y + r * D + d0) = pack8(o);
+  }
+  if (lane == 0) {
+    stats[2 * r] = mean;
+    stats[2 * r + 1] = rstd;
+  }
+}
+
+template <int NG>
+__global__ __launch_bounds__(kThreads) void layernorm_bwd_bf16_kernel(size_t rows, int rows_per_block, const uint16_t* __restrict__ dy,
+                                                                      const uint16_t* __restrict__ x, const float* __restrict__ stats,
+                                                                      const float* __restrict__ gamma_s, const float* __restrict__ gamma_l,
+                                                                      float alpha, float beta_c, uint16_t* __restrict__ dx,
+                                                                      float* __restrict__ partial) {
+  constexpr int D = NG * 512;
+  extern __shared__ float sm[];  // [4 waves][2*D]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float g[NG][8], dg[NG][8], db[NG][8];
+#pragma unroll
+  for (int k = 0; k < NG; ++k) {
+    const int d0 = (lane + 64 * k) * 8;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      g[k][j] = fmaf(alpha, gamma_s[d0 + j], beta_c * gamma_l[d0 + j]);
+      dg[k][j] = db[k][j] = 0.f;
+    }
+  }
+  const size_t r0 = (size_t)blockIdx.x * rows_per_block;
+  const size_t r1 = std::min(rows, r0 + rows_per_block);
+  for (size_t r = r0 + wave; r < r1; r += kThreads / 64) {
+    const float mean = stats[2 * r], rstd = stats[2 * r + 1];
+    float xh[NG][8], dyv[NG][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int k = 0; k < NG; ++k) {
+      const size_t at = r * D + (lane + 64 * k) * 8;
+      unpack8(*reinterpret_cast<const uint4*>(x + at), xh[k]);
+      unpack8(*reinterpret_cast<const uint4*>(dy + at), dyv[k]);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        xh[k][j] = (xh[k][j] - mean) * rstd;
+        const float dxh = dyv[k][j] * g[k][j];
+        s1 += dxh;
+        s2 += dxh * xh[k][j];
+        dg[k][j] += dyv[k][j] * xh[k][j];
+        db[k][j] += dyv[k][j];
+      }
+    }
+    s1 = wave_sum(s1) / D;
+    s2 = wave_sum(s2) / D;
+#pragma unroll
+    for (int k = 0; k < NG; ++k) {
+      float o[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o[j] = rstd * (dyv[k][j] * g[k][j] - s1 - xh[k][j] * s2);
+      *reinterpret_cast<uint4*>(dx + r * D + (lane + 64 * k) * 8) = pack8(o);
+    }
+  }
+  float* mine = sm + (size_t)wave * 2 * D;
+#pragma unroll
+  for (int k = 0; k < NG; ++k)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      mine[(lane + 64 * k) * 8 + j] = dg[k][j];
+      mine[D + (lane + 64 * k) * 8 + j] = db[k][j];
+    }
+  __syncthreads();
+  for (int d = threadIdx.x; d < 2 * D; d += kThreads)
+    partial[(size_t)blockIdx.x * 2 * D + d] = sm[d] + sm[2 * D + d] + sm[4 * D + d] + sm[6 * D + d];
+}
+
 template <typename T>
 __global__ __launch_bounds__(kThreads) void add_kernel(size_t count, const T* a, const T* b, T* out) {
   const size_t stride = (size_t)gridDim.x * kThreads;
@@ -393,6 +514,16 @@ inline int ln_rows_per_block(size_t rows) { return (int)std::max<size_t>(4, (row
 hipError_t launch_layernorm_fwd(hipStream_t s, int elt, size_t rows, int D, const void* x, const float* gamma,
                                 const float* beta, void* y, float* stats) {
   const unsigned blocks = (unsigned)((rows + 3) / 4);
+  if (elt == ELT_BF16 && D % 512 == 0 && D <= 4096 && !(((uintptr_t)x | (uintptr_t)y) & 15)) {
+    switch (D / 512) {
+#define TP_LN_FWD(NG) \
+  case NG: hipLaunchKernelGGL(layernorm_fwd_bf16_kernel<NG>, dim3(blocks), dim3(kThreads), 0, s, rows, (const uint16_t*)x, gamma, \
+                              beta, (uint16_t*)y, stats); break;
+      TP_LN_FWD(1) TP_LN_FWD(2) TP_LN_FWD(3) TP_LN_FWD(4) TP_LN_FWD(5) TP_LN_FWD(6) TP_LN_FWD(7) TP_LN_FWD(8)
+#undef TP_LN_FWD
+    }
+    return hipGetLastError();
+  }
   if (elt == ELT_BF16)
     hipLaunchKernelGGL(layernorm_fwd_kernel<uint16_t>, dim3(blocks), dim3(kThreads), 0, s, rows, D, (const uint16_t*)x, gamma,
                        beta, (uint16_t*)y, stats);
@@ -420,7 +551,20 @@ hipError_t launch_layernorm_bwd(hipStream_t s, int elt, size_t rows, int D, cons
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (attr_h != hipSuccess) return attr_h;
   if (attr_f != hipSuccess) return attr_f;
-  if (elt == ELT_BF16)
+  if (elt == ELT_BF16 && D % 512 == 0 && D <= 2048 && !(((uintptr_t)x | (uintptr_t)dy | (uintptr_t)dx) & 15)) {
+    switch (D / 512) {
+#define TP_LN_BWD(NG)                                                                                                         \
+  case NG: {                                                                                                                  \
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(layernorm_bwd_bf16_kernel<NG>),                \
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);                    \
+    if (attr != hipSuccess) return attr;                                                                                      \
+    hipLaunchKernelGGL(layernorm_bwd_bf16_kernel<NG>, dim3(blocks), dim3(kThreads), lds, s, rows, rpb, (const uint16_t*)dy,   \
+                       (const uint16_t*)x, stats, gamma_s, gamma_l, alpha, beta_c, (uint16_t*)dx, partials);                  \
+  } break;
+      TP_LN_BWD(1) TP_LN_BWD(2) TP_LN_BWD(3) TP_LN_BWD(4)
+#undef TP_LN_BWD
+    }
+  } else if (elt == ELT_BF16)
     hipLaunchKernelGGL(layernorm_bwd_kernel<uint16_t>, dim3(blocks), dim3(kThreads), lds, s, rows, D, rpb, (const uint16_t*)dy,
                        (const uint16_t*)x, stats, gamma_s, gamma_l, alpha, beta_c, (uint16_t*)dx, partials);
   else

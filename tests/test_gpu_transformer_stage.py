@@ -16,6 +16,12 @@ def test_layernorm_and_per_token_dense(dtype):
     print(dtype, _run_stage(specs, f"ln_{dtype}", dtype, mb=3, n=2))
 
 
+def test_layernorm_wide_rows_bf16():
+    # widths 512 and 1536: the register-resident bf16 normalisation kernels (rows of 1 and 3 groups per lane)
+    specs = (W.LayerNorm(512, 5), W.Dense(512, 1536, "gelu", tokens=5), W.LayerNorm(1536, 5), W.Dense(1536, 64, "none", tokens=5))
+    print(_run_stage(specs, "ln_wide", "bf16", mb=3, n=2))
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_attention_alone(dtype):
     # qkv projection -> attention -> output projection; 21 tokens: ragged against the 16-row / 64-key tiles
