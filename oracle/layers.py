@@ -200,3 +200,34 @@ def attention_backward(dout, qkv, heads):
     dk = ds.transpose(0, 1, 3, 2) @ q / np.sqrt(dh)
     back = lambda t: t.transpose(0, 2, 1, 3).reshape(B, S, D)
     return np.concatenate([back(dq), back(dk), back(dv)], axis=-1)
+
+
+# ---------------------------------------------------------------------------
+# Batch normalisation (training mode) for the bottleneck-shaped workload: statistics over all rows
+# (samples x positions) of what one forward call sees, per channel.  Standard definition.
+# ---------------------------------------------------------------------------
+
+BN_EPS = 1e-5
+
+
+def batchnorm_forward(x, gamma, beta, eps=BN_EPS):
+    """x: [..., C]; y = gamma * (x - mean_c) / sqrt(var_c + eps) + beta with mean/var over every leading index
+    (biased variance).  Returns y, the normalised values and 1/sqrt(var + eps) per channel."""
+    C = x.shape[-1]
+    x2 = x.reshape(-1, C)
+    mu = x2.mean(axis=0)
+    var = ((x2 - mu) ** 2).mean(axis=0)
+    rstd = 1.0 / np.sqrt(var + eps)
+    xhat = (x - mu) * rstd
+    return xhat * gamma + beta, xhat, rstd
+
+
+def batchnorm_backward(dy, xhat, rstd, gamma_b):
+    """Gradients of batchnorm_forward; gamma_b is the scale the backward pass is told to use."""
+    C = dy.shape[-1]
+    dy2, xh2 = dy.reshape(-1, C), xhat.reshape(-1, C)
+    R = dy2.shape[0]
+    dgamma = (dy2 * xh2).sum(axis=0)
+    dbeta = dy2.sum(axis=0)
+    dx = (gamma_b * rstd / R) * (R * dy - dbeta - xhat * dgamma)
+    return dgamma, dbeta, dx

@@ -89,6 +89,7 @@ class Stage:
         for li, spec in enumerate(self.specs):
             kind = getattr(spec, "kind", "dense")
             pi = self.pidx[li]
+            a = a.reshape((a.shape[0],) + tuple(spec.in_shape()))   # same memory, the layer's own view of a sample
             if kind == "pool":
                 y, idx = L.maxpool2_forward(a)
                 saved.append((a.shape, idx))
@@ -97,9 +98,16 @@ class Stage:
             if kind == "res":
                 if spec.mark == "begin":
                     skip = a
+                    saved.append(None)
                 else:
-                    a = self.q(a + skip)
-                saved.append(None)
+                    z = a + skip.reshape(a.shape)
+                    saved.append((None, z))
+                    a = self.q(L.act_forward(z, spec.act))
+                continue
+            if kind == "bn":
+                y, xhat, rstd = L.batchnorm_forward(a, W[pi], W[pi + 1])
+                saved.append((xhat, rstd, y))
+                a = self.q(L.act_forward(y, spec.act))
                 continue
             if kind == "ln":
                 y, xhat, rstd = L.layernorm_forward(a, W[pi], W[pi + 1])
@@ -159,15 +167,28 @@ class Stage:
                 spec = self.specs[li]
                 kind = getattr(spec, "kind", "dense")
                 pi = self.pidx[li]
+                da = da.reshape((da.shape[0],) + tuple(spec.out_shape()))
+                if dskip is not None:
+                    dskip = dskip.reshape(da.shape) if dskip.size == da.size else dskip
                 if kind == "pool":
                     in_shape, idx = saved[li]
                     da = L.maxpool2_backward(da, idx, in_shape)
                     continue
                 if kind == "res":
                     if spec.mark == "add":
+                        da = self.q(da * L.act_derivative(saved[li][1], spec.act))
                         dskip = da
                     else:
-                        da = self.q(da + dskip)
+                        da = self.q(da + dskip.reshape(da.shape))
+                        dskip = None
+                    continue
+                if kind == "bn":
+                    xhat, rstd, y = saved[li]
+                    dyv = self.q(da * L.act_derivative(y, spec.act))
+                    dgamma, dbeta, da = L.batchnorm_backward(dyv, xhat, rstd, W_b[pi])
+                    g[pi] += dgamma
+                    g[pi + 1] += dbeta
+                    da = self.q(da)
                     continue
                 if kind == "ln":
                     xhat, rstd = saved[li]

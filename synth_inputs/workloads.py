@@ -65,6 +65,28 @@ class LayerNorm:
 
 
 @dataclass(frozen=True)
+class BatchNorm:
+    """Batch normalisation (training mode) over all samples and positions of a micro-batch, per channel, on
+    [tokens, c] samples (tokens = H*W of an NHWC image), followed by an activation; parameters scale and shift."""
+    c: int
+    tokens: int
+    act: str = "none"
+    kind: str = "bn"
+
+    def param_shapes(self):
+        return [(self.c,), (self.c,)]
+
+    def in_shape(self):
+        return (self.tokens, self.c)
+
+    def out_shape(self):
+        return (self.tokens, self.c)
+
+    def out_dim(self):
+        return self.tokens * self.c
+
+
+@dataclass(frozen=True)
 class Attention:
     """Causal multi-head self-attention on [tokens, 3*d] (queries | keys | values) -> [tokens, d]; no parameters."""
     d: int
@@ -88,7 +110,8 @@ class Attention:
 
 @dataclass(frozen=True)
 class Residual:
-    """mark = "begin": remember the current activation; mark = "add": add the remembered one. No parameters."""
+    """mark = "begin": remember the current activation; mark = "add": add the remembered one, then apply the
+    activation (if any). No parameters."""
     d: int
     tokens: int
     mark: str
@@ -235,6 +258,25 @@ def vgg_stage0(mb: int = 64, n: int = 4, size: int = 32, c1: int = 64, c2: int =
                     classes=classes)
 
 
+def bottleneck_block(c: int, mid: int, h: int, w: int) -> tuple:
+    """Identity bottleneck of a ResNet-50-style net on [h, w, c] images: 1x1 conv c->mid, BN, ReLU, 3x3 conv
+    mid->mid, BN, ReLU, 1x1 conv mid->c, BN, add the block input, ReLU.  1x1 convolutions are per-position
+    dense layers; NHWC images and [positions, channels] samples are the same memory."""
+    t = h * w
+    return (Residual(c, t, "begin"), Dense(c, mid, "none", tokens=t), BatchNorm(mid, t, "relu"),
+            Conv2d(mid, mid, h, w, "none"), BatchNorm(mid, t, "relu"), Dense(mid, c, "none", tokens=t),
+            BatchNorm(c, t, "none"), Residual(c, t, "add", act="relu"))
+
+
+def bottleneck_stage(c: int = 1024, mid: int = 256, h: int = 4, w: int = 4, blocks: int = 5, mb: int = 128, n: int = 4,
+                     dtype: str = "bf16") -> Workload:
+    """The identity bottlenecks of the conv4_x group of a ResNet-50-style net on 64x64 inputs (4x4 feature
+    maps, 1024 channels), as an interior stage.  The group's first block (stride 2, projection shortcut) is
+    not described."""
+    layers = tuple(l for _ in range(blocks) for l in bottleneck_block(c, mid, h, w))
+    return Workload(name=f"bneck{c}x{blocks}_{dtype}_s1", dtype=dtype, stages=((), layers, (), ()), mb=mb, n=n, classes=2)
+
+
 def transformer_block(d: int, heads: int, ffn: int, tokens: int) -> tuple:
     """Pre-norm decoder block: x + proj(attn(qkv(LN(x)))), then x + ffn2(gelu(ffn1(LN(x))))."""
     return (Residual(d, tokens, "begin"), LayerNorm(d, tokens), Dense(d, 3 * d, "none", tokens=tokens),
@@ -271,7 +313,7 @@ def init_params(w: Workload, s: int) -> List[np.ndarray]:
         if not layer.param_shapes():
             continue
         wshape, bshape = layer.param_shapes()
-        if layer.kind == "ln":                               # scale 1, shift 0
+        if layer.kind in ("ln", "bn"):                       # scale 1, shift 0
             out.append(np.ones(wshape, dtype=np.float64))
             out.append(np.zeros(bshape, dtype=np.float64))
             continue
