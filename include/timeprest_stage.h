@@ -88,9 +88,13 @@ enum tp_layer_type {
   TP_LAYER_ATTENTION = 4, /* causal multi-head self-attention, no parameters: in_features = 3*D (queries | keys |
                              values, head h in columns h*D/heads ..), out_features = D, geom = {tokens, heads};
                              must not be the last layer of a stage (its output is kept for the backward pass) */
-  TP_LAYER_RESIDUAL = 5   /* skip connection, no parameters: in_features = out_features = D, geom = {tokens, mark};
+  TP_LAYER_RESIDUAL = 5,  /* skip connection, no parameters: in_features = out_features = D, geom = {tokens, mark};
                              mark 0 remembers the activation at this point, mark 1 adds the remembered one to
-                             the activation at this point; marks alternate 0, 1, 0, 1, ... within a stage    */
+                             the activation at this point and applies `act`; marks alternate 0, 1, 0, 1, ...  */
+  TP_LAYER_BATCHNORM = 6  /* batch normalisation in training mode + act (BASELINE configuration 4): statistics per
+                             channel over all samples and positions of the micro-batch a forward call sees, biased
+                             variance, eps 1e-5; in_features = out_features = C, geom = {positions per sample};
+                             parameters gamma[C], beta[C] (fp32 in every mode); no running statistics are kept */
 };
 
 #define TP_MAX_LAYERS 64
@@ -102,7 +106,7 @@ typedef struct tp_layer_desc {
   int32_t in_features;  /* dense: columns of the layer input;  conv/pool: input channels;  others: see the type */
   int32_t out_features; /* dense: columns of the layer output; conv/pool: output channels; others: see the type */
   int32_t geom[5];      /* conv: {H, W, kernel, stride, pad}; pool: {H, W, 0, 0, 0}; dense, layer norm: {tokens};
-                           attention: {tokens, heads}; residual: {tokens, mark}; unused entries zero */
+                           attention: {tokens, heads}; residual: {tokens, mark}; batch norm: {positions}; unused entries zero */
   int32_t reserved[7];  /* must be zero */
 } tp_layer_desc;
 

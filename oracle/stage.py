@@ -89,7 +89,8 @@ class Stage:
         for li, spec in enumerate(self.specs):
             kind = getattr(spec, "kind", "dense")
             pi = self.pidx[li]
-            a = a.reshape((a.shape[0],) + tuple(spec.in_shape()))   # same memory, the layer's own view of a sample
+            if hasattr(spec, "in_shape"):                  # same memory, the layer's own view of a sample
+                a = a.reshape((a.shape[0],) + tuple(spec.in_shape()))
             if kind == "pool":
                 y, idx = L.maxpool2_forward(a)
                 saved.append((a.shape, idx))
@@ -167,7 +168,8 @@ class Stage:
                 spec = self.specs[li]
                 kind = getattr(spec, "kind", "dense")
                 pi = self.pidx[li]
-                da = da.reshape((da.shape[0],) + tuple(spec.out_shape()))
+                if hasattr(spec, "out_shape"):
+                    da = da.reshape((da.shape[0],) + tuple(spec.out_shape()))
                 if dskip is not None:
                     dskip = dskip.reshape(da.shape) if dskip.size == da.size else dskip
                 if kind == "pool":

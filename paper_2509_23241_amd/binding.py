@@ -10,7 +10,7 @@ TP_OK, TP_EINVAL, TP_ESTATE, TP_ENOVERSION, TP_EFULL, TP_EBUSY, TP_EHIP = 0, -1,
 TP_LATEST, TP_INTERMEDIATE_EQ1, TP_INTERMEDIATE_CONVEX, TP_STASHED = 0, 1, 2, 3
 TP_F32, TP_BF16 = 0, 1
 TP_ACT_NONE, TP_ACT_RELU, TP_ACT_GELU = 0, 1, 2
-TP_LAYER_DENSE, TP_LAYER_CONV2D, TP_LAYER_MAXPOOL2, TP_LAYER_LAYERNORM, TP_LAYER_ATTENTION, TP_LAYER_RESIDUAL = 0, 1, 2, 3, 4, 5
+TP_LAYER_DENSE, TP_LAYER_CONV2D, TP_LAYER_MAXPOOL2, TP_LAYER_LAYERNORM, TP_LAYER_ATTENTION, TP_LAYER_RESIDUAL, TP_LAYER_BATCHNORM = 0, 1, 2, 3, 4, 5, 6
 TP_MAX_LAYERS, TP_MAX_SLOTS, TP_MAX_IN_FLIGHT = 64, 16, 16
 TP_NONE = (1 << 64) - 1
 TP_DIAG_GRAD_SQ, TP_DIAG_WEIGHT_SQ, TP_DIAG_DRIFT_SQ, TP_DIAG_WB_SQ, TP_DIAG_COUNT = 0, 1, 2, 3, 4
@@ -126,7 +126,8 @@ def make_desc(layers, *, dtype, mb, n, stage_index, num_stages, ring_capacity, m
               lam, lr, momentum) -> tp_stage_desc:
     """layers: sequence of (in_features, out_features, act-name[, tokens]) for dense layers,
     ("conv", cin, cout, H, W, act-name) for 3x3/stride 1/pad 1 convolutions, ("pool", C, H, W) for 2x2 pooling,
-    ("ln", D, tokens), ("attn", D, heads, tokens), ("res", D, tokens, "begin" | "add")."""
+    ("ln", D, tokens), ("attn", D, heads, tokens), ("res", D, tokens, "begin" | "add"[, act-name]),
+    ("bn", C, positions, act-name)."""
     if len(layers) > TP_MAX_LAYERS:
         raise ValueError(f"{len(layers)} layers: a stage takes at most {TP_MAX_LAYERS}")
     d = tp_stage_desc()
@@ -160,10 +161,14 @@ def make_desc(layers, *, dtype, mb, n, stage_index, num_stages, ring_capacity, m
             L.type, L.in_features, L.out_features = TP_LAYER_ATTENTION, 3 * dm, dm
             L.geom[0], L.geom[1] = tokens, heads
         elif spec[0] == "res":
-            _, dm, tokens, mark = spec
-            act = "none"
+            _, dm, tokens, mark = spec[:4]
+            act = spec[4] if len(spec) > 4 else "none"
             L.type, L.in_features, L.out_features = TP_LAYER_RESIDUAL, dm, dm
             L.geom[0], L.geom[1] = tokens, {"begin": 0, "add": 1}[mark]
+        elif spec[0] == "bn":
+            _, ch, tokens, act = spec
+            L.type, L.in_features, L.out_features = TP_LAYER_BATCHNORM, ch, ch
+            L.geom[0] = tokens
         else:
             fin, fout, act = spec[:3]
             L.type, L.in_features, L.out_features = TP_LAYER_DENSE, fin, fout
@@ -178,7 +183,7 @@ def layer_in_elems(spec) -> int:
         return spec[3] * spec[4] * spec[1]
     if spec[0] == "pool":
         return spec[2] * spec[3] * spec[1]
-    if spec[0] == "ln":
+    if spec[0] in ("ln", "bn"):
         return spec[1] * spec[2]
     if spec[0] == "attn":
         return 3 * spec[1] * spec[3]
@@ -192,7 +197,7 @@ def layer_out_elems(spec) -> int:
         return spec[3] * spec[4] * spec[2]
     if spec[0] == "pool":
         return (spec[2] // 2) * (spec[3] // 2) * spec[1]
-    if spec[0] == "ln":
+    if spec[0] in ("ln", "bn"):
         return spec[1] * spec[2]
     if spec[0] == "attn":
         return spec[1] * spec[3]
@@ -206,7 +211,7 @@ def layer_param_shapes(spec):
         return [(spec[2], 3, 3, spec[1]), (spec[2],)]
     if spec[0] in ("pool", "attn", "res"):
         return []
-    if spec[0] == "ln":
+    if spec[0] in ("ln", "bn"):
         return [(spec[1],), (spec[1],)]
     return [(spec[1], spec[0]), (spec[1],)]
 

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIBDIR = os.path.join(HERE, "lib")
 LIBNAME = "libtimeprest_stage.so"
-SOURCES = ["stage_api.cpp", "kernels_elementwise.hip", "kernels_gemm.hip", "kernels_gemm_mfma.hip", "kernels_conv.hip", "kernels_conv_mfma.hip", "kernels_transformer.hip", "kernels_attention_mfma.hip"]
+SOURCES = ["stage_api.cpp", "kernels_elementwise.hip", "kernels_gemm.hip", "kernels_gemm_mfma.hip", "kernels_conv.hip", "kernels_conv_mfma.hip", "kernels_transformer.hip", "kernels_attention_mfma.hip", "kernels_batchnorm.hip"]
 
 # Packed fp32 instructions are switched off for all device code.
 HIPCC_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

@@ -1,0 +1,26 @@
+// Batch normalisation in training mode on [rows x C] activations (row = one position of one sample of
+// the micro-batch the call sees): per-channel statistics over the rows, scale, shift, activation.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace tp {
+
+// a = act(gamma (x - mean)/sqrt(var + 1e-5) + beta), d = act' of the same pre-activation (d_out may be null);
+// stats[2c] = mean_c, stats[2c+1] = 1/sqrt(var_c + eps) are kept for the backward pass.  Mean and variance are
+// formed in two passes over x (no E[x^2] - mean^2).  scratch: batchnorm_scratch_floats(rows, C) floats.
+hipError_t launch_batchnorm_fwd(hipStream_t s, int elt, size_t rows, int C, const void* x, const float* gamma, const float* beta,
+                                int act, void* a_out, void* d_out, float* stats, float* scratch);
+// dy: gradient with respect to the normalised, scaled and shifted value (the activation's derivative already
+// applied).  dx for the rows of this call; sums[0..C) = sum dy * xhat, sums[C..2C) = sum dy (this call's share of
+// dgamma, dbeta).  The scale of the backward pass is alpha*gamma_s + beta_c*gamma_l, formed in fp32.
+hipError_t launch_batchnorm_bwd(hipStream_t s, int elt, size_t rows, int C, const void* dy, const void* x, const float* stats,
+                                const float* gamma_s, const float* gamma_l, float alpha, float beta_c, void* dx, float* sums,
+                                float* scratch);
+size_t batchnorm_scratch_floats(size_t rows, int C);
+
+// out = act(a + b), d_out = act'(a + b) (null: not kept)
+hipError_t launch_add_act(hipStream_t s, int elt, size_t count, const void* a, const void* b, int act, void* out, void* d_out);
+
+}  // namespace tp

@@ -17,6 +17,7 @@
 
 #include "conv.h"
 #include "transformer.h"
+#include "batchnorm.h"
 #include "kernels.h"
 
 namespace {
@@ -42,6 +43,7 @@ struct LayerPlan {
   uint64_t xpad_off = UINT64_MAX;  // first image layer in bf16: the input again, padded to 8 channels per pixel
   uint64_t stat_off = UINT64_MAX;  // layer norm: mean and 1/std per token; attention: log-sum-exp per (head, query)
   uint64_t stat_elems = 0;         // floats per sample behind stat_off
+  uint64_t stat_bytes = 0;         // batch norm: bytes behind stat_off (per micro-batch, not per sample)
   int tokens = 1;                  // positions per sample (rows of the layer's matrices per sample)
   int skip_layer = -1;             // residual add: index of the layer that remembered the skip activation
 };
@@ -100,8 +102,13 @@ int check_desc(const tp_stage_desc* d) {
       const uint64_t T = L.geom[0] > 1 ? L.geom[0] : 1;
       in_e = T * L.in_features;
       out_e = T * L.out_features;
+    } else if (L.type == TP_LAYER_BATCHNORM) {
+      if (L.geom[0] < 1 || L.in_features != L.out_features || L.geom[1] || L.geom[2] || L.geom[3] || L.geom[4])
+        return fail(TP_EINVAL, "layer %d: malformed batch normalisation layer", l);
+      in_e = out_e = (uint64_t)L.geom[0] * L.in_features;
     } else if (L.type == TP_LAYER_LAYERNORM || L.type == TP_LAYER_RESIDUAL) {
-      if (L.geom[0] < 1 || L.in_features != L.out_features || L.act != TP_ACT_NONE || L.geom[2] || L.geom[3] || L.geom[4])
+      const bool act_ok = L.act == TP_ACT_NONE || (L.type == TP_LAYER_RESIDUAL && L.geom[1] == 1);
+      if (L.geom[0] < 1 || L.in_features != L.out_features || !act_ok || L.geom[2] || L.geom[3] || L.geom[4])
         return fail(TP_EINVAL, "layer %d: malformed %s layer", l, L.type == TP_LAYER_LAYERNORM ? "normalisation" : "residual");
       if (L.type == TP_LAYER_LAYERNORM && (L.geom[1] != 0 || L.in_features > 20480))
         return fail(TP_EINVAL, "layer %d: malformed normalisation layer", l);
@@ -182,6 +189,13 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
       lp.w_elems = L.in_features;                      // gamma; beta sits where a dense layer keeps its bias
       lp.stat_elems = 2 * (uint64_t)lp.tokens;
       norm_scratch = std::max<uint64_t>(norm_scratch, tp::layernorm_scratch_floats(rows * lp.tokens, L.in_features));
+    } else if (L.type == TP_LAYER_BATCHNORM) {
+      lp.tokens = L.geom[0];
+      lp.in_elems = lp.out_elems = (uint64_t)lp.tokens * L.in_features;
+      lp.w_elems = L.in_features;
+      lp.stat_bytes = (uint64_t)d->n * 2 * L.in_features * 4;   // (mean, 1/std) per channel and micro-batch
+      norm_scratch = std::max<uint64_t>(norm_scratch, tp::batchnorm_scratch_floats((size_t)d->mb * lp.tokens, L.in_features) +
+                                                          (uint64_t)d->n * 2 * L.in_features);
     } else if (L.type == TP_LAYER_ATTENTION) {
       lp.tokens = L.geom[0];
       lp.in_elems = (uint64_t)lp.tokens * L.in_features;
@@ -221,9 +235,9 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
       act += round_up(rows * lp.in_elems * p->elt_size, 256);
     }
     alias_prev = L.type == TP_LAYER_RESIDUAL && L.geom[1] == 0;
-    if (lp.stat_elems) {
+    if (lp.stat_elems || lp.stat_bytes) {
       lp.stat_off = act;
-      act += round_up(rows * lp.stat_elems * 4, 256);
+      act += round_up(lp.stat_bytes ? lp.stat_bytes : rows * lp.stat_elems * 4, 256);
     }
     if (L.act != TP_ACT_NONE) {
       lp.z_off = act;
@@ -249,7 +263,7 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
   for (const LayerPlan& lp : p->layers) {
     if (!lp.w_elems) continue;
     // bias gradients: column sums over rows (dense) or over all pixels (conv)
-    if (lp.d.type == TP_LAYER_LAYERNORM) continue;
+    if (lp.d.type == TP_LAYER_LAYERNORM || lp.d.type == TP_LAYER_BATCHNORM) continue;
     const uint64_t r = lp.d.type == TP_LAYER_CONV2D ? rows * lp.d.geom[0] * lp.d.geom[1] : rows * lp.tokens;
     wg = std::max<uint64_t>(wg, tp::colsum_scratch_floats((int)r, lp.d.out_features));
   }
@@ -601,7 +615,18 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
       if (lp.skip_layer < 0) continue;  // begin: the next layer reads this layer's input in place
       ProfScope ps(st, TP_K_ADD);
       const char* skip = aslot + st->plan.layers[lp.skip_layer].x_off + row0 * lp.in_elems * es;
-      HIP_TRY(tp::launch_add(st->stream, d.dtype, (size_t)d.mb * lp.in_elems, x_saved, skip, a_out));
+      if (lp.d.act == TP_ACT_NONE)
+        HIP_TRY(tp::launch_add(st->stream, d.dtype, (size_t)d.mb * lp.in_elems, x_saved, skip, a_out));
+      else
+        HIP_TRY(tp::launch_add_act(st->stream, d.dtype, (size_t)d.mb * lp.in_elems, x_saved, skip, lp.d.act, a_out, z_out));
+      continue;
+    }
+    if (lp.d.type == TP_LAYER_BATCHNORM) {
+      ProfScope ps(st, TP_K_NORM);
+      const int C = lp.d.in_features;
+      float* stats = (float*)(aslot + lp.stat_off) + (size_t)ub_idx * 2 * C;
+      HIP_TRY(tp::launch_batchnorm_fwd(st->stream, d.dtype, (size_t)d.mb * lp.tokens, C, x_saved, master + lp.w_off,
+                                       master + lp.b_off, lp.d.act, a_out, z_out, stats, st->partials()));
       continue;
     }
     if (lp.d.type == TP_LAYER_CONV2D) {
@@ -758,6 +783,30 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
           HIP_TRY(tp::launch_layernorm_bwd(st->stream, d.dtype, (size_t)rows * lp.tokens, lp.d.in_features, dz, aslot + lp.x_off,
                                            (const float*)(aslot + lp.stat_off), gs, gl, (float)ca, (float)cb, dst,
                                            g + lp.w_off, g + lp.b_off, st->partials()));
+        }
+        if (no_dx) break;
+        if (int rc = through_activation(dst)) return rc;
+        dz = dst;
+        continue;
+      }
+      if (lp.d.type == TP_LAYER_BATCHNORM) {
+        const int C = lp.d.in_features;
+        const float* gl = st->ring(slot_now) + lp.w_off;
+        const float* gs = delta != 0 ? st->ring(slot_f) + lp.w_off : gl;
+        const size_t seg_rows = (size_t)d.mb * lp.tokens;        // the statistics belong to one micro-batch
+        const size_t seg_bytes = seg_rows * C * es;
+        const size_t bn_scratch = tp::batchnorm_scratch_floats(seg_rows, C);
+        float* sums = st->partials() + bn_scratch;                // [n][2*C]
+        {
+          ProfScope ps(st, TP_K_NORM);
+          for (int ub = 0; ub < d.n; ++ub)
+            HIP_TRY(tp::launch_batchnorm_bwd(st->stream, d.dtype, seg_rows, C, (const char*)dz + ub * seg_bytes,
+                                             aslot + lp.x_off + ub * seg_bytes,
+                                             (const float*)(aslot + lp.stat_off) + (size_t)ub * 2 * C, gs, gl, (float)ca,
+                                             (float)cb, (char*)dst + ub * seg_bytes, sums + (size_t)ub * 2 * C,
+                                             st->partials()));
+          HIP_TRY(tp::launch_sum_partials_strided(st->stream, (size_t)C, d.n, sums, 2 * (size_t)C, g + lp.w_off));
+          HIP_TRY(tp::launch_sum_partials_strided(st->stream, (size_t)C, d.n, sums + C, 2 * (size_t)C, g + lp.b_off));
         }
         if (no_dx) break;
         if (int rc = through_activation(dst)) return rc;

@@ -26,7 +26,9 @@ def layer_tuple(spec) -> tuple:
     if kind == "attn":
         return ("attn", spec.d, spec.heads, spec.tokens)
     if kind == "res":
-        return ("res", spec.d, spec.tokens, spec.mark)
+        return ("res", spec.d, spec.tokens, spec.mark, spec.act)
+    if kind == "bn":
+        return ("bn", spec.c, spec.tokens, spec.act)
     return (spec.in_features, spec.out_features, spec.act, getattr(spec, "tokens", 1))
 
 

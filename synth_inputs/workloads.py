@@ -258,14 +258,15 @@ def vgg_stage0(mb: int = 64, n: int = 4, size: int = 32, c1: int = 64, c2: int =
                     classes=classes)
 
 
-def bottleneck_block(c: int, mid: int, h: int, w: int) -> tuple:
+def bottleneck_block(c: int, mid: int, h: int, w: int, act: str = "relu") -> tuple:
     """Identity bottleneck of a ResNet-50-style net on [h, w, c] images: 1x1 conv c->mid, BN, ReLU, 3x3 conv
     mid->mid, BN, ReLU, 1x1 conv mid->c, BN, add the block input, ReLU.  1x1 convolutions are per-position
-    dense layers; NHWC images and [positions, channels] samples are the same memory."""
+    dense layers; NHWC images and [positions, channels] samples are the same memory.  `act` replaces the ReLUs
+    (parity runs in bf16 use a smooth activation where they want the tight tolerance)."""
     t = h * w
-    return (Residual(c, t, "begin"), Dense(c, mid, "none", tokens=t), BatchNorm(mid, t, "relu"),
-            Conv2d(mid, mid, h, w, "none"), BatchNorm(mid, t, "relu"), Dense(mid, c, "none", tokens=t),
-            BatchNorm(c, t, "none"), Residual(c, t, "add", act="relu"))
+    return (Residual(c, t, "begin"), Dense(c, mid, "none", tokens=t), BatchNorm(mid, t, act),
+            Conv2d(mid, mid, h, w, "none"), BatchNorm(mid, t, act), Dense(mid, c, "none", tokens=t),
+            BatchNorm(c, t, "none"), Residual(c, t, "add", act=act))
 
 
 def bottleneck_stage(c: int = 1024, mid: int = 256, h: int = 4, w: int = 4, blocks: int = 5, mb: int = 128, n: int = 4,

@@ -26,9 +26,10 @@ def _run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, dept
 
     w = W.Workload(name=w_name, dtype=dtype, stages=(tuple(specs),) + ((),) * (depth - 1), mb=mb, n=n, classes=2)
     params = W.init_params(w, 0)
-    # biases away from zero so that their gradients and updates are exercised
+    # biases (and the scale / shift of normalisation layers) away from their initial 0 / 1, so that their
+    # gradients and updates are exercised
     rng = np.random.default_rng(7)
-    params = [p if p.ndim > 1 else W.round_f32(rng.standard_normal(p.shape) * 0.1) for p in params]
+    params = [p if p.ndim > 1 else W.round_f32(p + rng.standard_normal(p.shape) * 0.1) for p in params]
     # bf16 workloads: the oracle keeps its stored tensors in bf16 too (fp64 arithmetic), so that the
     # choice of the maximum in a pooling window is taken in the same precision on both sides
     ost = Stage(specs, params, policy=policy, lam=0.4, lr=lr, momentum=0.9, n=n, first_stage=not needs_dx,
@@ -49,9 +50,18 @@ def _run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, dept
     # ReLU are therefore held to the normal tolerance while both sides still run on identical
     # weights (mini-batches whose forward preceded the first update -- these cover every staleness
     # the schedule produces -- and everything in fp32) and to ROUTED_TOL afterwards.
-    ROUTED_TOL = 0.15
+    # Behind a batch normalisation the same happens without any update: two bf16 executions of a deep
+    # stack differ by one ulp in a percent of the activations, the division by a channel's standard
+    # deviation carries that onto the pre-activations, and a ReLU next to zero decides differently
+    # (measured: ~1e-3 of the mask of a 128-channel layer, concentrated in a few channels, 2-5 % on the
+    # gradients; the fp32 run of the same stack agrees to 1e-6 and a smooth activation to 5e-3).
+    # Stages with ReLU behind a batch normalisation are held to the loose tolerance in bf16 from the start
+    # (0.25 for them: the flips of several normalised layers add up); what pins their kernels is the fp32
+    # run and the bf16 run with a smooth activation, both at the normal tolerances.
     nonsmooth = any(l.kind == "pool" or getattr(l, "act", "") == "relu" for l in specs)
-    diverged = [False]
+    bn_relu = nonsmooth and any(l.kind == "bn" for l in specs)
+    ROUTED_TOL = 0.25 if bn_relu else 0.15
+    diverged = [bn_relu]
 
     def note(k, e, routed=False):
         worst[k] = max(worst.get(k, 0.0), e)
@@ -78,12 +88,21 @@ def _run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, dept
         dx, delta = st.backward(j, torch.from_numpy(dy.reshape(n * mb, -1)).cuda().to(st.tdtype))
         assert delta == ost.trace[-1][4]
         print(f"  mini-batch {j}: delta {delta}", {k: f"{v:.1e}" for k, v in worst.items()}, flush=True)
-        diverged[0] = j >= depth                     # this mini-batch's forward ran after an update
+        diverged[0] = bn_relu or j >= depth          # this mini-batch's forward ran after an update
         if needs_dx:
             note("dx", rel_err(to_np(dx), dx_ref.reshape(n * mb, -1)), routed=nonsmooth)
         note("g", rel_err(to_np(st.grad), oracle_flat_to_arena(st, ost.flat(ost.g))), routed=nonsmooth)
+        # per-tensor gradients.  A tensor whose true gradient is zero (a bias in front of a batch
+        # normalisation: the mean subtraction removes it; what is left is the cancellation noise of a sum of
+        # terms that add up to zero) has no scale of its own: such tensors are measured against the typical
+        # gradient entry instead of their own (rounding-noise) norm.
+        g_rms = float(np.sqrt(np.mean(np.concatenate([r.reshape(-1) for r in ost.g]) ** 2)))
         for pi, (got, ref) in enumerate(zip(st.unpack(to_np(st.grad)), ost.g)):
-            note(f"g[{pi}]", rel_err(got, ref), routed=nonsmooth)
+            floor = g_rms * np.sqrt(ref.size)
+            if np.linalg.norm(ref) < 0.05 * floor:
+                note(f"g[{pi}]", float(np.linalg.norm(got.reshape(-1) - ref.reshape(-1)) / floor), routed=nonsmooth)
+            else:
+                note(f"g[{pi}]", rel_err(got, ref), routed=nonsmooth)
         ost.update(j)
         assert st.blend_update(j, j + 1) == ost.latest
         note("W_new", rel_err(to_np(st.export(ost.latest)), oracle_flat_to_arena(st, ost.flat(ost.weights[ost.latest]))))

@@ -37,6 +37,17 @@ def test_vgg_stage0_full_size():
     print(f"{time.time() - t0:.1f} s", worst)
 
 
+@pytest.mark.timeout(900)
+def test_bottleneck_blocks_full_geometry():
+    # two of the identity bottlenecks of the conv4_x group at their real geometry (1024 -> 256 -> 1024
+    # channels on 4x4 feature maps, micro-batch 128 x 4): small enough for the whole oracle
+    w = W.bottleneck_stage(blocks=2)
+    t0 = time.time()
+    worst = _run_stage(w.stages[1], "bneck_full", "bf16", mb=w.mb, n=w.n, policy="convex", depth=3, minibatches=3,
+                       needs_dx=True, lr=2e-4)
+    print(f"{time.time() - t0:.1f} s", worst)
+
+
 @pytest.mark.timeout(1200)
 def test_transformer_block_full_geometry_sampled_sequences():
     """One of the four identical blocks of the transformer stage at its real geometry (d_model 2048, 16 heads
