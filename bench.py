@@ -39,10 +39,11 @@ def parse():
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--policy", default="convex", choices=["latest", "eq1", "convex", "stashed"])
-    ap.add_argument("--workload", default="mlp", choices=["mlp", "vgg", "tfm"],
+    ap.add_argument("--workload", default="mlp", choices=["mlp", "vgg", "tfm", "bneck"],
                     help="mlp: interior stage of the width-4096 GELU MLP (the configuration the metric is quoted on); "
                          "vgg: stage 0 of the VGG-16-style net on 32x32x3 images (implicit-GEMM convolutions); "
-                         "tfm: interior stage of the decoder-only transformer (4 blocks, d_model 2048, 1024 tokens)")
+                         "tfm: interior stage of the decoder-only transformer (4 blocks, d_model 2048, 1024 tokens); "
+                         "bneck: the identity bottlenecks of the conv4_x group of the ResNet-50-style net (4x4 maps)")
     ap.add_argument("--blocks", type=int, default=4, help="transformer blocks in the tfm stage")
     ap.add_argument("--stage", type=int, default=None)
     ap.add_argument("--width", type=int, default=4096)
@@ -61,7 +62,7 @@ def layer_work(cls, layer, rows, mb):
     mini-batch (backward kernels), mb = samples of a micro-batch (forward kernels)."""
     if layer.kind == "pool":
         return 0.0, 0.0
-    if layer.kind in ("ln", "attn", "res"):
+    if layer.kind in ("ln", "attn", "res", "bn"):
         return 0.0, 0.0
     px = layer.h * layer.w if layer.kind == "conv" else getattr(layer, "tokens", 1)   # GEMM rows per sample
     fin = (9 * layer.cin) if layer.kind == "conv" else layer.in_features
@@ -102,6 +103,8 @@ def kernel_work(cls, w, s, needs_dx):
         return 0.0, tot
     if cls == "norm":                  # forward: x in, y out; backward: dy, x in, dx out
         tot = sum(2.0 * rows * l.out_dim() * 5 for l in layers if l.kind == "ln")
+        # batch norm forward: x three times in, a and act' out; backward: dy, x twice in, dx out
+        tot += sum(2.0 * rows * l.out_dim() * (3 + (2 if l.act != "none" else 1) + 5) for l in layers if l.kind == "bn")
         return 0.0, tot
     if cls == "add":                   # forward a + b -> out; backward the same on gradients
         tot = sum(2.0 * rows * l.out_dim() * 3 * 2 for l in layers if l.kind == "res" and l.mark == "add")
@@ -115,10 +118,10 @@ def kernel_work(cls, w, s, needs_dx):
         return fl, by
     if cls == "copy":                  # stage input saved for the backward where no GEMM can fuse it
         l = layers[0]
-        return 0.0, (2 * 2.0 * rows * np_prod(l.in_shape())) if l.kind in ("conv", "res", "ln") else 0.0
+        return 0.0, (2 * 2.0 * rows * np_prod(l.in_shape())) if l.kind in ("conv", "res", "ln", "bn") else 0.0
     flops = nbytes = 0.0
     for i, l in enumerate(layers):
-        if l.kind in ("pool", "ln", "attn", "res"):
+        if l.kind in ("pool", "ln", "attn", "res", "bn"):
             continue
         if cls == "dgrad" and i == 0 and not needs_dx:
             continue
@@ -142,6 +145,8 @@ def cpu_baseline(w, s, policy, minibatches):
     from dataclasses import replace
     if w.name.startswith("tfm"):
         w = replace(w, mb=1, n=1)
+        minibatches = 1
+    if w.name.startswith("bneck"):
         minibatches = 1
     import numpy as np
     from oracle.stage import Stage
@@ -207,6 +212,13 @@ def main():
             sys.exit("bench.py: the vgg workload describes stage 0 only")
         what = ("stage 0 (conv3-64, conv3-64, pool, conv3-128, conv3-128, pool; ReLU) of the 4-stage VGG-16-style "
                 "net on 32x32x3 images")
+    elif args.workload == "bneck":
+        w = W.bottleneck_stage(blocks=5, mb=args.mb or 128, n=args.n or 4)
+        s = 1
+        if args.stage not in (None, 1):
+            sys.exit("bench.py: the bneck workload describes stage 1 only")
+        what = ("stage 1 (the five identity bottlenecks 1024-256-256-1024 of the conv4_x group on 4x4 feature maps, batch "
+                "normalisation per micro-batch, ReLU) of the 4-stage ResNet-50-style net on 64x64x3 images")
     else:
         w = W.transformer_stage(layers=args.blocks, mb=args.mb or 8, n=args.n or 4)
         s = 1
