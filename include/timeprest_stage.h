@@ -80,8 +80,8 @@ enum tp_layer_type {
                             W[Cout][3][3][Cin], b[Cout]; a sample is H*W*Cin values in, H*W*Cout out     */
   TP_LAYER_MAXPOOL2 = 2, /* 2x2 max pooling, stride 2, no parameters: in_features = out_features = C,
                             geom = {H, W} of the input (both even); first maximum wins ties             */
-  /* Layers of a transformer-shaped stage; samples are [tokens x features] (BASELINE configuration 5; the
-     paper prescribes no layer formulas, these are the standard ones). */
+  /* Layers of a transformer-shaped stage; samples are [tokens x features].  The paper prescribes no layer
+     formulas; these are the standard ones. */
   TP_LAYER_LAYERNORM = 3, /* y = gamma (x - mean)/sqrt(var + 1e-5) + beta over the features of each token;
                              in_features = out_features = D, geom = {tokens}; parameters gamma[D] (stored where a
                              dense layer keeps W) and beta[D] (where it keeps b), both fp32 in every mode   */
@@ -91,7 +91,7 @@ enum tp_layer_type {
   TP_LAYER_RESIDUAL = 5,  /* skip connection, no parameters: in_features = out_features = D, geom = {tokens, mark};
                              mark 0 remembers the activation at this point, mark 1 adds the remembered one to
                              the activation at this point and applies `act`; marks alternate 0, 1, 0, 1, ...  */
-  TP_LAYER_BATCHNORM = 6  /* batch normalisation in training mode + act (BASELINE configuration 4): statistics per
+  TP_LAYER_BATCHNORM = 6  /* batch normalisation in training mode + act (bottleneck-shaped stages): statistics per
                              channel over all samples and positions of the micro-batch a forward call sees, biased
                              variance, eps 1e-5; in_features = out_features = C, geom = {positions per sample};
                              parameters gamma[C], beta[C] (fp32 in every mode); no running statistics are kept */
