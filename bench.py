@@ -43,7 +43,7 @@ def parse():
                     help="mlp: interior stage of the width-4096 GELU MLP (the configuration the metric is quoted on); "
                          "vgg: stage 0 of the VGG-16-style net on 32x32x3 images (implicit-GEMM convolutions); "
                          "tfm: interior stage of the decoder-only transformer (4 blocks, d_model 2048, 1024 tokens); "
-                         "bneck: the identity bottlenecks of the conv4_x group of the ResNet-50-style net (4x4 maps)")
+                         "bneck: the conv4_x group of the ResNet-50-style net (six bottlenecks, 8x8 -> 4x4 maps)")
     ap.add_argument("--blocks", type=int, default=4, help="transformer blocks in the tfm stage")
     ap.add_argument("--stage", type=int, default=None)
     ap.add_argument("--width", type=int, default=4096)
@@ -52,7 +52,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-minibatches", type=int, default=3)
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
-                    help="only run a plain device copy of BYTES bytes five times and exit (calibration of the "
+                    help="only run a plain device copy of BYTES bytes (5 untimed, 10 timed) and exit (calibration of the "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
@@ -62,18 +62,20 @@ def layer_work(cls, layer, rows, mb):
     mini-batch (backward kernels), mb = samples of a micro-batch (forward kernels)."""
     if layer.kind == "pool":
         return 0.0, 0.0
-    if layer.kind in ("ln", "attn", "res", "bn"):
+    if layer.kind in ("ln", "attn", "res", "bn", "sub", "swap"):
         return 0.0, 0.0
-    px = layer.h * layer.w if layer.kind == "conv" else getattr(layer, "tokens", 1)   # GEMM rows per sample
+    # GEMM rows per sample (output pixels of a convolution) and input pixels per sample (more with stride 2)
+    px = layer.ho * layer.wo if layer.kind == "conv" else getattr(layer, "tokens", 1)
+    pin = layer.h * layer.w if layer.kind == "conv" else px
     fin = (9 * layer.cin) if layer.kind == "conv" else layer.in_features
     cin = layer.cin if layer.kind == "conv" else layer.in_features
     fout = layer.cout if layer.kind == "conv" else layer.out_features
     if cls == "fprop":                 # x, W in; act'(z), a out
-        return 2.0 * mb * px * fin * fout, 2.0 * (mb * px * cin + fin * fout + 2 * mb * px * fout)
+        return 2.0 * mb * px * fin * fout, 2.0 * (mb * pin * cin + fin * fout + 2 * mb * px * fout)
     if cls == "dgrad":                 # dz, W_b, act'(z_prev) in; dz_prev out
-        return 2.0 * rows * px * fin * fout, 2.0 * (rows * px * fout + fin * fout + 2 * rows * px * cin)
+        return 2.0 * rows * px * fin * fout, 2.0 * (rows * px * fout + fin * fout + 2 * rows * pin * cin)
     if cls == "wgrad":                 # dz, x in; dW (fp32) out
-        return 2.0 * rows * px * fin * fout, 2.0 * (rows * px * fout + rows * px * cin) + 4.0 * fin * fout
+        return 2.0 * rows * px * fin * fout, 2.0 * (rows * px * fout + rows * pin * cin) + 4.0 * fin * fout
     if cls == "colsum":
         return 0.0, 2.0 * rows * px * fout
     return 0.0, 0.0
@@ -100,6 +102,9 @@ def kernel_work(cls, w, s, needs_dx):
             if l.kind == "pool":
                 e = l.c * l.h * l.w
                 tot += 2.0 * rows * (e + e / 4) + 2.0 * rows * (2 * e + 2 * e / 4)
+            if l.kind == "sub":        # forward: a quarter in, a quarter out; backward: a quarter in, all out
+                e = l.c * l.h * l.w
+                tot += 2.0 * rows * (e / 2) + 2.0 * rows * (e / 4 + e)
         return 0.0, tot
     if cls == "norm":                  # forward: x in, y out; backward: dy, x in, dx out
         tot = sum(2.0 * rows * l.out_dim() * 5 for l in layers if l.kind == "ln")
@@ -121,7 +126,7 @@ def kernel_work(cls, w, s, needs_dx):
         return 0.0, (2 * 2.0 * rows * np_prod(l.in_shape())) if l.kind in ("conv", "res", "ln", "bn") else 0.0
     flops = nbytes = 0.0
     for i, l in enumerate(layers):
-        if l.kind in ("pool", "ln", "attn", "res", "bn"):
+        if l.kind in ("pool", "ln", "attn", "res", "bn", "sub", "swap"):
             continue
         if cls == "dgrad" and i == 0 and not needs_dx:
             continue
@@ -195,7 +200,15 @@ def main():
         for _ in range(5):
             dst.copy_(src)
         torch.cuda.synchronize()
-        print(json.dumps({"copy_probe_bytes": args.copy_probe, "copies": 5}))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 100.0
+        print(json.dumps({"copy_probe_bytes": args.copy_probe, "copies": 15, "avg_us": round(us, 1),
+                          "gbs_read_plus_write": round(2 * args.copy_probe / us * 1e-3, 1)}))
         return
     from paper_2509_23241_amd import binding as B
     from paper_2509_23241_amd.runner import GpuStage, layer_tuple
@@ -213,11 +226,12 @@ def main():
         what = ("stage 0 (conv3-64, conv3-64, pool, conv3-128, conv3-128, pool; ReLU) of the 4-stage VGG-16-style "
                 "net on 32x32x3 images")
     elif args.workload == "bneck":
-        w = W.bottleneck_stage(blocks=5, mb=args.mb or 128, n=args.n or 4)
+        w = W.bottleneck_stage(blocks=5, mb=args.mb or 128, n=args.n or 4, down=True)
         s = 1
         if args.stage not in (None, 1):
             sys.exit("bench.py: the bneck workload describes stage 1 only")
-        what = ("stage 1 (the five identity bottlenecks 1024-256-256-1024 of the conv4_x group on 4x4 feature maps, batch "
+        what = ("stage 1 (the conv4_x group: first bottleneck 512 -> 1024 channels with the 3x3 at stride 2, 8x8 -> 4x4 "
+                "feature maps, and a projection shortcut, then five identity bottlenecks 1024-256-256-1024; batch "
                 "normalisation per micro-batch, ReLU) of the 4-stage ResNet-50-style net on 64x64x3 images")
     else:
         w = W.transformer_stage(layers=args.blocks, mb=args.mb or 8, n=args.n or 4)

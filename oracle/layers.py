@@ -129,6 +129,18 @@ def maxpool2_backward(dy, idx, in_shape):
     return dwin.reshape(B, H // 2, Wd // 2, 2, 2, C).transpose(0, 1, 3, 2, 4, 5).reshape(B, H, Wd, C)
 
 
+def subsample2_forward(x):
+    """y[n, i, j, :] = x[n, 2i, 2j, :]: the pixels a stride-2 1x1 convolution reads."""
+    return x[:, ::2, ::2, :]
+
+
+def subsample2_backward(dy, in_shape):
+    """The gradient goes back to the pixels that were kept; the others get zero."""
+    dx = np.zeros(in_shape, dtype=np.float64)
+    dx[:, ::2, ::2, :] = dy
+    return dx
+
+
 # ---------------------------------------------------------------------------
 # Layers of the transformer-shaped workload (layer normalisation, causal
 # multi-head self-attention); standard definitions, the paper prescribes none.

@@ -46,7 +46,7 @@ class Stage:
         # position of each layer's weight in the flat parameter list (None: layer has no parameters)
         self.pidx, nxt = [], 0
         for spec in self.specs:
-            if getattr(spec, "kind", "dense") in ("pool", "attn", "res"):
+            if getattr(spec, "kind", "dense") in ("pool", "attn", "res", "sub", "swap"):
                 self.pidx.append(None)
             else:
                 self.pidx.append(nxt)
@@ -95,6 +95,14 @@ class Stage:
                 y, idx = L.maxpool2_forward(a)
                 saved.append((a.shape, idx))
                 a = y
+                continue
+            if kind == "sub":
+                saved.append((a.shape,))
+                a = L.subsample2_forward(a)
+                continue
+            if kind == "swap":                             # projection shortcut: the second branch starts from the
+                saved.append(None)                         # remembered tensor, the main branch's result waits for the add
+                a, skip = skip, a
                 continue
             if kind == "res":
                 if spec.mark == "begin":
@@ -175,6 +183,13 @@ class Stage:
                 if kind == "pool":
                     in_shape, idx = saved[li]
                     da = L.maxpool2_backward(da, idx, in_shape)
+                    continue
+                if kind == "sub":
+                    da = L.subsample2_backward(da, saved[li][0])
+                    continue
+                if kind == "swap":                         # da: gradient of the remembered tensor through the second
+                    da, dskip = dskip, da                  # branch, kept for the begin; the main branch goes on
+                    da = da.reshape((da.shape[0],) + tuple(spec.in_shape()))
                     continue
                 if kind == "res":
                     if spec.mark == "add":

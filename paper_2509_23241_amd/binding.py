@@ -11,6 +11,7 @@ TP_LATEST, TP_INTERMEDIATE_EQ1, TP_INTERMEDIATE_CONVEX, TP_STASHED = 0, 1, 2, 3
 TP_F32, TP_BF16 = 0, 1
 TP_ACT_NONE, TP_ACT_RELU, TP_ACT_GELU = 0, 1, 2
 TP_LAYER_DENSE, TP_LAYER_CONV2D, TP_LAYER_MAXPOOL2, TP_LAYER_LAYERNORM, TP_LAYER_ATTENTION, TP_LAYER_RESIDUAL, TP_LAYER_BATCHNORM = 0, 1, 2, 3, 4, 5, 6
+TP_LAYER_SUBSAMPLE2 = 7
 TP_MAX_LAYERS, TP_MAX_SLOTS, TP_MAX_IN_FLIGHT = 64, 16, 16
 TP_NONE = (1 << 64) - 1
 TP_DIAG_GRAD_SQ, TP_DIAG_WEIGHT_SQ, TP_DIAG_DRIFT_SQ, TP_DIAG_WB_SQ, TP_DIAG_COUNT = 0, 1, 2, 3, 4
@@ -125,9 +126,10 @@ def _check(rc, soft=()):
 def make_desc(layers, *, dtype, mb, n, stage_index, num_stages, ring_capacity, max_in_flight, policy, needs_dx,
               lam, lr, momentum) -> tp_stage_desc:
     """layers: sequence of (in_features, out_features, act-name[, tokens]) for dense layers,
-    ("conv", cin, cout, H, W, act-name) for 3x3/stride 1/pad 1 convolutions, ("pool", C, H, W) for 2x2 pooling,
-    ("ln", D, tokens), ("attn", D, heads, tokens), ("res", D, tokens, "begin" | "add"[, act-name]),
-    ("bn", C, positions, act-name)."""
+    ("conv", cin, cout, H, W, act-name[, stride]) for 3x3/pad 1 convolutions, ("pool", C, H, W) for 2x2 pooling,
+    ("sub", C, H, W) for 2x subsampling, ("ln", D, tokens), ("attn", D, heads, tokens),
+    ("res", D, tokens, "begin" | "add"[, act-name]), ("swap", D_in, tokens_in, D_out, tokens_out) for the residual
+    mark that starts a projection shortcut, ("bn", C, positions, act-name)."""
     if len(layers) > TP_MAX_LAYERS:
         raise ValueError(f"{len(layers)} layers: a stage takes at most {TP_MAX_LAYERS}")
     d = tp_stage_desc()
@@ -142,14 +144,24 @@ def make_desc(layers, *, dtype, mb, n, stage_index, num_stages, ring_capacity, m
     for i, spec in enumerate(layers[:TP_MAX_LAYERS]):
         L = d.layers[i]
         if spec[0] == "conv":
-            _, cin, cout, H, W, act = spec
+            _, cin, cout, H, W, act = spec[:6]
             L.type, L.in_features, L.out_features = TP_LAYER_CONV2D, cin, cout
-            L.geom[0], L.geom[1], L.geom[2], L.geom[3], L.geom[4] = H, W, 3, 1, 1
+            L.geom[0], L.geom[1], L.geom[2], L.geom[3], L.geom[4] = H, W, 3, (spec[6] if len(spec) > 6 else 1), 1
         elif spec[0] == "pool":
             _, c, H, W = spec
             act = "none"
             L.type, L.in_features, L.out_features = TP_LAYER_MAXPOOL2, c, c
             L.geom[0], L.geom[1] = H, W
+        elif spec[0] == "sub":
+            _, c, H, W = spec
+            act = "none"
+            L.type, L.in_features, L.out_features = TP_LAYER_SUBSAMPLE2, c, c
+            L.geom[0], L.geom[1] = H, W
+        elif spec[0] == "swap":
+            _, din, tin, dout, tout = spec
+            act = "none"
+            L.type, L.in_features, L.out_features = TP_LAYER_RESIDUAL, din, dout
+            L.geom[0], L.geom[1], L.geom[2] = tin, 2, tout
         elif spec[0] == "ln":
             _, dm, tokens = spec
             act = "none"
@@ -181,9 +193,9 @@ def layer_in_elems(spec) -> int:
     """Values per sample a layer takes in / gives out (same tuple format as make_desc)."""
     if spec[0] == "conv":
         return spec[3] * spec[4] * spec[1]
-    if spec[0] == "pool":
+    if spec[0] in ("pool", "sub"):
         return spec[2] * spec[3] * spec[1]
-    if spec[0] in ("ln", "bn"):
+    if spec[0] in ("ln", "bn", "swap"):
         return spec[1] * spec[2]
     if spec[0] == "attn":
         return 3 * spec[1] * spec[3]
@@ -194,9 +206,12 @@ def layer_in_elems(spec) -> int:
 
 def layer_out_elems(spec) -> int:
     if spec[0] == "conv":
-        return spec[3] * spec[4] * spec[2]
-    if spec[0] == "pool":
+        st = spec[6] if len(spec) > 6 else 1
+        return (spec[3] // st) * (spec[4] // st) * spec[2]
+    if spec[0] in ("pool", "sub"):
         return (spec[2] // 2) * (spec[3] // 2) * spec[1]
+    if spec[0] == "swap":
+        return spec[3] * spec[4]
     if spec[0] in ("ln", "bn"):
         return spec[1] * spec[2]
     if spec[0] == "attn":
@@ -209,7 +224,7 @@ def layer_out_elems(spec) -> int:
 def layer_param_shapes(spec):
     if spec[0] == "conv":
         return [(spec[2], 3, 3, spec[1]), (spec[2],)]
-    if spec[0] in ("pool", "attn", "res"):
+    if spec[0] in ("pool", "attn", "res", "sub", "swap"):
         return []
     if spec[0] in ("ln", "bn"):
         return [(spec[1],), (spec[1],)]

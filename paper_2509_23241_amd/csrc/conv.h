@@ -1,4 +1,5 @@
-// Launch interface of the convolution and pooling kernels (3x3, stride 1, pad 1; 2x2 max pool).
+// Launch interface of the convolution, pooling and subsampling kernels (3x3, stride 1 or 2, pad 1; 2x2 max
+// pool; every second pixel).  H, W are the INPUT image; with stride s the output image is (H/s) x (W/s).
 // elt: 0 = fp32, 1 = bf16.  Activations are NHWC, [imgs*H*W x C] row-major; weights [Cout][3][3][Cin].
 #pragma once
 #include <hip/hip_runtime.h>
@@ -9,16 +10,16 @@ namespace tp {
 // a = act(conv(x, W) + bias), d = act'(.) (d_out may be null).  Outputs [imgs*H*W x cout].
 // zeros: device block of >= 128 zero bytes, 16-byte aligned (what padding positions read); the
 // matrix-core kernels need it, null sends everything to the generic kernels.
-hipError_t launch_conv_fprop(hipStream_t s, int elt, int imgs, int H, int W, int cin, int cout, const void* x,
+hipError_t launch_conv_fprop(hipStream_t s, int elt, int imgs, int H, int W, int stride, int cin, int cout, const void* x,
                              const void* wgt, const float* bias, int act, void* d_out, void* a_out, const void* zeros);
 
 // out = (transposed convolution of dz with W_b) (.) d_prev;  dz:[imgs*H*W x cout], out:[imgs*H*W x cin].
-hipError_t launch_conv_dgrad(hipStream_t s, int elt, int imgs, int H, int W, int cin, int cout, const void* dz,
+hipError_t launch_conv_dgrad(hipStream_t s, int elt, int imgs, int H, int W, int stride, int cin, int cout, const void* dz,
                              const void* wb, const void* d_prev, void* out, const void* zeros);
 
 // gW[cout][3][3][cin] (fp32) = sum over pixels of dz (x) shifted x.
 // partial: scratch of conv_wgrad_scratch_floats(imgs*H*W, cin, cout) floats.
-hipError_t launch_conv_wgrad(hipStream_t s, int elt, int imgs, int H, int W, int cin, int cout, const void* dz,
+hipError_t launch_conv_wgrad(hipStream_t s, int elt, int imgs, int H, int W, int stride, int cin, int cout, const void* dz,
                              const void* x, float* gW, float* partial, const void* zeros);
 size_t conv_wgrad_scratch_floats(int pixels, int cin, int cout);
 
@@ -28,16 +29,21 @@ hipError_t launch_maxpool_fwd(hipStream_t s, int elt, int imgs, int H, int W, in
 hipError_t launch_maxpool_bwd(hipStream_t s, int elt, int imgs, int H, int W, int C, const void* x, const void* dy,
                               void* dx);
 
+// y[imgs x H/2 x W/2 x C] = x at the even pixel positions; backward: the gradient at those positions, zero elsewhere.
+// C * element size must be a multiple of 16 bytes.
+hipError_t launch_subsample_fwd(hipStream_t s, int elt, int imgs, int H, int W, int C, const void* x, void* y);
+hipError_t launch_subsample_bwd(hipStream_t s, int elt, int imgs, int H, int W, int C, const void* dy, void* dx);
+
 // bf16 matrix-core versions (kernels_conv_mfma.hip) and the shapes they take
-bool conv_mfma_supported(int imgs, int H, int W, int cin, int cout);
+bool conv_mfma_supported(int imgs, int H, int W, int stride, int cin, int cout);
 int conv_mfma_wgrad_splits(int pixels, int cin, int cout);
 int conv_mfma_wgrad_max_splits(int pixels, int cin, int cout);
-hipError_t conv_mfma_fprop(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* x,
+hipError_t conv_mfma_fprop(hipStream_t s, int imgs, int H, int W, int stride, int cin, int cout, const uint16_t* x,
                            const uint16_t* wgt, const float* bias, int act, uint16_t* d_out, uint16_t* a_out,
                            const uint16_t* zeros);
-hipError_t conv_mfma_dgrad(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* dz,
+hipError_t conv_mfma_dgrad(hipStream_t s, int imgs, int H, int W, int stride, int cin, int cout, const uint16_t* dz,
                            const uint16_t* wb, const uint16_t* d_prev, uint16_t* out, const uint16_t* zeros);
-hipError_t conv_mfma_wgrad(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* dz,
+hipError_t conv_mfma_wgrad(hipStream_t s, int imgs, int H, int W, int stride, int cin, int cout, const uint16_t* dz,
                            const uint16_t* x, float* gW, float* partial, const uint16_t* zeros);
 
 // First layer of an image net (cin <= 8, bf16) on a zero-padded [pixel][8 channels] copy x8 of its input.

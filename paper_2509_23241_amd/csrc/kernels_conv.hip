@@ -1,11 +1,14 @@
-// 3x3 convolution (stride 1, zero padding 1) on NHWC activations as implicit GEMMs, and 2x2 max
-// pooling.  Weights are [Cout][3][3][Cin], i.e. a row-major [Cout x 9*Cin] matrix whose k index
+// 3x3 convolution (stride 1 or 2, zero padding 1) on NHWC activations as implicit GEMMs, 2x2 max
+// pooling and 2x subsampling.  Weights are [Cout][3][3][Cin], i.e. a row-major [Cout x 9*Cin] matrix whose k index
 // runs over (tap, input channel), tap = 3*kh + kw.
 //
 //   fprop  z[p][co]  = sum_{tap,ci} x[shift(p,+tap)][ci] * W[co][tap][ci]        rows: output pixels
 //   dgrad  dx[p][ci] = sum_{tap,co} dz[shift(p,-tap)][co] * W_b[co][tap][ci]     rows: input pixels
 //   wgrad  dW[co][tap][ci] = sum_p dz[p][co] * x[shift(p,+tap)][ci]              contraction: pixels
 // shift(p, +tap) moves pixel p = (img, h, w) by (kh-1, kw-1); positions outside the image read 0.
+// With stride s the output has (H/s) x (W/s) pixels and output pixel (oh, ow) reads the input at
+// (s*oh + kh - 1, s*ow + kw - 1); dgrad visits, for an input pixel, the taps whose output position
+// (h - kh + 1) / s, (w - kw + 1) / s is whole.
 //
 // This file holds the shape-generic, bounds-checked SIMT kernel (fp32 FMA, LDS-tiled), used for
 // the fp32 mode, for channel counts the matrix-core kernels do not take (the 3-channel first
@@ -27,14 +30,15 @@ namespace {
 constexpr int BM = 64, BN = 64, BK = 16, kThreads = 256;
 
 struct ConvGeom {
-  int imgs, H, W, Cin, Cout;
+  int imgs, H, W, Cin, Cout;  // H, W: input image
+  int S, Ho, Wo;              // stride, output image
 };
 
-__device__ __forceinline__ void pixel_of(int p, const ConvGeom& g, int& img, int& h, int& w) {
-  w = p % g.W;
-  const int t = p / g.W;
-  h = t % g.H;
-  img = t / g.H;
+__device__ __forceinline__ void pixel_of(int p, int H, int W, int& img, int& h, int& w) {
+  w = p % W;
+  const int t = p / W;
+  h = t % H;
+  img = t / H;
 }
 
 // PRODUCT: 0 fprop, 1 dgrad, 2 wgrad (partial sums over the pixel range of blockIdx.z)
@@ -46,12 +50,12 @@ __global__ __launch_bounds__(kThreads) void conv_simt_kernel(ConvGeom g, const T
                                                              int pixels_per_split) {
   __shared__ float As[BK][BM + 4];
   __shared__ float Bs[BK][BN + 4];
-  const int P = g.imgs * g.H * g.W;
-  const int M = PRODUCT == 2 ? g.Cout : P;
+  const int Pin = g.imgs * g.H * g.W, Pout = g.imgs * g.Ho * g.Wo;
+  const int M = PRODUCT == 0 ? Pout : (PRODUCT == 1 ? Pin : g.Cout);
   const int N = PRODUCT == 0 ? g.Cout : (PRODUCT == 1 ? g.Cin : 9 * g.Cin);
-  const int Kfull = PRODUCT == 0 ? 9 * g.Cin : (PRODUCT == 1 ? 9 * g.Cout : P);
+  const int Kfull = PRODUCT == 0 ? 9 * g.Cin : (PRODUCT == 1 ? 9 * g.Cout : Pout);
   const int kbeg = PRODUCT == 2 ? blockIdx.z * pixels_per_split : 0;
-  const int kend = PRODUCT == 2 ? min(P, kbeg + pixels_per_split) : Kfull;
+  const int kend = PRODUCT == 2 ? min(Pout, kbeg + pixels_per_split) : Kfull;
   const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
 
@@ -61,12 +65,20 @@ __global__ __launch_bounds__(kThreads) void conv_simt_kernel(ConvGeom g, const T
     if (PRODUCT == 2) return to_float(wgt_or_dz[(size_t)k * g.Cout + m]);  // dz[p][co]
     const int C = PRODUCT == 0 ? g.Cin : g.Cout;
     const int tap = k / C, c = k % C;
-    int img, h, w;
-    pixel_of(m, g, img, h, w);
     const int dh = tap / 3 - 1, dw = tap % 3 - 1;
-    const int sh = PRODUCT == 0 ? h + dh : h - dh, sw = PRODUCT == 0 ? w + dw : w - dw;
-    if (sh < 0 || sh >= g.H || sw < 0 || sw >= g.W) return 0.f;
-    return to_float(act_in[((size_t)(img * g.H + sh) * g.W + sw) * C + c]);
+    int img, h, w;
+    if (PRODUCT == 0) {  // output pixel m reads the input
+      pixel_of(m, g.Ho, g.Wo, img, h, w);
+      const int sh = h * g.S + dh, sw = w * g.S + dw;
+      if (sh < 0 || sh >= g.H || sw < 0 || sw >= g.W) return 0.f;
+      return to_float(act_in[((size_t)(img * g.H + sh) * g.W + sw) * C + c]);
+    }
+    pixel_of(m, g.H, g.W, img, h, w);  // input pixel m reads dz where the tap lands on a whole output position
+    const int nh = h - dh, nw = w - dw;
+    if (nh < 0 || nw < 0 || nh % g.S || nw % g.S) return 0.f;
+    const int oh = nh / g.S, ow = nw / g.S;
+    if (oh >= g.Ho || ow >= g.Wo) return 0.f;
+    return to_float(act_in[((size_t)(img * g.Ho + oh) * g.Wo + ow) * C + c]);
   };
   auto fetch_b = [&](int k, int n) -> float {
     if (n >= N || k >= kend) return 0.f;
@@ -77,8 +89,8 @@ __global__ __launch_bounds__(kThreads) void conv_simt_kernel(ConvGeom g, const T
     }
     const int tap = n / g.Cin, c = n % g.Cin;
     int img, h, w;
-    pixel_of(k, g, img, h, w);
-    const int sh = h + tap / 3 - 1, sw = w + tap % 3 - 1;
+    pixel_of(k, g.Ho, g.Wo, img, h, w);
+    const int sh = h * g.S + tap / 3 - 1, sw = w * g.S + tap % 3 - 1;
     if (sh < 0 || sh >= g.H || sw < 0 || sw >= g.W) return 0.f;
     return to_float(act_in[((size_t)(img * g.H + sh) * g.W + sw) * g.Cin + c]);
   };
@@ -179,6 +191,38 @@ __global__ __launch_bounds__(kThreads) void maxpool_bwd_kernel(int imgs, int H, 
   }
 }
 
+// y[img][oh][ow][:] = x[img][2*oh][2*ow][:] in 16-byte units (CV per pixel); the backward pass writes the
+// gradient back to those positions and zero everywhere else.
+__global__ __launch_bounds__(kThreads) void subsample_fwd_kernel(int imgs, int H, int W, int CV, const uint4* __restrict__ x,
+                                                                 uint4* __restrict__ y) {
+  const size_t total = (size_t)imgs * (H / 2) * (W / 2) * CV;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (size_t)gridDim.x * kThreads) {
+    const int c = i % CV;
+    size_t t = i / CV;
+    const int ow = t % (W / 2);
+    t /= (W / 2);
+    const int oh = t % (H / 2);
+    const size_t img = t / (H / 2);
+    y[i] = x[((img * H + 2 * oh) * W + 2 * ow) * CV + c];
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void subsample_bwd_kernel(int imgs, int H, int W, int CV, const uint4* __restrict__ dy,
+                                                                 uint4* __restrict__ dx) {
+  const size_t total = (size_t)imgs * H * W * CV;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (size_t)gridDim.x * kThreads) {
+    const int c = i % CV;
+    size_t t = i / CV;
+    const int w = t % W;
+    t /= W;
+    const int h = t % H;
+    const size_t img = t / H;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (!(h & 1) && !(w & 1)) v = dy[((img * (H / 2) + h / 2) * (W / 2) + w / 2) * CV + c];
+    dx[i] = v;
+  }
+}
+
 inline int stream_blocks(size_t items, int max_blocks) {
   size_t b = (items + kThreads - 1) / kThreads;
   return (int)(b < 1 ? 1 : (b < (size_t)max_blocks ? b : (size_t)max_blocks));
@@ -199,13 +243,13 @@ size_t conv_wgrad_scratch_floats(int pixels, int cin, int cout) {
   return (size_t)splits * cout * 9 * cin;
 }
 
-hipError_t launch_conv_fprop(hipStream_t s, int elt, int imgs, int H, int W, int cin, int cout, const void* x,
+hipError_t launch_conv_fprop(hipStream_t s, int elt, int imgs, int H, int W, int stride, int cin, int cout, const void* x,
                              const void* wgt, const float* bias, int act, void* d_out, void* a_out, const void* zeros) {
-  if (elt == 1 && zeros && conv_mfma_supported(imgs, H, W, cin, cout))
-    return conv_mfma_fprop(s, imgs, H, W, cin, cout, (const uint16_t*)x, (const uint16_t*)wgt, bias, act, (uint16_t*)d_out,
-                           (uint16_t*)a_out, (const uint16_t*)zeros);
-  const ConvGeom g{imgs, H, W, cin, cout};
-  const int P = imgs * H * W;
+  if (elt == 1 && zeros && conv_mfma_supported(imgs, H, W, stride, cin, cout))
+    return conv_mfma_fprop(s, imgs, H, W, stride, cin, cout, (const uint16_t*)x, (const uint16_t*)wgt, bias, act,
+                           (uint16_t*)d_out, (uint16_t*)a_out, (const uint16_t*)zeros);
+  const ConvGeom g{imgs, H, W, cin, cout, stride, H / stride, W / stride};
+  const int P = imgs * g.Ho * g.Wo;
   dim3 grid((cout + BN - 1) / BN, (P + BM - 1) / BM);
   if (elt == 1)
     hipLaunchKernelGGL((conv_simt_kernel<uint16_t, 0>), grid, dim3(kThreads), 0, s, g, (const uint16_t*)x, (const uint16_t*)wgt,
@@ -216,12 +260,12 @@ hipError_t launch_conv_fprop(hipStream_t s, int elt, int imgs, int H, int W, int
   return hipGetLastError();
 }
 
-hipError_t launch_conv_dgrad(hipStream_t s, int elt, int imgs, int H, int W, int cin, int cout, const void* dz,
+hipError_t launch_conv_dgrad(hipStream_t s, int elt, int imgs, int H, int W, int stride, int cin, int cout, const void* dz,
                              const void* wb, const void* d_prev, void* out, const void* zeros) {
-  if (elt == 1 && zeros && conv_mfma_supported(imgs, H, W, cin, cout))
-    return conv_mfma_dgrad(s, imgs, H, W, cin, cout, (const uint16_t*)dz, (const uint16_t*)wb, (const uint16_t*)d_prev,
-                           (uint16_t*)out, (const uint16_t*)zeros);
-  const ConvGeom g{imgs, H, W, cin, cout};
+  if (elt == 1 && zeros && conv_mfma_supported(imgs, H, W, stride, cin, cout))
+    return conv_mfma_dgrad(s, imgs, H, W, stride, cin, cout, (const uint16_t*)dz, (const uint16_t*)wb,
+                           (const uint16_t*)d_prev, (uint16_t*)out, (const uint16_t*)zeros);
+  const ConvGeom g{imgs, H, W, cin, cout, stride, H / stride, W / stride};
   const int P = imgs * H * W;
   dim3 grid((cin + BN - 1) / BN, (P + BM - 1) / BM);
   if (elt == 1)
@@ -233,13 +277,13 @@ hipError_t launch_conv_dgrad(hipStream_t s, int elt, int imgs, int H, int W, int
   return hipGetLastError();
 }
 
-hipError_t launch_conv_wgrad(hipStream_t s, int elt, int imgs, int H, int W, int cin, int cout, const void* dz,
+hipError_t launch_conv_wgrad(hipStream_t s, int elt, int imgs, int H, int W, int stride, int cin, int cout, const void* dz,
                              const void* x, float* gW, float* partial, const void* zeros) {
-  if (elt == 1 && zeros && conv_mfma_supported(imgs, H, W, cin, cout))
-    return conv_mfma_wgrad(s, imgs, H, W, cin, cout, (const uint16_t*)dz, (const uint16_t*)x, gW, partial,
+  if (elt == 1 && zeros && conv_mfma_supported(imgs, H, W, stride, cin, cout))
+    return conv_mfma_wgrad(s, imgs, H, W, stride, cin, cout, (const uint16_t*)dz, (const uint16_t*)x, gW, partial,
                            (const uint16_t*)zeros);
-  const ConvGeom g{imgs, H, W, cin, cout};
-  const int P = imgs * H * W;
+  const ConvGeom g{imgs, H, W, cin, cout, stride, H / stride, W / stride};
+  const int P = imgs * g.Ho * g.Wo;  // the contraction runs over output pixels
   const int splits = conv_wgrad_splits(P, cin, cout);
   const int per = ((P + splits - 1) / splits + BK - 1) / BK * BK;
   dim3 grid((9 * cin + BN - 1) / BN, (cout + BM - 1) / BM, splits);
@@ -253,6 +297,24 @@ hipError_t launch_conv_wgrad(hipStream_t s, int elt, int imgs, int H, int W, int
   if (e != hipSuccess) return e;
   const size_t count = (size_t)cout * 9 * cin;
   return launch_sum_partials(s, count, splits, partial, gW);
+}
+
+hipError_t launch_subsample_fwd(hipStream_t s, int elt, int imgs, int H, int W, int C, const void* x, void* y) {
+  const int es = elt == 1 ? 2 : 4;
+  if ((C * es) % 16 || (H & 1) || (W & 1)) return hipErrorInvalidValue;
+  const int CV = C * es / 16;
+  const int blocks = stream_blocks((size_t)imgs * (H / 2) * (W / 2) * CV, 8192);
+  hipLaunchKernelGGL(subsample_fwd_kernel, dim3(blocks), dim3(kThreads), 0, s, imgs, H, W, CV, (const uint4*)x, (uint4*)y);
+  return hipGetLastError();
+}
+
+hipError_t launch_subsample_bwd(hipStream_t s, int elt, int imgs, int H, int W, int C, const void* dy, void* dx) {
+  const int es = elt == 1 ? 2 : 4;
+  if ((C * es) % 16 || (H & 1) || (W & 1)) return hipErrorInvalidValue;
+  const int CV = C * es / 16;
+  const int blocks = stream_blocks((size_t)imgs * H * W * CV, 8192);
+  hipLaunchKernelGGL(subsample_bwd_kernel, dim3(blocks), dim3(kThreads), 0, s, imgs, H, W, CV, (const uint4*)dy, (uint4*)dx);
+  return hipGetLastError();
 }
 
 hipError_t launch_maxpool_fwd(hipStream_t s, int elt, int imgs, int H, int W, int C, const void* x, void* y) {

@@ -1,4 +1,4 @@
-// 3x3 convolutions (stride 1, pad 1, NHWC) on the gfx950 matrix cores as implicit GEMMs.
+// 3x3 convolutions (stride 1 or 2, pad 1, NHWC) on the gfx950 matrix cores as implicit GEMMs.
 //
 // The three products use the direct-to-LDS pipeline of the dense GEMMs (global_load_lds_dwordx4
 // into XOR-swizzled LDS stages, copies interleaved with the MFMAs, fragments prefetched one k
@@ -14,7 +14,8 @@
 //          added by a second kernel in a fixed order.
 // Needs: image height and width powers of two (pixel -> (h, w) by shift and mask), channel counts
 // that are multiples of 64, pixel count a multiple of 64.  Everything else goes to the generic
-// kernels of kernels_conv.hip.
+// kernels of kernels_conv.hip.  Stride 2 runs on the gather kernels only: the rows (fprop, wgrad:
+// output pixels; dgrad: input pixels) and the pixels they read live on grids of different size.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -38,14 +39,31 @@ __device__ __forceinline__ void dma16_addr(uint32_t lds_byte_addr, const void* l
 }
 
 struct GatherDesc {
-  const uint16_t* base;   // [P][C] activations or gradients
+  const uint16_t* base;   // [pixels of the source grid][C] activations or gradients
   const uint16_t* zeros;  // >= 128 bytes of zeros, 16-byte aligned
-  int P, H, W, lw;        // pixels, image size, log2(W)
+  int P, H, W, lw;        // the grid the rows (or the contraction index) run over: pixels, image size, log2(W)
   int C;                  // channels of `base`
+  int SH, SW;             // image size of the source grid (= H, W at stride 1)
 };
 
+// Source pixel of grid position (h, w) moved by (dh, dw), for stride S.  Forward (fprop, wgrad): the
+// position is an output pixel and reads the input at S*(h, w) + (dh, dw).  Backward (dgrad): the
+// position is an input pixel and reads dz at ((h, w) + (dh, dw)) / S where that is whole.
+template <int S, bool BACKWARD>
+__device__ __forceinline__ bool source_pixel(int h, int w, int dh, int dw, int SH, int SW, int& sh, int& sw) {
+  if (BACKWARD) {
+    const int nh = h + dh, nw = w + dw;
+    sh = nh / S;
+    sw = nw / S;
+    return nh >= 0 && nw >= 0 && nh % S == 0 && nw % S == 0 && sh < SH && sw < SW;
+  }
+  sh = h * S + dh;
+  sw = w * S + dw;
+  return (unsigned)sh < (unsigned)SH && (unsigned)sw < (unsigned)SW;
+}
+
 // k-contiguous gathered operand: stage [R pixels][64 channels of one tap].
-template <int R, int NW, bool BACKWARD>
+template <int R, int NW, bool BACKWARD, int S = 1>
 struct RowGather {
   using Desc = GatherDesc;
   static constexpr int kPerWave = R / 8 / NW;
@@ -53,7 +71,7 @@ struct RowGather {
   static_assert((R / 8) % NW == 0, "rows do not divide among the waves");
   Desc d;
   int cblocks;
-  uint32_t pix_off[kPerWave];  // byte offset of (pixel, chunk) inside base
+  uint32_t pix_off[kPerWave];  // S == 1: byte offset of (pixel, chunk) inside base; else of (image, chunk)
   int hw[kPerWave];            // h << 16 | w of the lane's pixel
   uint32_t zoff;
 
@@ -67,16 +85,29 @@ struct RowGather {
       const int c = (lane & 7) ^ ((r >> 1) & 7);
       const int p = min(r0 + r, d.P - 1);  // rows past the end repeat the last pixel: never stored
       hw[t] = (((p >> d.lw) & (d.H - 1)) << 16) | (p & (d.W - 1));
-      pix_off[t] = (uint32_t)(((size_t)p * d.C + c * 8) * 2);
+      if (S == 1) {
+        pix_off[t] = (uint32_t)(((size_t)p * d.C + c * 8) * 2);
+      } else {
+        const int img = p / (d.H * d.W);
+        pix_off[t] = (uint32_t)(((size_t)img * d.SH * d.SW * d.C + c * 8) * 2);
+      }
     }
   }
   __device__ __forceinline__ void issue_one(int t, uint32_t lds_stage, int tile, int wave) const {
     const int tap = tile / cblocks, c0 = (tile - tap * cblocks) * DBK;  // wave uniform
     int dh = tap / 3 - 1, dw = tap - (tap / 3) * 3 - 1;
     if (BACKWARD) { dh = -dh; dw = -dw; }
-    const int sh = (hw[t] >> 16) + dh, sw = (hw[t] & 0xffff) + dw;
-    const bool valid = (unsigned)sh < (unsigned)d.H && (unsigned)sw < (unsigned)d.W;
-    const long off = (long)pix_off[t] + ((long)(dh * d.W + dw) * d.C + c0) * 2;
+    bool valid;
+    long off;
+    if (S == 1) {
+      const int sh = (hw[t] >> 16) + dh, sw = (hw[t] & 0xffff) + dw;
+      valid = (unsigned)sh < (unsigned)d.H && (unsigned)sw < (unsigned)d.W;
+      off = (long)pix_off[t] + ((long)(dh * d.W + dw) * d.C + c0) * 2;
+    } else {
+      int sh, sw;
+      valid = source_pixel<S, BACKWARD>(hw[t] >> 16, hw[t] & 0xffff, dh, dw, d.SH, d.SW, sh, sw);
+      off = (long)pix_off[t] + ((long)(sh * d.SW + sw) * d.C + c0) * 2;
+    }
     const char* src = valid ? (const char*)d.base + off : (const char*)d.zeros + zoff;
     dma16_addr(lds_stage + (wave + NW * t) * 1024, src);
   }
@@ -86,7 +117,7 @@ struct RowGather {
 };
 
 // k-strided gathered operand: stage [64 pixels][R channels], one tap per workgroup (batch).
-template <int R, int NW>
+template <int R, int NW, int S = 1>
 struct ColGather {
   using Desc = GatherDesc;
   static constexpr int kPerK = R / 8;
@@ -115,9 +146,18 @@ struct ColGather {
   }
   __device__ __forceinline__ void issue_one(int t, uint32_t lds_stage, int tile, int wave) const {
     const int p = tile * DBK + krow[t];
-    const int sh = ((p >> d.lw) & (d.H - 1)) + dh, sw = (p & (d.W - 1)) + dw;
-    const bool valid = (unsigned)sh < (unsigned)d.H && (unsigned)sw < (unsigned)d.W;
-    const long off = ((long)p + dh * d.W + dw) * d.C * 2 + coff[t];
+    bool valid;
+    long off;
+    if (S == 1) {
+      const int sh = ((p >> d.lw) & (d.H - 1)) + dh, sw = (p & (d.W - 1)) + dw;
+      valid = (unsigned)sh < (unsigned)d.H && (unsigned)sw < (unsigned)d.W;
+      off = ((long)p + dh * d.W + dw) * d.C * 2 + coff[t];
+    } else {
+      int sh, sw;
+      valid = source_pixel<S, false>((p >> d.lw) & (d.H - 1), p & (d.W - 1), dh, dw, d.SH, d.SW, sh, sw);
+      const int img = p / (d.H * d.W);
+      off = (((long)img * d.SH + sh) * d.SW + sw) * d.C * 2 + coff[t];
+    }
     const char* src = valid ? (const char*)d.base + off : (const char*)d.zeros + zoff;
     dma16_addr(lds_stage + (wave + NW * t) * 1024, src);
   }
@@ -807,9 +847,10 @@ inline int wgrad_patch_splits(long px_tiles, int cin, int cout) {
   return (int)std::max(1l, std::min(px_tiles, 256 / blocks));
 }
 
-bool conv_mfma_supported(int imgs, int H, int W, int cin, int cout) {
-  const long P = (long)imgs * H * W;
-  return pow2(H) && pow2(W) && H <= 32768 && W <= 32768 && cin % 64 == 0 && cout % 64 == 0 && P % 64 == 0 &&
+bool conv_mfma_supported(int imgs, int H, int W, int stride, int cin, int cout) {
+  const long P = (long)imgs * H * W, Pout = P / (stride * stride);
+  if (stride != 1 && !(stride == 2 && H >= 2 && W >= 2)) return false;
+  return pow2(H) && pow2(W) && H <= 32768 && W <= 32768 && cin % 64 == 0 && cout % 64 == 0 && Pout % 64 == 0 &&
          P * std::max(cin, cout) * 2 < (1l << 31);
 }
 
@@ -828,46 +869,75 @@ int conv_mfma_wgrad_splits(int pixels, int cin, int cout) {
   return s;
 }
 
-hipError_t conv_mfma_fprop(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* x,
+hipError_t conv_mfma_fprop(hipStream_t s, int imgs, int H, int W, int stride, int cin, int cout, const uint16_t* x,
                            const uint16_t* wgt, const float* bias, int act, uint16_t* d_out, uint16_t* a_out,
                            const uint16_t* zeros) {
-  const int P = imgs * H * W;
   PlainDesc bd{wgt, 9 * cin, cout, 1 << 30, DBK, 0};
   EpiFprop e{bias, d_out, a_out, act, cout};
+  const int KT = 9 * cin / DBK;
+  if (stride == 2) {  // rows: output pixels on the (H/2) x (W/2) grid, source: the input
+    const int Ho = H / 2, Wo = W / 2, P = imgs * Ho * Wo;
+    GatherDesc ad{x, zeros, P, Ho, Wo, ilog2(Wo), cin, H, W};
+    if (cout % 128 == 0)
+      return launch_conv<128, 128, 3, RowGather<128, 4, false, 2>, Plain<128, 4, false>>(s, P, cout, KT, 1, 1, ad, bd, e);
+    return launch_conv<128, 64, 4, RowGather<128, 4, false, 2>, Plain<64, 4, false>>(s, P, cout, KT, 1, 1, ad, bd, e);
+  }
+  const int P = imgs * H * W;
   {
     const PatchDesc pd{x, zeros, H, W, ilog2(W), cin, 0, cin / 8, 0};
     const hipError_t err = launch_patch_conv<false>(s, P, H, W, cin, cout, pd, bd, e);
     if (err != hipErrorNotSupported) return err;
   }
-  GatherDesc ad{x, zeros, P, H, W, ilog2(W), cin};
-  const int KT = 9 * cin / DBK;
+  GatherDesc ad{x, zeros, P, H, W, ilog2(W), cin, H, W};
   if (cout % 128 == 0)
     return launch_conv<128, 128, 3, RowGather<128, 4, false>, Plain<128, 4, false>>(s, P, cout, KT, 1, 1, ad, bd, e);
   return launch_conv<128, 64, 4, RowGather<128, 4, false>, Plain<64, 4, false>>(s, P, cout, KT, 1, 1, ad, bd, e);
 }
 
-hipError_t conv_mfma_dgrad(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* dz,
+hipError_t conv_mfma_dgrad(hipStream_t s, int imgs, int H, int W, int stride, int cin, int cout, const uint16_t* dz,
                            const uint16_t* wb, const uint16_t* d_prev, uint16_t* out, const uint16_t* zeros) {
   const int P = imgs * H * W;
   // k tile -> (tap, block of 64 output channels): rows co0.. of W_b, columns tap*Cin..
   PlainDesc bd{wb, 9 * cin, cin, cout / DBK, (long)DBK * 9 * cin, cin};
   EpiDgrad e{d_prev, out, cin};
+  if (stride == 2) {  // rows: input pixels, source: dz on the (H/2) x (W/2) grid; taps of the wrong parity read zeros
+    GatherDesc ad{dz, zeros, P, H, W, ilog2(W), cout, H / 2, W / 2};
+    const int KT = 9 * cout / DBK;
+    if (cin % 128 == 0)
+      return launch_conv<128, 128, 3, RowGather<128, 4, true, 2>, Plain<128, 4, true>>(s, P, cin, KT, 1, 1, ad, bd, e);
+    return launch_conv<128, 64, 4, RowGather<128, 4, true, 2>, Plain<64, 4, true>>(s, P, cin, KT, 1, 1, ad, bd, e);
+  }
   {
     const PatchDesc pd{dz, zeros, H, W, ilog2(W), cout, 0, cout / 8, 0};
     const hipError_t err = launch_patch_conv<true>(s, P, H, W, cout, cin, pd, bd, e);
     if (err != hipErrorNotSupported) return err;
   }
-  GatherDesc ad{dz, zeros, P, H, W, ilog2(W), cout};
+  GatherDesc ad{dz, zeros, P, H, W, ilog2(W), cout, H, W};
   const int KT = 9 * cout / DBK;
   if (cin % 128 == 0)
     return launch_conv<128, 128, 3, RowGather<128, 4, true>, Plain<128, 4, true>>(s, P, cin, KT, 1, 1, ad, bd, e);
   return launch_conv<128, 64, 4, RowGather<128, 4, true>, Plain<64, 4, true>>(s, P, cin, KT, 1, 1, ad, bd, e);
 }
 
-hipError_t conv_mfma_wgrad(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* dz,
+hipError_t conv_mfma_wgrad(hipStream_t s, int imgs, int H, int W, int stride, int cin, int cout, const uint16_t* dz,
                            const uint16_t* x, float* gW, float* partial, const uint16_t* zeros) {
-  const int P = imgs * H * W;
   const size_t count = (size_t)cout * 9 * cin;
+  if (stride == 2) {  // contraction over the output pixels; x is gathered at 2*(oh, ow) + tap
+    const int Ho = H / 2, Wo = W / 2, P = imgs * Ho * Wo;
+    const int splits = conv_mfma_wgrad_splits(P, cin, cout);
+    const int KT = P / DBK / splits;
+    PlainDesc ad{dz, cout, cout, 1 << 30, (long)DBK * cout, 0};
+    GatherDesc bd{x, zeros, P, Ho, Wo, ilog2(Wo), cin, H, W};
+    EpiWgradConv e{splits > 1 ? partial : gW, cin, cout};
+    hipError_t err;
+    if (cout % 128 == 0 && cin % 128 == 0)
+      err = launch_conv<128, 128, 3, Plain<128, 4, true>, ColGather<128, 4, 2>>(s, cout, cin, KT, 9, splits, ad, bd, e);
+    else
+      err = launch_conv<64, 64, 4, Plain<64, 4, true>, ColGather<64, 4, 2>>(s, cout, cin, KT, 9, splits, ad, bd, e);
+    if (err != hipSuccess || splits == 1) return err;
+    return launch_sum_partials(s, count, splits, partial, gW);
+  }
+  const int P = imgs * H * W;
   if (wgrad_patch_ok(H, W)) {
     const int px_tiles = P / kWgradBM;
     const int splits = wgrad_patch_splits(px_tiles, cin, cout);
@@ -885,7 +955,7 @@ hipError_t conv_mfma_wgrad(hipStream_t s, int imgs, int H, int W, int cin, int c
   const int splits = conv_mfma_wgrad_splits(P, cin, cout);
   const int KT = P / DBK / splits;
   PlainDesc ad{dz, cout, cout, 1 << 30, (long)DBK * cout, 0};
-  GatherDesc bd{x, zeros, P, H, W, ilog2(W), cin};
+  GatherDesc bd{x, zeros, P, H, W, ilog2(W), cin, H, W};
   EpiWgradConv e{splits > 1 ? partial : gW, cin, cout};
   hipError_t err;
   if (cout % 128 == 0 && cin % 128 == 0)

@@ -72,6 +72,9 @@ struct Plan {
   size_t elt_size = 4;
 };
 
+// output pixels per image of a convolution layer (geom: H, W, kernel, stride, pad)
+inline uint64_t conv_out_px(const tp_layer_desc& L) { return (uint64_t)(L.geom[0] / L.geom[3]) * (L.geom[1] / L.geom[3]); }
+
 int check_desc(const tp_stage_desc* d) {
   if (!d) return fail(TP_EINVAL, "null stage description");
   if (d->num_layers < 1 || d->num_layers > TP_MAX_LAYERS)
@@ -90,6 +93,7 @@ int check_desc(const tp_stage_desc* d) {
   if (!std::isfinite(d->lr) || !std::isfinite(d->momentum)) return fail(TP_EINVAL, "lr/momentum not finite");
   uint64_t prev_out = 0;
   int open_skip = -1;  // layer of a residual begin that has not met its add yet
+  int open_swap = -1;  // layer of the swap between that begin and its add, if there is one
   for (int l = 0; l < d->num_layers; ++l) {
     const tp_layer_desc& L = d->layers[l];
     if (L.act < TP_ACT_NONE || L.act > TP_ACT_GELU) return fail(TP_EINVAL, "layer %d: unknown activation", l);
@@ -106,6 +110,18 @@ int check_desc(const tp_stage_desc* d) {
       if (L.geom[0] < 1 || L.in_features != L.out_features || L.geom[1] || L.geom[2] || L.geom[3] || L.geom[4])
         return fail(TP_EINVAL, "layer %d: malformed batch normalisation layer", l);
       in_e = out_e = (uint64_t)L.geom[0] * L.in_features;
+    } else if (L.type == TP_LAYER_RESIDUAL && L.geom[1] == 2) {
+      // swap: the main branch's result is set aside and the tensor remembered at the begin comes back,
+      // so that the layers up to the add form a second branch (a projection shortcut)
+      if (open_skip < 0 || open_swap >= 0) return fail(TP_EINVAL, "layer %d: residual swap needs an open begin and no earlier swap", l);
+      const tp_layer_desc& B = d->layers[open_skip];
+      if (L.geom[0] < 1 || L.geom[2] < 1 || L.act != TP_ACT_NONE || L.geom[3] || L.geom[4])
+        return fail(TP_EINVAL, "layer %d: malformed residual swap", l);
+      if (L.out_features != B.in_features || L.geom[2] != B.geom[0])
+        return fail(TP_EINVAL, "layer %d: residual swap does not give back the shape remembered at layer %d", l, open_skip);
+      open_swap = l;
+      in_e = (uint64_t)L.geom[0] * L.in_features;
+      out_e = (uint64_t)L.geom[2] * L.out_features;
     } else if (L.type == TP_LAYER_LAYERNORM || L.type == TP_LAYER_RESIDUAL) {
       const bool act_ok = L.act == TP_ACT_NONE || (L.type == TP_LAYER_RESIDUAL && L.geom[1] == 1);
       if (L.geom[0] < 1 || L.in_features != L.out_features || !act_ok || L.geom[2] || L.geom[3] || L.geom[4])
@@ -113,16 +129,17 @@ int check_desc(const tp_stage_desc* d) {
       if (L.type == TP_LAYER_LAYERNORM && (L.geom[1] != 0 || L.in_features > 20480))
         return fail(TP_EINVAL, "layer %d: malformed normalisation layer", l);
       if (L.type == TP_LAYER_RESIDUAL) {
-        if (L.geom[1] != 0 && L.geom[1] != 1) return fail(TP_EINVAL, "layer %d: residual mark must be 0 or 1", l);
+        if (L.geom[1] != 0 && L.geom[1] != 1) return fail(TP_EINVAL, "layer %d: residual mark must be 0, 1 or 2", l);
         if (L.geom[1] != (open_skip >= 0 ? 1 : 0))
           return fail(TP_EINVAL, "layer %d: residual marks must alternate begin, add", l);
         if (L.geom[1] == 0) {
           open_skip = l;
         } else {
-          const tp_layer_desc& B = d->layers[open_skip];
+          const int kept = open_swap >= 0 ? open_swap : open_skip;
+          const tp_layer_desc& B = d->layers[kept];
           if (B.in_features != L.in_features || B.geom[0] != L.geom[0])
-            return fail(TP_EINVAL, "layer %d: residual add does not match the shape remembered at layer %d", l, open_skip);
-          open_skip = -1;
+            return fail(TP_EINVAL, "layer %d: residual add does not match the shape remembered at layer %d", l, kept);
+          open_skip = open_swap = -1;
         }
       }
       in_e = out_e = (uint64_t)L.geom[0] * L.in_features;
@@ -138,15 +155,26 @@ int check_desc(const tp_stage_desc* d) {
       out_e = (uint64_t)L.geom[0] * L.out_features;
     } else if (L.type == TP_LAYER_CONV2D) {
       if (L.geom[0] < 1 || L.geom[1] < 1) return fail(TP_EINVAL, "layer %d: empty image", l);
-      if (L.geom[2] != 3 || L.geom[3] != 1 || L.geom[4] != 1)
-        return fail(TP_EINVAL, "layer %d: only 3x3 / stride 1 / pad 1 convolutions are built", l);
+      if (L.geom[2] != 3 || (L.geom[3] != 1 && L.geom[3] != 2) || L.geom[4] != 1)
+        return fail(TP_EINVAL, "layer %d: only 3x3 / stride 1 or 2 / pad 1 convolutions are built", l);
+      if (L.geom[3] == 2 && ((L.geom[0] & 1) || (L.geom[1] & 1)))
+        return fail(TP_EINVAL, "layer %d: a stride-2 convolution needs even height and width", l);
       in_e = (uint64_t)L.geom[0] * L.geom[1] * L.in_features;
-      out_e = (uint64_t)L.geom[0] * L.geom[1] * L.out_features;
+      out_e = (uint64_t)(L.geom[0] / L.geom[3]) * (L.geom[1] / L.geom[3]) * L.out_features;
     } else if (L.type == TP_LAYER_MAXPOOL2) {
       if (L.geom[0] < 2 || L.geom[1] < 2 || (L.geom[0] & 1) || (L.geom[1] & 1))
         return fail(TP_EINVAL, "layer %d: pooling needs even height and width", l);
       if (L.in_features != L.out_features || L.act != TP_ACT_NONE || L.geom[2] || L.geom[3] || L.geom[4])
         return fail(TP_EINVAL, "layer %d: malformed pooling layer", l);
+      in_e = (uint64_t)L.geom[0] * L.geom[1] * L.in_features;
+      out_e = in_e / 4;
+    } else if (L.type == TP_LAYER_SUBSAMPLE2) {
+      if (L.geom[0] < 2 || L.geom[1] < 2 || (L.geom[0] & 1) || (L.geom[1] & 1))
+        return fail(TP_EINVAL, "layer %d: subsampling needs even height and width", l);
+      if (L.in_features != L.out_features || L.act != TP_ACT_NONE || L.geom[2] || L.geom[3] || L.geom[4])
+        return fail(TP_EINVAL, "layer %d: malformed subsampling layer", l);
+      if ((L.in_features * (d->dtype == TP_BF16 ? 2 : 4)) % 16)
+        return fail(TP_EINVAL, "layer %d: subsampling needs pixels of whole 16-byte units", l);
       in_e = (uint64_t)L.geom[0] * L.geom[1] * L.in_features;
       out_e = in_e / 4;
     } else {
@@ -172,8 +200,8 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
   std::memset(&p->sizes, 0, sizeof(p->sizes));
   uint64_t off = 0, act = 0, max_feat = 0;
   uint64_t conv_scratch = 0, norm_scratch = 0;
-  int open_skip = -1;
-  bool alias_prev = false;  // the previous layer was a residual begin: this layer reads the same tensor
+  int open_skip = -1, open_swap = -1;
+  int alias_of = -1;  // >= 0: this layer reads the tensor layer `alias_of` saved (it follows a residual begin or swap)
   for (int l = 0; l < d->num_layers; ++l) {
     LayerPlan lp;
     lp.d = d->layers[l];
@@ -209,12 +237,21 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
       lp.tokens = L.geom[0];
       lp.in_elems = lp.out_elems = (uint64_t)lp.tokens * L.in_features;
       lp.w_elems = 0;
-      if (L.geom[1] == 0) open_skip = l; else lp.skip_layer = open_skip;
+      if (L.geom[1] == 0) {
+        open_skip = l;
+      } else if (L.geom[1] == 2) {
+        lp.out_elems = (uint64_t)L.geom[2] * L.out_features;
+        lp.skip_layer = open_skip;   // whose saved input the next layer reads
+        open_swap = l;
+      } else {
+        lp.skip_layer = open_swap >= 0 ? open_swap : open_skip;  // the tensor that is added: saved input of that layer
+        open_skip = open_swap = -1;
+      }
     } else if (L.type == TP_LAYER_CONV2D) {
       lp.in_elems = (uint64_t)L.geom[0] * L.geom[1] * L.in_features;
-      lp.out_elems = (uint64_t)L.geom[0] * L.geom[1] * L.out_features;
+      lp.out_elems = conv_out_px(L) * L.out_features;
       lp.w_elems = (uint64_t)L.out_features * 9 * L.in_features;
-      conv_scratch = std::max<uint64_t>(conv_scratch, tp::conv_wgrad_scratch_floats((int)(rows * L.geom[0] * L.geom[1]),
+      conv_scratch = std::max<uint64_t>(conv_scratch, tp::conv_wgrad_scratch_floats((int)(rows * conv_out_px(L)),
                                                                                     L.in_features, L.out_features));
     } else {
       lp.in_elems = (uint64_t)L.geom[0] * L.geom[1] * L.in_features;
@@ -228,13 +265,13 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
       lp.b_off = off;
       off += round_up((uint64_t)L.out_features, 64);
     }
-    if (alias_prev) {
-      lp.x_off = p->layers.back().x_off;
+    if (alias_of >= 0) {
+      lp.x_off = p->layers[alias_of].x_off;
     } else {
       lp.x_off = act;
       act += round_up(rows * lp.in_elems * p->elt_size, 256);
     }
-    alias_prev = L.type == TP_LAYER_RESIDUAL && L.geom[1] == 0;
+    alias_of = L.type != TP_LAYER_RESIDUAL ? -1 : L.geom[1] == 0 ? l : L.geom[1] == 2 ? lp.skip_layer : -1;
     if (lp.stat_elems || lp.stat_bytes) {
       lp.stat_off = act;
       act += round_up(lp.stat_bytes ? lp.stat_bytes : rows * lp.stat_elems * 4, 256);
@@ -245,7 +282,7 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
     } else {
       lp.z_off = UINT64_MAX;
     }
-    if (l == 0 && L.type == TP_LAYER_CONV2D && d->dtype == TP_BF16 &&
+    if (l == 0 && L.type == TP_LAYER_CONV2D && L.geom[3] == 1 && d->dtype == TP_BF16 &&
         tp::conv_c8_supported((int)rows, L.geom[0], L.geom[1], L.in_features, L.out_features) &&
         tp::conv_c8_supported(d->mb, L.geom[0], L.geom[1], L.in_features, L.out_features)) {
       lp.xpad_off = act;
@@ -264,7 +301,7 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
     if (!lp.w_elems) continue;
     // bias gradients: column sums over rows (dense) or over all pixels (conv)
     if (lp.d.type == TP_LAYER_LAYERNORM || lp.d.type == TP_LAYER_BATCHNORM) continue;
-    const uint64_t r = lp.d.type == TP_LAYER_CONV2D ? rows * lp.d.geom[0] * lp.d.geom[1] : rows * lp.tokens;
+    const uint64_t r = lp.d.type == TP_LAYER_CONV2D ? rows * conv_out_px(lp.d) : rows * lp.tokens;
     wg = std::max<uint64_t>(wg, tp::colsum_scratch_floats((int)r, lp.d.out_features));
   }
   p->partial_floats = round_up(std::max<uint64_t>({wg, tp::update_scratch_floats(), rows, conv_scratch, norm_scratch}), 64);
@@ -613,6 +650,7 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
     }
     if (lp.d.type == TP_LAYER_RESIDUAL) {
       if (lp.skip_layer < 0) continue;  // begin: the next layer reads this layer's input in place
+      if (lp.d.geom[1] == 2) continue;  // swap: this layer's input stays saved for the add, the next layer reads the begin's
       ProfScope ps(st, TP_K_ADD);
       const char* skip = aslot + st->plan.layers[lp.skip_layer].x_off + row0 * lp.in_elems * es;
       if (lp.d.act == TP_ACT_NONE)
@@ -631,9 +669,13 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
     }
     if (lp.d.type == TP_LAYER_CONV2D) {
       ProfScope ps(st, TP_K_FPROP);
-      HIP_TRY(tp::launch_conv_fprop(st->stream, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features,
+      HIP_TRY(tp::launch_conv_fprop(st->stream, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.geom[3], lp.d.in_features,
                                     lp.d.out_features, x_saved, wcopy + lp.w_off * es, master + lp.b_off, lp.d.act,
                                     z_out, a_out, st->zeros()));
+    } else if (lp.d.type == TP_LAYER_SUBSAMPLE2) {
+      ProfScope ps(st, TP_K_POOL);
+      HIP_TRY(tp::launch_subsample_fwd(st->stream, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, x_saved,
+                                       a_out));
     } else {
       ProfScope ps(st, TP_K_POOL);
       HIP_TRY(tp::launch_maxpool_fwd(st->stream, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, x_saved,
@@ -732,7 +774,7 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
       // where the gradient w.r.t. this layer's input goes, and what it is multiplied with on the way
       const bool to_caller = l == 0;
       const bool no_dx = to_caller && !d.needs_dx;
-      if (no_dx && (lp.d.type == TP_LAYER_MAXPOOL2 || lp.d.type == TP_LAYER_ATTENTION)) break;
+      if (no_dx && (lp.d.type == TP_LAYER_MAXPOOL2 || lp.d.type == TP_LAYER_SUBSAMPLE2 || lp.d.type == TP_LAYER_ATTENTION)) break;
       const void* dprev = nullptr;
       if (l > 0) {
         const LayerPlan& prev = st->plan.layers[l - 1];
@@ -753,6 +795,29 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
         }
         if (int rc = through_activation(dst)) return rc;
         dz = dst;
+        continue;
+      }
+      if (lp.d.type == TP_LAYER_SUBSAMPLE2) {
+        {
+          ProfScope ps(st, TP_K_POOL);
+          HIP_TRY(tp::launch_subsample_bwd(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, dz, dst));
+        }
+        if (int rc = through_activation(dst)) return rc;
+        dz = dst;
+        continue;
+      }
+      if (lp.d.type == TP_LAYER_RESIDUAL && lp.d.geom[1] == 2) {
+        // swap: what came down the second branch is the gradient w.r.t. the tensor remembered at the begin and
+        // waits for it; the gradient set aside at the add goes on into the main branch.
+        const void* main_grad = pinned;
+        pinned = dz;
+        if (dprev) {
+          void* buf = scratch_for(main_grad);  // not the one just set aside, not the one read
+          ProfScope ps(st, TP_K_ACT_BWD);
+          HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * lp.in_elems, main_grad, dprev, buf));
+          main_grad = buf;
+        }
+        dz = main_grad;
         continue;
       }
       if (lp.d.type == TP_LAYER_RESIDUAL) {
@@ -826,7 +891,7 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
         dz = dst;
         continue;
       }
-      const int grad_rows = lp.d.type == TP_LAYER_CONV2D ? rows * lp.d.geom[0] * lp.d.geom[1] : rows * lp.tokens;
+      const int grad_rows = lp.d.type == TP_LAYER_CONV2D ? rows * (int)conv_out_px(lp.d) : rows * lp.tokens;
       {
         ProfScope ps(st, TP_K_COLSUM);
         HIP_TRY(tp::launch_colsum(st->stream, d.dtype, grad_rows, lp.d.out_features, dz, g + lp.b_off, st->partials()));
@@ -841,7 +906,7 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
                                     (const uint16_t*)dz, (const uint16_t*)(aslot + lp.xpad_off), g + lp.w_off, st->partials(),
                                     (const uint16_t*)st->zeros()));
         else
-          HIP_TRY(tp::launch_conv_wgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features,
+          HIP_TRY(tp::launch_conv_wgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.geom[3], lp.d.in_features,
                                         lp.d.out_features, dz, aslot + lp.x_off, g + lp.w_off, st->partials(),
                                         st->zeros()));
       }
@@ -852,7 +917,7 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
           HIP_TRY(tp::launch_dgrad(st->stream, d.dtype, grad_rows, lp.d.out_features, lp.d.in_features, dz, wb + lp.w_off * es,
                                    dprev, dst));
         else
-          HIP_TRY(tp::launch_conv_dgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features,
+          HIP_TRY(tp::launch_conv_dgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.geom[3], lp.d.in_features,
                                         lp.d.out_features, dz, wb + lp.w_off * es, dprev, dst, st->zeros()));
       }
       dz = dst;

@@ -17,10 +17,14 @@ def layer_tuple(spec) -> tuple:
     """Workload layer description -> the tuple format of binding.make_desc."""
     kind = getattr(spec, "kind", "dense")
     if kind == "conv":
-        assert (spec.k, spec.stride, spec.pad) == (3, 1, 1), "only 3x3 / stride 1 / pad 1 convolutions are built"
-        return ("conv", spec.cin, spec.cout, spec.h, spec.w, spec.act)
+        assert (spec.k, spec.pad) == (3, 1) and spec.stride in (1, 2), "only 3x3 / stride 1 or 2 / pad 1 convolutions are built"
+        return ("conv", spec.cin, spec.cout, spec.h, spec.w, spec.act, spec.stride)
     if kind == "pool":
         return ("pool", spec.c, spec.h, spec.w)
+    if kind == "sub":
+        return ("sub", spec.c, spec.h, spec.w)
+    if kind == "swap":
+        return ("swap", spec.d, spec.tokens, spec.out_d, spec.out_tokens)
     if kind == "ln":
         return ("ln", spec.d, spec.tokens)
     if kind == "attn":

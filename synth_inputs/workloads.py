@@ -132,6 +132,53 @@ class Residual:
 
 
 @dataclass(frozen=True)
+class ResidualSwap:
+    """Between a Residual "begin" and its "add": sets the current activation (the main branch's result,
+    [tokens, d]) aside as the one the add will add, and hands the tensor remembered at the begin
+    ([out_tokens, out_d]) to the next layer, so that the layers up to the add form a projection shortcut."""
+    d: int
+    tokens: int
+    out_d: int
+    out_tokens: int
+    kind: str = "swap"
+    act: str = "none"
+
+    def param_shapes(self):
+        return []
+
+    def in_shape(self):
+        return (self.tokens, self.d)
+
+    def out_shape(self):
+        return (self.out_tokens, self.out_d)
+
+    def out_dim(self):
+        return self.out_tokens * self.out_d
+
+
+@dataclass(frozen=True)
+class Subsample2:
+    """Every second pixel of every second row of an NHWC image (what a stride-2 1x1 convolution reads); no parameters."""
+    c: int
+    h: int
+    w: int
+    act: str = "none"
+    kind: str = "sub"
+
+    def param_shapes(self):
+        return []
+
+    def in_shape(self):
+        return (self.h, self.w, self.c)
+
+    def out_shape(self):
+        return (self.h // 2, self.w // 2, self.c)
+
+    def out_dim(self):
+        return (self.h // 2) * (self.w // 2) * self.c
+
+
+@dataclass(frozen=True)
 class Conv2d:
     """3x3-style convolution on NHWC activations, weights [Cout][kh][kw][Cin], plus bias and activation."""
     cin: int
@@ -269,13 +316,27 @@ def bottleneck_block(c: int, mid: int, h: int, w: int, act: str = "relu") -> tup
             BatchNorm(c, t, "none"), Residual(c, t, "add", act=act))
 
 
+def bottleneck_down_block(cin: int, mid: int, cout: int, h: int, w: int, act: str = "relu") -> tuple:
+    """First bottleneck of a group: [h, w, cin] -> [h/2, w/2, cout].  Main branch 1x1 conv cin->mid, BN, ReLU, 3x3
+    conv mid->mid with stride 2, BN, ReLU, 1x1 conv mid->cout, BN; shortcut 1x1 conv cin->cout with stride 2
+    (= subsampling, then a per-position dense layer), BN; sum, ReLU."""
+    t, to = h * w, (h // 2) * (w // 2)
+    return (Residual(cin, t, "begin"), Dense(cin, mid, "none", tokens=t), BatchNorm(mid, t, act),
+            Conv2d(mid, mid, h, w, "none", stride=2), BatchNorm(mid, to, act), Dense(mid, cout, "none", tokens=to),
+            BatchNorm(cout, to, "none"), ResidualSwap(cout, to, cin, t), Subsample2(cin, h, w),
+            Dense(cin, cout, "none", tokens=to), BatchNorm(cout, to, "none"), Residual(cout, to, "add", act=act))
+
+
 def bottleneck_stage(c: int = 1024, mid: int = 256, h: int = 4, w: int = 4, blocks: int = 5, mb: int = 128, n: int = 4,
-                     dtype: str = "bf16") -> Workload:
-    """The identity bottlenecks of the conv4_x group of a ResNet-50-style net on 64x64 inputs (4x4 feature
-    maps, 1024 channels), as an interior stage.  The group's first block (stride 2, projection shortcut) is
-    not described."""
-    layers = tuple(l for _ in range(blocks) for l in bottleneck_block(c, mid, h, w))
-    return Workload(name=f"bneck{c}x{blocks}_{dtype}_s1", dtype=dtype, stages=((), layers, (), ()), mb=mb, n=n, classes=2)
+                     dtype: str = "bf16", down: bool = False, act: str = "relu") -> Workload:
+    """A bottleneck group of a ResNet-50-style net as an interior stage; the defaults are conv4_x on 64x64
+    inputs (4x4 feature maps, 1024 channels).  down=True puts the group's first block in front -- from
+    [2h, 2w, c/2] with stride 2 and a projection shortcut -- followed by `blocks` identity bottlenecks."""
+    layers = tuple(l for _ in range(blocks) for l in bottleneck_block(c, mid, h, w, act))
+    if down:
+        layers = bottleneck_down_block(c // 2, mid, c, 2 * h, 2 * w, act) + layers
+    tag = f"d{blocks}" if down else f"{blocks}"
+    return Workload(name=f"bneck{c}x{tag}_{dtype}_s1", dtype=dtype, stages=((), layers, (), ()), mb=mb, n=n, classes=2)
 
 
 def transformer_block(d: int, heads: int, ffn: int, tokens: int) -> tuple:

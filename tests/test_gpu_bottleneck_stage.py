@@ -33,3 +33,34 @@ def test_bottleneck_matrix_core_shapes_bf16(act):
     # are held to the looser one (mask decisions behind a batch normalisation, see _run_stage).
     specs = W.bottleneck_block(256, 128, 4, 4, act) + W.bottleneck_block(256, 128, 4, 4, act)
     print(act, _run_stage(specs, f"bneck_mfma_{act}", "bf16", mb=8, n=2, depth=2, minibatches=3))
+
+
+# ---- first block of a group: 3x3 with stride 2, projection shortcut (subsample + 1x1 + batch norm) -------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_small_down_block_then_identity_block(dtype):
+    # 16 channels on 8x8 -> 32 channels on 4x4 (generic kernels); 64 values per channel and micro-batch behind the
+    # stride, so that the batch statistics do not amplify bf16 noise
+    specs = W.bottleneck_down_block(16, 16, 32, 8, 8, "gelu") + W.bottleneck_block(32, 16, 4, 4, "gelu")
+    print(dtype, _run_stage(specs, f"bneck_down_small_{dtype}", dtype, mb=4, n=2, depth=3, minibatches=3))
+
+
+def test_down_block_first_stage_relu_fp32():
+    print(_run_stage(W.bottleneck_down_block(8, 4, 8, 4, 6), "bneck_down_first", "f32", mb=3, n=2, needs_dx=False))
+
+
+def test_strided_convolution_alone_fp32_and_bf16():
+    # 3x3 stride 2 on a non-square image, followed by a dense layer on the smaller grid
+    specs = (W.Conv2d(8, 16, 6, 4, "gelu", stride=2), W.Dense(16, 8, "none", tokens=6))
+    print(_run_stage(specs, "conv_s2_f32", "f32", mb=3, n=2))
+    print(_run_stage(specs, "conv_s2_bf16", "bf16", mb=3, n=2))
+
+
+@pytest.mark.parametrize("act", ["gelu", "relu"])
+def test_down_block_matrix_core_shapes_bf16(act):
+    # 128 channels on 8x8 -> 256 on 4x4 with 64 / 128 in the middle: the strided 3x3 runs on the gathered matrix-core
+    # kernels (fprop rows: output pixels; dgrad rows: input pixels, taps of the wrong parity read zeros; wgrad
+    # contraction over the output pixels)
+    for mid in (64, 128):
+        specs = W.bottleneck_down_block(128, mid, 256, 8, 8, act) + W.bottleneck_block(256, mid, 4, 4, act)
+        print(act, mid, _run_stage(specs, f"bneck_down_mfma_{act}_{mid}", "bf16", mb=8, n=2, depth=2, minibatches=3))

@@ -48,6 +48,17 @@ def test_bottleneck_blocks_full_geometry():
     print(f"{time.time() - t0:.1f} s", worst)
 
 
+@pytest.mark.timeout(900)
+def test_bottleneck_down_block_full_geometry():
+    # the first block of the conv4_x group at its real geometry: [8, 8, 512] -> [4, 4, 1024], 3x3 with stride 2 on
+    # 256 channels, projection shortcut 512 -> 1024; followed by one identity block
+    w = W.bottleneck_stage(blocks=1, down=True)
+    t0 = time.time()
+    worst = _run_stage(w.stages[1], "bneck_down_full", "bf16", mb=w.mb, n=w.n, policy="convex", depth=3, minibatches=3,
+                       needs_dx=True, lr=2e-4)
+    print(f"{time.time() - t0:.1f} s", worst)
+
+
 @pytest.mark.timeout(1200)
 def test_transformer_block_full_geometry_sampled_sequences():
     """One of the four identical blocks of the transformer stage at its real geometry (d_model 2048, 16 heads
