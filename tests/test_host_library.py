@@ -231,6 +231,37 @@ def test_transformer_layer_descriptions():
         B.make_desc([(4, 4, "none")] * (B.TP_MAX_LAYERS + 1), **good)
 
 
+def test_projection_shortcut_descriptions():
+    from paper_2509_23241_amd.runner import layer_tuple
+    from synth_inputs import workloads as W
+    good = dict(dtype="bf16", mb=2, n=2, stage_index=1, num_stages=4, ring_capacity=3, max_in_flight=3,
+                policy="convex", needs_dx=True, lam=0.1, lr=0.01, momentum=0.9)
+    block = [layer_tuple(l) for l in W.bottleneck_down_block(16, 8, 32, 4, 4)]
+    s = B.stage_workspace_query(B.make_desc(block, **good))
+    assert B.layer_in_elems(block[0]) == 16 * 16 and B.layer_out_elems(block[-1]) == 4 * 32
+    # parameters: 1x1 (16 -> 8), bn 8, 3x3 stride 2 (8 -> 8), bn 8, 1x1 (8 -> 32), bn 32, projection 1x1 (16 -> 32), bn 32
+    assert s.param_count == (128 + 64) + 128 + (576 + 64) + 128 + (256 + 64) + 128 + (512 + 64) + 128
+    swap = block.index(("swap", 32, 4, 16, 16))
+    bad_cases = [
+        block[swap:],                                                        # swap without a begin
+        block[:swap] + [("swap", 32, 4, 16, 4)] + block[swap + 1:],          # does not give back the remembered shape
+        block[:swap + 1] + [("swap", 16, 16, 16, 16)] + block[swap + 1:],    # second swap before the add
+        block[:-1] + [("res", 16, 16, "add")],                               # add with the begin's shape, not the kept one
+        [("conv", 8, 8, 4, 4, "none", 3)],                                   # stride 3
+        [("conv", 8, 8, 5, 4, "none", 2)],                                   # stride 2 on an odd height
+        [("sub", 8, 4, 3)],                                                  # odd width
+        [("sub", 4, 4, 4)],                                                  # bf16 pixels of 8 bytes
+    ]
+    for layers in bad_cases:
+        with pytest.raises(B.StageLibError) as ei:
+            B.stage_workspace_query(B.make_desc(layers, **good))
+        assert ei.value.code == B.TP_EINVAL, layers
+    # a stride-2 convolution quarters the sample: its output chains into a layer on the smaller grid only
+    B.stage_workspace_query(B.make_desc([("conv", 8, 8, 4, 4, "none", 2), (8, 8, "none", 4)], **good))
+    with pytest.raises(B.StageLibError):
+        B.stage_workspace_query(B.make_desc([("conv", 8, 8, 4, 4, "none", 2), (8, 8, "none", 16)], **good))
+
+
 def test_workspace_layout():
     d = B.make_desc([(256, 512, "relu"), (512, 10, "none")], dtype="bf16", mb=32, n=4, stage_index=0, num_stages=2,
                     ring_capacity=2, max_in_flight=2, policy="convex", needs_dx=False, lam=0.1, lr=0.01, momentum=0.9)
