@@ -862,7 +862,12 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
         const size_t seg_bytes = seg_rows * C * es;
         const size_t bn_scratch = tp::batchnorm_scratch_floats(seg_rows, C);
         float* sums = st->partials() + bn_scratch;                // [n][2*C]
-        {
+        if (tp::batchnorm_fused_bwd_supported(d.dtype, seg_rows, C)) {
+          ProfScope ps(st, TP_K_NORM);
+          HIP_TRY(tp::launch_batchnorm_bwd_fused(st->stream, d.dtype, seg_rows, C, d.n, dz, aslot + lp.x_off,
+                                                 (const float*)(aslot + lp.stat_off), gs, gl, (float)ca, (float)cb, dst,
+                                                 g + lp.w_off, g + lp.b_off));
+        } else {
           ProfScope ps(st, TP_K_NORM);
           for (int ub = 0; ub < d.n; ++ub)
             HIP_TRY(tp::launch_batchnorm_bwd(st->stream, d.dtype, seg_rows, C, (const char*)dz + ub * seg_bytes,

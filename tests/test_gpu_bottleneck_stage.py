@@ -64,3 +64,12 @@ def test_down_block_matrix_core_shapes_bf16(act):
     for mid in (64, 128):
         specs = W.bottleneck_down_block(128, mid, 256, 8, 8, act) + W.bottleneck_block(256, mid, 4, 4, act)
         print(act, mid, _run_stage(specs, f"bneck_down_mfma_{act}_{mid}", "bf16", mb=8, n=2, depth=2, minibatches=3))
+
+
+@pytest.mark.parametrize("mb,positions", [(6, 300), (3, 3000), (2, 9000)])
+def test_batchnorm_row_counts_across_kernel_families_bf16(mb, positions):
+    # rows per micro-batch 1800 (register-resident kernels, two loads per lane, ragged), 9000 (forward in registers,
+    # backward streaming) and 18000 (both streaming); GELU keeps bf16 away from kinks
+    specs = (W.Dense(8, 16, "none", tokens=positions), W.BatchNorm(16, positions, "gelu"),
+             W.Dense(16, 8, "none", tokens=positions), W.BatchNorm(8, positions, "none"))
+    print(mb * positions, _run_stage(specs, f"bn_rows_{mb * positions}", "bf16", mb=mb, n=3))
