@@ -22,6 +22,9 @@ hipError_t mfma_fprop(hipStream_t s, int M, int N, int K, const uint16_t* x, con
 // out = (dz Wb) (.) d_prev, d_prev = saved act'(z) of the previous layer or null.
 hipError_t mfma_dgrad(hipStream_t s, int M, int N, int K, const uint16_t* dz, const uint16_t* Wb,
                       const uint16_t* d_prev, uint16_t* out);
-hipError_t mfma_wgrad(hipStream_t s, int M, int N, int K, const uint16_t* dz, const uint16_t* x, float* gW);
+// partial: scratch of mfma_wgrad_scratch_floats(M, N, K) floats, or null.  A gradient with too few output tiles to
+// fill the chip is formed over several ranges of the M rows into `partial` and summed in a fixed order.
+hipError_t mfma_wgrad(hipStream_t s, int M, int N, int K, const uint16_t* dz, const uint16_t* x, float* gW, float* partial);
+size_t mfma_wgrad_scratch_floats(int M, int N, int K);
 
 }  // namespace tp

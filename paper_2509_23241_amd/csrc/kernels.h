@@ -22,7 +22,9 @@ hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void*
                         const void* d_prev, void* out);
 
 // gW = dz^T x  (fp32 [N x K]).
-hipError_t launch_wgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* x, float* gW);
+// partial: scratch of wgrad_scratch_floats(elt, M, N, K) floats (may be null when that is 0)
+hipError_t launch_wgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* x, float* gW, float* partial);
+size_t wgrad_scratch_floats(int elt, int M, int N, int K);
 
 // gb = column sums of dz[M x N] (fp32 [N]).
 // partials: scratch of at least colsum_scratch_floats(M, N) floats.

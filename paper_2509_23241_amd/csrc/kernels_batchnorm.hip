@@ -2,8 +2,8 @@
 // Two families.  Streaming kernels (any type and size): column statistics are formed by blocks of 64 columns x
 // a chunk of rows (lanes along the columns: every row read is one contiguous segment), block partials are
 // added in a fixed order by the shared partial-sum kernel; x is read three times in the forward pass and twice
-// in the backward pass.  Slab kernels (bf16, up to 16384 rows forward / 8192 backward): one launch per layer,
-// the values stay in registers between the passes.
+// in the backward pass.  Slab kernels (bf16, up to 8192 rows forward / 2048 backward -- what fits the register
+// file without spilling): one launch per layer, the values stay in registers between the passes.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -103,8 +103,8 @@ __global__ __launch_bounds__(kThreads) void bn_dx_kernel(size_t rows, int C, con
 // One workgroup of 1024 lanes owns 8 adjacent channels (one 16-byte unit per row) for ALL rows the
 // statistics run over; lane t holds rows t, t + 1024, ... in registers.  The passes of the layer --
 // mean, centred variance, normalise (forward); the two column sums, dx (backward) -- then cost one read
-// of the slab and one launch instead of five (forward) or three per micro-batch plus the sums over the
-// micro-batches (backward).  For the layers of a bottleneck stage (a few MB per call) the launches, not
+// of the slab and one launch instead of five (forward) or three per micro-batch (backward; the sums over the
+// micro-batches stay a launch of their own).  For the layers of a bottleneck stage (a few MB per call) the launches, not
 // the bytes, were what took the time.  Workgroups are renumbered so that those of one XCD (every eighth
 // workgroup id) take neighbouring slabs: a 128-byte line of x is then fetched into one L2, not eight.
 constexpr int kSlabThreads = 1024, kSlabWaves = kSlabThreads / 64;
@@ -166,9 +166,13 @@ __global__ __launch_bounds__(kSlabThreads) void bn_fwd_slab_kernel(int rows, int
     v[i] = r < rows ? *reinterpret_cast<const uint4*>(x + (size_t)r * C + c0) : make_uint4(0, 0, 0, 0);
   }
   const float inv_rows = 1.f / (float)rows;
-  float mean[8], rstd[8], s[8];
+  float mean[8], rstd[8], s[8], ga[8], be[8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) s[j] = 0.f;
+  for (int j = 0; j < 8; ++j) {
+    s[j] = 0.f;
+    ga[j] = gamma[c0 + j];
+    be[j] = beta[c0 + j];
+  }
 #pragma unroll
   for (int i = 0; i < NL; ++i) {  // rows past the end hold zeros
     float f[8];
@@ -188,13 +192,8 @@ __global__ __launch_bounds__(kSlabThreads) void bn_fwd_slab_kernel(int rows, int
     for (int j = 0; j < 8; ++j) s[j] = fmaf(f[j] - mean[j], f[j] - mean[j], s[j]);
   }
   slab_sum<8>(s, red);
-  float ga[8], be[8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    rstd[j] = rsqrtf(s[j] * inv_rows + kBnEps);
-    ga[j] = gamma[c0 + j];
-    be[j] = beta[c0 + j];
-  }
+  for (int j = 0; j < 8; ++j) rstd[j] = rsqrtf(s[j] * inv_rows + kBnEps);
   if (threadIdx.x == 0) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -219,75 +218,66 @@ __global__ __launch_bounds__(kSlabThreads) void bn_fwd_slab_kernel(int rows, int
   }
 }
 
-// All nseg micro-batches of a mini-batch in one launch: segment q has its own rows [q*rows, (q+1)*rows) and its
-// own statistics stats[q][2C]; dgamma, dbeta are the sums over the segments in order.
+// All micro-batches of a mini-batch in one launch: blockIdx.y = q owns rows [q*rows, (q+1)*rows) with its own
+// statistics stats[q][2C]; its column sums go to sums[q][0..C) (dy * xhat) and sums[q][C..2C) (dy).
 template <int NL>
-__global__ __launch_bounds__(kSlabThreads) void bn_bwd_slab_kernel(int rows, int C, int nseg, const uint16_t* __restrict__ dy,
+__global__ __launch_bounds__(kSlabThreads) void bn_bwd_slab_kernel(int rows, int C, const uint16_t* __restrict__ dy,
                                                                    const uint16_t* __restrict__ x, const float* __restrict__ stats,
                                                                    const float* __restrict__ gamma_s,
                                                                    const float* __restrict__ gamma_l, float alpha, float beta_c,
-                                                                   uint16_t* __restrict__ dx, float* __restrict__ dgamma,
-                                                                   float* __restrict__ dbeta) {
+                                                                   uint16_t* __restrict__ dx, float* __restrict__ sums) {
   __shared__ float red[(kSlabWaves + 1) * 16];
   const int c0 = slab_of_block(blockIdx.x, gridDim.x) * 8;
+  const int q = blockIdx.y;
   const float inv_rows = 1.f / (float)rows;
-  float g[8], tg[8], tb[8];
+  const size_t base = (size_t)q * rows * C + c0;
+  uint4 vx[NL], vd[NL];
+#pragma unroll
+  for (int i = 0; i < NL; ++i) {
+    const int r = i * kSlabThreads + threadIdx.x;
+    vx[i] = r < rows ? *reinterpret_cast<const uint4*>(x + base + (size_t)r * C) : make_uint4(0, 0, 0, 0);
+    vd[i] = r < rows ? *reinterpret_cast<const uint4*>(dy + base + (size_t)r * C) : make_uint4(0, 0, 0, 0);
+  }
+  float g[8], mean[8], rstd[8], s[16];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     g[j] = fmaf(alpha, gamma_s[c0 + j], beta_c * gamma_l[c0 + j]);
-    tg[j] = tb[j] = 0.f;
+    mean[j] = stats[(size_t)q * 2 * C + 2 * (c0 + j)];
+    rstd[j] = stats[(size_t)q * 2 * C + 2 * (c0 + j) + 1];
+    s[j] = s[8 + j] = 0.f;
   }
-  for (int q = 0; q < nseg; ++q) {
-    const size_t base = (size_t)q * rows * C + c0;
-    uint4 vx[NL], vd[NL];
 #pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      const int r = i * kSlabThreads + threadIdx.x;
-      vx[i] = r < rows ? *reinterpret_cast<const uint4*>(x + base + (size_t)r * C) : make_uint4(0, 0, 0, 0);
-      vd[i] = r < rows ? *reinterpret_cast<const uint4*>(dy + base + (size_t)r * C) : make_uint4(0, 0, 0, 0);
-    }
-    float mean[8], rstd[8], s[16];
+  for (int i = 0; i < NL; ++i) {  // rows past the end: dy = 0 adds nothing
+    float fx[8], fd[8];
+    unpack8(vx[i], fx);
+    unpack8(vd[i], fd);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      mean[j] = stats[(size_t)q * 2 * C + 2 * (c0 + j)];
-      rstd[j] = stats[(size_t)q * 2 * C + 2 * (c0 + j) + 1];
-      s[j] = s[8 + j] = 0.f;
-    }
-#pragma unroll
-    for (int i = 0; i < NL; ++i) {  // rows past the end: dy = 0 adds nothing
-      float fx[8], fd[8];
-      unpack8(vx[i], fx);
-      unpack8(vd[i], fd);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        s[j] = fmaf(fd[j], (fx[j] - mean[j]) * rstd[j], s[j]);
-        s[8 + j] += fd[j];
-      }
-    }
-    slab_sum<16>(s, red);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { tg[j] += s[j]; tb[j] += s[8 + j]; }
-#pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      const int r = i * kSlabThreads + threadIdx.x;
-      if (r >= rows) continue;
-      float fx[8], fd[8], o[8];
-      unpack8(vx[i], fx);
-      unpack8(vd[i], fd);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float xh = (fx[j] - mean[j]) * rstd[j];
-        o[j] = g[j] * rstd[j] * (fd[j] - (s[8 + j] + xh * s[j]) * inv_rows);
-      }
-      *reinterpret_cast<uint4*>(dx + base + (size_t)r * C) = pack8(o);
+      s[j] = fmaf(fd[j], (fx[j] - mean[j]) * rstd[j], s[j]);
+      s[8 + j] += fd[j];
     }
   }
+  slab_sum<16>(s, red);
   if (threadIdx.x == 0) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      dgamma[c0 + j] = tg[j];
-      dbeta[c0 + j] = tb[j];
+      sums[(size_t)q * 2 * C + c0 + j] = s[j];
+      sums[(size_t)q * 2 * C + C + c0 + j] = s[8 + j];
     }
+  }
+#pragma unroll
+  for (int i = 0; i < NL; ++i) {
+    const int r = i * kSlabThreads + threadIdx.x;
+    if (r >= rows) continue;
+    float fx[8], fd[8], o[8];
+    unpack8(vx[i], fx);
+    unpack8(vd[i], fd);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float xh = (fx[j] - mean[j]) * rstd[j];
+      o[j] = g[j] * rstd[j] * (fd[j] - (s[8 + j] + xh * s[j]) * inv_rows);
+    }
+    *reinterpret_cast<uint4*>(dx + base + (size_t)r * C) = pack8(o);
   }
 }
 
@@ -355,38 +345,34 @@ inline int slab_loads(size_t rows, int max_loads) {
 size_t batchnorm_scratch_floats(size_t rows, int C) { return ((size_t)bn_chunks(rows) * 2 + 2) * C; }
 
 bool batchnorm_fused_bwd_supported(int elt, size_t rows, int C) {
-  return elt == ELT_BF16 && C % 8 == 0 && rows >= 1 && slab_loads(rows, 8) != 0 && rows * C < (1ull << 31);
+  return elt == ELT_BF16 && C % 8 == 0 && rows >= 1 && slab_loads(rows, 2) != 0 && rows * C < (1ull << 31);
 }
 
 hipError_t launch_batchnorm_bwd_fused(hipStream_t s, int elt, size_t rows, int C, int nseg, const void* dy, const void* x,
                                       const float* stats, const float* gamma_s, const float* gamma_l, float alpha, float beta_c,
-                                      void* dx, float* dgamma, float* dbeta) {
-  if (!batchnorm_fused_bwd_supported(elt, rows, C)) return hipErrorNotSupported;
-#define TP_BN_BWD(NL)                                                                                                     \
-  hipLaunchKernelGGL(bn_bwd_slab_kernel<NL>, dim3(C / 8), dim3(kSlabThreads), 0, s, (int)rows, C, nseg, (const uint16_t*)dy, \
-                     (const uint16_t*)x, stats, gamma_s, gamma_l, alpha, beta_c, (uint16_t*)dx, dgamma, dbeta)
-  switch (slab_loads(rows, 8)) {
-    case 1: TP_BN_BWD(1); break;
-    case 2: TP_BN_BWD(2); break;
-    case 4: TP_BN_BWD(4); break;
-    default: TP_BN_BWD(8); break;
-  }
-#undef TP_BN_BWD
+                                      void* dx, float* sums) {
+  if (!batchnorm_fused_bwd_supported(elt, rows, C) || nseg < 1 || nseg > 65535) return hipErrorNotSupported;
+  const dim3 grid(C / 8, nseg);
+  if (slab_loads(rows, 2) == 1)
+    hipLaunchKernelGGL(bn_bwd_slab_kernel<1>, grid, dim3(kSlabThreads), 0, s, (int)rows, C, (const uint16_t*)dy, (const uint16_t*)x,
+                       stats, gamma_s, gamma_l, alpha, beta_c, (uint16_t*)dx, sums);
+  else
+    hipLaunchKernelGGL(bn_bwd_slab_kernel<2>, grid, dim3(kSlabThreads), 0, s, (int)rows, C, (const uint16_t*)dy, (const uint16_t*)x,
+                       stats, gamma_s, gamma_l, alpha, beta_c, (uint16_t*)dx, sums);
   return hipGetLastError();
 }
 
 hipError_t launch_batchnorm_fwd(hipStream_t s, int elt, size_t rows, int C, const void* x, const float* gamma, const float* beta,
                                 int act, void* a_out, void* d_out, float* stats, float* scratch) {
-  if (elt == ELT_BF16 && C % 8 == 0 && rows >= 1 && slab_loads(rows, 16) != 0 && rows * C < (1ull << 31)) {
+  if (elt == ELT_BF16 && C % 8 == 0 && rows >= 1 && slab_loads(rows, 8) != 0 && rows * C < (1ull << 31)) {
 #define TP_BN_FWD(NL)                                                                                                    \
   hipLaunchKernelGGL(bn_fwd_slab_kernel<NL>, dim3(C / 8), dim3(kSlabThreads), 0, s, (int)rows, C, (const uint16_t*)x, gamma, \
                      beta, act, (uint16_t*)a_out, (uint16_t*)d_out, stats)
-    switch (slab_loads(rows, 16)) {
+    switch (slab_loads(rows, 8)) {
       case 1: TP_BN_FWD(1); break;
       case 2: TP_BN_FWD(2); break;
       case 4: TP_BN_FWD(4); break;
-      case 8: TP_BN_FWD(8); break;
-      default: TP_BN_FWD(16); break;
+      default: TP_BN_FWD(8); break;
     }
 #undef TP_BN_FWD
     return hipGetLastError();

@@ -869,6 +869,17 @@ int conv_mfma_wgrad_splits(int pixels, int cin, int cout) {
   return s;
 }
 
+// Gathered fprop / dgrad: the largest tile that still gives half the CUs a workgroup, else the smallest.
+template <bool BWD, int S, class Epi>
+hipError_t launch_gather_rows(hipStream_t s, int P, int N, int KT, const GatherDesc& ad, const PlainDesc& bd, const Epi& e) {
+  const long rows128 = (P + 127) / 128;
+  if (N % 128 == 0 && rows128 * (N / 128) >= 128)
+    return launch_conv<128, 128, 3, RowGather<128, 4, BWD, S>, Plain<128, 4, BWD>>(s, P, N, KT, 1, 1, ad, bd, e);
+  if (rows128 * ((N + 63) / 64) >= 128)
+    return launch_conv<128, 64, 4, RowGather<128, 4, BWD, S>, Plain<64, 4, BWD>>(s, P, N, KT, 1, 1, ad, bd, e);
+  return launch_conv<64, 64, 4, RowGather<64, 4, BWD, S>, Plain<64, 4, BWD>>(s, P, N, KT, 1, 1, ad, bd, e);
+}
+
 hipError_t conv_mfma_fprop(hipStream_t s, int imgs, int H, int W, int stride, int cin, int cout, const uint16_t* x,
                            const uint16_t* wgt, const float* bias, int act, uint16_t* d_out, uint16_t* a_out,
                            const uint16_t* zeros) {
@@ -878,9 +889,7 @@ hipError_t conv_mfma_fprop(hipStream_t s, int imgs, int H, int W, int stride, in
   if (stride == 2) {  // rows: output pixels on the (H/2) x (W/2) grid, source: the input
     const int Ho = H / 2, Wo = W / 2, P = imgs * Ho * Wo;
     GatherDesc ad{x, zeros, P, Ho, Wo, ilog2(Wo), cin, H, W};
-    if (cout % 128 == 0)
-      return launch_conv<128, 128, 3, RowGather<128, 4, false, 2>, Plain<128, 4, false>>(s, P, cout, KT, 1, 1, ad, bd, e);
-    return launch_conv<128, 64, 4, RowGather<128, 4, false, 2>, Plain<64, 4, false>>(s, P, cout, KT, 1, 1, ad, bd, e);
+    return launch_gather_rows<false, 2>(s, P, cout, KT, ad, bd, e);
   }
   const int P = imgs * H * W;
   {
@@ -889,9 +898,7 @@ hipError_t conv_mfma_fprop(hipStream_t s, int imgs, int H, int W, int stride, in
     if (err != hipErrorNotSupported) return err;
   }
   GatherDesc ad{x, zeros, P, H, W, ilog2(W), cin, H, W};
-  if (cout % 128 == 0)
-    return launch_conv<128, 128, 3, RowGather<128, 4, false>, Plain<128, 4, false>>(s, P, cout, KT, 1, 1, ad, bd, e);
-  return launch_conv<128, 64, 4, RowGather<128, 4, false>, Plain<64, 4, false>>(s, P, cout, KT, 1, 1, ad, bd, e);
+  return launch_gather_rows<false, 1>(s, P, cout, KT, ad, bd, e);
 }
 
 hipError_t conv_mfma_dgrad(hipStream_t s, int imgs, int H, int W, int stride, int cin, int cout, const uint16_t* dz,
@@ -902,10 +909,7 @@ hipError_t conv_mfma_dgrad(hipStream_t s, int imgs, int H, int W, int stride, in
   EpiDgrad e{d_prev, out, cin};
   if (stride == 2) {  // rows: input pixels, source: dz on the (H/2) x (W/2) grid; taps of the wrong parity read zeros
     GatherDesc ad{dz, zeros, P, H, W, ilog2(W), cout, H / 2, W / 2};
-    const int KT = 9 * cout / DBK;
-    if (cin % 128 == 0)
-      return launch_conv<128, 128, 3, RowGather<128, 4, true, 2>, Plain<128, 4, true>>(s, P, cin, KT, 1, 1, ad, bd, e);
-    return launch_conv<128, 64, 4, RowGather<128, 4, true, 2>, Plain<64, 4, true>>(s, P, cin, KT, 1, 1, ad, bd, e);
+    return launch_gather_rows<true, 2>(s, P, cin, 9 * cout / DBK, ad, bd, e);
   }
   {
     const PatchDesc pd{dz, zeros, H, W, ilog2(W), cout, 0, cout / 8, 0};
@@ -913,10 +917,7 @@ hipError_t conv_mfma_dgrad(hipStream_t s, int imgs, int H, int W, int stride, in
     if (err != hipErrorNotSupported) return err;
   }
   GatherDesc ad{dz, zeros, P, H, W, ilog2(W), cout, H, W};
-  const int KT = 9 * cout / DBK;
-  if (cin % 128 == 0)
-    return launch_conv<128, 128, 3, RowGather<128, 4, true>, Plain<128, 4, true>>(s, P, cin, KT, 1, 1, ad, bd, e);
-  return launch_conv<128, 64, 4, RowGather<128, 4, true>, Plain<64, 4, true>>(s, P, cin, KT, 1, 1, ad, bd, e);
+  return launch_gather_rows<true, 1>(s, P, cin, 9 * cout / DBK, ad, bd, e);
 }
 
 hipError_t conv_mfma_wgrad(hipStream_t s, int imgs, int H, int W, int stride, int cin, int cout, const uint16_t* dz,
@@ -930,7 +931,7 @@ hipError_t conv_mfma_wgrad(hipStream_t s, int imgs, int H, int W, int stride, in
     GatherDesc bd{x, zeros, P, Ho, Wo, ilog2(Wo), cin, H, W};
     EpiWgradConv e{splits > 1 ? partial : gW, cin, cout};
     hipError_t err;
-    if (cout % 128 == 0 && cin % 128 == 0)
+    if (cout % 128 == 0 && cin % 128 == 0 && (long)(cout / 128) * (cin / 128) * 9 * splits >= 256)
       err = launch_conv<128, 128, 3, Plain<128, 4, true>, ColGather<128, 4, 2>>(s, cout, cin, KT, 9, splits, ad, bd, e);
     else
       err = launch_conv<64, 64, 4, Plain<64, 4, true>, ColGather<64, 4, 2>>(s, cout, cin, KT, 9, splits, ad, bd, e);
@@ -958,7 +959,7 @@ hipError_t conv_mfma_wgrad(hipStream_t s, int imgs, int H, int W, int stride, in
   GatherDesc bd{x, zeros, P, H, W, ilog2(W), cin, H, W};
   EpiWgradConv e{splits > 1 ? partial : gW, cin, cout};
   hipError_t err;
-  if (cout % 128 == 0 && cin % 128 == 0)
+  if (cout % 128 == 0 && cin % 128 == 0 && (long)(cout / 128) * (cin / 128) * 9 * splits >= 256)
     err = launch_conv<128, 128, 3, Plain<128, 4, true>, ColGather<128, 4>>(s, cout, cin, KT, 9, splits, ad, bd, e);
   else
     err = launch_conv<64, 64, 4, Plain<64, 4, true>, ColGather<64, 4>>(s, cout, cin, KT, 9, splits, ad, bd, e);

@@ -272,9 +272,13 @@ hipError_t launch_colsum(hipStream_t s, int elt, int M, int N, const void* dz, f
   return launch_sum_partials(s, (size_t)N, cs.chunks, partials, gb);
 }
 
-hipError_t launch_wgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* x, float* gW) {
+size_t wgrad_scratch_floats(int elt, int M, int N, int K) {
+  return elt == ELT_BF16 && mfma_wgrad_supported(M, N, K) ? mfma_wgrad_scratch_floats(M, N, K) : 0;
+}
+
+hipError_t launch_wgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* x, float* gW, float* partial) {
   if (elt == ELT_BF16 && mfma_wgrad_supported(M, N, K))
-    return mfma_wgrad(s, M, N, K, (const uint16_t*)dz, (const uint16_t*)x, gW);
+    return mfma_wgrad(s, M, N, K, (const uint16_t*)dz, (const uint16_t*)x, gW, partial);
   EpiArgs e{};
   e.c_f32 = gW;
   // gW[N x K] = dz^T[N x M] . x[M x K]: contraction over M

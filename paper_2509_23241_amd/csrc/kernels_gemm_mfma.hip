@@ -19,11 +19,14 @@
 // Workgroup ids are remapped so that the workgroups of one XCD (ids equal mod 8) cover a
 // compact 2-D patch of output tiles and share their operand panels in that XCD's L2.
 #include <hip/hip_runtime.h>
+
+#include <algorithm>
 #include <stdint.h>
 
 #include "device_utils.h"
 #include "gemm_mfma.h"
 #include "mfma_common.h"
+#include "kernels.h"
 
 namespace tp {
 
@@ -215,6 +218,17 @@ hipError_t launch(hipStream_t s, int M, int N, int K, const uint16_t* A, int lda
 }
 
 
+// output of contraction range `split`: only the fp32 weight-gradient product is ever split
+template <class E>
+__device__ __forceinline__ const E& epi_of_split(const E& e, int) { return e; }
+struct EpiWgradSplit {
+  float* out; int ldc; size_t split_stride;
+  static constexpr bool kSwap = false;
+};
+__device__ __forceinline__ EpiWgrad epi_of_split(const EpiWgradSplit& e, int split) {
+  return EpiWgrad{e.out + (size_t)split * e.split_stride, e.ldc};
+}
+
 template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, class Epi>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, int N, int K,
                                                                         const uint16_t* __restrict__ A, int lda,
@@ -237,6 +251,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, in
   map.get(blockIdx.x, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const uint32_t lds_base = lds_addr_of(lds_raw);
+  // blockIdx.y: range of the contraction this workgroup sums over (K is the length of one range); each range
+  // writes its own output (fp32 partial results that a second kernel adds in a fixed order)
+  const int split = blockIdx.y;
+  A += (size_t)split * K * (A_COL ? lda : 1);
+  B += (size_t)split * K * (B_COL ? ldb : 1);
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -330,7 +349,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, in
       return;
     }
   }
-  store_tiles<TM, TN>(acc, epi, m0 + wm, n0 + wn, M, N, lane);
+  store_tiles<TM, TN>(acc, epi_of_split(epi, split), m0 + wm, n0 + wn, M, N, lane);
 }
 
 // Shapes the direct-to-LDS kernel takes: whole 64-wide k tiles, 32-bit byte offsets inside each
@@ -345,7 +364,7 @@ inline bool dma_ok(int M, int N, int K, int lda, int ldb, bool a_col, bool b_col
 
 template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, class Epi>
 hipError_t launch_dma(hipStream_t s, int M, int N, int K, const uint16_t* A, int lda, const uint16_t* B, int ldb,
-                      const Epi& epi, SideCopy side = SideCopy{nullptr, nullptr, 0}) {
+                      const Epi& epi, SideCopy side = SideCopy{nullptr, nullptr, 0}, int splits = 1) {
   constexpr int NW = WGM * WGN;
   using AT = typename DmaSel<BM, NW, A_COL>::type;
   using BT = typename DmaSel<BN, NW, B_COL>::type;
@@ -362,8 +381,8 @@ hipError_t launch_dma(hipStream_t s, int M, int N, int K, const uint16_t* A, int
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const TileMap map = make_tile_map(tiles_m, tiles_n);
-  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n), dim3(64 * NW), lds_bytes, s, M, N, K, A, lda, B, ldb, epi, map,
-                     side);
+  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n, splits), dim3(64 * NW), lds_bytes, s, M, N, K / splits, A, lda, B, ldb,
+                     epi, map, side);
   return hipGetLastError();
 }
 
@@ -436,8 +455,32 @@ hipError_t mfma_dgrad(hipStream_t s, int M, int N, int K, const uint16_t* dz, co
   TP_GEMM_DISPATCH(pick(M, K, N, N, K, false, true, g_cfg[1]), false, true, s, M, K, N, dz, N, Wb, K, e)
 }
 
-hipError_t mfma_wgrad(hipStream_t s, int M, int N, int K, const uint16_t* dz, const uint16_t* x, float* gW) {
+// Ranges of the contraction (the rows of the mini-batch) a weight gradient is split into when its output has too
+// few tiles to fill the chip: whole 64-row k tiles, at least 8 per range, at most 8 ranges.
+int mfma_wgrad_splits(int M, int N, int K) {
+  if (!dma_ok(N, K, M, N, K, true, true)) return 1;
+  const int cfg = pick(N, K, M, N, K, true, true, g_cfg[2]);
+  if (cfg != 10) return 1;  // larger tiles are only chosen when they already give 256 workgroups
+  const long blocks = (long)((N + 63) / 64) * ((K + 63) / 64);
+  int s = (int)std::min<long>(8, 256 / std::max<long>(blocks, 1));
+  while (s > 1 && (M % (DBK * s) != 0 || M / (DBK * s) < 8)) --s;
+  return std::max(s, 1);
+}
+
+size_t mfma_wgrad_scratch_floats(int M, int N, int K) {
+  const int s = mfma_wgrad_splits(M, N, K);
+  return s > 1 ? (size_t)s * N * K : 0;
+}
+
+hipError_t mfma_wgrad(hipStream_t s, int M, int N, int K, const uint16_t* dz, const uint16_t* x, float* gW, float* partial) {
   // gW[N x K] = dz^T[N x M] . x[M x K]: GEMM (N, K, contraction M)
+  const int splits = partial ? mfma_wgrad_splits(M, N, K) : 1;
+  if (splits > 1) {
+    EpiWgradSplit e{partial, K, (size_t)N * K};
+    const hipError_t err = launch_dma<64, 64, 2, 2, 4, true, true>(s, N, K, M, dz, N, x, K, e, SideCopy{nullptr, nullptr, 0}, splits);
+    if (err != hipSuccess) return err;
+    return launch_sum_partials(s, (size_t)N * K, splits, partial, gW);
+  }
   EpiWgrad e{gW, K};
   TP_GEMM_DISPATCH(pick(N, K, M, N, K, true, true, g_cfg[2]), true, true, s, N, K, M, dz, N, x, K, e)
 }

@@ -303,6 +303,8 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
     if (lp.d.type == TP_LAYER_LAYERNORM || lp.d.type == TP_LAYER_BATCHNORM) continue;
     const uint64_t r = lp.d.type == TP_LAYER_CONV2D ? rows * conv_out_px(lp.d) : rows * lp.tokens;
     wg = std::max<uint64_t>(wg, tp::colsum_scratch_floats((int)r, lp.d.out_features));
+    if (lp.d.type == TP_LAYER_DENSE)
+      wg = std::max<uint64_t>(wg, tp::wgrad_scratch_floats(d->dtype, (int)r, lp.d.out_features, lp.d.in_features));
   }
   p->partial_floats = round_up(std::max<uint64_t>({wg, tp::update_scratch_floats(), rows, conv_scratch, norm_scratch}), 64);
   tp_sizes& s = p->sizes;
@@ -862,19 +864,19 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
         const size_t seg_bytes = seg_rows * C * es;
         const size_t bn_scratch = tp::batchnorm_scratch_floats(seg_rows, C);
         float* sums = st->partials() + bn_scratch;                // [n][2*C]
-        if (tp::batchnorm_fused_bwd_supported(d.dtype, seg_rows, C)) {
+        {
           ProfScope ps(st, TP_K_NORM);
-          HIP_TRY(tp::launch_batchnorm_bwd_fused(st->stream, d.dtype, seg_rows, C, d.n, dz, aslot + lp.x_off,
-                                                 (const float*)(aslot + lp.stat_off), gs, gl, (float)ca, (float)cb, dst,
-                                                 g + lp.w_off, g + lp.b_off));
-        } else {
-          ProfScope ps(st, TP_K_NORM);
-          for (int ub = 0; ub < d.n; ++ub)
-            HIP_TRY(tp::launch_batchnorm_bwd(st->stream, d.dtype, seg_rows, C, (const char*)dz + ub * seg_bytes,
-                                             aslot + lp.x_off + ub * seg_bytes,
-                                             (const float*)(aslot + lp.stat_off) + (size_t)ub * 2 * C, gs, gl, (float)ca,
-                                             (float)cb, (char*)dst + ub * seg_bytes, sums + (size_t)ub * 2 * C,
-                                             st->partials()));
+          if (tp::batchnorm_fused_bwd_supported(d.dtype, seg_rows, C)) {
+            HIP_TRY(tp::launch_batchnorm_bwd_fused(st->stream, d.dtype, seg_rows, C, d.n, dz, aslot + lp.x_off,
+                                                   (const float*)(aslot + lp.stat_off), gs, gl, (float)ca, (float)cb, dst, sums));
+          } else {
+            for (int ub = 0; ub < d.n; ++ub)
+              HIP_TRY(tp::launch_batchnorm_bwd(st->stream, d.dtype, seg_rows, C, (const char*)dz + ub * seg_bytes,
+                                               aslot + lp.x_off + ub * seg_bytes,
+                                               (const float*)(aslot + lp.stat_off) + (size_t)ub * 2 * C, gs, gl, (float)ca,
+                                               (float)cb, (char*)dst + ub * seg_bytes, sums + (size_t)ub * 2 * C,
+                                               st->partials()));
+          }
           HIP_TRY(tp::launch_sum_partials_strided(st->stream, (size_t)C, d.n, sums, 2 * (size_t)C, g + lp.w_off));
           HIP_TRY(tp::launch_sum_partials_strided(st->stream, (size_t)C, d.n, sums + C, 2 * (size_t)C, g + lp.b_off));
         }
@@ -905,7 +907,7 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
         ProfScope ps(st, TP_K_WGRAD);
         if (lp.d.type == TP_LAYER_DENSE)
           HIP_TRY(tp::launch_wgrad(st->stream, d.dtype, grad_rows, lp.d.out_features, lp.d.in_features, dz, aslot + lp.x_off,
-                                   g + lp.w_off));
+                                   g + lp.w_off, st->partials()));
         else if (lp.xpad_off != UINT64_MAX)
           HIP_TRY(tp::conv_c8_wgrad(st->stream, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, lp.d.out_features,
                                     (const uint16_t*)dz, (const uint16_t*)(aslot + lp.xpad_off), g + lp.w_off, st->partials(),

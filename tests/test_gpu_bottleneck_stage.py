@@ -73,3 +73,10 @@ def test_batchnorm_row_counts_across_kernel_families_bf16(mb, positions):
     specs = (W.Dense(8, 16, "none", tokens=positions), W.BatchNorm(16, positions, "gelu"),
              W.Dense(16, 8, "none", tokens=positions), W.BatchNorm(8, positions, "none"))
     print(mb * positions, _run_stage(specs, f"bn_rows_{mb * positions}", "bf16", mb=mb, n=3))
+
+
+def test_dense_weight_gradient_split_over_rows_bf16():
+    # 2048 rows (64 x 2 samples x 16 positions) against weight matrices of 128 x 256 and 64 x 128: too few output
+    # tiles to fill the chip, so the gradient is formed over several row ranges and summed in a fixed order
+    specs = (W.Dense(256, 128, "gelu", tokens=16), W.Dense(128, 64, "none", tokens=16))
+    print(_run_stage(specs, "wgrad_split", "bf16", mb=64, n=2))
