@@ -869,13 +869,13 @@ int conv_mfma_wgrad_splits(int pixels, int cin, int cout) {
   return s;
 }
 
-// Gathered fprop / dgrad: the largest tile that still gives half the CUs a workgroup, else the smallest.
+// Gathered fprop / dgrad: the largest tile that still gives every CU a workgroup, else the smallest.
 template <bool BWD, int S, class Epi>
 hipError_t launch_gather_rows(hipStream_t s, int P, int N, int KT, const GatherDesc& ad, const PlainDesc& bd, const Epi& e) {
   const long rows128 = (P + 127) / 128;
-  if (N % 128 == 0 && rows128 * (N / 128) >= 128)
+  if (N % 128 == 0 && rows128 * (N / 128) >= 256)
     return launch_conv<128, 128, 3, RowGather<128, 4, BWD, S>, Plain<128, 4, BWD>>(s, P, N, KT, 1, 1, ad, bd, e);
-  if (rows128 * ((N + 63) / 64) >= 128)
+  if (rows128 * ((N + 63) / 64) >= 256)
     return launch_conv<128, 64, 4, RowGather<128, 4, BWD, S>, Plain<64, 4, BWD>>(s, P, N, KT, 1, 1, ad, bd, e);
   return launch_conv<64, 64, 4, RowGather<64, 4, BWD, S>, Plain<64, 4, BWD>>(s, P, N, KT, 1, 1, ad, bd, e);
 }
