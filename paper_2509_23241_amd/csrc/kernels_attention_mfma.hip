@@ -4,7 +4,8 @@
 //   skip    output tiles that lie entirely above the diagonal are not computed (Q K^T, dO V^T);
 //   limit   the contraction over keys stops at the last query row of the tile (P V, dS K);
 //   start   the contraction over queries starts at the first key row of the tile (P^T dO, dS^T Q).
-// forward   S = Q K^T (fp32)  ->  P = softmax(scale S) (bf16, zeros above the diagonal), lse  ->  O = P V
+// forward   head widths 64 and 128: one fused kernel (online softmax, no score matrix in memory), see below;
+//           otherwise S = Q K^T (fp32)  ->  P = softmax(scale S) (bf16, zeros above the diagonal), lse  ->  O = P V
 // backward  S = Q K^T, dP = dO V^T (fp32)  ->  P, dS = scale P (dP - rowsum(P dP)) (bf16)
 //           ->  dQ = dS K, dK = dS^T Q, dV = P^T dO
 // The score matrices are transient: a call works through the sequences in chunks that fit the
@@ -218,6 +219,204 @@ __global__ __launch_bounds__(256) void attn_softmax_bwd_kernel(int S, size_t row
   }
 }
 
+// ---- fused forward --------------------------------------------------------------------------------
+// One workgroup = 256 queries of one (sequence, head): 8 waves x 32 queries.  It walks over the keys
+// in blocks of 64; K [64 keys][dh] and V [64 keys][dh] of a block are copied global -> LDS (three
+// stages in flight) and shared by the eight waves.  Per wave and block:
+//   S^T = K Q^T     the transposed score tile: MFMA rows = keys, columns = the wave's queries.  Every
+//                   lane then holds ONE query (lane % 32) and 16 of the 32 keys of a tile, so the
+//                   running maximum / sum of the online softmax are per-lane scalars and one exchange
+//                   with lane ^ 32 per block completes them.  Q fragments stay in registers.
+//   O^T += V^T P^T  P = exp(S - max) never leaves the registers: accumulator element r of a lane is
+//                   key 8*(r/4) + 4*(lane/32) + r%4, so packing elements 8g..8g+7 to bf16 gives the B
+//                   fragment of a 16-key MFMA step in which lanes 0-31 carry keys {0-3, 8-11} and lanes
+//                   32-63 keys {4-7, 12-15}; the V fragment is read from LDS (transposing reads) with
+//                   its keys in the same order.
+// Key blocks above the diagonal are skipped per wave; the diagonal ones are masked.  The output tile is
+// divided by the row sums and turned through LDS for 16-byte row stores; lse = max + log(sum) (natural
+// logarithm of the scaled scores) is what the backward pass recomputes the probabilities from.
+// No score matrix reaches memory.
+constexpr int kFlashWaves = 8, kFlashStages = 3, kFlashQ = 32 * kFlashWaves;
+
+template <int DH>
+__device__ __forceinline__ bf16x8 flash_v_frag(const uint16_t* lds, int dbase, int g16, int lane) {
+  using VT = ColDma<DH, kFlashWaves>;
+  const int g = lane >> 4, s = lane & 15;
+  const int k = g16 * 16 + 4 * (g >> 1) + (s >> 2);       // keys {0-3} / {4-7} of the group, +8 below
+  const int col = dbase + 16 * (g & 1) + 4 * (s & 3);
+  const int slot = (col >> 3) ^ VT::swz(k);
+  typedef __attribute__((address_space(3))) shortx4* lds_ptr;
+  const uint16_t* p = lds + k * DH + slot * 8 + (col & 7);
+  const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+  const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 8 * DH));  // k+8: same swizzle
+  const shortx8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+template <int DH>
+__global__ __launch_bounds__(64 * kFlashWaves) void attn_flash_fwd_kernel(int S, int heads, const uint16_t* __restrict__ qkv,
+                                                                          uint16_t* __restrict__ out, float* __restrict__ lse,
+                                                                          float scale_log2) {
+  constexpr int NW = kFlashWaves, NS = kFlashStages;
+  constexpr int HALVES = DH / 64, TN = DH / 32;
+  using KT = RowDma<64, NW>;   // 64 keys x one 64-wide chunk of the head dimension
+  using VT = ColDma<DH, NW>;   // [64 keys][DH]
+  constexpr int kKBytes = HALVES * KT::kBytes;
+  constexpr int kStageBytes = kKBytes + VT::kBytes;
+  constexpr int kLoads = HALVES * KT::kPerWave + VT::kPerWave;
+  static_assert((NS - 2) * kLoads < 64, "too many copies in flight for vmcnt");
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds_raw[];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int half = lane >> 5;
+  const int zb = blockIdx.y / heads, zh = blockIdx.y - zb * heads;
+  const int D = heads * DH, ld = 3 * D;
+  const int q0 = (gridDim.x - 1 - blockIdx.x) * kFlashQ;  // the longest rows of the triangle start first
+  const int qw = q0 + wave * 32;                           // first query of this wave
+  const bool active = qw < S;                              // S is a multiple of 64: a wave is whole or absent
+  const uint16_t* qbase = qkv + (size_t)zb * S * ld + zh * DH;
+  const uint16_t* kbase = qbase + D;
+  const uint16_t* vbase = qbase + 2 * D;
+  const uint32_t lds_base = lds_addr_of(lds_raw);
+
+  // Q fragments (B operand: column = query lane % 32, 8 consecutive head-dimension values)
+  bf16x8 qf[DH / 16];
+  {
+    const uint16_t* qrow = qbase + (size_t)(active ? qw + (lane & 31) : 0) * ld + 8 * half;
+#pragma unroll
+    for (int kk = 0; kk < DH / 16; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qrow + kk * 16));
+  }
+  wait_vmcnt<0>();  // nothing but the copies below is in flight from here on
+#pragma unroll
+  for (int kk = 0; kk < DH / 16; ++kk) asm volatile("" : "+v"(qf[kk]));  // the compiler's own wait for these loads lands here
+
+  KT kt;
+  VT vt;
+  kt.init(ld, 0, 64, wave, lane);
+  vt.init(ld, 0, DH, wave, lane);
+  const int nkb = min(S, q0 + kFlashQ) / 64;  // key blocks any query of the workgroup can see
+  auto issue_block = [&](int blk, int st) {
+    const int kb = min(blk, nkb - 1);  // blocks past the end re-read the last one into a stage nobody reads again
+    const uint32_t dst = lds_base + st * kStageBytes;
+    const uint16_t* ksrc = kbase + (size_t)kb * 64 * ld;
+    const uint16_t* vsrc = vbase + (size_t)kb * 64 * ld;
+#pragma unroll
+    for (int c = 0; c < HALVES; ++c)
+#pragma unroll
+      for (int t = 0; t < KT::kPerWave; ++t) kt.issue_one(t, dst + c * KT::kBytes, ksrc + c * 64, wave);
+#pragma unroll
+    for (int t = 0; t < VT::kPerWave; ++t) vt.issue_one(t, dst + kKBytes, vsrc, wave);
+  };
+#pragma unroll
+  for (int st = 0; st < NS - 1; ++st) issue_block(st, st);
+
+  floatx16 oacc[1][TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[0][j][r] = 0.f;
+  float mrun = -INFINITY, lsum = 0.f;  // running maximum (log2 domain) and this lane's share of the row sum
+  const int query = qw + (lane & 31);
+
+  int rd = 0, wr = NS - 1;
+  for (int kb = 0; kb < nkb; ++kb) {
+    wait_vmcnt<(NS - 2) * kLoads>();
+    lds_barrier();  // block kb visible to all waves; everybody is done reading stage `wr`
+    issue_block(kb + NS - 1, wr);
+    if (active && kb * 64 <= qw + 31) {  // wave-uniform: some key of the block is visible to some query of the wave
+      const uint16_t* lk = lds_raw + rd * (kStageBytes / 2);
+      const uint16_t* lv = lk + kKBytes / 2;
+      floatx16 sacc[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[j][r] = 0.f;
+#pragma unroll
+        for (int c = 0; c < HALVES; ++c)
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk)
+            sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(KT::frag(lk + c * (KT::kBytes / 2), 32 * j, kk, lane),
+                                                              qf[c * 4 + kk], sacc[j], 0, 0, 0);
+      }
+      const bool diagonal = kb * 64 + 63 > qw;  // some (query, key) pair of this wave and block is masked
+      float mloc = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float v = sacc[j][r] * scale_log2;
+          if (diagonal) {
+            const int key = kb * 64 + 32 * j + 8 * (r >> 2) + 4 * half + (r & 3);
+            if (key > query) v = -INFINITY;
+          }
+          sacc[j][r] = v;
+          mloc = fmaxf(mloc, v);
+        }
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+      const float mnew = fmaxf(mrun, mloc);  // finite: block 0 shows key 0 to every query
+      const float alpha = __builtin_amdgcn_exp2f(mrun - mnew);
+      mrun = mnew;
+      float psum = 0.f;
+      bf16x8 pf[4];
+#pragma unroll
+      for (int g16 = 0; g16 < 4; ++g16) {
+        float e[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          e[t] = __builtin_amdgcn_exp2f(sacc[g16 >> 1][8 * (g16 & 1) + t] - mnew);
+          psum += e[t];
+        }
+        const uint4 u = make_uint4(pack_bf16x2(e[0], e[1]), pack_bf16x2(e[2], e[3]), pack_bf16x2(e[4], e[5]), pack_bf16x2(e[6], e[7]));
+        pf[g16] = __builtin_bit_cast(bf16x8, u);
+      }
+      lsum = fmaf(lsum, alpha, psum);
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {  // some row's maximum moved: rescale what is accumulated
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[0][j][r] *= alpha;
+      }
+#pragma unroll
+      for (int g16 = 0; g16 < 4; ++g16)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          oacc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(flash_v_frag<DH>(lv, 32 * j, g16, lane), pf[g16], oacc[0][j], 0, 0, 0);
+    }
+    rd = rd + 1 == NS ? 0 : rd + 1;
+    wr = wr + 1 == NS ? 0 : wr + 1;
+  }
+  wait_vmcnt<0>();  // the trailing dummy copies must have landed before LDS is reused
+  lds_barrier();
+  if (!active) return;
+  const float ltot = lsum + __shfl_xor(lsum, 32, 64);
+  const float inv = 1.f / ltot;
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[0][j][r] *= inv;
+  if (half == 0) lse[(size_t)blockIdx.y * S + query] = (mrun + __builtin_amdgcn_logf(ltot)) * 0.6931471805599453f;
+  float* wave_lds = reinterpret_cast<float*>(lds_raw) + wave * (wave_epilogue_bytes<1, TN>() / 4);
+  store_tiles_coalesced<1, TN>(oacc, EpiDgrad{nullptr, out, D}, zb * S + qw, zh * DH, lane, wave_lds);
+}
+
+template <int DH>
+hipError_t launch_flash_fwd(hipStream_t s, int seqs, int S, int heads, const uint16_t* qkv, uint16_t* out, float* lse) {
+  constexpr size_t stage_bytes = (size_t)kFlashStages * ((DH / 64) * RowDma<64, kFlashWaves>::kBytes + ColDma<DH, kFlashWaves>::kBytes);
+  constexpr size_t epi_bytes = (size_t)kFlashWaves * wave_epilogue_bytes<1, DH / 32>();
+  constexpr size_t lds_bytes = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
+  static_assert(lds_bytes <= 160 * 1024, "stages do not fit the LDS of a CU");
+  auto kernel = attn_flash_fwd_kernel<DH>;
+  static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (attr != hipSuccess) return attr;
+  // scores are scaled by 1/sqrt(dh) and exponentiated in base 2
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
+  hipLaunchKernelGGL(kernel, dim3((S + kFlashQ - 1) / kFlashQ, seqs * heads), dim3(64 * kFlashWaves), lds_bytes, s, S, heads, qkv,
+                     out, lse, scale_log2);
+  return hipGetLastError();
+}
+
 // bytes of scratch per sequence: scores and dP in fp32, P and dS in bf16
 inline size_t per_seq_bytes(int S, int heads) { return (size_t)heads * S * S * 12; }
 
@@ -233,6 +432,16 @@ size_t attention_mfma_scratch_bytes(int seqs, int S, int heads) {
   const size_t per = per_seq_bytes(S, heads);
   const size_t chunk = std::max<size_t>(1, std::min<size_t>(seqs, (2ull << 30) / per));
   return chunk * per;
+}
+
+bool attention_flash_fwd_supported(int seqs, int S, int heads, int dh) {
+  return (dh == 64 || dh == 128) && S >= 64 && S % 64 == 0 && heads >= 1 && seqs >= 1 && (long)seqs * heads <= 65535 &&
+         64ull * 3 * heads * dh * 2 < (1ull << 31);  // 32-bit byte offsets inside one 64-key block
+}
+
+hipError_t attention_flash_fwd(hipStream_t s, int seqs, int S, int heads, int dh, const uint16_t* qkv, uint16_t* out, float* lse) {
+  if (!attention_flash_fwd_supported(seqs, S, heads, dh)) return hipErrorNotSupported;
+  return dh == 64 ? launch_flash_fwd<64>(s, seqs, S, heads, qkv, out, lse) : launch_flash_fwd<128>(s, seqs, S, heads, qkv, out, lse);
 }
 
 hipError_t attention_mfma_fwd(hipStream_t s, int seqs, int S, int heads, int dh, const uint16_t* qkv, uint16_t* out, float* lse,

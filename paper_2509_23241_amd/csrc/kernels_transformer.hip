@@ -600,6 +600,8 @@ size_t attention_scratch_bytes(int elt, int seqs, int S, int heads, int dh) {
 hipError_t launch_attention_fwd(hipStream_t s, int elt, int seqs, int S, int heads, int dh, const void* qkv, void* out,
                                 float* lse, void* scratch, size_t scratch_bytes) {
   if (!attention_supported(S, heads, dh) || seqs > 65535) return hipErrorInvalidValue;
+  if (elt == ELT_BF16 && attention_flash_fwd_supported(seqs, S, heads, dh))
+    return attention_flash_fwd(s, seqs, S, heads, dh, (const uint16_t*)qkv, (uint16_t*)out, lse);
   if (elt == ELT_BF16 && scratch && attention_mfma_supported(S, heads, dh) &&
       scratch_bytes >= attention_mfma_scratch_bytes(1, S, heads))
     return attention_mfma_fwd(s, seqs, S, heads, dh, (const uint16_t*)qkv, (uint16_t*)out, lse, scratch, scratch_bytes);

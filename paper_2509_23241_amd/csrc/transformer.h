@@ -38,6 +38,9 @@ bool attention_supported(int S, int heads, int dh);
 // Matrix-core attention (bf16; kernels_attention_mfma.hip): same arguments and results as the two
 // launchers above, plus scratch for the transient score matrices (attention_mfma_scratch_bytes for the
 // largest number of sequences a call will see; a smaller scratch makes the call work in smaller chunks).
+// Fused forward (head widths 64 and 128, tokens a multiple of 64): online softmax, no score matrix in memory, no scratch.
+bool attention_flash_fwd_supported(int seqs, int S, int heads, int dh);
+hipError_t attention_flash_fwd(hipStream_t s, int seqs, int S, int heads, int dh, const uint16_t* qkv, uint16_t* out, float* lse);
 bool attention_mfma_supported(int S, int heads, int dh);
 size_t attention_mfma_scratch_bytes(int seqs, int S, int heads);
 hipError_t attention_mfma_fwd(hipStream_t s, int seqs, int S, int heads, int dh, const uint16_t* qkv, uint16_t* out, float* lse,

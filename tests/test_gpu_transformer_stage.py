@@ -67,3 +67,13 @@ def test_transformer_stage_reduced_bf16():
     # 4 heads of 64, FFN 1024, 128 tokens, micro-batch 2 x 2, depth 3 (staleness 0, 1, 2)
     w = W.transformer_stage(d=256, heads=4, ffn=1024, tokens=128, layers=4, mb=2, n=2)
     print(_run_stage(w.stages[1], "tfm_reduced", "bf16", mb=2, n=2, depth=3, minibatches=3))
+
+
+@pytest.mark.parametrize("tokens,heads,dh", [(64, 2, 64), (192, 1, 128), (320, 2, 64), (512, 1, 128)])
+def test_fused_attention_forward_bf16(tokens, heads, dh):
+    # the fused forward kernel: one 64-key block (two of eight waves at work), a partly filled workgroup, two
+    # workgroups per head with different numbers of key blocks (320 = 256 + 64 queries), several diagonal blocks;
+    # head widths 64 and 128.  The projections around it make the inputs and the upstream gradient ordinary.
+    d = heads * dh
+    specs = (W.Dense(32, 3 * d, "none", tokens=tokens), W.Attention(d, heads, tokens), W.Dense(d, 32, "none", tokens=tokens))
+    print(tokens, heads, dh, _run_stage(specs, f"attn_flash_{tokens}_{heads}_{dh}", "bf16", mb=2, n=2))
