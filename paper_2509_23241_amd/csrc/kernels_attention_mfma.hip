@@ -240,7 +240,7 @@ constexpr int kFlashWaves = 8, kFlashStages = 3, kFlashQ = 32 * kFlashWaves;
 
 template <int DH>
 __device__ __forceinline__ bf16x8 flash_v_frag(const uint16_t* lds, int dbase, int g16, int lane) {
-  using VT = ColDma<DH, kFlashWaves>;
+  using VT = ColDma<DH, kFlashWaves>;  // only its chunk swizzle is used, which does not depend on the wave count
   const int g = lane >> 4, s = lane & 15;
   const int k = g16 * 16 + 4 * (g >> 1) + (s >> 2);       // keys {0-3} / {4-7} of the group, +8 below
   const int col = dbase + 16 * (g & 1) + 4 * (s & 3);
@@ -417,6 +417,242 @@ hipError_t launch_flash_fwd(hipStream_t s, int seqs, int S, int heads, const uin
   return hipGetLastError();
 }
 
+// ---- fused backward -------------------------------------------------------------------------------
+// Two launches of one kernel template, both in the register layout of the fused forward:
+//   dQ      a workgroup owns 128 queries (4 waves x 32) and walks over the key blocks up to its diagonal:
+//           S^T = K Q^T and dP^T = V dO^T with Q, dO fragments in registers, K and V streamed through LDS;
+//           lse and delta = dO . O are per-lane scalars; dQ^T += K^T dS^T.
+//   dK, dV  a workgroup owns 128 keys and walks over the query blocks from its diagonal to the end:
+//           S = Q K^T and dP = dO V^T with K, V fragments in registers, Q and dO streamed; lse, delta of the 64
+//           streamed queries come through LDS with the block; dV^T += dO^T P, dK^T += Q^T dS.
+// P = exp(scale S - lse) and dS = scale P (dP - delta) are formed in registers and packed to bf16 as the B
+// fragments of the second products, exactly like P in the forward kernel; the streamed operand is staged twice,
+// once in the row layout the first products read and once in the layout the transposing reads of the second
+// products want.  The scores are recomputed in both launches (7 matrix products instead of 5), no score-sized
+// tensor reaches memory, nothing is accumulated with atomics: every output element has one owner.
+constexpr int kBwdWaves = 4, kBwdOwn = 32 * kBwdWaves;
+constexpr float kLog2e = 1.4426950408889634f;
+
+// stat[(z*S + i)*2] = lse_i * log2(e), stat[(z*S + i)*2 + 1] = delta_i = sum_d dO[i][d] * O[i][d];  z = sequence*heads + head.
+// One wave per token row; a lane takes 8 consecutive columns per step, the dh/8 lanes of a head are added.
+__global__ __launch_bounds__(256) void attn_stat_kernel(int S, int heads, int dh, size_t rows, const uint16_t* __restrict__ dout,
+                                                        const uint16_t* __restrict__ out, const float* __restrict__ lse,
+                                                        float* __restrict__ stat) {
+  const int lane = threadIdx.x & 63;
+  const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int D = heads * dh, group = dh / 8;
+  const size_t b = row / S, i = row - b * S;
+  for (int c0 = 0; c0 < D; c0 += 512) {
+    const int col = c0 + lane * 8;
+    float acc = 0.f;
+    if (col < D) {
+      const uint4 a = *reinterpret_cast<const uint4*>(dout + row * D + col), o = *reinterpret_cast<const uint4*>(out + row * D + col);
+      const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, ow[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc += __uint_as_float(aw[j] << 16) * __uint_as_float(ow[j] << 16) +
+               __uint_as_float(aw[j] & 0xffff0000u) * __uint_as_float(ow[j] & 0xffff0000u);
+    }
+    for (int off = 1; off < group; off <<= 1) acc += __shfl_xor(acc, off, 64);
+    if (col < D && (lane % group) == 0) {
+      const size_t zi = (b * heads + col / dh) * S + i;
+      stat[zi * 2] = lse[zi] * kLog2e;
+      stat[zi * 2 + 1] = acc;
+    }
+  }
+}
+
+template <int DH, bool OWN_KEYS>
+__global__ __launch_bounds__(64 * kBwdWaves) void attn_flash_bwd_kernel(int S, int heads, const uint16_t* __restrict__ qkv,
+                                                                        const uint16_t* __restrict__ dout,
+                                                                        const float* __restrict__ stat, uint16_t* __restrict__ dqkv,
+                                                                        float scale, float scale_log2) {
+  constexpr int NW = kBwdWaves;
+  constexpr int HALVES = DH / 64, TN = DH / 32;
+  using RT = RowDma<64, NW>;   // 64 streamed rows x one 64-wide chunk of the head dimension
+  using CT = ColDma<DH, NW>;   // [64 streamed rows][DH], read transposed
+  constexpr int kRowBytes = HALVES * RT::kBytes;
+  constexpr int kStatBytes = OWN_KEYS ? 1024 : 0;
+  constexpr int kCols = OWN_KEYS ? 2 : 1;
+  constexpr int kStageBytes = 2 * kRowBytes + kCols * CT::kBytes + kStatBytes;
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds_raw[];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int half = lane >> 5;
+  const int z = blockIdx.y, zb = z / heads, zh = z - zb * heads;
+  const int D = heads * DH, ld3 = 3 * D;
+  const uint16_t* qp = qkv + (size_t)zb * S * ld3 + zh * DH;
+  const uint16_t* dop = dout + (size_t)zb * S * D + zh * DH;
+  // own rows (fragments in registers) and streamed rows (through LDS)
+  const uint16_t* own1 = OWN_KEYS ? qp + D : qp;          // K | Q
+  const uint16_t* own2 = OWN_KEYS ? qp + 2 * D : dop;     // V | dO
+  const int ld_own2 = OWN_KEYS ? ld3 : D;
+  const uint16_t* str1 = OWN_KEYS ? qp : qp + D;          // Q | K
+  const uint16_t* str2 = OWN_KEYS ? dop : qp + 2 * D;     // dO | V
+  const int ld_str2 = OWN_KEYS ? D : ld3;
+  // the workgroups with the most blocks to walk start first: low keys, high queries
+  const int o0 = (OWN_KEYS ? (int)blockIdx.x : (int)(gridDim.x - 1 - blockIdx.x)) * kBwdOwn;
+  const int ow = o0 + wave * 32;
+  const bool active = ow < S;
+  const int oi = ow + (lane & 31);  // this lane's own row
+  const uint32_t lds_base = lds_addr_of(lds_raw);
+
+  bf16x8 f1[DH / 16], f2[DH / 16];
+  float own_l2 = 0.f, own_delta = 0.f;
+  {
+    const size_t r = active ? oi : 0;
+    const uint16_t* p1 = own1 + r * ld3 + 8 * half;
+    const uint16_t* p2 = own2 + r * ld_own2 + 8 * half;
+#pragma unroll
+    for (int kk = 0; kk < DH / 16; ++kk) {
+      f1[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p1 + kk * 16));
+      f2[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p2 + kk * 16));
+    }
+    if (!OWN_KEYS) {
+      const float2 st = *reinterpret_cast<const float2*>(stat + ((size_t)z * S + r) * 2);
+      own_l2 = st.x;
+      own_delta = st.y;
+    }
+  }
+  wait_vmcnt<0>();  // nothing but the copies below is in flight from here on
+#pragma unroll
+  for (int kk = 0; kk < DH / 16; ++kk) asm volatile("" : "+v"(f1[kk]), "+v"(f2[kk]));
+  asm volatile("" : "+v"(own_l2), "+v"(own_delta));
+
+  RT rt1, rt2;
+  CT ct1, ct2;
+  rt1.init(ld3, 0, 64, wave, lane);
+  rt2.init(ld_str2, 0, 64, wave, lane);
+  ct1.init(ld3, 0, DH, wave, lane);
+  ct2.init(ld_str2, 0, DH, wave, lane);
+  // streamed blocks of 64 rows: keys 0 .. diagonal of the workgroup | queries diagonal .. end
+  const int sb_begin = OWN_KEYS ? o0 / 64 : 0;
+  const int sb_end = OWN_KEYS ? S / 64 : min(S, o0 + kBwdOwn) / 64;
+  auto issue_block = [&](int blk, int st) {
+    const int sb = min(blk, sb_end - 1);  // past the end: re-read the last block into a stage nobody reads again
+    const uint32_t dst = lds_base + st * kStageBytes;
+    const uint16_t* s1 = str1 + (size_t)sb * 64 * ld3;
+    const uint16_t* s2 = str2 + (size_t)sb * 64 * ld_str2;
+#pragma unroll
+    for (int c = 0; c < HALVES; ++c)
+#pragma unroll
+      for (int t = 0; t < RT::kPerWave; ++t) {
+        rt1.issue_one(t, dst + c * RT::kBytes, s1 + c * 64, wave);
+        rt2.issue_one(t, dst + kRowBytes + c * RT::kBytes, s2 + c * 64, wave);
+      }
+#pragma unroll
+    for (int t = 0; t < CT::kPerWave; ++t) {
+      ct1.issue_one(t, dst + 2 * kRowBytes, s1, wave);
+      if (OWN_KEYS) ct2.issue_one(t, dst + 2 * kRowBytes + CT::kBytes, s2, wave);
+    }
+    // (lse*log2e, delta) of the 64 streamed queries: 512 bytes, lanes 32-63 repeat lanes 0-31 into the spare half
+    if (OWN_KEYS) dma16(dst + 2 * kRowBytes + 2 * CT::kBytes, stat + ((size_t)z * S + (size_t)sb * 64) * 2, (uint32_t)(lane & 31) * 16);
+  };
+  issue_block(sb_begin, 0);
+
+  floatx16 acc1[1][TN], acc2[1][TN];  // dQ | dK, and dV
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc1[0][j][r] = acc2[0][j][r] = 0.f;
+
+  int st = 0;
+  for (int sb = sb_begin; sb < sb_end; ++sb) {
+    wait_vmcnt<0>();
+    lds_barrier();  // block sb visible to all waves; everybody is done reading the other stage
+    issue_block(sb + 1, st ^ 1);
+    // wave-uniform: does any (query, key <= query) pair of this wave fall into the block?
+    const bool some = OWN_KEYS ? sb * 64 + 63 >= ow : sb * 64 <= ow + 31;
+    if (active && some) {
+      const uint16_t* lr1 = lds_raw + st * (kStageBytes / 2);
+      const uint16_t* lr2 = lr1 + kRowBytes / 2;
+      const uint16_t* lc1 = lr2 + kRowBytes / 2;
+      const uint16_t* lc2 = lc1 + CT::kBytes / 2;
+      const float* lstat = reinterpret_cast<const float*>(lc1 + kCols * (CT::kBytes / 2));
+      floatx16 sacc[2], pacc[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[j][r] = pacc[j][r] = 0.f;
+#pragma unroll
+        for (int c = 0; c < HALVES; ++c)
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) {
+            sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(RT::frag(lr1 + c * (RT::kBytes / 2), 32 * j, kk, lane),
+                                                              f1[c * 4 + kk], sacc[j], 0, 0, 0);
+            pacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(RT::frag(lr2 + c * (RT::kBytes / 2), 32 * j, kk, lane),
+                                                              f2[c * 4 + kk], pacc[j], 0, 0, 0);
+          }
+      }
+      // some pair of this wave and block lies above the diagonal
+      const bool diagonal = OWN_KEYS ? sb * 64 < ow + 31 : sb * 64 + 63 > ow;
+      bf16x8 pf[4], dsf[4];
+#pragma unroll
+      for (int g16 = 0; g16 < 4; ++g16) {
+        const int j = g16 >> 1;
+        float pe[8], de[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          const int r = 8 * (g16 & 1) + t;
+          const int srow = 32 * j + 8 * (r >> 2) + 4 * half + (r & 3);  // streamed row inside the block
+          float l2 = own_l2, dl = own_delta;
+          if (OWN_KEYS) {
+            l2 = lstat[2 * srow];
+            dl = lstat[2 * srow + 1];
+          }
+          float p = __builtin_amdgcn_exp2f(sacc[j][r] * scale_log2 - l2);
+          if (diagonal) {
+            const int si = sb * 64 + srow;
+            const int key = OWN_KEYS ? oi : si, query = OWN_KEYS ? si : oi;
+            if (key > query) p = 0.f;
+          }
+          pe[t] = p;
+          de[t] = p * (pacc[j][r] - dl) * scale;
+        }
+        pf[g16] = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16x2(pe[0], pe[1]), pack_bf16x2(pe[2], pe[3]),
+                                                         pack_bf16x2(pe[4], pe[5]), pack_bf16x2(pe[6], pe[7])));
+        dsf[g16] = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16x2(de[0], de[1]), pack_bf16x2(de[2], de[3]),
+                                                          pack_bf16x2(de[4], de[5]), pack_bf16x2(de[6], de[7])));
+      }
+#pragma unroll
+      for (int g16 = 0; g16 < 4; ++g16)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          acc1[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(flash_v_frag<DH>(lc1, 32 * j, g16, lane), dsf[g16], acc1[0][j], 0, 0, 0);
+          if (OWN_KEYS)
+            acc2[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(flash_v_frag<DH>(lc2, 32 * j, g16, lane), pf[g16], acc2[0][j], 0, 0, 0);
+        }
+    }
+    st ^= 1;
+  }
+  wait_vmcnt<0>();  // the trailing dummy copies must have landed before LDS is reused
+  lds_barrier();
+  if (!active) return;
+  float* wave_lds = reinterpret_cast<float*>(lds_raw) + wave * (wave_epilogue_bytes<1, TN>() / 4);
+  store_tiles_coalesced<1, TN>(acc1, EpiDgrad{nullptr, dqkv + (OWN_KEYS ? D : 0), ld3}, zb * S + ow, zh * DH, lane, wave_lds);
+  if (OWN_KEYS) store_tiles_coalesced<1, TN>(acc2, EpiDgrad{nullptr, dqkv + 2 * D, ld3}, zb * S + ow, zh * DH, lane, wave_lds);
+}
+
+template <int DH, bool OWN_KEYS>
+hipError_t launch_flash_bwd(hipStream_t s, int seqs, int S, int heads, const uint16_t* qkv, const uint16_t* dout, const float* stat,
+                            uint16_t* dqkv) {
+  constexpr size_t row_bytes = (size_t)(DH / 64) * RowDma<64, kBwdWaves>::kBytes, col_bytes = ColDma<DH, kBwdWaves>::kBytes;
+  constexpr size_t stage_bytes = 2 * (2 * row_bytes + (OWN_KEYS ? 2 : 1) * col_bytes + (OWN_KEYS ? 1024 : 0));
+  constexpr size_t epi_bytes = (size_t)kBwdWaves * wave_epilogue_bytes<1, DH / 32>();
+  constexpr size_t lds_bytes = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
+  static_assert(lds_bytes <= 160 * 1024, "stages do not fit the LDS of a CU");
+  auto kernel = attn_flash_bwd_kernel<DH, OWN_KEYS>;
+  static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (attr != hipSuccess) return attr;
+  const float scale = 1.0f / sqrtf((float)DH);
+  hipLaunchKernelGGL(kernel, dim3((S + kBwdOwn - 1) / kBwdOwn, seqs * heads), dim3(64 * kBwdWaves), lds_bytes, s, S, heads, qkv, dout,
+                     stat, dqkv, scale, scale * kLog2e);
+  return hipGetLastError();
+}
+
 // bytes of scratch per sequence: scores and dP in fp32, P and dS in bf16
 inline size_t per_seq_bytes(int S, int heads) { return (size_t)heads * S * S * 12; }
 
@@ -442,6 +678,24 @@ bool attention_flash_fwd_supported(int seqs, int S, int heads, int dh) {
 hipError_t attention_flash_fwd(hipStream_t s, int seqs, int S, int heads, int dh, const uint16_t* qkv, uint16_t* out, float* lse) {
   if (!attention_flash_fwd_supported(seqs, S, heads, dh)) return hipErrorNotSupported;
   return dh == 64 ? launch_flash_fwd<64>(s, seqs, S, heads, qkv, out, lse) : launch_flash_fwd<128>(s, seqs, S, heads, qkv, out, lse);
+}
+
+size_t attention_flash_bwd_scratch_bytes(int seqs, int S, int heads) { return (size_t)seqs * heads * S * 2 * sizeof(float); }
+
+hipError_t attention_flash_bwd(hipStream_t s, int seqs, int S, int heads, int dh, const uint16_t* qkv, const uint16_t* out,
+                               const uint16_t* dout, const float* lse, uint16_t* dqkv, void* scratch, size_t scratch_bytes) {
+  if (!attention_flash_fwd_supported(seqs, S, heads, dh) || !scratch || scratch_bytes < attention_flash_bwd_scratch_bytes(seqs, S, heads))
+    return hipErrorNotSupported;
+  float* stat = (float*)scratch;
+  const size_t rows = (size_t)seqs * S;
+  hipLaunchKernelGGL(attn_stat_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, S, heads, dh, rows, dout, out, lse, stat);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  e = dh == 64 ? launch_flash_bwd<64, false>(s, seqs, S, heads, qkv, dout, stat, dqkv)
+               : launch_flash_bwd<128, false>(s, seqs, S, heads, qkv, dout, stat, dqkv);
+  if (e != hipSuccess) return e;
+  return dh == 64 ? launch_flash_bwd<64, true>(s, seqs, S, heads, qkv, dout, stat, dqkv)
+                  : launch_flash_bwd<128, true>(s, seqs, S, heads, qkv, dout, stat, dqkv);
 }
 
 hipError_t attention_mfma_fwd(hipStream_t s, int seqs, int S, int heads, int dh, const uint16_t* qkv, uint16_t* out, float* lse,

@@ -594,7 +594,9 @@ bool attention_supported(int S, int heads, int dh) {
 }
 
 size_t attention_scratch_bytes(int elt, int seqs, int S, int heads, int dh) {
-  return elt == ELT_BF16 && attention_mfma_supported(S, heads, dh) ? attention_mfma_scratch_bytes(seqs, S, heads) : 0;
+  if (elt != ELT_BF16) return 0;
+  if (attention_flash_fwd_supported(seqs, S, heads, dh)) return attention_flash_bwd_scratch_bytes(seqs, S, heads);
+  return attention_mfma_supported(S, heads, dh) ? attention_mfma_scratch_bytes(seqs, S, heads) : 0;
 }
 
 hipError_t launch_attention_fwd(hipStream_t s, int elt, int seqs, int S, int heads, int dh, const void* qkv, void* out,
@@ -647,6 +649,10 @@ static hipError_t attention_bwd_typed(hipStream_t s, int seqs, int S, int heads,
 hipError_t launch_attention_bwd(hipStream_t s, int elt, int seqs, int S, int heads, int dh, const void* qkv, const void* out,
                                 const void* dout, const float* lse, void* dqkv, void* scratch, size_t scratch_bytes) {
   if (!attention_supported(S, heads, dh) || seqs > 65535) return hipErrorInvalidValue;
+  if (elt == ELT_BF16 && scratch && attention_flash_fwd_supported(seqs, S, heads, dh) &&
+      scratch_bytes >= attention_flash_bwd_scratch_bytes(seqs, S, heads))
+    return attention_flash_bwd(s, seqs, S, heads, dh, (const uint16_t*)qkv, (const uint16_t*)out, (const uint16_t*)dout, lse,
+                               (uint16_t*)dqkv, scratch, scratch_bytes);
   if (elt == ELT_BF16 && scratch && attention_mfma_supported(S, heads, dh) &&
       scratch_bytes >= attention_mfma_scratch_bytes(1, S, heads))
     return attention_mfma_bwd(s, seqs, S, heads, dh, (const uint16_t*)qkv, (const uint16_t*)dout, lse, (uint16_t*)dqkv, scratch,

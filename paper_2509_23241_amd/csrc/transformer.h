@@ -41,6 +41,11 @@ bool attention_supported(int S, int heads, int dh);
 // Fused forward (head widths 64 and 128, tokens a multiple of 64): online softmax, no score matrix in memory, no scratch.
 bool attention_flash_fwd_supported(int seqs, int S, int heads, int dh);
 hipError_t attention_flash_fwd(hipStream_t s, int seqs, int S, int heads, int dh, const uint16_t* qkv, uint16_t* out, float* lse);
+// Fused backward for the same shapes: two launches (dQ; dK and dV) that recompute the probabilities from lse, after a
+// small kernel that forms delta = dO . O per token and head into `scratch` (attention_flash_bwd_scratch_bytes).
+size_t attention_flash_bwd_scratch_bytes(int seqs, int S, int heads);
+hipError_t attention_flash_bwd(hipStream_t s, int seqs, int S, int heads, int dh, const uint16_t* qkv, const uint16_t* out,
+                               const uint16_t* dout, const float* lse, uint16_t* dqkv, void* scratch, size_t scratch_bytes);
 bool attention_mfma_supported(int S, int heads, int dh);
 size_t attention_mfma_scratch_bytes(int seqs, int S, int heads);
 hipError_t attention_mfma_fwd(hipStream_t s, int seqs, int S, int heads, int dh, const uint16_t* qkv, uint16_t* out, float* lse,

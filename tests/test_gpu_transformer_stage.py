@@ -70,10 +70,11 @@ def test_transformer_stage_reduced_bf16():
 
 
 @pytest.mark.parametrize("tokens,heads,dh", [(64, 2, 64), (192, 1, 128), (320, 2, 64), (512, 1, 128)])
-def test_fused_attention_forward_bf16(tokens, heads, dh):
-    # the fused forward kernel: one 64-key block (two of eight waves at work), a partly filled workgroup, two
-    # workgroups per head with different numbers of key blocks (320 = 256 + 64 queries), several diagonal blocks;
-    # head widths 64 and 128.  The projections around it make the inputs and the upstream gradient ordinary.
+def test_fused_attention_bf16(tokens, heads, dh):
+    # the fused forward and backward kernels: one 64-row block (two of the waves at work), partly filled workgroups,
+    # several workgroups per head with different numbers of blocks to walk (320 = 256 + 64 = 128 + 128 + 64), several
+    # diagonal blocks; head widths 64 and 128.  The projections around it make the inputs and the upstream gradient
+    # ordinary.
     d = heads * dh
     specs = (W.Dense(32, 3 * d, "none", tokens=tokens), W.Attention(d, heads, tokens), W.Dense(d, 32, "none", tokens=tokens))
     print(tokens, heads, dh, _run_stage(specs, f"attn_flash_{tokens}_{heads}_{dh}", "bf16", mb=2, n=2))
