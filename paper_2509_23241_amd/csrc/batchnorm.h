@@ -10,8 +10,11 @@ namespace tp {
 // a = act(gamma (x - mean)/sqrt(var + 1e-5) + beta), d = act' of the same pre-activation (d_out may be null);
 // stats[2c] = mean_c, stats[2c+1] = 1/sqrt(var_c + eps) are kept for the backward pass.  Mean and variance are
 // formed in two passes over x (no E[x^2] - mean^2).  scratch: batchnorm_scratch_floats(rows, C) floats.
+// addend (null: none; only where batchnorm_fwd_add_supported): the residual add that follows a normalisation without
+// activation of its own, fused: a = act(bf16(normalised) + addend), d = act' of the same sum.
 hipError_t launch_batchnorm_fwd(hipStream_t s, int elt, size_t rows, int C, const void* x, const float* gamma, const float* beta,
-                                int act, void* a_out, void* d_out, float* stats, float* scratch);
+                                int act, void* a_out, void* d_out, float* stats, float* scratch, const void* addend = nullptr);
+bool batchnorm_fwd_add_supported(int elt, size_t rows, int C);
 // dy: gradient with respect to the normalised, scaled and shifted value (the activation's derivative already
 // applied).  dx for the rows of this call; sums[0..C) = sum dy * xhat, sums[C..2C) = sum dy (this call's share of
 // dgamma, dbeta).  The scale of the backward pass is alpha*gamma_s + beta_c*gamma_l, formed in fp32.

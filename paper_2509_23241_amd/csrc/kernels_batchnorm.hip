@@ -113,30 +113,33 @@ __device__ __forceinline__ int slab_of_block(int b, int nblocks) {
   return (nblocks & 7) ? b : (b & 7) * (nblocks >> 3) + (b >> 3);
 }
 
-// Sums NV values per lane over the whole workgroup, in a fixed order; every lane gets the totals.
+// Sums NV values per lane over the whole workgroup, in a fixed order; every lane gets the totals.  The values
+// go through LDS as [NV][1024]: thread (v, p) adds 16 neighbouring lanes' values of quantity v, the 64 threads of
+// quantity v finish with one butterfly -- 6 shuffles on one value in NV waves instead of 6 * NV in all sixteen.
 template <int NV>
-__device__ __forceinline__ void slab_sum(float (&v)[NV], float* red /* [kSlabWaves + 1][NV] */) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-  for (int i = 0; i < NV; ++i) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v[i] += __shfl_xor(v[i], off, 64);
-  }
+__device__ __forceinline__ void slab_sum(float (&v)[NV], float* red /* [NV][kSlabThreads] + [NV] */) {
+  static_assert(NV * 64 <= kSlabThreads, "one wave per quantity");
+  const int t = threadIdx.x;
   __syncthreads();  // the previous totals have been read
-  if (lane == 0) {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) red[wave * NV + i] = v[i];
+  for (int i = 0; i < NV; ++i) red[i * kSlabThreads + t] = v[i];
+  __syncthreads();
+  if (t < NV * 64) {
+    const int q = t >> 6, p = t & 63;
+    const float4* src = reinterpret_cast<const float4*>(red + q * kSlabThreads + p * 16);
+    float a = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float4 f = src[k];
+      a += (f.x + f.y) + (f.z + f.w);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off, 64);
+    if (p == 0) red[NV * kSlabThreads + q] = a;
   }
   __syncthreads();
-  if (threadIdx.x < NV) {
-    float t = 0.f;
 #pragma unroll
-    for (int w = 0; w < kSlabWaves; ++w) t += red[w * NV + threadIdx.x];
-    red[kSlabWaves * NV + threadIdx.x] = t;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < NV; ++i) v[i] = red[kSlabWaves * NV + i];
+  for (int i = 0; i < NV; ++i) v[i] = red[NV * kSlabThreads + i];
 }
 
 __device__ __forceinline__ void unpack8(const uint4& u, float (&f)[8]) {
@@ -155,9 +158,10 @@ template <int NL>
 __global__ __launch_bounds__(kSlabThreads) void bn_fwd_slab_kernel(int rows, int C, const uint16_t* __restrict__ x,
                                                                    const float* __restrict__ gamma,
                                                                    const float* __restrict__ beta, int act,
+                                                                   const uint16_t* __restrict__ addend,
                                                                    uint16_t* __restrict__ a_out, uint16_t* __restrict__ d_out,
                                                                    float* __restrict__ stats) {
-  __shared__ float red[(kSlabWaves + 1) * 8];
+  __shared__ __attribute__((aligned(16))) float red[8 * kSlabThreads + 8];
   const int c0 = slab_of_block(blockIdx.x, gridDim.x) * 8;
   uint4 v[NL];
 #pragma unroll
@@ -205,11 +209,15 @@ __global__ __launch_bounds__(kSlabThreads) void bn_fwd_slab_kernel(int rows, int
   for (int i = 0; i < NL; ++i) {
     const int r = i * kSlabThreads + threadIdx.x;
     if (r >= rows) continue;
-    float f[8], a[8], d[8];
+    float f[8], a[8], d[8], sk[8];
     unpack8(v[i], f);
+    if (addend) unpack8(*reinterpret_cast<const uint4*>(addend + (size_t)r * C + c0), sk);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const float z = fmaf((f[j] - mean[j]) * rstd[j], ga[j], be[j]);
+      float z = fmaf((f[j] - mean[j]) * rstd[j], ga[j], be[j]);
+      // with an addend the normalisation itself has no activation: its result takes the bf16 rounding it would get
+      // as a stored tensor, then act(. + addend) is the residual add that follows it in the layer list
+      if (addend) z = bf16_to_float(float_to_bf16(z)) + sk[j];
       a[j] = act_forward(z, act);
       d[j] = act_derivative(z, act);
     }
@@ -226,7 +234,7 @@ __global__ __launch_bounds__(kSlabThreads) void bn_bwd_slab_kernel(int rows, int
                                                                    const float* __restrict__ gamma_s,
                                                                    const float* __restrict__ gamma_l, float alpha, float beta_c,
                                                                    uint16_t* __restrict__ dx, float* __restrict__ sums) {
-  __shared__ float red[(kSlabWaves + 1) * 16];
+  __shared__ __attribute__((aligned(16))) float red[16 * kSlabThreads + 16];
   const int c0 = slab_of_block(blockIdx.x, gridDim.x) * 8;
   const int q = blockIdx.y;
   const float inv_rows = 1.f / (float)rows;
@@ -362,12 +370,17 @@ hipError_t launch_batchnorm_bwd_fused(hipStream_t s, int elt, size_t rows, int C
   return hipGetLastError();
 }
 
+bool batchnorm_fwd_add_supported(int elt, size_t rows, int C) {
+  return elt == ELT_BF16 && C % 8 == 0 && rows >= 1 && slab_loads(rows, 8) != 0 && rows * C < (1ull << 31);
+}
+
 hipError_t launch_batchnorm_fwd(hipStream_t s, int elt, size_t rows, int C, const void* x, const float* gamma, const float* beta,
-                                int act, void* a_out, void* d_out, float* stats, float* scratch) {
-  if (elt == ELT_BF16 && C % 8 == 0 && rows >= 1 && slab_loads(rows, 8) != 0 && rows * C < (1ull << 31)) {
+                                int act, void* a_out, void* d_out, float* stats, float* scratch, const void* addend) {
+  if (addend && !batchnorm_fwd_add_supported(elt, rows, C)) return hipErrorNotSupported;
+  if (batchnorm_fwd_add_supported(elt, rows, C)) {
 #define TP_BN_FWD(NL)                                                                                                    \
   hipLaunchKernelGGL(bn_fwd_slab_kernel<NL>, dim3(C / 8), dim3(kSlabThreads), 0, s, (int)rows, C, (const uint16_t*)x, gamma, \
-                     beta, act, (uint16_t*)a_out, (uint16_t*)d_out, stats)
+                     beta, act, (const uint16_t*)addend, (uint16_t*)a_out, (uint16_t*)d_out, stats)
     switch (slab_loads(rows, 8)) {
       case 1: TP_BN_FWD(1); break;
       case 2: TP_BN_FWD(2); break;

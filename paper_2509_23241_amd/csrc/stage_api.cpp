@@ -665,6 +665,19 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
       ProfScope ps(st, TP_K_NORM);
       const int C = lp.d.in_features;
       float* stats = (float*)(aslot + lp.stat_off) + (size_t)ub_idx * 2 * C;
+      // a normalisation without activation followed by a residual add: one kernel forms act(bn(x) + kept tensor)
+      // and act' of it, written where the add would have written them
+      if (l + 1 < L && lp.d.act == TP_ACT_NONE && st->plan.layers[l + 1].d.type == TP_LAYER_RESIDUAL &&
+          st->plan.layers[l + 1].d.geom[1] == 1 && tp::batchnorm_fwd_add_supported(d.dtype, (size_t)d.mb * lp.tokens, C)) {
+        const LayerPlan& add = st->plan.layers[l + 1];
+        const char* skip = aslot + st->plan.layers[add.skip_layer].x_off + row0 * add.in_elems * es;
+        void* add_z = add.z_off == UINT64_MAX ? nullptr : aslot + add.z_off + row0 * add.out_elems * es;
+        void* add_a = (l + 1 == L - 1) ? y_dev : (void*)(aslot + st->plan.layers[l + 2].x_off + row0 * add.out_elems * es);
+        HIP_TRY(tp::launch_batchnorm_fwd(st->stream, d.dtype, (size_t)d.mb * lp.tokens, C, x_saved, master + lp.w_off,
+                                         master + lp.b_off, add.d.act, add_a, add_z, stats, st->partials(), skip));
+        ++l;  // the add is done
+        continue;
+      }
       HIP_TRY(tp::launch_batchnorm_fwd(st->stream, d.dtype, (size_t)d.mb * lp.tokens, C, x_saved, master + lp.w_off,
                                        master + lp.b_off, lp.d.act, a_out, z_out, stats, st->partials()));
       continue;
