@@ -17,8 +17,9 @@ void mfma_set_config(int product, int cfg);
 
 // d_out receives act'(z) (what the backward pass multiplies with), a_out = act(z).  If x_copy is
 // not null (16-byte aligned, like x) the launch also leaves a copy of x there.
+// addend (or null): an [M x N] tensor added to the rounded activation -- the residual add that follows the layer.
 hipError_t mfma_fprop(hipStream_t s, int M, int N, int K, const uint16_t* x, const uint16_t* W, const float* bias,
-                      int act, uint16_t* d_out, uint16_t* a_out, uint16_t* x_copy);
+                      int act, uint16_t* d_out, uint16_t* a_out, uint16_t* x_copy, const uint16_t* addend = nullptr);
 // out = (dz Wb) (.) d_prev, d_prev = saved act'(z) of the previous layer or null.
 hipError_t mfma_dgrad(hipStream_t s, int M, int N, int K, const uint16_t* dz, const uint16_t* Wb,
                       const uint16_t* d_prev, uint16_t* out);

@@ -14,8 +14,11 @@ enum Act : int { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
 // d_out (what the backward pass multiplies with) may be null; a_out is always written.
 // Both [M x N] in elt.  If x_copy is not null the launch also leaves a copy of x there (fused
 // into the GEMM where the kernel supports it, a separate copy otherwise).
+// addend (null: none; only where fprop_add_supported, 16-byte aligned): an [M x N] tensor added to the rounded
+// activation, i.e. the residual add that follows the layer.
 hipError_t launch_fprop(hipStream_t s, int elt, int M, int N, int K, const void* x, const void* W,
-                        const float* bias, int act, void* d_out, void* a_out, void* x_copy);
+                        const float* bias, int act, void* d_out, void* a_out, void* x_copy, const void* addend = nullptr);
+bool fprop_add_supported(int elt, int M, int N, int K);
 
 // out = (dz W_b) (.) d_prev   dz:[M x N] W_b:[N x K] d_prev:[M x K] saved act'(z), or null.
 hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* Wb,

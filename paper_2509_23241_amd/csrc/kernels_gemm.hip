@@ -216,19 +216,22 @@ size_t colsum_scratch_floats(int M, int N) {
   return (size_t)std::max(colsum_shape(M, N, 4).chunks, colsum_shape(M, N, 8).chunks) * (size_t)N;
 }
 
+bool fprop_add_supported(int elt, int M, int N, int K) { return elt == ELT_BF16 && mfma_fprop_supported(M, N, K) && N % 8 == 0; }
+
 hipError_t launch_fprop(hipStream_t s, int elt, int M, int N, int K, const void* x, const void* W, const float* bias,
-                        int act, void* d_out, void* a_out, void* x_copy) {
+                        int act, void* d_out, void* a_out, void* x_copy, const void* addend) {
+  if (addend && (!fprop_add_supported(elt, M, N, K) || ((uintptr_t)addend & 15))) return hipErrorNotSupported;
   const bool aligned = (((uintptr_t)x | (uintptr_t)x_copy) & 15) == 0;
   if (elt == ELT_BF16 && mfma_fprop_supported(M, N, K) && aligned)
     return mfma_fprop(s, M, N, K, (const uint16_t*)x, (const uint16_t*)W, bias, act, (uint16_t*)d_out, (uint16_t*)a_out,
-                      (uint16_t*)x_copy);
+                      (uint16_t*)x_copy, (const uint16_t*)addend);
   if (x_copy) {
     hipError_t err = launch_copy(s, x, x_copy, (size_t)M * K * (elt == ELT_BF16 ? 2 : 4));
     if (err != hipSuccess) return err;
   }
   if (elt == ELT_BF16 && mfma_fprop_supported(M, N, K))
     return mfma_fprop(s, M, N, K, (const uint16_t*)x, (const uint16_t*)W, bias, act, (uint16_t*)d_out, (uint16_t*)a_out,
-                      nullptr);
+                      nullptr, (const uint16_t*)addend);
   EpiArgs e{};
   e.bias = bias; e.d_out = d_out; e.a_out = a_out; e.act = act;
   return simt<EPI_FPROP>(s, elt, M, N, K, x, K, 1, W, 1, K, e);

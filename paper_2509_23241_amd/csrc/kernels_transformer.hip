@@ -170,8 +170,8 @@ template <int NG>
 __global__ __launch_bounds__(kThreads) void layernorm_bwd_bf16_kernel(size_t rows, int rows_per_block, const uint16_t* __restrict__ dy,
                                                                       const uint16_t* __restrict__ x, const float* __restrict__ stats,
                                                                       const float* __restrict__ gamma_s, const float* __restrict__ gamma_l,
-                                                                      float alpha, float beta_c, uint16_t* __restrict__ dx,
-                                                                      float* __restrict__ partial) {
+                                                                      float alpha, float beta_c, const uint16_t* __restrict__ addend,
+                                                                      uint16_t* __restrict__ dx, float* __restrict__ partial) {
   constexpr int D = NG * 512;
   extern __shared__ float sm[];  // [4 waves][2*D]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -213,6 +213,12 @@ __global__ __launch_bounds__(kThreads) void layernorm_bwd_bf16_kernel(size_t row
       float o[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) o[j] = rstd * (dyv[k][j] * g[k][j] - s1 - xh[k][j] * s2);
+      if (addend) {  // the gradient that went around the residual branch: added to the rounded result, as a separate add would
+        float sk[8];
+        unpack8(*reinterpret_cast<const uint4*>(addend + r * D + (lane + 64 * k) * 8), sk);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] = bf16_to_float(float_to_bf16(o[j])) + sk[j];
+      }
       *reinterpret_cast<uint4*>(dx + r * D + (lane + 64 * k) * 8) = pack8(o);
     }
   }
@@ -538,9 +544,13 @@ size_t layernorm_scratch_floats(size_t rows, int D) {
   return ((rows + rpb - 1) / rpb) * 2 * (size_t)D;
 }
 
+bool layernorm_bwd_add_supported(int elt, int D) { return elt == ELT_BF16 && D % 512 == 0 && D <= 2048; }
+
 hipError_t launch_layernorm_bwd(hipStream_t s, int elt, size_t rows, int D, const void* dy, const void* x,
                                 const float* stats, const float* gamma_s, const float* gamma_l, float alpha, float beta_c,
-                                void* dx, float* dgamma, float* dbeta, float* partials) {
+                                void* dx, float* dgamma, float* dbeta, float* partials, const void* addend) {
+  if (addend && (!layernorm_bwd_add_supported(elt, D) || (((uintptr_t)x | (uintptr_t)dy | (uintptr_t)dx | (uintptr_t)addend) & 15)))
+    return hipErrorNotSupported;
   const int rpb = ln_rows_per_block(rows);
   const unsigned blocks = (unsigned)((rows + rpb - 1) / rpb);
   const size_t lds = (size_t)4 * 2 * D * sizeof(float);
@@ -559,7 +569,8 @@ hipError_t launch_layernorm_bwd(hipStream_t s, int elt, size_t rows, int D, cons
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);                    \
     if (attr != hipSuccess) return attr;                                                                                      \
     hipLaunchKernelGGL(layernorm_bwd_bf16_kernel<NG>, dim3(blocks), dim3(kThreads), lds, s, rows, rpb, (const uint16_t*)dy,   \
-                       (const uint16_t*)x, stats, gamma_s, gamma_l, alpha, beta_c, (uint16_t*)dx, partials);                  \
+                       (const uint16_t*)x, stats, gamma_s, gamma_l, alpha, beta_c, (const uint16_t*)addend, (uint16_t*)dx,  \
+                       partials);                                                                                              \
   } break;
       TP_LN_BWD(1) TP_LN_BWD(2) TP_LN_BWD(3) TP_LN_BWD(4)
 #undef TP_LN_BWD

@@ -24,6 +24,7 @@ typedef short shortx8 __attribute__((ext_vector_type(8)));
 // orientation, where the 32 lanes of a half wave already cover 128 contiguous bytes.
 struct EpiFprop {
   const float* bias; uint16_t* d_out; uint16_t* a_out; int act; int ldc;  // d_out: act'(z) for the backward, or null
+  const uint16_t* addend = nullptr;  // [M x ldc] tensor added to the rounded activation (a residual add that follows), or null
   static constexpr bool kSwap = true;
   // 8 consecutive columns n..n+7 of row m (n and ldc multiples of 8)
   __device__ __forceinline__ void row8(int m, int n, float (&v)[8]) const {
@@ -37,6 +38,15 @@ struct EpiFprop {
       a[j] = p.a;
       d[j] = p.d;
     }
+    if (addend) {
+      const uint4 u = *reinterpret_cast<const uint4*>(addend + i);
+      const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        a[2 * j] = bf16_to_float(float_to_bf16(a[2 * j])) + __uint_as_float(w[j] << 16);
+        a[2 * j + 1] = bf16_to_float(float_to_bf16(a[2 * j + 1])) + __uint_as_float(w[j] & 0xffff0000u);
+      }
+    }
     if (d_out)
       *reinterpret_cast<uint4*>(d_out + i) =
           make_uint4(pack_bf16x2(d[0], d[1]), pack_bf16x2(d[2], d[3]), pack_bf16x2(d[4], d[5]), pack_bf16x2(d[6], d[7]));
@@ -45,7 +55,7 @@ struct EpiFprop {
   }
   __device__ __forceinline__ void quad(int m, int n, int count, float v0, float v1, float v2, float v3) const {
     const size_t i = (size_t)m * ldc + n;
-    if (count == 4 && (ldc & 3) == 0) {
+    if (count == 4 && (ldc & 3) == 0 && !addend) {
       const float4 b = *reinterpret_cast<const float4*>(bias + n);
       const ActPair p0 = act_pair_fast(v0 + b.x, act), p1 = act_pair_fast(v1 + b.y, act);
       const ActPair p2 = act_pair_fast(v2 + b.z, act), p3 = act_pair_fast(v3 + b.w, act);
@@ -56,7 +66,7 @@ struct EpiFprop {
       for (int j = 0; j < count; ++j) {
         const ActPair p = act_pair_fast(v[j] + bias[n + j], act);
         if (d_out) d_out[i + j] = float_to_bf16(p.d);
-        a_out[i + j] = float_to_bf16(p.a);
+        a_out[i + j] = addend ? float_to_bf16(bf16_to_float(float_to_bf16(p.a)) + bf16_to_float(addend[i + j])) : float_to_bf16(p.a);
       }
     }
   }

@@ -612,6 +612,21 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
     void* a_out = (l == L - 1) ? y_dev : (void*)(aslot + st->plan.layers[l + 1].x_off + row0 * lp.out_elems * es);
     if (lp.d.type == TP_LAYER_DENSE) {
       ProfScope ps(st, TP_K_FPROP);
+      // a dense layer followed by a plain residual add: the epilogue of the GEMM adds the kept tensor
+      if (l + 1 < L && st->plan.layers[l + 1].d.type == TP_LAYER_RESIDUAL && st->plan.layers[l + 1].d.geom[1] == 1 &&
+          st->plan.layers[l + 1].d.act == TP_ACT_NONE &&
+          tp::fprop_add_supported(d.dtype, d.mb * lp.tokens, lp.d.out_features, lp.d.in_features)) {
+        const LayerPlan& add = st->plan.layers[l + 1];
+        const char* skip = aslot + st->plan.layers[add.skip_layer].x_off + row0 * add.in_elems * es;
+        void* add_a = (l + 1 == L - 1) ? y_dev : (void*)(aslot + st->plan.layers[l + 2].x_off + row0 * add.out_elems * es);
+        if ((((uintptr_t)skip | (uintptr_t)add_a) & 15) == 0) {
+          HIP_TRY(tp::launch_fprop(st->stream, d.dtype, d.mb * lp.tokens, lp.d.out_features, lp.d.in_features, x_in,
+                                   wcopy + lp.w_off * es, master + lp.b_off, lp.d.act, z_out, add_a,
+                                   need_copy ? x_saved : nullptr, skip));
+          ++l;  // the add is done
+          continue;
+        }
+      }
       HIP_TRY(tp::launch_fprop(st->stream, d.dtype, d.mb * lp.tokens, lp.d.out_features, lp.d.in_features, x_in,
                                wcopy + lp.w_off * es, master + lp.b_off, lp.d.act, z_out, a_out,
                                need_copy ? x_saved : nullptr));
@@ -762,6 +777,7 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
     // Three temporaries: the gradient in hand, the one being formed, and the one a residual add has
     // set aside for the matching begin.
     const void* pinned = nullptr;
+    bool begin_added = false;  // the layer behind a residual begin has already added the gradient that was set aside
     auto scratch_for = [&](const void* cur) -> void* {
       for (int i = 0; i < 3; ++i)
         if (st->dz_buf(i) != cur && st->dz_buf(i) != pinned) return st->dz_buf(i);
@@ -846,6 +862,12 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
           continue;
         }
         if (no_dx) break;
+        if (begin_added) {  // dz already holds the sum (it lies in one of the temporaries)
+          begin_added = false;
+          pinned = nullptr;
+          if (int rc = through_activation(const_cast<void*>(dz))) return rc;
+          continue;
+        }
         {
           ProfScope ps(st, TP_K_ADD);
           HIP_TRY(tp::launch_add(st->stream, d.dtype, (size_t)rows * lp.in_elems, dz, pinned, dst));
@@ -859,10 +881,16 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
         const float* gl = st->ring(slot_now) + lp.w_off;
         const float* gs = delta != 0 ? st->ring(slot_f) + lp.w_off : gl;
         {
+          // a residual begin right in front (not the stage's first layer): the gradient set aside at the add is
+          // added by this kernel, where the begin would have needed a launch of its own
+          const bool fuse = l >= 2 && pinned && st->plan.layers[l - 1].d.type == TP_LAYER_RESIDUAL &&
+                            st->plan.layers[l - 1].d.geom[1] == 0 && tp::layernorm_bwd_add_supported(d.dtype, lp.d.in_features) &&
+                            ((((uintptr_t)dz | (uintptr_t)pinned | (uintptr_t)dst) & 15) == 0);
           ProfScope ps(st, TP_K_NORM);
           HIP_TRY(tp::launch_layernorm_bwd(st->stream, d.dtype, (size_t)rows * lp.tokens, lp.d.in_features, dz, aslot + lp.x_off,
                                            (const float*)(aslot + lp.stat_off), gs, gl, (float)ca, (float)cb, dst,
-                                           g + lp.w_off, g + lp.b_off, st->partials()));
+                                           g + lp.w_off, g + lp.b_off, st->partials(), fuse ? pinned : nullptr));
+          begin_added = fuse;
         }
         if (no_dx) break;
         if (int rc = through_activation(dst)) return rc;

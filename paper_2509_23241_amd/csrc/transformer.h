@@ -14,9 +14,12 @@ hipError_t launch_layernorm_fwd(hipStream_t s, int elt, size_t rows, int D, cons
 // dx, dgamma, dbeta of the above.  The scale the backward pass uses is alpha*gamma_s + beta_c*gamma_l
 // (the intermediate weight of the method, formed on the fly in fp32; pass gamma_l twice with 1, 0 for
 // the plain case).  partials: scratch of layernorm_scratch_floats(rows, D) floats.
+// addend (null: none; only where layernorm_bwd_add_supported and all pointers are 16-byte aligned): a tensor of dx's shape
+// that is added to the rounded dx -- the gradient that went around a residual branch which starts in front of this layer.
 hipError_t launch_layernorm_bwd(hipStream_t s, int elt, size_t rows, int D, const void* dy, const void* x,
                                 const float* stats, const float* gamma_s, const float* gamma_l, float alpha, float beta_c,
-                                void* dx, float* dgamma, float* dbeta, float* partials);
+                                void* dx, float* dgamma, float* dbeta, float* partials, const void* addend = nullptr);
+bool layernorm_bwd_add_supported(int elt, int D);
 size_t layernorm_scratch_floats(size_t rows, int D);
 
 // out = a + b, elementwise (out may alias a or b)
