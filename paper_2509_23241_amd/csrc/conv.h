@@ -14,8 +14,9 @@ hipError_t launch_conv_fprop(hipStream_t s, int elt, int imgs, int H, int W, int
                              const void* wgt, const float* bias, int act, void* d_out, void* a_out, const void* zeros);
 
 // out = (transposed convolution of dz with W_b) (.) d_prev;  dz:[imgs*H*W x cout], out:[imgs*H*W x cin].
+// relu_mask = 1: d_prev holds the previous layer's ReLU output and the factor is (output > 0).
 hipError_t launch_conv_dgrad(hipStream_t s, int elt, int imgs, int H, int W, int stride, int cin, int cout, const void* dz,
-                             const void* wb, const void* d_prev, void* out, const void* zeros);
+                             const void* wb, const void* d_prev, void* out, const void* zeros, int relu_mask = 0);
 
 // gW[cout][3][3][cin] (fp32) = sum over pixels of dz (x) shifted x.
 // partial: scratch of conv_wgrad_scratch_floats(imgs*H*W, cin, cout) floats.
@@ -42,7 +43,7 @@ hipError_t conv_mfma_fprop(hipStream_t s, int imgs, int H, int W, int stride, in
                            const uint16_t* wgt, const float* bias, int act, uint16_t* d_out, uint16_t* a_out,
                            const uint16_t* zeros);
 hipError_t conv_mfma_dgrad(hipStream_t s, int imgs, int H, int W, int stride, int cin, int cout, const uint16_t* dz,
-                           const uint16_t* wb, const uint16_t* d_prev, uint16_t* out, const uint16_t* zeros);
+                           const uint16_t* wb, const uint16_t* d_prev, uint16_t* out, const uint16_t* zeros, int relu_mask = 0);
 hipError_t conv_mfma_wgrad(hipStream_t s, int imgs, int H, int W, int stride, int cin, int cout, const uint16_t* dz,
                            const uint16_t* x, float* gW, float* partial, const uint16_t* zeros);
 

@@ -22,7 +22,7 @@ bool fprop_add_supported(int elt, int M, int N, int K);
 
 // out = (dz W_b) (.) d_prev   dz:[M x N] W_b:[N x K] d_prev:[M x K] saved act'(z), or null.
 hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* Wb,
-                        const void* d_prev, void* out);
+                        const void* d_prev, void* out, int relu_mask = 0);
 
 // gW = dz^T x  (fp32 [N x K]).
 // partial: scratch of wgrad_scratch_floats(elt, M, N, K) floats (may be null when that is 0)
@@ -40,7 +40,8 @@ hipError_t launch_sum_partials_strided(hipStream_t s, size_t count, int splits, 
                                        float* out);
 
 // dz = dy (.) d    all [rows x cols] in elt; d = saved act'(z).
-hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* d, void* dz);
+// relu_mask = 1: d holds a ReLU output instead of its derivative; the factor is (d > 0).
+hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* d, void* dz, int relu_mask = 0);
 
 // Device-to-device copy of `bytes` bytes.
 hipError_t launch_copy(hipStream_t s, const void* src, void* dst, size_t bytes);

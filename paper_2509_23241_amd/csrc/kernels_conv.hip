@@ -135,7 +135,10 @@ __global__ __launch_bounds__(kThreads) void conv_simt_kernel(ConvGeom g, const T
         if (d_out) d_out[idx] = from_float<T>(act_derivative(v, act));
         out[idx] = from_float<T>(act_forward(v, act));
       } else if (PRODUCT == 1) {
-        if (d_prev) v *= to_float(d_prev[idx]);
+        if (d_prev) {  // dgrad reuses the `act` argument: 1 = d_prev holds the ReLU output, the factor is (output > 0)
+          const float dp = to_float(d_prev[idx]);
+          v = act ? (dp > 0.f ? v : 0.f) : v * dp;
+        }
         out[idx] = from_float<T>(v);
       } else {
         partial[(size_t)blockIdx.z * M * N + idx] = v;
@@ -261,19 +264,19 @@ hipError_t launch_conv_fprop(hipStream_t s, int elt, int imgs, int H, int W, int
 }
 
 hipError_t launch_conv_dgrad(hipStream_t s, int elt, int imgs, int H, int W, int stride, int cin, int cout, const void* dz,
-                             const void* wb, const void* d_prev, void* out, const void* zeros) {
+                             const void* wb, const void* d_prev, void* out, const void* zeros, int relu_mask) {
   if (elt == 1 && zeros && conv_mfma_supported(imgs, H, W, stride, cin, cout))
     return conv_mfma_dgrad(s, imgs, H, W, stride, cin, cout, (const uint16_t*)dz, (const uint16_t*)wb,
-                           (const uint16_t*)d_prev, (uint16_t*)out, (const uint16_t*)zeros);
+                           (const uint16_t*)d_prev, (uint16_t*)out, (const uint16_t*)zeros, relu_mask);
   const ConvGeom g{imgs, H, W, cin, cout, stride, H / stride, W / stride};
   const int P = imgs * H * W;
   dim3 grid((cin + BN - 1) / BN, (P + BM - 1) / BM);
   if (elt == 1)
     hipLaunchKernelGGL((conv_simt_kernel<uint16_t, 1>), grid, dim3(kThreads), 0, s, g, (const uint16_t*)dz, (const uint16_t*)wb,
-                       (const float*)nullptr, 0, (const uint16_t*)d_prev, (uint16_t*)nullptr, (uint16_t*)out, (float*)nullptr, 0);
+                       (const float*)nullptr, relu_mask, (const uint16_t*)d_prev, (uint16_t*)nullptr, (uint16_t*)out, (float*)nullptr, 0);
   else
     hipLaunchKernelGGL((conv_simt_kernel<float, 1>), grid, dim3(kThreads), 0, s, g, (const float*)dz, (const float*)wb,
-                       (const float*)nullptr, 0, (const float*)d_prev, (float*)nullptr, (float*)out, (float*)nullptr, 0);
+                       (const float*)nullptr, relu_mask, (const float*)d_prev, (float*)nullptr, (float*)out, (float*)nullptr, 0);
   return hipGetLastError();
 }
 

@@ -902,11 +902,11 @@ hipError_t conv_mfma_fprop(hipStream_t s, int imgs, int H, int W, int stride, in
 }
 
 hipError_t conv_mfma_dgrad(hipStream_t s, int imgs, int H, int W, int stride, int cin, int cout, const uint16_t* dz,
-                           const uint16_t* wb, const uint16_t* d_prev, uint16_t* out, const uint16_t* zeros) {
+                           const uint16_t* wb, const uint16_t* d_prev, uint16_t* out, const uint16_t* zeros, int relu_mask) {
   const int P = imgs * H * W;
   // k tile -> (tap, block of 64 output channels): rows co0.. of W_b, columns tap*Cin..
   PlainDesc bd{wb, 9 * cin, cin, cout / DBK, (long)DBK * 9 * cin, cin};
-  EpiDgrad e{d_prev, out, cin};
+  EpiDgrad e{d_prev, out, cin, relu_mask};
   if (stride == 2) {  // rows: input pixels, source: dz on the (H/2) x (W/2) grid; taps of the wrong parity read zeros
     GatherDesc ad{dz, zeros, P, H, W, ilog2(W), cout, H / 2, W / 2};
     return launch_gather_rows<true, 2>(s, P, cin, 9 * cout / DBK, ad, bd, e);

@@ -177,13 +177,15 @@ __global__ __launch_bounds__(kThreads) void convert_kernel(size_t n4, const floa
 
 // dz = dy (.) d, 16 bytes per lane per step; `count` elements, the tail element-wise.
 // dz may be the same buffer as dy (every element is read before it is written by the same lane).
-template <typename T>
+// MASK: d holds a ReLU output instead of its derivative; the factor is (d > 0).
+template <typename T, bool MASK>
 __global__ __launch_bounds__(kThreads) void act_backward_kernel(size_t count, const T* dy, const T* __restrict__ d,
                                                                 T* dz) {
   constexpr int V = 16 / sizeof(T);
   const size_t nvec = count / V;
   const size_t stride = (size_t)gridDim.x * kThreads;
   const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  auto through = [](float g, float dv) { return MASK ? (dv > 0.f ? g : 0.f) : g * dv; };
   for (size_t i = tid; i < nvec; i += stride) {
     const uint4 a = reinterpret_cast<const uint4*>(dy)[i];
     const uint4 b = reinterpret_cast<const uint4*>(d)[i];
@@ -193,18 +195,18 @@ __global__ __launch_bounds__(kThreads) void act_backward_kernel(size_t count, co
       uint32_t ow[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        ow[j] = pack_bf16x2(__uint_as_float(aw[j] << 16) * __uint_as_float(bw[j] << 16),
-                            __uint_as_float(aw[j] & 0xffff0000u) * __uint_as_float(bw[j] & 0xffff0000u));
+        ow[j] = pack_bf16x2(through(__uint_as_float(aw[j] << 16), __uint_as_float(bw[j] << 16)),
+                            through(__uint_as_float(aw[j] & 0xffff0000u), __uint_as_float(bw[j] & 0xffff0000u)));
       o = make_uint4(ow[0], ow[1], ow[2], ow[3]);
     } else {
-      o = make_uint4(__float_as_uint(__uint_as_float(a.x) * __uint_as_float(b.x)),
-                     __float_as_uint(__uint_as_float(a.y) * __uint_as_float(b.y)),
-                     __float_as_uint(__uint_as_float(a.z) * __uint_as_float(b.z)),
-                     __float_as_uint(__uint_as_float(a.w) * __uint_as_float(b.w)));
+      o = make_uint4(__float_as_uint(through(__uint_as_float(a.x), __uint_as_float(b.x))),
+                     __float_as_uint(through(__uint_as_float(a.y), __uint_as_float(b.y))),
+                     __float_as_uint(through(__uint_as_float(a.z), __uint_as_float(b.z))),
+                     __float_as_uint(through(__uint_as_float(a.w), __uint_as_float(b.w))));
     }
     reinterpret_cast<uint4*>(dz)[i] = o;
   }
-  for (size_t i = nvec * V + tid; i < count; i += stride) dz[i] = from_float<T>(to_float(dy[i]) * to_float(d[i]));
+  for (size_t i = nvec * V + tid; i < count; i += stride) dz[i] = from_float<T>(through(to_float(dy[i]), to_float(d[i])));
 }
 
 // Plain 16-byte-per-lane copy (activations handed to a stage that are not yet in its workspace).
@@ -322,14 +324,16 @@ hipError_t launch_convert(hipStream_t s, int elt, size_t count, const float* src
   return hipGetLastError();
 }
 
-hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* d, void* dz) {
+hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* d, void* dz, int relu_mask) {
   const int blocks = stream_blocks(count / 8 + 1, 4096);
-  if (elt == ELT_BF16)
-    hipLaunchKernelGGL(act_backward_kernel<uint16_t>, dim3(blocks), dim3(kThreads), 0, s, count, (const uint16_t*)dy,
-                       (const uint16_t*)d, (uint16_t*)dz);
-  else
-    hipLaunchKernelGGL(act_backward_kernel<float>, dim3(blocks), dim3(kThreads), 0, s, count, (const float*)dy,
-                       (const float*)d, (float*)dz);
+#define TP_ACT_BWD(T, MASK) \
+  hipLaunchKernelGGL((act_backward_kernel<T, MASK>), dim3(blocks), dim3(kThreads), 0, s, count, (const T*)dy, (const T*)d, (T*)dz)
+  if (elt == ELT_BF16) {
+    if (relu_mask) TP_ACT_BWD(uint16_t, true); else TP_ACT_BWD(uint16_t, false);
+  } else {
+    if (relu_mask) TP_ACT_BWD(float, true); else TP_ACT_BWD(float, false);
+  }
+#undef TP_ACT_BWD
   return hipGetLastError();
 }
 

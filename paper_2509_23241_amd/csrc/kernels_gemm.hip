@@ -28,6 +28,7 @@ struct EpiArgs {
   void* a_out;         // EPI_FPROP: activation; EPI_DGRAD: output
   const void* d_prev;  // EPI_DGRAD: optional saved act'(z) of the previous layer
   int act;
+  int relu_mask;       // EPI_DGRAD: d_prev holds the ReLU output, the factor is (output > 0)
 };
 
 // C(m,n) = sum_k A[m*sam + k*sak] * B[k*sbk + n*sbn], 64x64 tile per block, 4x4 per thread.
@@ -88,7 +89,10 @@ __global__ __launch_bounds__(kThreads) void gemm_simt_kernel(int M, int N, int K
         if (e.d_out) ((T*)e.d_out)[idx] = from_float<T>(act_derivative(v, e.act));
         ((T*)e.a_out)[idx] = from_float<T>(act_forward(v, e.act));
       } else {
-        if (e.d_prev) v *= to_float(((const T*)e.d_prev)[idx]);
+        if (e.d_prev) {
+          const float dp = to_float(((const T*)e.d_prev)[idx]);
+          v = e.relu_mask ? (dp > 0.f ? v : 0.f) : v * dp;
+        }
         ((T*)e.a_out)[idx] = from_float<T>(v);
       }
     }
@@ -238,11 +242,11 @@ hipError_t launch_fprop(hipStream_t s, int elt, int M, int N, int K, const void*
 }
 
 hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void* dz, const void* Wb, const void* d_prev,
-                        void* out) {
+                        void* out, int relu_mask) {
   if (elt == ELT_BF16 && mfma_dgrad_supported(M, N, K))
-    return mfma_dgrad(s, M, N, K, (const uint16_t*)dz, (const uint16_t*)Wb, (const uint16_t*)d_prev, (uint16_t*)out);
+    return mfma_dgrad(s, M, N, K, (const uint16_t*)dz, (const uint16_t*)Wb, (const uint16_t*)d_prev, (uint16_t*)out, relu_mask);
   EpiArgs e{};
-  e.a_out = out; e.d_prev = d_prev;
+  e.a_out = out; e.d_prev = d_prev; e.relu_mask = relu_mask;
   // out[M x K] = dz[M x N] . Wb[N x K]: contraction over N
   return simt<EPI_DGRAD>(s, elt, M, K, N, dz, N, 1, Wb, K, 1, e);
 }

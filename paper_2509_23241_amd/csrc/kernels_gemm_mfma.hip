@@ -449,9 +449,9 @@ hipError_t mfma_fprop(hipStream_t s, int M, int N, int K, const uint16_t* x, con
 }
 
 hipError_t mfma_dgrad(hipStream_t s, int M, int N, int K, const uint16_t* dz, const uint16_t* Wb,
-                      const uint16_t* d_prev, uint16_t* out) {
+                      const uint16_t* d_prev, uint16_t* out, int relu_mask) {
   // out[M x K] = dz[M x N] . Wb[N x K]: GEMM (M, K, contraction N)
-  EpiDgrad e{d_prev, out, K};
+  EpiDgrad e{d_prev, out, K, relu_mask};
   TP_GEMM_DISPATCH(pick(M, K, N, N, K, false, true, g_cfg[1]), false, true, s, M, K, N, dz, N, Wb, K, e)
 }
 

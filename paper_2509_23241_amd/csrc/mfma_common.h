@@ -73,7 +73,9 @@ struct EpiFprop {
 };
 struct EpiDgrad {
   const uint16_t* d_prev; uint16_t* out; int ldc;  // d_prev: saved act'(z) of the previous layer, or null
+  int relu_mask = 0;  // 1: d_prev holds the previous layer's ReLU OUTPUT instead; its derivative is (output > 0)
   static constexpr bool kSwap = true;
+  __device__ __forceinline__ float through(float v, float d) const { return relu_mask ? (d > 0.f ? v : 0.f) : v * d; }
   // 8 consecutive columns n..n+7 of row m (n and ldc multiples of 8)
   __device__ __forceinline__ void row8(int m, int n, float (&v)[8]) const {
     const size_t i = (size_t)m * ldc + n;
@@ -82,8 +84,8 @@ struct EpiDgrad {
       const uint32_t w[4] = {d.x, d.y, d.z, d.w};
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        v[2 * j] *= __uint_as_float(w[j] << 16);
-        v[2 * j + 1] *= __uint_as_float(w[j] & 0xffff0000u);
+        v[2 * j] = through(v[2 * j], __uint_as_float(w[j] << 16));
+        v[2 * j + 1] = through(v[2 * j + 1], __uint_as_float(w[j] & 0xffff0000u));
       }
     }
     *reinterpret_cast<uint4*>(out + i) =
@@ -94,17 +96,17 @@ struct EpiDgrad {
     if (count == 4 && (ldc & 3) == 0) {
       if (d_prev) {
         const uint2 d = *reinterpret_cast<const uint2*>(d_prev + i);
-        v0 *= __uint_as_float(d.x << 16);
-        v1 *= __uint_as_float(d.x & 0xffff0000u);
-        v2 *= __uint_as_float(d.y << 16);
-        v3 *= __uint_as_float(d.y & 0xffff0000u);
+        v0 = through(v0, __uint_as_float(d.x << 16));
+        v1 = through(v1, __uint_as_float(d.x & 0xffff0000u));
+        v2 = through(v2, __uint_as_float(d.y << 16));
+        v3 = through(v3, __uint_as_float(d.y & 0xffff0000u));
       }
       *reinterpret_cast<uint2*>(out + i) = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
     } else {
       const float v[4] = {v0, v1, v2, v3};
       for (int j = 0; j < count; ++j) {
         float d = v[j];
-        if (d_prev) d *= bf16_to_float(d_prev[i + j]);
+        if (d_prev) d = through(d, bf16_to_float(d_prev[i + j]));
         out[i + j] = float_to_bf16(d);
       }
     }

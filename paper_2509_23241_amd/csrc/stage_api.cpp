@@ -46,6 +46,7 @@ struct LayerPlan {
   uint64_t stat_bytes = 0;         // batch norm: bytes behind stat_off (per micro-batch, not per sample)
   int tokens = 1;                  // positions per sample (rows of the layer's matrices per sample)
   int skip_layer = -1;             // residual add: index of the layer that remembered the skip activation
+  bool relu_out = false;           // ReLU whose derivative is read off its saved OUTPUT (the next layer's input): no act' tensor
 };
 
 struct Slot {
@@ -276,7 +277,12 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
       lp.stat_off = act;
       act += round_up(lp.stat_bytes ? lp.stat_bytes : rows * lp.stat_elems * 4, 256);
     }
-    if (L.act != TP_ACT_NONE) {
+    // act'(z) is kept for the backward pass -- except for a ReLU whose output the stage keeps anyway as the next
+    // layer's input: relu'(z) = (output > 0).  Not for the last layer (its output goes to the caller) and not in
+    // front of a residual add (the add may be formed in this layer's kernel, the bare output then never exists).
+    const bool next_is_add = l + 1 < d->num_layers && d->layers[l + 1].type == TP_LAYER_RESIDUAL && d->layers[l + 1].geom[1] == 1;
+    lp.relu_out = L.act == TP_ACT_RELU && l + 1 < d->num_layers && !next_is_add;
+    if (L.act != TP_ACT_NONE && !lp.relu_out) {
       lp.z_off = act;
       act += round_up(rows * lp.out_elems * p->elt_size, 256);
     } else {
@@ -806,16 +812,24 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
       const bool to_caller = l == 0;
       const bool no_dx = to_caller && !d.needs_dx;
       if (no_dx && (lp.d.type == TP_LAYER_MAXPOOL2 || lp.d.type == TP_LAYER_SUBSAMPLE2 || lp.d.type == TP_LAYER_ATTENTION)) break;
+      // what the gradient w.r.t. this layer's input is multiplied with: the saved act'(z) of the previous layer, or
+      // (dmask = 1) that layer's saved ReLU output, which is this layer's own saved input
       const void* dprev = nullptr;
+      int dmask = 0;
       if (l > 0) {
         const LayerPlan& prev = st->plan.layers[l - 1];
-        dprev = prev.z_off == UINT64_MAX ? nullptr : aslot + prev.z_off;
+        if (prev.z_off != UINT64_MAX) {
+          dprev = aslot + prev.z_off;
+        } else if (prev.relu_out) {
+          dprev = aslot + lp.x_off;
+          dmask = 1;
+        }
       }
       void* dst = to_caller && !no_dx ? dx_dev : scratch_for(dz);
       auto through_activation = [&](void* grad) -> int {  // dz_prev = dx (.) act'(z_prev), in place
         if (!dprev) return TP_OK;
         ProfScope ps(st, TP_K_ACT_BWD);
-        HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * lp.in_elems, grad, dprev, grad));
+        HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * lp.in_elems, grad, dprev, grad, dmask));
         return TP_OK;
       };
       if (lp.d.type == TP_LAYER_MAXPOOL2) {
@@ -845,7 +859,7 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
         if (dprev) {
           void* buf = scratch_for(main_grad);  // not the one just set aside, not the one read
           ProfScope ps(st, TP_K_ACT_BWD);
-          HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * lp.in_elems, main_grad, dprev, buf));
+          HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * lp.in_elems, main_grad, dprev, buf, dmask));
           main_grad = buf;
         }
         dz = main_grad;
@@ -856,7 +870,7 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
           pinned = dz;
           if (dprev) {
             ProfScope ps(st, TP_K_ACT_BWD);
-            HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * lp.in_elems, dz, dprev, dst));
+            HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * lp.in_elems, dz, dprev, dst, dmask));
             dz = dst;
           }
           continue;
@@ -963,10 +977,10 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
         ProfScope ps(st, TP_K_DGRAD);
         if (lp.d.type == TP_LAYER_DENSE)
           HIP_TRY(tp::launch_dgrad(st->stream, d.dtype, grad_rows, lp.d.out_features, lp.d.in_features, dz, wb + lp.w_off * es,
-                                   dprev, dst));
+                                   dprev, dst, dmask));
         else
           HIP_TRY(tp::launch_conv_dgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.geom[3], lp.d.in_features,
-                                        lp.d.out_features, dz, wb + lp.w_off * es, dprev, dst, st->zeros()));
+                                        lp.d.out_features, dz, wb + lp.w_off * es, dprev, dst, st->zeros(), dmask));
       }
       dz = dst;
     }
