@@ -43,7 +43,8 @@ def parse():
                     help="mlp: interior stage of the width-4096 GELU MLP (the configuration the metric is quoted on); "
                          "vgg: stage 0 of the VGG-16-style net on 32x32x3 images (implicit-GEMM convolutions); "
                          "tfm: interior stage of the decoder-only transformer (4 blocks, d_model 2048, 1024 tokens); "
-                         "bneck: the conv4_x group of the ResNet-50-style net (six bottlenecks, 8x8 -> 4x4 maps)")
+                         "bneck: the conv4_x group of the ResNet-50-style net (six bottlenecks, 8x8 -> 4x4 maps; "
+                         "--stage 1: its conv3_x group, four bottlenecks, 16x16 -> 8x8)")
     ap.add_argument("--blocks", type=int, default=4, help="transformer blocks in the tfm stage")
     ap.add_argument("--stage", type=int, default=None)
     ap.add_argument("--width", type=int, default=4096)
@@ -151,7 +152,7 @@ def cpu_baseline(w, s, policy, minibatches):
     if w.name.startswith("tfm"):
         w = replace(w, mb=1, n=1)
         minibatches = 1
-    if w.name.startswith("bneck"):
+    if w.name.startswith("resnet"):
         minibatches = 1
     import numpy as np
     from oracle.stage import Stage
@@ -226,13 +227,15 @@ def main():
         what = ("stage 0 (conv3-64, conv3-64, pool, conv3-128, conv3-128, pool; ReLU) of the 4-stage VGG-16-style "
                 "net on 32x32x3 images")
     elif args.workload == "bneck":
-        w = W.bottleneck_stage(blocks=5, mb=args.mb or 128, n=args.n or 4, down=True)
-        s = 1
-        if args.stage not in (None, 1):
-            sys.exit("bench.py: the bneck workload describes stage 1 only")
-        what = ("stage 1 (the conv4_x group: first bottleneck 512 -> 1024 channels with the 3x3 at stride 2, 8x8 -> 4x4 "
-                "feature maps, and a projection shortcut, then five identity bottlenecks 1024-256-256-1024; batch "
-                "normalisation per micro-batch, ReLU) of the 4-stage ResNet-50-style net on 64x64x3 images")
+        w = W.resnet_middle_stages(mb=args.mb or 128, n=args.n or 4)
+        s = 2 if args.stage is None else args.stage
+        if s not in (1, 2):
+            sys.exit("bench.py: the bneck workload describes stages 1 (conv3_x) and 2 (conv4_x) only")
+        what = ("stage 2 (the conv4_x group: first bottleneck 512 -> 1024 channels with the 3x3 at stride 2, 8x8 -> 4x4 "
+                "feature maps, and a projection shortcut, then five identity bottlenecks 1024-256-256-1024" if s == 2 else
+                "stage 1 (the conv3_x group: first bottleneck 256 -> 512 channels with the 3x3 at stride 2, 16x16 -> 8x8 "
+                "feature maps, and a projection shortcut, then three identity bottlenecks 512-128-128-512")
+        what += ("; batch normalisation per micro-batch, ReLU) of the 4-stage ResNet-50-style net on 64x64x3 images")
     else:
         w = W.transformer_stage(layers=args.blocks, mb=args.mb or 8, n=args.n or 4)
         s = 1

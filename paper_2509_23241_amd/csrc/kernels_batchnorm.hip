@@ -1,9 +1,10 @@
 // Batch normalisation (training mode) and the residual add with activation of the bottleneck-shaped stage.
 // Two families.  Streaming kernels (any type and size): column statistics are formed by blocks of 64 columns x
 // a chunk of rows (lanes along the columns: every row read is one contiguous segment), block partials are
-// added in a fixed order by the shared partial-sum kernel; x is read three times in the forward pass and twice
-// in the backward pass.  Slab kernels (bf16, up to 8192 rows forward / 2048 backward -- what fits the register
-// file without spilling): one launch per layer, the values stay in registers between the passes.
+// added in a fixed order by the shared partial-sum kernel; mean and variance come from one pass over x (sums
+// of x - x[0][c] and of its square), so x is read twice in the forward pass and twice in the backward pass; the
+// backward pass takes all micro-batches of a mini-batch in the same three launches.  Slab kernels (bf16, up to 2048 rows per micro-batch): one launch per layer, the values
+// stay in registers between the passes; above that size the streaming kernels are faster.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -23,8 +24,11 @@ constexpr float kBnEps = 1e-5f;
 inline int bn_chunk_rows(size_t rows) { return (int)std::max<size_t>(16, (rows + 255) / 256); }
 inline int bn_chunks(size_t rows) { return (int)((rows + bn_chunk_rows(rows) - 1) / bn_chunk_rows(rows)); }
 
-// MODE 0: sum x          MODE 1: sum (x - mean)^2, mean = totals[c] / rows
+// MODE 0: sum d and sum d^2 with d = x - x[0][c] (out[0..C), out[C..2C)): mean and variance from ONE pass; the shift by the
+//         channel's first value keeps the subtraction var = E[d^2] - E[d]^2 away from cancellation
 // MODE 2: sum dy * xhat (out[0..C)) and sum dy (out[C..2C)), xhat from stats
+// blockIdx.z = segment (micro-batch) q: rows [q*rows, (q+1)*rows), statistics aux[q][2C]; the partial sums of row chunk k
+// go to partial[(k*nseg + q)][2C], so that one strided sum over k finishes all segments.
 template <typename T, int MODE>
 __global__ __launch_bounds__(kThreads) void bn_colsum_kernel(size_t rows, int C, int chunk_rows, const T* __restrict__ x,
                                                              const T* __restrict__ dy, const float* __restrict__ aux,
@@ -32,17 +36,22 @@ __global__ __launch_bounds__(kThreads) void bn_colsum_kernel(size_t rows, int C,
   __shared__ float sm[2][4][64];
   const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + cl;
+  const size_t seg = blockIdx.z, nseg = gridDim.z;
+  x += seg * rows * C;
+  if (MODE == 2) { dy += seg * rows * C; aux += seg * 2 * C; }
   const size_t r0 = (size_t)blockIdx.y * chunk_rows;
   const size_t r1 = std::min(rows, r0 + chunk_rows);
   float s0 = 0.f, s1 = 0.f;
   if (c < C) {
     float mean = 0.f, rstd = 0.f;
-    if (MODE == 1) mean = aux[c] / (float)rows;
+    if (MODE == 0) mean = to_float(x[c]);
     if (MODE == 2) { mean = aux[2 * c]; rstd = aux[2 * c + 1]; }
     for (size_t r = r0 + rl; r < r1; r += 4) {
       const float v = to_float(x[r * C + c]);
-      if (MODE == 0) s0 += v;
-      if (MODE == 1) s0 += (v - mean) * (v - mean);
+      if (MODE == 0) {
+        s0 += v - mean;
+        s1 = fmaf(v - mean, v - mean, s1);
+      }
       if (MODE == 2) {
         const float g = to_float(dy[r * C + c]);
         s0 += g * (v - mean) * rstd;
@@ -54,50 +63,71 @@ __global__ __launch_bounds__(kThreads) void bn_colsum_kernel(size_t rows, int C,
   sm[1][rl][cl] = s1;
   __syncthreads();
   if (rl == 0 && c < C) {
-    const size_t width = MODE == 2 ? 2 * (size_t)C : (size_t)C;
-    partial[blockIdx.y * width + c] = sm[0][0][cl] + sm[0][1][cl] + sm[0][2][cl] + sm[0][3][cl];
-    if (MODE == 2) partial[blockIdx.y * width + C + c] = sm[1][0][cl] + sm[1][1][cl] + sm[1][2][cl] + sm[1][3][cl];
+    float* out = partial + ((size_t)blockIdx.y * nseg + seg) * 2 * C;
+    out[c] = sm[0][0][cl] + sm[0][1][cl] + sm[0][2][cl] + sm[0][3][cl];
+    out[C + c] = sm[1][0][cl] + sm[1][1][cl] + sm[1][2][cl] + sm[1][3][cl];
   }
+}
+
+// sums[0..C) = sum d, sums[C..2C) = sum d^2 (d = x - x[0][c])  ->  stats[2c] = mean, stats[2c+1] = 1/sqrt(var + eps)
+template <typename T>
+__global__ __launch_bounds__(kThreads) void bn_finalize_kernel(size_t rows, int C, const T* __restrict__ x,
+                                                               const float* __restrict__ sums, float* __restrict__ stats) {
+  const int c = blockIdx.x * kThreads + threadIdx.x;
+  if (c >= C) return;
+  const float inv = 1.f / (float)rows;
+  const float md = sums[c] * inv;
+  const float var = fmaxf(sums[C + c] * inv - md * md, 0.f);
+  stats[2 * c] = to_float(x[c]) + md;
+  stats[2 * c + 1] = rsqrtf(var + kBnEps);
 }
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void bn_normalize_kernel(size_t rows, int C, const T* __restrict__ x,
-                                                                const float* __restrict__ sum_x, const float* __restrict__ sum_sq,
+                                                                const float* __restrict__ stats,
                                                                 const float* __restrict__ gamma, const float* __restrict__ beta,
-                                                                int act, T* __restrict__ a_out, T* __restrict__ d_out,
-                                                                float* __restrict__ stats) {
+                                                                int act, T* __restrict__ a_out, T* __restrict__ d_out) {
   const size_t total = rows * C;
   const size_t stride = (size_t)gridDim.x * kThreads;
   for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
     const int c = (int)(i % C);
-    const float mean = sum_x[c] / (float)rows;
-    const float rstd = rsqrtf(sum_sq[c] / (float)rows + kBnEps);
-    const float z = fmaf((to_float(x[i]) - mean) * rstd, gamma[c], beta[c]);
+    const float z = fmaf((to_float(x[i]) - stats[2 * c]) * stats[2 * c + 1], gamma[c], beta[c]);
     a_out[i] = from_float<T>(act_forward(z, act));
     if (d_out) d_out[i] = from_float<T>(act_derivative(z, act));
-    if (i < (size_t)C) {  // the first row's threads also record the statistics
-      stats[2 * c] = mean;
-      stats[2 * c + 1] = rstd;
-    }
   }
 }
 
+// all segments at once: element i belongs to segment i / (rows*C)
 template <typename T>
-__global__ __launch_bounds__(kThreads) void bn_dx_kernel(size_t rows, int C, const T* __restrict__ dy, const T* __restrict__ x,
+__global__ __launch_bounds__(kThreads) void bn_dx_kernel(size_t rows, int C, size_t nseg, const T* __restrict__ dy, const T* __restrict__ x,
                                                          const float* __restrict__ stats, const float* __restrict__ sums,
                                                          const float* __restrict__ gamma_s, const float* __restrict__ gamma_l,
                                                          float alpha, float beta_c, T* __restrict__ dx) {
-  const size_t total = rows * C;
+  const size_t per = rows * C, total = per * nseg;
   const size_t stride = (size_t)gridDim.x * kThreads;
   const float inv_rows = 1.f / (float)rows;
   for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+    const size_t q = i / per;
     const int c = (int)(i % C);
-    const float mean = stats[2 * c], rstd = stats[2 * c + 1];
+    const float* st = stats + q * 2 * C;
+    const float* sq = sums + q * 2 * C;
+    const float mean = st[2 * c], rstd = st[2 * c + 1];
     const float g = fmaf(alpha, gamma_s[c], beta_c * gamma_l[c]);
     const float xh = (to_float(x[i]) - mean) * rstd;
-    dx[i] = from_float<T>(g * rstd * (to_float(dy[i]) - (sums[C + c] + xh * sums[c]) * inv_rows));
+    dx[i] = from_float<T>(g * rstd * (to_float(dy[i]) - (sq[C + c] + xh * sq[c]) * inv_rows));
   }
 }
+
+// bf16, C a multiple of 8: the two elementwise kernels with 16 bytes per lane
+__global__ __launch_bounds__(kThreads) void bn_normalize_vec_kernel(size_t rows, int C, const uint16_t* __restrict__ x,
+                                                                    const float* __restrict__ stats,
+                                                                    const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                                    int act, uint16_t* __restrict__ a_out, uint16_t* __restrict__ d_out);
+__global__ __launch_bounds__(kThreads) void bn_dx_vec_kernel(size_t rows, int C, size_t nseg, const uint16_t* __restrict__ dy,
+                                                             const uint16_t* __restrict__ x, const float* __restrict__ stats,
+                                                             const float* __restrict__ sums, const float* __restrict__ gamma_s,
+                                                             const float* __restrict__ gamma_l, float alpha, float beta_c,
+                                                             uint16_t* __restrict__ dx);
 
 // ---- slab kernels (bf16, small layers) -----------------------------------------------------------------
 // One workgroup of 1024 lanes owns 8 adjacent channels (one 16-byte unit per row) for ALL rows the
@@ -152,6 +182,57 @@ __device__ __forceinline__ void unpack8(const uint4& u, float (&f)[8]) {
 }
 __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
   return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+}
+
+__global__ __launch_bounds__(kThreads) void bn_normalize_vec_kernel(size_t rows, int C, const uint16_t* __restrict__ x,
+                                                                    const float* __restrict__ stats,
+                                                                    const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                                    int act, uint16_t* __restrict__ a_out, uint16_t* __restrict__ d_out) {
+  const size_t nvec = rows * C / 8;
+  const int cv = C / 8;
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
+    const int c0 = (int)(i % cv) * 8;
+    float f[8], a[8], d[8];
+    unpack8(reinterpret_cast<const uint4*>(x)[i], f);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float z = fmaf((f[j] - stats[2 * (c0 + j)]) * stats[2 * (c0 + j) + 1], gamma[c0 + j], beta[c0 + j]);
+      a[j] = act_forward(z, act);
+      d[j] = act_derivative(z, act);
+    }
+    reinterpret_cast<uint4*>(a_out)[i] = pack8(a);
+    if (d_out) reinterpret_cast<uint4*>(d_out)[i] = pack8(d);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void bn_dx_vec_kernel(size_t rows, int C, size_t nseg, const uint16_t* __restrict__ dy,
+                                                             const uint16_t* __restrict__ x, const float* __restrict__ stats,
+                                                             const float* __restrict__ sums, const float* __restrict__ gamma_s,
+                                                             const float* __restrict__ gamma_l, float alpha, float beta_c,
+                                                             uint16_t* __restrict__ dx) {
+  const size_t per = rows * C / 8, nvec = per * nseg;
+  const int cv = C / 8;
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  const float inv_rows = 1.f / (float)rows;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
+    const size_t q = i / per;
+    const int c0 = (int)(i % cv) * 8;
+    const float* st = stats + q * 2 * C;
+    const float* sq = sums + q * 2 * C;
+    float fx[8], fd[8], o[8];
+    unpack8(reinterpret_cast<const uint4*>(x)[i], fx);
+    unpack8(reinterpret_cast<const uint4*>(dy)[i], fd);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int c = c0 + j;
+      const float rstd = st[2 * c + 1];
+      const float g = fmaf(alpha, gamma_s[c], beta_c * gamma_l[c]);
+      const float xh = (fx[j] - st[2 * c]) * rstd;
+      o[j] = g * rstd * (fd[j] - (sq[C + c] + xh * sq[c]) * inv_rows);
+    }
+    reinterpret_cast<uint4*>(dx)[i] = pack8(o);
+  }
 }
 
 template <int NL>
@@ -301,43 +382,51 @@ __global__ __launch_bounds__(kThreads) void add_act_kernel(size_t count, const T
 
 inline unsigned stream_grid(size_t count) { return (unsigned)std::min<size_t>(std::max<size_t>((count + kThreads - 1) / kThreads, 1), 8192); }
 
+inline bool vec_ok(int es, int C, const void* p0, const void* p1, const void* p2) {
+  return es == 2 && C % 8 == 0 && ((((uintptr_t)p0 | (uintptr_t)p1 | (uintptr_t)p2) & 15) == 0);
+}
+
+// scratch: [chunks][2C] partial sums, then [2C] totals
 template <typename T>
 hipError_t bn_fwd_typed(hipStream_t s, size_t rows, int C, const T* x, const float* gamma, const float* beta, int act, T* a_out,
                         T* d_out, float* stats, float* scratch) {
   const int cr = bn_chunk_rows(rows), chunks = bn_chunks(rows);
-  float* partial = scratch;                          // [chunks][C]
-  float* sum_x = scratch + (size_t)chunks * 2 * C;   // [C]
-  float* sum_sq = sum_x + C;                         // [C]
-  const dim3 grid((C + 63) / 64, chunks);
-  hipLaunchKernelGGL((bn_colsum_kernel<T, 0>), grid, dim3(kThreads), 0, s, rows, C, cr, x, (const T*)nullptr, (const float*)nullptr,
-                     partial);
+  float* partial = scratch;
+  float* totals = scratch + (size_t)chunks * 2 * C;
+  hipLaunchKernelGGL((bn_colsum_kernel<T, 0>), dim3((C + 63) / 64, chunks, 1), dim3(kThreads), 0, s, rows, C, cr, x, (const T*)nullptr,
+                     (const float*)nullptr, partial);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  e = launch_sum_partials(s, (size_t)C, chunks, partial, sum_x);
+  e = launch_sum_partials(s, 2 * (size_t)C, chunks, partial, totals);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((bn_colsum_kernel<T, 1>), grid, dim3(kThreads), 0, s, rows, C, cr, x, (const T*)nullptr, (const float*)sum_x,
-                     partial);
+  hipLaunchKernelGGL(bn_finalize_kernel<T>, dim3((C + kThreads - 1) / kThreads), dim3(kThreads), 0, s, rows, C, x, totals, stats);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  e = launch_sum_partials(s, (size_t)C, chunks, partial, sum_sq);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(bn_normalize_kernel<T>, dim3(stream_grid(rows * C)), dim3(kThreads), 0, s, rows, C, x, sum_x, sum_sq, gamma, beta,
-                     act, a_out, d_out, stats);
+  if (vec_ok(sizeof(T), C, x, a_out, d_out))
+    hipLaunchKernelGGL(bn_normalize_vec_kernel, dim3(stream_grid(rows * C / 8)), dim3(kThreads), 0, s, rows, C, (const uint16_t*)x, stats,
+                       gamma, beta, act, (uint16_t*)a_out, (uint16_t*)d_out);
+  else
+    hipLaunchKernelGGL(bn_normalize_kernel<T>, dim3(stream_grid(rows * C)), dim3(kThreads), 0, s, rows, C, x, stats, gamma, beta, act,
+                       a_out, d_out);
   return hipGetLastError();
 }
 
+// all nseg segments in three launches; scratch: [chunks][nseg][2C] partial sums; sums: [nseg][2C]
 template <typename T>
-hipError_t bn_bwd_typed(hipStream_t s, size_t rows, int C, const T* dy, const T* x, const float* stats, const float* gamma_s,
+hipError_t bn_bwd_typed(hipStream_t s, size_t rows, int C, int nseg, const T* dy, const T* x, const float* stats, const float* gamma_s,
                         const float* gamma_l, float alpha, float beta_c, T* dx, float* sums, float* scratch) {
   const int cr = bn_chunk_rows(rows), chunks = bn_chunks(rows);
-  const dim3 grid((C + 63) / 64, chunks);
-  hipLaunchKernelGGL((bn_colsum_kernel<T, 2>), grid, dim3(kThreads), 0, s, rows, C, cr, x, dy, stats, scratch);
+  hipLaunchKernelGGL((bn_colsum_kernel<T, 2>), dim3((C + 63) / 64, chunks, nseg), dim3(kThreads), 0, s, rows, C, cr, x, dy, stats, scratch);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  e = launch_sum_partials(s, 2 * (size_t)C, chunks, scratch, sums);
+  e = launch_sum_partials(s, (size_t)nseg * 2 * C, chunks, scratch, sums);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(bn_dx_kernel<T>, dim3(stream_grid(rows * C)), dim3(kThreads), 0, s, rows, C, dy, x, stats, sums, gamma_s, gamma_l,
-                     alpha, beta_c, dx);
+  if (vec_ok(sizeof(T), C, x, dy, dx))
+    hipLaunchKernelGGL(bn_dx_vec_kernel, dim3(stream_grid(rows * C / 8 * nseg)), dim3(kThreads), 0, s, rows, C, (size_t)nseg,
+                       (const uint16_t*)dy, (const uint16_t*)x, stats, sums, gamma_s, gamma_l, alpha, beta_c, (uint16_t*)dx);
+  else
+    hipLaunchKernelGGL(bn_dx_kernel<T>, dim3(stream_grid(rows * C * nseg)), dim3(kThreads), 0, s, rows, C, (size_t)nseg, dy, x, stats, sums,
+                       gamma_s, gamma_l, alpha, beta_c, dx);
   return hipGetLastError();
 }
 
@@ -350,7 +439,7 @@ inline int slab_loads(size_t rows, int max_loads) {
 
 }  // namespace
 
-size_t batchnorm_scratch_floats(size_t rows, int C) { return ((size_t)bn_chunks(rows) * 2 + 2) * C; }
+size_t batchnorm_scratch_floats(size_t rows, int C, int nseg) { return ((size_t)bn_chunks(rows) * std::max(nseg, 1) + 1) * 2 * C; }
 
 bool batchnorm_fused_bwd_supported(int elt, size_t rows, int C) {
   return elt == ELT_BF16 && C % 8 == 0 && rows >= 1 && slab_loads(rows, 2) != 0 && rows * C < (1ull << 31);
@@ -370,8 +459,11 @@ hipError_t launch_batchnorm_bwd_fused(hipStream_t s, int elt, size_t rows, int C
   return hipGetLastError();
 }
 
+#ifndef TP_BN_SLAB_FWD_LOADS
+#define TP_BN_SLAB_FWD_LOADS 2  // forward slab kernels up to 2048 rows; beyond that the streaming kernels are faster
+#endif
 bool batchnorm_fwd_add_supported(int elt, size_t rows, int C) {
-  return elt == ELT_BF16 && C % 8 == 0 && rows >= 1 && slab_loads(rows, 8) != 0 && rows * C < (1ull << 31);
+  return elt == ELT_BF16 && C % 8 == 0 && rows >= 1 && slab_loads(rows, TP_BN_SLAB_FWD_LOADS) != 0 && rows * C < (1ull << 31);
 }
 
 hipError_t launch_batchnorm_fwd(hipStream_t s, int elt, size_t rows, int C, const void* x, const float* gamma, const float* beta,
@@ -381,7 +473,7 @@ hipError_t launch_batchnorm_fwd(hipStream_t s, int elt, size_t rows, int C, cons
 #define TP_BN_FWD(NL)                                                                                                    \
   hipLaunchKernelGGL(bn_fwd_slab_kernel<NL>, dim3(C / 8), dim3(kSlabThreads), 0, s, (int)rows, C, (const uint16_t*)x, gamma, \
                      beta, act, (const uint16_t*)addend, (uint16_t*)a_out, (uint16_t*)d_out, stats)
-    switch (slab_loads(rows, 8)) {
+    switch (slab_loads(rows, TP_BN_SLAB_FWD_LOADS)) {
       case 1: TP_BN_FWD(1); break;
       case 2: TP_BN_FWD(2); break;
       case 4: TP_BN_FWD(4); break;
@@ -395,14 +487,15 @@ hipError_t launch_batchnorm_fwd(hipStream_t s, int elt, size_t rows, int C, cons
   return bn_fwd_typed<float>(s, rows, C, (const float*)x, gamma, beta, act, (float*)a_out, (float*)d_out, stats, scratch);
 }
 
-hipError_t launch_batchnorm_bwd(hipStream_t s, int elt, size_t rows, int C, const void* dy, const void* x, const float* stats,
+hipError_t launch_batchnorm_bwd(hipStream_t s, int elt, size_t rows, int C, int nseg, const void* dy, const void* x, const float* stats,
                                 const float* gamma_s, const float* gamma_l, float alpha, float beta_c, void* dx, float* sums,
                                 float* scratch) {
+  if (nseg < 1 || nseg > 65535) return hipErrorInvalidValue;
   if (elt == ELT_BF16)
-    return bn_bwd_typed<uint16_t>(s, rows, C, (const uint16_t*)dy, (const uint16_t*)x, stats, gamma_s, gamma_l, alpha, beta_c,
+    return bn_bwd_typed<uint16_t>(s, rows, C, nseg, (const uint16_t*)dy, (const uint16_t*)x, stats, gamma_s, gamma_l, alpha, beta_c,
                                   (uint16_t*)dx, sums, scratch);
-  return bn_bwd_typed<float>(s, rows, C, (const float*)dy, (const float*)x, stats, gamma_s, gamma_l, alpha, beta_c, (float*)dx, sums,
-                             scratch);
+  return bn_bwd_typed<float>(s, rows, C, nseg, (const float*)dy, (const float*)x, stats, gamma_s, gamma_l, alpha, beta_c, (float*)dx,
+                             sums, scratch);
 }
 
 hipError_t launch_add_act(hipStream_t s, int elt, size_t count, const void* a, const void* b, int act, void* out, void* d_out) {

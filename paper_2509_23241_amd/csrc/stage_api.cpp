@@ -223,7 +223,7 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
       lp.in_elems = lp.out_elems = (uint64_t)lp.tokens * L.in_features;
       lp.w_elems = L.in_features;
       lp.stat_bytes = (uint64_t)d->n * 2 * L.in_features * 4;   // (mean, 1/std) per channel and micro-batch
-      norm_scratch = std::max<uint64_t>(norm_scratch, tp::batchnorm_scratch_floats((size_t)d->mb * lp.tokens, L.in_features) +
+      norm_scratch = std::max<uint64_t>(norm_scratch, tp::batchnorm_scratch_floats((size_t)d->mb * lp.tokens, L.in_features, d->n) +
                                                           (uint64_t)d->n * 2 * L.in_features);
     } else if (L.type == TP_LAYER_ATTENTION) {
       lp.tokens = L.geom[0];
@@ -916,22 +916,17 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
         const float* gl = st->ring(slot_now) + lp.w_off;
         const float* gs = delta != 0 ? st->ring(slot_f) + lp.w_off : gl;
         const size_t seg_rows = (size_t)d.mb * lp.tokens;        // the statistics belong to one micro-batch
-        const size_t seg_bytes = seg_rows * C * es;
-        const size_t bn_scratch = tp::batchnorm_scratch_floats(seg_rows, C);
+        const size_t bn_scratch = tp::batchnorm_scratch_floats(seg_rows, C, d.n);
         float* sums = st->partials() + bn_scratch;                // [n][2*C]
         {
           ProfScope ps(st, TP_K_NORM);
-          if (tp::batchnorm_fused_bwd_supported(d.dtype, seg_rows, C)) {
+          if (tp::batchnorm_fused_bwd_supported(d.dtype, seg_rows, C))
             HIP_TRY(tp::launch_batchnorm_bwd_fused(st->stream, d.dtype, seg_rows, C, d.n, dz, aslot + lp.x_off,
                                                    (const float*)(aslot + lp.stat_off), gs, gl, (float)ca, (float)cb, dst, sums));
-          } else {
-            for (int ub = 0; ub < d.n; ++ub)
-              HIP_TRY(tp::launch_batchnorm_bwd(st->stream, d.dtype, seg_rows, C, (const char*)dz + ub * seg_bytes,
-                                               aslot + lp.x_off + ub * seg_bytes,
-                                               (const float*)(aslot + lp.stat_off) + (size_t)ub * 2 * C, gs, gl, (float)ca,
-                                               (float)cb, (char*)dst + ub * seg_bytes, sums + (size_t)ub * 2 * C,
-                                               st->partials()));
-          }
+          else
+            HIP_TRY(tp::launch_batchnorm_bwd(st->stream, d.dtype, seg_rows, C, d.n, dz, aslot + lp.x_off,
+                                             (const float*)(aslot + lp.stat_off), gs, gl, (float)ca, (float)cb, dst, sums,
+                                             st->partials()));
           HIP_TRY(tp::launch_sum_partials_strided(st->stream, (size_t)C, d.n, sums, 2 * (size_t)C, g + lp.w_off));
           HIP_TRY(tp::launch_sum_partials_strided(st->stream, (size_t)C, d.n, sums + C, 2 * (size_t)C, g + lp.b_off));
         }

@@ -339,6 +339,15 @@ def bottleneck_stage(c: int = 1024, mid: int = 256, h: int = 4, w: int = 4, bloc
     return Workload(name=f"bneck{c}x{tag}_{dtype}_s1", dtype=dtype, stages=((), layers, (), ()), mb=mb, n=n, classes=2)
 
 
+def resnet_middle_stages(mb: int = 128, n: int = 4, dtype: str = "bf16") -> Workload:
+    """The two middle stages of a 4-stage split of a ResNet-50-style net on 64x64 inputs: stage 1 = the conv3_x
+    group ([16, 16, 256] -> [8, 8, 512], four bottlenecks with 128 middle channels), stage 2 = the conv4_x group
+    ([8, 8, 512] -> [4, 4, 1024], six bottlenecks with 256 middle channels).  Stages 0 and 3 are not described."""
+    conv3 = bottleneck_stage(c=512, mid=128, h=8, w=8, blocks=3, mb=mb, n=n, dtype=dtype, down=True).stages[1]
+    conv4 = bottleneck_stage(c=1024, mid=256, h=4, w=4, blocks=5, mb=mb, n=n, dtype=dtype, down=True).stages[1]
+    return Workload(name=f"resnet_mid_{dtype}", dtype=dtype, stages=((), conv3, conv4, ()), mb=mb, n=n, classes=2)
+
+
 def transformer_block(d: int, heads: int, ffn: int, tokens: int) -> tuple:
     """Pre-norm decoder block: x + proj(attn(qkv(LN(x)))), then x + ffn2(gelu(ffn1(LN(x))))."""
     return (Residual(d, tokens, "begin"), LayerNorm(d, tokens), Dense(d, 3 * d, "none", tokens=tokens),

@@ -59,6 +59,18 @@ def test_bottleneck_down_block_full_geometry():
     print(f"{time.time() - t0:.1f} s", worst)
 
 
+@pytest.mark.timeout(900)
+def test_conv3_group_first_block_full_geometry():
+    # the first block of the conv3_x group at its real geometry: [16, 16, 256] -> [8, 8, 512] with 128 middle
+    # channels (32768 rows per micro-batch in front of the stride: the streaming normalisation kernels), one
+    # identity block behind it
+    w = W.bottleneck_stage(c=512, mid=128, h=8, w=8, blocks=1, down=True)
+    t0 = time.time()
+    worst = _run_stage(w.stages[1], "conv3_down_full", "bf16", mb=w.mb, n=w.n, policy="convex", depth=3, minibatches=2,
+                       needs_dx=True, lr=2e-4)
+    print(f"{time.time() - t0:.1f} s", worst)
+
+
 @pytest.mark.timeout(1200)
 def test_transformer_block_full_geometry_sampled_sequences():
     """One of the four identical blocks of the transformer stage at its real geometry (d_model 2048, 16 heads
