@@ -442,9 +442,13 @@ bool mfma_wgrad_supported(int M, int N, int K) { return M >= 1 && N % 8 == 0 && 
 
 hipError_t mfma_fprop(hipStream_t s, int M, int N, int K, const uint16_t* x, const uint16_t* W, const float* bias,
                       int act, uint16_t* d_out, uint16_t* a_out, uint16_t* x_copy, const uint16_t* addend) {
-  EpiFprop e{bias, d_out, a_out, act, N, addend};
   // x is [M x K] with K % 8 == 0 and 16-byte aligned rows, so it is a whole number of 16-byte units
   SideCopy side{(const uint4*)x, (uint4*)x_copy, x_copy ? (size_t)M * K / 8 : 0};
+  if (addend) {
+    EpiFpropAdd e{bias, d_out, a_out, act, N, addend};
+    TP_GEMM_DISPATCH(pick(M, N, K, K, K, false, false, g_cfg[0]), false, false, s, M, N, K, x, K, W, K, e, side)
+  }
+  EpiFprop e{bias, d_out, a_out, act, N};
   TP_GEMM_DISPATCH(pick(M, N, K, K, K, false, false, g_cfg[0]), false, false, s, M, N, K, x, K, W, K, e, side)
 }
 

@@ -22,9 +22,12 @@ typedef short shortx8 __attribute__((ext_vector_type(8)));
 // that each lane ends up with 4 consecutive COLUMNS n..n+3 of one output row m and can load and
 // store 8 contiguous bytes without a trip through LDS.  fp32 output (wgrad) keeps the plain
 // orientation, where the 32 lanes of a half wave already cover 128 contiguous bytes.
-struct EpiFprop {
+// ADD: the epilogue also adds `addend` (an [M x ldc] tensor: the residual add that follows the layer) to the rounded
+// activation; a type of its own so that the plain forward GEMM carries none of it.
+template <bool ADD>
+struct EpiFpropT {
   const float* bias; uint16_t* d_out; uint16_t* a_out; int act; int ldc;  // d_out: act'(z) for the backward, or null
-  const uint16_t* addend = nullptr;  // [M x ldc] tensor added to the rounded activation (a residual add that follows), or null
+  const uint16_t* addend = nullptr;
   static constexpr bool kSwap = true;
   // 8 consecutive columns n..n+7 of row m (n and ldc multiples of 8)
   __device__ __forceinline__ void row8(int m, int n, float (&v)[8]) const {
@@ -38,7 +41,7 @@ struct EpiFprop {
       a[j] = p.a;
       d[j] = p.d;
     }
-    if (addend) {
+    if constexpr (ADD) {
       const uint4 u = *reinterpret_cast<const uint4*>(addend + i);
       const uint32_t w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
@@ -55,7 +58,7 @@ struct EpiFprop {
   }
   __device__ __forceinline__ void quad(int m, int n, int count, float v0, float v1, float v2, float v3) const {
     const size_t i = (size_t)m * ldc + n;
-    if (count == 4 && (ldc & 3) == 0 && !addend) {
+    if (count == 4 && (ldc & 3) == 0 && !ADD) {
       const float4 b = *reinterpret_cast<const float4*>(bias + n);
       const ActPair p0 = act_pair_fast(v0 + b.x, act), p1 = act_pair_fast(v1 + b.y, act);
       const ActPair p2 = act_pair_fast(v2 + b.z, act), p3 = act_pair_fast(v3 + b.w, act);
@@ -66,11 +69,13 @@ struct EpiFprop {
       for (int j = 0; j < count; ++j) {
         const ActPair p = act_pair_fast(v[j] + bias[n + j], act);
         if (d_out) d_out[i + j] = float_to_bf16(p.d);
-        a_out[i + j] = addend ? float_to_bf16(bf16_to_float(float_to_bf16(p.a)) + bf16_to_float(addend[i + j])) : float_to_bf16(p.a);
+        a_out[i + j] = ADD ? float_to_bf16(bf16_to_float(float_to_bf16(p.a)) + bf16_to_float(addend[i + j])) : float_to_bf16(p.a);
       }
     }
   }
 };
+using EpiFprop = EpiFpropT<false>;
+using EpiFpropAdd = EpiFpropT<true>;
 struct EpiDgrad {
   const uint16_t* d_prev; uint16_t* out; int ldc;  // d_prev: saved act'(z) of the previous layer, or null
   int relu_mask = 0;  // 1: d_prev holds the previous layer's ReLU OUTPUT instead; its derivative is (output > 0)
