@@ -47,7 +47,7 @@ __global__ __launch_bounds__(kThreads) void conv_simt_kernel(ConvGeom g, const T
                                                              const T* __restrict__ wgt_or_dz, const float* __restrict__ bias,
                                                              int act, const T* __restrict__ d_prev, T* __restrict__ d_out,
                                                              T* __restrict__ out, float* __restrict__ partial,
-                                                             int pixels_per_split) {
+                                                             int pixels_per_split, int relu_mask) {
   __shared__ float As[BK][BM + 4];
   __shared__ float Bs[BK][BN + 4];
   const int Pin = g.imgs * g.H * g.W, Pout = g.imgs * g.Ho * g.Wo;
@@ -135,9 +135,9 @@ __global__ __launch_bounds__(kThreads) void conv_simt_kernel(ConvGeom g, const T
         if (d_out) d_out[idx] = from_float<T>(act_derivative(v, act));
         out[idx] = from_float<T>(act_forward(v, act));
       } else if (PRODUCT == 1) {
-        if (d_prev) {  // dgrad reuses the `act` argument: 1 = d_prev holds the ReLU output, the factor is (output > 0)
+        if (d_prev) {  // relu_mask: d_prev holds the previous layer's ReLU output, the factor is (output > 0)
           const float dp = to_float(d_prev[idx]);
-          v = act ? (dp > 0.f ? v : 0.f) : v * dp;
+          v = relu_mask ? (dp > 0.f ? v : 0.f) : v * dp;
         }
         out[idx] = from_float<T>(v);
       } else {
@@ -256,10 +256,10 @@ hipError_t launch_conv_fprop(hipStream_t s, int elt, int imgs, int H, int W, int
   dim3 grid((cout + BN - 1) / BN, (P + BM - 1) / BM);
   if (elt == 1)
     hipLaunchKernelGGL((conv_simt_kernel<uint16_t, 0>), grid, dim3(kThreads), 0, s, g, (const uint16_t*)x, (const uint16_t*)wgt,
-                       bias, act, (const uint16_t*)nullptr, (uint16_t*)d_out, (uint16_t*)a_out, (float*)nullptr, 0);
+                       bias, act, (const uint16_t*)nullptr, (uint16_t*)d_out, (uint16_t*)a_out, (float*)nullptr, 0, 0);
   else
     hipLaunchKernelGGL((conv_simt_kernel<float, 0>), grid, dim3(kThreads), 0, s, g, (const float*)x, (const float*)wgt, bias,
-                       act, (const float*)nullptr, (float*)d_out, (float*)a_out, (float*)nullptr, 0);
+                       act, (const float*)nullptr, (float*)d_out, (float*)a_out, (float*)nullptr, 0, 0);
   return hipGetLastError();
 }
 
@@ -273,10 +273,10 @@ hipError_t launch_conv_dgrad(hipStream_t s, int elt, int imgs, int H, int W, int
   dim3 grid((cin + BN - 1) / BN, (P + BM - 1) / BM);
   if (elt == 1)
     hipLaunchKernelGGL((conv_simt_kernel<uint16_t, 1>), grid, dim3(kThreads), 0, s, g, (const uint16_t*)dz, (const uint16_t*)wb,
-                       (const float*)nullptr, relu_mask, (const uint16_t*)d_prev, (uint16_t*)nullptr, (uint16_t*)out, (float*)nullptr, 0);
+                       (const float*)nullptr, 0, (const uint16_t*)d_prev, (uint16_t*)nullptr, (uint16_t*)out, (float*)nullptr, 0, relu_mask);
   else
     hipLaunchKernelGGL((conv_simt_kernel<float, 1>), grid, dim3(kThreads), 0, s, g, (const float*)dz, (const float*)wb,
-                       (const float*)nullptr, relu_mask, (const float*)d_prev, (float*)nullptr, (float*)out, (float*)nullptr, 0);
+                       (const float*)nullptr, 0, (const float*)d_prev, (float*)nullptr, (float*)out, (float*)nullptr, 0, relu_mask);
   return hipGetLastError();
 }
 
@@ -292,10 +292,10 @@ hipError_t launch_conv_wgrad(hipStream_t s, int elt, int imgs, int H, int W, int
   dim3 grid((9 * cin + BN - 1) / BN, (cout + BM - 1) / BM, splits);
   if (elt == 1)
     hipLaunchKernelGGL((conv_simt_kernel<uint16_t, 2>), grid, dim3(kThreads), 0, s, g, (const uint16_t*)x, (const uint16_t*)dz,
-                       (const float*)nullptr, 0, (const uint16_t*)nullptr, (uint16_t*)nullptr, (uint16_t*)nullptr, partial, per);
+                       (const float*)nullptr, 0, (const uint16_t*)nullptr, (uint16_t*)nullptr, (uint16_t*)nullptr, partial, per, 0);
   else
     hipLaunchKernelGGL((conv_simt_kernel<float, 2>), grid, dim3(kThreads), 0, s, g, (const float*)x, (const float*)dz,
-                       (const float*)nullptr, 0, (const float*)nullptr, (float*)nullptr, (float*)nullptr, partial, per);
+                       (const float*)nullptr, 0, (const float*)nullptr, (float*)nullptr, (float*)nullptr, partial, per, 0);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const size_t count = (size_t)cout * 9 * cin;
