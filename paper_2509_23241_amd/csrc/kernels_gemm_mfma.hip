@@ -229,7 +229,12 @@ __device__ __forceinline__ EpiWgrad epi_of_split(const EpiWgradSplit& e, int spl
   return EpiWgrad{e.out + (size_t)split * e.split_stride, e.ldc};
 }
 
-template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, class Epi>
+// LEAN: small wave tiles (one or two 32x32 blocks) have so few MFMAs per k tile that the address and stage
+// bookkeeping is a third of the instructions of the loop.  The k loop is then unrolled over the NS stage buffers,
+// so that every LDS address is a loop-invariant register plus an immediate and the stage indices are constants;
+// the source pointers of the copies advance instead of being recomputed.  The last tiles (no copies left to issue
+// in step with them) run through the generic loop.  Worth about 5 % on the 64x64 and 128x64 tiles.
+template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, class Epi, bool LEAN = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, int N, int K,
                                                                         const uint16_t* __restrict__ A, int lda,
                                                                         const uint16_t* __restrict__ B, int ldb,
@@ -292,9 +297,59 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, in
 #pragma unroll
     for (int t = 0; t < kLoads; ++t) issue_copy(t, st, st);
 
-  int rd = 0;        // stage holding tile kt
+  int kt0 = 0;
+  if constexpr (LEAN) {
+    const uint16_t* pa = A + (size_t)(NS - 1) * step_a;  // source of the next tile to copy
+    const uint16_t* pb = B + (size_t)(NS - 1) * step_b;
+    for (; kt0 + NS <= KT - (NS - 1); kt0 += NS) {
+#pragma unroll
+      for (int u = 0; u < NS; ++u) {  // tile kt0 + u lives in buffer u, tile kt0 + u + NS - 1 goes to buffer (u + NS - 1) % NS
+        wait_vmcnt<(NS - 2) * kLoads>();
+        lds_barrier();
+        const uint16_t* la = lds_raw + u * (kStageBytes / 2);
+        const uint16_t* lb = la + AT::kBytes / 2;
+        const uint32_t dst = lds_base + ((u + NS - 1) % NS) * kStageBytes;
+        bf16x8 af[2][TM], bfr[2][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[0][i] = AT::frag(la, wm + i * 32, 0, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[0][j] = BT::frag(lb, wn + j * 32, 0, lane);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kk = 0; kk < DBK / 16; ++kk) {
+          const int c = kk & 1, nx = c ^ 1;
+          if (kk + 1 < DBK / 16) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[nx][i] = AT::frag(la, wm + i * 32, kk + 1, lane);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bfr[nx][j] = BT::frag(lb, wn + j * 32, kk + 1, lane);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+              acc[i][j] = mma<Epi::kSwap>(af[c][i], bfr[c][j], acc[i][j]);
+              const int q = (kk * TM + i) * TN + j;  // compile-time after unrolling
+#pragma unroll
+              for (int t = 0; t < kLoads; ++t)
+                if ((t * NM) / kLoads == q) {
+                  __builtin_amdgcn_sched_barrier(0);
+                  if (t < AT::kPerWave) ta.issue_one(t, dst, pa, wave);
+                  else tb.issue_one(t - AT::kPerWave, dst + AT::kBytes, pb, wave);
+                  __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        pa += step_a;
+        pb += step_b;
+      }
+    }
+  }
+  int rd = 0;        // stage holding tile kt (kt0 is a multiple of NS)
   int wr = NS - 1;   // stage that receives tile kt + NS - 1
-  for (int kt = 0; kt < KT; ++kt) {
+  for (int kt = kt0; kt < KT; ++kt) {
     // tile kt has landed once at most the NS-2 newer tiles are still in flight
     wait_vmcnt<(NS - 2) * kLoads>();
     lds_barrier();  // tile kt visible to all waves; everybody is done reading stage `wr`
@@ -362,7 +417,7 @@ inline bool dma_ok(int M, int N, int K, int lda, int ldb, bool a_col, bool b_col
   return true;
 }
 
-template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, class Epi>
+template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, class Epi, bool LEAN = false>
 hipError_t launch_dma(hipStream_t s, int M, int N, int K, const uint16_t* A, int lda, const uint16_t* B, int ldb,
                       const Epi& epi, SideCopy side = SideCopy{nullptr, nullptr, 0}, int splits = 1) {
   constexpr int NW = WGM * WGN;
@@ -373,7 +428,7 @@ hipError_t launch_dma(hipStream_t s, int M, int N, int K, const uint16_t* A, int
   constexpr size_t epi_bytes = Epi::kSwap && epi_all <= 160 * 1024 ? epi_all : 0;  // wave tiles turned through LDS
   constexpr size_t lds_bytes = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
   static_assert(lds_bytes <= 160 * 1024, "stages do not fit the LDS of a CU");
-  auto kernel = gemm_bf16_dma_kernel<BM, BN, WGM, WGN, NS, A_COL, B_COL, Epi>;
+  auto kernel = gemm_bf16_dma_kernel<BM, BN, WGM, WGN, NS, A_COL, B_COL, Epi, LEAN>;
   if (lds_bytes > 64 * 1024) {
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -422,8 +477,8 @@ bool mfma_wgrad_supported(int M, int N, int K) { return M >= 1 && N % 8 == 0 && 
 
 #define TP_GEMM_DISPATCH(cfg, ACOL, BCOL, ...)                                  \
   switch (cfg) {                                                                \
-    case 10: return launch_dma<64, 64, 2, 2, 4, ACOL, BCOL>(__VA_ARGS__);       \
-    case 11: return launch_dma<128, 64, 2, 2, 4, ACOL, BCOL>(__VA_ARGS__);      \
+    case 10: return launch_dma<64, 64, 2, 2, 4, ACOL, BCOL, decltype(e), true>(__VA_ARGS__);  \
+    case 11: return launch_dma<128, 64, 2, 2, 4, ACOL, BCOL, decltype(e), true>(__VA_ARGS__); \
     case 12: return launch_dma<128, 128, 2, 2, 3, ACOL, BCOL>(__VA_ARGS__);     \
     case 13: return launch_dma<256, 128, 2, 2, 3, ACOL, BCOL>(__VA_ARGS__);     \
     case 14: return launch_dma<128, 256, 2, 2, 3, ACOL, BCOL>(__VA_ARGS__);     \
