@@ -234,7 +234,11 @@ __device__ __forceinline__ EpiWgrad epi_of_split(const EpiWgradSplit& e, int spl
 // so that every LDS address is a loop-invariant register plus an immediate and the stage indices are constants;
 // the source pointers of the copies advance instead of being recomputed.  The last tiles (no copies left to issue
 // in step with them) run through the generic loop.  Worth about 5 % on the 64x64 and 128x64 tiles.
-template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, class Epi, bool LEAN = false>
+// ROT: the barrier that makes a k tile visible sits one k step early, before the last MFMA group of the tile
+// before it, so that the first fragment reads of the new tile run under that group instead of stalling the wave
+// (with one wave per SIMD nothing else would cover them).
+template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, class Epi, bool LEAN = false,
+          bool ROT = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, int N, int K,
                                                                         const uint16_t* __restrict__ A, int lda,
                                                                         const uint16_t* __restrict__ B, int ldb,
@@ -280,6 +284,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, in
   const int KT = K / DBK;
   const size_t step_a = AT::tile_step(lda), step_b = BT::tile_step(ldb);
   constexpr int NM = (DBK / 16) * TM * TN;  // MFMAs of one wave per k tile
+  // MFMA after which copy t of the next tile is issued.  With three or more stages a copy has a whole tile of slack
+  // and the copies are spread evenly; with two stages the tile they fill is waited for at the next barrier, so
+  // they all go out during the first MFMAs and the rest of the tile's arithmetic covers their latency.
+  auto copy_slot = [](int t) constexpr { return NS == 2 && kLoads <= NM ? t : (t * NM) / kLoads; };
 
   // copy number t (0 .. kLoads-1) of k tile `tile` into stage `st`.  Tiles past the end re-read
   // the last tile into a stage nobody reads again, which keeps the number of copies per
@@ -333,7 +341,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, in
               const int q = (kk * TM + i) * TN + j;  // compile-time after unrolling
 #pragma unroll
               for (int t = 0; t < kLoads; ++t)
-                if ((t * NM) / kLoads == q) {
+                if (copy_slot(t) == q) {
                   __builtin_amdgcn_sched_barrier(0);
                   if (t < AT::kPerWave) ta.issue_one(t, dst, pa, wave);
                   else tb.issue_one(t - AT::kPerWave, dst + AT::kBytes, pb, wave);
@@ -349,6 +357,59 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, in
   }
   int rd = 0;        // stage holding tile kt (kt0 is a multiple of NS)
   int wr = NS - 1;   // stage that receives tile kt + NS - 1
+  if constexpr (ROT) {
+    static_assert(!LEAN, "the rotated loop has no unrolled form");
+    constexpr int KS = DBK / 16;
+    static_assert(KS % 2 == 0, "fragment buffers alternate with the k steps");
+    // Step s of iteration kt reads the fragments of (tile kt, k step s) and multiplies those of the step before:
+    // step 0 multiplies the last k step of tile kt-1 (zeros in the first iteration).
+    bf16x8 af[2][TM], bfr[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) af[1][i][e] = 0;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) bfr[1][j][e] = 0;
+    for (int kt = 0; kt < KT; ++kt) {
+      wait_vmcnt<(NS - 2) * kLoads>();
+      lds_barrier();  // tile kt visible; every wave holds its last fragments of tile kt-1 in registers
+      const uint16_t* la = lds_raw + rd * (kStageBytes / 2);
+      const uint16_t* lb = la + AT::kBytes / 2;
+#pragma unroll
+      for (int st = 0; st < KS; ++st) {
+        const int nx = st & 1, c = nx ^ 1;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[nx][i] = AT::frag(la, wm + i * 32, st, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[nx][j] = BT::frag(lb, wn + j * 32, st, lane);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            acc[i][j] = mma<Epi::kSwap>(af[c][i], bfr[c][j], acc[i][j]);
+            const int q = (st * TM + i) * TN + j;
+#pragma unroll
+            for (int t = 0; t < kLoads; ++t)
+              if (copy_slot(t) == q) {
+                __builtin_amdgcn_sched_barrier(0);
+                issue_copy(t, kt + NS - 1, wr);
+                __builtin_amdgcn_sched_barrier(0);
+              }
+          }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      rd = rd + 1 == NS ? 0 : rd + 1;
+      wr = wr + 1 == NS ? 0 : wr + 1;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] = mma<Epi::kSwap>(af[1][i], bfr[1][j], acc[i][j]);
+    kt0 = KT;
+  }
   for (int kt = kt0; kt < KT; ++kt) {
     // tile kt has landed once at most the NS-2 newer tiles are still in flight
     wait_vmcnt<(NS - 2) * kLoads>();
@@ -383,7 +444,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, in
             const int q = (kk * TM + i) * TN + j;  // compile-time after unrolling
 #pragma unroll
             for (int t = 0; t < kLoads; ++t)
-              if ((t * NM) / kLoads == q) {
+              if (copy_slot(t) == q) {
                 __builtin_amdgcn_sched_barrier(0);
                 issue_copy(t, kt + NS - 1, wr);
                 __builtin_amdgcn_sched_barrier(0);
@@ -417,7 +478,8 @@ inline bool dma_ok(int M, int N, int K, int lda, int ldb, bool a_col, bool b_col
   return true;
 }
 
-template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, class Epi, bool LEAN = false>
+template <int BM, int BN, int WGM, int WGN, int NS, bool A_COL, bool B_COL, class Epi, bool LEAN = false,
+          bool ROT = false>
 hipError_t launch_dma(hipStream_t s, int M, int N, int K, const uint16_t* A, int lda, const uint16_t* B, int ldb,
                       const Epi& epi, SideCopy side = SideCopy{nullptr, nullptr, 0}, int splits = 1) {
   constexpr int NW = WGM * WGN;
@@ -428,7 +490,7 @@ hipError_t launch_dma(hipStream_t s, int M, int N, int K, const uint16_t* A, int
   constexpr size_t epi_bytes = Epi::kSwap && epi_all <= 160 * 1024 ? epi_all : 0;  // wave tiles turned through LDS
   constexpr size_t lds_bytes = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
   static_assert(lds_bytes <= 160 * 1024, "stages do not fit the LDS of a CU");
-  auto kernel = gemm_bf16_dma_kernel<BM, BN, WGM, WGN, NS, A_COL, B_COL, Epi, LEAN>;
+  auto kernel = gemm_bf16_dma_kernel<BM, BN, WGM, WGN, NS, A_COL, B_COL, Epi, LEAN, ROT>;
   if (lds_bytes > 64 * 1024) {
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -485,8 +547,8 @@ bool mfma_wgrad_supported(int M, int N, int K) { return M >= 1 && N % 8 == 0 && 
     case 15: return launch_dma<256, 256, 2, 2, 2, ACOL, BCOL>(__VA_ARGS__);     \
     case 16: return launch_dma<128, 128, 2, 2, 4, ACOL, BCOL>(__VA_ARGS__);     \
     case 17: return launch_dma<64, 64, 2, 2, 8, ACOL, BCOL>(__VA_ARGS__);       \
-    case 18: return launch_dma<256, 256, 2, 4, 2, ACOL, BCOL>(__VA_ARGS__);     \
-    case 19: return launch_dma<256, 128, 2, 4, 3, ACOL, BCOL>(__VA_ARGS__);     \
+    case 18: return launch_dma<256, 256, 2, 4, 2, ACOL, BCOL, decltype(e), false, true>(__VA_ARGS__); \
+    case 19: return launch_dma<256, 128, 2, 4, 3, ACOL, BCOL, decltype(e), false, true>(__VA_ARGS__); \
     case 5: return launch<128, 256, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);         \
     case 4: return launch<64, 64, 2, 2, 128, ACOL, BCOL>(__VA_ARGS__);          \
     case 3: return launch<256, 128, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);         \
