@@ -514,7 +514,9 @@ int pick(int rows, int cols, int contraction, int lda, int ldb, bool a_col, bool
   auto blocks = [&](int bm, int bn) { return (long)((rows + bm - 1) / bm) * ((cols + bn - 1) / bn); };
   if (dma_ok(rows, cols, contraction, lda, ldb, a_col, b_col)) {
     // 8 waves on the big tiles: two waves per SIMD hide each other's LDS and barrier latency
-    if (a_col && b_col && blocks(256, 256) >= 256) return 18;  // fp32-output product only (register budget)
+    // the backward products gain from the 256x256 tile; the forward product (bias, activation and two bf16 outputs
+    // in its epilogue, 128 elements per lane) measured slower with it inside the transformer stage
+    if ((a_col || b_col) && blocks(256, 256) >= 256) return 18;
     if (blocks(256, 128) >= 256) return 19;
     if (blocks(128, 128) >= 256) return 12;
     if (blocks(128, 64) >= 256) return 11;
