@@ -419,7 +419,7 @@ hipError_t launch_flash_fwd(hipStream_t s, int seqs, int S, int heads, const uin
 
 // ---- fused backward -------------------------------------------------------------------------------
 // Two launches of one kernel template, both in the register layout of the fused forward:
-//   dQ      a workgroup owns 128 queries (4 waves x 32) and walks over the key blocks up to its diagonal:
+//   dQ      a workgroup owns 256 queries (8 waves x 32) and walks over the key blocks up to its diagonal:
 //           S^T = K Q^T and dP^T = V dO^T with Q, dO fragments in registers, K and V streamed through LDS;
 //           lse and delta = dO . O are per-lane scalars; dQ^T += K^T dS^T.
 //   dK, dV  a workgroup owns 128 keys and walks over the query blocks from its diagonal to the end:
@@ -430,7 +430,10 @@ hipError_t launch_flash_fwd(hipStream_t s, int seqs, int S, int heads, const uin
 // once in the row layout the first products read and once in the layout the transposing reads of the second
 // products want.  The scores are recomputed in both launches (7 matrix products instead of 5), no score-sized
 // tensor reaches memory, nothing is accumulated with atomics: every output element has one owner.
-constexpr int kBwdWaves = 4, kBwdOwn = 32 * kBwdWaves;
+// Waves per workgroup.  The dQ launch fits two waves per SIMD (223 registers at head width 128) and gains 25 % from
+// the second wave covering the first one's LDS and barrier stalls; the dK/dV launch holds two accumulator tiles and
+// would spill with the 256 registers that leaves, so it keeps one wave per SIMD.
+constexpr int bwd_waves(bool own_keys) { return own_keys ? 4 : 8; }
 constexpr float kLog2e = 1.4426950408889634f;
 
 // stat[(z*S + i)*2] = lse_i * log2(e), stat[(z*S + i)*2 + 1] = delta_i = sum_d dO[i][d] * O[i][d];  z = sequence*heads + head.
@@ -464,11 +467,11 @@ __global__ __launch_bounds__(256) void attn_stat_kernel(int S, int heads, int dh
 }
 
 template <int DH, bool OWN_KEYS>
-__global__ __launch_bounds__(64 * kBwdWaves) void attn_flash_bwd_kernel(int S, int heads, const uint16_t* __restrict__ qkv,
+__global__ __launch_bounds__(64 * bwd_waves(OWN_KEYS)) void attn_flash_bwd_kernel(int S, int heads, const uint16_t* __restrict__ qkv,
                                                                         const uint16_t* __restrict__ dout,
                                                                         const float* __restrict__ stat, uint16_t* __restrict__ dqkv,
                                                                         float scale, float scale_log2) {
-  constexpr int NW = kBwdWaves;
+  constexpr int NW = bwd_waves(OWN_KEYS), kBwdOwn = 32 * NW;
   constexpr int HALVES = DH / 64, TN = DH / 32;
   using RT = RowDma<64, NW>;   // 64 streamed rows x one 64-wide chunk of the head dimension
   using CT = ColDma<DH, NW>;   // [64 streamed rows][DH], read transposed
@@ -638,6 +641,7 @@ __global__ __launch_bounds__(64 * kBwdWaves) void attn_flash_bwd_kernel(int S, i
 template <int DH, bool OWN_KEYS>
 hipError_t launch_flash_bwd(hipStream_t s, int seqs, int S, int heads, const uint16_t* qkv, const uint16_t* dout, const float* stat,
                             uint16_t* dqkv) {
+  constexpr int kBwdWaves = bwd_waves(OWN_KEYS), kBwdOwn = 32 * kBwdWaves;
   constexpr size_t row_bytes = (size_t)(DH / 64) * RowDma<64, kBwdWaves>::kBytes, col_bytes = ColDma<DH, kBwdWaves>::kBytes;
   constexpr size_t stage_bytes = 2 * (2 * row_bytes + (OWN_KEYS ? 2 : 1) * col_bytes + (OWN_KEYS ? 1024 : 0));
   constexpr size_t epi_bytes = (size_t)kBwdWaves * wave_epilogue_bytes<1, DH / 32>();
