@@ -422,7 +422,7 @@ hipError_t launch_flash_fwd(hipStream_t s, int seqs, int S, int heads, const uin
 //   dQ      a workgroup owns 256 queries (8 waves x 32) and walks over the key blocks up to its diagonal:
 //           S^T = K Q^T and dP^T = V dO^T with Q, dO fragments in registers, K and V streamed through LDS;
 //           lse and delta = dO . O are per-lane scalars; dQ^T += K^T dS^T.
-//   dK, dV  a workgroup owns 128 keys and walks over the query blocks from its diagonal to the end:
+//   dK, dV  a workgroup owns 256 keys and walks over the query blocks from its diagonal to the end:
 //           S = Q K^T and dP = dO V^T with K, V fragments in registers, Q and dO streamed; lse, delta of the 64
 //           streamed queries come through LDS with the block; dV^T += dO^T P, dK^T += Q^T dS.
 // P = exp(scale S - lse) and dS = scale P (dP - delta) are formed in registers and packed to bf16 as the B
@@ -430,10 +430,10 @@ hipError_t launch_flash_fwd(hipStream_t s, int seqs, int S, int heads, const uin
 // once in the row layout the first products read and once in the layout the transposing reads of the second
 // products want.  The scores are recomputed in both launches (7 matrix products instead of 5), no score-sized
 // tensor reaches memory, nothing is accumulated with atomics: every output element has one owner.
-// Waves per workgroup.  The dQ launch fits two waves per SIMD (223 registers at head width 128) and gains 25 % from
-// the second wave covering the first one's LDS and barrier stalls; the dK/dV launch holds two accumulator tiles and
-// would spill with the 256 registers that leaves, so it keeps one wave per SIMD.
-constexpr int bwd_waves(bool own_keys) { return own_keys ? 4 : 8; }
+// 8 waves per workgroup, two per SIMD: the second wave covers the first one's LDS and barrier stalls (25 % faster than
+// 4 waves in both launches).  The dK/dV launch fits the 256 registers that leaves because only one half of a streamed
+// block has its score tiles alive at a time.
+constexpr int kBwdWaves = 8;
 constexpr float kLog2e = 1.4426950408889634f;
 
 // stat[(z*S + i)*2] = lse_i * log2(e), stat[(z*S + i)*2 + 1] = delta_i = sum_d dO[i][d] * O[i][d];  z = sequence*heads + head.
@@ -467,11 +467,11 @@ __global__ __launch_bounds__(256) void attn_stat_kernel(int S, int heads, int dh
 }
 
 template <int DH, bool OWN_KEYS>
-__global__ __launch_bounds__(64 * bwd_waves(OWN_KEYS)) void attn_flash_bwd_kernel(int S, int heads, const uint16_t* __restrict__ qkv,
+__global__ __launch_bounds__(64 * kBwdWaves) void attn_flash_bwd_kernel(int S, int heads, const uint16_t* __restrict__ qkv,
                                                                         const uint16_t* __restrict__ dout,
                                                                         const float* __restrict__ stat, uint16_t* __restrict__ dqkv,
                                                                         float scale, float scale_log2) {
-  constexpr int NW = bwd_waves(OWN_KEYS), kBwdOwn = 32 * NW;
+  constexpr int NW = kBwdWaves, kBwdOwn = 32 * NW;
   constexpr int HALVES = DH / 64, TN = DH / 32;
   using RT = RowDma<64, NW>;   // 64 streamed rows x one 64-wide chunk of the head dimension
   using CT = ColDma<DH, NW>;   // [64 streamed rows][DH], read transposed
@@ -574,59 +574,63 @@ __global__ __launch_bounds__(64 * bwd_waves(OWN_KEYS)) void attn_flash_bwd_kerne
       const uint16_t* lc1 = lr2 + kRowBytes / 2;
       const uint16_t* lc2 = lc1 + CT::kBytes / 2;
       const float* lstat = reinterpret_cast<const float*>(lc1 + kCols * (CT::kBytes / 2));
-      floatx16 sacc[2], pacc[2];
+      // some pair of this wave and block lies above the diagonal
+      const bool diagonal = OWN_KEYS ? sb * 64 < ow + 31 : sb * 64 + 63 > ow;
+      // one half of the block (32 streamed rows) at a time, first products to second products: the score tiles of
+      // one half only are alive at any time, which is what lets two waves share a SIMD's registers
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
+        floatx16 sacc, pacc;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[j][r] = pacc[j][r] = 0.f;
+        for (int r = 0; r < 16; ++r) sacc[r] = pacc[r] = 0.f;
 #pragma unroll
         for (int c = 0; c < HALVES; ++c)
 #pragma unroll
           for (int kk = 0; kk < 4; ++kk) {
-            sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(RT::frag(lr1 + c * (RT::kBytes / 2), 32 * j, kk, lane),
-                                                              f1[c * 4 + kk], sacc[j], 0, 0, 0);
-            pacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(RT::frag(lr2 + c * (RT::kBytes / 2), 32 * j, kk, lane),
-                                                              f2[c * 4 + kk], pacc[j], 0, 0, 0);
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(RT::frag(lr1 + c * (RT::kBytes / 2), 32 * j, kk, lane),
+                                                           f1[c * 4 + kk], sacc, 0, 0, 0);
+            pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(RT::frag(lr2 + c * (RT::kBytes / 2), 32 * j, kk, lane),
+                                                           f2[c * 4 + kk], pacc, 0, 0, 0);
           }
-      }
-      // some pair of this wave and block lies above the diagonal
-      const bool diagonal = OWN_KEYS ? sb * 64 < ow + 31 : sb * 64 + 63 > ow;
-      bf16x8 pf[4], dsf[4];
+        bf16x8 pf[2], dsf[2];
 #pragma unroll
-      for (int g16 = 0; g16 < 4; ++g16) {
-        const int j = g16 >> 1;
-        float pe[8], de[8];
+        for (int h = 0; h < 2; ++h) {
+          float pe[8], de[8];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          const int r = 8 * (g16 & 1) + t;
-          const int srow = 32 * j + 8 * (r >> 2) + 4 * half + (r & 3);  // streamed row inside the block
-          float l2 = own_l2, dl = own_delta;
-          if (OWN_KEYS) {
-            l2 = lstat[2 * srow];
-            dl = lstat[2 * srow + 1];
+          for (int t = 0; t < 8; ++t) {
+            const int r = 8 * h + t;
+            const int srow = 32 * j + 8 * (r >> 2) + 4 * half + (r & 3);  // streamed row inside the block
+            float l2 = own_l2, dl = own_delta;
+            if (OWN_KEYS) {
+              l2 = lstat[2 * srow];
+              dl = lstat[2 * srow + 1];
+            }
+            float p = __builtin_amdgcn_exp2f(sacc[r] * scale_log2 - l2);
+            if (diagonal) {
+              const int si = sb * 64 + srow;
+              const int key = OWN_KEYS ? oi : si, query = OWN_KEYS ? si : oi;
+              if (key > query) p = 0.f;
+            }
+            pe[t] = p;
+            de[t] = p * (pacc[r] - dl) * scale;
           }
-          float p = __builtin_amdgcn_exp2f(sacc[j][r] * scale_log2 - l2);
-          if (diagonal) {
-            const int si = sb * 64 + srow;
-            const int key = OWN_KEYS ? oi : si, query = OWN_KEYS ? si : oi;
-            if (key > query) p = 0.f;
-          }
-          pe[t] = p;
-          de[t] = p * (pacc[j][r] - dl) * scale;
-        }
-        pf[g16] = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16x2(pe[0], pe[1]), pack_bf16x2(pe[2], pe[3]),
+          pf[h] = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16x2(pe[0], pe[1]), pack_bf16x2(pe[2], pe[3]),
                                                          pack_bf16x2(pe[4], pe[5]), pack_bf16x2(pe[6], pe[7])));
-        dsf[g16] = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16x2(de[0], de[1]), pack_bf16x2(de[2], de[3]),
+          dsf[h] = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16x2(de[0], de[1]), pack_bf16x2(de[2], de[3]),
                                                           pack_bf16x2(de[4], de[5]), pack_bf16x2(de[6], de[7])));
-      }
-#pragma unroll
-      for (int g16 = 0; g16 < 4; ++g16)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          acc1[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(flash_v_frag<DH>(lc1, 32 * j, g16, lane), dsf[g16], acc1[0][j], 0, 0, 0);
-          if (OWN_KEYS)
-            acc2[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(flash_v_frag<DH>(lc2, 32 * j, g16, lane), pf[g16], acc2[0][j], 0, 0, 0);
         }
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int jj = 0; jj < TN; ++jj) {
+            acc1[0][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(flash_v_frag<DH>(lc1, 32 * jj, 2 * j + h, lane), dsf[h],
+                                                                  acc1[0][jj], 0, 0, 0);
+            if (OWN_KEYS)
+              acc2[0][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(flash_v_frag<DH>(lc2, 32 * jj, 2 * j + h, lane), pf[h],
+                                                                    acc2[0][jj], 0, 0, 0);
+          }
+        if (OWN_KEYS) __builtin_amdgcn_sched_barrier(0);
+      }
     }
     st ^= 1;
   }
@@ -641,7 +645,7 @@ __global__ __launch_bounds__(64 * bwd_waves(OWN_KEYS)) void attn_flash_bwd_kerne
 template <int DH, bool OWN_KEYS>
 hipError_t launch_flash_bwd(hipStream_t s, int seqs, int S, int heads, const uint16_t* qkv, const uint16_t* dout, const float* stat,
                             uint16_t* dqkv) {
-  constexpr int kBwdWaves = bwd_waves(OWN_KEYS), kBwdOwn = 32 * kBwdWaves;
+  constexpr int kBwdOwn = 32 * kBwdWaves;
   constexpr size_t row_bytes = (size_t)(DH / 64) * RowDma<64, kBwdWaves>::kBytes, col_bytes = ColDma<DH, kBwdWaves>::kBytes;
   constexpr size_t stage_bytes = 2 * (2 * row_bytes + (OWN_KEYS ? 2 : 1) * col_bytes + (OWN_KEYS ? 1024 : 0));
   constexpr size_t epi_bytes = (size_t)kBwdWaves * wave_epilogue_bytes<1, DH / 32>();
