@@ -458,10 +458,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, in
   }
   wait_vmcnt<0>();  // the trailing dummy copies must have landed before LDS is reused
   lds_barrier();    // all waves are done with the last stage
-  if constexpr (Epi::kSwap && NW * wave_epilogue_bytes<TM, TN>() <= 160 * 1024) {
+  if constexpr (Epi::kSwap) {
     if (m0 + wm + WM <= M && n0 + wn + WN <= N && (N & 7) == 0) {
-      float* wave_lds = reinterpret_cast<float*>(lds_raw) + wave * (wave_epilogue_bytes<TM, TN>() / 4);
-      store_tiles_coalesced<TM, TN>(acc, epi, m0 + wm, n0 + wn, lane, wave_lds);
+      if constexpr (NW * wave_epilogue_bytes<TM, TN>() <= 160 * 1024) {
+        float* wave_lds = reinterpret_cast<float*>(lds_raw) + wave * (wave_epilogue_bytes<TM, TN>() / 4);
+        store_tiles_coalesced<TM, TN>(acc, epi, m0 + wm, n0 + wn, lane, wave_lds);
+      } else {
+        // the whole wave tiles do not fit the LDS together (256x256): one 32-row block of every wave at a time
+        float* wave_lds = reinterpret_cast<float*>(lds_raw) + wave * (wave_epilogue_bytes<1, TN>() / 4);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+          store_tiles_coalesced<1, TN>(reinterpret_cast<const floatx16(&)[1][TN]>(acc[i]), epi, m0 + wm + 32 * i, n0 + wn,
+                                       lane, wave_lds);
+      }
       return;
     }
   }
@@ -486,8 +495,9 @@ hipError_t launch_dma(hipStream_t s, int M, int N, int K, const uint16_t* A, int
   using AT = typename DmaSel<BM, NW, A_COL>::type;
   using BT = typename DmaSel<BN, NW, B_COL>::type;
   constexpr size_t stage_bytes = (size_t)NS * (AT::kBytes + BT::kBytes);
-  constexpr size_t epi_all = (size_t)NW * wave_epilogue_bytes<BM / WGM / 32, BN / WGN / 32>();
-  constexpr size_t epi_bytes = Epi::kSwap && epi_all <= 160 * 1024 ? epi_all : 0;  // wave tiles turned through LDS
+  constexpr size_t epi_whole = (size_t)NW * wave_epilogue_bytes<BM / WGM / 32, BN / WGN / 32>();
+  constexpr size_t epi_rows = (size_t)NW * wave_epilogue_bytes<1, BN / WGN / 32>();  // one 32-row block per wave
+  constexpr size_t epi_bytes = !Epi::kSwap ? 0 : epi_whole <= 160 * 1024 ? epi_whole : epi_rows;  // tiles turned through LDS
   constexpr size_t lds_bytes = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
   static_assert(lds_bytes <= 160 * 1024, "stages do not fit the LDS of a CU");
   auto kernel = gemm_bf16_dma_kernel<BM, BN, WGM, WGN, NS, A_COL, B_COL, Epi, LEAN, ROT>;
@@ -514,9 +524,7 @@ int pick(int rows, int cols, int contraction, int lda, int ldb, bool a_col, bool
   auto blocks = [&](int bm, int bn) { return (long)((rows + bm - 1) / bm) * ((cols + bn - 1) / bn); };
   if (dma_ok(rows, cols, contraction, lda, ldb, a_col, b_col)) {
     // 8 waves on the big tiles: two waves per SIMD hide each other's LDS and barrier latency
-    // the backward products gain from the 256x256 tile; the forward product (bias, activation and two bf16 outputs
-    // in its epilogue, 128 elements per lane) measured slower with it inside the transformer stage
-    if ((a_col || b_col) && blocks(256, 256) >= 256) return 18;
+    if (blocks(256, 256) >= 256) return 18;
     if (blocks(256, 128) >= 256) return 19;
     if (blocks(128, 128) >= 256) return 12;
     if (blocks(128, 64) >= 256) return 11;
