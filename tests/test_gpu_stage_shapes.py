@@ -18,6 +18,11 @@ SHAPES = [
     (64, 3, 520, 128, 1000),
     (7, 2, 19, 23, 5),          # nothing is a multiple of 8: generic kernel
     (256, 2, 256, 512, 256),
+    # outputs of 4096 x 4096 (the 256 x 256 tile: 256 workgroups) over contractions of one and three k tiles:
+    # forward and input gradient ...
+    (4096, 1, 64, 4096, 192),
+    # ... and weight gradient (64 rows in the mini-batch)
+    (64, 1, 4096, 4096, 8),
 ]
 
 
