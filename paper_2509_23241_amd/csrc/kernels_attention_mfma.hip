@@ -596,23 +596,29 @@ __global__ __launch_bounds__(64 * kBwdWaves) void attn_flash_bwd_kernel(int S, i
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
           float pe[8], de[8];
+          // (lse, delta) of the streamed rows of this lane's elements: two runs of four consecutive rows, 32 bytes each
 #pragma unroll
-          for (int t = 0; t < 8; ++t) {
-            const int r = 8 * h + t;
-            const int srow = 32 * j + 8 * (r >> 2) + 4 * half + (r & 3);  // streamed row inside the block
-            float l2 = own_l2, dl = own_delta;
+          for (int q = 0; q < 2; ++q) {
+            float l2v[4] = {own_l2, own_l2, own_l2, own_l2}, dlv[4] = {own_delta, own_delta, own_delta, own_delta};
             if (OWN_KEYS) {
-              l2 = lstat[2 * srow];
-              dl = lstat[2 * srow + 1];
+              const float4* sp = reinterpret_cast<const float4*>(lstat + 2 * (32 * j + 8 * (2 * h + q) + 4 * half));
+              const float4 s0 = sp[0], s1 = sp[1];
+              l2v[0] = s0.x; dlv[0] = s0.y; l2v[1] = s0.z; dlv[1] = s0.w;
+              l2v[2] = s1.x; dlv[2] = s1.y; l2v[3] = s1.z; dlv[3] = s1.w;
             }
-            float p = __builtin_amdgcn_exp2f(sacc[r] * scale_log2 - l2);
-            if (diagonal) {
-              const int si = sb * 64 + srow;
-              const int key = OWN_KEYS ? oi : si, query = OWN_KEYS ? si : oi;
-              if (key > query) p = 0.f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const int t = 4 * q + u, r = 8 * h + t;
+              const int srow = 32 * j + 8 * (r >> 2) + 4 * half + (r & 3);  // streamed row inside the block
+              float p = __builtin_amdgcn_exp2f(sacc[r] * scale_log2 - l2v[u]);
+              if (diagonal) {
+                const int si = sb * 64 + srow;
+                const int key = OWN_KEYS ? oi : si, query = OWN_KEYS ? si : oi;
+                if (key > query) p = 0.f;
+              }
+              pe[t] = p;
+              de[t] = p * (pacc[r] - dlv[u]) * scale;
             }
-            pe[t] = p;
-            de[t] = p * (pacc[r] - dl) * scale;
           }
           pf[h] = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16x2(pe[0], pe[1]), pack_bf16x2(pe[2], pe[3]),
                                                          pack_bf16x2(pe[4], pe[5]), pack_bf16x2(pe[6], pe[7])));
