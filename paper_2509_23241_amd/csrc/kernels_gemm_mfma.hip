@@ -520,9 +520,10 @@ int g_cfg[3] = {-1, -1, -1};  // tuning override per product (fprop, dgrad, wgra
 // together with the LDS reads is what bounds these kernels).  Ragged shapes go to the
 // register-staged kernel.
 int pick(int rows, int cols, int contraction, int lda, int ldb, bool a_col, bool b_col, int override_cfg) {
-  if (override_cfg >= 0) return override_cfg;
+  const bool dma = dma_ok(rows, cols, contraction, lda, ldb, a_col, b_col);
+  if (override_cfg >= 0 && (override_cfg < 10 || dma)) return override_cfg;  // a direct-to-LDS tile only where it is valid
   auto blocks = [&](int bm, int bn) { return (long)((rows + bm - 1) / bm) * ((cols + bn - 1) / bn); };
-  if (dma_ok(rows, cols, contraction, lda, ldb, a_col, b_col)) {
+  if (dma) {
     // 8 waves on the big tiles: two waves per SIMD hide each other's LDS and barrier latency
     if (blocks(256, 256) >= 256) return 18;
     if (blocks(256, 128) >= 256) return 19;
@@ -552,16 +553,8 @@ bool mfma_wgrad_supported(int M, int N, int K) { return M >= 1 && N % 8 == 0 && 
     case 10: return launch_dma<64, 64, 2, 2, 4, ACOL, BCOL, decltype(e), true>(__VA_ARGS__);  \
     case 11: return launch_dma<128, 64, 2, 2, 4, ACOL, BCOL, decltype(e), true>(__VA_ARGS__); \
     case 12: return launch_dma<128, 128, 2, 2, 3, ACOL, BCOL>(__VA_ARGS__);     \
-    case 13: return launch_dma<256, 128, 2, 2, 3, ACOL, BCOL>(__VA_ARGS__);     \
-    case 14: return launch_dma<128, 256, 2, 2, 3, ACOL, BCOL>(__VA_ARGS__);     \
-    case 15: return launch_dma<256, 256, 2, 2, 2, ACOL, BCOL>(__VA_ARGS__);     \
-    case 16: return launch_dma<128, 128, 2, 2, 4, ACOL, BCOL>(__VA_ARGS__);     \
-    case 17: return launch_dma<64, 64, 2, 2, 8, ACOL, BCOL>(__VA_ARGS__);       \
     case 18: return launch_dma<256, 256, 2, 4, 2, ACOL, BCOL, decltype(e), false, true>(__VA_ARGS__); \
     case 19: return launch_dma<256, 128, 2, 4, 3, ACOL, BCOL, decltype(e), false, true>(__VA_ARGS__); \
-    case 5: return launch<128, 256, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);         \
-    case 4: return launch<64, 64, 2, 2, 128, ACOL, BCOL>(__VA_ARGS__);          \
-    case 3: return launch<256, 128, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);         \
     case 2: return launch<128, 128, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);         \
     case 1: return launch<128, 64, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);          \
     default: return launch<64, 64, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);          \
