@@ -270,9 +270,11 @@ __global__ __launch_bounds__(64 * kFlashWaves) void attn_flash_fwd_kernel(int S,
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int half = lane >> 5;
-  const int zb = blockIdx.y / heads, zh = blockIdx.y - zb * heads;
+  // grid: x = (sequence, head), y = query block.  Workgroups are handed out x first, so all the longest rows of
+  // the triangle (the last query block of every head) start before any shorter one
+  const int zb = blockIdx.x / heads, zh = blockIdx.x - zb * heads;
   const int D = heads * DH, ld = 3 * D;
-  const int q0 = (gridDim.x - 1 - blockIdx.x) * kFlashQ;  // the longest rows of the triangle start first
+  const int q0 = (gridDim.y - 1 - blockIdx.y) * kFlashQ;
   const int qw = q0 + wave * 32;                           // first query of this wave
   const bool active = qw < S;                              // S is a multiple of 64: a wave is whole or absent
   const uint16_t* qbase = qkv + (size_t)zb * S * ld + zh * DH;
@@ -395,7 +397,7 @@ __global__ __launch_bounds__(64 * kFlashWaves) void attn_flash_fwd_kernel(int S,
   for (int j = 0; j < TN; ++j)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[0][j][r] *= inv;
-  if (half == 0) lse[(size_t)blockIdx.y * S + query] = (mrun + __builtin_amdgcn_logf(ltot)) * 0.6931471805599453f;
+  if (half == 0) lse[(size_t)blockIdx.x * S + query] = (mrun + __builtin_amdgcn_logf(ltot)) * 0.6931471805599453f;
   float* wave_lds = reinterpret_cast<float*>(lds_raw) + wave * (wave_epilogue_bytes<1, TN>() / 4);
   store_tiles_coalesced<1, TN>(oacc, EpiDgrad{nullptr, out, D}, zb * S + qw, zh * DH, lane, wave_lds);
 }
@@ -412,7 +414,7 @@ hipError_t launch_flash_fwd(hipStream_t s, int seqs, int S, int heads, const uin
   if (attr != hipSuccess) return attr;
   // scores are scaled by 1/sqrt(dh) and exponentiated in base 2
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-  hipLaunchKernelGGL(kernel, dim3((S + kFlashQ - 1) / kFlashQ, seqs * heads), dim3(64 * kFlashWaves), lds_bytes, s, S, heads, qkv,
+  hipLaunchKernelGGL(kernel, dim3(seqs * heads, (S + kFlashQ - 1) / kFlashQ), dim3(64 * kFlashWaves), lds_bytes, s, S, heads, qkv,
                      out, lse, scale_log2);
   return hipGetLastError();
 }
@@ -484,7 +486,7 @@ __global__ __launch_bounds__(64 * kBwdWaves) void attn_flash_bwd_kernel(int S, i
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int half = lane >> 5;
-  const int z = blockIdx.y, zb = z / heads, zh = z - zb * heads;
+  const int z = blockIdx.x, zb = z / heads, zh = z - zb * heads;  // grid: x = (sequence, head), y = block of own rows
   const int D = heads * DH, ld3 = 3 * D;
   const uint16_t* qp = qkv + (size_t)zb * S * ld3 + zh * DH;
   const uint16_t* dop = dout + (size_t)zb * S * D + zh * DH;
@@ -496,7 +498,7 @@ __global__ __launch_bounds__(64 * kBwdWaves) void attn_flash_bwd_kernel(int S, i
   const uint16_t* str2 = OWN_KEYS ? dop : qp + 2 * D;     // dO | V
   const int ld_str2 = OWN_KEYS ? D : ld3;
   // the workgroups with the most blocks to walk start first: low keys, high queries
-  const int o0 = (OWN_KEYS ? (int)blockIdx.x : (int)(gridDim.x - 1 - blockIdx.x)) * kBwdOwn;
+  const int o0 = (OWN_KEYS ? (int)blockIdx.y : (int)(gridDim.y - 1 - blockIdx.y)) * kBwdOwn;
   const int ow = o0 + wave * 32;
   const bool active = ow < S;
   const int oi = ow + (lane & 31);  // this lane's own row
@@ -662,7 +664,7 @@ hipError_t launch_flash_bwd(hipStream_t s, int seqs, int S, int heads, const uin
                                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (attr != hipSuccess) return attr;
   const float scale = 1.0f / sqrtf((float)DH);
-  hipLaunchKernelGGL(kernel, dim3((S + kBwdOwn - 1) / kBwdOwn, seqs * heads), dim3(64 * kBwdWaves), lds_bytes, s, S, heads, qkv, dout,
+  hipLaunchKernelGGL(kernel, dim3(seqs * heads, (S + kBwdOwn - 1) / kBwdOwn), dim3(64 * kBwdWaves), lds_bytes, s, S, heads, qkv, dout,
                      stat, dqkv, scale, scale * kLog2e);
   return hipGetLastError();
 }
