@@ -458,7 +458,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(int M, in
   }
   wait_vmcnt<0>();  // the trailing dummy copies must have landed before LDS is reused
   lds_barrier();    // all waves are done with the last stage
-  if constexpr (Epi::kSwap) {
+  if constexpr (Epi::kSwap && 64 % (4 * TN) == 0) {  // a row of the wave tile is stored by 4 * TN lanes
     if (m0 + wm + WM <= M && n0 + wn + WN <= N && (N & 7) == 0) {
       if constexpr (NW * wave_epilogue_bytes<TM, TN>() <= 160 * 1024) {
         float* wave_lds = reinterpret_cast<float*>(lds_raw) + wave * (wave_epilogue_bytes<TM, TN>() / 4);
@@ -497,7 +497,8 @@ hipError_t launch_dma(hipStream_t s, int M, int N, int K, const uint16_t* A, int
   constexpr size_t stage_bytes = (size_t)NS * (AT::kBytes + BT::kBytes);
   constexpr size_t epi_whole = (size_t)NW * wave_epilogue_bytes<BM / WGM / 32, BN / WGN / 32>();
   constexpr size_t epi_rows = (size_t)NW * wave_epilogue_bytes<1, BN / WGN / 32>();  // one 32-row block per wave
-  constexpr size_t epi_bytes = !Epi::kSwap ? 0 : epi_whole <= 160 * 1024 ? epi_whole : epi_rows;  // tiles turned through LDS
+  constexpr bool epi_lds = Epi::kSwap && 64 % (4 * (BN / WGN / 32)) == 0;
+  constexpr size_t epi_bytes = !epi_lds ? 0 : epi_whole <= 160 * 1024 ? epi_whole : epi_rows;  // tiles turned through LDS
   constexpr size_t lds_bytes = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
   static_assert(lds_bytes <= 160 * 1024, "stages do not fit the LDS of a CU");
   auto kernel = gemm_bf16_dma_kernel<BM, BN, WGM, WGN, NS, A_COL, B_COL, Epi, LEAN, ROT>;
@@ -524,12 +525,24 @@ int pick(int rows, int cols, int contraction, int lda, int ldb, bool a_col, bool
   if (override_cfg >= 0 && (override_cfg < 10 || dma)) return override_cfg;  // a direct-to-LDS tile only where it is valid
   auto blocks = [&](int bm, int bn) { return (long)((rows + bm - 1) / bm) * ((cols + bn - 1) / bn); };
   if (dma) {
-    // 8 waves on the big tiles: two waves per SIMD hide each other's LDS and barrier latency
-    if (blocks(256, 256) >= 256) return 18;
-    if (blocks(256, 128) >= 256) return 19;
-    if (blocks(128, 128) >= 256) return 12;
-    if (blocks(128, 64) >= 256) return 11;
-    return 10;
+    // The tile that needs the least time on 256 CUs, taken as (rounds of 256 workgroups) x (tile area) / (rate the
+    // tile sustains relative to the largest one): large tiles move less data per flop, but a last round that fills
+    // a fraction of the chip costs a whole round -- the 6144 x 2048 weight gradient of a fused QKV projection is 1.5
+    // rounds of 256x128 tiles, 192 tiles of 256x256 and exactly 256 tiles of 384x128 (51 us against 65 us and 57 us
+    // at 2048 rows).  The 384-wide tiles serve the fp32-output product only (three 32-wide blocks per wave row do
+    // not fit the 16-byte row stores of the bf16 epilogues) and only shapes they divide.
+    struct Tile { int cfg, bm, bn, rate; bool wgrad_only; };  // rate in per cent of the 256x256 tile's
+    static const Tile tiles[] = {{18, 256, 256, 100, false}, {25, 384, 128, 88, true}, {24, 128, 384, 88, true},
+                                 {19, 256, 128, 88, false},  {12, 128, 128, 78, false}, {11, 128, 64, 62, false},
+                                 {10, 64, 64, 45, false}};
+    int best = 10;
+    long best_cost = -1;
+    for (const Tile& t : tiles) {
+      if (t.wgrad_only && !(a_col && b_col && rows % t.bm == 0 && cols % t.bn == 0)) continue;
+      const long cost = ((blocks(t.bm, t.bn) + 255) / 256) * t.bm * t.bn * 100 / t.rate;
+      if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = t.cfg; }
+    }
+    return best;
   }
   if (blocks(128, 128) >= 256) return 2;
   if (blocks(128, 64) >= 128) return 1;
@@ -555,6 +568,8 @@ bool mfma_wgrad_supported(int M, int N, int K) { return M >= 1 && N % 8 == 0 && 
     case 12: return launch_dma<128, 128, 2, 2, 3, ACOL, BCOL, decltype(e), false, true>(__VA_ARGS__); \
     case 18: return launch_dma<256, 256, 2, 4, 2, ACOL, BCOL, decltype(e), false, true>(__VA_ARGS__); \
     case 19: return launch_dma<256, 128, 2, 4, 3, ACOL, BCOL, decltype(e), false, true>(__VA_ARGS__); \
+    case 24: return launch_dma<128, 384, 2, 4, 2, ACOL, BCOL, decltype(e), false, true>(__VA_ARGS__); \
+    case 25: return launch_dma<384, 128, 4, 2, 2, ACOL, BCOL, decltype(e), false, true>(__VA_ARGS__); \
     case 2: return launch<128, 128, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);         \
     case 1: return launch<128, 64, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);          \
     default: return launch<64, 64, 2, 2, 64, ACOL, BCOL>(__VA_ARGS__);          \
