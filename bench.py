@@ -55,10 +55,6 @@ def parse():
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
                     help="only run a plain device copy of BYTES bytes (5 untimed, 10 timed) and exit (calibration of the "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--library-gemm-probe", action="store_true",
-                    help="only time the vendor library's bf16 GEMM (torch.matmul, no bias, no activation) on the three "
-                         "products of one dense layer of the mlp workload and exit: context for the kernels' rates, "
-                         "no part of the measured path")
     return ap.parse_args()
 
 
@@ -191,31 +187,6 @@ def cpu_baseline(w, s, policy, minibatches):
                       f"of the same stage, numpy fp64, {dt:.1f} s"}
 
 
-def library_gemm_probe(torch, width, mb, n):
-    """Rates of the vendor library on the shapes of one dense layer: forward of one micro-batch (x W^T),
-    input gradient of the mini-batch (dz W) and weight gradient (dz^T x)."""
-    rows = mb * n
-    out = {}
-    for name, (M, N, K, ta, tb) in {"fprop": (mb, width, width, False, True),
-                                    "dgrad": (rows, width, width, False, False),
-                                    "wgrad": (width, width, rows, True, False)}.items():
-        a = torch.randn((K, M) if ta else (M, K), device="cuda:0", dtype=torch.bfloat16)
-        b = torch.randn((N, K) if tb else (K, N), device="cuda:0", dtype=torch.bfloat16)
-        A, Bm = (a.t() if ta else a), (b.t() if tb else b)
-        for _ in range(5):
-            A @ Bm
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(50):
-            A @ Bm
-        e1.record()
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / 50
-        out[name] = {"M": M, "N": N, "K": K, "avg_us": round(us, 1), "tflops": round(2.0 * M * N * K / us * 1e-6, 1)}
-    return out
-
-
 def main():
     args = parse()
     if args.gpus != 1:
@@ -239,9 +210,6 @@ def main():
         us = e0.elapsed_time(e1) * 100.0
         print(json.dumps({"copy_probe_bytes": args.copy_probe, "copies": 15, "avg_us": round(us, 1),
                           "gbs_read_plus_write": round(2 * args.copy_probe / us * 1e-3, 1)}))
-        return
-    if args.library_gemm_probe:
-        print(json.dumps({"library_gemm_probe": library_gemm_probe(torch, args.width, args.mb or 256, args.n or 8)}))
         return
     from paper_2509_23241_amd import binding as B
     from paper_2509_23241_amd.runner import GpuStage, layer_tuple

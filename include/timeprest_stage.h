@@ -251,9 +251,11 @@ int stage_blend_update(tp_stage* st, uint64_t mb_id_done, uint64_t mb_id_next_bw
  * ring slot.  TP_ENOVERSION if the ring does not hold it. */
 int stash_push(tp_stage* st, uint64_t version, uint32_t* slot);
 
-/* Drop one user of `version`; the slot is freed when no user is left and the version is
- * not the latest, else TP_EBUSY is returned (the count has still been decremented if it
- * was positive).  TP_ENOVERSION if the ring does not hold it. */
+/* Drop one user of `version` that was added with stash_push; the slot is freed when no user is left and
+ * the version is not the latest, else TP_EBUSY is returned (an outside user has still been dropped if there
+ * was one).  The users the stage holds itself -- mini-batches between their forward and their backward
+ * (Section "Memory Overhead") -- cannot be dropped from outside: with only those left the call changes
+ * nothing and returns TP_EBUSY.  TP_ENOVERSION if the ring does not hold the version. */
 int stash_evict(tp_stage* st, uint64_t version);
 
 /* Snapshot of the host bookkeeping. */

@@ -18,17 +18,11 @@ namespace tp {
 namespace {
 
 constexpr int kThreads = 256;
-// Launch shape of the update kernel (overridable at build time for tuning sweeps).
-#ifndef TP_UPDATE_BLOCKS
-#define TP_UPDATE_BLOCKS 2048  // 8 blocks per CU on 256 CUs; grid-stride beyond that
-#endif
-#ifndef TP_UPDATE_UNROLL
-#define TP_UPDATE_UNROLL 2
-#endif
-#ifndef TP_UPDATE_NT
-#define TP_UPDATE_NT 1  // non-temporal accesses for the streams that are not re-read soon
-#endif
-constexpr int kUpdateBlocks = TP_UPDATE_BLOCKS;
+// Launch shape of the update kernel: 8 blocks per CU on 256 CUs, grid-stride beyond that; two 16-byte
+// chunks per lane and stream in flight; non-temporal accesses for the streams that are not re-read soon.
+constexpr int kUpdateBlocks = 2048;
+constexpr int kUnroll = 2;
+constexpr bool kNonTemporal = true;
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -73,7 +67,6 @@ struct Store4<uint16_t> {
 // bytes each) before the first dependent instruction, so that each lane keeps up to 16 loads in
 // flight; the fp32 streams that are not re-read soon (momentum, new master weights) bypass the
 // caches with non-temporal accesses.
-constexpr int kUnroll = TP_UPDATE_UNROLL;
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
@@ -95,8 +88,8 @@ __global__ __launch_bounds__(kThreads) void update_kernel(size_t n4, const float
       const size_t i = base + (size_t)u * kThreads + threadIdx.x;
       ok[u] = i < n4;
       if (ok[u]) {
-        gv[u] = TP_UPDATE_NT ? __builtin_nontemporal_load(g + i) : g[i];
-        mv[u] = TP_UPDATE_NT ? __builtin_nontemporal_load(m + i) : m[i];
+        gv[u] = kNonTemporal ? __builtin_nontemporal_load(g + i) : g[i];
+        mv[u] = kNonTemporal ? __builtin_nontemporal_load(m + i) : m[i];
         wv[u] = w_old[i];
         if (BLEND) sv[u] = w_stale[i];
       }
@@ -113,7 +106,7 @@ __global__ __launch_bounds__(kThreads) void update_kernel(size_t n4, const float
         acc[0] = fmaf(gv[u][c], gv[u][c], acc[0]);
         acc[1] = fmaf(wn[c], wn[c], acc[1]);
       }
-      if (TP_UPDATE_NT) {
+      if (kNonTemporal) {
         __builtin_nontemporal_store(mn, m + i);
         __builtin_nontemporal_store(wn, w_new + i);
       } else {

@@ -542,7 +542,15 @@ int stash_evict(tp_stage* st, uint64_t version) {
   int s = st->find_slot(version);
   if (s < 0) return fail(TP_ENOVERSION, "version %llu is not in the ring", (unsigned long long)version);
   Slot& sl = st->slots[s];
-  if (sl.refcnt > 0) sl.refcnt--;
+  // Users the stage itself holds: mini-batches between their forward and their backward (Section "Memory
+  // Overhead": their stale version stays until their intermediate weights are built).  Only pins taken
+  // with stash_push can be dropped from outside.
+  uint32_t own = 0;
+  for (const InFlight& f : st->inflight)
+    if (f.pinned && f.v_f == version) ++own;
+  if (sl.refcnt > own) sl.refcnt--;
+  else if (own > 0)
+    return fail(TP_EBUSY, "version %llu is held by %u mini-batches in flight", (unsigned long long)version, own);
   if (sl.refcnt > 0) return fail(TP_EBUSY, "version %llu still has %u users", (unsigned long long)version, sl.refcnt);
   if (version == st->latest) return fail(TP_EBUSY, "version %llu is the latest", (unsigned long long)version);
   sl.occupied = false;

@@ -44,16 +44,20 @@ def stream_seed(name: str, seed: int = GLOBAL_SEED) -> int:
     return _mix_scalar(_mix_scalar(seed) ^ name_hash(name))
 
 
-def raw_u64(name: str, count: int, seed: int = GLOBAL_SEED) -> np.ndarray:
-    """`count` 64-bit words of the stream that belongs to `name`."""
-    s0 = np.uint64(stream_seed(name, seed))
+def _splitmix64_words(s0: int, count: int) -> np.ndarray:
+    """Words 1..count of the splitmix64 sequence whose state starts at s0 (word k mixes s0 + k*gamma)."""
     idx = np.arange(1, count + 1, dtype=np.uint64)
     with np.errstate(over="ignore"):
-        z = s0 + idx * _GAMMA
+        z = np.uint64(s0 & _MASK64) + idx * _GAMMA
         z = (z ^ (z >> np.uint64(30))) * _M1
         z = (z ^ (z >> np.uint64(27))) * _M2
         z = z ^ (z >> np.uint64(31))
     return z
+
+
+def raw_u64(name: str, count: int, seed: int = GLOBAL_SEED) -> np.ndarray:
+    """`count` 64-bit words of the stream that belongs to `name`."""
+    return _splitmix64_words(stream_seed(name, seed), count)
 
 
 def uniform01(name: str, count: int, seed: int = GLOBAL_SEED) -> np.ndarray:
@@ -91,12 +95,27 @@ def round_f32(x: np.ndarray) -> np.ndarray:
 
 
 def bf16_bits(x: np.ndarray) -> np.ndarray:
-    """fp -> bfloat16 bit patterns (uint16), round to nearest even."""
-    f = np.ascontiguousarray(np.asarray(x, dtype=np.float32))
-    u = f.view(np.uint32)
+    """fp -> bfloat16 bit patterns (uint16): ONE rounding to nearest, ties to even, from the value given.
+
+    An fp64 value is not rounded to fp32 on the way (two roundings to nearest can land one bfloat16 step
+    away from the single one): it is first cut to fp32 towards zero, with the last fp32 bit set when
+    anything was cut off, which keeps every case of the final rounding -- below, at or above the halfway
+    point -- what it was.  NaN gives a quiet NaN of the same sign; values at or beyond the halfway point
+    above the largest finite bfloat16 give infinity."""
+    v = np.ascontiguousarray(np.asarray(x, dtype=np.float64))
+    with np.errstate(over="ignore", invalid="ignore"):
+        f = v.astype(np.float32)
+        too_big = np.abs(f.astype(np.float64)) > np.abs(v)            # fp32 rounding went away from zero
+        f = np.where(too_big, np.nextafter(f, np.float32(0.0)), f).astype(np.float32)
+    u = np.ascontiguousarray(f).view(np.uint32).copy()
+    inexact = np.isfinite(v) & (f.astype(np.float64) != v)
+    u = np.where(inexact, u | np.uint32(1), u)
     lsb = (u >> np.uint32(16)) & np.uint32(1)
-    rounded = u + np.uint32(0x7FFF) + lsb
-    return (rounded >> np.uint32(16)).astype(np.uint16)
+    with np.errstate(over="ignore"):
+        rounded = (u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)
+    sign = (u >> np.uint32(16)) & np.uint32(0x8000)
+    rounded = np.where(np.isnan(v), sign | np.uint32(0x7FC0), rounded)
+    return rounded.astype(np.uint16)
 
 
 def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:

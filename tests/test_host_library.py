@@ -172,16 +172,37 @@ def test_error_codes():
     B.stage_backward(h, 0, 0, 0)
     assert code(B.stage_blend_update, h, 0, B.TP_NONE) == B.TP_EFULL
     B.stage_destroy(h)
-    # caller-driven eviction makes a later backward fail with TP_ENOVERSION
+    # a version held by a mini-batch in flight cannot be evicted from outside (Section "Memory Overhead": it stays
+    # until that mini-batch has built its intermediate weights); forward -> evict -> update -> backward works
     h = _dry_stage(2, 0, "eq1", C=2)
     for ub in range(2):
         B.stage_forward(h, 0, ub, 0, 0)
     for ub in range(2):
         B.stage_forward(h, 1, ub, 0, 0)
+    assert B.stash_evict(h, 0) == B.TP_EBUSY                              # two mini-batches forwarded on version 0
+    assert _live(B.stage_query(h)) == {0: 2}                              # and the count is untouched
     B.stage_backward(h, 0, 0, 0)
     B.stage_blend_update(h, 0, B.TP_NONE)
-    assert B.stash_evict(h, 0) == B.TP_OK                                 # drops mini-batch 1's pin, frees slot
-    assert code(B.stage_backward, h, 1, 0, 0) == B.TP_ENOVERSION
+    assert B.stash_evict(h, 0) == B.TP_EBUSY                              # still mini-batch 1's forward version
+    assert "in flight" in B.tp_last_error()
+    assert _live(B.stage_query(h)) == {0: 1, 1: 0}
+    # an outside user on top of the stage's own: its pin can be dropped, the stage's cannot
+    assert B.stash_push(h, 0) == 0
+    assert _live(B.stage_query(h)) == {0: 2, 1: 0}
+    assert B.stash_evict(h, 0) == B.TP_EBUSY and _live(B.stage_query(h)) == {0: 1, 1: 0}
+    assert B.stash_evict(h, 0) == B.TP_EBUSY and _live(B.stage_query(h)) == {0: 1, 1: 0}
+    assert B.stage_backward(h, 1, 0, 0) == 1                              # delta 1 on the stashed version 0
+    assert _live(B.stage_query(h)) == {1: 0}                              # last user gone: evicted
+    B.stage_destroy(h)
+    # an outside pin alone keeps a version, and dropping it frees the slot
+    h = _dry_stage(2, 0, "eq1", C=2)
+    B.stash_push(h, 0)
+    for ub in range(2):
+        B.stage_forward(h, 0, ub, 0, 0)
+    B.stage_backward(h, 0, 0, 0)
+    B.stage_blend_update(h, 0, B.TP_NONE)
+    assert _live(B.stage_query(h)) == {0: 1, 1: 0}
+    assert B.stash_evict(h, 0) == B.TP_OK and _live(B.stage_query(h)) == {1: 0}
     B.stage_destroy(h)
 
 
