@@ -217,6 +217,18 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
  * stage_forward needs no copy.  Valid for the mini-batch's first micro-batch onwards. */
 int stage_input_ptr(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, void** x_dev);
 
+/* Where the stage keeps the input of layer `layer` (0-based) for micro-batch `ub_idx` of the in-flight
+ * mini-batch `mb_id`: the tensor saved for the single backward pass of the mini-batch (Section "Methodology");
+ * for layer > 0 it is the stored output of layer - 1, [mb x values per sample] in the activation type.  For
+ * inspection (parity tests read every stored activation, not only the stage's output); the memory belongs to the
+ * stage and must not be written.  Valid from that micro-batch's stage_forward until the mini-batch's
+ * stage_backward.  Not every layer's input is materialised: the input of a residual add whose producer formed
+ * the sum in its own kernel, and of a few-channel first convolution (kept padded to 8 channels elsewhere), are
+ * never written -- the contents behind their pointers are unspecified.  bytes (optional) receives the size.
+ * TP_ESTATE: that micro-batch is not in flight. */
+int stage_saved_input_ptr(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, int32_t layer, void** x_dev,
+                          uint64_t* bytes);
+
 /* Softmax cross-entropy of a whole mini-batch at the last stage (Section "Methodology":
  * the loss is taken at the last node and starts the backward pass), mean over the n*mb
  * rows.  logits_dev: [n*mb x classes] in the activation type, labels_dev: int32[n*mb],

@@ -84,6 +84,8 @@ class Stage:
         W = [self.q(p) if p.ndim > 1 else p for p in self.weights[self.latest]]   # compute copy
         rec["versions"].append(self.latest)
         saved = []
+        outs = []                                          # inspection only: every layer's stored output, in layer order
+        rec.setdefault("outs", []).append(outs)
         a = np.asarray(x, dtype=np.float64)
         skip = None                                        # activation remembered by a residual "begin"
         for li, spec in enumerate(self.specs):
@@ -95,14 +97,17 @@ class Stage:
                 y, idx = L.maxpool2_forward(a)
                 saved.append((a.shape, idx))
                 a = y
+                outs.append(a)
                 continue
             if kind == "sub":
                 saved.append((a.shape,))
                 a = L.subsample2_forward(a)
+                outs.append(a)
                 continue
             if kind == "swap":                             # projection shortcut: the second branch starts from the
                 saved.append(None)                         # remembered tensor, the main branch's result waits for the add
                 a, skip = skip, a
+                outs.append(a)
                 continue
             if kind == "res":
                 if spec.mark == "begin":
@@ -112,20 +117,24 @@ class Stage:
                     z = a + skip.reshape(a.shape)
                     saved.append((None, z))
                     a = self.q(L.act_forward(z, spec.act))
+                outs.append(a)
                 continue
             if kind == "bn":
                 y, xhat, rstd = L.batchnorm_forward(a, W[pi], W[pi + 1])
                 saved.append((xhat, rstd, y))
                 a = self.q(L.act_forward(y, spec.act))
+                outs.append(a)
                 continue
             if kind == "ln":
                 y, xhat, rstd = L.layernorm_forward(a, W[pi], W[pi + 1])
                 saved.append((xhat, rstd))
                 a = self.q(y)
+                outs.append(a)
                 continue
             if kind == "attn":
                 saved.append((a,))
                 a = self.q(L.attention_forward(a, spec.heads))
+                outs.append(a)
                 continue
             if kind == "conv":
                 z = L.conv2d_forward(a, W[pi], W[pi + 1], spec.stride, spec.pad)
@@ -133,6 +142,7 @@ class Stage:
                 z = L.dense_forward(a, W[pi], W[pi + 1])
             saved.append((a, z))
             a = self.q(L.act_forward(z, spec.act))
+            outs.append(a)
         rec["saved"].append(saved)
         return a
 

@@ -20,7 +20,7 @@ POLICY = {"latest": TP_LATEST, "eq1": TP_INTERMEDIATE_EQ1, "convex": TP_INTERMED
 ACT = {"none": TP_ACT_NONE, "relu": TP_ACT_RELU, "gelu": TP_ACT_GELU}
 DTYPE = {"f32": TP_F32, "bf16": TP_BF16}
 
-EXPORTS = ["stage_workspace_query", "stage_init", "stage_destroy", "stage_forward", "stage_input_ptr",
+EXPORTS = ["stage_workspace_query", "stage_init", "stage_destroy", "stage_forward", "stage_input_ptr", "stage_saved_input_ptr",
            "stage_loss_softmax_ce", "stage_backward", "stage_blend_update", "stash_push", "stash_evict",
            "stage_query", "stage_export_params", "tp_blend_coefficients", "tp_schedule_events",
            "stage_profile_begin", "stage_profile_end", "tp_last_error"]
@@ -97,6 +97,7 @@ lib.stage_init.argtypes = [C.POINTER(tp_stage_desc), C.POINTER(tp_buffers), _vp,
 lib.stage_destroy.argtypes = [_vp]
 lib.stage_forward.argtypes = [_vp, _u64, _u32, _vp, _vp, C.POINTER(_u64)]
 lib.stage_input_ptr.argtypes = [_vp, _u64, _u32, C.POINTER(_vp)]
+lib.stage_saved_input_ptr.argtypes = [_vp, _u64, _u32, _i32, C.POINTER(_vp), C.POINTER(_u64)]
 lib.stage_loss_softmax_ce.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp]
 lib.stage_backward.argtypes = [_vp, _u64, _vp, _vp, C.POINTER(_u32)]
 lib.stage_blend_update.argtypes = [_vp, _u64, _u64, C.POINTER(_u64)]
@@ -258,6 +259,13 @@ def stage_input_ptr(st, mb_id: int, ub_idx: int) -> int:
     p = _vp()
     _check(lib.stage_input_ptr(st, mb_id, ub_idx, C.byref(p)))
     return p.value or 0
+
+
+def stage_saved_input_ptr(st, mb_id: int, ub_idx: int, layer: int):
+    """(device pointer, bytes) of the saved input of `layer` for micro-batch ub_idx of mini-batch mb_id."""
+    p, nb = _vp(), _u64()
+    _check(lib.stage_saved_input_ptr(st, mb_id, ub_idx, layer, C.byref(p), C.byref(nb)))
+    return (p.value or 0), nb.value
 
 
 def stage_loss_softmax_ce(st, mb_id: int, logits_dev: int, labels_dev: int, dlogits_dev: int, loss_dev: int):

@@ -577,6 +577,20 @@ int stage_input_ptr(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, void** x_dev)
   return TP_OK;
 }
 
+int stage_saved_input_ptr(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, int32_t layer, void** x_dev, uint64_t* bytes) {
+  if (!st || !x_dev) return fail(TP_EINVAL, "null argument");
+  if (layer < 0 || layer >= st->desc.num_layers) return fail(TP_EINVAL, "layer %d out of range", layer);
+  InFlight* f = st->find_mb(mb_id);
+  if (!f || ub_idx >= f->forwards)
+    return fail(TP_ESTATE, "micro-batch %u of mini-batch %llu has not been forwarded (or its backward is done)", ub_idx,
+                (unsigned long long)mb_id);
+  const LayerPlan& lp = st->plan.layers[layer];
+  const uint64_t nbytes = (uint64_t)st->desc.mb * lp.in_elems * st->plan.elt_size;
+  if (bytes) *bytes = nbytes;
+  *x_dev = st->dry ? nullptr : st->act_slot(f->act_slot) + lp.x_off + (uint64_t)ub_idx * nbytes;
+  return TP_OK;
+}
+
 int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_dev, void* y_dev,
                   uint64_t* version_used) {
   if (!st) return fail(TP_EINVAL, "null stage");

@@ -135,6 +135,12 @@ class GpuStage:
         nbytes = self.mb * self.in_elems * self.act_elt()
         return self.act[off: off + nbytes].view(self.tdtype).view(self.mb, self.in_elems)
 
+    def saved_input(self, mb_id: int, ub: int, layer: int) -> torch.Tensor:
+        """Tensor view [mb, values per sample] of the input the stage saved for `layer` (inspection only)."""
+        ptr, nbytes = B.stage_saved_input_ptr(self.handle, mb_id, ub, layer)
+        off = ptr - self.act.data_ptr()
+        return self.act[off: off + nbytes].view(self.tdtype).view(self.mb, -1)
+
     def act_elt(self) -> int:
         return 2 if self.dtype == "bf16" else 4
 

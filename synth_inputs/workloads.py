@@ -411,9 +411,13 @@ def stage_input(w: Workload, s: int, j: int) -> np.ndarray:
     return w.cast(x)
 
 
-def stage_upstream_grad(w: Workload, s: int, j: int) -> np.ndarray:
-    """Synthetic gradient w.r.t. the output of stage s: N(0,1)/sqrt(out_dim)."""
+def stage_upstream_grad(w: Workload, s: int, j: int, mean_loss: bool = False) -> np.ndarray:
+    """Synthetic gradient w.r.t. the output of stage s: N(0,1)/sqrt(out_dim), a sample's gradient has norm ~ 1.
+    mean_loss: the same draw scaled like the gradient of a loss AVERAGED over the mini-batch's n*mb samples
+    (a sample's gradient has norm ~ 1/(n*mb), as (softmax - onehot)/(n*mb) has at the last stage)."""
     d = w.stage_out_dim(s)
-    g = _normal(f"{w.name}/s{s}/dy/{j}", (w.n * w.mb,) + tuple(w.stages[s][-1].out_shape()),
-                std=float(1.0 / np.sqrt(d)), seed=w.seed)
+    std = 1.0 / np.sqrt(d)
+    if mean_loss:
+        std /= w.n * w.mb
+    g = _normal(f"{w.name}/s{s}/dy/{j}", (w.n * w.mb,) + tuple(w.stages[s][-1].out_shape()), std=float(std), seed=w.seed)
     return w.cast(g)

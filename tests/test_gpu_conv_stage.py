@@ -2,114 +2,12 @@
 synthetic inputs and upstream gradients through forward, backward (with real staleness under the
 I-TiMePReSt blend) and update, in both precisions, at shapes that cover image borders, channel
 counts that do and do not fit the matrix-core kernels, and the VGG-style first stage."""
-import numpy as np
 import pytest
 
-from oracle.stage import Stage
-from parity_utils import TOL, oracle_flat_to_arena, rel_err, to_np
+from stage_parity import run_stage as _run_stage
 from synth_inputs import workloads as W
 
 pytestmark = pytest.mark.gpu
-
-
-def _run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, depth=2, needs_dx=True, lr=None):
-    """Steady schedule of a stage of pipeline depth `depth`: forwards run `depth` mini-batches ahead.
-
-    The fp32 runs take large steps (lr 0.05): at tolerance 1e-4 any mix-up of weight versions in the
-    blend shows.  The bf16 runs take small ones (lr 0.002): with the synthetic upstream gradients a
-    large step changes the weights by O(1) per update and the ~1 % bf16 noise of one gradient would
-    compound through the following mini-batches instead of testing the kernels."""
-    if lr is None:
-        lr = 0.05 if dtype == "f32" else 0.002
-    import torch
-    from paper_2509_23241_amd.runner import GpuStage, layer_tuple
-
-    w = W.Workload(name=w_name, dtype=dtype, stages=(tuple(specs),) + ((),) * (depth - 1), mb=mb, n=n, classes=2)
-    params = W.init_params(w, 0)
-    # biases (and the scale / shift of normalisation layers) away from their initial 0 / 1, so that their
-    # gradients and updates are exercised
-    rng = np.random.default_rng(7)
-    params = [p if p.ndim > 1 else W.round_f32(p + rng.standard_normal(p.shape) * 0.1) for p in params]
-    # bf16 workloads: the oracle keeps its stored tensors in bf16 too (fp64 arithmetic), so that the
-    # choice of the maximum in a pooling window is taken in the same precision on both sides
-    ost = Stage(specs, params, policy=policy, lam=0.4, lr=lr, momentum=0.9, n=n, first_stage=not needs_dx,
-                storage=W.round_bf16 if dtype == "bf16" else None)
-    st = GpuStage([layer_tuple(l) for l in specs], params, dtype=dtype, mb=mb, n=n, stage_index=0, num_stages=depth,
-                  policy=policy, lam=0.4, lr=lr, momentum=0.9, needs_dx=needs_dx)
-    tol = TOL[dtype]
-    worst = {}
-    failures = []
-    # Pooling picks one element per window and ReLU one side of its kink.  Once the two sides have
-    # taken an update, their bf16 weight copies differ in the last bit for ~1 % of the weights,
-    # activations differ in the last bit here and there, and a window whose two largest values are a
-    # bf16 ulp apart may route its gradient to the other element (a pre-activation next to zero may
-    # switch its gradient on or off).  Forward outputs and updated weights are unaffected and stay
-    # within the normal tolerance.  Gradients are sums of terms of random sign (the synthetic
-    # upstream gradient has no preferred sign), so a fraction e of re-routed terms moves a sum by
-    # sqrt(e) of its size: a few percent for e ~ 1e-3.  Gradient tensors of stages with a pool or a
-    # ReLU are therefore held to the normal tolerance while both sides still run on identical
-    # weights (mini-batches whose forward preceded the first update -- these cover every staleness
-    # the schedule produces -- and everything in fp32) and to ROUTED_TOL afterwards.
-    # Behind a batch normalisation the same happens without any update: two bf16 executions of a deep
-    # stack differ by one ulp in a percent of the activations, the division by a channel's standard
-    # deviation carries that onto the pre-activations, and a ReLU next to zero decides differently
-    # (measured: ~1e-3 of the mask of a 128-channel layer, concentrated in a few channels, 2-5 % on the
-    # gradients; the fp32 run of the same stack agrees to 1e-6 and a smooth activation to 5e-3).
-    # Stages with ReLU behind a batch normalisation are held to the loose tolerance in bf16 from the start
-    # (0.25 for them: the flips of several normalised layers add up); what pins their kernels is the fp32
-    # run and the bf16 run with a smooth activation, both at the normal tolerances.
-    nonsmooth = any(l.kind == "pool" or getattr(l, "act", "") == "relu" for l in specs)
-    bn_relu = nonsmooth and any(l.kind == "bn" for l in specs)
-    ROUTED_TOL = 0.25 if bn_relu else 0.15
-    diverged = [bn_relu]
-
-    def note(k, e, routed=False):
-        worst[k] = max(worst.get(k, 0.0), e)
-        limit = ROUTED_TOL if (routed and dtype == "bf16" and diverged[0]) else tol
-        if not e <= limit:
-            failures.append((k, e))
-
-    def forward(j):
-        x = W.stage_input(w, 0, j)
-        xt = torch.from_numpy(x.reshape(n * mb, -1)).cuda().to(st.tdtype)
-        y = torch.empty(n * mb, st.out_elems, dtype=st.tdtype, device="cuda")
-        ref = []
-        for ub in range(n):
-            ref.append(ost.forward(j, ub, x[ub * mb:(ub + 1) * mb]))
-            _, v = st.forward(j, ub, xt[ub * mb:(ub + 1) * mb], y[ub * mb:(ub + 1) * mb])
-            assert v == ost.inflight[j]["v_f"]
-        note("y", rel_err(to_np(y), np.concatenate(ref).reshape(n * mb, -1)))
-
-    for j in range(depth):
-        forward(j)
-    for j in range(minibatches):
-        dy = W.stage_upstream_grad(w, 0, j)
-        dx_ref = ost.backward(j, dy)
-        dx, delta = st.backward(j, torch.from_numpy(dy.reshape(n * mb, -1)).cuda().to(st.tdtype))
-        assert delta == ost.trace[-1][4]
-        print(f"  mini-batch {j}: delta {delta}", {k: f"{v:.1e}" for k, v in worst.items()}, flush=True)
-        diverged[0] = bn_relu or j >= depth          # this mini-batch's forward ran after an update
-        if needs_dx:
-            note("dx", rel_err(to_np(dx), dx_ref.reshape(n * mb, -1)), routed=nonsmooth)
-        note("g", rel_err(to_np(st.grad), oracle_flat_to_arena(st, ost.flat(ost.g))), routed=nonsmooth)
-        # per-tensor gradients.  A tensor whose true gradient is zero (a bias in front of a batch
-        # normalisation: the mean subtraction removes it; what is left is the cancellation noise of a sum of
-        # terms that add up to zero) has no scale of its own: such tensors are measured against the typical
-        # gradient entry instead of their own (rounding-noise) norm.
-        g_rms = float(np.sqrt(np.mean(np.concatenate([r.reshape(-1) for r in ost.g]) ** 2)))
-        for pi, (got, ref) in enumerate(zip(st.unpack(to_np(st.grad)), ost.g)):
-            floor = g_rms * np.sqrt(ref.size)
-            if np.linalg.norm(ref) < 0.05 * floor:
-                note(f"g[{pi}]", float(np.linalg.norm(got.reshape(-1) - ref.reshape(-1)) / floor), routed=nonsmooth)
-            else:
-                note(f"g[{pi}]", rel_err(got, ref), routed=nonsmooth)
-        ost.update(j)
-        assert st.blend_update(j, j + 1) == ost.latest
-        note("W_new", rel_err(to_np(st.export(ost.latest)), oracle_flat_to_arena(st, ost.flat(ost.weights[ost.latest]))))
-        forward(j + depth)
-    st.close()
-    assert not failures, (failures, worst)
-    return worst
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -133,11 +31,13 @@ def test_conv_channels_multiple_of_64(dtype):
     print(dtype, _run_stage(specs, f"conv64_{dtype}", dtype, mb=4, n=2, depth=3, minibatches=4))
 
 
-def test_conv_matrix_core_tile_variants():
+@pytest.mark.parametrize("pure_oracle", [False, True])
+def test_conv_matrix_core_tile_variants(pure_oracle):
     # non-square power-of-two image, channel counts that are multiples of 64 but not of 128 (the
-    # narrower tiles), 768 pixels per mini-batch = six row tiles, no pooling: normal tolerance throughout
+    # narrower tiles), 768 pixels per mini-batch = six row tiles, no pooling: normal tolerance throughout,
+    # against the oracle with bf16-stored tensors and against the plain fp64 oracle
     specs = (W.Conv2d(128, 192, 4, 16, "gelu"), W.Conv2d(192, 64, 4, 16, "gelu"), W.Conv2d(64, 128, 4, 16, "none"))
-    print(_run_stage(specs, "convtiles_bf16", "bf16", mb=6, n=2, depth=2, minibatches=3))
+    print(_run_stage(specs, "convtiles_bf16", "bf16", mb=6, n=2, depth=2, minibatches=3, pure_oracle=pure_oracle))
 
 
 def test_first_layer_few_channels_bf16():
@@ -159,3 +59,37 @@ def test_vgg_first_stage_reduced_bf16():
 def test_vgg_first_stage_relu_fp32():
     w = W.vgg_stage0(mb=2, n=2, size=8, c1=16, c2=32, dtype="f32")
     print(_run_stage(w.stages[0], "vgg8px_f32", "f32", mb=2, n=2, depth=4, minibatches=4, needs_dx=False))
+
+
+# ---- ReLU in bf16 with masks that do not hinge on rounding: normal tolerance on every tensor ----------------------
+
+def test_conv_relu_fixed_masks_patch_kernels_bf16():
+    # 16x16 images (256 pixels: the patch kernels), few-channel first layer, 64 / 128 channels, ReLU everywhere with
+    # every pre-activation four standard deviations away from zero: the input-gradient kernels take their ReLU mask
+    # from the saved outputs and must meet the normal tolerance
+    specs = (W.Conv2d(3, 64, 16, 16, "relu"), W.Conv2d(64, 64, 16, 16, "relu"), W.Conv2d(64, 128, 16, 16, "relu"),
+             W.Conv2d(128, 64, 16, 16, "none"))
+    print(_run_stage(specs, "conv_relu_fixed_patch", "bf16", mb=4, n=2, depth=3, minibatches=4, needs_dx=False,
+                     fixed_masks=True))
+
+
+def test_conv_relu_fixed_masks_gather_kernels_bf16():
+    # 4x4 images (the gathered kernels), a ReLU in front of a subsampling (its mask is applied by the elementwise
+    # kernel) and in front of convolutions (by the input-gradient epilogue), input gradient requested
+    specs = (W.Conv2d(64, 128, 8, 8, "relu"), W.Subsample2(128, 8, 8), W.Conv2d(128, 128, 4, 4, "relu"),
+             W.Conv2d(128, 64, 4, 4, "relu"), W.Conv2d(64, 64, 4, 4, "none"))
+    print(_run_stage(specs, "conv_relu_fixed_gather", "bf16", mb=4, n=2, depth=2, minibatches=3, fixed_masks=True))
+
+
+def test_vgg_first_stage_reduced_relu_fixed_masks_bf16():
+    # the VGG-style stage 0 with its ReLUs and pools on 16x16 images; ReLU masks fixed, pooling windows decided by
+    # the data (differing windows are counted and must be near-ties)
+    w = W.vgg_stage0(mb=4, n=2, size=16)
+    print(_run_stage(w.stages[0], "vgg16px_relu_fixed", "bf16", mb=4, n=2, depth=4, minibatches=4, needs_dx=False,
+                     fixed_masks=True))
+
+
+def test_dense_relu_fixed_masks_bf16():
+    # dense ReLU layers at matrix-core shapes: dgrad with the mask read off the saved output
+    specs = (W.Dense(256, 512, "relu"), W.Dense(512, 256, "relu"), W.Dense(256, 128, "relu"), W.Dense(128, 64, "none"))
+    print(_run_stage(specs, "dense_relu_fixed", "bf16", mb=64, n=2, depth=3, minibatches=4, fixed_masks=True))

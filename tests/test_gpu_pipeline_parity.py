@@ -28,6 +28,16 @@ def _run_and_compare(w, policy, num_mb, fuse=True, tol=None):
         worst[name] = max(worst.get(name, 0.0), err)
         assert err <= tol, (name, err)
 
+    def per_tensor(name, got_arena, ref_arena, st):
+        """The whole arena and every weight matrix and bias vector in it on its own (a wrong bias vector is a few
+        thousand of millions of values: invisible in the norm of the whole arena)."""
+        note(name, rel_err(got_arena, ref_arena))
+        for pi, (got, ref) in enumerate(zip(st.unpack(got_arena), st.unpack(ref_arena))):
+            if np.linalg.norm(ref) > 0:
+                note(f"{name}[{pi}]", rel_err(got, ref))
+            else:
+                assert np.linalg.norm(got) == 0, (name, pi)
+
     def get_input(j):
         return torch.from_numpy(W.minibatch_input(w, j)).to(dev).to(tdt)
 
@@ -49,7 +59,7 @@ def _run_and_compare(w, policy, num_mb, fuse=True, tol=None):
             note("dy", rel_err(to_np(info["dy"]), ref["dy"]))
             if ref["dx"] is not None:
                 note("dx", rel_err(to_np(info["dx"]), ref["dx"]))
-            note("g", rel_err(to_np(st.grad), oracle_flat_to_arena(st, ref["g"])))
+            per_tensor("g", to_np(st.grad), oracle_flat_to_arena(st, ref["g"]), st)
             # the weights the backward ran on
             if delta > 0:
                 wb = to_np(st.wbwd)
@@ -60,11 +70,11 @@ def _run_and_compare(w, policy, num_mb, fuse=True, tol=None):
                 wb = to_np(st.ring[slot * st.P:(slot + 1) * st.P])
             wb_ref = oracle_flat_to_arena(st, ref["W_b"])
             # biases of the bf16 copies are compared too: they are blended like every parameter
-            note("W_b", rel_err(wb, wb_ref))
+            per_tensor("W_b", wb, wb_ref, st)
         if kind == "B" and phase == "done":
             assert info["new_version"] == ref["latest"]
-            note("m", rel_err(to_np(st.momentum), oracle_flat_to_arena(st, ref["m"])))
-            note("W_new", rel_err(to_np(st.export(ref["latest"])), oracle_flat_to_arena(st, ref["W_new"])))
+            per_tensor("m", to_np(st.momentum), oracle_flat_to_arena(st, ref["m"]), st)
+            per_tensor("W_new", to_np(st.export(ref["latest"])), oracle_flat_to_arena(st, ref["W_new"]), st)
             diag = st.diag.cpu().numpy()
             for key, idx in (("diag_grad_sq", B.TP_DIAG_GRAD_SQ), ("diag_weight_sq", B.TP_DIAG_WEIGHT_SQ)):
                 note(key, abs(diag[idx] - ref[key]) / (abs(ref[key]) + 1e-30))   # 2x the tensor tolerance never needed

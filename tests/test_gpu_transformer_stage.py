@@ -4,7 +4,7 @@ layers, causal multi-head attention and residual connections, driven like the ot
 import pytest
 
 from synth_inputs import workloads as W
-from test_gpu_conv_stage import _run_stage
+from stage_parity import run_stage as _run_stage
 
 pytestmark = pytest.mark.gpu
 
