@@ -259,6 +259,20 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
 int stage_blend_update(tp_stage* st, uint64_t mb_id_done, uint64_t mb_id_next_bwd,
                        uint64_t* new_version);
 
+/* stage_blend_update for callers that cannot allocate device memory and bring no workspace for it: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results,
+ * bookkeeping and errors as stage_blend_update; the block partials of the diagnostics live in a 32 KiB device
+ * array the library itself holds on every GPU it runs on (for the life of the process) instead of in
+ * tp_buffers.scratch_dev, so the call touches no memory but the stage's ring, momentum, gradient, compute
+ * copies and diag_dev, calls no allocating routine, and enqueues two kernels on the stage's stream.
+ * Stages of more than TP_NOALLOC_MAX_PARAMS parameters per version are refused with TP_EINVAL.  All stages on
+ * one GPU share that array: two such calls whose kernels may overlap on one GPU (different streams) race on
+ * the diagnostics; calls on one stream, or ordered by events, do not.  Nothing in the array has to be
+ * cleared between calls (every partial that is read has been written by the same call). */
+#define TP_NOALLOC_MAX_PARAMS (1ull << 31)
+int stage_blend_update_noalloc(tp_stage* st, uint64_t mb_id_done, uint64_t mb_id_next_bwd,
+                               uint64_t* new_version);
+
 /* Pin `version` for one more forward user (refcount + 1); slot (optional) receives its
  * ring slot.  TP_ENOVERSION if the ring does not hold it. */
 int stash_push(tp_stage* st, uint64_t version, uint32_t* slot);

@@ -21,7 +21,7 @@ ACT = {"none": TP_ACT_NONE, "relu": TP_ACT_RELU, "gelu": TP_ACT_GELU}
 DTYPE = {"f32": TP_F32, "bf16": TP_BF16}
 
 EXPORTS = ["stage_workspace_query", "stage_init", "stage_destroy", "stage_forward", "stage_input_ptr", "stage_saved_input_ptr",
-           "stage_loss_softmax_ce", "stage_backward", "stage_blend_update", "stash_push", "stash_evict",
+           "stage_loss_softmax_ce", "stage_backward", "stage_blend_update", "stage_blend_update_noalloc", "stash_push", "stash_evict",
            "stage_query", "stage_export_params", "tp_blend_coefficients", "tp_schedule_events",
            "stage_profile_begin", "stage_profile_end", "tp_last_error"]
 
@@ -101,6 +101,7 @@ lib.stage_saved_input_ptr.argtypes = [_vp, _u64, _u32, _i32, C.POINTER(_vp), C.P
 lib.stage_loss_softmax_ce.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp]
 lib.stage_backward.argtypes = [_vp, _u64, _vp, _vp, C.POINTER(_u32)]
 lib.stage_blend_update.argtypes = [_vp, _u64, _u64, C.POINTER(_u64)]
+lib.stage_blend_update_noalloc.argtypes = [_vp, _u64, _u64, C.POINTER(_u64)]
 lib.stash_push.argtypes = [_vp, _u64, C.POINTER(_u32)]
 lib.stash_evict.argtypes = [_vp, _u64]
 lib.stage_query.argtypes = [_vp, C.POINTER(tp_state)]
@@ -281,6 +282,12 @@ def stage_backward(st, mb_id: int, dy_dev: int, dx_dev: int) -> int:
 def stage_blend_update(st, mb_id_done: int, mb_id_next_bwd: int = TP_NONE) -> int:
     v = _u64()
     _check(lib.stage_blend_update(st, mb_id_done, mb_id_next_bwd, C.byref(v)))
+    return v.value
+
+
+def stage_blend_update_noalloc(st, mb_id_done: int, mb_id_next_bwd: int = TP_NONE) -> int:
+    v = _u64()
+    _check(lib.stage_blend_update_noalloc(st, mb_id_done, mb_id_next_bwd, C.byref(v)))
     return v.value
 
 

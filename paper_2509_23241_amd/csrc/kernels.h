@@ -80,5 +80,8 @@ struct UpdateArgs {
 };
 hipError_t launch_update(hipStream_t s, int elt, const UpdateArgs& a);
 size_t update_scratch_floats();
+// Device address, on the current GPU, of the library's own update_scratch_floats() floats of block partials
+// (a file-scope device array; looked up once per device).  Allocates nothing.
+hipError_t update_static_scratch(float** out, size_t* floats);
 
 }  // namespace tp

@@ -10,6 +10,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -286,6 +288,35 @@ hipError_t update_dispatch(hipStream_t s, const UpdateArgs& a) {
 }  // namespace
 
 size_t update_scratch_floats() { return 4 * (size_t)kUpdateBlocks; }
+
+namespace {
+// Block partials of the update kernel's diagnostics for the entry point that takes no workspace from the
+// caller and allocates nothing: 4 quantities x kUpdateBlocks floats (32 KiB), resident on every GPU the
+// library runs on until the process ends.  In host code this name is only a handle for the symbol lookup
+// below; kernels and copies get the device address that lookup returns.
+static __device__ __align__(256) float scratch[4 * kUpdateBlocks];
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+float* scratch_ptr[kMaxDevices] = {};  // per device: each GPU holds its own copy of the array at its own address
+}  // namespace
+
+hipError_t update_static_scratch(float** out, size_t* floats) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    float* p = nullptr;
+    e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));  // looked up with `dev` current
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    scratch_ptr[dev] = p;
+  }
+  *out = scratch_ptr[dev];
+  if (floats) *floats = 4 * (size_t)kUpdateBlocks;
+  return hipSuccess;
+}
 
 hipError_t launch_update(hipStream_t s, int elt, const UpdateArgs& a) {
   if (a.count % 4 != 0) return hipErrorInvalidValue;

@@ -1017,8 +1017,12 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
   return TP_OK;
 }
 
-int stage_blend_update(tp_stage* st, uint64_t mb_id_done, uint64_t mb_id_next_bwd, uint64_t* new_version) {
-  if (!st) return fail(TP_EINVAL, "null stage");
+}  // extern "C"
+
+namespace {
+// The update (Section "Pipeline Parallelism": after every mini-batch) with the look-ahead blend (Eq. 1-2);
+// `partials`: where the update kernel leaves the block partials of its diagnostics.
+int blend_update_impl(tp_stage* st, uint64_t mb_id_done, uint64_t mb_id_next_bwd, uint64_t* new_version, float* partials) {
   const tp_stage_desc& d = st->desc;
   if (!st->grad_pending || st->grad_mb != mb_id_done)
     return fail(TP_ESTATE, "no gradient of mini-batch %llu is pending", (unsigned long long)mb_id_done);
@@ -1061,7 +1065,7 @@ int stage_blend_update(tp_stage* st, uint64_t mb_id_done, uint64_t mb_id_next_bw
     u.mu = (float)d.momentum;
     u.alpha = (float)a;
     u.beta = (float)b;
-    u.partials = st->partials();
+    u.partials = partials;
     u.diag = (double*)st->bufs.diag_dev;
     ProfScope ps(st, TP_K_UPDATE);
     HIP_TRY(tp::launch_update(st->stream, d.dtype, u));
@@ -1079,6 +1083,29 @@ int stage_blend_update(tp_stage* st, uint64_t mb_id_done, uint64_t mb_id_next_bw
   st->grad_pending = false;
   if (new_version) *new_version = v + 1;
   return TP_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int stage_blend_update(tp_stage* st, uint64_t mb_id_done, uint64_t mb_id_next_bwd, uint64_t* new_version) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  return blend_update_impl(st, mb_id_done, mb_id_next_bwd, new_version, st->dry ? nullptr : st->partials());
+}
+
+int stage_blend_update_noalloc(tp_stage* st, uint64_t mb_id_done, uint64_t mb_id_next_bwd, uint64_t* new_version) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  if (st->plan.sizes.param_count > TP_NOALLOC_MAX_PARAMS)
+    return fail(TP_EINVAL, "stage_blend_update_noalloc takes at most %llu parameters per version, this stage has %llu",
+                (unsigned long long)TP_NOALLOC_MAX_PARAMS, (unsigned long long)st->plan.sizes.param_count);
+  float* partials = nullptr;
+  if (!st->dry) {
+    size_t floats = 0;
+    hipError_t e = tp::update_static_scratch(&partials, &floats);
+    if (e != hipSuccess) return fail(TP_EHIP, "address of the library's scratch array: %s", hipGetErrorString(e));
+    if (floats < tp::update_scratch_floats()) return fail(TP_EINVAL, "the library's scratch array is too small");
+  }
+  return blend_update_impl(st, mb_id_done, mb_id_next_bwd, new_version, partials);
 }
 
 int stage_query(const tp_stage* st, tp_state* out) {

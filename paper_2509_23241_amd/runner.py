@@ -168,6 +168,9 @@ class GpuStage:
     def blend_update(self, mb_done: int, mb_next: int = B.TP_NONE) -> int:
         return B.stage_blend_update(self.handle, mb_done, mb_next)
 
+    def blend_update_noalloc(self, mb_done: int, mb_next: int = B.TP_NONE) -> int:
+        return B.stage_blend_update_noalloc(self.handle, mb_done, mb_next)
+
     def query(self):
         return B.stage_query(self.handle)
 

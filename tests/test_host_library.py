@@ -206,6 +206,35 @@ def test_error_codes():
     B.stage_destroy(h)
 
 
+def test_noalloc_update_bookkeeping_and_size_limit():
+    # without device buffers the call is the bookkeeping of stage_blend_update, no kernel, no scratch lookup
+    h = _dry_stage(2, 0, "convex")
+    for j in range(2):
+        for ub in range(2):
+            B.stage_forward(h, j, ub, 0, 0)
+    B.stage_backward(h, 0, 0, 0)
+    assert B.stage_blend_update_noalloc(h, 0, 1) == 1
+    q = B.stage_query(h)
+    assert q.latest_version == 1 and q.wb_ready_mb == 1 and _live(q) == {0: 1, 1: 0}
+    with pytest.raises(B.StageLibError) as ei:
+        B.stage_blend_update_noalloc(h, 0, B.TP_NONE)                      # no gradient pending
+    assert ei.value.code == B.TP_ESTATE
+    B.stage_destroy(h)
+    # a stage beyond the stated maximum is refused before anything else happens
+    limit = int(re.search(r"#define TP_NOALLOC_MAX_PARAMS \(1ull << (\d+)\)", open(HEADER).read()).group(1))
+    d = B.make_desc([(65536, 65536, "none")], dtype="f32", mb=1, n=1, stage_index=0, num_stages=1, ring_capacity=1,
+                    max_in_flight=1, policy="latest", needs_dx=False, lam=0.1, lr=0.01, momentum=0.9)
+    assert B.stage_workspace_query(d).param_count > (1 << limit)
+    h = B.stage_init(d, None, 0)
+    B.stage_forward(h, 0, 0, 0, 0)
+    B.stage_backward(h, 0, 0, 0)
+    with pytest.raises(B.StageLibError) as ei:
+        B.stage_blend_update_noalloc(h, 0, B.TP_NONE)
+    assert ei.value.code == B.TP_EINVAL and "at most" in str(ei.value)
+    assert B.stage_blend_update(h, 0, B.TP_NONE) == 1                     # the workspace-based call has no such limit
+    B.stage_destroy(h)
+
+
 def test_invalid_descriptions():
     good = dict(dtype="f32", mb=2, n=2, stage_index=0, num_stages=2, ring_capacity=2, max_in_flight=2,
                 policy="eq1", needs_dx=False, lam=0.1, lr=0.01, momentum=0.9)
