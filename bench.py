@@ -50,6 +50,8 @@ def parse():
     ap.add_argument("--width", type=int, default=4096)
     ap.add_argument("--mb", type=int, default=None, help="micro-batch size (default 256 mlp, 64 vgg, 8 tfm)")
     ap.add_argument("--n", type=int, default=None, help="micro-batches per mini-batch (default 8 mlp, 4 vgg, 4 tfm)")
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="timed blocks of --steps steps each; the line reports the median block (and all of them)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-minibatches", type=int, default=3)
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
@@ -167,7 +169,7 @@ def cpu_baseline(w, s, policy, minibatches):
                first_stage=(s == 0))
     depth = w.K - s
     xs = [W.stage_input(w, s, j) for j in range(2)]
-    dys = [W.stage_upstream_grad(w, s, j) for j in range(2)]
+    dys = [W.stage_upstream_grad(w, s, j, mean_loss=True) for j in range(2)]
 
     def fwd(j):
         x = xs[j % 2]
@@ -253,7 +255,7 @@ def main():
     rows = w.n * w.mb
     nbuf = 2                                       # distinct synthetic mini-batches, resident in HBM
     xs = [torch.from_numpy(W.stage_input(w, s, j).reshape(rows, -1)).to(dev).to(tdt) for j in range(nbuf)]
-    dys = [torch.from_numpy(W.stage_upstream_grad(w, s, j).reshape(rows, -1)).to(dev).to(tdt) for j in range(nbuf)]
+    dys = [torch.from_numpy(W.stage_upstream_grad(w, s, j, mean_loss=True).reshape(rows, -1)).to(dev).to(tdt) for j in range(nbuf)]
     y = torch.empty(rows, st.out_elems, dtype=tdt, device=dev)
     dx = torch.empty(rows, st.in_elems, dtype=tdt, device=dev) if st.needs_dx else None
 
@@ -273,14 +275,28 @@ def main():
     for _ in range(args.warmup):
         step(j)
         j += 1
-    # pass 1: EXACTLY `steps` steps, nothing but the path itself on the stream -> value
+    # pass 1: blocks of EXACTLY `steps` steps, nothing but the path itself on the stream, each bracketed by a
+    # device synchronisation on both sides -> value from the median block, the others reported beside it
+    block_ms = []
+    for _ in range(max(1, args.repeats)):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step(j)
+            j += 1
+        torch.cuda.synchronize()
+        block_ms.append((time.perf_counter() - t0) / args.steps * 1e3)
+    dt = sorted(block_ms)[len(block_ms) // 2] * 1e-3 * args.steps
+    # what an event pair with nothing between it reads on this stream: taken off every event-bracketed kernel
+    # duration below (rocprofv3's kernel durations, which have no such term, are in profiles/)
+    pairs = []
+    for _ in range(200):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        e1.record()
+        pairs.append((e0, e1))
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(j)
-        j += 1
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    event_pair_us = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)[len(pairs) // 2]
     # pass 2: the same `steps` steps again with every kernel bracketed by HIP events on the stage's
     # stream -> per-kernel durations for the roofline.  (The event pairs cost several microseconds of
     # pipeline bubble each, which is why they are kept out of the pass that `value` comes from.)
@@ -305,8 +321,9 @@ def main():
             continue
         per_step = launches / args.steps
         flops, nbytes = (v / per_step for v in kernel_work(cls, w, s, st.needs_dx))
-        avg_us = ms / launches * 1e3
+        avg_us = max(ms / launches * 1e3 - event_pair_us, 1e-3)
         kernels[cls] = {"launches_per_step": launches / args.steps, "avg_us": round(avg_us, 2),
+                        "avg_us_with_event_pair": round(ms / launches * 1e3, 2),
                         "share_of_step": round(ms / args.steps / (dt_prof / args.steps * 1e3), 4),
                         "tflops": round(flops / (avg_us * 1e-6) / 1e12, 2) if flops else None,
                         "gbs": round(nbytes / (avg_us * 1e-6) / 1e9, 1) if nbytes else None}
@@ -332,7 +349,10 @@ def main():
     out = {
         "metric": "stage fwd+bwd samples/s on 1 MI355X; MFMA util %; blend/update HBM GB/s",
         "value": round(value, 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "ms_per_step_with_events": round(dt_prof / args.steps * 1e3, 4),
+        "ms_per_step": round(ms_per_step, 4), "repeats": len(block_ms),
+        "ms_per_step_blocks": [round(v, 4) for v in block_ms],
+        "ms_per_step_spread_pct": round(100 * (max(block_ms) - min(block_ms)) / ms_per_step, 2),
+        "ms_per_step_with_events": round(dt_prof / args.steps * 1e3, 4), "event_pair_us": round(event_pair_us, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{what}: bf16 activations, "

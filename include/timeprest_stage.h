@@ -145,7 +145,8 @@ typedef struct tp_sizes {
   uint64_t momentum_bytes;
   uint64_t grad_bytes;
   uint64_t wfwd_bytes;   /* bf16 copy of the latest version (0 in TP_F32 mode) */
-  uint64_t wbwd_bytes;   /* W_b compute copy, P elements of the activation type */
+  uint64_t wbwd_bytes;   /* W_b compute copy, P elements of the activation type (0 under TP_LATEST, which
+                            never builds intermediate weights: wbwd_dev may then be NULL) */
   uint64_t act_bytes;    /* saved activations of max_in_flight mini-batches */
   uint64_t scratch_bytes;/* backward temporaries and reduction partials */
   uint64_t diag_bytes;   /* TP_DIAG_COUNT doubles written by stage_blend_update */

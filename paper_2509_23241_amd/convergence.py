@@ -53,10 +53,15 @@ class TeacherData:
         self.w2 = S.normal("teacher/w2", (hidden, classes), std=4.0 / math.sqrt(hidden))
         self.cache: Dict[int, tuple] = {}
 
+    def host(self, j: int):
+        """(inputs in the storage type's values, labels) of mini-batch j as host arrays."""
+        x = S.normal(f"teacher/x/{j}", (self.rows, self.in_dim))
+        y = np.argmax(np.tanh(x @ self.w1) @ self.w2, axis=1).astype(np.int32)
+        return (S.round_bf16(x) if self.dtype == torch.bfloat16 else S.round_f32(x)), y
+
     def _make(self, j: int):
         if j not in self.cache:
-            x = S.normal(f"teacher/x/{j}", (self.rows, self.in_dim))
-            y = np.argmax(np.tanh(x @ self.w1) @ self.w2, axis=1).astype(np.int32)
+            x, y = self.host(j)
             self.cache[j] = (torch.from_numpy(x).to(self.device).to(self.dtype), torch.from_numpy(y).to(self.device))
         return self.cache[j]
 

@@ -565,6 +565,8 @@ bool mfma_wgrad_supported(int M, int N, int K) { return M >= 1 && N % 8 == 0 && 
   switch (cfg) {                                                                \
     case 10: return launch_dma<64, 64, 2, 2, 4, ACOL, BCOL, decltype(e), true>(__VA_ARGS__);  \
     case 11: return launch_dma<128, 64, 2, 2, 4, ACOL, BCOL, decltype(e), true>(__VA_ARGS__); \
+    case 30: return launch_dma<64, 64, 2, 2, 8, ACOL, BCOL, decltype(e), true>(__VA_ARGS__);  \
+    case 31: return launch_dma<64, 64, 2, 2, 6, ACOL, BCOL, decltype(e), true>(__VA_ARGS__);  \
     case 12: return launch_dma<128, 128, 2, 2, 3, ACOL, BCOL, decltype(e), false, true>(__VA_ARGS__); \
     case 18: return launch_dma<256, 256, 2, 4, 2, ACOL, BCOL, decltype(e), false, true>(__VA_ARGS__); \
     case 19: return launch_dma<256, 128, 2, 4, 3, ACOL, BCOL, decltype(e), false, true>(__VA_ARGS__); \

@@ -319,7 +319,7 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
   s.momentum_bytes = P * 4;
   s.grad_bytes = P * 4;
   s.wfwd_bytes = d->dtype == TP_BF16 ? P * 2 : 0;
-  s.wbwd_bytes = P * p->elt_size;
+  s.wbwd_bytes = d->policy == TP_LATEST ? 0 : P * p->elt_size;  // V-TiMePReSt never builds intermediate weights
   s.act_bytes = (uint64_t)d->max_in_flight * act;
   s.scratch_bytes = 3 * p->dz_bytes + p->partial_floats * 4 + 512 + p->attn_scratch_bytes;  // + an aligned block of 256 zero bytes (conv padding)
   s.diag_bytes = TP_DIAG_COUNT * sizeof(double);
@@ -494,8 +494,8 @@ int stage_init(const tp_stage_desc* desc, const tp_buffers* bufs, void* hip_stre
   if (bufs) {
     st->bufs = *bufs;
     const bool bf = desc->dtype == TP_BF16;
-    if (!bufs->ring_dev || !bufs->momentum_dev || !bufs->grad_dev || !bufs->wbwd_dev || !bufs->act_dev ||
-        !bufs->scratch_dev || !bufs->diag_dev || (bf && !bufs->wfwd_dev)) {
+    if (!bufs->ring_dev || !bufs->momentum_dev || !bufs->grad_dev || !bufs->act_dev || !bufs->scratch_dev ||
+        !bufs->diag_dev || (bf && !bufs->wfwd_dev) || (stashing(desc->policy) && !bufs->wbwd_dev)) {
       delete st;
       return fail(TP_EINVAL, "null device buffer");
     }

@@ -78,7 +78,7 @@ class GpuStage:
         self.momentum = torch.zeros(self.P, dtype=torch.float32, device=dev)
         self.grad = torch.zeros(self.P, dtype=torch.float32, device=dev)
         self.wfwd = torch.zeros(self.P if dtype == "bf16" else 64, dtype=torch.bfloat16, device=dev)
-        self.wbwd = torch.zeros(self.P, dtype=self.tdtype, device=dev)
+        self.wbwd = torch.zeros(max(self.sizes.wbwd_bytes // (2 if dtype == "bf16" else 4), 64), dtype=self.tdtype, device=dev)
         self.act = raw(self.sizes.act_bytes)
         self.scratch = raw(self.sizes.scratch_bytes)
         self.diag = torch.zeros(B.TP_DIAG_COUNT, dtype=torch.float64, device=dev)

@@ -321,3 +321,29 @@ def test_workspace_layout():
     assert s.param_count == s.b_offset[1] + 64 and s.param_count % 64 == 0
     assert s.ring_bytes == 2 * s.param_count * 4 and s.wfwd_bytes == 2 * s.param_count
     assert s.momentum_bytes == s.grad_bytes == 4 * s.param_count
+
+
+def test_memory_per_stage_and_policy_follows_the_papers_ordering():
+    # Section "Memory Overhead": V-TiMePReSt holds the least (one weight version, no intermediate weights), the
+    # stashing policies hold K - s versions at stage s; momentum, gradient and saved activations do not depend on
+    # the policy.  Sizes are the library's own workspace figures.
+    from paper_2509_23241_amd import footprint as F
+    from synth_inputs import workloads as W
+    w = W.mlp_wide()
+    for s in range(w.K):
+        v = F.stage_bytes(w, s, "latest")
+        P4 = 4 * v["params"]
+        assert v["ring_bytes"] == P4 and v["wbwd_bytes"] == 0 and v["wfwd_bytes"] == P4 // 2
+        for policy in ("eq1", "convex", "stashed"):
+            i = F.stage_bytes(w, s, policy)
+            assert i["ring_bytes"] == (w.K - s) * P4 and i["wbwd_bytes"] == P4 // 2
+            for k in ("momentum_bytes", "grad_bytes", "act_bytes", "scratch_bytes", "wfwd_bytes", "params"):
+                assert i[k] == v[k], k
+            assert i["total"] - v["total"] == (w.K - s - 1) * P4 + P4 // 2
+            assert i["total"] > v["total"]
+        assert v["act_bytes"] % (w.K - s) == 0                           # K - s mini-batches in flight
+    assert "| MLP width 4096, stage 0 | V-TiMePReSt |" in F.table(F.default_rows())
+    # a V-TiMePReSt stage can be created without a buffer for intermediate weights, a stashing one cannot
+    d = B.make_desc([(8, 8, "relu")], dtype="f32", mb=2, n=2, stage_index=0, num_stages=2, ring_capacity=1,
+                    max_in_flight=2, policy="latest", needs_dx=False, lam=0.1, lr=0.01, momentum=0.9)
+    assert B.stage_workspace_query(d).wbwd_bytes == 0
