@@ -67,7 +67,16 @@ enum tp_policy {
   TP_INTERMEDIATE_EQ1 = 1,    /* I-TiMePReSt as printed in Eq. 1: alpha = 2 - 1/f, beta = 0   */
   TP_INTERMEDIATE_CONVEX = 2, /* I-TiMePReSt read as a blend (Appendix A.2: the stale weight
                                  scaled by f, the rest 1-f to the latest): alpha=f, beta=1-f */
-  TP_STASHED = 3              /* backward on the forward's own version: alpha=1, beta=0      */
+  TP_STASHED = 3,             /* backward on the forward's own version: alpha=1, beta=0      */
+  TP_TIMEPREST = 4            /* the parent method (Sections "Methodology", "V-TiMePReSt" Challenge 1): no
+                                 horizontal stashing, but a pass cannot pick up updates that happen while it is
+                                 under way -- every stage of a pass reads the version that was the latest THERE
+                                 when the pass started.  The caller, who drives all stages, knows that version:
+                                 it pins it with stash_push when the pass starts, names it in stage_forward_on /
+                                 stage_backward_on, and drops it with stash_evict when the pass has left the
+                                 stage.  stage_forward / stage_backward read the latest version as under
+                                 TP_LATEST; nothing is pinned by the stage itself and no blend is built.  In
+                                 TP_BF16 mode wbwd_dev holds the compute copy of the one older version in use. */
 };
 
 enum tp_dtype { TP_F32 = 0, TP_BF16 = 1 };
@@ -214,6 +223,12 @@ int stage_destroy(tp_stage* st);
 int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_dev, void* y_dev,
                   uint64_t* version_used);
 
+/* TP_TIMEPREST only: stage_forward on `version` (which must be in the ring: pin it with stash_push when the
+ * pass starts) instead of the latest one.  TP_EINVAL under any other policy, TP_ENOVERSION if the ring does
+ * not hold the version. */
+int stage_forward_on(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, uint64_t version, const void* x_dev,
+                     void* y_dev);
+
 /* Where the stage wants the input of (mb_id, ub_idx) to be written so that
  * stage_forward needs no copy.  Valid for the mini-batch's first micro-batch onwards. */
 int stage_input_ptr(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, void** x_dev);
@@ -249,6 +264,10 @@ int stage_loss_softmax_ce(tp_stage* st, uint64_t mb_id, const void* logits_dev,
  * version is no longer in the ring. */
 int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev,
                    uint32_t* delta_used);
+
+/* TP_TIMEPREST only: stage_backward with every use of a parameter in the backward pass reading `version` as
+ * it is (the version the backward pass started on; no blend, delta plays no part).  Errors as stage_forward_on. */
+int stage_backward_on(tp_stage* st, uint64_t mb_id, uint64_t version, const void* dy_dev, void* dx_dev);
 
 /* Update after mini-batch `mb_id_done` (its backward must be the last one run):
  * m <- mu*m + g, W[v+1] = W[v] - lr*m written into ring slot (v+1) mod C, plus the bf16
@@ -303,11 +322,23 @@ typedef struct tp_event {
   int32_t t;
   int32_t kind;
   int32_t stage;
-  int32_t reserved;
+  int32_t ub;      /* micro-batch index of a forward event of tp_schedule_microbatch_events; else 0 */
   uint64_t mb_id;
 } tp_event;
 int tp_schedule_events(int32_t num_stages, uint64_t num_minibatches, tp_event* out,
                        uint64_t capacity, uint64_t* count);
+
+/* The same pipeline at micro-batch granularity, one box per stage and tick as the paper's timing figures are
+ * described (Section "Methodology", last paragraph): kind 0 = forward pass of ONE micro-batch (`ub`), 1 =
+ * backward pass of the mini-batch followed by its update.  A stage takes a micro-batch as soon as the stage
+ * before it has produced it, holds at most K-s mini-batches between first forward and backward, and lets a
+ * backward pass that is ready go first -- with mid_pass_updates != 0 also between two micro-batches of one
+ * mini-batch, so that the update lands in the middle of that mini-batch's forward pass and its remaining
+ * micro-batches read the newer weights (V-TiMePReSt "checks for the newer versions of weights even during the
+ * execution of a pass", Section "V-TiMePReSt"; the stashing policies need mid_pass_updates = 0).  With
+ * mid_pass_updates = 0 the version every mini-batch reads is the one tp_schedule_events gives.  Host only. */
+int tp_schedule_microbatch_events(int32_t num_stages, uint64_t num_minibatches, int32_t n,
+                                  int32_t mid_pass_updates, tp_event* out, uint64_t capacity, uint64_t* count);
 
 /* Measurement hooks (not part of the method): while profiling is on, every kernel the stage
  * enqueues is bracketed by a pair of HIP events on the stage's stream.  stage_profile_end waits

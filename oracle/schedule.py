@@ -98,3 +98,76 @@ def simulate(K: int, num_mb: int) -> Tuple[List[Event], Dict[Tuple[int, int], Tu
             events.append(Event(t, kind, s, j))
         t += 1
     return events, {k: tuple(v) for k, v in table.items()}
+
+
+# ---------------------------------------------------------------------------
+# Micro-batch granularity
+# ---------------------------------------------------------------------------
+
+@dataclass(frozen=True)
+class MicroEvent:
+    t: int        # time step
+    kind: str     # "F" forward of ONE micro-batch | "B" backward of the mini-batch + update
+    s: int        # stage
+    j: int        # mini-batch
+    ub: int       # micro-batch (0 for "B")
+    version: int  # latest version at the stage when the event runs (before the update of a "B")
+
+
+def simulate_microbatches(K: int, num_mb: int, n: int, mid_pass_updates: bool) -> List[MicroEvent]:
+    """The pipeline clock with one box per stage and time step, a box being the forward pass of one micro-batch
+    or the backward pass of one mini-batch (the way the paper's timing figures are described: Section
+    "Methodology", last paragraph).  A stage takes the next micro-batch as soon as the previous stage has
+    produced it, holds at most K - s mini-batches between their first forward and their backward, and gives a
+    backward pass that is ready precedence over further forwards:
+
+      mid_pass_updates = True   also between two micro-batches of one mini-batch -- the update then lands in
+                                the middle of that mini-batch's forward pass at this stage, and its remaining
+                                micro-batches read the newer weights.  Only V-TiMePReSt allows this (it "checks
+                                for the newer versions of weights even during the execution of a pass", Section
+                                "V-TiMePReSt", Challenge 1);
+      mid_pass_updates = False  only between mini-batches: a mini-batch whose forward has started at a stage
+                                finishes it on one version (what stashing a forward version needs).
+
+    Within a time step backward events are listed from the last stage to the first, then forward events from
+    the first stage to the last; an event sees what earlier time steps produced."""
+    nf = [[0, 0] for _ in range(K)]        # next forward per stage: (mini-batch, micro-batch)
+    nb = [0] * K                           # next backward per stage
+    version = [0] * K
+    f_done: Dict[Tuple[int, int, int], int] = {}
+    b_done: Dict[Tuple[int, int], int] = {}
+    events: List[MicroEvent] = []
+    t = 0
+    while any(nb[s] < num_mb for s in range(K)):
+        run = []
+        for s in range(K):
+            if nb[s] >= num_mb:
+                continue
+            jb = nb[s]
+            if s == K - 1:
+                b_ready = f_done.get((s, jb, n - 1), t) < t
+            else:
+                b_ready = b_done.get((s + 1, jb), t) < t
+            jf, ub = nf[s]
+            f_ready = jf < num_mb and (s == 0 or f_done.get((s - 1, jf, ub), t) < t) and \
+                (ub > 0 or jf - nb[s] < K - s)                      # a new mini-batch only below the in-flight limit
+            mid_pass = ub > 0                                       # a mini-batch's forward is under way here
+            if b_ready and (mid_pass_updates or not mid_pass or not f_ready):
+                run.append(("B", s, jb, 0))
+            elif f_ready:
+                run.append(("F", s, jf, ub))
+        if not run:
+            raise RuntimeError("pipeline deadlock")
+        order = sorted([e for e in run if e[0] == "B"], key=lambda e: -e[1]) + \
+                sorted([e for e in run if e[0] == "F"], key=lambda e: e[1])
+        for kind, s, j, ub in order:
+            events.append(MicroEvent(t, kind, s, j, ub, version[s]))
+            if kind == "F":
+                f_done[(s, j, ub)] = t
+                nf[s] = [j, ub + 1] if ub + 1 < n else [j + 1, 0]
+            else:
+                b_done[(s, j)] = t
+                version[s] += 1
+                nb[s] += 1
+        t += 1
+    return events

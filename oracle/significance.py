@@ -17,7 +17,7 @@ from __future__ import annotations
 
 import math
 
-POLICIES = ("latest", "eq1", "convex", "stashed")
+POLICIES = ("latest", "eq1", "convex", "stashed")   # the policies that fix the backward weights from (v_f, latest, delta)
 
 
 def f(delta: float, lam: float) -> float:

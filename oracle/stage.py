@@ -19,6 +19,15 @@ Follows, in event order:
 
 Parameters of a stage are a flat list [W0, b0, W1, b1, ...]; every entry is
 versioned, stashed and blended alike.
+
+Policy "timeprest" is the parent method as Sections "Methodology" and
+"V-TiMePReSt" (Challenge 1) describe it: no horizontal stashing (forward and
+backward of a mini-batch may read different versions) but a pass cannot pick
+up updates that happen while it is under way -- every stage of a pass reads
+the version that was the latest THERE when the pass started.  Which version
+that is, is known to whoever drives the stages (pipeline.py takes the
+snapshot when a pass starts); the stage is told the version per call and
+keeps it alive through pin()/unpin().
 """
 from __future__ import annotations
 
@@ -68,21 +77,41 @@ class Stage:
         self.trace: List[tuple] = []                       # (event, mb, v_f, v_now, delta)
 
     # -- forward ---------------------------------------------------------
-    def forward(self, mb: int, ub: int, x: np.ndarray) -> np.ndarray:
+    def pin(self, version: int) -> None:
+        """One more user of `version` (it stays in memory until unpinned and no longer the latest)."""
+        if version not in self.weights:
+            raise StageError(f"version {version} is not held")
+        self.refcnt[version] += 1
+
+    def unpin(self, version: int) -> None:
+        if self.refcnt.get(version, 0) <= 0:
+            raise StageError(f"version {version} has no user to drop")
+        self.refcnt[version] -= 1
+        self._evict_if_unused(version)
+
+    def forward(self, mb: int, ub: int, x: np.ndarray, version: Optional[int] = None) -> np.ndarray:
+        """version: the weights to read, for policy "timeprest" (default: the latest at the stage)."""
+        if version is not None and self.policy != "timeprest":
+            raise StageError("only the timeprest policy names the version of a pass")
         rec = self.inflight.get(mb)
         if rec is None:
             if ub != 0:
                 raise StageError("micro-batches of a mini-batch must arrive in order")
             rec = {"v_f": self.latest, "saved": [], "versions": []}
             self.inflight[mb] = rec
-            if self.policy != "latest":
+            if version is not None:
+                rec["v_f"] = version
+            if self.policy not in ("latest", "timeprest"):
                 self.refcnt[self.latest] += 1              # stash: one user per mini-batch
         if ub != len(rec["saved"]) or ub >= self.n:
             raise StageError("micro-batch index out of order")
-        if self.policy != "latest" and rec["v_f"] != self.latest:
+        if self.policy not in ("latest", "timeprest") and rec["v_f"] != self.latest:
             raise StageError("update landed between micro-batches of one mini-batch")
-        W = [self.q(p) if p.ndim > 1 else p for p in self.weights[self.latest]]   # compute copy
-        rec["versions"].append(self.latest)
+        v_read = self.latest if version is None else version
+        if v_read not in self.weights:
+            raise StageError(f"version {v_read} is not held")
+        W = [self.q(p) if p.ndim > 1 else p for p in self.weights[v_read]]        # compute copy
+        rec["versions"].append(v_read)
         saved = []
         outs = []                                          # inspection only: every layer's stored output, in layer order
         rec.setdefault("outs", []).append(outs)
@@ -147,10 +176,15 @@ class Stage:
         return a
 
     # -- backward weights ------------------------------------------------
-    def backward_weights(self, mb: int):
+    def backward_weights(self, mb: int, version: Optional[int] = None):
         """W_b for mini-batch mb and the (v_f, v_now, delta) triple behind it."""
         rec = self.inflight[mb]
         v_now = self.latest
+        if self.policy == "timeprest":                     # the version the backward pass started on, as it is
+            v_b = v_now if version is None else version
+            if v_b not in self.weights:
+                raise StageError(f"version {v_b} is not held")
+            return self.weights[v_b], (rec["versions"][0], v_b, 0)
         if self.policy == "latest":
             return self.weights[v_now], (rec["versions"][0], v_now, 0)
         v_f = rec["v_f"]
@@ -166,11 +200,13 @@ class Stage:
         return W_b, (v_f, v_now, delta)
 
     # -- backward --------------------------------------------------------
-    def backward(self, mb: int, dy: np.ndarray) -> Optional[np.ndarray]:
+    def backward(self, mb: int, dy: np.ndarray, version: Optional[int] = None) -> Optional[np.ndarray]:
         rec = self.inflight.get(mb)
         if rec is None or len(rec["saved"]) != self.n:
             raise StageError("backward needs all n micro-batch forwards of the mini-batch")
-        W_b, (v_f, v_now, delta) = self.backward_weights(mb)
+        if version is not None and self.policy != "timeprest":
+            raise StageError("only the timeprest policy names the version of a pass")
+        W_b, (v_f, v_now, delta) = self.backward_weights(mb, version)
         self.last_W_b = W_b
         W_b = [self.q(p) if p.ndim > 1 else p for p in W_b]                       # compute copy
         self.trace.append(("B", mb, v_f, v_now, delta))
@@ -238,7 +274,7 @@ class Stage:
             dx_parts.append(self.q(da))
         self.g = g
         # the intermediate weights are built: this mini-batch no longer needs its stale version
-        if self.policy != "latest":
+        if self.policy not in ("latest", "timeprest"):
             self.refcnt[rec["v_f"]] -= 1
             self._evict_if_unused(rec["v_f"])
         del self.inflight[mb]

@@ -7,7 +7,7 @@ import os
 from .build import lib_path
 
 TP_OK, TP_EINVAL, TP_ESTATE, TP_ENOVERSION, TP_EFULL, TP_EBUSY, TP_EHIP = 0, -1, -2, -3, -4, -5, -6
-TP_LATEST, TP_INTERMEDIATE_EQ1, TP_INTERMEDIATE_CONVEX, TP_STASHED = 0, 1, 2, 3
+TP_LATEST, TP_INTERMEDIATE_EQ1, TP_INTERMEDIATE_CONVEX, TP_STASHED, TP_TIMEPREST = 0, 1, 2, 3, 4
 TP_F32, TP_BF16 = 0, 1
 TP_ACT_NONE, TP_ACT_RELU, TP_ACT_GELU = 0, 1, 2
 TP_LAYER_DENSE, TP_LAYER_CONV2D, TP_LAYER_MAXPOOL2, TP_LAYER_LAYERNORM, TP_LAYER_ATTENTION, TP_LAYER_RESIDUAL, TP_LAYER_BATCHNORM = 0, 1, 2, 3, 4, 5, 6
@@ -16,13 +16,14 @@ TP_MAX_LAYERS, TP_MAX_SLOTS, TP_MAX_IN_FLIGHT = 64, 16, 16
 TP_NONE = (1 << 64) - 1
 TP_DIAG_GRAD_SQ, TP_DIAG_WEIGHT_SQ, TP_DIAG_DRIFT_SQ, TP_DIAG_WB_SQ, TP_DIAG_COUNT = 0, 1, 2, 3, 4
 
-POLICY = {"latest": TP_LATEST, "eq1": TP_INTERMEDIATE_EQ1, "convex": TP_INTERMEDIATE_CONVEX, "stashed": TP_STASHED}
+POLICY = {"latest": TP_LATEST, "eq1": TP_INTERMEDIATE_EQ1, "convex": TP_INTERMEDIATE_CONVEX, "stashed": TP_STASHED,
+          "timeprest": TP_TIMEPREST}
 ACT = {"none": TP_ACT_NONE, "relu": TP_ACT_RELU, "gelu": TP_ACT_GELU}
 DTYPE = {"f32": TP_F32, "bf16": TP_BF16}
 
-EXPORTS = ["stage_workspace_query", "stage_init", "stage_destroy", "stage_forward", "stage_input_ptr", "stage_saved_input_ptr",
+EXPORTS = ["stage_workspace_query", "stage_init", "stage_destroy", "stage_forward", "stage_forward_on", "stage_backward_on", "stage_input_ptr", "stage_saved_input_ptr",
            "stage_loss_softmax_ce", "stage_backward", "stage_blend_update", "stage_blend_update_noalloc", "stash_push", "stash_evict",
-           "stage_query", "stage_export_params", "tp_blend_coefficients", "tp_schedule_events",
+           "stage_query", "stage_export_params", "tp_blend_coefficients", "tp_schedule_events", "tp_schedule_microbatch_events",
            "stage_profile_begin", "stage_profile_end", "tp_last_error"]
 
 
@@ -60,7 +61,7 @@ class tp_state(C.Structure):
 
 
 class tp_event(C.Structure):
-    _fields_ = [("t", C.c_int32), ("kind", C.c_int32), ("stage", C.c_int32), ("reserved", C.c_int32),
+    _fields_ = [("t", C.c_int32), ("kind", C.c_int32), ("stage", C.c_int32), ("ub", C.c_int32),
                 ("mb_id", C.c_uint64)]
 
 
@@ -96,6 +97,8 @@ lib.stage_workspace_query.argtypes = [C.POINTER(tp_stage_desc), C.POINTER(tp_siz
 lib.stage_init.argtypes = [C.POINTER(tp_stage_desc), C.POINTER(tp_buffers), _vp, C.POINTER(_vp)]
 lib.stage_destroy.argtypes = [_vp]
 lib.stage_forward.argtypes = [_vp, _u64, _u32, _vp, _vp, C.POINTER(_u64)]
+lib.stage_forward_on.argtypes = [_vp, _u64, _u32, _u64, _vp, _vp]
+lib.stage_backward_on.argtypes = [_vp, _u64, _u64, _vp, _vp]
 lib.stage_input_ptr.argtypes = [_vp, _u64, _u32, C.POINTER(_vp)]
 lib.stage_saved_input_ptr.argtypes = [_vp, _u64, _u32, _i32, C.POINTER(_vp), C.POINTER(_u64)]
 lib.stage_loss_softmax_ce.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp]
@@ -108,6 +111,7 @@ lib.stage_query.argtypes = [_vp, C.POINTER(tp_state)]
 lib.stage_export_params.argtypes = [_vp, _u64, _vp]
 lib.tp_blend_coefficients.argtypes = [_i32, _u32, C.c_double, C.POINTER(C.c_double), C.POINTER(C.c_double)]
 lib.tp_schedule_events.argtypes = [_i32, _u64, C.POINTER(tp_event), _u64, C.POINTER(_u64)]
+lib.tp_schedule_microbatch_events.argtypes = [_i32, _u64, _i32, _i32, C.POINTER(tp_event), _u64, C.POINTER(_u64)]
 lib.stage_profile_begin.argtypes = [_vp, _u32]
 lib.stage_profile_end.argtypes = [_vp, C.POINTER(tp_profile)]
 lib.tp_last_error.restype = C.c_char_p
@@ -256,6 +260,14 @@ def stage_forward(st, mb_id: int, ub_idx: int, x_dev: int, y_dev: int) -> int:
     return v.value
 
 
+def stage_forward_on(st, mb_id: int, ub_idx: int, version: int, x_dev: int, y_dev: int):
+    _check(lib.stage_forward_on(st, mb_id, ub_idx, version, _vp(x_dev), _vp(y_dev)))
+
+
+def stage_backward_on(st, mb_id: int, version: int, dy_dev: int, dx_dev: int):
+    _check(lib.stage_backward_on(st, mb_id, version, _vp(dy_dev), _vp(dx_dev)))
+
+
 def stage_input_ptr(st, mb_id: int, ub_idx: int) -> int:
     p = _vp()
     _check(lib.stage_input_ptr(st, mb_id, ub_idx, C.byref(p)))
@@ -326,6 +338,16 @@ def tp_schedule_events(num_stages: int, num_minibatches: int):
     cnt = _u64()
     _check(lib.tp_schedule_events(num_stages, num_minibatches, arr, cap, C.byref(cnt)))
     return [(arr[i].t, "FB"[arr[i].kind], arr[i].stage, arr[i].mb_id) for i in range(cnt.value)]
+
+
+def tp_schedule_microbatch_events(num_stages: int, num_minibatches: int, n: int, mid_pass_updates: bool):
+    """List of (t, kind, stage, mb_id, ub); kind 'F' (one micro-batch) or 'B' (backward + update, ub 0)."""
+    cap = num_stages * num_minibatches * (n + 1)
+    arr = (tp_event * max(cap, 1))()
+    cnt = _u64()
+    _check(lib.tp_schedule_microbatch_events(num_stages, num_minibatches, n, 1 if mid_pass_updates else 0, arr, cap,
+                                             C.byref(cnt)))
+    return [(arr[i].t, "FB"[arr[i].kind], arr[i].stage, arr[i].mb_id, arr[i].ub) for i in range(cnt.value)]
 
 
 def stage_profile_begin(st, max_launches: int):

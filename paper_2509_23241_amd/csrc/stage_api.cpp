@@ -89,7 +89,7 @@ int check_desc(const tp_stage_desc* d) {
     return fail(TP_EINVAL, "ring_capacity %d outside 1..%d", d->ring_capacity, TP_MAX_SLOTS);
   if (d->max_in_flight < 1 || d->max_in_flight > TP_MAX_IN_FLIGHT)
     return fail(TP_EINVAL, "max_in_flight %d outside 1..%d", d->max_in_flight, TP_MAX_IN_FLIGHT);
-  if (d->policy < TP_LATEST || d->policy > TP_STASHED) return fail(TP_EINVAL, "unknown policy %d", d->policy);
+  if (d->policy < TP_LATEST || d->policy > TP_TIMEPREST) return fail(TP_EINVAL, "unknown policy %d", d->policy);
   if (!(d->lambda > 0.0) || !std::isfinite(d->lambda)) return fail(TP_EINVAL, "lambda must be > 0");
   if (!std::isfinite(d->lr) || !std::isfinite(d->momentum)) return fail(TP_EINVAL, "lr/momentum not finite");
   uint64_t prev_out = 0;
@@ -326,7 +326,8 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
   return TP_OK;
 }
 
-bool stashing(int policy) { return policy != TP_LATEST; }
+// policies under which a mini-batch's forward version is stashed for its backward pass
+bool stashing(int policy) { return policy == TP_INTERMEDIATE_EQ1 || policy == TP_INTERMEDIATE_CONVEX || policy == TP_STASHED; }
 
 }  // namespace
 
@@ -355,6 +356,10 @@ struct tp_stage {
   // W_b prepared ahead by the fused update
   bool wb_valid = false;
   uint64_t wb_mb = TP_NONE, wb_vf = 0, wb_vnow = 0;
+  // TP_TIMEPREST in bf16 mode: the version whose compute copy wbwd_dev holds (passes on a version that is no
+  // longer the latest read their weights from there)
+  bool copy_valid = false;
+  uint64_t copy_version = 0;
 
   int find_slot(uint64_t v) const {
     const Slot& s = slots[v % desc.ring_capacity];
@@ -415,6 +420,7 @@ int tp_blend_coefficients(int32_t policy, uint32_t delta, double lambda, double*
   switch (policy) {
     case TP_LATEST: *alpha = 0.0; *beta = 1.0; break;
     case TP_STASHED: *alpha = 1.0; *beta = 0.0; break;
+    case TP_TIMEPREST: *alpha = 1.0; *beta = 0.0; break;   // the version the pass started on, as it is
     case TP_INTERMEDIATE_EQ1: *alpha = 2.0 - 1.0 / f; *beta = 0.0; break;          // Eq. 1
     case TP_INTERMEDIATE_CONVEX: *alpha = f; *beta = 1.0 - f; break;               // Appendix A.2
     default: return fail(TP_EINVAL, "unknown policy %d", policy);
@@ -470,6 +476,57 @@ int tp_schedule_events(int32_t K, uint64_t num_mb, tp_event* out, uint64_t capac
   return TP_OK;
 }
 
+int tp_schedule_microbatch_events(int32_t K, uint64_t num_mb, int32_t n, int32_t mid_pass_updates, tp_event* out,
+                                  uint64_t capacity, uint64_t* count) {
+  if (K < 1 || K > 1024 || n < 1 || n > 65536 || !count) return fail(TP_EINVAL, "bad schedule arguments");
+  // One box per stage and tick: the forward pass of one micro-batch or the backward pass (and update) of one
+  // mini-batch.  A stage holds at most K-s mini-batches between first forward and backward; a backward pass that
+  // is ready goes first -- between two micro-batches of one mini-batch only if mid_pass_updates is set.
+  struct StageCursor { uint64_t f_mb = 0; int32_t f_ub = 0; uint64_t b_mb = 0; };
+  std::vector<StageCursor> cur(K);
+  // tick at which (stage, mini-batch, micro-batch) was forwarded / (stage, mini-batch) went backward; -1: not yet
+  std::vector<std::vector<int64_t>> f_at(K, std::vector<int64_t>(num_mb * (uint64_t)n, -1));
+  std::vector<std::vector<int64_t>> b_at(K, std::vector<int64_t>(num_mb, -1));
+  struct Box { int kind, s, ub; uint64_t j; };
+  uint64_t emitted = 0;
+  const uint64_t total = (uint64_t)K * num_mb * ((uint64_t)n + 1);
+  for (int64_t t = 0; emitted < total; ++t) {
+    if (t > (int64_t)(4 * total + 16)) return fail(TP_ESTATE, "schedule did not terminate");
+    std::vector<Box> bwd, fwd;
+    for (int s = 0; s < K; ++s) {
+      const StageCursor& c = cur[s];
+      if (c.b_mb >= num_mb) continue;
+      const int64_t b_dep = s == K - 1 ? f_at[s][c.b_mb * n + (n - 1)] : b_at[s + 1][c.b_mb];
+      const bool b_ready = b_dep >= 0 && b_dep < t;
+      bool f_ready = c.f_mb < num_mb;
+      if (f_ready && s > 0) {
+        const int64_t dep = f_at[s - 1][c.f_mb * n + c.f_ub];
+        f_ready = dep >= 0 && dep < t;
+      }
+      if (f_ready && c.f_ub == 0) f_ready = c.f_mb - c.b_mb < (uint64_t)(K - s);   // a new mini-batch: in-flight limit
+      const bool mid_pass = c.f_ub > 0;
+      if (b_ready && (mid_pass_updates || !mid_pass || !f_ready)) bwd.push_back(Box{1, s, 0, c.b_mb});
+      else if (f_ready) fwd.push_back(Box{0, s, c.f_ub, c.f_mb});
+    }
+    if (bwd.empty() && fwd.empty()) return fail(TP_ESTATE, "schedule deadlock");
+    for (auto it = bwd.rbegin(); it != bwd.rend(); ++it) {
+      b_at[it->s][it->j] = t;
+      cur[it->s].b_mb++;
+      if (out && emitted < capacity) out[emitted] = tp_event{(int32_t)t, 1, it->s, 0, it->j};
+      ++emitted;
+    }
+    for (const Box& b : fwd) {
+      f_at[b.s][b.j * n + b.ub] = t;
+      StageCursor& c = cur[b.s];
+      if (++c.f_ub == n) { c.f_ub = 0; c.f_mb++; }
+      if (out && emitted < capacity) out[emitted] = tp_event{(int32_t)t, 0, b.s, b.ub, b.j};
+      ++emitted;
+    }
+  }
+  *count = emitted;
+  return TP_OK;
+}
+
 int stage_workspace_query(const tp_stage_desc* desc, tp_sizes* out) {
   if (!out) return fail(TP_EINVAL, "null output");
   Plan p;
@@ -495,7 +552,7 @@ int stage_init(const tp_stage_desc* desc, const tp_buffers* bufs, void* hip_stre
     st->bufs = *bufs;
     const bool bf = desc->dtype == TP_BF16;
     if (!bufs->ring_dev || !bufs->momentum_dev || !bufs->grad_dev || !bufs->act_dev || !bufs->scratch_dev ||
-        !bufs->diag_dev || (bf && !bufs->wfwd_dev) || (stashing(desc->policy) && !bufs->wbwd_dev)) {
+        !bufs->diag_dev || (bf && !bufs->wfwd_dev) || (desc->policy != TP_LATEST && !bufs->wbwd_dev)) {
       delete st;
       return fail(TP_EINVAL, "null device buffer");
     }
@@ -591,12 +648,33 @@ int stage_saved_input_ptr(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, int32_t
   return TP_OK;
 }
 
-int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_dev, void* y_dev,
-                  uint64_t* version_used) {
-  if (!st) return fail(TP_EINVAL, "null stage");
+}  // extern "C"
+
+namespace {
+// bf16 compute copy of a version that is not the latest (TP_TIMEPREST): converted into wbwd_dev on demand
+int old_version_copy(tp_stage* st, uint64_t v, int slot, const char** out) {
+  if (!(st->copy_valid && st->copy_version == v)) {
+    ProfScope ps(st, TP_K_COPY);
+    HIP_TRY(tp::launch_convert(st->stream, tp::ELT_BF16, st->plan.sizes.param_count, st->ring(slot), st->bufs.wbwd_dev));
+    st->copy_valid = true;
+    st->copy_version = v;
+    st->wb_valid = false;
+  }
+  *out = (const char*)st->bufs.wbwd_dev;
+  return TP_OK;
+}
+
+// `version`: TP_NONE = the latest version at the stage (every policy); a retained version under TP_TIMEPREST
+int forward_impl(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_dev, void* y_dev, uint64_t version,
+                 uint64_t* version_used) {
   if (!st->dry && (!x_dev || !y_dev)) return fail(TP_EINVAL, "null activation pointer");
   if (mb_id == TP_NONE) return fail(TP_EINVAL, "reserved mini-batch id");
   const tp_stage_desc& d = st->desc;
+  if (version != TP_NONE && d.policy != TP_TIMEPREST)
+    return fail(TP_EINVAL, "only TP_TIMEPREST names the version a pass reads");
+  const uint64_t v_read = version == TP_NONE ? st->latest : version;
+  if (st->find_slot(v_read) < 0)
+    return fail(TP_ENOVERSION, "version %llu is not in the ring", (unsigned long long)v_read);
   InFlight* f = st->find_mb(mb_id);
   if (!f) {
     if (ub_idx != 0) return fail(TP_ESTATE, "mini-batch %llu: first forward must be micro-batch 0", (unsigned long long)mb_id);
@@ -604,7 +682,7 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
     for (int i = 0; i < d.max_in_flight; ++i)
       if (!st->act_used[i]) { q = i; break; }
     if (q < 0) return fail(TP_ESTATE, "more than %d mini-batches in flight", d.max_in_flight);
-    InFlight nf{mb_id, st->latest, 0, q, false};
+    InFlight nf{mb_id, v_read, 0, q, false};
     if (stashing(d.policy)) {
       int rc = stash_push(st, st->latest, nullptr);   // the forward version stays until blended
       if (rc) return rc;
@@ -618,7 +696,7 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
     return fail(TP_ESTATE, "mini-batch %llu: expected micro-batch %u, got %u", (unsigned long long)mb_id, f->forwards, ub_idx);
   if (stashing(d.policy) && f->v_f != st->latest)
     return fail(TP_ESTATE, "an update landed between micro-batches of mini-batch %llu", (unsigned long long)mb_id);
-  const uint64_t v = st->latest;                       // always the latest weights at the stage
+  const uint64_t v = v_read;                           // the latest weights at the stage, unless the pass names its version
   if (version_used) *version_used = v;
   f->forwards++;
   if (st->dry) return TP_OK;
@@ -626,7 +704,12 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
   const int slot = st->find_slot(v);
   const size_t es = st->plan.elt_size;
   const float* master = st->ring(slot);
-  const char* wcopy = d.dtype == TP_BF16 ? (const char*)st->bufs.wfwd_dev : (const char*)master;
+  const char* wcopy = (const char*)master;
+  if (d.dtype == TP_BF16) {
+    wcopy = (const char*)st->bufs.wfwd_dev;
+    if (v != st->latest)
+      if (int rc = old_version_copy(st, v, slot, &wcopy)) return rc;
+  }
   char* aslot = st->act_slot(f->act_slot);
   const uint64_t row0 = (uint64_t)ub_idx * d.mb;
   const int L = d.num_layers;
@@ -742,6 +825,21 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
   }
   return TP_OK;
 }
+}  // namespace
+
+extern "C" {
+
+int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_dev, void* y_dev,
+                  uint64_t* version_used) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  return forward_impl(st, mb_id, ub_idx, x_dev, y_dev, TP_NONE, version_used);
+}
+
+int stage_forward_on(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, uint64_t version, const void* x_dev, void* y_dev) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  if (version == TP_NONE) return fail(TP_EINVAL, "stage_forward_on needs a version");
+  return forward_impl(st, mb_id, ub_idx, x_dev, y_dev, version, nullptr);
+}
 
 int stage_loss_softmax_ce(tp_stage* st, uint64_t mb_id, const void* logits_dev, const int32_t* labels_dev,
                           void* dlogits_dev, float* loss_dev) {
@@ -760,9 +858,13 @@ int stage_loss_softmax_ce(tp_stage* st, uint64_t mb_id, const void* logits_dev, 
   return TP_OK;
 }
 
-int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev, uint32_t* delta_used) {
-  if (!st) return fail(TP_EINVAL, "null stage");
+}  // extern "C"
+
+namespace {
+int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev, uint64_t version, uint32_t* delta_used) {
   const tp_stage_desc& d = st->desc;
+  if (version != TP_NONE && d.policy != TP_TIMEPREST)
+    return fail(TP_EINVAL, "only TP_TIMEPREST names the version a pass reads");
   InFlight* f = st->find_mb(mb_id);
   if (!f) return fail(TP_ESTATE, "mini-batch %llu is not in flight", (unsigned long long)mb_id);
   if (f->forwards != (uint32_t)d.n)
@@ -770,12 +872,14 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
   if (st->grad_pending) return fail(TP_ESTATE, "gradient of mini-batch %llu has not been applied yet", (unsigned long long)st->grad_mb);
   if (!st->dry && (!dy_dev || (d.needs_dx && !dx_dev))) return fail(TP_EINVAL, "null gradient pointer");
 
-  // Which weights: V reads the latest; I blends the stashed forward version towards it.
-  const uint64_t v_now = st->latest;
+  // Which weights: V reads the latest; I blends the stashed forward version towards it; TiMePReSt reads the
+  // version its backward pass started on, as it is.
+  const uint64_t v_now = version == TP_NONE ? st->latest : version;
   const uint64_t v_f = stashing(d.policy) ? f->v_f : v_now;
   const uint32_t delta = (uint32_t)(v_now - v_f);
   const int slot_now = st->find_slot(v_now);
   const int slot_f = st->find_slot(v_f);
+  if (slot_now < 0) return fail(TP_ENOVERSION, "version %llu is not in the ring", (unsigned long long)v_now);
   if (slot_f < 0) return fail(TP_ENOVERSION, "forward version %llu of mini-batch %llu is no longer stashed", (unsigned long long)v_f, (unsigned long long)mb_id);
   if (delta_used) *delta_used = delta;
 
@@ -786,6 +890,8 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
     if (delta == 0) {
       // no staleness: intermediate = stale = latest (bit for bit)
       wb = d.dtype == TP_BF16 ? (const char*)st->bufs.wfwd_dev : (const char*)st->ring(slot_now);
+      if (d.dtype == TP_BF16 && v_now != st->latest)
+        if (int rc = old_version_copy(st, v_now, slot_now, &wb)) return rc;
     } else if (st->wb_valid && st->wb_mb == mb_id && st->wb_vf == v_f && st->wb_vnow == v_now) {
       wb = (const char*)st->bufs.wbwd_dev;            // built by the fused update
     } else {
@@ -794,6 +900,7 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
       if (rc) return rc;
       ProfScope ps(st, TP_K_BLEND);
       HIP_TRY(tp::launch_blend(st->stream, d.dtype, P, st->ring(slot_f), st->ring(slot_now), (float)a, (float)b, st->bufs.wbwd_dev));
+      st->copy_valid = false;
       wb = (const char*)st->bufs.wbwd_dev;
     }
 
@@ -1016,6 +1123,20 @@ int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_de
   st->grad_mb = mb_id;
   return TP_OK;
 }
+}  // namespace
+
+extern "C" {
+
+int stage_backward(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev, uint32_t* delta_used) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  return backward_impl(st, mb_id, dy_dev, dx_dev, TP_NONE, delta_used);
+}
+
+int stage_backward_on(tp_stage* st, uint64_t mb_id, uint64_t version, const void* dy_dev, void* dx_dev) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  if (version == TP_NONE) return fail(TP_EINVAL, "stage_backward_on needs a version");
+  return backward_impl(st, mb_id, dy_dev, dx_dev, version, nullptr);
+}
 
 }  // extern "C"
 
@@ -1071,6 +1192,7 @@ int blend_update_impl(tp_stage* st, uint64_t mb_id_done, uint64_t mb_id_next_bwd
     HIP_TRY(tp::launch_update(st->stream, d.dtype, u));
   }
   st->wb_valid = blend;
+  if (blend) st->copy_valid = false;
   st->wb_mb = blend ? mb_id_next_bwd : TP_NONE;
   st->wb_vf = vf_next;
   st->wb_vnow = v + 1;

@@ -54,7 +54,8 @@ class GpuStage:
         self.s, self.K = stage_index, num_stages
         depth = num_stages - stage_index
         if ring_capacity is None:
-            ring_capacity = 1 if policy == "latest" else depth
+            # TiMePReSt: a pass under way may still read a version up to K - 1 updates older than the latest
+            ring_capacity = 1 if policy == "latest" else (num_stages if policy == "timeprest" else depth)
         if max_in_flight is None:
             max_in_flight = depth
         if needs_dx is None:
@@ -127,6 +128,22 @@ class GpuStage:
         assert y.shape[0] == self.mb and y.numel() == self.mb * self.out_elems
         v = B.stage_forward(self.handle, mb_id, ub, x.data_ptr(), y.data_ptr())
         return y, v
+
+    def forward_on(self, mb_id: int, ub: int, version: int, x: torch.Tensor, y: torch.Tensor):
+        """Forward on a retained version (TP_TIMEPREST)."""
+        assert x.is_contiguous() and y.is_contiguous() and x.dtype == self.tdtype and y.dtype == self.tdtype
+        assert x.numel() == self.mb * self.in_elems and y.numel() == self.mb * self.out_elems
+        B.stage_forward_on(self.handle, mb_id, ub, version, x.data_ptr(), y.data_ptr())
+        return y
+
+    def backward_on(self, mb_id: int, version: int, dy: torch.Tensor, dx: Optional[torch.Tensor] = None):
+        """Backward on a retained version (TP_TIMEPREST)."""
+        rows = self.mb * self.n
+        assert dy.numel() == rows * self.out_elems and dy.is_contiguous() and dy.dtype == self.tdtype
+        if self.needs_dx and dx is None:
+            dx = torch.empty(rows, self.in_elems, dtype=self.tdtype, device=self.device)
+        B.stage_backward_on(self.handle, mb_id, version, dy.data_ptr(), dx.data_ptr() if dx is not None else 0)
+        return dx
 
     def input_view(self, mb_id: int, ub: int) -> torch.Tensor:
         """Tensor view of the workspace rows where the input of (mb_id, ub) belongs."""
@@ -250,6 +267,76 @@ class GpuPipeline:
                 info["new_version"] = st.blend_update(j, nxt)
             if on_event is not None:
                 on_event("done", (t, kind, s, j), self, info)
+        return events, losses
+
+    def run_microbatches(self, num_mb: int, get_input, get_labels, *, mid_pass_updates: bool = False, on_event=None):
+        """The micro-batch-granular clock of the library (tp_schedule_microbatch_events).  Under TP_TIMEPREST the
+        versions every stage holds when a pass starts are read off the stages (stage_query), pinned (stash_push),
+        named in stage_forward_on / stage_backward_on and dropped (stash_evict) as the pass leaves each stage."""
+        w = self.w
+        n, mb, K = w.n, w.mb, self.K
+        rows = n * mb
+        timeprest = self.stages[0].desc.policy == B.TP_TIMEPREST
+        events = B.tp_schedule_microbatch_events(K, num_mb, n, mid_pass_updates)
+        outs: Dict[tuple, torch.Tensor] = {}
+        grads: Dict[tuple, torch.Tensor] = {}
+        inputs: Dict[int, torch.Tensor] = {}
+        fwd_v: Dict[int, list] = {}
+        bwd_v: Dict[int, list] = {}
+        losses: Dict[int, torch.Tensor] = {}
+        for (t, kind, s, j, ub) in events:
+            st = self.stages[s]
+            info = {}
+            if kind == "F":
+                if timeprest and s == 0 and ub == 0:
+                    fwd_v[j] = [int(r.query().latest_version) for r in self.stages]
+                    for r, v in zip(self.stages, fwd_v[j]):
+                        B.stash_push(r.handle, v)
+                if s == 0 and j not in inputs:
+                    inputs[j] = get_input(j)
+                x = (inputs[j] if s == 0 else outs[(s - 1, j)])[ub * mb:(ub + 1) * mb]
+                if (s, j) not in outs:
+                    outs[(s, j)] = torch.empty(rows, st.out_elems, dtype=st.tdtype, device=self.device)
+                y = outs[(s, j)][ub * mb:(ub + 1) * mb]
+                if timeprest:
+                    st.forward_on(j, ub, fwd_v[j][s], x, y)
+                    v = fwd_v[j][s]
+                else:
+                    _, v = st.forward(j, ub, x, y)
+                info.update(y=y, version=v)
+                if ub == n - 1:
+                    if s == 0:
+                        inputs.pop(j)
+                    else:
+                        outs.pop((s - 1, j))
+                    if timeprest:
+                        B.stash_evict(st.handle, fwd_v[j][s])
+            else:
+                if timeprest and s == K - 1:
+                    bwd_v[j] = [int(r.query().latest_version) for r in self.stages]
+                    for r, v in zip(self.stages, bwd_v[j]):
+                        B.stash_push(r.handle, v)
+                if s == K - 1:
+                    loss, dy = st.loss(j, outs.pop((s, j)), get_labels(j))
+                    losses[j] = loss
+                    info["loss"] = loss
+                else:
+                    dy = grads.pop((s + 1, j))
+                info["dy"] = dy
+                if timeprest:
+                    dx = st.backward_on(j, bwd_v[j][s], dy)
+                    B.stash_evict(st.handle, bwd_v[j][s])
+                    info["version"] = bwd_v[j][s]
+                else:
+                    dx, info["delta"] = st.backward(j, dy)
+                if s > 0:
+                    grads[(s, j)] = dx
+                info["dx"] = dx
+                if on_event is not None:
+                    on_event("pre_update", (t, kind, s, j, ub), self, info)
+                info["new_version"] = st.blend_update(j, B.TP_NONE)
+            if on_event is not None:
+                on_event("done", (t, kind, s, j, ub), self, info)
         return events, losses
 
     def close(self):

@@ -347,3 +347,96 @@ def test_memory_per_stage_and_policy_follows_the_papers_ordering():
     d = B.make_desc([(8, 8, "relu")], dtype="f32", mb=2, n=2, stage_index=0, num_stages=2, ring_capacity=1,
                     max_in_flight=2, policy="latest", needs_dx=False, lam=0.1, lr=0.01, momentum=0.9)
     assert B.stage_workspace_query(d).wbwd_bytes == 0
+
+
+@pytest.mark.parametrize("mid", [False, True])
+@pytest.mark.parametrize("K,num,n", [(1, 4, 3), (2, 7, 4), (4, 9, 2), (4, 9, 4), (6, 8, 8), (3, 2, 1)])
+def test_microbatch_schedule_events_equal_oracle(K, num, n, mid):
+    from oracle.schedule import simulate_microbatches
+    ref = [(e.t, e.kind, e.s, e.j, e.ub) for e in simulate_microbatches(K, num, n, mid)]
+    assert B.tp_schedule_microbatch_events(K, num, n, mid) == ref
+
+
+@pytest.mark.parametrize("policy,mid", [("timeprest", False), ("latest", True), ("latest", False), ("convex", False)])
+def test_bookkeeping_equals_oracle_under_microbatch_schedule(policy, mid):
+    # K dry stages driven through the micro-batch clock next to the oracle pipeline: versions read, live versions,
+    # reference counts.  TiMePReSt: pins taken when a pass starts, versions named per call.
+    from oracle.pipeline import run_microbatches
+    K, n, num = 4, 4, 9
+    specs = tuple((Dense(5, 5, "relu"),) for _ in range(K - 1)) + ((Dense(5, 3, "none"),),)
+    rng = np.random.default_rng(3)
+    params = [[rng.standard_normal((l.out_features, l.in_features)) * 0.3, np.zeros(l.out_features)]
+              for st in specs for l in st]
+    pipe = Pipeline(specs, [params[s] for s in range(K)], policy=policy, lam=0.1, lr=0.01, momentum=0.9, n=n, mb=2)
+    C = {"latest": 1, "timeprest": K}
+    handles = [_dry_stage(K, s, policy, n=n, C=C.get(policy)) for s in range(K)]
+    fwd_v, bwd_v = {}, {}
+    seen_split = []
+
+    def on_event(ev, p, info):
+        h, ost = handles[ev.s], p.stages[ev.s]
+        if ev.kind == "F":
+            if policy == "timeprest":
+                if ev.s == 0 and ev.ub == 0:
+                    fwd_v[ev.j] = [B.stage_query(r).latest_version for r in handles]
+                    for r, v in zip(handles, fwd_v[ev.j]):
+                        B.stash_push(r, v)
+                B.stage_forward_on(h, ev.j, ev.ub, fwd_v[ev.j][ev.s], 0, 0)
+                assert fwd_v[ev.j][ev.s] == info["version"]
+                if ev.ub == n - 1:
+                    B.stash_evict(h, fwd_v[ev.j][ev.s])
+            else:
+                assert B.stage_forward(h, ev.j, ev.ub, 0, 0) == info["version"] == ev.version
+                if ev.ub > 0 and info["version"] != ost.inflight[ev.j]["versions"][0]:
+                    seen_split.append((ev.s, ev.j))
+        else:
+            if policy == "timeprest":
+                if ev.s == K - 1:
+                    bwd_v[ev.j] = [B.stage_query(r).latest_version for r in handles]
+                    for r, v in zip(handles, bwd_v[ev.j]):
+                        B.stash_push(r, v)
+                B.stage_backward_on(h, ev.j, bwd_v[ev.j][ev.s], 0, 0)
+                assert bwd_v[ev.j][ev.s] == info["trace"][3]
+                B.stash_evict(h, bwd_v[ev.j][ev.s])
+            else:
+                assert B.stage_backward(h, ev.j, 0, 0) == info["trace"][4]
+            assert B.stage_blend_update(h, ev.j, B.TP_NONE) == ost.latest
+        # the pins of a pass are taken at all stages at once: compare every stage after every event
+        for r, ost_r in zip(handles, p.stages):
+            q = B.stage_query(r)
+            live = _live(q)
+            assert q.latest_version == ost_r.latest
+            assert sorted(live) == ost_r.live_versions(), (ev, live, ost_r.live_versions())
+            assert all(live[v] == ost_r.refcnt[v] for v in live)
+
+    events, (fv, bv) = run_microbatches(pipe, num, lambda j: np.zeros((2 * n, 5)), lambda j: np.zeros(2 * n, dtype=int),
+                                        mid_pass_updates=mid, on_event=on_event)
+    if policy == "timeprest":
+        assert {j: list(v) for j, v in fv.items()} == fwd_v and {j: list(v) for j, v in bv.items()} == bwd_v
+        for h in handles:                                              # every pin was dropped again
+            assert list(_live(B.stage_query(h)).values()) == [0]
+    assert bool(seen_split) == (policy == "latest" and mid)            # an update in the middle of a pass: V only
+    for h in handles:
+        B.stage_destroy(h)
+
+
+def test_pass_versions_are_refused_outside_timeprest_and_when_not_held():
+    h = _dry_stage(2, 0, "convex")
+    with pytest.raises(B.StageLibError) as ei:
+        B.stage_forward_on(h, 0, 0, 0, 0, 0)
+    assert ei.value.code == B.TP_EINVAL
+    B.stage_destroy(h)
+    h = _dry_stage(2, 0, "timeprest", C=2)
+    with pytest.raises(B.StageLibError) as ei:
+        B.stage_forward_on(h, 0, 0, 5, 0, 0)
+    assert ei.value.code == B.TP_ENOVERSION
+    for ub in range(2):
+        B.stage_forward_on(h, 0, ub, 0, 0, 0)
+    with pytest.raises(B.StageLibError) as ei:
+        B.stage_backward_on(h, 0, 3, 0, 0)
+    assert ei.value.code == B.TP_ENOVERSION
+    B.stage_backward_on(h, 0, 0, 0, 0)
+    assert B.stage_blend_update(h, 0, B.TP_NONE) == 1
+    assert _live(B.stage_query(h)) == {1: 0}                           # nothing pinned: the old version is gone
+    assert B.tp_blend_coefficients("timeprest", 3, 0.5) == (1.0, 0.0)
+    B.stage_destroy(h)

@@ -339,3 +339,107 @@ def test_error_paths():
         st.backward(0, np.zeros((2, 2)))                    # not all micro-batches seen
     with pytest.raises(StageError):
         st.update(0)                                        # no gradient yet
+
+
+# ---- TiMePReSt (pass-consistent versions) and the micro-batch clock --------------------------------------------
+
+def _one_layer_pipeline(policy, K=4, n=4, seed=3):
+    specs = tuple((Dense(5, 5, "gelu"),) for _ in range(K - 1)) + ((Dense(5, 3, "none"),),)
+    rng = np.random.default_rng(seed)
+    params = [[rng.standard_normal((l.out_features, l.in_features)) * 0.4, rng.standard_normal(l.out_features) * 0.1]
+              for st in specs for l in st]
+    return specs, Pipeline(specs, [params[s] for s in range(K)], policy=policy, lam=0.3, lr=0.05, momentum=0.9, n=n, mb=2)
+
+
+def _mb_data(j, rows=8):
+    rng = np.random.default_rng(50 + j)
+    return rng.standard_normal((rows, 5)), rng.integers(0, 3, rows)
+
+
+def test_timeprest_reads_the_versions_its_passes_started_on():
+    # every forward and backward event re-derived by hand from copies of the weight versions kept on the side:
+    # y = act(x W_f^T + b_f) on the forward pass's version, dx = (dy . act'(z)) W_b on the backward pass's version,
+    # dW from the saved forward activations, the update applied to the latest weights
+    from oracle.pipeline import run_microbatches
+    K, n = 4, 4
+    specs, pipe = _one_layer_pipeline("timeprest", K, n)
+    history = [{0: [p.copy() for p in st.weights[0]]} for st in pipe.stages]
+    xs, zs = {}, {}
+    used = {"f_stale": 0, "b_stale": 0, "differ": 0}
+
+    def on_event(ev, p, info):
+        st, act = p.stages[ev.s], specs[ev.s][0].act
+        if ev.kind == "F":
+            v = info["version"]
+            Wf, bf = history[ev.s][v]
+            x = (_mb_data(ev.j)[0] if ev.s == 0 else xs[(ev.s - 1, ev.j, ev.ub)][1])
+            x = x[ev.ub * 2:(ev.ub + 1) * 2] if ev.s == 0 else x
+            z = x @ Wf.T + bf
+            assert np.allclose(info["y"], L.act_forward(z, act), rtol=0, atol=1e-13)
+            xs[(ev.s, ev.j, ev.ub)] = (x, info["y"])
+            zs[(ev.s, ev.j, ev.ub)] = z
+            used["f_stale"] += v < ev.version
+        else:
+            _, _, v_f, v_b, delta = info["trace"]
+            assert delta == 0
+            Wb = history[ev.s][v_b][0]
+            dW = np.zeros_like(Wb)
+            for ub in range(n):
+                dz = info["dy"][ub * 2:(ub + 1) * 2] * L.act_derivative(zs[(ev.s, ev.j, ub)], act)
+                dW += dz.T @ xs[(ev.s, ev.j, ub)][0]
+                if ev.s > 0:
+                    assert np.allclose(info["dx"][ub * 2:(ub + 1) * 2], dz @ Wb, rtol=0, atol=1e-13)
+            assert np.allclose(info["g"][:dW.size].reshape(dW.shape), dW, rtol=0, atol=1e-13)
+            used["b_stale"] += v_b < ev.version
+            used["differ"] += v_f != v_b
+            latest = st.latest
+            history[ev.s][latest] = [w.copy() for w in st.weights[latest]]
+            old = history[ev.s][latest - 1]
+            assert np.allclose(st.weights[latest][0], old[0] - 0.05 * st.m[0], rtol=0, atol=1e-13)   # update on the latest
+
+    run_microbatches(pipe, 9, lambda j: _mb_data(j)[0], lambda j: _mb_data(j)[1], on_event=on_event)
+    assert used["f_stale"] > 0 and used["b_stale"] > 0 and used["differ"] > 0
+    assert all(st.live_versions() == [9] and st.refcnt == {9: 0} for st in pipe.stages)
+
+
+@pytest.mark.parametrize("policy", ["latest", "convex", "timeprest"])
+def test_microbatch_clock_equals_minibatch_clock_without_mid_pass_updates(policy):
+    # the same versions are read either way, so the same numbers come out -- except under TiMePReSt, whose passes
+    # read older versions than the stage's latest
+    from oracle.pipeline import run_microbatches
+    _, coarse = _one_layer_pipeline("latest" if policy == "timeprest" else policy)
+    coarse.run(8, lambda j: _mb_data(j)[0], lambda j: _mb_data(j)[1])
+    _, fine = _one_layer_pipeline(policy)
+    run_microbatches(fine, 8, lambda j: _mb_data(j)[0], lambda j: _mb_data(j)[1])
+    same = all(np.array_equal(a, b) for sa, sb in zip(coarse.stages, fine.stages)
+               for a, b in zip(sa.weights[sa.latest], sb.weights[sb.latest]))
+    assert same == (policy != "timeprest")
+    assert (coarse.losses == fine.losses) == (policy != "timeprest")
+
+
+def test_timeprest_with_one_stage_or_frozen_weights_is_plain_sgd():
+    from oracle.pipeline import run_microbatches
+    for K in (1,):
+        _, a = _one_layer_pipeline("timeprest", K=K)
+        _, b = _one_layer_pipeline("latest", K=K)
+        run_microbatches(a, 6, lambda j: _mb_data(j)[0], lambda j: _mb_data(j)[1])
+        b.run(6, lambda j: _mb_data(j)[0], lambda j: _mb_data(j)[1])
+        assert a.losses == b.losses
+
+
+def test_mid_pass_updates_change_what_later_micro_batches_read():
+    from oracle.pipeline import run_microbatches
+    _, strict = _one_layer_pipeline("latest")
+    _, loose = _one_layer_pipeline("latest")
+    run_microbatches(strict, 8, lambda j: _mb_data(j)[0], lambda j: _mb_data(j)[1], mid_pass_updates=False)
+    seen = []
+    run_microbatches(loose, 8, lambda j: _mb_data(j)[0], lambda j: _mb_data(j)[1], mid_pass_updates=True,
+                     on_event=lambda ev, p, info: seen.append((ev.s, ev.j, ev.ub, info["version"])) if ev.kind == "F" else None)
+    per_pass = {}
+    for s, j, ub, v in seen:
+        per_pass.setdefault((s, j), []).append(v)
+    assert any(len(set(v)) > 1 for v in per_pass.values())
+    assert strict.losses != loose.losses
+    with pytest.raises(StageError):                                     # a stashed forward version cannot change mid-pass
+        _, bad = _one_layer_pipeline("convex")
+        run_microbatches(bad, 8, lambda j: _mb_data(j)[0], lambda j: _mb_data(j)[1], mid_pass_updates=True)
