@@ -72,11 +72,15 @@ class TeacherData:
         return self._make(j)[1]
 
 
-def run_policy(w: W.Workload, policy: str, data: TeacherData, minibatches: int):
+def run_policy(w: W.Workload, policy: str, data: TeacherData, minibatches: int, mid_pass_updates: bool = False):
+    """Train through the stage library; TiMePReSt and mid-pass updates run on the micro-batch-granular clock."""
     params = [W.init_params(w, s) for s in range(w.K)]
     pipe = GpuPipeline(w, params, policy=policy)
     stash = [(st.C, int(st.C) * int(st.P) * 4) for st in pipe.stages]
-    _, losses = pipe.run(minibatches, data.inputs, data.labels)
+    if policy == "timeprest" or mid_pass_updates:
+        _, losses = pipe.run_microbatches(minibatches, data.inputs, data.labels, mid_pass_updates=mid_pass_updates)
+    else:
+        _, losses = pipe.run(minibatches, data.inputs, data.labels)
     out = torch.cat([losses[j] for j in range(minibatches)]).cpu().numpy().astype(np.float64)
     pipe.close()
     return out, stash
@@ -118,6 +122,8 @@ def main(argv=None):
 
     runs = [("sequential SGD (1 stage, no staleness)", 1, "latest", 0.1),
             ("V-TiMePReSt (latest, no stash)", args.stages, "latest", 0.1),
+            ("V-TiMePReSt, updates also in the middle of a pass", args.stages, "latest-mid", 0.1),
+            ("TiMePReSt (versions of the pass start)", args.stages, "timeprest", 0.1),
             ("I-TiMePReSt Eq. 1, lambda 0.1", args.stages, "eq1", 0.1),
             ("I-TiMePReSt convex, lambda 0.1", args.stages, "convex", 0.1),
             ("I-TiMePReSt convex, lambda ln 2", args.stages, "convex", math.log(2.0)),
@@ -125,7 +131,8 @@ def main(argv=None):
             ("stashed (backward on the forward version)", args.stages, "stashed", 0.1)]
     results = []
     for name, stages, policy, lam in runs:
-        loss, stash = run_policy(wl(stages, lam), policy, data, args.minibatches)
+        loss, stash = run_policy(wl(stages, lam), policy.replace("-mid", ""), data, args.minibatches,
+                                 mid_pass_updates=policy.endswith("-mid"))
         results.append({"name": name, "stages": stages, "policy": policy, "lambda": lam, "loss": loss, "stash": stash})
         print(f"ran {name}: first {loss[:10].mean():.4f} last {loss[-50:].mean():.4f}", file=sys.stderr, flush=True)
     best_final = min(float(r["loss"][-50:].mean()) for r in results if np.isfinite(r["loss"][-50:].mean()))

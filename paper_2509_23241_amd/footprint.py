@@ -18,15 +18,43 @@ from .runner import layer_tuple
 PARTS = ("ring_bytes", "momentum_bytes", "grad_bytes", "wfwd_bytes", "wbwd_bytes", "act_bytes", "scratch_bytes")
 
 
+def timeprest_versions(K: int, n: int, s: int, num_mb: int = 16) -> int:
+    """How many consecutive weight versions stage s must be able to hold under TiMePReSt: the latest one and those
+    that passes under way still read (pinned when a pass starts at its first stage, dropped when the pass has left
+    this stage), replayed on the library's micro-batch clock."""
+    events = B.tp_schedule_microbatch_events(K, num_mb, n, False)
+    version = [0] * K
+    fwd, bwd, pins, widest = {}, {}, {}, 1
+    for (t, kind, st, j, ub) in events:
+        if kind == "F":
+            if st == 0 and ub == 0:
+                fwd[j] = list(version)
+                pins[("f", j)] = fwd[j][s]
+            if st == s and ub == n - 1:
+                pins.pop(("f", j))
+        else:
+            if st == K - 1:
+                bwd[j] = list(version)
+                pins[("b", j)] = bwd[j][s]
+            if st == s:
+                pins.pop(("b", j))
+            version[st] += 1
+        held = set(pins.values()) | {version[s]}
+        widest = max(widest, max(held) - min(held) + 1)
+    return widest
+
+
 def stage_bytes(w: W.Workload, s: int, policy: str) -> Dict[str, int]:
     """Bytes per buffer of stage s of workload w under `policy`, with the ring and in-flight depth of the nF1B schedule."""
     depth = w.K - s
+    ring = 1 if policy == "latest" else timeprest_versions(w.K, w.n, s) if policy == "timeprest" else depth
     d = B.make_desc([layer_tuple(l) for l in w.stages[s]], dtype=w.dtype, mb=w.mb, n=w.n, stage_index=s, num_stages=w.K,
-                    ring_capacity=1 if policy == "latest" else depth, max_in_flight=depth, policy=policy,
+                    ring_capacity=ring, max_in_flight=depth, policy=policy,
                     needs_dx=s > 0, lam=w.lam, lr=w.lr, momentum=w.momentum)
     sz = B.stage_workspace_query(d)
     out = {k: int(getattr(sz, k)) for k in PARTS}
     out["params"] = int(sz.param_count)
+    out["versions"] = ring
     out["total"] = sum(out[k] for k in PARTS)
     return out
 
@@ -35,9 +63,9 @@ def table(rows: List[tuple]) -> str:
     lines = ["| workload, stage | policy | parameters | ring (versions) | momentum + gradient | compute copies | saved activations | scratch | total MB |",
              "|---|---|---|---|---|---|---|---|---|"]
     for name, w, s in rows:
-        for policy, label in (("latest", "V-TiMePReSt"), ("convex", "I-TiMePReSt / stashed")):
+        for policy, label in (("latest", "V-TiMePReSt"), ("timeprest", "TiMePReSt"), ("convex", "I-TiMePReSt / stashed")):
             b = stage_bytes(w, s, policy)
-            versions = 1 if policy == "latest" else w.K - s
+            versions = b["versions"]
             mb = lambda v: f"{v / 1e6:.1f}"
             lines.append(f"| {name}, stage {s} | {label} | {b['params'] / 1e6:.2f} M | {mb(b['ring_bytes'])} ({versions}) | "
                          f"{mb(b['momentum_bytes'] + b['grad_bytes'])} | {mb(b['wfwd_bytes'] + b['wbwd_bytes'])} | "

@@ -342,6 +342,11 @@ def test_memory_per_stage_and_policy_follows_the_papers_ordering():
             assert i["total"] - v["total"] == (w.K - s - 1) * P4 + P4 // 2
             assert i["total"] > v["total"]
         assert v["act_bytes"] % (w.K - s) == 0                           # K - s mini-batches in flight
+        # the parent method sits between the two at the first stages: it keeps the versions passes under way read
+        t = F.stage_bytes(w, s, "timeprest")
+        assert 1 <= t["versions"] <= w.K and v["total"] < t["total"]
+        if s == 0:
+            assert t["versions"] < w.K - s and t["total"] < F.stage_bytes(w, s, "convex")["total"]
     assert "| MLP width 4096, stage 0 | V-TiMePReSt |" in F.table(F.default_rows())
     # a V-TiMePReSt stage can be created without a buffer for intermediate weights, a stashing one cannot
     d = B.make_desc([(8, 8, "relu")], dtype="f32", mb=2, n=2, stage_index=0, num_stages=2, ring_capacity=1,
