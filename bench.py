@@ -26,11 +26,17 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM-side bytes per launch at the default workload, from two rocprofv3 --pmc runs (FETCH_SIZE, then
-# WRITE_SIZE) scaled by what the same counters read for a plain 1 GiB copy (FETCH_SIZE reports half the
-# bytes, WRITE_SIZE all of them); commands and raw counts: profiles/bench_mlp4096_stage1_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = {"fprop": 56.1e6, "dgrad": 159.6e6, "wgrad": 168.0e6, "update": 940.1e6,
-                          "act_bwd": 50.4e6, "colsum": 17.9e6}
+# Figures of the default workload taken with rocprofv3 on the library at commit d8014b7 (kernel sources of the three
+# GEMMs and the update unchanged since); commands and raw counts in profiles/.
+#   traffic: HBM-side bytes per launch from two --pmc runs (FETCH_SIZE, then WRITE_SIZE) scaled by what the same
+#            counters read for a plain 1 GiB copy (FETCH_SIZE reports half the bytes, WRITE_SIZE all of them):
+#            profiles/bench_mlp4096_stage1_hbm_traffic.md
+#   rocprof_avg_us: average kernel duration from --kernel-trace --stats (no event brackets):
+#            profiles/bench_mlp4096_stage1_kernel_stats.md
+MEASURED_TRAFFIC_BYTES = {"fprop": 56.1e6, "dgrad": 159.5e6, "wgrad": 168.0e6, "update": 940.1e6,
+                          "act_bwd": 50.4e6, "colsum": 19.0e6}
+ROCPROF_AVG_US = {"fprop": 18.82, "dgrad": 67.15, "wgrad": 66.34, "update": 160.25, "act_bwd": 11.22}
+PROFILED_AT = "d8014b7"
 
 
 def parse():
@@ -343,6 +349,13 @@ def main():
                     "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
     default_workload = (args.workload, args.width, w.mb, w.n, s, args.policy) == ("mlp", 4096, 256, 8, 1, "convex")
     roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(dominant) if default_workload else None
+    if default_workload and dominant in ROCPROF_AVG_US:
+        # the same ratio from rocprofv3's kernel duration (another run, another box of the pool): no event brackets
+        work = nbytes if roofline["bound"] == "hbm" else flops
+        peak = PEAK_HBM_GBS * 1e9 if roofline["bound"] == "hbm" else PEAK_BF16_TFLOPS * 1e12
+        roofline["rocprof_avg_us"] = ROCPROF_AVG_US[dominant]
+        roofline["frac_rocprof"] = round(work / (ROCPROF_AVG_US[dominant] * 1e-6) / peak, 4)
+        roofline["profiled_at_commit"] = PROFILED_AT
     roofline["algorithmic"] = nbytes if roofline["bound"] == "hbm" else flops
     roofline["avg_us"] = dk["avg_us"]
     roofline["launches_per_step"] = dk["launches_per_step"]

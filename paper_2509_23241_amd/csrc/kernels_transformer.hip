@@ -583,7 +583,9 @@ hipError_t launch_layernorm_bwd(hipStream_t s, int elt, size_t rows, int D, cons
                        (const float*)x, stats, gamma_s, gamma_l, alpha, beta_c, (float*)dx, partials);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  // partial[block][0..D) = dgamma, [D..2D) = dbeta: two strided sums over the blocks
+  // partial[block][0..D) = dgamma, [D..2D) = dbeta: strided sums over the blocks, one launch when the two
+  // gradients lie side by side
+  if (dbeta == dgamma + D) return launch_sum_partials_strided(s, 2 * (size_t)D, (int)blocks, partials, 2 * (size_t)D, dgamma);
   e = launch_sum_partials_strided(s, (size_t)D, (int)blocks, partials, 2 * (size_t)D, dgamma);
   if (e != hipSuccess) return e;
   return launch_sum_partials_strided(s, (size_t)D, (int)blocks, partials + D, 2 * (size_t)D, dbeta);

@@ -1056,8 +1056,12 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
             HIP_TRY(tp::launch_batchnorm_bwd(st->stream, d.dtype, seg_rows, C, d.n, dz, aslot + lp.x_off,
                                              (const float*)(aslot + lp.stat_off), gs, gl, (float)ca, (float)cb, dst, sums,
                                              st->partials()));
-          HIP_TRY(tp::launch_sum_partials_strided(st->stream, (size_t)C, d.n, sums, 2 * (size_t)C, g + lp.w_off));
-          HIP_TRY(tp::launch_sum_partials_strided(st->stream, (size_t)C, d.n, sums + C, 2 * (size_t)C, g + lp.b_off));
+          if (lp.b_off == lp.w_off + (uint64_t)C) {  // scale and shift gradients lie side by side: one launch sums both
+            HIP_TRY(tp::launch_sum_partials_strided(st->stream, 2 * (size_t)C, d.n, sums, 2 * (size_t)C, g + lp.w_off));
+          } else {
+            HIP_TRY(tp::launch_sum_partials_strided(st->stream, (size_t)C, d.n, sums, 2 * (size_t)C, g + lp.w_off));
+            HIP_TRY(tp::launch_sum_partials_strided(st->stream, (size_t)C, d.n, sums + C, 2 * (size_t)C, g + lp.b_off));
+          }
         }
         if (no_dx) break;
         if (int rc = through_activation(dst)) return rc;
