@@ -12,14 +12,20 @@ What follows the paper and where:
                    (Section "I-TiMePReSt", Eq. 1-2; Appendix A.1, A.2)
   schedule.py      nF1B order of forward/backward/update events and the
                    weight version each one sees (Section "Methodology",
-                   Sections "V-TiMePReSt" and "I-TiMePReSt", worked examples)
-  layers.py        textbook layer mathematics (dense, ReLU, GELU, softmax
+                   Sections "V-TiMePReSt" and "I-TiMePReSt", worked examples),
+                   at mini-batch and at micro-batch granularity (the latter
+                   with or without updates in the middle of a pass)
+  layers.py        textbook layer mathematics (dense, convolution, pooling,
+                   normalisations, attention, ReLU, GELU, softmax
                    cross-entropy); the paper gives no formulas for these
   stage.py         one stage: forward per micro-batch on the latest weights,
                    one backward per mini-batch on the prescribed weights, the
                    stash of stale versions and its retention rule (Section
                    "Memory Overhead"), SGD-momentum update per mini-batch
-  pipeline.py      K stages driven through the event order on one host
+  pipeline.py      K stages driven through the event order on one host; on
+                   the micro-batch clock also the parent method TiMePReSt,
+                   whose passes read the versions of their start (Section
+                   "V-TiMePReSt", Challenge 1)
 
 Parity status: every function here is pinned by tests that run without a GPU
 (closed forms, the paper's worked version examples, finite differences,
