@@ -359,7 +359,8 @@ enum tp_kernel_class {
   TP_K_NORM = 10,    /* layer normalisation forward / backward       */
   TP_K_ATTN = 11,    /* attention forward / backward                 */
   TP_K_ADD = 12,     /* residual additions                           */
-  TP_K_CLASSES = 13
+  TP_K_SUMS = 13,    /* a backward pass's sums of partials, one launch */
+  TP_K_CLASSES = 14
 };
 typedef struct tp_profile {
   uint64_t launches[TP_K_CLASSES];

@@ -66,11 +66,12 @@ class tp_event(C.Structure):
 
 
 KERNEL_CLASSES = ["fprop", "dgrad", "wgrad", "colsum", "act_bwd", "update", "blend", "loss", "copy", "pool", "norm", "attn",
-                  "add"]
+                  "add", "sums"]
 
 
 class tp_profile(C.Structure):
-    _fields_ = [("launches", C.c_uint64 * 13), ("ms", C.c_double * 13), ("dropped", C.c_uint64)]
+    _fields_ = [("launches", C.c_uint64 * len(KERNEL_CLASSES)), ("ms", C.c_double * len(KERNEL_CLASSES)),
+                ("dropped", C.c_uint64)]
 
 
 class StageLibError(RuntimeError):

@@ -27,11 +27,12 @@ hipError_t launch_batchnorm_bwd(hipStream_t s, int elt, size_t rows, int C, int 
 size_t batchnorm_scratch_floats(size_t rows, int C, int nseg = 1);
 // The backward pass of all nseg micro-batches of a mini-batch in one launch (bf16, small layers): segment q =
 // rows [q*rows, (q+1)*rows) of dy, x, dx with its own statistics stats[q][2C]; sums[q][0..C) = sum dy * xhat and
-// sums[q][C..2C) = sum dy of that segment.  hipErrorNotSupported (nothing launched) for shapes it does not take.
+// sums[q][C..2C) = sum dy of that segment; dx_sums (may be null): [nseg][C] column sums of each segment's dx as
+// stored.  hipErrorNotSupported (nothing launched) for shapes it does not take.
 bool batchnorm_fused_bwd_supported(int elt, size_t rows, int C);
 hipError_t launch_batchnorm_bwd_fused(hipStream_t s, int elt, size_t rows, int C, int nseg, const void* dy, const void* x,
                                       const float* stats, const float* gamma_s, const float* gamma_l, float alpha, float beta_c,
-                                      void* dx, float* sums);
+                                      void* dx, float* sums, float* dx_sums = nullptr);
 
 // out = act(a + b), d_out = act'(a + b) (null: not kept)
 hipError_t launch_add_act(hipStream_t s, int elt, size_t count, const void* a, const void* b, int act, void* out, void* d_out);

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 namespace tp {
 
 enum Elt : int { ELT_F32 = 0, ELT_BF16 = 1 };
@@ -38,6 +40,18 @@ hipError_t launch_sum_partials(hipStream_t s, size_t count, int splits, const fl
 // the same with partial row z starting at partial + z*stride
 hipError_t launch_sum_partials_strided(hipStream_t s, size_t count, int splits, const float* partial, size_t stride,
                                        float* out);
+// Sums put off: while a sink is set on the calling thread, the two calls above (also where another launcher makes
+// them) append their job to it and launch nothing; launch_sum_jobs then forms all of them in one launch per 96
+// jobs, with the bits the separate launches would have given.  The caller keeps every job's partials untouched, and
+// reads no result, until that launch has run.
+struct SumJob {
+  const float* partial;
+  float* out;
+  size_t count, stride;
+  int splits;
+};
+void set_sum_sink(std::vector<SumJob>* sink);
+hipError_t launch_sum_jobs(hipStream_t s, const SumJob* jobs, size_t njobs);
 
 // dz = dy (.) d    all [rows x cols] in elt; d = saved act'(z).
 // relu_mask = 1: d holds a ReLU output instead of its derivative; the factor is (d > 0).

@@ -308,13 +308,16 @@ __global__ __launch_bounds__(kSlabThreads) void bn_fwd_slab_kernel(int rows, int
 }
 
 // All micro-batches of a mini-batch in one launch: blockIdx.y = q owns rows [q*rows, (q+1)*rows) with its own
-// statistics stats[q][2C]; its column sums go to sums[q][0..C) (dy * xhat) and sums[q][C..2C) (dy).
+// statistics stats[q][2C]; its column sums go to sums[q][0..C) (dy * xhat) and sums[q][C..2C) (dy).  dx_sums (may be
+// null): dx_sums[q][0..C) = column sums of the segment's dx as stored (rounded to bf16) -- the bias gradient of the
+// layer in front, which then needs no pass of its own over dx.
 template <int NL>
 __global__ __launch_bounds__(kSlabThreads) void bn_bwd_slab_kernel(int rows, int C, const uint16_t* __restrict__ dy,
                                                                    const uint16_t* __restrict__ x, const float* __restrict__ stats,
                                                                    const float* __restrict__ gamma_s,
                                                                    const float* __restrict__ gamma_l, float alpha, float beta_c,
-                                                                   uint16_t* __restrict__ dx, float* __restrict__ sums) {
+                                                                   uint16_t* __restrict__ dx, float* __restrict__ sums,
+                                                                   float* __restrict__ dx_sums) {
   __shared__ __attribute__((aligned(16))) float red[16 * kSlabThreads + 16];
   const int c0 = slab_of_block(blockIdx.x, gridDim.x) * 8;
   const int q = blockIdx.y;
@@ -354,6 +357,7 @@ __global__ __launch_bounds__(kSlabThreads) void bn_bwd_slab_kernel(int rows, int
       sums[(size_t)q * 2 * C + C + c0 + j] = s[8 + j];
     }
   }
+  float t[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int i = 0; i < NL; ++i) {
     const int r = i * kSlabThreads + threadIdx.x;
@@ -366,7 +370,18 @@ __global__ __launch_bounds__(kSlabThreads) void bn_bwd_slab_kernel(int rows, int
       const float xh = (fx[j] - mean[j]) * rstd[j];
       o[j] = g[j] * rstd[j] * (fd[j] - (s[8 + j] + xh * s[j]) * inv_rows);
     }
-    *reinterpret_cast<uint4*>(dx + base + (size_t)r * C) = pack8(o);
+    const uint4 packed = pack8(o);
+    *reinterpret_cast<uint4*>(dx + base + (size_t)r * C) = packed;
+    unpack8(packed, o);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) t[j] += o[j];
+  }
+  if (dx_sums) {  // the same for every lane of the workgroup
+    slab_sum<8>(t, red);
+    if (threadIdx.x == 0) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) dx_sums[(size_t)q * C + c0 + j] = t[j];
+    }
   }
 }
 
@@ -447,15 +462,15 @@ bool batchnorm_fused_bwd_supported(int elt, size_t rows, int C) {
 
 hipError_t launch_batchnorm_bwd_fused(hipStream_t s, int elt, size_t rows, int C, int nseg, const void* dy, const void* x,
                                       const float* stats, const float* gamma_s, const float* gamma_l, float alpha, float beta_c,
-                                      void* dx, float* sums) {
+                                      void* dx, float* sums, float* dx_sums) {
   if (!batchnorm_fused_bwd_supported(elt, rows, C) || nseg < 1 || nseg > 65535) return hipErrorNotSupported;
   const dim3 grid(C / 8, nseg);
   if (slab_loads(rows, 2) == 1)
     hipLaunchKernelGGL(bn_bwd_slab_kernel<1>, grid, dim3(kSlabThreads), 0, s, (int)rows, C, (const uint16_t*)dy, (const uint16_t*)x,
-                       stats, gamma_s, gamma_l, alpha, beta_c, (uint16_t*)dx, sums);
+                       stats, gamma_s, gamma_l, alpha, beta_c, (uint16_t*)dx, sums, dx_sums);
   else
     hipLaunchKernelGGL(bn_bwd_slab_kernel<2>, grid, dim3(kSlabThreads), 0, s, (int)rows, C, (const uint16_t*)dy, (const uint16_t*)x,
-                       stats, gamma_s, gamma_l, alpha, beta_c, (uint16_t*)dx, sums);
+                       stats, gamma_s, gamma_l, alpha, beta_c, (uint16_t*)dx, sums, dx_sums);
   return hipGetLastError();
 }
 

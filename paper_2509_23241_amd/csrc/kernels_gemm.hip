@@ -187,13 +187,15 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(int M, int N, 
 // in a fixed order.  Large outputs take few threads per output (whole cache lines per partial
 // row, enough blocks anyway); small ones take many, so that a thousand partials do not end up
 // as one long chain of dependent loads.
+constexpr int kSumLds = 64 * (kThreads / 64 + 1);  // floats; the largest of ZG * (256/ZG + 1) for ZG in {4, 16, 64}
+
 template <int ZG>
-__global__ __launch_bounds__(kThreads) void sum_partials_kernel(size_t count, int splits, size_t stride,
-                                                                const float* __restrict__ partial, float* __restrict__ out) {
+__device__ __forceinline__ void sum_partials_block(float* sm /* [ZG][IL + 1] */, size_t block, size_t count, int splits,
+                                                   size_t stride, const float* __restrict__ partial, float* __restrict__ out) {
   constexpr int IL = kThreads / ZG;
-  __shared__ float sm[ZG][IL + 1];
+  static_assert(ZG * (IL + 1) <= kSumLds, "LDS of the sum kernels");
   const int il = threadIdx.x % IL, zg = threadIdx.x / IL;
-  const size_t i = (size_t)blockIdx.x * IL + il;
+  const size_t i = block * IL + il;
   float s0 = 0.f, s1 = 0.f;
   if (i < count) {
     int z = zg;
@@ -203,15 +205,82 @@ __global__ __launch_bounds__(kThreads) void sum_partials_kernel(size_t count, in
     }
     if (z < splits) s0 += partial[(size_t)z * stride + i];
   }
-  sm[zg][il] = s0 + s1;
+  sm[zg * (IL + 1) + il] = s0 + s1;
   __syncthreads();
   if (zg == 0 && i < count) {
     float t = 0.f;
 #pragma unroll
-    for (int k = 0; k < ZG; ++k) t += sm[k][il];
+    for (int k = 0; k < ZG; ++k) t += sm[k * (IL + 1) + il];
     out[i] = t;
   }
 }
+
+template <int ZG>
+__global__ __launch_bounds__(kThreads) void sum_partials_kernel(size_t count, int splits, size_t stride,
+                                                                const float* __restrict__ partial, float* __restrict__ out) {
+  __shared__ float sm[kSumLds];
+  sum_partials_block<ZG>(sm, blockIdx.x, count, splits, stride, partial, out);
+}
+
+// Few partials of a large output: one thread per four neighbouring outputs, 16-byte loads, the partials added one
+// after the other.
+__device__ __forceinline__ void sum_partials_block_vec(size_t block, size_t count, int splits, size_t stride,
+                                                       const float* __restrict__ partial, float* __restrict__ out) {
+  const size_t i = (block * kThreads + threadIdx.x) * 4;
+  if (i >= count) return;
+  float4 t = *reinterpret_cast<const float4*>(partial + i);
+  for (int z = 1; z < splits; ++z) {
+    const float4 p = *reinterpret_cast<const float4*>(partial + (size_t)z * stride + i);
+    t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+  }
+  *reinterpret_cast<float4*>(out + i) = t;
+}
+
+__global__ __launch_bounds__(kThreads) void sum_partials_vec_kernel(size_t count, int splits, size_t stride,
+                                                                    const float* __restrict__ partial, float* __restrict__ out) {
+  sum_partials_block_vec(blockIdx.x, count, splits, stride, partial, out);
+}
+
+// Threads per output the sum kernels use for a job of this shape; 0: the 16-byte kernel (four outputs per thread).
+inline int sum_zg(size_t count, int splits, size_t stride, const float* partial, const float* out) {
+  if (splits <= 8 && count >= 16384 && count % 4 == 0 && stride % 4 == 0 && (((uintptr_t)partial | (uintptr_t)out) & 15) == 0)
+    return 0;
+  return (count >= 512 * 64 || splits <= 8) ? 4 : count >= 512 * 16 ? 16 : 64;
+}
+inline int sum_outputs_per_block(int zg) { return zg == 0 ? 4 * kThreads : kThreads / zg; }
+
+// Many sums in one launch.  The table travels as the kernel's argument (no device memory, nothing to upload):
+// block b belongs to the job j with first_block[j] <= b < first_block[j + 1] and does there exactly what block
+// b - first_block[j] of sum_partials_kernel would do, so both give the same bits.
+constexpr int kMaxSumJobs = 96;
+struct PackedSumJob {
+  const float* partial;
+  float* out;
+  uint32_t count, stride, splits, zg;
+};
+struct SumBatch {
+  uint32_t njobs;
+  uint32_t first_block[kMaxSumJobs + 1];
+  PackedSumJob job[kMaxSumJobs];
+};
+static_assert(sizeof(SumBatch) <= 4096, "kernel arguments are limited to 4 KB");
+
+__global__ __launch_bounds__(kThreads) void sum_jobs_kernel(const SumBatch b) {
+  __shared__ float sm[kSumLds];
+  int lo = 0, hi = (int)b.njobs;  // first_block[lo] <= blockIdx.x < first_block[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (b.first_block[mid] <= blockIdx.x) lo = mid; else hi = mid;
+  }
+  const PackedSumJob& J = b.job[lo];
+  const size_t block = blockIdx.x - b.first_block[lo];
+  if (J.zg == 0) sum_partials_block_vec(block, J.count, (int)J.splits, J.stride, J.partial, J.out);
+  else if (J.zg == 4) sum_partials_block<4>(sm, block, J.count, (int)J.splits, J.stride, J.partial, J.out);
+  else if (J.zg == 16) sum_partials_block<16>(sm, block, J.count, (int)J.splits, J.stride, J.partial, J.out);
+  else sum_partials_block<64>(sm, block, J.count, (int)J.splits, J.stride, J.partial, J.out);
+}
+
+thread_local std::vector<SumJob>* g_sum_sink = nullptr;
 
 }  // namespace
 
@@ -251,16 +320,52 @@ hipError_t launch_dgrad(hipStream_t s, int elt, int M, int N, int K, const void*
   return simt<EPI_DGRAD>(s, elt, M, K, N, dz, N, 1, Wb, K, 1, e);
 }
 
+void set_sum_sink(std::vector<SumJob>* sink) { g_sum_sink = sink; }
+
 hipError_t launch_sum_partials_strided(hipStream_t s, size_t count, int splits, const float* partial, size_t stride,
                                        float* out) {
+  if (g_sum_sink && count < (1ull << 32) && stride < (1ull << 32)) {
+    g_sum_sink->push_back(SumJob{partial, out, count, stride, splits});
+    return hipSuccess;
+  }
   auto blocks = [&](int il) { return dim3((unsigned)((count + il - 1) / il)); };
-  if (count >= 512 * 64 || splits <= 8)
-    hipLaunchKernelGGL(sum_partials_kernel<4>, blocks(64), dim3(kThreads), 0, s, count, splits, stride, partial, out);
-  else if (count >= 512 * 16)
-    hipLaunchKernelGGL(sum_partials_kernel<16>, blocks(16), dim3(kThreads), 0, s, count, splits, stride, partial, out);
-  else
-    hipLaunchKernelGGL(sum_partials_kernel<64>, blocks(4), dim3(kThreads), 0, s, count, splits, stride, partial, out);
+  switch (sum_zg(count, splits, stride, partial, out)) {
+    case 0: hipLaunchKernelGGL(sum_partials_vec_kernel, blocks(4 * kThreads), dim3(kThreads), 0, s, count, splits, stride, partial, out); break;
+    case 4: hipLaunchKernelGGL(sum_partials_kernel<4>, blocks(64), dim3(kThreads), 0, s, count, splits, stride, partial, out); break;
+    case 16: hipLaunchKernelGGL(sum_partials_kernel<16>, blocks(16), dim3(kThreads), 0, s, count, splits, stride, partial, out); break;
+    default: hipLaunchKernelGGL(sum_partials_kernel<64>, blocks(4), dim3(kThreads), 0, s, count, splits, stride, partial, out);
+  }
   return hipGetLastError();
+}
+
+hipError_t launch_sum_jobs(hipStream_t s, const SumJob* jobs, size_t njobs) {
+  size_t done = 0;
+  while (done < njobs) {
+    SumBatch b;
+    b.njobs = 0;
+    uint64_t blocks = 0;
+    while (done < njobs && b.njobs < (uint32_t)kMaxSumJobs) {
+      const SumJob& j = jobs[done];
+      if (j.count == 0 || j.splits < 1 || j.count >= (1ull << 32) || j.stride >= (1ull << 32)) return hipErrorInvalidValue;
+      const int zg = sum_zg(j.count, j.splits, j.stride, j.partial, j.out), il = sum_outputs_per_block(zg);
+      const uint64_t nb = (j.count + il - 1) / il;
+      if (blocks + nb >= (1ull << 31)) {
+        if (b.njobs == 0) return hipErrorInvalidValue;
+        break;
+      }
+      b.first_block[b.njobs] = (uint32_t)blocks;
+      b.job[b.njobs] = PackedSumJob{j.partial, j.out, (uint32_t)j.count, (uint32_t)j.stride, (uint32_t)j.splits, (uint32_t)zg};
+      blocks += nb;
+      ++b.njobs;
+      ++done;
+    }
+    for (uint32_t k = b.njobs; k <= (uint32_t)kMaxSumJobs; ++k) b.first_block[k] = (uint32_t)blocks;
+    for (uint32_t k = b.njobs; k < (uint32_t)kMaxSumJobs; ++k) b.job[k] = PackedSumJob{nullptr, nullptr, 0, 0, 0, 4};
+    hipLaunchKernelGGL(sum_jobs_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, b);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_sum_partials(hipStream_t s, size_t count, int splits, const float* partial, float* out) {

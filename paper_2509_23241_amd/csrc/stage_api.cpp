@@ -69,6 +69,7 @@ struct Plan {
   uint64_t act_slot_bytes = 0;
   uint64_t dz_bytes = 0;       // one backward temporary
   uint64_t partial_floats = 0; // reduction partials
+  uint64_t deferred_floats = 0; // behind them: partials of the backward pass's sums, which one launch forms at its end
   uint64_t attn_scratch_bytes = 0;  // transient score matrices of the matrix-core attention
   size_t elt_size = 4;
 };
@@ -193,6 +194,34 @@ int check_desc(const tp_stage_desc* d) {
   return TP_OK;
 }
 
+// Floats of partial sums one layer's backward pass keeps until the sums are formed (each rounded up to 64).
+struct DeferredNeed {
+  uint64_t bias = 0, weight = 0, norm = 0;
+  uint64_t total() const { return bias + weight + norm; }
+};
+constexpr uint64_t kMaxDeferredFloats = 1ull << 28;  // 1 GiB
+
+DeferredNeed deferred_need(const tp_stage_desc& d, const LayerPlan& lp) {
+  DeferredNeed need;
+  if (!lp.w_elems) return need;
+  const uint64_t rows = (uint64_t)d.mb * d.n;
+  const tp_layer_desc& L = lp.d;
+  if (L.type == TP_LAYER_LAYERNORM) {
+    need.norm = round_up(tp::layernorm_scratch_floats(rows * lp.tokens, L.in_features), 64);
+  } else if (L.type == TP_LAYER_BATCHNORM) {
+    need.norm = round_up((uint64_t)d.n * 3 * L.in_features, 64);  // per micro-batch: two column sums + those of dx
+  } else if (L.type == TP_LAYER_CONV2D) {
+    const uint64_t px = rows * conv_out_px(L);
+    need.bias = round_up(tp::colsum_scratch_floats((int)px, L.out_features), 64);
+    need.weight = round_up(tp::conv_wgrad_scratch_floats((int)px, L.in_features, L.out_features), 64);
+  } else if (L.type == TP_LAYER_DENSE) {
+    const uint64_t r = rows * lp.tokens;
+    need.bias = round_up(tp::colsum_scratch_floats((int)r, L.out_features), 64);
+    need.weight = round_up(tp::wgrad_scratch_floats(d.dtype, (int)r, L.out_features, L.in_features), 64);
+  }
+  return need;
+}
+
 int make_plan(const tp_stage_desc* d, Plan* p) {
   int rc = check_desc(d);
   if (rc) return rc;
@@ -313,6 +342,11 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
       wg = std::max<uint64_t>(wg, tp::wgrad_scratch_floats(d->dtype, (int)r, lp.d.out_features, lp.d.in_features));
   }
   p->partial_floats = round_up(std::max<uint64_t>({wg, tp::update_scratch_floats(), rows, conv_scratch, norm_scratch}), 64);
+  // Every sum of partials the backward pass needs (bias and split weight gradients, scale and shift gradients of the
+  // normalisations) is put off to one launch at its end: each keeps partials of its own until then.
+  uint64_t deferred = 0;
+  for (const LayerPlan& lp : p->layers) deferred += deferred_need(*d, lp).total();
+  p->deferred_floats = deferred <= kMaxDeferredFloats ? deferred : 0;  // beyond that: sums right away, shared partials
   tp_sizes& s = p->sizes;
   s.param_count = P;
   s.ring_bytes = (uint64_t)d->ring_capacity * P * 4;
@@ -321,7 +355,7 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
   s.wfwd_bytes = d->dtype == TP_BF16 ? P * 2 : 0;
   s.wbwd_bytes = d->policy == TP_LATEST ? 0 : P * p->elt_size;  // V-TiMePReSt never builds intermediate weights
   s.act_bytes = (uint64_t)d->max_in_flight * act;
-  s.scratch_bytes = 3 * p->dz_bytes + p->partial_floats * 4 + 512 + p->attn_scratch_bytes;  // + an aligned block of 256 zero bytes (conv padding)
+  s.scratch_bytes = 3 * p->dz_bytes + (p->partial_floats + p->deferred_floats) * 4 + 512 + p->attn_scratch_bytes;  // + an aligned block of 256 zero bytes (conv padding)
   s.diag_bytes = TP_DIAG_COUNT * sizeof(double);
   return TP_OK;
 }
@@ -374,8 +408,10 @@ struct tp_stage {
   char* act_slot(int q) const { return (char*)bufs.act_dev + (uint64_t)q * plan.act_slot_bytes; }
   char* dz_buf(int i) const { return (char*)bufs.scratch_dev + (uint64_t)i * plan.dz_bytes; }
   float* partials() const { return (float*)((char*)bufs.scratch_dev + 3 * plan.dz_bytes); }
+  float* deferred_partials() const { return partials() + plan.partial_floats; }
+  std::vector<tp::SumJob> sum_jobs;  // the backward pass under way: sums still to be formed
   const void* zeros() const {  // 256-byte aligned, behind the partial sums
-    const uintptr_t p = (uintptr_t)bufs.scratch_dev + 3 * plan.dz_bytes + plan.partial_floats * 4;
+    const uintptr_t p = (uintptr_t)bufs.scratch_dev + 3 * plan.dz_bytes + (plan.partial_floats + plan.deferred_floats) * 4;
     return (const void*)((p + 255) & ~(uintptr_t)255);
   }
   void* attn_scratch() const { return plan.attn_scratch_bytes ? (char*)zeros() + 256 : nullptr; }
@@ -935,8 +971,29 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
         dz = buf;
       }
     }
+    // Sums of partials are put off to one launch behind the loop (when the plan has room for every layer's partials
+    // side by side): `hold(need)` hands out the next `need` floats, SumsDeferred makes the launchers record their sums.
+    const bool defer = st->plan.deferred_floats > 0;
+    st->sum_jobs.clear();
+    uint64_t held = 0;
+    bool held_overflow = false;
+    auto hold = [&](uint64_t need) -> float* {
+      if (!defer) return st->partials();
+      if (held + need > st->plan.deferred_floats) { held_overflow = true; return st->partials(); }
+      float* at = st->deferred_partials() + held;
+      held += need;
+      return at;
+    };
+    struct SumsDeferred {
+      explicit SumsDeferred(std::vector<tp::SumJob>* jobs) { tp::set_sum_sink(jobs); }
+      ~SumsDeferred() { tp::set_sum_sink(nullptr); }
+    };
+    std::vector<tp::SumJob>* sink = defer ? &st->sum_jobs : nullptr;
+    bool bias_summed = false;  // the normalisation just passed has left the column sums of its dx: the bias gradient of this layer
     for (int l = L - 1; l >= 0; --l) {
       const LayerPlan& lp = st->plan.layers[l];
+      const DeferredNeed need = deferred_need(d, lp);
+      if (held_overflow) return fail(TP_ESTATE, "partial sums of the backward pass outgrew their plan");
       // where the gradient w.r.t. this layer's input goes, and what it is multiplied with on the way
       const bool to_caller = l == 0;
       const bool no_dx = to_caller && !d.needs_dx;
@@ -1030,9 +1087,10 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
                             st->plan.layers[l - 1].d.geom[1] == 0 && tp::layernorm_bwd_add_supported(d.dtype, lp.d.in_features) &&
                             ((((uintptr_t)dz | (uintptr_t)pinned | (uintptr_t)dst) & 15) == 0);
           ProfScope ps(st, TP_K_NORM);
+          SumsDeferred later(sink);
           HIP_TRY(tp::launch_layernorm_bwd(st->stream, d.dtype, (size_t)rows * lp.tokens, lp.d.in_features, dz, aslot + lp.x_off,
                                            (const float*)(aslot + lp.stat_off), gs, gl, (float)ca, (float)cb, dst,
-                                           g + lp.w_off, g + lp.b_off, st->partials(), fuse ? pinned : nullptr));
+                                           g + lp.w_off, g + lp.b_off, hold(need.norm), fuse ? pinned : nullptr));
           begin_added = fuse;
         }
         if (no_dx) break;
@@ -1046,21 +1104,39 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
         const float* gs = delta != 0 ? st->ring(slot_f) + lp.w_off : gl;
         const size_t seg_rows = (size_t)d.mb * lp.tokens;        // the statistics belong to one micro-batch
         const size_t bn_scratch = tp::batchnorm_scratch_floats(seg_rows, C, d.n);
-        float* sums = st->partials() + bn_scratch;                // [n][2*C]
+        // [n][2*C], then [n][C]: with the sums put off they wait in this layer's own block, else behind the scratch
+        // of the streaming kernels
+        float* sums = defer ? hold(need.norm) : st->partials() + bn_scratch;
+        float* dx_sums = nullptr;
         {
           ProfScope ps(st, TP_K_NORM);
-          if (tp::batchnorm_fused_bwd_supported(d.dtype, seg_rows, C))
+          if (tp::batchnorm_fused_bwd_supported(d.dtype, seg_rows, C)) {
+            // a dense or convolution layer without activation right in front: its bias gradient is the column sum
+            // of the dx formed here, which this kernel holds in registers anyway
+            if (defer && l > 0 && !dprev && !no_dx) {
+              const tp_layer_desc& pl = st->plan.layers[l - 1].d;
+              if ((pl.type == TP_LAYER_DENSE || pl.type == TP_LAYER_CONV2D) && pl.out_features == C)
+                dx_sums = sums + (size_t)d.n * 2 * C;
+            }
             HIP_TRY(tp::launch_batchnorm_bwd_fused(st->stream, d.dtype, seg_rows, C, d.n, dz, aslot + lp.x_off,
-                                                   (const float*)(aslot + lp.stat_off), gs, gl, (float)ca, (float)cb, dst, sums));
-          else
+                                                   (const float*)(aslot + lp.stat_off), gs, gl, (float)ca, (float)cb, dst, sums,
+                                                   dx_sums));
+          } else {
             HIP_TRY(tp::launch_batchnorm_bwd(st->stream, d.dtype, seg_rows, C, d.n, dz, aslot + lp.x_off,
                                              (const float*)(aslot + lp.stat_off), gs, gl, (float)ca, (float)cb, dst, sums,
                                              st->partials()));
+          }
+          SumsDeferred later(sink);
           if (lp.b_off == lp.w_off + (uint64_t)C) {  // scale and shift gradients lie side by side: one launch sums both
             HIP_TRY(tp::launch_sum_partials_strided(st->stream, 2 * (size_t)C, d.n, sums, 2 * (size_t)C, g + lp.w_off));
           } else {
             HIP_TRY(tp::launch_sum_partials_strided(st->stream, (size_t)C, d.n, sums, 2 * (size_t)C, g + lp.w_off));
             HIP_TRY(tp::launch_sum_partials_strided(st->stream, (size_t)C, d.n, sums + C, 2 * (size_t)C, g + lp.b_off));
+          }
+          if (dx_sums) {
+            HIP_TRY(tp::launch_sum_partials_strided(st->stream, (size_t)C, d.n, dx_sums, (size_t)C,
+                                                    g + st->plan.layers[l - 1].b_off));
+            bias_summed = true;
           }
         }
         if (no_dx) break;
@@ -1082,22 +1158,27 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
         continue;
       }
       const int grad_rows = lp.d.type == TP_LAYER_CONV2D ? rows * (int)conv_out_px(lp.d) : rows * lp.tokens;
-      {
+      if (bias_summed) {
+        bias_summed = false;
+      } else {
         ProfScope ps(st, TP_K_COLSUM);
-        HIP_TRY(tp::launch_colsum(st->stream, d.dtype, grad_rows, lp.d.out_features, dz, g + lp.b_off, st->partials()));
+        SumsDeferred later(sink);
+        HIP_TRY(tp::launch_colsum(st->stream, d.dtype, grad_rows, lp.d.out_features, dz, g + lp.b_off, hold(need.bias)));
       }
       {
         ProfScope ps(st, TP_K_WGRAD);
+        SumsDeferred later(sink);
+        float* part = hold(need.weight);
         if (lp.d.type == TP_LAYER_DENSE)
           HIP_TRY(tp::launch_wgrad(st->stream, d.dtype, grad_rows, lp.d.out_features, lp.d.in_features, dz, aslot + lp.x_off,
-                                   g + lp.w_off, st->partials()));
+                                   g + lp.w_off, part));
         else if (lp.xpad_off != UINT64_MAX)
           HIP_TRY(tp::conv_c8_wgrad(st->stream, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, lp.d.out_features,
-                                    (const uint16_t*)dz, (const uint16_t*)(aslot + lp.xpad_off), g + lp.w_off, st->partials(),
+                                    (const uint16_t*)dz, (const uint16_t*)(aslot + lp.xpad_off), g + lp.w_off, part,
                                     (const uint16_t*)st->zeros()));
         else
           HIP_TRY(tp::launch_conv_wgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.geom[3], lp.d.in_features,
-                                        lp.d.out_features, dz, aslot + lp.x_off, g + lp.w_off, st->partials(),
+                                        lp.d.out_features, dz, aslot + lp.x_off, g + lp.w_off, part,
                                         st->zeros()));
       }
       if (no_dx) break;
@@ -1111,6 +1192,12 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
                                         lp.d.out_features, dz, wb + lp.w_off * es, dprev, dst, st->zeros(), dmask));
       }
       dz = dst;
+    }
+    if (held_overflow) return fail(TP_ESTATE, "partial sums of the backward pass outgrew their plan");
+    if (!st->sum_jobs.empty()) {
+      ProfScope ps(st, TP_K_SUMS);
+      HIP_TRY(tp::launch_sum_jobs(st->stream, st->sum_jobs.data(), st->sum_jobs.size()));
+      st->sum_jobs.clear();
     }
   }
 
