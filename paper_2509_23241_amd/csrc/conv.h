@@ -27,8 +27,12 @@ size_t conv_wgrad_scratch_floats(int pixels, int cin, int cout);
 // y[imgs x H/2 x W/2 x C] = 2x2/2 max pooling of x[imgs x H x W x C];  backward recomputes the
 // position of the (first) maximum from the saved input x.
 hipError_t launch_maxpool_fwd(hipStream_t s, int elt, int imgs, int H, int W, int C, const void* x, void* y);
+// d_prev (may be null; only where maxpool_bwd_fuses_activation says so and all pointers are 16-byte aligned): the
+// gradient also passes the activation in front of the pooling, dx (.)= d_prev (saved act'), or (relu_mask) the
+// factor (d_prev > 0) of a saved ReLU output -- with the bits of the two separate kernels.
 hipError_t launch_maxpool_bwd(hipStream_t s, int elt, int imgs, int H, int W, int C, const void* x, const void* dy,
-                              void* dx);
+                              void* dx, const void* d_prev = nullptr, int relu_mask = 0);
+bool maxpool_bwd_fuses_activation(int elt, int C);
 
 // y[imgs x H/2 x W/2 x C] = x at the even pixel positions; backward: the gradient at those positions, zero elsewhere.
 // C * element size must be a multiple of 16 bytes.

@@ -55,7 +55,9 @@ hipError_t launch_sum_jobs(hipStream_t s, const SumJob* jobs, size_t njobs);
 
 // dz = dy (.) d    all [rows x cols] in elt; d = saved act'(z).
 // relu_mask = 1: d holds a ReLU output instead of its derivative; the factor is (d > 0).
-hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* d, void* dz, int relu_mask = 0);
+// add (may be null): the gradient is dy + add, rounded to elt, before it is multiplied.  All pointers 16-byte aligned.
+hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* d, void* dz, int relu_mask = 0,
+                               const void* add = nullptr);
 
 // Device-to-device copy of `bytes` bytes.
 hipError_t launch_copy(hipStream_t s, const void* src, void* dst, size_t bytes);

@@ -194,6 +194,93 @@ __global__ __launch_bounds__(kThreads) void maxpool_bwd_kernel(int imgs, int H, 
   }
 }
 
+// The same for bf16 with C % 8 == 0: a lane takes 8 neighbouring channels (16 bytes) of one window.
+__device__ __forceinline__ void unpack_bf16x8(const uint4& u, float (&f)[8]) {
+  const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    f[2 * j] = __uint_as_float(w[j] << 16);
+    f[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ uint4 pack_bf16x8(const float (&f)[8]) {
+  return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+}
+
+__global__ __launch_bounds__(kThreads) void maxpool_fwd_vec_kernel(int imgs, int H, int W, int CV, const uint4* __restrict__ x,
+                                                                   uint4* __restrict__ y) {
+  const size_t total = (size_t)imgs * (H / 2) * (W / 2) * CV;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (size_t)gridDim.x * kThreads) {
+    const int c = i % CV;
+    size_t t = i / CV;
+    const int ow = t % (W / 2);
+    t /= (W / 2);
+    const int oh = t % (H / 2);
+    const size_t img = t / (H / 2);
+    const uint4* p = x + ((img * H + 2 * oh) * W + 2 * ow) * CV + c;
+    float m[8], v[8];
+    unpack_bf16x8(p[0], m);
+    const size_t off[3] = {(size_t)CV, (size_t)W * CV, (size_t)W * CV + CV};
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+      unpack_bf16x8(p[off[q]], v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) m[j] = fmaxf(m[j], v[j]);
+    }
+    y[i] = pack_bf16x8(m);  // bf16 values: packing is exact
+  }
+}
+
+// FUSE: the gradient also passes the activation in front of the pooling: dx = (gradient at the maximum) (.) d, with
+// d the saved act' tensor at the pooling input's positions, or (MASK) the factor (d > 0) of a saved ReLU output.
+template <bool FUSE, bool MASK>
+__global__ __launch_bounds__(kThreads) void maxpool_bwd_vec_kernel(int imgs, int H, int W, int CV, const uint4* __restrict__ x,
+                                                                   const uint4* __restrict__ dy, const uint4* d,
+                                                                   uint4* __restrict__ dx) {
+  const size_t total = (size_t)imgs * (H / 2) * (W / 2) * CV;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (size_t)gridDim.x * kThreads) {
+    const int c = i % CV;
+    size_t t = i / CV;
+    const int ow = t % (W / 2);
+    t /= (W / 2);
+    const int oh = t % (H / 2);
+    const size_t img = t / (H / 2);
+    const size_t base = ((img * H + 2 * oh) * W + 2 * ow) * CV + c;
+    const size_t off[4] = {0, (size_t)CV, (size_t)W * CV, (size_t)W * CV + CV};
+    float xv[4][8], g[8], o[4][8];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) unpack_bf16x8(x[base + off[q]], xv[q]);
+    unpack_bf16x8(dy[i], g);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float best = xv[0][j];
+      int arg = 0;
+#pragma unroll
+      for (int q = 1; q < 4; ++q)
+        if (xv[q][j] > best) { best = xv[q][j]; arg = q; }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) o[q][j] = q == arg ? g[j] : 0.f;
+    }
+    if constexpr (FUSE) {
+      const bool same = d == x;  // a ReLU output that is this layer's own saved input
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float dv[8];
+        if (same) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) dv[j] = xv[q][j];
+        } else {
+          unpack_bf16x8(d[base + off[q]], dv);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[q][j] = MASK ? (dv[j] > 0.f ? o[q][j] : 0.f) : o[q][j] * dv[j];
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) dx[base + off[q]] = pack_bf16x8(o[q]);
+  }
+}
+
 // y[img][oh][ow][:] = x[img][2*oh][2*ow][:] in 16-byte units (CV per pixel); the backward pass writes the
 // gradient back to those positions and zero everywhere else.
 __global__ __launch_bounds__(kThreads) void subsample_fwd_kernel(int imgs, int H, int W, int CV, const uint4* __restrict__ x,
@@ -320,8 +407,17 @@ hipError_t launch_subsample_bwd(hipStream_t s, int elt, int imgs, int H, int W, 
   return hipGetLastError();
 }
 
+inline bool pool_vec_ok(int elt, int C, const void* a, const void* b, const void* c, const void* d) {
+  return elt == 1 && C % 8 == 0 && ((((uintptr_t)a | (uintptr_t)b | (uintptr_t)c | (uintptr_t)d) & 15) == 0);
+}
+
 hipError_t launch_maxpool_fwd(hipStream_t s, int elt, int imgs, int H, int W, int C, const void* x, void* y) {
   const size_t total = (size_t)imgs * (H / 2) * (W / 2) * C;
+  if (pool_vec_ok(elt, C, x, y, nullptr, nullptr)) {
+    hipLaunchKernelGGL(maxpool_fwd_vec_kernel, dim3(stream_blocks(total / 8, 8192)), dim3(kThreads), 0, s, imgs, H, W, C / 8,
+                       (const uint4*)x, (uint4*)y);
+    return hipGetLastError();
+  }
   const int blocks = stream_blocks(total, 8192);
   if (elt == 1)
     hipLaunchKernelGGL(maxpool_fwd_kernel<uint16_t>, dim3(blocks), dim3(kThreads), 0, s, imgs, H, W, C, (const uint16_t*)x, (uint16_t*)y);
@@ -330,9 +426,23 @@ hipError_t launch_maxpool_fwd(hipStream_t s, int elt, int imgs, int H, int W, in
   return hipGetLastError();
 }
 
+bool maxpool_bwd_fuses_activation(int elt, int C) { return elt == 1 && C % 8 == 0; }
+
 hipError_t launch_maxpool_bwd(hipStream_t s, int elt, int imgs, int H, int W, int C, const void* x, const void* dy,
-                              void* dx) {
+                              void* dx, const void* d_prev, int relu_mask) {
   const size_t total = (size_t)imgs * (H / 2) * (W / 2) * C;
+  if (pool_vec_ok(elt, C, x, dy, dx, d_prev)) {
+    const dim3 grid(stream_blocks(total / 8, 8192));
+#define TP_POOL_BWD(FUSE, MASK)                                                                                          \
+  hipLaunchKernelGGL((maxpool_bwd_vec_kernel<FUSE, MASK>), grid, dim3(kThreads), 0, s, imgs, H, W, C / 8, (const uint4*)x, \
+                     (const uint4*)dy, (const uint4*)d_prev, (uint4*)dx)
+    if (!d_prev) TP_POOL_BWD(false, false);
+    else if (relu_mask) TP_POOL_BWD(true, true);
+    else TP_POOL_BWD(true, false);
+#undef TP_POOL_BWD
+    return hipGetLastError();
+  }
+  if (d_prev) return hipErrorNotSupported;  // the caller asks maxpool_bwd_fuses_activation first
   const int blocks = stream_blocks(total, 8192);
   if (elt == 1)
     hipLaunchKernelGGL(maxpool_bwd_kernel<uint16_t>, dim3(blocks), dim3(kThreads), 0, s, imgs, H, W, C, (const uint16_t*)x,

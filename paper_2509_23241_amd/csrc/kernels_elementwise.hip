@@ -173,35 +173,42 @@ __global__ __launch_bounds__(kThreads) void convert_kernel(size_t n4, const floa
 // dz = dy (.) d, 16 bytes per lane per step; `count` elements, the tail element-wise.
 // dz may be the same buffer as dy (every element is read before it is written by the same lane).
 // MASK: d holds a ReLU output instead of its derivative; the factor is (d > 0).
-template <typename T, bool MASK>
+// ADD: the gradient is dy + add (two branches of a residual connection meeting), rounded to T as the separate
+// addition would have stored it, before it passes the activation.
+template <typename T, bool MASK, bool ADD>
 __global__ __launch_bounds__(kThreads) void act_backward_kernel(size_t count, const T* dy, const T* __restrict__ d,
-                                                                T* dz) {
+                                                                T* dz, const T* __restrict__ add) {
   constexpr int V = 16 / sizeof(T);
   const size_t nvec = count / V;
   const size_t stride = (size_t)gridDim.x * kThreads;
   const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
   auto through = [](float g, float dv) { return MASK ? (dv > 0.f ? g : 0.f) : g * dv; };
+  auto summed = [](float g, float a) { return ADD ? to_float(from_float<T>(g + a)) : g; };
   for (size_t i = tid; i < nvec; i += stride) {
     const uint4 a = reinterpret_cast<const uint4*>(dy)[i];
     const uint4 b = reinterpret_cast<const uint4*>(d)[i];
+    uint4 c = make_uint4(0, 0, 0, 0);
+    if constexpr (ADD) c = reinterpret_cast<const uint4*>(add)[i];
     uint4 o;
     if (sizeof(T) == 2) {
-      const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+      const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w}, cw[4] = {c.x, c.y, c.z, c.w};
       uint32_t ow[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        ow[j] = pack_bf16x2(through(__uint_as_float(aw[j] << 16), __uint_as_float(bw[j] << 16)),
-                            through(__uint_as_float(aw[j] & 0xffff0000u), __uint_as_float(bw[j] & 0xffff0000u)));
+        ow[j] = pack_bf16x2(through(summed(__uint_as_float(aw[j] << 16), __uint_as_float(cw[j] << 16)), __uint_as_float(bw[j] << 16)),
+                            through(summed(__uint_as_float(aw[j] & 0xffff0000u), __uint_as_float(cw[j] & 0xffff0000u)),
+                                    __uint_as_float(bw[j] & 0xffff0000u)));
       o = make_uint4(ow[0], ow[1], ow[2], ow[3]);
     } else {
-      o = make_uint4(__float_as_uint(through(__uint_as_float(a.x), __uint_as_float(b.x))),
-                     __float_as_uint(through(__uint_as_float(a.y), __uint_as_float(b.y))),
-                     __float_as_uint(through(__uint_as_float(a.z), __uint_as_float(b.z))),
-                     __float_as_uint(through(__uint_as_float(a.w), __uint_as_float(b.w))));
+      o = make_uint4(__float_as_uint(through(summed(__uint_as_float(a.x), __uint_as_float(c.x)), __uint_as_float(b.x))),
+                     __float_as_uint(through(summed(__uint_as_float(a.y), __uint_as_float(c.y)), __uint_as_float(b.y))),
+                     __float_as_uint(through(summed(__uint_as_float(a.z), __uint_as_float(c.z)), __uint_as_float(b.z))),
+                     __float_as_uint(through(summed(__uint_as_float(a.w), __uint_as_float(c.w)), __uint_as_float(b.w))));
     }
     reinterpret_cast<uint4*>(dz)[i] = o;
   }
-  for (size_t i = nvec * V + tid; i < count; i += stride) dz[i] = from_float<T>(through(to_float(dy[i]), to_float(d[i])));
+  for (size_t i = nvec * V + tid; i < count; i += stride)
+    dz[i] = from_float<T>(through(summed(to_float(dy[i]), ADD ? to_float(add[i]) : 0.f), to_float(d[i])));
 }
 
 // Plain 16-byte-per-lane copy (activations handed to a stage that are not yet in its workspace).
@@ -348,15 +355,23 @@ hipError_t launch_convert(hipStream_t s, int elt, size_t count, const float* src
   return hipGetLastError();
 }
 
-hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* d, void* dz, int relu_mask) {
+hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* d, void* dz, int relu_mask,
+                               const void* add) {
+  if ((((uintptr_t)dy | (uintptr_t)d | (uintptr_t)dz | (uintptr_t)add) & 15) != 0) return hipErrorInvalidValue;
   const int blocks = stream_blocks(count / 8 + 1, 4096);
-#define TP_ACT_BWD(T, MASK) \
-  hipLaunchKernelGGL((act_backward_kernel<T, MASK>), dim3(blocks), dim3(kThreads), 0, s, count, (const T*)dy, (const T*)d, (T*)dz)
-  if (elt == ELT_BF16) {
-    if (relu_mask) TP_ACT_BWD(uint16_t, true); else TP_ACT_BWD(uint16_t, false);
-  } else {
-    if (relu_mask) TP_ACT_BWD(float, true); else TP_ACT_BWD(float, false);
-  }
+#define TP_ACT_BWD(T, MASK, ADD)                                                                                        \
+  hipLaunchKernelGGL((act_backward_kernel<T, MASK, ADD>), dim3(blocks), dim3(kThreads), 0, s, count, (const T*)dy, (const T*)d, \
+                     (T*)dz, (const T*)add)
+#define TP_ACT_BWD_T(T)                                   \
+  do {                                                    \
+    if (relu_mask) {                                      \
+      if (add) TP_ACT_BWD(T, true, true); else TP_ACT_BWD(T, true, false);   \
+    } else {                                              \
+      if (add) TP_ACT_BWD(T, false, true); else TP_ACT_BWD(T, false, false); \
+    }                                                     \
+  } while (0)
+  if (elt == ELT_BF16) TP_ACT_BWD_T(uint16_t); else TP_ACT_BWD_T(float);
+#undef TP_ACT_BWD_T
 #undef TP_ACT_BWD
   return hipGetLastError();
 }

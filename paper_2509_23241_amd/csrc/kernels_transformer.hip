@@ -242,6 +242,26 @@ __global__ __launch_bounds__(kThreads) void add_kernel(size_t count, const T* a,
     out[i] = from_float<T>(to_float(a[i]) + to_float(b[i]));
 }
 
+// bf16, 16 bytes per lane; `tail` elements behind the last whole unit go one by one
+__global__ __launch_bounds__(kThreads) void add_bf16_vec_kernel(size_t nvec, size_t tail, const uint4* a, const uint4* b, uint4* out) {
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  for (size_t i = tid; i < nvec; i += stride) {
+    const uint4 u = a[i], v = b[i];
+    const uint32_t uw[4] = {u.x, u.y, u.z, u.w}, vw[4] = {v.x, v.y, v.z, v.w};
+    uint32_t ow[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      ow[j] = pack_bf16x2(__uint_as_float(uw[j] << 16) + __uint_as_float(vw[j] << 16),
+                          __uint_as_float(uw[j] & 0xffff0000u) + __uint_as_float(vw[j] & 0xffff0000u));
+    out[i] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+  }
+  const uint16_t* ta = reinterpret_cast<const uint16_t*>(a + nvec);
+  const uint16_t* tb = reinterpret_cast<const uint16_t*>(b + nvec);
+  uint16_t* to = reinterpret_cast<uint16_t*>(out + nvec);
+  for (size_t i = tid; i < tail; i += stride) to[i] = float_to_bf16(bf16_to_float(ta[i]) + bf16_to_float(tb[i]));
+}
+
 // ---- attention ------------------------------------------------------------------------------------
 constexpr int kTile = 64;   // keys (or queries) per LDS tile
 constexpr int kRows = 16;   // rows of the walking side per workgroup (4 per wave)
@@ -592,6 +612,12 @@ hipError_t launch_layernorm_bwd(hipStream_t s, int elt, size_t rows, int D, cons
 }
 
 hipError_t launch_add(hipStream_t s, int elt, size_t count, const void* a, const void* b, void* out) {
+  if (elt == ELT_BF16 && ((((uintptr_t)a | (uintptr_t)b | (uintptr_t)out) & 15) == 0)) {
+    const size_t nvec = count / 8;
+    hipLaunchKernelGGL(add_bf16_vec_kernel, dim3(blocks_for((nvec + kThreads - 1) / kThreads + 1, 4096)), dim3(kThreads), 0, s, nvec,
+                       count % 8, (const uint4*)a, (const uint4*)b, (uint4*)out);
+    return hipGetLastError();
+  }
   const int blocks = blocks_for((count + kThreads - 1) / kThreads, 8192);
   if (elt == ELT_BF16)
     hipLaunchKernelGGL(add_kernel<uint16_t>, dim3(blocks), dim3(kThreads), 0, s, count, (const uint16_t*)a, (const uint16_t*)b,

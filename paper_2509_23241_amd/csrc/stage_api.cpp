@@ -1019,12 +1019,16 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
         return TP_OK;
       };
       if (lp.d.type == TP_LAYER_MAXPOOL2) {
+        // the activation in front of the pooling is passed by the same kernel where it takes 16-byte units
+        const bool fused = dprev && tp::maxpool_bwd_fuses_activation(d.dtype, lp.d.in_features) &&
+                           ((((uintptr_t)dz | (uintptr_t)dst | (uintptr_t)dprev) & 15) == 0);
         {
           ProfScope ps(st, TP_K_POOL);
           HIP_TRY(tp::launch_maxpool_bwd(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features,
-                                         aslot + lp.x_off, dz, dst));
+                                         aslot + lp.x_off, dz, dst, fused ? dprev : nullptr, dmask));
         }
-        if (int rc = through_activation(dst)) return rc;
+        if (!fused)
+          if (int rc = through_activation(dst)) return rc;
         dz = dst;
         continue;
       }
@@ -1068,12 +1072,19 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
           if (int rc = through_activation(const_cast<void*>(dz))) return rc;
           continue;
         }
-        {
-          ProfScope ps(st, TP_K_ADD);
-          HIP_TRY(tp::launch_add(st->stream, d.dtype, (size_t)rows * lp.in_elems, dz, pinned, dst));
+        if (dprev && ((((uintptr_t)dz | (uintptr_t)pinned | (uintptr_t)dst | (uintptr_t)dprev) & 15) == 0)) {
+          // the two gradients meet and pass the activation in front of the begin in one kernel
+          ProfScope ps(st, TP_K_ACT_BWD);
+          HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * lp.in_elems, dz, dprev, dst, dmask, pinned));
+          pinned = nullptr;
+        } else {
+          {
+            ProfScope ps(st, TP_K_ADD);
+            HIP_TRY(tp::launch_add(st->stream, d.dtype, (size_t)rows * lp.in_elems, dz, pinned, dst));
+          }
+          pinned = nullptr;
+          if (int rc = through_activation(dst)) return rc;
         }
-        pinned = nullptr;
-        if (int rc = through_activation(dst)) return rc;
         dz = dst;
         continue;
       }
