@@ -26,7 +26,7 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# Figures of the default workload taken with rocprofv3 on the library at commit d8014b7 (kernel sources of the three
+# Figures of the default workload taken with rocprofv3 on the library at commit 0214482 (kernel sources of the three
 # GEMMs and the update unchanged since); commands and raw counts in profiles/.
 #   traffic: HBM-side bytes per launch from two --pmc runs (FETCH_SIZE, then WRITE_SIZE) scaled by what the same
 #            counters read for a plain 1 GiB copy (FETCH_SIZE reports half the bytes, WRITE_SIZE all of them):
@@ -35,8 +35,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 #            profiles/bench_mlp4096_stage1_kernel_stats.md
 MEASURED_TRAFFIC_BYTES = {"fprop": 56.1e6, "dgrad": 159.5e6, "wgrad": 168.0e6, "update": 940.1e6,
                           "act_bwd": 50.4e6, "colsum": 19.0e6}
-ROCPROF_AVG_US = {"fprop": 18.82, "dgrad": 67.15, "wgrad": 66.34, "update": 160.25, "act_bwd": 11.22}
-PROFILED_AT = "d8014b7"
+ROCPROF_AVG_US = {"fprop": 18.98, "dgrad": 66.67, "wgrad": 65.67, "update": 163.35, "act_bwd": 10.51}
+PROFILED_AT = "0214482"
 
 
 def parse():
@@ -117,8 +117,9 @@ def kernel_work(cls, w, s, needs_dx):
         return 0.0, tot
     if cls == "norm":                  # forward: x in, y out; backward: dy, x in, dx out
         tot = sum(2.0 * rows * l.out_dim() * 5 for l in layers if l.kind == "ln")
-        # batch norm forward: x three times in, a and act' out; backward: dy, x twice in, dx out
-        tot += sum(2.0 * rows * l.out_dim() * (3 + (2 if l.act != "none" else 1) + 5) for l in layers if l.kind == "bn")
+        # batch norm, every operand once: forward x in, a out (a ReLU's derivative is read off a); backward dy, x in,
+        # dx out; the tensor a fused residual add reads is left out
+        tot += sum(2.0 * rows * l.out_dim() * (2 + 3) for l in layers if l.kind == "bn")
         return 0.0, tot
     if cls == "add":                   # forward a + b -> out; backward the same on gradients
         tot = sum(2.0 * rows * l.out_dim() * 3 * 2 for l in layers if l.kind == "res" and l.mark == "add")
@@ -139,6 +140,12 @@ def kernel_work(cls, w, s, needs_dx):
             continue
         if cls == "dgrad" and i == 0 and not needs_dx:
             continue
+        if cls == "colsum" and i + 1 < len(layers) and layers[i + 1].kind == "bn" and l.act == "none":
+            # the bias gradient comes out of the normalisation's backward kernel (layers of up to 2048 rows per
+            # micro-batch, whole 16-byte units of channels): no pass over dz of its own
+            px = l.ho * l.wo if l.kind == "conv" else getattr(l, "tokens", 1)
+            if w.mb * px <= 2048 and (l.cout if l.kind == "conv" else l.out_features) % 8 == 0:
+                continue
         f, b = layer_work(cls, l, rows, w.mb)
         mult = w.n if cls == "fprop" else 1
         flops += mult * f

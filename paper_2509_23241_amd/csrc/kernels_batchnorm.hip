@@ -130,29 +130,34 @@ __global__ __launch_bounds__(kThreads) void bn_dx_vec_kernel(size_t rows, int C,
                                                              uint16_t* __restrict__ dx);
 
 // ---- slab kernels (bf16, small layers) -----------------------------------------------------------------
-// One workgroup of 1024 lanes owns 8 adjacent channels (one 16-byte unit per row) for ALL rows the
-// statistics run over; lane t holds rows t, t + 1024, ... in registers.  The passes of the layer --
-// mean, centred variance, normalise (forward); the two column sums, dx (backward) -- then cost one read
-// of the slab and one launch instead of five (forward) or three per micro-batch (backward; the sums over the
-// micro-batches stay a launch of their own).  For the layers of a bottleneck stage (a few MB per call) the launches, not
-// the bytes, were what took the time.  Workgroups are renumbered so that those of one XCD (every eighth
-// workgroup id) take neighbouring slabs: a 128-byte line of x is then fetched into one L2, not eight.
+// One workgroup of 1024 lanes owns W adjacent 16-byte units of every row (8 * W channels) for ALL rows the
+// statistics run over: lane t takes unit t % W of rows t / W, t / W + 1024 / W, ... and keeps them in registers.
+// The passes of the layer -- mean, centred variance, normalise (forward); the column sums, dx (backward) -- then
+// cost one read of the slab and one launch instead of five (forward) or three per micro-batch (backward; the sums
+// over the micro-batches stay a launch of their own).  For the layers of a bottleneck stage (a few MB per call) the
+// launches, not the bytes, were what took the time.  W = 1 in the forward kernel, 2 in the backward kernel of layers
+// with more than 1024 rows (the launchers say why).  Workgroups are renumbered so that those of one XCD (every eighth
+// workgroup id) take neighbouring slabs: the 128-byte lines they share then meet in one L2 (without it the forward
+// kernel at W = 2 took 18.6 us instead of 14.5 us).
 constexpr int kSlabThreads = 1024, kSlabWaves = kSlabThreads / 64;
 
 __device__ __forceinline__ int slab_of_block(int b, int nblocks) {
   return (nblocks & 7) ? b : (b & 7) * (nblocks >> 3) + (b >> 3);
 }
 
-// Sums NV values per lane over the whole workgroup, in a fixed order; every lane gets the totals.  The values
-// go through LDS as [NV][1024]: thread (v, p) adds 16 neighbouring lanes' values of quantity v, the 64 threads of
-// quantity v finish with one butterfly -- 6 shuffles on one value in NV waves instead of 6 * NV in all sixteen.
-template <int NV>
-__device__ __forceinline__ void slab_sum(float (&v)[NV], float* red /* [NV][kSlabThreads] + [NV] */) {
+// Sums NV values per lane over the lanes that hold the same unit t % W, in a fixed order; every lane gets the totals
+// of its unit.  The values go through LDS as [NV][1024] with the lanes of one unit next to each other: thread (v, p)
+// adds 16 neighbouring entries of quantity v, the 64 / W threads of one unit finish with a butterfly.
+template <int NV, int W>
+__device__ __forceinline__ void slab_sum(float (&v)[NV], float* red /* [NV][kSlabThreads] + [NV][W] */) {
   static_assert(NV * 64 <= kSlabThreads, "one wave per quantity");
+  constexpr int kSeg = kSlabThreads / W;  // lanes per unit
+  constexpr int kTpu = 64 / W;            // adding threads per unit
   const int t = threadIdx.x;
+  const int at = (t % W) * kSeg + t / W;
   __syncthreads();  // the previous totals have been read
 #pragma unroll
-  for (int i = 0; i < NV; ++i) red[i * kSlabThreads + t] = v[i];
+  for (int i = 0; i < NV; ++i) red[i * kSlabThreads + at] = v[i];
   __syncthreads();
   if (t < NV * 64) {
     const int q = t >> 6, p = t & 63;
@@ -164,12 +169,12 @@ __device__ __forceinline__ void slab_sum(float (&v)[NV], float* red /* [NV][kSla
       a += (f.x + f.y) + (f.z + f.w);
     }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off, 64);
-    if (p == 0) red[NV * kSlabThreads + q] = a;
+    for (int off = kTpu / 2; off > 0; off >>= 1) a += __shfl_xor(a, off, 64);
+    if (p % kTpu == 0) red[NV * kSlabThreads + q * W + p / kTpu] = a;
   }
   __syncthreads();
 #pragma unroll
-  for (int i = 0; i < NV; ++i) v[i] = red[NV * kSlabThreads + i];
+  for (int i = 0; i < NV; ++i) v[i] = red[NV * kSlabThreads + i * W + t % W];
 }
 
 __device__ __forceinline__ void unpack8(const uint4& u, float (&f)[8]) {
@@ -235,20 +240,25 @@ __global__ __launch_bounds__(kThreads) void bn_dx_vec_kernel(size_t rows, int C,
   }
 }
 
-template <int NL>
+template <int NL, int W>
 __global__ __launch_bounds__(kSlabThreads) void bn_fwd_slab_kernel(int rows, int C, const uint16_t* __restrict__ x,
                                                                    const float* __restrict__ gamma,
                                                                    const float* __restrict__ beta, int act,
                                                                    const uint16_t* __restrict__ addend,
                                                                    uint16_t* __restrict__ a_out, uint16_t* __restrict__ d_out,
                                                                    float* __restrict__ stats) {
-  __shared__ __attribute__((aligned(16))) float red[8 * kSlabThreads + 8];
-  const int c0 = slab_of_block(blockIdx.x, gridDim.x) * 8;
-  uint4 v[NL];
+  __shared__ __attribute__((aligned(16))) float red[8 * kSlabThreads + 8 * W];
+  constexpr int kRowsPerPass = kSlabThreads / W;
+  const int r0 = threadIdx.x / W;
+  const int c0 = slab_of_block(blockIdx.x, gridDim.x) * 8 * W + 8 * (threadIdx.x % W);
+  // everything this lane will read is requested up front, the tensor of a fused residual add included: fetched
+  // where it is used, its rows would arrive one memory latency after the other at the end of the kernel
+  uint4 v[NL], va[NL];
 #pragma unroll
   for (int i = 0; i < NL; ++i) {
-    const int r = i * kSlabThreads + threadIdx.x;
+    const int r = i * kRowsPerPass + r0;
     v[i] = r < rows ? *reinterpret_cast<const uint4*>(x + (size_t)r * C + c0) : make_uint4(0, 0, 0, 0);
+    va[i] = (addend && r < rows) ? *reinterpret_cast<const uint4*>(addend + (size_t)r * C + c0) : make_uint4(0, 0, 0, 0);
   }
   const float inv_rows = 1.f / (float)rows;
   float mean[8], rstd[8], s[8], ga[8], be[8];
@@ -265,21 +275,21 @@ __global__ __launch_bounds__(kSlabThreads) void bn_fwd_slab_kernel(int rows, int
 #pragma unroll
     for (int j = 0; j < 8; ++j) s[j] += f[j];
   }
-  slab_sum<8>(s, red);
+  slab_sum<8, W>(s, red);
 #pragma unroll
   for (int j = 0; j < 8; ++j) { mean[j] = s[j] * inv_rows; s[j] = 0.f; }
 #pragma unroll
   for (int i = 0; i < NL; ++i) {
-    if (i * kSlabThreads + (int)threadIdx.x >= rows) continue;
+    if (i * kRowsPerPass + r0 >= rows) continue;
     float f[8];
     unpack8(v[i], f);
 #pragma unroll
     for (int j = 0; j < 8; ++j) s[j] = fmaf(f[j] - mean[j], f[j] - mean[j], s[j]);
   }
-  slab_sum<8>(s, red);
+  slab_sum<8, W>(s, red);
 #pragma unroll
   for (int j = 0; j < 8; ++j) rstd[j] = rsqrtf(s[j] * inv_rows + kBnEps);
-  if (threadIdx.x == 0) {
+  if (r0 == 0) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       stats[2 * (c0 + j)] = mean[j];
@@ -288,11 +298,11 @@ __global__ __launch_bounds__(kSlabThreads) void bn_fwd_slab_kernel(int rows, int
   }
 #pragma unroll
   for (int i = 0; i < NL; ++i) {
-    const int r = i * kSlabThreads + threadIdx.x;
+    const int r = i * kRowsPerPass + r0;
     if (r >= rows) continue;
     float f[8], a[8], d[8], sk[8];
     unpack8(v[i], f);
-    if (addend) unpack8(*reinterpret_cast<const uint4*>(addend + (size_t)r * C + c0), sk);
+    unpack8(va[i], sk);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       float z = fmaf((f[j] - mean[j]) * rstd[j], ga[j], be[j]);
@@ -311,22 +321,24 @@ __global__ __launch_bounds__(kSlabThreads) void bn_fwd_slab_kernel(int rows, int
 // statistics stats[q][2C]; its column sums go to sums[q][0..C) (dy * xhat) and sums[q][C..2C) (dy).  dx_sums (may be
 // null): dx_sums[q][0..C) = column sums of the segment's dx as stored (rounded to bf16) -- the bias gradient of the
 // layer in front, which then needs no pass of its own over dx.
-template <int NL>
+template <int NL, int W>
 __global__ __launch_bounds__(kSlabThreads) void bn_bwd_slab_kernel(int rows, int C, const uint16_t* __restrict__ dy,
                                                                    const uint16_t* __restrict__ x, const float* __restrict__ stats,
                                                                    const float* __restrict__ gamma_s,
                                                                    const float* __restrict__ gamma_l, float alpha, float beta_c,
                                                                    uint16_t* __restrict__ dx, float* __restrict__ sums,
                                                                    float* __restrict__ dx_sums) {
-  __shared__ __attribute__((aligned(16))) float red[16 * kSlabThreads + 16];
-  const int c0 = slab_of_block(blockIdx.x, gridDim.x) * 8;
+  __shared__ __attribute__((aligned(16))) float red[16 * kSlabThreads + 16 * W];
+  constexpr int kRowsPerPass = kSlabThreads / W;
+  const int r0 = threadIdx.x / W;
+  const int c0 = slab_of_block(blockIdx.x, gridDim.x) * 8 * W + 8 * (threadIdx.x % W);
   const int q = blockIdx.y;
   const float inv_rows = 1.f / (float)rows;
   const size_t base = (size_t)q * rows * C + c0;
   uint4 vx[NL], vd[NL];
 #pragma unroll
   for (int i = 0; i < NL; ++i) {
-    const int r = i * kSlabThreads + threadIdx.x;
+    const int r = i * kRowsPerPass + r0;
     vx[i] = r < rows ? *reinterpret_cast<const uint4*>(x + base + (size_t)r * C) : make_uint4(0, 0, 0, 0);
     vd[i] = r < rows ? *reinterpret_cast<const uint4*>(dy + base + (size_t)r * C) : make_uint4(0, 0, 0, 0);
   }
@@ -349,8 +361,8 @@ __global__ __launch_bounds__(kSlabThreads) void bn_bwd_slab_kernel(int rows, int
       s[8 + j] += fd[j];
     }
   }
-  slab_sum<16>(s, red);
-  if (threadIdx.x == 0) {
+  slab_sum<16, W>(s, red);
+  if (r0 == 0) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       sums[(size_t)q * 2 * C + c0 + j] = s[j];
@@ -360,7 +372,7 @@ __global__ __launch_bounds__(kSlabThreads) void bn_bwd_slab_kernel(int rows, int
   float t[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int i = 0; i < NL; ++i) {
-    const int r = i * kSlabThreads + threadIdx.x;
+    const int r = i * kRowsPerPass + r0;
     if (r >= rows) continue;
     float fx[8], fd[8], o[8];
     unpack8(vx[i], fx);
@@ -377,8 +389,8 @@ __global__ __launch_bounds__(kSlabThreads) void bn_bwd_slab_kernel(int rows, int
     for (int j = 0; j < 8; ++j) t[j] += o[j];
   }
   if (dx_sums) {  // the same for every lane of the workgroup
-    slab_sum<8>(t, red);
-    if (threadIdx.x == 0) {
+    slab_sum<8, W>(t, red);
+    if (r0 == 0) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) dx_sums[(size_t)q * C + c0 + j] = t[j];
     }
@@ -445,11 +457,14 @@ hipError_t bn_bwd_typed(hipStream_t s, size_t rows, int C, int nseg, const T* dy
   return hipGetLastError();
 }
 
-// Loads per lane the slab kernels are built for; rows beyond 1024 * the largest go to the streaming kernels.
-inline int slab_loads(size_t rows, int max_loads) {
-  for (int nl = 1; nl <= max_loads; nl *= 2)
-    if (rows <= (size_t)nl * kSlabThreads) return nl;
-  return 0;
+// Rows per micro-batch the slab kernels take (beyond that the streaming kernels are faster) and the loads per lane (a
+// power of two) that cover `rows` when a workgroup owns `width` 16-byte units of every row.
+constexpr size_t kSlabMaxRows = 2048;
+inline int slab_loads(size_t rows, int width) {
+  const size_t rows_per_pass = kSlabThreads / width;
+  int nl = 1;
+  while ((size_t)nl * rows_per_pass < rows) nl *= 2;
+  return nl;
 }
 
 }  // namespace
@@ -457,43 +472,43 @@ inline int slab_loads(size_t rows, int max_loads) {
 size_t batchnorm_scratch_floats(size_t rows, int C, int nseg) { return ((size_t)bn_chunks(rows) * std::max(nseg, 1) + 1) * 2 * C; }
 
 bool batchnorm_fused_bwd_supported(int elt, size_t rows, int C) {
-  return elt == ELT_BF16 && C % 8 == 0 && rows >= 1 && slab_loads(rows, 2) != 0 && rows * C < (1ull << 31);
+  return elt == ELT_BF16 && C % 8 == 0 && rows >= 1 && rows <= kSlabMaxRows && rows * C < (1ull << 31);
 }
 
 hipError_t launch_batchnorm_bwd_fused(hipStream_t s, int elt, size_t rows, int C, int nseg, const void* dy, const void* x,
                                       const float* stats, const float* gamma_s, const float* gamma_l, float alpha, float beta_c,
                                       void* dx, float* sums, float* dx_sums) {
   if (!batchnorm_fused_bwd_supported(elt, rows, C) || nseg < 1 || nseg > 65535) return hipErrorNotSupported;
-  const dim3 grid(C / 8, nseg);
-  if (slab_loads(rows, 2) == 1)
-    hipLaunchKernelGGL(bn_bwd_slab_kernel<1>, grid, dim3(kSlabThreads), 0, s, (int)rows, C, (const uint16_t*)dy, (const uint16_t*)x,
-                       stats, gamma_s, gamma_l, alpha, beta_c, (uint16_t*)dx, sums, dx_sums);
-  else
-    hipLaunchKernelGGL(bn_bwd_slab_kernel<2>, grid, dim3(kSlabThreads), 0, s, (int)rows, C, (const uint16_t*)dy, (const uint16_t*)x,
-                       stats, gamma_s, gamma_l, alpha, beta_c, (uint16_t*)dx, sums, dx_sums);
+  // 32 bytes per row where a micro-batch has more than 1024 rows and the channels allow it (measured on the layers of
+  // a bottleneck group, 2048 rows: 16.0 us against 19.0 us at 16 bytes per row; 64 bytes per row would need eight loads
+  // of x and of dy per lane, more than the 128 registers of a lane in a 1024-lane workgroup hold)
+  const int W = (C % 16 == 0 && rows > (size_t)kSlabThreads) ? 2 : 1;
+  const dim3 grid(C / (8 * W), nseg);
+#define TP_BN_BWD(NL, W)                                                                                                     \
+  hipLaunchKernelGGL((bn_bwd_slab_kernel<NL, W>), grid, dim3(kSlabThreads), 0, s, (int)rows, C, (const uint16_t*)dy,        \
+                     (const uint16_t*)x, stats, gamma_s, gamma_l, alpha, beta_c, (uint16_t*)dx, sums, dx_sums)
+  if (W == 2) TP_BN_BWD(4, 2);
+  else if (slab_loads(rows, 1) == 1) TP_BN_BWD(1, 1);
+  else TP_BN_BWD(2, 1);
+#undef TP_BN_BWD
   return hipGetLastError();
 }
 
-#ifndef TP_BN_SLAB_FWD_LOADS
-#define TP_BN_SLAB_FWD_LOADS 2  // forward slab kernels up to 2048 rows; beyond that the streaming kernels are faster
-#endif
 bool batchnorm_fwd_add_supported(int elt, size_t rows, int C) {
-  return elt == ELT_BF16 && C % 8 == 0 && rows >= 1 && slab_loads(rows, TP_BN_SLAB_FWD_LOADS) != 0 && rows * C < (1ull << 31);
+  return elt == ELT_BF16 && C % 8 == 0 && rows >= 1 && rows <= kSlabMaxRows && rows * C < (1ull << 31);
 }
 
 hipError_t launch_batchnorm_fwd(hipStream_t s, int elt, size_t rows, int C, const void* x, const float* gamma, const float* beta,
                                 int act, void* a_out, void* d_out, float* stats, float* scratch, const void* addend) {
   if (addend && !batchnorm_fwd_add_supported(elt, rows, C)) return hipErrorNotSupported;
   if (batchnorm_fwd_add_supported(elt, rows, C)) {
-#define TP_BN_FWD(NL)                                                                                                    \
-  hipLaunchKernelGGL(bn_fwd_slab_kernel<NL>, dim3(C / 8), dim3(kSlabThreads), 0, s, (int)rows, C, (const uint16_t*)x, gamma, \
-                     beta, act, (const uint16_t*)addend, (uint16_t*)a_out, (uint16_t*)d_out, stats)
-    switch (slab_loads(rows, TP_BN_SLAB_FWD_LOADS)) {
-      case 1: TP_BN_FWD(1); break;
-      case 2: TP_BN_FWD(2); break;
-      case 4: TP_BN_FWD(4); break;
-      default: TP_BN_FWD(8); break;
-    }
+    // 16 bytes per row: wider slabs, which pay in the backward kernel, were slower here on the layers of a bottleneck
+    // group (C = 1024, 2048 rows: 14.5 us at 32 bytes per row against 10.9 us), where x has just been written by another
+    // kernel and more workgroups fetch it from more CUs
+#define TP_BN_FWD(NL, W)                                                                                                     \
+  hipLaunchKernelGGL((bn_fwd_slab_kernel<NL, W>), dim3(C / (8 * W)), dim3(kSlabThreads), 0, s, (int)rows, C, (const uint16_t*)x, \
+                     gamma, beta, act, (const uint16_t*)addend, (uint16_t*)a_out, (uint16_t*)d_out, stats)
+    if (slab_loads(rows, 1) == 1) TP_BN_FWD(1, 1); else TP_BN_FWD(2, 1);
 #undef TP_BN_FWD
     return hipGetLastError();
   }
