@@ -245,7 +245,8 @@ __global__ __launch_bounds__(kThreads) void sum_partials_vec_kernel(size_t count
 inline int sum_zg(size_t count, int splits, size_t stride, const float* partial, const float* out) {
   if (splits <= 8 && count >= 16384 && count % 4 == 0 && stride % 4 == 0 && (((uintptr_t)partial | (uintptr_t)out) & 15) == 0)
     return 0;
-  return (count >= 512 * 64 || splits <= 8) ? 4 : count >= 512 * 16 ? 16 : 64;
+  // at least 16 neighbouring outputs per block where there are that many: 64 bytes of every partial row, not 16
+  return (count >= 512 * 64 || splits <= 8) ? 4 : count >= 1024 ? 16 : 64;
 }
 inline int sum_outputs_per_block(int zg) { return zg == 0 ? 4 * kThreads : kThreads / zg; }
 
