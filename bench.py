@@ -26,7 +26,7 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# Figures of the default workload taken with rocprofv3 on the library at commit 89c5a02 (kernel sources of the three
+# Figures of the default workload taken with rocprofv3 on the library at commit 5e927d5 (kernel sources of the three
 # GEMMs and the update unchanged since); commands and raw counts in profiles/.
 #   traffic: HBM-side bytes per launch from two --pmc runs (FETCH_SIZE, then WRITE_SIZE) scaled by what the same
 #            counters read for a plain 1 GiB copy (FETCH_SIZE reports half the bytes, WRITE_SIZE all of them):
@@ -35,8 +35,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 #            profiles/bench_mlp4096_stage1_kernel_stats.md
 MEASURED_TRAFFIC_BYTES = {"fprop": 56.1e6, "dgrad": 159.5e6, "wgrad": 168.0e6, "update": 940.1e6,
                           "act_bwd": 50.4e6, "colsum": 19.0e6}
-ROCPROF_AVG_US = {"fprop": 18.86, "dgrad": 64.87, "wgrad": 64.76, "update": 164.74, "act_bwd": 10.44}
-PROFILED_AT = "89c5a02"
+ROCPROF_AVG_US = {"fprop": 18.81, "dgrad": 66.58, "wgrad": 66.07, "update": 164.23, "act_bwd": 10.43}
+PROFILED_AT = "5e927d5"
 
 
 def parse():
