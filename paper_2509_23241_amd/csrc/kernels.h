@@ -59,6 +59,13 @@ hipError_t launch_sum_jobs(hipStream_t s, const SumJob* jobs, size_t njobs);
 hipError_t launch_act_backward(hipStream_t s, int elt, size_t count, const void* dy, const void* d, void* dz, int relu_mask = 0,
                                const void* add = nullptr);
 
+// The two in one pass over dy: dz = dy (.) d as launch_act_backward forms it, gb = column sums of that dz as
+// launch_colsum forms them (same partial layout, same scratch).  Only where act_backward_colsum_supported and all three
+// tensors are 16-byte aligned; hipErrorNotSupported (nothing launched) otherwise.
+bool act_backward_colsum_supported(int elt, int N);
+hipError_t launch_act_backward_colsum(hipStream_t s, int elt, int M, int N, const void* dy, const void* d, void* dz,
+                                      int relu_mask, float* gb, float* partials);
+
 // Device-to-device copy of `bytes` bytes.
 hipError_t launch_copy(hipStream_t s, const void* src, void* dst, size_t bytes);
 

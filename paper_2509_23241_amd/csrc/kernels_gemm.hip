@@ -182,6 +182,52 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(int M, int N, 
   }
 }
 
+// dz = dy (.) d (MASK: d is a ReLU output, the factor is (d > 0)) and, in the same pass, the partial column sums of
+// the dz it stores: the first two steps of a backward pass whose last layer has an activation, with the structure --
+// and therefore the sums -- of colsum_partial_kernel.  bf16, N % 8 == 0, 16-byte aligned pointers.
+template <bool MASK>
+__global__ __launch_bounds__(kThreads) void act_backward_colsum_kernel(int M, int N, ColsumShape cs, const uint16_t* __restrict__ dy,
+                                                                       const uint16_t* __restrict__ d, uint16_t* __restrict__ dz,
+                                                                       float* __restrict__ partials) {
+  constexpr int V = 8;
+  __shared__ float sm[kThreads * V];
+  const int lr = threadIdx.x % cs.lanes_per_row, rsub = threadIdx.x / cs.lanes_per_row;
+  const int col = (blockIdx.x * cs.lanes_per_row + lr) * V;
+  const int r0 = blockIdx.y * cs.chunk_rows;
+  const int r1 = min(M, r0 + cs.chunk_rows);
+  float s[V];
+#pragma unroll
+  for (int j = 0; j < V; ++j) s[j] = 0.f;
+  if (col < N) {
+#pragma unroll 4
+    for (int r = r0 + rsub; r < r1; r += cs.rows_per_iter) {
+      const size_t at = (size_t)r * N + col;
+      const uint4 a = *reinterpret_cast<const uint4*>(dy + at), b = *reinterpret_cast<const uint4*>(d + at);
+      const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+      uint32_t ow[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float g0 = __uint_as_float(aw[j] << 16), g1 = __uint_as_float(aw[j] & 0xffff0000u);
+        const float d0 = __uint_as_float(bw[j] << 16), d1 = __uint_as_float(bw[j] & 0xffff0000u);
+        ow[j] = pack_bf16x2(MASK ? (d0 > 0.f ? g0 : 0.f) : g0 * d0, MASK ? (d1 > 0.f ? g1 : 0.f) : g1 * d1);
+        s[2 * j] += __uint_as_float(ow[j] << 16);          // what is stored, as the separate pass over dz would read it
+        s[2 * j + 1] += __uint_as_float(ow[j] & 0xffff0000u);
+      }
+      *reinterpret_cast<uint4*>(dz + at) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < V; ++j) sm[(rsub * cs.lanes_per_row + lr) * V + j] = s[j];
+  __syncthreads();
+  if (rsub == 0 && col < N) {
+    for (int j = 0; j < V; ++j) {
+      float t = 0.f;
+      for (int q = 0; q < cs.rows_per_iter; ++q) t += sm[(q * cs.lanes_per_row + lr) * V + j];
+      partials[(size_t)blockIdx.y * N + col + j] = t;
+    }
+  }
+}
+
 // Sum of partial results.  A block covers IL = 256/ZG consecutive outputs with ZG threads each:
 // thread (zg, il) adds partials zg, zg + ZG, ... of output il, the ZG sums are combined through LDS
 // in a fixed order.  Large outputs take few threads per output (whole cache lines per partial
@@ -380,6 +426,25 @@ hipError_t launch_colsum(hipStream_t s, int elt, int M, int N, const void* dz, f
     hipLaunchKernelGGL(colsum_partial_kernel<uint16_t>, g1, dim3(kThreads), 0, s, M, N, cs, (const uint16_t*)dz, partials);
   else
     hipLaunchKernelGGL(colsum_partial_kernel<float>, g1, dim3(kThreads), 0, s, M, N, cs, (const float*)dz, partials);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  return launch_sum_partials(s, (size_t)N, cs.chunks, partials, gb);
+}
+
+bool act_backward_colsum_supported(int elt, int N) { return elt == ELT_BF16 && N % 8 == 0; }
+
+hipError_t launch_act_backward_colsum(hipStream_t s, int elt, int M, int N, const void* dy, const void* d, void* dz,
+                                      int relu_mask, float* gb, float* partials) {
+  if (!act_backward_colsum_supported(elt, N) || ((((uintptr_t)dy | (uintptr_t)d | (uintptr_t)dz) & 15) != 0))
+    return hipErrorNotSupported;
+  const ColsumShape cs = colsum_shape(M, N, 8);
+  dim3 g1(cs.col_blocks, cs.chunks);
+  if (relu_mask)
+    hipLaunchKernelGGL(act_backward_colsum_kernel<true>, g1, dim3(kThreads), 0, s, M, N, cs, (const uint16_t*)dy,
+                       (const uint16_t*)d, (uint16_t*)dz, partials);
+  else
+    hipLaunchKernelGGL(act_backward_colsum_kernel<false>, g1, dim3(kThreads), 0, s, M, N, cs, (const uint16_t*)dy,
+                       (const uint16_t*)d, (uint16_t*)dz, partials);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   return launch_sum_partials(s, (size_t)N, cs.chunks, partials, gb);

@@ -960,17 +960,6 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
       int rc = tp_blend_coefficients(d.policy, delta, d.lambda, &ca, &cb);
       if (rc) return rc;
     }
-    {
-      const LayerPlan& last = st->plan.layers[L - 1];
-      if (last.d.act == TP_ACT_NONE) {
-        dz = dy_dev;
-      } else {
-        ProfScope ps(st, TP_K_ACT_BWD);
-        void* buf = scratch_for(nullptr);
-        HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * last.out_elems, dy_dev, aslot + last.z_off, buf));
-        dz = buf;
-      }
-    }
     // Sums of partials are put off to one launch behind the loop (when the plan has room for every layer's partials
     // side by side): `hold(need)` hands out the next `need` floats, SumsDeferred makes the launchers record their sums.
     const bool defer = st->plan.deferred_floats > 0;
@@ -989,7 +978,31 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
       ~SumsDeferred() { tp::set_sum_sink(nullptr); }
     };
     std::vector<tp::SumJob>* sink = defer ? &st->sum_jobs : nullptr;
-    bool bias_summed = false;  // the normalisation just passed has left the column sums of its dx: the bias gradient of this layer
+    bool bias_summed = false;  // the bias gradient of the layer coming up has already been formed (or recorded)
+    {
+      const LayerPlan& last = st->plan.layers[L - 1];
+      if (last.d.act == TP_ACT_NONE) {
+        dz = dy_dev;
+      } else {
+        ProfScope ps(st, TP_K_ACT_BWD);
+        void* buf = scratch_for(nullptr);
+        const void* dlast = aslot + last.z_off;
+        // a dense or convolution layer: the pass that forms dz = dy (.) act'(z) also takes its column sums
+        const bool with_bias = (last.d.type == TP_LAYER_DENSE || last.d.type == TP_LAYER_CONV2D) &&
+                               tp::act_backward_colsum_supported(d.dtype, last.d.out_features) &&
+                               ((((uintptr_t)dy_dev | (uintptr_t)dlast | (uintptr_t)buf) & 15) == 0);
+        if (with_bias) {
+          const int grad_rows = last.d.type == TP_LAYER_CONV2D ? rows * (int)conv_out_px(last.d) : rows * last.tokens;
+          SumsDeferred later(sink);
+          HIP_TRY(tp::launch_act_backward_colsum(st->stream, d.dtype, grad_rows, last.d.out_features, dy_dev, dlast, buf, 0,
+                                                 g + last.b_off, hold(deferred_need(d, last).bias)));
+          bias_summed = true;
+        } else {
+          HIP_TRY(tp::launch_act_backward(st->stream, d.dtype, (size_t)rows * last.out_elems, dy_dev, dlast, buf));
+        }
+        dz = buf;
+      }
+    }
     for (int l = L - 1; l >= 0; --l) {
       const LayerPlan& lp = st->plan.layers[l];
       const DeferredNeed need = deferred_need(d, lp);
