@@ -2,6 +2,7 @@
 synthetic inputs and upstream gradients through forward, backward (with real staleness under the
 I-TiMePReSt blend) and update, in both precisions, at shapes that cover image borders, channel
 counts that do and do not fit the matrix-core kernels, and the VGG-style first stage."""
+import numpy as np
 import pytest
 
 from stage_parity import run_stage as _run_stage
@@ -93,3 +94,20 @@ def test_dense_relu_fixed_masks_bf16():
     # dense ReLU layers at matrix-core shapes: dgrad with the mask read off the saved output
     specs = (W.Dense(256, 512, "relu"), W.Dense(512, 256, "relu"), W.Dense(256, 128, "relu"), W.Dense(128, 64, "none"))
     print(_run_stage(specs, "dense_relu_fixed", "bf16", mb=64, n=2, depth=3, minibatches=4, fixed_masks=True))
+
+
+def test_deep_dense_stack_more_sums_than_one_launch_takes_bf16():
+    # 60 dense GELU layers of width 64 on 1024 rows: every layer's weight gradient is formed over two row ranges, so
+    # with the bias column sums the backward pass ends with 120 sums of partials -- more than the 96 one launch takes,
+    # so they go out in two.  Weights N(0, 1 / fan_in): every layer contracts, so the rounding noise of bf16 storage is
+    # damped on its way through the stack instead of amplified (at unit scale 60 GELU layers turn it into 10-40 % of
+    # the exact gradients); what is left of it floors the tolerance (see run_stage).
+    from synth_inputs import normal, round_f32
+    specs = tuple(W.Dense(64, 64, "gelu") for _ in range(60))
+    params = []
+    for i in range(60):
+        params.append(round_f32(normal(f"deep_dense60/W{i}", (64, 64), std=float(np.sqrt(1.0 / 64)))))
+        params.append(round_f32(normal(f"deep_dense60/b{i}", (64,), std=0.05)))
+    worst = _run_stage(specs, "deep_dense60", "bf16", mb=256, n=4, policy="convex", minibatches=2, depth=2, needs_dx=True,
+                       mean_loss_dy=True, lr=0.01, params=params, storage_floor=True)
+    print({k: v for k, v in worst.items() if "[" not in k})
