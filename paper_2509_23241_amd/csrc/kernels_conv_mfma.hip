@@ -208,10 +208,17 @@ __device__ __forceinline__ const E& epi_at(const E& e, int, int) { return e; }
 __device__ __forceinline__ EpiWgrad epi_at(const EpiWgradConv& e, int tap, int split) { return e.at(tap, split); }
 
 // grid = (output tiles, batches, splits); every workgroup runs KT k tiles starting at split*KT.
-template <int BM, int BN, int WGM, int WGN, int NS, class AL, class BL, class Epi>
-__global__ __launch_bounds__(64 * WGM * WGN) void conv_bf16_dma_kernel(int M, int N, int KT, typename AL::Desc ad,
-                                                                        typename BL::Desc bd, Epi epi, TileMap map) {
-  constexpr int NW = WGM * WGN;
+// KG = 2: two groups of WGM x WGN waves share the output tile and take every other k tile each (group g the tiles
+// g, g + 2, ...; KT even), with stage buffers and copies of their own; both groups meet at the same barriers.  At
+// the end the second group hands its accumulators over through LDS and the first one stores the tile.  For products
+// with few output tiles and a long contraction (3x3 convolutions on 4x4 maps: 128 workgroups, 36 k tiles, one MFMA
+// per wave and k step) this halves the chain of barrier -> fragment reads -> MFMAs: 17.3 -> 15.4 us.  What remains is
+// the 576 KB every workgroup gathers through its CU's L1 (each input pixel nine times), 7.5 us at the rate one CU
+// fetches from L2.
+template <int BM, int BN, int WGM, int WGN, int NS, class AL, class BL, class Epi, int KG = 1>
+__global__ __launch_bounds__(64 * WGM * WGN * KG) void conv_bf16_dma_kernel(int M, int N, int KT, typename AL::Desc ad,
+                                                                             typename BL::Desc bd, Epi epi, TileMap map) {
+  constexpr int NW = WGM * WGN;  // waves of one group
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int kStageBytes = AL::kBytes + BL::kBytes;
@@ -219,17 +226,22 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_bf16_dma_kernel(int M, in
   constexpr int NM = (DBK / 16) * TM * TN;
   constexpr bool kSwap = Epi::kSwap;
   static_assert((NS - 2) * kLoads < 64, "too many copies in flight for vmcnt");
+  static_assert(KG == 1 || KG == 2, "one or two groups of waves along the contraction");
   extern __shared__ __attribute__((aligned(16))) uint16_t lds_raw[];
 
   const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int kg = KG == 1 ? 0 : wave_all / NW;  // group along the contraction
+  const int wave = KG == 1 ? wave_all : wave_all % NW;
   const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
   int tile_m, tile_n;
   map.get(blockIdx.x, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int batch = blockIdx.y, split = blockIdx.z;
   const int tile0 = split * KT;
-  const uint32_t lds_base = lds_addr_of(lds_raw);
+  const int KTg = KT / KG;  // k tiles of this group: tile0 + kg, tile0 + kg + KG, ...
+  const uint32_t lds_base = lds_addr_of(lds_raw) + kg * (NS * kStageBytes);
+  const uint16_t* lds_group = lds_raw + kg * (NS * kStageBytes / 2);
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -246,7 +258,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_bf16_dma_kernel(int M, in
 
   // tiles past the end re-read the last tile into a stage nobody reads again (constant vmcnt arithmetic)
   auto issue_copy = [&](int t, int tile, int st) {
-    const int tc = tile0 + min(tile, KT - 1);
+    const int tc = tile0 + min(tile, KTg - 1) * KG + kg;
     const uint32_t dst = lds_base + st * kStageBytes;
     if (t < AL::kPerWave) ta.issue_one(t, dst, tc, wave);
     else tb.issue_one(t - AL::kPerWave, dst + AL::kBytes, tc, wave);
@@ -257,10 +269,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_bf16_dma_kernel(int M, in
     for (int t = 0; t < kLoads; ++t) issue_copy(t, st, st);
 
   int rd = 0, wr = NS - 1;
-  for (int kt = 0; kt < KT; ++kt) {
+  for (int kt = 0; kt < KTg; ++kt) {
     wait_vmcnt<(NS - 2) * kLoads>();
     lds_barrier();
-    const uint16_t* la = lds_raw + rd * (kStageBytes / 2);
+    const uint16_t* la = lds_group + rd * (kStageBytes / 2);
     const uint16_t* lb = la + AL::kBytes / 2;
     bf16x8 af[2][TM], bfr[2][TN];
 #pragma unroll
@@ -298,7 +310,28 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_bf16_dma_kernel(int M, in
     wr = wr + 1 == NS ? 0 : wr + 1;
   }
   wait_vmcnt<0>();
-  lds_barrier();
+  lds_barrier();  // all waves of both groups are done with the stages
+  if constexpr (KG == 2) {
+    // the second group's accumulators go through LDS, behind the regions the first group's epilogue turns its tiles
+    // through: [wave][accumulator register][lane]
+    float* handover = reinterpret_cast<float*>(lds_raw) + NW * (wave_epilogue_bytes<TM, TN>() / 4) + wave * (TM * TN * 16 * 64);
+    if (kg == 1) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) handover[((i * TN + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+    }
+    lds_barrier();  // the last barrier of the workgroup: every wave of both groups reaches it
+    if (kg == 1) return;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] += handover[((i * TN + j) * 16 + r) * 64 + lane];
+  }
   if constexpr (Epi::kSwap) {
     if (m0 + wm + WM <= M && n0 + wn + WN <= N && (N & 7) == 0) {
       float* wave_lds = reinterpret_cast<float*>(lds_raw) + wave * (wave_epilogue_bytes<TM, TN>() / 4);
@@ -309,14 +342,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void conv_bf16_dma_kernel(int M, in
   store_tiles<TM, TN>(acc, epi_at(epi, batch, split), m0 + wm, n0 + wn, M, N, lane);
 }
 
-template <int BM, int BN, int NS, class AL, class BL, class Epi>
+template <int BM, int BN, int NS, class AL, class BL, class Epi, int KG = 1>
 hipError_t launch_conv(hipStream_t s, int M, int N, int KT, int batches, int splits, const typename AL::Desc& ad,
                        const typename BL::Desc& bd, const Epi& epi) {
-  constexpr size_t stage_bytes = (size_t)NS * (AL::kBytes + BL::kBytes);
-  constexpr size_t epi_bytes = (size_t)4 * wave_epilogue_bytes<BM / 64, BN / 64>();
+  constexpr size_t stage_bytes = (size_t)KG * NS * (AL::kBytes + BL::kBytes);
+  // epilogue: the four wave tiles turned through LDS, and behind them (KG = 2) the second group's accumulators
+  constexpr size_t epi_bytes = (size_t)4 * wave_epilogue_bytes<BM / 64, BN / 64>() + (KG == 2 ? (size_t)BM * BN * 4 : 0);
   constexpr size_t lds_bytes = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
   static_assert(lds_bytes <= 160 * 1024, "stages do not fit the LDS of a CU");
-  auto kernel = conv_bf16_dma_kernel<BM, BN, 2, 2, NS, AL, BL, Epi>;
+  if (KG == 2 && (KT % 2 != 0 || KT < 4)) return hipErrorInvalidValue;
+  auto kernel = conv_bf16_dma_kernel<BM, BN, 2, 2, NS, AL, BL, Epi, KG>;
   if (lds_bytes > 32 * 1024) {
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -324,7 +359,7 @@ hipError_t launch_conv(hipStream_t s, int M, int N, int KT, int batches, int spl
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const TileMap map = make_tile_map(tiles_m, tiles_n);
-  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n, batches, splits), dim3(256), lds_bytes, s, M, N, KT, ad, bd, epi, map);
+  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n, batches, splits), dim3(256 * KG), lds_bytes, s, M, N, KT, ad, bd, epi, map);
   return hipGetLastError();
 }
 
@@ -877,6 +912,10 @@ hipError_t launch_gather_rows(hipStream_t s, int P, int N, int KT, const GatherD
     return launch_conv<128, 128, 3, RowGather<128, 4, BWD, S>, Plain<128, 4, BWD>>(s, P, N, KT, 1, 1, ad, bd, e);
   if (rows128 * ((N + 63) / 64) >= 256)
     return launch_conv<128, 64, 4, RowGather<128, 4, BWD, S>, Plain<64, 4, BWD>>(s, P, N, KT, 1, 1, ad, bd, e);
+  // no more than half the CUs get a 64 x 64 tile and the contraction is long: two groups of waves share it
+  const long tiles64 = (long)((P + 63) / 64) * ((N + 63) / 64);
+  if (tiles64 <= 128 && KT % 2 == 0 && KT >= 8)
+    return launch_conv<64, 64, 4, RowGather<64, 4, BWD, S>, Plain<64, 4, BWD>, Epi, 2>(s, P, N, KT, 1, 1, ad, bd, e);
   return launch_conv<64, 64, 4, RowGather<64, 4, BWD, S>, Plain<64, 4, BWD>>(s, P, N, KT, 1, 1, ad, bd, e);
 }
 
