@@ -69,17 +69,39 @@ __global__ __launch_bounds__(kThreads) void bn_colsum_kernel(size_t rows, int C,
   }
 }
 
-// sums[0..C) = sum d, sums[C..2C) = sum d^2 (d = x - x[0][c])  ->  stats[2c] = mean, stats[2c+1] = 1/sqrt(var + eps)
+// partial[chunk][0..C) = sum d, [C..2C) = sum d^2 over the chunk's rows (d = x - x[0][c])  ->  stats[2c] = mean,
+// stats[2c+1] = 1/sqrt(var + eps).  16 channels per workgroup: lane (g, c) adds chunks g, g + 16, ... of channel c, the
+// sixteen results meet in LDS in a fixed order.
 template <typename T>
-__global__ __launch_bounds__(kThreads) void bn_finalize_kernel(size_t rows, int C, const T* __restrict__ x,
-                                                               const float* __restrict__ sums, float* __restrict__ stats) {
-  const int c = blockIdx.x * kThreads + threadIdx.x;
-  if (c >= C) return;
-  const float inv = 1.f / (float)rows;
-  const float md = sums[c] * inv;
-  const float var = fmaxf(sums[C + c] * inv - md * md, 0.f);
-  stats[2 * c] = to_float(x[c]) + md;
-  stats[2 * c + 1] = rsqrtf(var + kBnEps);
+__global__ __launch_bounds__(kThreads) void bn_finalize_sum_kernel(size_t rows, int C, int chunks, const T* __restrict__ x,
+                                                                   const float* __restrict__ partial, float* __restrict__ stats) {
+  __shared__ float sm[2][16][16];
+  const int cl = threadIdx.x & 15, g = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + cl;
+  float s0 = 0.f, s1 = 0.f;
+  if (c < C) {
+#pragma unroll 4
+    for (int k = g; k < chunks; k += 16) {
+      s0 += partial[(size_t)k * 2 * C + c];
+      s1 += partial[(size_t)k * 2 * C + C + c];
+    }
+  }
+  sm[0][g][cl] = s0;
+  sm[1][g][cl] = s1;
+  __syncthreads();
+  if (g == 0 && c < C) {
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      a += sm[0][k][cl];
+      b += sm[1][k][cl];
+    }
+    const float inv = 1.f / (float)rows;
+    const float md = a * inv;
+    const float var = fmaxf(b * inv - md * md, 0.f);
+    stats[2 * c] = to_float(x[c]) + md;
+    stats[2 * c + 1] = rsqrtf(var + kBnEps);
+  }
 }
 
 template <typename T>
@@ -122,7 +144,8 @@ __global__ __launch_bounds__(kThreads) void bn_dx_kernel(size_t rows, int C, siz
 __global__ __launch_bounds__(kThreads) void bn_normalize_vec_kernel(size_t rows, int C, const uint16_t* __restrict__ x,
                                                                     const float* __restrict__ stats,
                                                                     const float* __restrict__ gamma, const float* __restrict__ beta,
-                                                                    int act, uint16_t* __restrict__ a_out, uint16_t* __restrict__ d_out);
+                                                                    int act, const uint16_t* __restrict__ addend,
+                                                                    uint16_t* __restrict__ a_out, uint16_t* __restrict__ d_out);
 __global__ __launch_bounds__(kThreads) void bn_dx_vec_kernel(size_t rows, int C, size_t nseg, const uint16_t* __restrict__ dy,
                                                              const uint16_t* __restrict__ x, const float* __restrict__ stats,
                                                              const float* __restrict__ sums, const float* __restrict__ gamma_s,
@@ -189,20 +212,38 @@ __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
   return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
 }
 
+// The launchers give these two kernels a grid whose stride (threads of the grid, in 16-byte units) is a multiple of
+// the units per row, so a lane stays on the same 8 channels for all its rows and reads their statistics and affine
+// parameters once (fetched per element they were 32-48 extra loads for every 16 bytes of x: 14 us for a layer the
+// kernel now streams in a few).  addend (or null): the kept tensor of a residual add that follows a normalisation
+// without activation -- the result is act(bf16(bn(x)) + addend), as the slab kernel forms it.
 __global__ __launch_bounds__(kThreads) void bn_normalize_vec_kernel(size_t rows, int C, const uint16_t* __restrict__ x,
                                                                     const float* __restrict__ stats,
                                                                     const float* __restrict__ gamma, const float* __restrict__ beta,
-                                                                    int act, uint16_t* __restrict__ a_out, uint16_t* __restrict__ d_out) {
+                                                                    int act, const uint16_t* __restrict__ addend,
+                                                                    uint16_t* __restrict__ a_out, uint16_t* __restrict__ d_out) {
   const size_t nvec = rows * C / 8;
   const int cv = C / 8;
-  const size_t stride = (size_t)gridDim.x * kThreads;
-  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
-    const int c0 = (int)(i % cv) * 8;
-    float f[8], a[8], d[8];
+  const size_t stride = (size_t)gridDim.x * kThreads;  // a multiple of cv
+  const size_t first = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const int c0 = (int)(first % cv) * 8;
+  float mean[8], rstd[8], ga[8], be[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    mean[j] = stats[2 * (c0 + j)];
+    rstd[j] = stats[2 * (c0 + j) + 1];
+    ga[j] = gamma[c0 + j];
+    be[j] = beta[c0 + j];
+  }
+#pragma unroll 2
+  for (size_t i = first; i < nvec; i += stride) {
+    float f[8], a[8], d[8], sk[8];
     unpack8(reinterpret_cast<const uint4*>(x)[i], f);
+    if (addend) unpack8(reinterpret_cast<const uint4*>(addend)[i], sk);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const float z = fmaf((f[j] - stats[2 * (c0 + j)]) * stats[2 * (c0 + j) + 1], gamma[c0 + j], beta[c0 + j]);
+      float z = fmaf((f[j] - mean[j]) * rstd[j], ga[j], be[j]);
+      if (addend) z = bf16_to_float(float_to_bf16(z)) + sk[j];
       a[j] = act_forward(z, act);
       d[j] = act_derivative(z, act);
     }
@@ -211,32 +252,45 @@ __global__ __launch_bounds__(kThreads) void bn_normalize_vec_kernel(size_t rows,
   }
 }
 
+// grid.y = segment (micro-batch)
 __global__ __launch_bounds__(kThreads) void bn_dx_vec_kernel(size_t rows, int C, size_t nseg, const uint16_t* __restrict__ dy,
                                                              const uint16_t* __restrict__ x, const float* __restrict__ stats,
                                                              const float* __restrict__ sums, const float* __restrict__ gamma_s,
                                                              const float* __restrict__ gamma_l, float alpha, float beta_c,
                                                              uint16_t* __restrict__ dx) {
-  const size_t per = rows * C / 8, nvec = per * nseg;
+  const size_t per = rows * C / 8;
   const int cv = C / 8;
-  const size_t stride = (size_t)gridDim.x * kThreads;
+  const size_t q = blockIdx.y;
+  const size_t stride = (size_t)gridDim.x * kThreads;  // a multiple of cv
+  const size_t first = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const int c0 = (int)(first % cv) * 8;
   const float inv_rows = 1.f / (float)rows;
-  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
-    const size_t q = i / per;
-    const int c0 = (int)(i % cv) * 8;
-    const float* st = stats + q * 2 * C;
-    const float* sq = sums + q * 2 * C;
+  const float* st = stats + q * 2 * C;
+  const float* sq = sums + q * 2 * C;
+  float mean[8], rstd[8], gr[8], s_xh[8], s_dy[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int c = c0 + j;
+    mean[j] = st[2 * c];
+    rstd[j] = st[2 * c + 1];
+    gr[j] = fmaf(alpha, gamma_s[c], beta_c * gamma_l[c]) * rstd[j];
+    s_xh[j] = sq[c];
+    s_dy[j] = sq[C + c];
+  }
+  const uint4* xs = reinterpret_cast<const uint4*>(x) + q * per;
+  const uint4* ds = reinterpret_cast<const uint4*>(dy) + q * per;
+  uint4* os = reinterpret_cast<uint4*>(dx) + q * per;
+#pragma unroll 2
+  for (size_t i = first; i < per; i += stride) {
     float fx[8], fd[8], o[8];
-    unpack8(reinterpret_cast<const uint4*>(x)[i], fx);
-    unpack8(reinterpret_cast<const uint4*>(dy)[i], fd);
+    unpack8(xs[i], fx);
+    unpack8(ds[i], fd);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const int c = c0 + j;
-      const float rstd = st[2 * c + 1];
-      const float g = fmaf(alpha, gamma_s[c], beta_c * gamma_l[c]);
-      const float xh = (fx[j] - st[2 * c]) * rstd;
-      o[j] = g * rstd * (fd[j] - (sq[C + c] + xh * sq[c]) * inv_rows);
+      const float xh = (fx[j] - mean[j]) * rstd[j];
+      o[j] = gr[j] * (fd[j] - (s_dy[j] + xh * s_xh[j]) * inv_rows);
     }
-    reinterpret_cast<uint4*>(dx)[i] = pack8(o);
+    os[i] = pack8(o);
   }
 }
 
@@ -409,29 +463,39 @@ __global__ __launch_bounds__(kThreads) void add_act_kernel(size_t count, const T
 
 inline unsigned stream_grid(size_t count) { return (unsigned)std::min<size_t>(std::max<size_t>((count + kThreads - 1) / kThreads, 1), 8192); }
 
+// Workgroups for the 16-byte kernels: enough for `units` 16-byte units at two per lane, at most 4096, and such that
+// the threads of the grid are a multiple of the units per row (a lane then stays on the same channels).
+inline unsigned vec_grid(size_t units, int units_per_row) {
+  size_t a = (size_t)units_per_row, b = kThreads;
+  while (b) { const size_t t = a % b; a = b; b = t; }  // a = gcd(units_per_row, 256)
+  const size_t mult = (size_t)units_per_row / a;
+  size_t g = std::min<size_t>(std::max<size_t>((units + 2 * kThreads - 1) / (2 * kThreads), 1), 4096);
+  g = (g + mult - 1) / mult * mult;
+  return (unsigned)g;
+}
+
 inline bool vec_ok(int es, int C, const void* p0, const void* p1, const void* p2) {
   return es == 2 && C % 8 == 0 && ((((uintptr_t)p0 | (uintptr_t)p1 | (uintptr_t)p2) & 15) == 0);
 }
 
-// scratch: [chunks][2C] partial sums, then [2C] totals
+// scratch: [chunks][2C] partial sums
 template <typename T>
 hipError_t bn_fwd_typed(hipStream_t s, size_t rows, int C, const T* x, const float* gamma, const float* beta, int act, T* a_out,
-                        T* d_out, float* stats, float* scratch) {
+                        T* d_out, float* stats, float* scratch, const T* addend) {
+  const bool vec = vec_ok(sizeof(T), C, x, a_out, d_out) && (((uintptr_t)addend) & 15) == 0;
+  if (addend && !vec) return hipErrorNotSupported;
   const int cr = bn_chunk_rows(rows), chunks = bn_chunks(rows);
   float* partial = scratch;
-  float* totals = scratch + (size_t)chunks * 2 * C;
   hipLaunchKernelGGL((bn_colsum_kernel<T, 0>), dim3((C + 63) / 64, chunks, 1), dim3(kThreads), 0, s, rows, C, cr, x, (const T*)nullptr,
                      (const float*)nullptr, partial);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  e = launch_sum_partials(s, 2 * (size_t)C, chunks, partial, totals);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(bn_finalize_kernel<T>, dim3((C + kThreads - 1) / kThreads), dim3(kThreads), 0, s, rows, C, x, totals, stats);
+  hipLaunchKernelGGL(bn_finalize_sum_kernel<T>, dim3((C + 15) / 16), dim3(kThreads), 0, s, rows, C, chunks, x, partial, stats);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (vec_ok(sizeof(T), C, x, a_out, d_out))
-    hipLaunchKernelGGL(bn_normalize_vec_kernel, dim3(stream_grid(rows * C / 8)), dim3(kThreads), 0, s, rows, C, (const uint16_t*)x, stats,
-                       gamma, beta, act, (uint16_t*)a_out, (uint16_t*)d_out);
+  if (vec)
+    hipLaunchKernelGGL(bn_normalize_vec_kernel, dim3(vec_grid(rows * C / 8, C / 8)), dim3(kThreads), 0, s, rows, C, (const uint16_t*)x,
+                       stats, gamma, beta, act, (const uint16_t*)addend, (uint16_t*)a_out, (uint16_t*)d_out);
   else
     hipLaunchKernelGGL(bn_normalize_kernel<T>, dim3(stream_grid(rows * C)), dim3(kThreads), 0, s, rows, C, x, stats, gamma, beta, act,
                        a_out, d_out);
@@ -449,7 +513,7 @@ hipError_t bn_bwd_typed(hipStream_t s, size_t rows, int C, int nseg, const T* dy
   e = launch_sum_partials(s, (size_t)nseg * 2 * C, chunks, scratch, sums);
   if (e != hipSuccess) return e;
   if (vec_ok(sizeof(T), C, x, dy, dx))
-    hipLaunchKernelGGL(bn_dx_vec_kernel, dim3(stream_grid(rows * C / 8 * nseg)), dim3(kThreads), 0, s, rows, C, (size_t)nseg,
+    hipLaunchKernelGGL(bn_dx_vec_kernel, dim3(vec_grid(rows * C / 8, C / 8), nseg), dim3(kThreads), 0, s, rows, C, (size_t)nseg,
                        (const uint16_t*)dy, (const uint16_t*)x, stats, sums, gamma_s, gamma_l, alpha, beta_c, (uint16_t*)dx);
   else
     hipLaunchKernelGGL(bn_dx_kernel<T>, dim3(stream_grid(rows * C * nseg)), dim3(kThreads), 0, s, rows, C, (size_t)nseg, dy, x, stats, sums,
@@ -494,14 +558,18 @@ hipError_t launch_batchnorm_bwd_fused(hipStream_t s, int elt, size_t rows, int C
   return hipGetLastError();
 }
 
+// bf16 with whole 16-byte units of channels: the slab kernel up to kSlabMaxRows rows, the streaming normalise beyond
 bool batchnorm_fwd_add_supported(int elt, size_t rows, int C) {
+  return elt == ELT_BF16 && C % 8 == 0 && rows >= 1 && rows * C < (1ull << 31);
+}
+inline bool batchnorm_fwd_slab(int elt, size_t rows, int C) {
   return elt == ELT_BF16 && C % 8 == 0 && rows >= 1 && rows <= kSlabMaxRows && rows * C < (1ull << 31);
 }
 
 hipError_t launch_batchnorm_fwd(hipStream_t s, int elt, size_t rows, int C, const void* x, const float* gamma, const float* beta,
                                 int act, void* a_out, void* d_out, float* stats, float* scratch, const void* addend) {
   if (addend && !batchnorm_fwd_add_supported(elt, rows, C)) return hipErrorNotSupported;
-  if (batchnorm_fwd_add_supported(elt, rows, C)) {
+  if (batchnorm_fwd_slab(elt, rows, C)) {
     // 16 bytes per row: wider slabs, which pay in the backward kernel, were slower here on the layers of a bottleneck
     // group (C = 1024, 2048 rows: 14.5 us at 32 bytes per row against 10.9 us), where x has just been written by another
     // kernel and more workgroups fetch it from more CUs
@@ -513,8 +581,10 @@ hipError_t launch_batchnorm_fwd(hipStream_t s, int elt, size_t rows, int C, cons
     return hipGetLastError();
   }
   if (elt == ELT_BF16)
-    return bn_fwd_typed<uint16_t>(s, rows, C, (const uint16_t*)x, gamma, beta, act, (uint16_t*)a_out, (uint16_t*)d_out, stats, scratch);
-  return bn_fwd_typed<float>(s, rows, C, (const float*)x, gamma, beta, act, (float*)a_out, (float*)d_out, stats, scratch);
+    return bn_fwd_typed<uint16_t>(s, rows, C, (const uint16_t*)x, gamma, beta, act, (uint16_t*)a_out, (uint16_t*)d_out, stats, scratch,
+                                  (const uint16_t*)addend);
+  return bn_fwd_typed<float>(s, rows, C, (const float*)x, gamma, beta, act, (float*)a_out, (float*)d_out, stats, scratch,
+                             (const float*)nullptr);
 }
 
 hipError_t launch_batchnorm_bwd(hipStream_t s, int elt, size_t rows, int C, int nseg, const void* dy, const void* x, const float* stats,

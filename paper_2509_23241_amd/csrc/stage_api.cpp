@@ -835,10 +835,12 @@ int forward_impl(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_de
         const char* skip = aslot + st->plan.layers[add.skip_layer].x_off + row0 * add.in_elems * es;
         void* add_z = add.z_off == UINT64_MAX ? nullptr : aslot + add.z_off + row0 * add.out_elems * es;
         void* add_a = (l + 1 == L - 1) ? y_dev : (void*)(aslot + st->plan.layers[l + 2].x_off + row0 * add.out_elems * es);
-        HIP_TRY(tp::launch_batchnorm_fwd(st->stream, d.dtype, (size_t)d.mb * lp.tokens, C, x_saved, master + lp.w_off,
-                                         master + lp.b_off, add.d.act, add_a, add_z, stats, st->partials(), skip));
-        ++l;  // the add is done
-        continue;
+        if ((((uintptr_t)x_saved | (uintptr_t)skip | (uintptr_t)add_a | (uintptr_t)add_z) & 15) == 0) {
+          HIP_TRY(tp::launch_batchnorm_fwd(st->stream, d.dtype, (size_t)d.mb * lp.tokens, C, x_saved, master + lp.w_off,
+                                           master + lp.b_off, add.d.act, add_a, add_z, stats, st->partials(), skip));
+          ++l;  // the add is done
+          continue;
+        }
       }
       HIP_TRY(tp::launch_batchnorm_fwd(st->stream, d.dtype, (size_t)d.mb * lp.tokens, C, x_saved, master + lp.w_off,
                                        master + lp.b_off, lp.d.act, a_out, z_out, stats, st->partials()));
