@@ -69,6 +69,75 @@ __global__ __launch_bounds__(kThreads) void bn_colsum_kernel(size_t rows, int C,
   }
 }
 
+// The same for bf16 with C % 8 == 0 in 16-byte units: a workgroup covers 128 channels (16 lanes of 8) x 16 rows per
+// step; the sixteen row lanes of a channel meet in LDS in a fixed order.  Same partial layout.
+__device__ __forceinline__ void bn_unpack8(const uint4& u, float (&f)[8]) {
+  const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    f[2 * j] = __uint_as_float(w[j] << 16);
+    f[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+  }
+}
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void bn_colsum_vec_kernel(size_t rows, int C, int chunk_rows, const uint16_t* __restrict__ x,
+                                                                 const uint16_t* __restrict__ dy, const float* __restrict__ aux,
+                                                                 float* __restrict__ partial) {
+  __shared__ float sm[2][16][128 + 4];
+  const int cl = threadIdx.x & 15, rl = threadIdx.x >> 4;
+  const int c = blockIdx.x * 128 + cl * 8;
+  const size_t seg = blockIdx.z, nseg = gridDim.z;
+  x += seg * rows * C;
+  if (MODE == 2) { dy += seg * rows * C; aux += seg * 2 * C; }
+  const size_t r0 = (size_t)blockIdx.y * chunk_rows;
+  const size_t r1 = std::min(rows, r0 + chunk_rows);
+  float s0[8], s1[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) s0[j] = s1[j] = 0.f;
+  if (c < C) {
+    float mean[8], rstd[8];
+    if (MODE == 0) {
+      bn_unpack8(*reinterpret_cast<const uint4*>(x + c), mean);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { mean[j] = aux[2 * (c + j)]; rstd[j] = aux[2 * (c + j) + 1]; }
+    }
+#pragma unroll 2
+    for (size_t r = r0 + rl; r < r1; r += 16) {
+      float v[8], g[8];
+      bn_unpack8(*reinterpret_cast<const uint4*>(x + r * C + c), v);
+      if (MODE == 2) bn_unpack8(*reinterpret_cast<const uint4*>(dy + r * C + c), g);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (MODE == 0) {
+          s0[j] += v[j] - mean[j];
+          s1[j] = fmaf(v[j] - mean[j], v[j] - mean[j], s1[j]);
+        } else {
+          s0[j] += g[j] * (v[j] - mean[j]) * rstd[j];
+          s1[j] += g[j];
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    sm[0][rl][cl * 8 + j] = s0[j];
+    sm[1][rl][cl * 8 + j] = s1[j];
+  }
+  __syncthreads();
+  if (threadIdx.x < 128 && blockIdx.x * 128 + threadIdx.x < C) {
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      a += sm[0][k][threadIdx.x];
+      b += sm[1][k][threadIdx.x];
+    }
+    float* out = partial + ((size_t)blockIdx.y * nseg + seg) * 2 * C;
+    out[blockIdx.x * 128 + threadIdx.x] = a;
+    out[C + blockIdx.x * 128 + threadIdx.x] = b;
+  }
+}
+
 // partial[chunk][0..C) = sum d, [C..2C) = sum d^2 over the chunk's rows (d = x - x[0][c])  ->  stats[2c] = mean,
 // stats[2c+1] = 1/sqrt(var + eps).  16 channels per workgroup: lane (g, c) adds chunks g, g + 16, ... of channel c, the
 // sixteen results meet in LDS in a fixed order.
@@ -486,8 +555,12 @@ hipError_t bn_fwd_typed(hipStream_t s, size_t rows, int C, const T* x, const flo
   if (addend && !vec) return hipErrorNotSupported;
   const int cr = bn_chunk_rows(rows), chunks = bn_chunks(rows);
   float* partial = scratch;
-  hipLaunchKernelGGL((bn_colsum_kernel<T, 0>), dim3((C + 63) / 64, chunks, 1), dim3(kThreads), 0, s, rows, C, cr, x, (const T*)nullptr,
-                     (const float*)nullptr, partial);
+  if (sizeof(T) == 2 && C % 8 == 0 && (((uintptr_t)x) & 15) == 0)
+    hipLaunchKernelGGL(bn_colsum_vec_kernel<0>, dim3((C + 127) / 128, chunks, 1), dim3(kThreads), 0, s, rows, C, cr, (const uint16_t*)x,
+                       (const uint16_t*)nullptr, (const float*)nullptr, partial);
+  else
+    hipLaunchKernelGGL((bn_colsum_kernel<T, 0>), dim3((C + 63) / 64, chunks, 1), dim3(kThreads), 0, s, rows, C, cr, x, (const T*)nullptr,
+                       (const float*)nullptr, partial);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(bn_finalize_sum_kernel<T>, dim3((C + 15) / 16), dim3(kThreads), 0, s, rows, C, chunks, x, partial, stats);
@@ -507,7 +580,11 @@ template <typename T>
 hipError_t bn_bwd_typed(hipStream_t s, size_t rows, int C, int nseg, const T* dy, const T* x, const float* stats, const float* gamma_s,
                         const float* gamma_l, float alpha, float beta_c, T* dx, float* sums, float* scratch) {
   const int cr = bn_chunk_rows(rows), chunks = bn_chunks(rows);
-  hipLaunchKernelGGL((bn_colsum_kernel<T, 2>), dim3((C + 63) / 64, chunks, nseg), dim3(kThreads), 0, s, rows, C, cr, x, dy, stats, scratch);
+  if (sizeof(T) == 2 && C % 8 == 0 && ((((uintptr_t)x | (uintptr_t)dy)) & 15) == 0)
+    hipLaunchKernelGGL(bn_colsum_vec_kernel<2>, dim3((C + 127) / 128, chunks, nseg), dim3(kThreads), 0, s, rows, C, cr, (const uint16_t*)x,
+                       (const uint16_t*)dy, stats, scratch);
+  else
+    hipLaunchKernelGGL((bn_colsum_kernel<T, 2>), dim3((C + 63) / 64, chunks, nseg), dim3(kThreads), 0, s, rows, C, cr, x, dy, stats, scratch);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   e = launch_sum_partials(s, (size_t)nseg * 2 * C, chunks, scratch, sums);
