@@ -26,7 +26,7 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# Figures of the default workload taken with rocprofv3 on the library at commit 519c5e4 (kernel sources of the three
+# Figures of the default workload taken with rocprofv3 on the library at commit 11d5330 (kernel sources of the three
 # GEMMs and the update unchanged since); commands and raw counts in profiles/.
 #   traffic: HBM-side bytes per launch from two --pmc runs (FETCH_SIZE, then WRITE_SIZE) scaled by what the same
 #            counters read for a plain 1 GiB copy (FETCH_SIZE reports half the bytes, WRITE_SIZE all of them):
@@ -35,8 +35,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 #            profiles/bench_mlp4096_stage1_kernel_stats.md
 MEASURED_TRAFFIC_BYTES = {"fprop": 56.1e6, "dgrad": 159.5e6, "wgrad": 168.0e6, "update": 940.1e6,
                           "act_bwd": 52.5e6, "colsum": 19.0e6}
-ROCPROF_AVG_US = {"fprop": 19.08, "dgrad": 66.35, "wgrad": 65.56, "update": 161.52, "act_bwd": 12.85}
-PROFILED_AT = "519c5e4"
+ROCPROF_AVG_US = {"fprop": 19.02, "dgrad": 66.57, "wgrad": 66.13, "update": 163.5, "act_bwd": 12.75}
+PROFILED_AT = "11d5330"
 
 
 def parse():
