@@ -129,6 +129,21 @@ def maxpool2_backward(dy, idx, in_shape):
     return dwin.reshape(B, H // 2, Wd // 2, 2, 2, C).transpose(0, 1, 3, 2, 4, 5).reshape(B, H, Wd, C)
 
 
+def avgpool_forward(x):
+    """Global average pooling of an NHWC image (or a [positions, channels] sample): y[n, c] = mean over all
+    positions of x[n, ..., c]."""
+    B, C = x.shape[0], x.shape[-1]
+    return x.reshape(B, -1, C).mean(axis=1)
+
+
+def avgpool_backward(dy, in_shape):
+    """Every position of a sample gets the output gradient of its channel divided by the number of positions."""
+    B, C = in_shape[0], in_shape[-1]
+    positions = int(np.prod(in_shape[1:-1]))
+    dx = np.broadcast_to(dy.reshape(B, 1, C) / positions, (B, positions, C))
+    return dx.reshape(in_shape).copy()
+
+
 def subsample2_forward(x):
     """y[n, i, j, :] = x[n, 2i, 2j, :]: the pixels a stride-2 1x1 convolution reads."""
     return x[:, ::2, ::2, :]

@@ -55,7 +55,7 @@ class Stage:
         # position of each layer's weight in the flat parameter list (None: layer has no parameters)
         self.pidx, nxt = [], 0
         for spec in self.specs:
-            if getattr(spec, "kind", "dense") in ("pool", "attn", "res", "sub", "swap"):
+            if getattr(spec, "kind", "dense") in ("pool", "attn", "res", "sub", "swap", "avg"):
                 self.pidx.append(None)
             else:
                 self.pidx.append(nxt)
@@ -131,6 +131,11 @@ class Stage:
             if kind == "sub":
                 saved.append((a.shape,))
                 a = L.subsample2_forward(a)
+                outs.append(a)
+                continue
+            if kind == "avg":
+                saved.append((a.shape,))
+                a = self.q(L.avgpool_forward(a))
                 outs.append(a)
                 continue
             if kind == "swap":                             # projection shortcut: the second branch starts from the
@@ -232,6 +237,9 @@ class Stage:
                     continue
                 if kind == "sub":
                     da = L.subsample2_backward(da, saved[li][0])
+                    continue
+                if kind == "avg":
+                    da = self.q(L.avgpool_backward(da, saved[li][0]))
                     continue
                 if kind == "swap":                         # da: gradient of the remembered tensor through the second
                     da, dskip = dskip, da                  # branch, kept for the begin; the main branch goes on

@@ -180,7 +180,7 @@ class Subsample2:
 
 @dataclass(frozen=True)
 class Conv2d:
-    """3x3-style convolution on NHWC activations, weights [Cout][kh][kw][Cin], plus bias and activation."""
+    """k x k convolution (k odd) on NHWC activations, weights [Cout][kh][kw][Cin], plus bias and activation."""
     cin: int
     cout: int
     h: int           # input height
@@ -232,6 +232,27 @@ class MaxPool2:
 
     def out_dim(self):
         return (self.h // 2) * (self.w // 2) * self.c
+
+
+@dataclass(frozen=True)
+class AvgPool:
+    """Global average pooling: [positions, c] -> [c]; no parameters."""
+    c: int
+    tokens: int      # positions (H * W) that are averaged
+    act: str = "none"
+    kind: str = "avg"
+
+    def param_shapes(self):
+        return []
+
+    def in_shape(self):
+        return (self.tokens, self.c)
+
+    def out_shape(self):
+        return (self.c,)
+
+    def out_dim(self):
+        return self.c
 
 
 @dataclass(frozen=True)
