@@ -84,10 +84,12 @@ enum tp_act { TP_ACT_NONE = 0, TP_ACT_RELU = 1, TP_ACT_GELU = 2 /* exact erf for
 enum tp_layer_type {
   TP_LAYER_DENSE = 0,    /* z = x W^T + b, a = act(z);  W[out x in].  geom[0] = token positions per sample
                             (0 or 1: one): the layer is applied to every position of a [tokens x in] sample */
-  TP_LAYER_CONV2D = 1,   /* 3x3 convolution, stride s = 1 or 2, zero padding 1, + bias + act, on NHWC activations:
-                            in_features = Cin, out_features = Cout, geom = {H, W, 3, s, 1} (H, W of the input,
-                            even for s = 2); W[Cout][3][3][Cin], b[Cout]; a sample is H*W*Cin values in,
-                            (H/s)*(W/s)*Cout out: output pixel (i, j) is centred on input pixel (s*i, s*j)  */
+  TP_LAYER_CONV2D = 1,   /* k x k convolution with k = 1, 3, 5 or 7, stride s = 1 or 2, zero padding (k-1)/2, + bias +
+                            act, on NHWC activations: in_features = Cin, out_features = Cout,
+                            geom = {H, W, k, s, (k-1)/2} (H, W of the input, even for s = 2); W[Cout][k][k][Cin],
+                            b[Cout]; a sample is H*W*Cin values in, (H/s)*(W/s)*Cout out: output pixel (i, j) is
+                            centred on input pixel (s*i, s*j).  The matrix-core kernels take k = 3; other kernel
+                            sizes run on the generic kernels in both precisions */
   TP_LAYER_MAXPOOL2 = 2, /* 2x2 max pooling, stride 2, no parameters: in_features = out_features = C,
                             geom = {H, W} of the input (both even); first maximum wins ties             */
   /* Layers of a transformer-shaped stage; samples are [tokens x features].  The paper prescribes no layer
@@ -110,9 +112,11 @@ enum tp_layer_type {
                              channel over all samples and positions of the micro-batch a forward call sees, biased
                              variance, eps 1e-5; in_features = out_features = C, geom = {positions per sample};
                              parameters gamma[C], beta[C] (fp32 in every mode); no running statistics are kept */
-  TP_LAYER_SUBSAMPLE2 = 7 /* every second pixel of every second row (the pixels a stride-2 1x1 convolution reads), no
+  TP_LAYER_SUBSAMPLE2 = 7, /* every second pixel of every second row (the pixels a stride-2 1x1 convolution reads), no
                              parameters: in_features = out_features = C, geom = {H, W} of the input (both even),
                              C * element size a multiple of 16 bytes */
+  TP_LAYER_AVGPOOL = 8    /* global average pooling, no parameters: a sample of [positions x C] values becomes the C
+                             means over its positions; in_features = out_features = C, geom = {positions} */
 };
 
 #define TP_MAX_LAYERS 64
@@ -125,7 +129,7 @@ typedef struct tp_layer_desc {
   int32_t out_features; /* dense: columns of the layer output; conv/pool: output channels; others: see the type */
   int32_t geom[5];      /* conv: {H, W, kernel, stride, pad}; pool: {H, W, 0, 0, 0}; dense, layer norm: {tokens};
                            attention: {tokens, heads}; residual: {tokens, mark[, tokens out]}; batch norm: {positions};
-                           subsampling: {H, W}; unused entries zero */
+                           subsampling: {H, W}; average pooling: {positions}; unused entries zero */
   int32_t reserved[7];  /* must be zero */
 } tp_layer_desc;
 

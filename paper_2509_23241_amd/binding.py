@@ -12,6 +12,7 @@ TP_F32, TP_BF16 = 0, 1
 TP_ACT_NONE, TP_ACT_RELU, TP_ACT_GELU = 0, 1, 2
 TP_LAYER_DENSE, TP_LAYER_CONV2D, TP_LAYER_MAXPOOL2, TP_LAYER_LAYERNORM, TP_LAYER_ATTENTION, TP_LAYER_RESIDUAL, TP_LAYER_BATCHNORM = 0, 1, 2, 3, 4, 5, 6
 TP_LAYER_SUBSAMPLE2 = 7
+TP_LAYER_AVGPOOL = 8
 TP_MAX_LAYERS, TP_MAX_SLOTS, TP_MAX_IN_FLIGHT = 64, 16, 16
 TP_NONE = (1 << 64) - 1
 TP_DIAG_GRAD_SQ, TP_DIAG_WEIGHT_SQ, TP_DIAG_DRIFT_SQ, TP_DIAG_WB_SQ, TP_DIAG_COUNT = 0, 1, 2, 3, 4
@@ -133,8 +134,9 @@ def _check(rc, soft=()):
 def make_desc(layers, *, dtype, mb, n, stage_index, num_stages, ring_capacity, max_in_flight, policy, needs_dx,
               lam, lr, momentum) -> tp_stage_desc:
     """layers: sequence of (in_features, out_features, act-name[, tokens]) for dense layers,
-    ("conv", cin, cout, H, W, act-name[, stride]) for 3x3/pad 1 convolutions, ("pool", C, H, W) for 2x2 pooling,
-    ("sub", C, H, W) for 2x subsampling, ("ln", D, tokens), ("attn", D, heads, tokens),
+    ("conv", cin, cout, H, W, act-name[, stride[, kernel]]) for kernel x kernel convolutions (default 3) with pad
+    (kernel-1)/2, ("pool", C, H, W) for 2x2 pooling, ("sub", C, H, W) for 2x subsampling, ("avg", C, positions) for
+    global average pooling, ("ln", D, tokens), ("attn", D, heads, tokens),
     ("res", D, tokens, "begin" | "add"[, act-name]), ("swap", D_in, tokens_in, D_out, tokens_out) for the residual
     mark that starts a projection shortcut, ("bn", C, positions, act-name)."""
     if len(layers) > TP_MAX_LAYERS:
@@ -153,7 +155,8 @@ def make_desc(layers, *, dtype, mb, n, stage_index, num_stages, ring_capacity, m
         if spec[0] == "conv":
             _, cin, cout, H, W, act = spec[:6]
             L.type, L.in_features, L.out_features = TP_LAYER_CONV2D, cin, cout
-            L.geom[0], L.geom[1], L.geom[2], L.geom[3], L.geom[4] = H, W, 3, (spec[6] if len(spec) > 6 else 1), 1
+            k = spec[7] if len(spec) > 7 else 3
+            L.geom[0], L.geom[1], L.geom[2], L.geom[3], L.geom[4] = H, W, k, (spec[6] if len(spec) > 6 else 1), (k - 1) // 2
         elif spec[0] == "pool":
             _, c, H, W = spec
             act = "none"
@@ -164,6 +167,11 @@ def make_desc(layers, *, dtype, mb, n, stage_index, num_stages, ring_capacity, m
             act = "none"
             L.type, L.in_features, L.out_features = TP_LAYER_SUBSAMPLE2, c, c
             L.geom[0], L.geom[1] = H, W
+        elif spec[0] == "avg":
+            _, c, positions = spec
+            act = "none"
+            L.type, L.in_features, L.out_features = TP_LAYER_AVGPOOL, c, c
+            L.geom[0] = positions
         elif spec[0] == "swap":
             _, din, tin, dout, tout = spec
             act = "none"
@@ -202,7 +210,7 @@ def layer_in_elems(spec) -> int:
         return spec[3] * spec[4] * spec[1]
     if spec[0] in ("pool", "sub"):
         return spec[2] * spec[3] * spec[1]
-    if spec[0] in ("ln", "bn", "swap"):
+    if spec[0] in ("ln", "bn", "swap", "avg"):
         return spec[1] * spec[2]
     if spec[0] == "attn":
         return 3 * spec[1] * spec[3]
@@ -219,6 +227,8 @@ def layer_out_elems(spec) -> int:
         return (spec[2] // 2) * (spec[3] // 2) * spec[1]
     if spec[0] == "swap":
         return spec[3] * spec[4]
+    if spec[0] == "avg":
+        return spec[1]
     if spec[0] in ("ln", "bn"):
         return spec[1] * spec[2]
     if spec[0] == "attn":
@@ -230,8 +240,9 @@ def layer_out_elems(spec) -> int:
 
 def layer_param_shapes(spec):
     if spec[0] == "conv":
-        return [(spec[2], 3, 3, spec[1]), (spec[2],)]
-    if spec[0] in ("pool", "attn", "res", "sub", "swap"):
+        k = spec[7] if len(spec) > 7 else 3
+        return [(spec[2], k, k, spec[1]), (spec[2],)]
+    if spec[0] in ("pool", "attn", "res", "sub", "swap", "avg"):
         return []
     if spec[0] in ("ln", "bn"):
         return [(spec[1],), (spec[1],)]

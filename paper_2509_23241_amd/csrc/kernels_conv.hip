@@ -1,18 +1,17 @@
-// 3x3 convolution (stride 1 or 2, zero padding 1) on NHWC activations as implicit GEMMs, 2x2 max
-// pooling and 2x subsampling.  Weights are [Cout][3][3][Cin], i.e. a row-major [Cout x 9*Cin] matrix whose k index
-// runs over (tap, input channel), tap = 3*kh + kw.
+// R x R convolution (R odd, stride 1 or 2, zero padding (R-1)/2) on NHWC activations as implicit GEMMs, 2x2 max
+// pooling, 2x subsampling and global average pooling.  Weights are [Cout][R][R][Cin], i.e. a row-major
+// [Cout x R*R*Cin] matrix whose k index runs over (tap, input channel), tap = R*kh + kw.
 //
 //   fprop  z[p][co]  = sum_{tap,ci} x[shift(p,+tap)][ci] * W[co][tap][ci]        rows: output pixels
 //   dgrad  dx[p][ci] = sum_{tap,co} dz[shift(p,-tap)][co] * W_b[co][tap][ci]     rows: input pixels
 //   wgrad  dW[co][tap][ci] = sum_p dz[p][co] * x[shift(p,+tap)][ci]              contraction: pixels
-// shift(p, +tap) moves pixel p = (img, h, w) by (kh-1, kw-1); positions outside the image read 0.
+// shift(p, +tap) moves pixel p = (img, h, w) by (kh-pad, kw-pad); positions outside the image read 0.
 // With stride s the output has (H/s) x (W/s) pixels and output pixel (oh, ow) reads the input at
-// (s*oh + kh - 1, s*ow + kw - 1); dgrad visits, for an input pixel, the taps whose output position
-// (h - kh + 1) / s, (w - kw + 1) / s is whole.
+// (s*oh + kh - pad, s*ow + kw - pad); dgrad visits, for an input pixel, the taps whose output position
+// (h - kh + pad) / s, (w - kw + pad) / s is whole.
 //
 // This file holds the shape-generic, bounds-checked SIMT kernel (fp32 FMA, LDS-tiled), used for
-// the fp32 mode, for channel counts the matrix-core kernels do not take (the 3-channel first
-// layer) and as their reference.  wgrad contracts over all pixels of the mini-batch, so it is
+// the fp32 mode, for kernel sizes and channel counts the matrix-core kernels do not take and as their reference.  wgrad contracts over all pixels of the mini-batch, so it is
 // split over pixel ranges; a second kernel adds the partial results in a fixed order.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -32,6 +31,7 @@ constexpr int BM = 64, BN = 64, BK = 16, kThreads = 256;
 struct ConvGeom {
   int imgs, H, W, Cin, Cout;  // H, W: input image
   int S, Ho, Wo;              // stride, output image
+  int R, Pd;                  // kernel edge, zero padding on every side
 };
 
 __device__ __forceinline__ void pixel_of(int p, int H, int W, int& img, int& h, int& w) {
@@ -52,8 +52,9 @@ __global__ __launch_bounds__(kThreads) void conv_simt_kernel(ConvGeom g, const T
   __shared__ float Bs[BK][BN + 4];
   const int Pin = g.imgs * g.H * g.W, Pout = g.imgs * g.Ho * g.Wo;
   const int M = PRODUCT == 0 ? Pout : (PRODUCT == 1 ? Pin : g.Cout);
-  const int N = PRODUCT == 0 ? g.Cout : (PRODUCT == 1 ? g.Cin : 9 * g.Cin);
-  const int Kfull = PRODUCT == 0 ? 9 * g.Cin : (PRODUCT == 1 ? 9 * g.Cout : Pout);
+  const int KK = g.R * g.R;
+  const int N = PRODUCT == 0 ? g.Cout : (PRODUCT == 1 ? g.Cin : KK * g.Cin);
+  const int Kfull = PRODUCT == 0 ? KK * g.Cin : (PRODUCT == 1 ? KK * g.Cout : Pout);
   const int kbeg = PRODUCT == 2 ? blockIdx.z * pixels_per_split : 0;
   const int kend = PRODUCT == 2 ? min(Pout, kbeg + pixels_per_split) : Kfull;
   const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
@@ -65,7 +66,7 @@ __global__ __launch_bounds__(kThreads) void conv_simt_kernel(ConvGeom g, const T
     if (PRODUCT == 2) return to_float(wgt_or_dz[(size_t)k * g.Cout + m]);  // dz[p][co]
     const int C = PRODUCT == 0 ? g.Cin : g.Cout;
     const int tap = k / C, c = k % C;
-    const int dh = tap / 3 - 1, dw = tap % 3 - 1;
+    const int dh = tap / g.R - g.Pd, dw = tap % g.R - g.Pd;
     int img, h, w;
     if (PRODUCT == 0) {  // output pixel m reads the input
       pixel_of(m, g.Ho, g.Wo, img, h, w);
@@ -82,15 +83,15 @@ __global__ __launch_bounds__(kThreads) void conv_simt_kernel(ConvGeom g, const T
   };
   auto fetch_b = [&](int k, int n) -> float {
     if (n >= N || k >= kend) return 0.f;
-    if (PRODUCT == 0) return to_float(wgt_or_dz[(size_t)n * (9 * g.Cin) + k]);  // W[co][k]
+    if (PRODUCT == 0) return to_float(wgt_or_dz[(size_t)n * (KK * g.Cin) + k]);  // W[co][k]
     if (PRODUCT == 1) {
       const int tap = k / g.Cout, co = k % g.Cout;
-      return to_float(wgt_or_dz[(size_t)co * (9 * g.Cin) + tap * g.Cin + n]);   // W_b[co][tap][ci]
+      return to_float(wgt_or_dz[(size_t)co * (KK * g.Cin) + tap * g.Cin + n]);  // W_b[co][tap][ci]
     }
     const int tap = n / g.Cin, c = n % g.Cin;
     int img, h, w;
     pixel_of(k, g.Ho, g.Wo, img, h, w);
-    const int sh = h * g.S + tap / 3 - 1, sw = w * g.S + tap % 3 - 1;
+    const int sh = h * g.S + tap / g.R - g.Pd, sw = w * g.S + tap % g.R - g.Pd;
     if (sh < 0 || sh >= g.H || sw < 0 || sw >= g.W) return 0.f;
     return to_float(act_in[((size_t)(img * g.H + sh) * g.W + sw) * g.Cin + c]);
   };
@@ -313,6 +314,34 @@ __global__ __launch_bounds__(kThreads) void subsample_bwd_kernel(int imgs, int H
   }
 }
 
+// Global average pooling: y[img][c] = mean over the positions of x[img][p][c], summed in position order in fp32;
+// backward: every position gets dy[img][c] / positions.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void avgpool_fwd_kernel(int imgs, int positions, int C, const T* __restrict__ x,
+                                                               T* __restrict__ y) {
+  const size_t total = (size_t)imgs * C;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (size_t)gridDim.x * kThreads) {
+    const size_t img = i / C;
+    const int c = (int)(i - img * C);
+    const T* p = x + img * positions * C + c;
+    float sum = 0.f;
+    for (int q = 0; q < positions; ++q) sum += to_float(p[(size_t)q * C]);
+    y[i] = from_float<T>(sum / (float)positions);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void avgpool_bwd_kernel(int imgs, int positions, int C, const T* __restrict__ dy,
+                                                               T* __restrict__ dx) {
+  const size_t total = (size_t)imgs * positions * C;
+  const size_t per_img = (size_t)positions * C;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (size_t)gridDim.x * kThreads) {
+    const size_t img = i / per_img;
+    const int c = (int)(i % C);
+    dx[i] = from_float<T>(to_float(dy[img * C + c]) / (float)positions);
+  }
+}
+
 inline int stream_blocks(size_t items, int max_blocks) {
   size_t b = (items + kThreads - 1) / kThreads;
   return (int)(b < 1 ? 1 : (b < (size_t)max_blocks ? b : (size_t)max_blocks));
@@ -320,25 +349,32 @@ inline int stream_blocks(size_t items, int max_blocks) {
 
 }  // namespace
 
-int conv_wgrad_splits(int pixels, int cin, int cout) {
+int conv_wgrad_splits(int pixels, int cin, int cout, int ksize) {
   // enough pixel ranges to put ~1024 workgroups on the chip even when dW has only a handful of
   // tiles (the 3-channel first layer has one), at least 256 pixels each
-  const int tiles = ((9 * cin + BN - 1) / BN) * ((cout + BM - 1) / BM);
+  const int tiles = ((ksize * ksize * cin + BN - 1) / BN) * ((cout + BM - 1) / BM);
   int s = std::min((1024 + tiles - 1) / tiles, (pixels + 255) / 256);
   return s < 1 ? 1 : (s > 1024 ? 1024 : s);
 }
 
-size_t conv_wgrad_scratch_floats(int pixels, int cin, int cout) {
-  const int splits = std::max(conv_wgrad_splits(pixels, cin, cout), conv_mfma_wgrad_max_splits(pixels, cin, cout));
-  return (size_t)splits * cout * 9 * cin;
+size_t conv_wgrad_scratch_floats(int pixels, int cin, int cout, int ksize) {
+  int splits = conv_wgrad_splits(pixels, cin, cout, ksize);
+  if (ksize == 3) splits = std::max(splits, conv_mfma_wgrad_max_splits(pixels, cin, cout));
+  return (size_t)splits * cout * ksize * ksize * cin;
 }
 
-hipError_t launch_conv_fprop(hipStream_t s, int elt, int imgs, int H, int W, int stride, int cin, int cout, const void* x,
-                             const void* wgt, const float* bias, int act, void* d_out, void* a_out, const void* zeros) {
-  if (elt == 1 && zeros && conv_mfma_supported(imgs, H, W, stride, cin, cout))
+bool conv_geometry_supported(int ksize, int stride, int pad) {
+  return (ksize == 1 || ksize == 3 || ksize == 5 || ksize == 7) && (stride == 1 || stride == 2) && pad == (ksize - 1) / 2;
+}
+
+hipError_t launch_conv_fprop(hipStream_t s, int elt, int imgs, int H, int W, int ksize, int stride, int cin, int cout,
+                             const void* x, const void* wgt, const float* bias, int act, void* d_out, void* a_out,
+                             const void* zeros) {
+  if (!conv_geometry_supported(ksize, stride, (ksize - 1) / 2) || (stride == 2 && ((H | W) & 1))) return hipErrorInvalidValue;
+  if (ksize == 3 && elt == 1 && zeros && conv_mfma_supported(imgs, H, W, stride, cin, cout))
     return conv_mfma_fprop(s, imgs, H, W, stride, cin, cout, (const uint16_t*)x, (const uint16_t*)wgt, bias, act,
                            (uint16_t*)d_out, (uint16_t*)a_out, (const uint16_t*)zeros);
-  const ConvGeom g{imgs, H, W, cin, cout, stride, H / stride, W / stride};
+  const ConvGeom g{imgs, H, W, cin, cout, stride, H / stride, W / stride, ksize, (ksize - 1) / 2};
   const int P = imgs * g.Ho * g.Wo;
   dim3 grid((cout + BN - 1) / BN, (P + BM - 1) / BM);
   if (elt == 1)
@@ -350,12 +386,14 @@ hipError_t launch_conv_fprop(hipStream_t s, int elt, int imgs, int H, int W, int
   return hipGetLastError();
 }
 
-hipError_t launch_conv_dgrad(hipStream_t s, int elt, int imgs, int H, int W, int stride, int cin, int cout, const void* dz,
-                             const void* wb, const void* d_prev, void* out, const void* zeros, int relu_mask) {
-  if (elt == 1 && zeros && conv_mfma_supported(imgs, H, W, stride, cin, cout))
+hipError_t launch_conv_dgrad(hipStream_t s, int elt, int imgs, int H, int W, int ksize, int stride, int cin, int cout,
+                             const void* dz, const void* wb, const void* d_prev, void* out, const void* zeros,
+                             int relu_mask) {
+  if (!conv_geometry_supported(ksize, stride, (ksize - 1) / 2) || (stride == 2 && ((H | W) & 1))) return hipErrorInvalidValue;
+  if (ksize == 3 && elt == 1 && zeros && conv_mfma_supported(imgs, H, W, stride, cin, cout))
     return conv_mfma_dgrad(s, imgs, H, W, stride, cin, cout, (const uint16_t*)dz, (const uint16_t*)wb,
                            (const uint16_t*)d_prev, (uint16_t*)out, (const uint16_t*)zeros, relu_mask);
-  const ConvGeom g{imgs, H, W, cin, cout, stride, H / stride, W / stride};
+  const ConvGeom g{imgs, H, W, cin, cout, stride, H / stride, W / stride, ksize, (ksize - 1) / 2};
   const int P = imgs * H * W;
   dim3 grid((cin + BN - 1) / BN, (P + BM - 1) / BM);
   if (elt == 1)
@@ -367,16 +405,17 @@ hipError_t launch_conv_dgrad(hipStream_t s, int elt, int imgs, int H, int W, int
   return hipGetLastError();
 }
 
-hipError_t launch_conv_wgrad(hipStream_t s, int elt, int imgs, int H, int W, int stride, int cin, int cout, const void* dz,
-                             const void* x, float* gW, float* partial, const void* zeros) {
-  if (elt == 1 && zeros && conv_mfma_supported(imgs, H, W, stride, cin, cout))
+hipError_t launch_conv_wgrad(hipStream_t s, int elt, int imgs, int H, int W, int ksize, int stride, int cin, int cout,
+                             const void* dz, const void* x, float* gW, float* partial, const void* zeros) {
+  if (!conv_geometry_supported(ksize, stride, (ksize - 1) / 2) || (stride == 2 && ((H | W) & 1))) return hipErrorInvalidValue;
+  if (ksize == 3 && elt == 1 && zeros && conv_mfma_supported(imgs, H, W, stride, cin, cout))
     return conv_mfma_wgrad(s, imgs, H, W, stride, cin, cout, (const uint16_t*)dz, (const uint16_t*)x, gW, partial,
                            (const uint16_t*)zeros);
-  const ConvGeom g{imgs, H, W, cin, cout, stride, H / stride, W / stride};
+  const ConvGeom g{imgs, H, W, cin, cout, stride, H / stride, W / stride, ksize, (ksize - 1) / 2};
   const int P = imgs * g.Ho * g.Wo;  // the contraction runs over output pixels
-  const int splits = conv_wgrad_splits(P, cin, cout);
+  const int splits = conv_wgrad_splits(P, cin, cout, ksize);
   const int per = ((P + splits - 1) / splits + BK - 1) / BK * BK;
-  dim3 grid((9 * cin + BN - 1) / BN, (cout + BM - 1) / BM, splits);
+  dim3 grid((ksize * ksize * cin + BN - 1) / BN, (cout + BM - 1) / BM, splits);
   if (elt == 1)
     hipLaunchKernelGGL((conv_simt_kernel<uint16_t, 2>), grid, dim3(kThreads), 0, s, g, (const uint16_t*)x, (const uint16_t*)dz,
                        (const float*)nullptr, 0, (const uint16_t*)nullptr, (uint16_t*)nullptr, (uint16_t*)nullptr, partial, per, 0);
@@ -385,7 +424,7 @@ hipError_t launch_conv_wgrad(hipStream_t s, int elt, int imgs, int H, int W, int
                        (const float*)nullptr, 0, (const float*)nullptr, (float*)nullptr, (float*)nullptr, partial, per, 0);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const size_t count = (size_t)cout * 9 * cin;
+  const size_t count = (size_t)cout * ksize * ksize * cin;
   return launch_sum_partials(s, count, splits, partial, gW);
 }
 
@@ -404,6 +443,28 @@ hipError_t launch_subsample_bwd(hipStream_t s, int elt, int imgs, int H, int W, 
   const int CV = C * es / 16;
   const int blocks = stream_blocks((size_t)imgs * H * W * CV, 8192);
   hipLaunchKernelGGL(subsample_bwd_kernel, dim3(blocks), dim3(kThreads), 0, s, imgs, H, W, CV, (const uint4*)dy, (uint4*)dx);
+  return hipGetLastError();
+}
+
+hipError_t launch_avgpool_fwd(hipStream_t s, int elt, int imgs, int positions, int C, const void* x, void* y) {
+  if (imgs < 1 || positions < 1 || C < 1) return hipErrorInvalidValue;
+  const int blocks = stream_blocks((size_t)imgs * C, 8192);
+  if (elt == 1)
+    hipLaunchKernelGGL(avgpool_fwd_kernel<uint16_t>, dim3(blocks), dim3(kThreads), 0, s, imgs, positions, C, (const uint16_t*)x,
+                       (uint16_t*)y);
+  else
+    hipLaunchKernelGGL(avgpool_fwd_kernel<float>, dim3(blocks), dim3(kThreads), 0, s, imgs, positions, C, (const float*)x, (float*)y);
+  return hipGetLastError();
+}
+
+hipError_t launch_avgpool_bwd(hipStream_t s, int elt, int imgs, int positions, int C, const void* dy, void* dx) {
+  if (imgs < 1 || positions < 1 || C < 1) return hipErrorInvalidValue;
+  const int blocks = stream_blocks((size_t)imgs * positions * C, 8192);
+  if (elt == 1)
+    hipLaunchKernelGGL(avgpool_bwd_kernel<uint16_t>, dim3(blocks), dim3(kThreads), 0, s, imgs, positions, C, (const uint16_t*)dy,
+                       (uint16_t*)dx);
+  else
+    hipLaunchKernelGGL(avgpool_bwd_kernel<float>, dim3(blocks), dim3(kThreads), 0, s, imgs, positions, C, (const float*)dy, (float*)dx);
   return hipGetLastError();
 }
 

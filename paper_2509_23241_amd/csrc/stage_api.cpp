@@ -157,8 +157,8 @@ int check_desc(const tp_stage_desc* d) {
       out_e = (uint64_t)L.geom[0] * L.out_features;
     } else if (L.type == TP_LAYER_CONV2D) {
       if (L.geom[0] < 1 || L.geom[1] < 1) return fail(TP_EINVAL, "layer %d: empty image", l);
-      if (L.geom[2] != 3 || (L.geom[3] != 1 && L.geom[3] != 2) || L.geom[4] != 1)
-        return fail(TP_EINVAL, "layer %d: only 3x3 / stride 1 or 2 / pad 1 convolutions are built", l);
+      if (!tp::conv_geometry_supported(L.geom[2], L.geom[3], L.geom[4]))
+        return fail(TP_EINVAL, "layer %d: convolutions are built for kernels 1, 3, 5, 7 with stride 1 or 2 and pad (kernel-1)/2", l);
       if (L.geom[3] == 2 && ((L.geom[0] & 1) || (L.geom[1] & 1)))
         return fail(TP_EINVAL, "layer %d: a stride-2 convolution needs even height and width", l);
       in_e = (uint64_t)L.geom[0] * L.geom[1] * L.in_features;
@@ -170,6 +170,12 @@ int check_desc(const tp_stage_desc* d) {
         return fail(TP_EINVAL, "layer %d: malformed pooling layer", l);
       in_e = (uint64_t)L.geom[0] * L.geom[1] * L.in_features;
       out_e = in_e / 4;
+    } else if (L.type == TP_LAYER_AVGPOOL) {
+      if (L.geom[0] < 1 || L.in_features != L.out_features || L.act != TP_ACT_NONE || L.geom[1] || L.geom[2] || L.geom[3] ||
+          L.geom[4])
+        return fail(TP_EINVAL, "layer %d: malformed average pooling layer", l);
+      in_e = (uint64_t)L.geom[0] * L.in_features;
+      out_e = L.out_features;
     } else if (L.type == TP_LAYER_SUBSAMPLE2) {
       if (L.geom[0] < 2 || L.geom[1] < 2 || (L.geom[0] & 1) || (L.geom[1] & 1))
         return fail(TP_EINVAL, "layer %d: subsampling needs even height and width", l);
@@ -213,7 +219,7 @@ DeferredNeed deferred_need(const tp_stage_desc& d, const LayerPlan& lp) {
   } else if (L.type == TP_LAYER_CONV2D) {
     const uint64_t px = rows * conv_out_px(L);
     need.bias = round_up(tp::colsum_scratch_floats((int)px, L.out_features), 64);
-    need.weight = round_up(tp::conv_wgrad_scratch_floats((int)px, L.in_features, L.out_features), 64);
+    need.weight = round_up(tp::conv_wgrad_scratch_floats((int)px, L.in_features, L.out_features, L.geom[2]), 64);
   } else if (L.type == TP_LAYER_DENSE) {
     const uint64_t r = rows * lp.tokens;
     need.bias = round_up(tp::colsum_scratch_floats((int)r, L.out_features), 64);
@@ -280,9 +286,14 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
     } else if (L.type == TP_LAYER_CONV2D) {
       lp.in_elems = (uint64_t)L.geom[0] * L.geom[1] * L.in_features;
       lp.out_elems = conv_out_px(L) * L.out_features;
-      lp.w_elems = (uint64_t)L.out_features * 9 * L.in_features;
+      lp.w_elems = (uint64_t)L.out_features * L.geom[2] * L.geom[2] * L.in_features;
       conv_scratch = std::max<uint64_t>(conv_scratch, tp::conv_wgrad_scratch_floats((int)(rows * conv_out_px(L)),
-                                                                                    L.in_features, L.out_features));
+                                                                                    L.in_features, L.out_features, L.geom[2]));
+    } else if (L.type == TP_LAYER_AVGPOOL) {
+      lp.tokens = L.geom[0];
+      lp.in_elems = (uint64_t)lp.tokens * L.in_features;
+      lp.out_elems = L.out_features;
+      lp.w_elems = 0;
     } else {
       lp.in_elems = (uint64_t)L.geom[0] * L.geom[1] * L.in_features;
       lp.out_elems = lp.in_elems / 4;
@@ -317,7 +328,7 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
     } else {
       lp.z_off = UINT64_MAX;
     }
-    if (l == 0 && L.type == TP_LAYER_CONV2D && L.geom[3] == 1 && d->dtype == TP_BF16 &&
+    if (l == 0 && L.type == TP_LAYER_CONV2D && L.geom[2] == 3 && L.geom[3] == 1 && d->dtype == TP_BF16 &&
         tp::conv_c8_supported((int)rows, L.geom[0], L.geom[1], L.in_features, L.out_features) &&
         tp::conv_c8_supported(d->mb, L.geom[0], L.geom[1], L.in_features, L.out_features)) {
       lp.xpad_off = act;
@@ -848,9 +859,12 @@ int forward_impl(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_de
     }
     if (lp.d.type == TP_LAYER_CONV2D) {
       ProfScope ps(st, TP_K_FPROP);
-      HIP_TRY(tp::launch_conv_fprop(st->stream, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.geom[3], lp.d.in_features,
-                                    lp.d.out_features, x_saved, wcopy + lp.w_off * es, master + lp.b_off, lp.d.act,
-                                    z_out, a_out, st->zeros()));
+      HIP_TRY(tp::launch_conv_fprop(st->stream, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.geom[2], lp.d.geom[3],
+                                    lp.d.in_features, lp.d.out_features, x_saved, wcopy + lp.w_off * es, master + lp.b_off,
+                                    lp.d.act, z_out, a_out, st->zeros()));
+    } else if (lp.d.type == TP_LAYER_AVGPOOL) {
+      ProfScope ps(st, TP_K_POOL);
+      HIP_TRY(tp::launch_avgpool_fwd(st->stream, d.dtype, d.mb, lp.tokens, lp.d.in_features, x_saved, a_out));
     } else if (lp.d.type == TP_LAYER_SUBSAMPLE2) {
       ProfScope ps(st, TP_K_POOL);
       HIP_TRY(tp::launch_subsample_fwd(st->stream, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, x_saved,
@@ -1012,7 +1026,9 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
       // where the gradient w.r.t. this layer's input goes, and what it is multiplied with on the way
       const bool to_caller = l == 0;
       const bool no_dx = to_caller && !d.needs_dx;
-      if (no_dx && (lp.d.type == TP_LAYER_MAXPOOL2 || lp.d.type == TP_LAYER_SUBSAMPLE2 || lp.d.type == TP_LAYER_ATTENTION)) break;
+      if (no_dx && (lp.d.type == TP_LAYER_MAXPOOL2 || lp.d.type == TP_LAYER_SUBSAMPLE2 || lp.d.type == TP_LAYER_ATTENTION ||
+                    lp.d.type == TP_LAYER_AVGPOOL))
+        break;
       // what the gradient w.r.t. this layer's input is multiplied with: the saved act'(z) of the previous layer, or
       // (dmask = 1) that layer's saved ReLU output, which is this layer's own saved input
       const void* dprev = nullptr;
@@ -1044,6 +1060,15 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
         }
         if (!fused)
           if (int rc = through_activation(dst)) return rc;
+        dz = dst;
+        continue;
+      }
+      if (lp.d.type == TP_LAYER_AVGPOOL) {
+        {
+          ProfScope ps(st, TP_K_POOL);
+          HIP_TRY(tp::launch_avgpool_bwd(st->stream, d.dtype, rows, lp.tokens, lp.d.in_features, dz, dst));
+        }
+        if (int rc = through_activation(dst)) return rc;
         dz = dst;
         continue;
       }
@@ -1203,8 +1228,8 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
                                     (const uint16_t*)dz, (const uint16_t*)(aslot + lp.xpad_off), g + lp.w_off, part,
                                     (const uint16_t*)st->zeros()));
         else
-          HIP_TRY(tp::launch_conv_wgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.geom[3], lp.d.in_features,
-                                        lp.d.out_features, dz, aslot + lp.x_off, g + lp.w_off, part,
+          HIP_TRY(tp::launch_conv_wgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.geom[2], lp.d.geom[3],
+                                        lp.d.in_features, lp.d.out_features, dz, aslot + lp.x_off, g + lp.w_off, part,
                                         st->zeros()));
       }
       if (no_dx) break;
@@ -1214,8 +1239,9 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
           HIP_TRY(tp::launch_dgrad(st->stream, d.dtype, grad_rows, lp.d.out_features, lp.d.in_features, dz, wb + lp.w_off * es,
                                    dprev, dst, dmask));
         else
-          HIP_TRY(tp::launch_conv_dgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.geom[3], lp.d.in_features,
-                                        lp.d.out_features, dz, wb + lp.w_off * es, dprev, dst, st->zeros(), dmask));
+          HIP_TRY(tp::launch_conv_dgrad(st->stream, d.dtype, rows, lp.d.geom[0], lp.d.geom[1], lp.d.geom[2], lp.d.geom[3],
+                                        lp.d.in_features, lp.d.out_features, dz, wb + lp.w_off * es, dprev, dst, st->zeros(),
+                                        dmask));
       }
       dz = dst;
     }

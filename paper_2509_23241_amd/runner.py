@@ -17,12 +17,15 @@ def layer_tuple(spec) -> tuple:
     """Workload layer description -> the tuple format of binding.make_desc."""
     kind = getattr(spec, "kind", "dense")
     if kind == "conv":
-        assert (spec.k, spec.pad) == (3, 1) and spec.stride in (1, 2), "only 3x3 / stride 1 or 2 / pad 1 convolutions are built"
-        return ("conv", spec.cin, spec.cout, spec.h, spec.w, spec.act, spec.stride)
+        assert spec.k in (1, 3, 5, 7) and spec.pad == (spec.k - 1) // 2 and spec.stride in (1, 2), \
+            "convolutions are built for kernels 1, 3, 5, 7 with stride 1 or 2 and pad (kernel-1)/2"
+        return ("conv", spec.cin, spec.cout, spec.h, spec.w, spec.act, spec.stride, spec.k)
     if kind == "pool":
         return ("pool", spec.c, spec.h, spec.w)
     if kind == "sub":
         return ("sub", spec.c, spec.h, spec.w)
+    if kind == "avg":
+        return ("avg", spec.c, spec.tokens)
     if kind == "swap":
         return ("swap", spec.d, spec.tokens, spec.out_d, spec.out_tokens)
     if kind == "ln":

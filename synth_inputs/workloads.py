@@ -369,6 +369,51 @@ def resnet_middle_stages(mb: int = 128, n: int = 4, dtype: str = "bf16") -> Work
     return Workload(name=f"resnet_mid_{dtype}", dtype=dtype, stages=((), conv3, conv4, ()), mb=mb, n=n, classes=2)
 
 
+def bottleneck_proj_block(cin: int, mid: int, cout: int, h: int, w: int, act: str = "relu") -> tuple:
+    """First bottleneck of a group that keeps the image size (conv2_x): [h, w, cin] -> [h, w, cout].  Main branch 1x1
+    conv cin->mid, BN, ReLU, 3x3 conv mid->mid, BN, ReLU, 1x1 conv mid->cout, BN; shortcut 1x1 conv cin->cout, BN; sum,
+    ReLU."""
+    t = h * w
+    return (Residual(cin, t, "begin"), Dense(cin, mid, "none", tokens=t), BatchNorm(mid, t, act),
+            Conv2d(mid, mid, h, w, "none"), BatchNorm(mid, t, act), Dense(mid, cout, "none", tokens=t),
+            BatchNorm(cout, t, "none"), ResidualSwap(cout, t, cin, t),
+            Dense(cin, cout, "none", tokens=t), BatchNorm(cout, t, "none"), Residual(cout, t, "add", act=act))
+
+
+def resnet_stem_stage(size: int = 64, c: int = 64, mid: int = 64, cout: int = 256, blocks: int = 2, act: str = "relu") -> tuple:
+    """Stage 0 of the 4-stage split: 7x7 stride-2 convolution 3->c, BN, ReLU, 2x2 max pooling (size -> size/4), then
+    the conv2_x group: a projection bottleneck c->cout and `blocks` identity bottlenecks, `mid` middle channels."""
+    h = size // 4
+    stem = (Conv2d(3, c, size, size, "none", k=7, stride=2, pad=3), BatchNorm(c, (size // 2) ** 2, act),
+            MaxPool2(c, size // 2, size // 2))
+    return stem + bottleneck_proj_block(c, mid, cout, h, h, act) + tuple(
+        l for _ in range(blocks) for l in bottleneck_block(cout, mid, h, h, act))
+
+
+def resnet_head_stage(c: int = 2048, mid: int = 512, h: int = 2, blocks: int = 2, classes: int = 200, act: str = "relu") -> tuple:
+    """Stage 3 of the 4-stage split: the conv5_x group ([2h, 2h, c/2] -> [h, h, c]: a stride-2 bottleneck with
+    projection shortcut and `blocks` identity bottlenecks), global average pooling, and the classifier c -> classes."""
+    return (bottleneck_down_block(c // 2, mid, c, 2 * h, 2 * h, act) +
+            tuple(l for _ in range(blocks) for l in bottleneck_block(c, mid, h, h, act)) +
+            (AvgPool(c, h * h), Dense(c, classes, "none")))
+
+
+def resnet_stages(mb: int = 128, n: int = 4, dtype: str = "bf16", scale: int = 1, size: int = 64, classes: int = 200,
+                  act: str = "relu") -> Workload:
+    """All four stages of a ResNet-50-style bottleneck net on size x size x 3 images: {stem, conv2_x}, {conv3_x},
+    {conv4_x}, {conv5_x, average pooling, classifier}.  scale divides every channel count (reduced copies the CPU
+    oracle finishes in seconds keep the structure: 3 + 4 + 6 + 3 bottlenecks, strides, projection shortcuts)."""
+    c = 64 // scale
+    q = size // 4
+    s0 = resnet_stem_stage(size, c, c, 4 * c, 2, act)
+    s1 = bottleneck_down_block(4 * c, 2 * c, 8 * c, q, q, act) + tuple(
+        l for _ in range(3) for l in bottleneck_block(8 * c, 2 * c, q // 2, q // 2, act))
+    s2 = bottleneck_down_block(8 * c, 4 * c, 16 * c, q // 2, q // 2, act) + tuple(
+        l for _ in range(5) for l in bottleneck_block(16 * c, 4 * c, q // 4, q // 4, act))
+    s3 = resnet_head_stage(32 * c, 8 * c, q // 8, 2, classes, act)
+    return Workload(name=f"resnet{size}_c{c}_{dtype}_k4", dtype=dtype, stages=(s0, s1, s2, s3), mb=mb, n=n, classes=classes)
+
+
 def transformer_block(d: int, heads: int, ffn: int, tokens: int) -> tuple:
     """Pre-norm decoder block: x + proj(attn(qkv(LN(x)))), then x + ffn2(gelu(ffn1(LN(x))))."""
     return (Residual(d, tokens, "begin"), LayerNorm(d, tokens), Dense(d, 3 * d, "none", tokens=tokens),

@@ -75,7 +75,11 @@ def run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, depth
     upstream gradient like that of a loss averaged over the mini-batch (1 / (n mb) per sample): the scale at
     which the workloads' own lr 0.01 is a training step.
 
-    storage_floor (smooth stages only; meant for stacks of dozens of layers): the plain fp64 oracle runs beside the
+    storage_floor (stages without ReLU, or with ReLUs whose masks are fixed, so that the oracle takes the same ReLU
+    decisions in both of its modes; a max pooling may be there -- the few windows whose routing the storage precision
+    changes are part of what it does to the result; meant for stacks of dozens of layers and for gradients that are
+    sums of terms which nearly cancel, such as the shift in front of a dense layer followed by a batch
+    normalisation): the plain fp64 oracle runs beside the
     bf16-storing one, and a tensor's limit is the larger of the normal tolerance and the distance between the two
     ORACLES on that tensor (times sqrt 2) -- what storing every activation in bf16 does to the exact result, by the
     oracle's own account.  The GPU's bf16 execution then has to sit as close to the bf16-storing oracle as two
@@ -101,7 +105,9 @@ def run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, depth
     # stored values are taken in the same precision on both sides; pure_oracle (smooth stages only) compares with
     # the plain fp64 run instead
     smooth = not any(l.kind == "pool" or getattr(l, "act", "") == "relu" for l in specs)
-    assert smooth or not (pure_oracle or storage_floor)
+    no_relu = not any(getattr(l, "act", "") == "relu" for l in specs)
+    assert smooth or not pure_oracle
+    assert no_relu or fixed_masks or not storage_floor
     ost = Stage(specs, params, policy=policy, lam=lam, lr=lr, momentum=0.9, n=n, first_stage=not needs_dx,
                 storage=W.round_bf16 if (bf16 and not pure_oracle) else None)
     st = GpuStage([layer_tuple(l) for l in specs], params, dtype=dtype, mb=mb, n=n, stage_index=stage_index,

@@ -312,6 +312,41 @@ def test_projection_shortcut_descriptions():
         B.stage_workspace_query(B.make_desc([("conv", 8, 8, 4, 4, "none", 2), (8, 8, "none", 16)], **good))
 
 
+def test_stem_and_head_descriptions():
+    """Kernel sizes other than 3 and global average pooling: accepted geometries, parameter counts, chaining."""
+    from paper_2509_23241_amd.runner import layer_tuple
+    from synth_inputs import workloads as W
+    good = dict(dtype="bf16", mb=2, n=2, stage_index=0, num_stages=4, ring_capacity=4, max_in_flight=4,
+                policy="convex", needs_dx=False, lam=0.1, lr=0.01, momentum=0.9)
+    w = W.resnet_stages(mb=2, n=2)
+    for stage in range(4):
+        layers = [layer_tuple(l) for l in w.stages[stage]]
+        s = B.stage_workspace_query(B.make_desc(layers, **{**good, "stage_index": stage, "needs_dx": stage > 0}))
+        padded = sum((int(np.prod(sh)) + 63) // 64 * 64 for l in w.stages[stage] for sh in l.param_shapes())
+        assert s.param_count == padded
+        assert B.layer_in_elems(layers[0]) == w.stage_in_dim(stage) and B.layer_out_elems(layers[-1]) == w.stage_out_dim(stage)
+        assert [tuple(sh) for l in layers for sh in B.layer_param_shapes(l)] == \
+            [tuple(sh) for l in w.stages[stage] for sh in l.param_shapes()]
+    stem = layer_tuple(w.stages[0][0])
+    assert stem == ("conv", 3, 64, 64, 64, "none", 2, 7)
+    assert B.layer_out_elems(stem) == 32 * 32 * 64 and B.layer_param_shapes(stem)[0] == (64, 7, 7, 3)
+    for k in (1, 3, 5, 7):
+        B.stage_workspace_query(B.make_desc([("conv", 3, 8, 6, 4, "relu", 1, k)], **good))
+    d = B.make_desc([("conv", 3, 8, 6, 4, "relu", 1, 7)], **good)
+    d.layers[0].geom[4] = 1                                                  # pad that does not centre the kernel
+    bad = [d, B.make_desc([("conv", 3, 8, 6, 4, "relu", 1, 4)], **good),     # even kernel
+           B.make_desc([("conv", 3, 8, 6, 4, "relu", 1, 9)], **good),        # kernel larger than what is built
+           B.make_desc([("avg", 8, 0)], **good),                             # no positions
+           B.make_desc([("avg", 8, 4), (8 * 4, 4, "none")], **good)]         # the pooled sample has 8 values, not 32
+    d2 = B.make_desc([("avg", 8, 4)], **good)
+    d2.layers[0].act = B.ACT["relu"]                                         # pooling has no activation
+    for desc in bad + [d2]:
+        with pytest.raises(B.StageLibError) as ei:
+            B.stage_workspace_query(desc)
+        assert ei.value.code == B.TP_EINVAL
+    B.stage_workspace_query(B.make_desc([("avg", 8, 4), (8, 4, "none")], **good))
+
+
 def test_workspace_layout():
     d = B.make_desc([(256, 512, "relu"), (512, 10, "none")], dtype="bf16", mb=32, n=4, stage_index=0, num_stages=2,
                     ring_capacity=2, max_in_flight=2, policy="convex", needs_dx=False, lam=0.1, lr=0.01, momentum=0.9)
