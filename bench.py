@@ -50,7 +50,8 @@ def parse():
                          "vgg: stage 0 of the VGG-16-style net on 32x32x3 images (implicit-GEMM convolutions); "
                          "tfm: interior stage of the decoder-only transformer (4 blocks, d_model 2048, 1024 tokens); "
                          "bneck: the conv4_x group of the ResNet-50-style net (six bottlenecks, 8x8 -> 4x4 maps; "
-                         "--stage 1: its conv3_x group, four bottlenecks, 16x16 -> 8x8)")
+                         "--stage 1: its conv3_x group, four bottlenecks, 16x16 -> 8x8; --stage 0: stem and conv2_x; "
+                         "--stage 3: conv5_x, average pooling, classifier)")
     ap.add_argument("--blocks", type=int, default=4, help="transformer blocks in the tfm stage")
     ap.add_argument("--stage", type=int, default=None)
     ap.add_argument("--width", type=int, default=4096)
@@ -71,12 +72,12 @@ def layer_work(cls, layer, rows, mb):
     mini-batch (backward kernels), mb = samples of a micro-batch (forward kernels)."""
     if layer.kind == "pool":
         return 0.0, 0.0
-    if layer.kind in ("ln", "attn", "res", "bn", "sub", "swap"):
+    if layer.kind in ("ln", "attn", "res", "bn", "sub", "swap", "avg"):
         return 0.0, 0.0
     # GEMM rows per sample (output pixels of a convolution) and input pixels per sample (more with stride 2)
     px = layer.ho * layer.wo if layer.kind == "conv" else getattr(layer, "tokens", 1)
     pin = layer.h * layer.w if layer.kind == "conv" else px
-    fin = (9 * layer.cin) if layer.kind == "conv" else layer.in_features
+    fin = (layer.k * layer.k * layer.cin) if layer.kind == "conv" else layer.in_features
     cin = layer.cin if layer.kind == "conv" else layer.in_features
     fout = layer.cout if layer.kind == "conv" else layer.out_features
     if cls == "fprop":                 # x, W in; act'(z), a out
@@ -114,6 +115,8 @@ def kernel_work(cls, w, s, needs_dx):
             if l.kind == "sub":        # forward: a quarter in, a quarter out; backward: a quarter in, all out
                 e = l.c * l.h * l.w
                 tot += 2.0 * rows * (e / 2) + 2.0 * rows * (e / 4 + e)
+            if l.kind == "avg":        # forward: all positions in, the means out; backward: their gradients in, all out
+                tot += 2 * 2.0 * rows * (l.c * l.tokens + l.c)
         return 0.0, tot
     if cls == "norm":                  # forward: x in, y out; backward: dy, x in, dx out
         tot = sum(2.0 * rows * l.out_dim() * 5 for l in layers if l.kind == "ln")
@@ -136,7 +139,7 @@ def kernel_work(cls, w, s, needs_dx):
         return 0.0, (2 * 2.0 * rows * np_prod(l.in_shape())) if l.kind in ("conv", "res", "ln", "bn") else 0.0
     flops = nbytes = 0.0
     for i, l in enumerate(layers):
-        if l.kind in ("pool", "ln", "attn", "res", "bn", "sub", "swap"):
+        if l.kind in ("pool", "ln", "attn", "res", "bn", "sub", "swap", "avg"):
             continue
         if cls == "dgrad" and i == 0 and not needs_dx:
             continue
@@ -244,14 +247,20 @@ def main():
         what = ("stage 0 (conv3-64, conv3-64, pool, conv3-128, conv3-128, pool; ReLU) of the 4-stage VGG-16-style "
                 "net on 32x32x3 images")
     elif args.workload == "bneck":
-        w = W.resnet_middle_stages(mb=args.mb or 128, n=args.n or 4)
         s = 2 if args.stage is None else args.stage
-        if s not in (1, 2):
-            sys.exit("bench.py: the bneck workload describes stages 1 (conv3_x) and 2 (conv4_x) only")
-        what = ("stage 2 (the conv4_x group: first bottleneck 512 -> 1024 channels with the 3x3 at stride 2, 8x8 -> 4x4 "
-                "feature maps, and a projection shortcut, then five identity bottlenecks 1024-256-256-1024" if s == 2 else
-                "stage 1 (the conv3_x group: first bottleneck 256 -> 512 channels with the 3x3 at stride 2, 16x16 -> 8x8 "
-                "feature maps, and a projection shortcut, then three identity bottlenecks 512-128-128-512")
+        if s not in (0, 1, 2, 3):
+            sys.exit("bench.py: the bneck workload has stages 0 .. 3")
+        w = (W.resnet_middle_stages if s in (1, 2) else W.resnet_stages)(mb=args.mb or 128, n=args.n or 4)
+        what = {0: "stage 0 (7x7 stride-2 stem 3 -> 64 channels, batch normalisation, ReLU, 2x2 max pooling, then the "
+                   "conv2_x group on 16x16 maps: a projection bottleneck 64 -> 256 and two identity bottlenecks "
+                   "256-64-64-256",
+                1: "stage 1 (the conv3_x group: first bottleneck 256 -> 512 channels with the 3x3 at stride 2, 16x16 -> 8x8 "
+                   "feature maps, and a projection shortcut, then three identity bottlenecks 512-128-128-512",
+                2: "stage 2 (the conv4_x group: first bottleneck 512 -> 1024 channels with the 3x3 at stride 2, 8x8 -> 4x4 "
+                   "feature maps, and a projection shortcut, then five identity bottlenecks 1024-256-256-1024",
+                3: "stage 3 (the conv5_x group: first bottleneck 1024 -> 2048 channels with the 3x3 at stride 2, 4x4 -> 2x2 "
+                   "feature maps, and a projection shortcut, then two identity bottlenecks 2048-512-512-2048, global "
+                   "average pooling and the classifier 2048 -> 200"}[s]
         what += ("; batch normalisation per micro-batch, ReLU) of the 4-stage ResNet-50-style net on 64x64x3 images")
     else:
         w = W.transformer_stage(layers=args.blocks, mb=args.mb or 8, n=args.n or 4)

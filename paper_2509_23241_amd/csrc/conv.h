@@ -69,4 +69,12 @@ hipError_t conv_c8_fprop(hipStream_t s, int imgs, int H, int W, int cin, int cou
 hipError_t conv_c8_wgrad(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* dz, const uint16_t* x8,
                          float* gW, float* partial, const uint16_t* zeros);
 
+// The 7x7 stride-2 pad-3 first layer (cin <= 8, bf16) on the same padded copy; H, W: the input image.
+bool conv_stem_supported(int imgs, int H, int W, int cin, int cout);
+int conv_stem_wgrad_splits(int out_pixels, int cout);
+hipError_t conv_stem_fprop(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* x8, const uint16_t* wgt,
+                           const float* bias, int act, uint16_t* d_out, uint16_t* a_out, const uint16_t* zeros);
+hipError_t conv_stem_wgrad(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* dz, const uint16_t* x8,
+                           float* gW, float* partial, const uint16_t* zeros);
+
 }  // namespace tp

@@ -360,6 +360,7 @@ int conv_wgrad_splits(int pixels, int cin, int cout, int ksize) {
 size_t conv_wgrad_scratch_floats(int pixels, int cin, int cout, int ksize) {
   int splits = conv_wgrad_splits(pixels, cin, cout, ksize);
   if (ksize == 3) splits = std::max(splits, conv_mfma_wgrad_max_splits(pixels, cin, cout));
+  if (ksize == 7 && cin <= 8 && cout % 64 == 0) splits = std::max(splits, conv_stem_wgrad_splits(pixels, cout));
   return (size_t)splits * cout * ksize * ksize * cin;
 }
 

@@ -803,6 +803,216 @@ __global__ __launch_bounds__(256) void conv_c8_wgrad_kernel(int H, int W, int lw
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// The same for an R x R kernel at stride S (the 7x7 stride-2 stem of a ResNet-style net), pad (R-1)/2
+// ------------------------------------------------------------------------------------------------
+// H, W: input image; the output is (H/S) x (W/S).  A tile of BM output pixels is BM/Wo whole output rows of one
+// image; its patch holds the S*(BM/Wo - 1) + R input rows they read, W + R - 1 pixels each (pad included), as
+// [pixel][8 channel slots], plus one zero pixel.  R*R taps are (R*R + 1)/2 k steps of two taps; the weights of 64
+// output channels, laid out [tap][channel][8 slots], are too many for registers (25 steps x 2 fragments) and sit
+// in LDS behind the patch.
+template <int R, int S>
+struct C8S {
+  static constexpr int kTaps = R * R, kSteps = (kTaps + 1) / 2, kPad = (R - 1) / 2;
+  static constexpr int kWeightBytes = 2 * kSteps * 64 * 16;
+  __host__ __device__ static int patch_cols(int W) { return W + R - 1; }
+  __host__ __device__ static int patch_rows(int BM, int Wo) { return S * (BM / Wo - 1) + R; }
+  __host__ __device__ static int patch_bytes(int BM, int W) {
+    return (((patch_rows(BM, W / S) * patch_cols(W) + 1) * 16 + 1023) / 1024) * 1024;
+  }
+};
+
+// p0: first output pixel of the tile (a multiple of the output row length, inside one image)
+template <int R, int S, int BM, int NW>
+__device__ __forceinline__ void issue_patch_c8s(const uint16_t* x8, const uint16_t* zeros, int H, int W, int lwo, uint32_t lds_patch,
+                                                int p0, int wave, int lane) {
+  using G = C8S<R, S>;
+  const int Wo = W / S, Ho = H / S;
+  const int PC = G::patch_cols(W), NPIX = G::patch_rows(BM, Wo) * PC;
+  const int img = p0 / (Ho * Wo), orow0 = (p0 - img * Ho * Wo) >> lwo;
+  const int instrs = G::patch_bytes(BM, W) / 1024;
+  for (int i = wave; i < instrs; i += NW) {
+    const int pp = i * 64 + lane;
+    const int pr = pp / PC, pc = pp - pr * PC;
+    const int h = S * orow0 - G::kPad + pr, w = pc - G::kPad;
+    const bool valid = pp < NPIX && (unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W;
+    const uint16_t* ptr = valid ? x8 + ((((long)img * H + h) * W + w) << 3) : zeros;
+    dma16_addr(lds_patch + i * 1024, ptr);
+  }
+}
+
+// out[p][co0 .. co0+63]: 256 output pixels per workgroup, 4 waves x (64 pixels x 64 channels)
+template <int R, int S>
+__global__ __launch_bounds__(256) void conv_c8s_fprop_kernel(int P, int H, int W, int lwo, int cin, int cout,
+                                                            const uint16_t* __restrict__ x8, const uint16_t* __restrict__ zeros,
+                                                            const uint16_t* __restrict__ wgt, EpiFprop epi) {
+  using G = C8S<R, S>;
+  constexpr int BM = 256, KT = G::kTaps, KS = G::kSteps;
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds_raw[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * 64;
+  const int Wo = W / S;
+  const int PC = G::patch_cols(W), NPIX = G::patch_rows(BM, Wo) * PC;
+  const int pbytes = G::patch_bytes(BM, W);
+  issue_patch_c8s<R, S, BM, 4>(x8, zeros, H, W, lwo, lds_addr_of(lds_raw), m0, wave, lane);
+
+  // weights -> LDS: entry (tap, channel) = 8 slots, channels >= cin and taps >= R*R zero.  Lanes 8 apart take
+  // neighbouring taps of one channel (consecutive in memory), lanes 1 apart neighbouring channels (consecutive in LDS).
+  uint16_t* wl = lds_raw + pbytes / 2;
+  for (int e = threadIdx.x; e < 64 * 8 * ((2 * KS + 7) / 8); e += 256) {
+    const int c = (e & 7) + 8 * ((e >> 6) & 7), tap = ((e >> 3) & 7) + 8 * (e >> 9);
+    if (tap >= 2 * KS) continue;
+    shortx8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (tap < KT && n0 + c < cout) {
+      const uint16_t* wp = wgt + ((size_t)(n0 + c) * KT + tap) * cin;
+#pragma unroll
+      for (int ch = 0; ch < kC8; ++ch)
+        if (ch < cin) v[ch] = (short)wp[ch];
+    }
+    *reinterpret_cast<shortx8*>(wl + (tap * 64 + c) * 8) = v;
+  }
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  const int khalf = lane >> 5;
+  int ppc[2];  // patch position of tap (0, 0) of the lane's output pixel
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int q = wave * 64 + i * 32 + (lane & 31);
+    ppc[i] = S * (q >> lwo) * PC + S * (q & (Wo - 1));
+  }
+  wait_vmcnt<0>();
+  __syncthreads();
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) {
+    const int tap = 2 * kk + khalf;
+    const int tapoff = (tap / R) * PC + tap % R;
+    bf16x8 af[2], bfr[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int pp = tap < KT ? ppc[i] + tapoff : NPIX;  // the zero pixel behind the patch
+      af[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(lds_raw + pp * 8));
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      bfr[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(wl + (tap * 64 + j * 32 + (lane & 31)) * 8));
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) acc[i][j] = mma<true>(af[i], bfr[j], acc[i][j]);
+  }
+  __syncthreads();  // patch and weights are dead: their LDS is reused for the output tiles
+  if (n0 + 64 <= cout && (cout & 7) == 0) {
+    float* wave_lds = reinterpret_cast<float*>(lds_raw) + wave * (wave_epilogue_bytes<2, 2>() / 4);
+    store_tiles_coalesced<2, 2>(acc, epi, m0 + wave * 64, n0, lane, wave_lds);
+  } else {
+    store_tiles<2, 2>(acc, epi, m0 + wave * 64, n0, P, cout, lane);
+  }
+}
+
+// partial dW[co0..co0+63][tap][c] over the output-pixel tiles split, split + splits, ...; 128 output pixels per tile.
+// The columns (tap, channel slot) are NT = ceil(R*R*8 / 32) tiles of 32 (4 taps each); waves 0, 1 (output channels
+// 0..31, 32..63) take the first half of them, waves 2, 3 the rest.
+template <int R, int S>
+__global__ __launch_bounds__(256) void conv_c8s_wgrad_kernel(int H, int W, int lwo, int cin, int cout, int px_tiles,
+                                                            const uint16_t* __restrict__ x8, const uint16_t* __restrict__ zeros,
+                                                            const uint16_t* __restrict__ dz, float* __restrict__ out) {
+  using G = C8S<R, S>;
+  constexpr int BM = 128, NW = 4, KT = G::kTaps;
+  constexpr int NT = (KT * 8 + 31) / 32, TPW = (NT + 1) / 2;
+  using DZ = ColDma<64, NW>;
+  constexpr int kDzInstr = BM * 8 / 64 / NW;
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds_raw[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int cob = blockIdx.x, split = blockIdx.y, splits = gridDim.y;
+  const int Wo = W / S;
+  const int pbytes = G::patch_bytes(BM, W);
+  const int buf_bytes = pbytes + BM * 128;
+  const uint32_t lds_base = lds_addr_of(lds_raw);
+  const int PC = G::patch_cols(W), NPIX = G::patch_rows(BM, Wo) * PC;
+  const int rb_co = (wave & 1) * 32;
+  const int ntile0 = (wave >> 1) * TPW, ntiles = min(TPW, NT - ntile0);
+
+  floatx16 acc[TPW];
+#pragma unroll
+  for (int t = 0; t < TPW; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+  uint32_t dzoff[kDzInstr];
+#pragma unroll
+  for (int i = 0; i < kDzInstr; ++i) {
+    const int flat = 64 * (wave + NW * i) + lane;
+    const int k = flat >> 3, c = (flat & 7) ^ DZ::swz(k);
+    dzoff[i] = (uint32_t)(((size_t)k * cout + cob * 64 + c * 8) * 2);
+  }
+  auto issue_tile = [&](int tile, int buf) {
+    const uint32_t dst = lds_base + buf * buf_bytes;
+    issue_patch_c8s<R, S, BM, NW>(x8, zeros, H, W, lwo, dst, tile * BM, wave, lane);
+    const uint16_t* src = dz + (size_t)tile * BM * cout;
+#pragma unroll
+    for (int i = 0; i < kDzInstr; ++i) dma16(dst + pbytes + (wave + NW * i) * 1024, src, dzoff[i]);
+  };
+  if (split < px_tiles) issue_tile(split, 0);
+  int buf = 0;
+  const int g = lane >> 4, s = lane & 15;
+  // the lane's 4 columns (tap, slots 0..3 or 4..7) in each of its column tiles: patch offset of the tap, or -1
+  int tapoff[TPW], slot4[TPW];
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) {
+    const int col = (ntile0 + t) * 32 + 16 * (g & 1) + 4 * (s & 3);
+    const int tap = col >> 3;
+    tapoff[t] = tap < KT ? (tap / R) * PC + tap % R : -1;
+    slot4[t] = col & 4;
+  }
+  for (int tile = split; tile < px_tiles; tile += splits) {
+    wait_vmcnt<0>();
+    lds_barrier();
+    if (tile + splits < px_tiles) issue_tile(tile + splits, buf ^ 1);
+    const uint16_t* lp = lds_raw + buf * (buf_bytes / 2);
+    const uint16_t* ldz = lp + pbytes / 2;
+#pragma unroll 2
+    for (int kk = 0; kk < BM / 16; ++kk) {
+      const bf16x8 a = DZ::frag(ldz, rb_co, kk, lane);
+      const int kq = kk * 16 + 8 * (g >> 1) + (s >> 2);              // output pixel of the tile; kq + 4 lies S*4 input
+      const int ppc = S * (kq >> lwo) * PC + S * (kq & (Wo - 1));    // pixels to the right in the same row (Wo >= 8)
+#pragma unroll
+      for (int t = 0; t < TPW; ++t) {
+        if (t < ntiles) {
+          typedef __attribute__((address_space(3))) shortx4* lds_ptr;
+          const uint16_t* p0 = lp + (tapoff[t] >= 0 ? ppc + tapoff[t] : NPIX) * 8 + slot4[t];
+          const uint16_t* p1 = lp + (tapoff[t] >= 0 ? ppc + 4 * S + tapoff[t] : NPIX) * 8 + slot4[t];
+          const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0));
+          const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p1));
+          const shortx8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          acc[t] = mma<false>(a, __builtin_bit_cast(bf16x8, v), acc[t]);
+        }
+      }
+    }
+    buf ^= 1;
+  }
+  // accumulator element r: row co = rb_co + 8*(r/4) + 4*(lane/32) + r%4, column lane%32 of the tile
+  float* o = out + (size_t)split * cout * KT * cin;
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) {
+    if (t >= ntiles) continue;
+    const int col = (ntile0 + t) * 32 + (lane & 31);
+    const int tap = col >> 3, c = col & 7;
+    if (tap >= KT || c >= cin) continue;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int co = cob * 64 + rb_co + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      if (co < cout) o[((size_t)co * KT + tap) * cin + c] = acc[t][r];
+    }
+  }
+}
+
 // x[P][cin] -> x8[P][8], channels >= cin zero
 __global__ __launch_bounds__(256) void pad_channels_kernel(size_t pixels, int cin, const uint16_t* __restrict__ x,
                                                            uint16_t* __restrict__ x8) {
@@ -1050,6 +1260,56 @@ hipError_t conv_c8_wgrad(hipStream_t s, int imgs, int H, int W, int cin, int cou
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || splits == 1) return err;
   return launch_sum_partials(s, (size_t)cout * 9 * cin, splits, partial, gW);
+}
+
+// ---- the same for the 7x7 stride-2 stem ---------------------------------------------------------
+namespace {
+using Stem = C8S<7, 2>;
+inline size_t stem_fprop_lds(int W) {
+  return std::max<size_t>((size_t)Stem::patch_bytes(256, W) + Stem::kWeightBytes, 4 * wave_epilogue_bytes<2, 2>());
+}
+inline size_t stem_wgrad_lds(int W) { return 2 * ((size_t)Stem::patch_bytes(128, W) + 128 * 128); }
+}  // namespace
+
+bool conv_stem_supported(int imgs, int H, int W, int cin, int cout) {
+  if (!(pow2(H) && pow2(W) && H >= 2 && W >= 16)) return false;
+  const int Ho = H / 2, Wo = W / 2;
+  const long P = (long)imgs * H * W;
+  return cin >= 1 && cin <= kC8 && cout % 64 == 0 && 128 % Wo == 0 && (Ho * Wo) % 256 == 0 &&
+         stem_fprop_lds(W) <= (size_t)kMaxLds && stem_wgrad_lds(W) <= (size_t)kMaxLds && P * 16 < (1l << 31) &&
+         (P / 4) * cout * 2 < (1l << 31);
+}
+
+hipError_t conv_stem_fprop(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* x8, const uint16_t* wgt,
+                           const float* bias, int act, uint16_t* d_out, uint16_t* a_out, const uint16_t* zeros) {
+  if (!conv_stem_supported(imgs, H, W, cin, cout)) return hipErrorInvalidValue;
+  const int P = imgs * (H / 2) * (W / 2);
+  auto kernel = conv_c8s_fprop_kernel<7, 2>;
+  static hipError_t attr =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
+  if (attr != hipSuccess) return attr;
+  hipLaunchKernelGGL(kernel, dim3(P / 256, cout / 64), dim3(256), stem_fprop_lds(W), s, P, H, W, ilog2(W / 2), cin, cout, x8,
+                     zeros, wgt, EpiFprop{bias, d_out, a_out, act, cout});
+  return hipGetLastError();
+}
+
+int conv_stem_wgrad_splits(int out_pixels, int cout) { return std::max(1, std::min(out_pixels / 128, 512 / (cout / 64))); }
+
+hipError_t conv_stem_wgrad(hipStream_t s, int imgs, int H, int W, int cin, int cout, const uint16_t* dz, const uint16_t* x8,
+                           float* gW, float* partial, const uint16_t* zeros) {
+  if (!conv_stem_supported(imgs, H, W, cin, cout)) return hipErrorInvalidValue;
+  const int P = imgs * (H / 2) * (W / 2);
+  const int px_tiles = P / 128;
+  const int splits = conv_stem_wgrad_splits(P, cout);
+  auto kernel = conv_c8s_wgrad_kernel<7, 2>;
+  static hipError_t attr =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
+  if (attr != hipSuccess) return attr;
+  hipLaunchKernelGGL(kernel, dim3(cout / 64, splits), dim3(256), stem_wgrad_lds(W), s, H, W, ilog2(W / 2), cin, cout, px_tiles, x8,
+                     zeros, dz, splits > 1 ? partial : gW);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess || splits == 1) return err;
+  return launch_sum_partials(s, (size_t)cout * 49 * cin, splits, partial, gW);
 }
 
 }  // namespace tp

@@ -597,13 +597,14 @@ hipError_t mfma_dgrad(hipStream_t s, int M, int N, int K, const uint16_t* dz, co
 }
 
 // Ranges of the contraction (the rows of the mini-batch) a weight gradient is split into when its output has too
-// few tiles to fill the chip: whole 64-row k tiles, at least 8 per range, at most 8 ranges.
+// few tiles to fill the chip: whole 64-row k tiles, at least 8 per range, as many ranges as give every CU a
+// workgroup (a 64 x 64 gradient over the 131072 pixels of 16x16 maps is one tile and 2048 k tiles).
 int mfma_wgrad_splits(int M, int N, int K) {
   if (!dma_ok(N, K, M, N, K, true, true)) return 1;
   const int cfg = pick(N, K, M, N, K, true, true, g_cfg[2]);
   if (cfg != 10) return 1;  // larger tiles are only chosen when they already give 256 workgroups
   const long blocks = (long)((N + 63) / 64) * ((K + 63) / 64);
-  int s = (int)std::min<long>(8, 256 / std::max<long>(blocks, 1));
+  int s = (int)std::min<long>(256, 256 / std::max<long>(blocks, 1));
   while (s > 1 && (M % (DBK * s) != 0 || M / (DBK * s) < 8)) --s;
   return std::max(s, 1);
 }

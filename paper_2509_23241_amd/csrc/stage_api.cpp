@@ -328,9 +328,13 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
     } else {
       lp.z_off = UINT64_MAX;
     }
-    if (l == 0 && L.type == TP_LAYER_CONV2D && L.geom[2] == 3 && L.geom[3] == 1 && d->dtype == TP_BF16 &&
-        tp::conv_c8_supported((int)rows, L.geom[0], L.geom[1], L.in_features, L.out_features) &&
-        tp::conv_c8_supported(d->mb, L.geom[0], L.geom[1], L.in_features, L.out_features)) {
+    const bool c8_3x3 = L.geom[2] == 3 && L.geom[3] == 1 &&
+                        tp::conv_c8_supported((int)rows, L.geom[0], L.geom[1], L.in_features, L.out_features) &&
+                        tp::conv_c8_supported(d->mb, L.geom[0], L.geom[1], L.in_features, L.out_features);
+    const bool c8_stem = L.geom[2] == 7 && L.geom[3] == 2 &&
+                         tp::conv_stem_supported((int)rows, L.geom[0], L.geom[1], L.in_features, L.out_features) &&
+                         tp::conv_stem_supported(d->mb, L.geom[0], L.geom[1], L.in_features, L.out_features);
+    if (l == 0 && L.type == TP_LAYER_CONV2D && d->dtype == TP_BF16 && (c8_3x3 || c8_stem)) {
       lp.xpad_off = act;
       act += round_up(rows * L.geom[0] * L.geom[1] * 8 * p->elt_size, 256);
     }
@@ -799,9 +803,14 @@ int forward_impl(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_de
         HIP_TRY(tp::conv_c8_pad(st->stream, d.mb * px, lp.d.in_features, (const uint16_t*)x_in, x8));
       }
       ProfScope ps(st, TP_K_FPROP);
-      HIP_TRY(tp::conv_c8_fprop(st->stream, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, lp.d.out_features, x8,
-                                (const uint16_t*)(wcopy + lp.w_off * es), master + lp.b_off, lp.d.act, (uint16_t*)z_out,
-                                (uint16_t*)a_out, (const uint16_t*)st->zeros()));
+      if (lp.d.geom[2] == 7)
+        HIP_TRY(tp::conv_stem_fprop(st->stream, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, lp.d.out_features, x8,
+                                    (const uint16_t*)(wcopy + lp.w_off * es), master + lp.b_off, lp.d.act, (uint16_t*)z_out,
+                                    (uint16_t*)a_out, (const uint16_t*)st->zeros()));
+      else
+        HIP_TRY(tp::conv_c8_fprop(st->stream, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, lp.d.out_features, x8,
+                                  (const uint16_t*)(wcopy + lp.w_off * es), master + lp.b_off, lp.d.act, (uint16_t*)z_out,
+                                  (uint16_t*)a_out, (const uint16_t*)st->zeros()));
       continue;
     }
     if (need_copy) {
@@ -1223,6 +1232,10 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
         if (lp.d.type == TP_LAYER_DENSE)
           HIP_TRY(tp::launch_wgrad(st->stream, d.dtype, grad_rows, lp.d.out_features, lp.d.in_features, dz, aslot + lp.x_off,
                                    g + lp.w_off, part));
+        else if (lp.xpad_off != UINT64_MAX && lp.d.geom[2] == 7)
+          HIP_TRY(tp::conv_stem_wgrad(st->stream, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, lp.d.out_features,
+                                      (const uint16_t*)dz, (const uint16_t*)(aslot + lp.xpad_off), g + lp.w_off, part,
+                                      (const uint16_t*)st->zeros()));
         else if (lp.xpad_off != UINT64_MAX)
           HIP_TRY(tp::conv_c8_wgrad(st->stream, rows, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, lp.d.out_features,
                                     (const uint16_t*)dz, (const uint16_t*)(aslot + lp.xpad_off), g + lp.w_off, part,

@@ -26,6 +26,14 @@ def test_convolution_7x7_many_channels_bf16():
     print(_run_stage(specs, "conv_k7_wide_bf16", "bf16", mb=4, n=3))
 
 
+@pytest.mark.parametrize("h,w,cin,cout", [(32, 32, 3, 64), (64, 32, 3, 128), (32, 64, 5, 64), (16, 128, 1, 64)])
+def test_stem_convolution_on_the_matrix_cores_bf16(h, w, cin, cout):
+    # 7x7 stride 2 as the first layer of a stage on few input channels: the matrix-core kernels on the 8-slot padded
+    # copy of the input (forward, weight gradient); tiles of 256 / 128 output pixels are 16, 8, 4 or 2 output rows
+    specs = (W.Conv2d(cin, cout, h, w, "gelu", k=7, stride=2, pad=3), W.Dense(cout, 16, "none", tokens=(h // 2) * (w // 2)))
+    print(_run_stage(specs, f"stem_mfma_{h}x{w}_{cin}_{cout}", "bf16", mb=2, n=3, needs_dx=False))
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_average_pooling_then_classifier(dtype):
     specs = (W.Dense(8, 24, "gelu", tokens=6), W.AvgPool(24, 6), W.Dense(24, 10, "none"))
@@ -69,7 +77,7 @@ def test_small_head_stage(dtype):
 @pytest.mark.parametrize("act,fixed", [("gelu", False), ("relu", True)])
 def test_stem_stage_matrix_core_shapes_bf16(act, fixed):
     # 32x32x3 images, 64 channels behind the stem: the conv2_x group's 1x1 and 3x3 convolutions (64 -> 64 -> 256 on
-    # 8x8 maps) run on the matrix cores, the stem itself on the generic kernel
+    # 8x8 maps) and the stem run on the matrix cores
     specs = W.resnet_stem_stage(size=32, c=64, mid=64, cout=256, blocks=1, act=act)
     print(act, _run_stage(specs, f"stem_mfma_{act}", "bf16", mb=8, n=2, depth=4, minibatches=3, needs_dx=False,
                           fixed_masks=fixed, mean_loss_dy=True, lr=0.01, storage_floor=True))
