@@ -86,6 +86,40 @@ def test_conv3_group_first_block_full_geometry():
     print(f"{time.time() - t0:.1f} s", worst)
 
 
+@pytest.mark.timeout(1200)
+@pytest.mark.parametrize("act,fixed", [("gelu", False), ("relu", True)])
+def test_stem_stage_full_geometry(act, fixed):
+    # stage 0 of the ResNet-style net as bench.py --workload bneck --stage 0 runs it: 64x64x3 images, 7x7 stride-2 stem
+    # to 64 channels (matrix-core kernels on the padded input), batch normalisation over 131072 positions per
+    # micro-batch, pooling to 16x16, then the first bottleneck of conv2_x with its projection shortcut and one
+    # identity bottleneck (the second one repeats it), micro-batch 128 x 4, no input gradient.  The gradients of
+    # the stem's normalisation are sums of terms that nearly cancel; every tensor is held to the larger of the
+    # tolerance and what bf16 storage does to it by the oracle's own account
+    w = W.resnet_stages()
+    specs = W.resnet_stem_stage(64, 64, 64, 256, 1, act)
+    t0 = time.time()
+    n = w.n if act == "gelu" else 2      # the second form on half the mini-batch: the oracle's time goes with it
+    worst = _run_stage(specs, f"stem_full_{act}", "bf16", mb=w.mb, n=n, policy="convex", depth=2, minibatches=2,
+                       needs_dx=False, lr=w.lr, lam=w.lam, mean_loss_dy=True, fixed_masks=fixed, storage_floor=True)
+    print(f"{time.time() - t0:.1f} s", {k: v for k, v in worst.items() if "[" not in k})
+
+
+@pytest.mark.timeout(1200)
+@pytest.mark.parametrize("act", ["gelu", "relu"])
+def test_head_stage_full_geometry(act):
+    # stage 3 as bench.py --workload bneck --stage 3 runs it, whole: conv5_x ([4, 4, 1024] -> [2, 2, 2048], 512 middle
+    # channels: strided bottleneck with projection shortcut and two identity bottlenecks, 3x3 convolutions on 2x2
+    # maps), global average pooling, classifier 2048 -> 200; micro-batch 128 x 4.  With GELU every tensor is held to
+    # the larger of the tolerance and the oracle's own bf16-storage distance; with the net's ReLUs (centred
+    # pre-activations) the differing mask decisions are counted and bound the gradient tolerance
+    w = W.resnet_stages()
+    specs = W.resnet_head_stage(2048, 512, 2, 2, 200, act)
+    t0 = time.time()
+    worst = _run_stage(specs, f"head_full_{act}", "bf16", mb=w.mb, n=w.n, policy="convex", depth=2, minibatches=2,
+                       needs_dx=True, lr=w.lr, lam=w.lam, mean_loss_dy=True, stage_index=2, storage_floor=(act == "gelu"))
+    print(f"{time.time() - t0:.1f} s", {k: v for k, v in worst.items() if "[" not in k})
+
+
 @pytest.mark.timeout(1500)
 def test_transformer_block_full_geometry_sampled_sequences():
     """One of the four identical blocks of the transformer stage at its real geometry (d_model 2048, 16 heads
