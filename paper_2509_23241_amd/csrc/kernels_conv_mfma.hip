@@ -114,6 +114,67 @@ struct RowGather {
   static __device__ __forceinline__ bf16x8 frag(const uint16_t* lds, int rbase, int kk, int lane) {
     return RowDma<R, NW>::frag(lds, rbase, kk, lane);
   }
+  static __device__ __forceinline__ int tiles_of(const Desc&, int /*batch*/, int KT) { return KT; }
+};
+
+// The 3x3 input gradient at stride 2, one parity class of input pixels per batch.  An input pixel (h, w) gets a
+// contribution from tap (kh, kw) only where h - kh + 1 and w - kw + 1 are even: for even h that is kh = 1, for odd
+// h kh = 0 and 2, likewise along w, so the four classes (h & 1, w & 1) have 1, 2, 2 and 4 taps -- 9 tap-products in
+// all where rows running over every input pixel and all nine taps multiply zeros three times out of four.
+// Class of a batch: the one with the most taps first (its workgroups run longest).
+__host__ __device__ __forceinline__ int s2_class(int batch) { return 3 - batch; }                  // 2*(h&1) + (w&1)
+__host__ __device__ __forceinline__ int s2_class_taps(int cls) { return (1 + (cls >> 1)) * (1 + (cls & 1)); }
+__device__ __forceinline__ int s2_class_tap(int cls, int ti) {  // ti-th tap of the class, as 3*kh + kw
+  const int ph = cls >> 1, pw = cls & 1;
+  const int kh = ph ? 2 * (ti >> pw) : 1, kw = pw ? 2 * (ti & 1) : 1;
+  return 3 * kh + kw;
+}
+
+// Rows: the pixels (img, h2, w2) of one class on the (H/2) x (W/2) grid, i.e. input pixel (2 h2 + ph, 2 w2 + pw);
+// the source is dz on that same grid at (h2 + (ph - kh + 1)/2, w2 + (pw - kw + 1)/2), zero past its edge.
+template <int R, int NW>
+struct RowGatherS2 {
+  using Desc = GatherDesc;  // P, H, W, lw: rows and grid of one class; SH, SW: the dz grid (the same size)
+  static constexpr int kPerWave = R / 8 / NW;
+  static constexpr int kBytes = R * DBK * 2;
+  static_assert((R / 8) % NW == 0, "rows do not divide among the waves");
+  Desc d;
+  int cblocks, cls;
+  uint32_t img_off[kPerWave];  // byte offset of (image, chunk) inside base
+  int hw[kPerWave];            // h2 << 16 | w2 of the lane's pixel
+  uint32_t zoff;
+
+  __device__ __forceinline__ void init(const Desc& desc, int r0, int wave, int lane, int batch) {
+    d = desc;
+    cblocks = d.C / DBK;
+    cls = s2_class(batch);
+    zoff = (lane & 7) * 16;
+#pragma unroll
+    for (int t = 0; t < kPerWave; ++t) {
+      const int r = 8 * (wave + NW * t) + (lane >> 3);
+      const int c = (lane & 7) ^ ((r >> 1) & 7);
+      const int p = min(r0 + r, d.P - 1);  // rows past the end repeat the last pixel: never stored
+      hw[t] = (((p >> d.lw) & (d.H - 1)) << 16) | (p & (d.W - 1));
+      const int img = p / (d.H * d.W);
+      img_off[t] = (uint32_t)(((size_t)img * d.SH * d.SW * d.C + c * 8) * 2);
+    }
+  }
+  __device__ __forceinline__ void issue_one(int t, uint32_t lds_stage, int tile, int wave) const {
+    const int ti = tile / cblocks, c0 = (tile - ti * cblocks) * DBK;  // wave uniform
+    const int tap = s2_class_tap(cls, ti);
+    const int kh = tap / 3, kw = tap - 3 * kh;
+    const int sh = (hw[t] >> 16) + (((cls >> 1) - kh + 1) >> 1), sw = (hw[t] & 0xffff) + (((cls & 1) - kw + 1) >> 1);
+    const bool valid = sh < d.SH && sw < d.SW;
+    const long off = (long)img_off[t] + ((long)(sh * d.SW + sw) * d.C + c0) * 2;
+    const char* src = valid ? (const char*)d.base + off : (const char*)d.zeros + zoff;
+    dma16_addr(lds_stage + (wave + NW * t) * 1024, src);
+  }
+  static __device__ __forceinline__ bf16x8 frag(const uint16_t* lds, int rbase, int kk, int lane) {
+    return RowDma<R, NW>::frag(lds, rbase, kk, lane);
+  }
+  static __device__ __forceinline__ int tiles_of(const Desc& desc, int batch, int /*KT*/) {
+    return s2_class_taps(s2_class(batch)) * (desc.C / DBK);
+  }
 };
 
 // k-strided gathered operand: stage [64 pixels][R channels], one tap per workgroup (batch).
@@ -164,6 +225,7 @@ struct ColGather {
   static __device__ __forceinline__ bf16x8 frag(const uint16_t* lds, int rbase, int kk, int lane) {
     return ColDma<R, NW>::frag(lds, rbase, kk, lane);
   }
+  static __device__ __forceinline__ int tiles_of(const Desc&, int /*batch*/, int KT) { return KT; }
 };
 
 // Operands that lie in memory the way the dense kernels read them; the source of k tile `tile`
@@ -192,6 +254,32 @@ struct Plain {
   static __device__ __forceinline__ bf16x8 frag(const uint16_t* lds, int rbase, int kk, int lane) {
     return Impl::frag(lds, rbase, kk, lane);
   }
+  static __device__ __forceinline__ int tiles_of(const Desc&, int /*batch*/, int KT) { return KT; }
+};
+
+// The weights of the stride-2 input gradient by parity class: k tile -> (ti-th tap of the batch's class, block of 64
+// output channels); the source of tile `tile` is base + (tile % inner) * step_in + tap * step_out.
+template <int R, int NW>
+struct PlainS2 {
+  using Desc = PlainDesc;
+  using Impl = ColDma<R, NW>;
+  static constexpr int kPerWave = Impl::kPerWave;
+  static constexpr int kBytes = Impl::kBytes;
+  Impl impl;
+  Desc d;
+  int cls;
+  __device__ __forceinline__ void init(const Desc& desc, int r0, int wave, int lane, int batch) {
+    d = desc;
+    cls = s2_class(batch);
+    impl.init(d.ld, r0, d.rows, wave, lane);
+  }
+  __device__ __forceinline__ void issue_one(int t, uint32_t lds_stage, int tile, int wave) const {
+    const int ti = tile / d.inner;
+    impl.issue_one(t, lds_stage, d.base + (tile - ti * d.inner) * d.step_in + s2_class_tap(cls, ti) * d.step_out, wave);
+  }
+  static __device__ __forceinline__ bf16x8 frag(const uint16_t* lds, int rbase, int kk, int lane) {
+    return Impl::frag(lds, rbase, kk, lane);
+  }
 };
 
 // fp32 partial tile of dW for one tap and one pixel range
@@ -203,8 +291,32 @@ struct EpiWgradConv {
     return EpiWgrad{partial + (size_t)split * cout * 9 * cin + (size_t)tap * cin, 9 * cin};
   }
 };
+// The input gradient of one parity class: row m of the class is input pixel (img, 2 h2 + ph, 2 w2 + pw)
+struct EpiDgradClass {
+  EpiDgrad e;
+  int H, W, lw2, lh2, ph, pw;  // input image, log2 of its half sizes
+  static constexpr bool kSwap = true;
+  __device__ __forceinline__ int pixel(int m) const {
+    const int w2 = m & ((W >> 1) - 1), h2 = (m >> lw2) & ((H >> 1) - 1), img = m >> (lw2 + lh2);
+    return (img * H + 2 * h2 + ph) * W + 2 * w2 + pw;
+  }
+  __device__ __forceinline__ void row8(int m, int n, float (&v)[8]) const { e.row8(pixel(m), n, v); }
+  __device__ __forceinline__ void quad(int m, int n, int count, float v0, float v1, float v2, float v3) const {
+    e.quad(pixel(m), n, count, v0, v1, v2, v3);
+  }
+};
+struct EpiDgradS2 {
+  EpiDgrad e;
+  int H, W, lw2, lh2;
+  static constexpr bool kSwap = true;
+  __device__ __forceinline__ EpiDgradClass at(int batch) const {
+    const int cls = s2_class(batch);
+    return EpiDgradClass{e, H, W, lw2, lh2, cls >> 1, cls & 1};
+  }
+};
 template <class E>
 __device__ __forceinline__ const E& epi_at(const E& e, int, int) { return e; }
+__device__ __forceinline__ EpiDgradClass epi_at(const EpiDgradS2& e, int batch, int) { return e.at(batch); }
 __device__ __forceinline__ EpiWgrad epi_at(const EpiWgradConv& e, int tap, int split) { return e.at(tap, split); }
 
 // grid = (output tiles, batches, splits); every workgroup runs KT k tiles starting at split*KT.
@@ -238,6 +350,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KG) void conv_bf16_dma_kernel(int 
   map.get(blockIdx.x, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int batch = blockIdx.y, split = blockIdx.z;
+  KT = AL::tiles_of(ad, batch, KT);  // the same for every batch but where batches differ in their taps
   const int tile0 = split * KT;
   const int KTg = KT / KG;  // k tiles of this group: tile0 + kg, tile0 + kg + KG, ...
   const uint32_t lds_base = lds_addr_of(lds_raw) + kg * (NS * kStageBytes);
@@ -1156,9 +1269,17 @@ hipError_t conv_mfma_dgrad(hipStream_t s, int imgs, int H, int W, int stride, in
   // k tile -> (tap, block of 64 output channels): rows co0.. of W_b, columns tap*Cin..
   PlainDesc bd{wb, 9 * cin, cin, cout / DBK, (long)DBK * 9 * cin, cin};
   EpiDgrad e{d_prev, out, cin, relu_mask};
-  if (stride == 2) {  // rows: input pixels, source: dz on the (H/2) x (W/2) grid; taps of the wrong parity read zeros
-    GatherDesc ad{dz, zeros, P, H, W, ilog2(W), cout, H / 2, W / 2};
-    return launch_gather_rows<true, 2>(s, P, cin, 9 * cout / DBK, ad, bd, e);
+  if (stride == 2) {  // one batch of workgroups per parity class of input pixels, each with its own taps
+    const int H2 = H / 2, W2 = W / 2, Pc = imgs * H2 * W2;
+    GatherDesc ad{dz, zeros, Pc, H2, W2, ilog2(W2), cout, H2, W2};
+    EpiDgradS2 e2{e, H, W, ilog2(W2), ilog2(H2)};
+    const int KT = 4 * cout / DBK;  // of the class with four taps; the kernel takes every class's own count
+    const long rows128 = (Pc + 127) / 128;
+    if (cin % 128 == 0 && 4 * rows128 * (cin / 128) >= 256)
+      return launch_conv<128, 128, 3, RowGatherS2<128, 4>, PlainS2<128, 4>>(s, Pc, cin, KT, 4, 1, ad, bd, e2);
+    if (4 * rows128 * ((cin + 63) / 64) >= 256)
+      return launch_conv<128, 64, 4, RowGatherS2<128, 4>, PlainS2<64, 4>>(s, Pc, cin, KT, 4, 1, ad, bd, e2);
+    return launch_conv<64, 64, 4, RowGatherS2<64, 4>, PlainS2<64, 4>>(s, Pc, cin, KT, 4, 1, ad, bd, e2);
   }
   {
     const PatchDesc pd{dz, zeros, H, W, ilog2(W), cout, 0, cout / 8, 0};
