@@ -59,6 +59,9 @@ def parse():
     ap.add_argument("--n", type=int, default=None, help="micro-batches per mini-batch (default 8 mlp, 4 vgg, 4 tfm)")
     ap.add_argument("--repeats", type=int, default=5,
                     help="timed blocks of --steps steps each; the line reports the median block (and all of them)")
+    ap.add_argument("--forward-streams", type=int, default=2, choices=[1, 2],
+                    help="2: the forward passes of odd micro-batches run on a second stream beside the even ones "
+                         "(stages without batch-normalisation and attention layers; elsewhere one stream is used)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-minibatches", type=int, default=3)
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
@@ -273,8 +276,11 @@ def main():
     torch.cuda.set_device(dev)
     depth = w.K - s
     layers = [layer_tuple(l) for l in w.stages[s]]
+    # micro-batch forwards on two streams where the stage's forward kernels share no scratch memory
+    two_streams = args.forward_streams == 2 and not any(l.kind in ("bn", "attn") for l in w.stages[s])
     st = GpuStage(layers, W.init_params(w, s), dtype=w.dtype, mb=w.mb, n=w.n, stage_index=s, num_stages=w.K,
-                  policy=args.policy, lam=w.lam, lr=w.lr, momentum=w.momentum, needs_dx=(s > 0), device=dev)
+                  policy=args.policy, lam=w.lam, lr=w.lr, momentum=w.momentum, needs_dx=(s > 0), device=dev,
+                  forward_stream=two_streams)
     tdt = st.tdtype
     rows = w.n * w.mb
     nbuf = 2                                       # distinct synthetic mini-batches, resident in HBM
@@ -389,8 +395,10 @@ def main():
         "config": {"workload": f"{what}: bf16 activations, "
                                f"fp32 master weights, micro-batch {w.mb} x {w.n}, policy {args.policy}, "
                                f"lambda {w.lam}, staleness {delta_steady}, one step = 1 backward + 1 fused update/blend "
-                               f"+ {w.n} micro-batch forwards",
-                   "params_per_stage": int(st.P), "ring_slots": int(st.C)},
+                               f"+ {w.n} micro-batch forwards"
+                               + (" (odd micro-batches on a second stream beside the even ones; the per-kernel "
+                                  "durations below are taken with all of them on one stream)" if two_streams else ""),
+                   "params_per_stage": int(st.P), "ring_slots": int(st.C), "forward_streams": 2 if two_streams else 1},
         "roofline": roofline,
         "kernels": kernels,
         "mfma_util_pct": {c: round(100 * kernels[c]["tflops"] / PEAK_BF16_TFLOPS, 2)

@@ -26,7 +26,8 @@
  *   - The caller owns every device buffer (ring arena, momentum, gradient, compute
  *     copies, activation workspace, scratch) and passes them in tp_buffers; sizes come
  *     from stage_workspace_query.  The library allocates no device memory, creates no
- *     stream, and enqueues work only on the stream given to stage_init.  Buffers must
+ *     stream, and enqueues work only on the stream given to stage_init (and on the one given
+ *     to stage_set_forward_stream, if any).  Buffers must
  *     stay alive, and must not be written by the caller, until stage_destroy -- except
  *     ring slot 0, which the caller fills with the initial weights (version 0), and the
  *     momentum buffer, which the caller zeroes, both before stage_init.
@@ -37,7 +38,7 @@
  *     incoming/outgoing gradients and the compute copies of the weights are bfloat16,
  *     while ring, momentum and gradient stay fp32; in TP_F32 mode everything is fp32.
  *   - Parameter arena: per layer that has parameters the weight tensor (dense W[out x in],
- *     conv W[Cout][3][3][Cin]) followed by the bias b[out]; each tensor starts at a multiple of
+ *     conv W[Cout][k][k][Cin]) followed by the bias b[out]; each tensor starts at a multiple of
  *     64 elements (offsets are reported by stage_workspace_query; padding elements are zero
  *     and stay zero).  Activations of conv/pool layers are NHWC; a row of a mini-batch is one
  *     sample with all its values.
@@ -232,6 +233,24 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
  * not hold the version. */
 int stage_forward_on(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, uint64_t version, const void* x_dev,
                      void* y_dev);
+
+/* Optional: a second stream of the caller's for the forward passes (a hipStream_t of default priority that is
+ * neither NULL nor the stage's own and does not synchronise with it implicitly; enable = 0 takes it away again).
+ * The micro-batch forward passes of a mini-batch do not depend on one another (Section "Methodology": they run one
+ * after another through the pipeline on the same weights), so while a second stream is set stage_forward and
+ * stage_forward_on enqueue micro-batches with an odd ub_idx there, beside the even ones on the stage's stream; the
+ * kernels and their results are the same bits.  Ordering, kept with events of the library's own:
+ *   - a forward pass on either stream starts behind everything the stage's stream held when the most recent call
+ *     other than a forward returned (weights, reuse of the activation slot).  x_dev of an odd micro-batch must be
+ *     complete, or ordered before that point, when the call is made;
+ *   - what odd micro-batches produce (y_dev, saved activations) is ordered on the stage's stream by the next call
+ *     that is not a forward -- every such call first makes the stage's stream wait for the second one -- or by
+ *     stage_forward_join.  Read y_dev of an odd micro-batch on the stage's stream only after one of them.
+ * Refused (TP_EINVAL) for stages with batch-normalisation or attention layers, whose forward kernels share scratch
+ * memory, and under TP_TIMEPREST.  Not used while profiling is on.  The stream must outlive the stage or be taken
+ * away first; stage_destroy waits for it. */
+int stage_set_forward_stream(tp_stage* st, void* hip_stream, int32_t enable);
+int stage_forward_join(tp_stage* st);
 
 /* Where the stage wants the input of (mb_id, ub_idx) to be written so that
  * stage_forward needs no copy.  Valid for the mini-batch's first micro-batch onwards. */

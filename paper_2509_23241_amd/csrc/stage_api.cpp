@@ -409,6 +409,11 @@ struct tp_stage {
   // longer the latest read their weights from there)
   bool copy_valid = false;
   uint64_t copy_version = 0;
+  // Optional second stream of the caller's: the forward passes of odd micro-batches run there, beside the even ones.
+  hipStream_t fwd_stream = nullptr;
+  hipEvent_t ev_main = nullptr, ev_fwd = nullptr;  // "the stage's stream is ready for forwards" / "the second stream is done"
+  bool main_dirty = true;    // the stage's stream got work other than forwards since ev_main was recorded
+  bool fwd_pending = false;  // the second stream holds forwards the stage's stream has not waited for yet
 
   int find_slot(uint64_t v) const {
     const Slot& s = slots[v % desc.ring_capacity];
@@ -458,6 +463,18 @@ struct ProfScope {
     hipError_t e_ = (expr);                                                               \
     if (e_ != hipSuccess) return fail(TP_EHIP, "%s: %s", #expr, hipGetErrorString(e_));   \
   } while (0)
+
+// Every entry point that enqueues work other than a forward pass, or hands out results, starts here: the stage's
+// stream waits for the forwards the second stream still holds, and the next forward knows it has to order itself
+// behind what this call enqueues.
+int join_forwards(tp_stage* st) {
+  st->main_dirty = true;
+  if (!st->fwd_pending) return TP_OK;
+  HIP_TRY(hipEventRecord(st->ev_fwd, st->fwd_stream));
+  HIP_TRY(hipStreamWaitEvent(st->stream, st->ev_fwd, 0));
+  st->fwd_pending = false;
+  return TP_OK;
+}
 
 extern "C" {
 
@@ -628,12 +645,44 @@ int stage_init(const tp_stage_desc* desc, const tp_buffers* bufs, void* hip_stre
 
 int stage_destroy(tp_stage* st) {
   if (!st) return fail(TP_EINVAL, "null stage");
+  if (st->fwd_stream) (void)hipStreamSynchronize(st->fwd_stream);  // nothing of this stage is left on the caller's stream
+  if (st->ev_main) (void)hipEventDestroy(st->ev_main);
+  if (st->ev_fwd) (void)hipEventDestroy(st->ev_fwd);
   for (ProfEntry& e : st->prof_pool) {
     (void)hipEventDestroy(e.start);
     (void)hipEventDestroy(e.stop);
   }
   delete st;
   return TP_OK;
+}
+
+int stage_set_forward_stream(tp_stage* st, void* hip_stream, int32_t enable) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  if (st->dry) return fail(TP_ESTATE, "a stage without device buffers launches nothing");
+  if (!enable) {
+    if (int rc = join_forwards(st)) return rc;
+    st->fwd_stream = nullptr;
+    return TP_OK;
+  }
+  if (!hip_stream || (hipStream_t)hip_stream == st->stream)
+    return fail(TP_EINVAL, "the second stream must be a stream of its own, not null and not the stage's");
+  if (st->desc.policy == TP_TIMEPREST)
+    return fail(TP_EINVAL, "forward passes on versions other than the latest share one compute copy: one stream only");
+  for (const LayerPlan& lp : st->plan.layers)
+    if (lp.d.type == TP_LAYER_BATCHNORM || lp.d.type == TP_LAYER_ATTENTION)
+      return fail(TP_EINVAL, "the forward kernels of batch normalisation and attention layers share scratch memory: one stream only");
+  if (int rc = join_forwards(st)) return rc;  // a stream given earlier is drained into the stage's first
+  if (!st->ev_main) HIP_TRY(hipEventCreateWithFlags(&st->ev_main, hipEventDisableTiming));
+  if (!st->ev_fwd) HIP_TRY(hipEventCreateWithFlags(&st->ev_fwd, hipEventDisableTiming));
+  st->fwd_stream = (hipStream_t)hip_stream;
+  st->main_dirty = true;
+  return TP_OK;
+}
+
+int stage_forward_join(tp_stage* st) {
+  if (!st) return fail(TP_EINVAL, "null stage");
+  if (st->dry) return TP_OK;
+  return join_forwards(st);
 }
 
 int stash_push(tp_stage* st, uint64_t version, uint32_t* slot) {
@@ -696,6 +745,8 @@ int stage_saved_input_ptr(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, int32_t
   const uint64_t nbytes = (uint64_t)st->desc.mb * lp.in_elems * st->plan.elt_size;
   if (bytes) *bytes = nbytes;
   *x_dev = st->dry ? nullptr : st->act_slot(f->act_slot) + lp.x_off + (uint64_t)ub_idx * nbytes;
+  if (!st->dry)
+    if (int rc = join_forwards(st)) return rc;  // whoever reads it on the stage's stream sees every forward enqueued so far
   return TP_OK;
 }
 
@@ -762,6 +813,20 @@ int forward_impl(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_de
       if (int rc = old_version_copy(st, v, slot, &wcopy)) return rc;
   }
   char* aslot = st->act_slot(f->act_slot);
+  // micro-batches with an odd index go to the second stream, if the caller gave one (not while kernels are timed one
+  // by one).  Either stream's forwards start behind everything the stage's stream held before this run of forwards.
+  hipStream_t fs = st->stream;
+  if (st->fwd_stream && !st->prof_on) {
+    if (st->main_dirty) {
+      HIP_TRY(hipEventRecord(st->ev_main, st->stream));
+      st->main_dirty = false;
+    }
+    if (ub_idx & 1) {
+      HIP_TRY(hipStreamWaitEvent(st->fwd_stream, st->ev_main, 0));
+      fs = st->fwd_stream;
+      st->fwd_pending = true;
+    }
+  }
   const uint64_t row0 = (uint64_t)ub_idx * d.mb;
   const int L = d.num_layers;
   for (int l = 0; l < L; ++l) {
@@ -782,14 +847,14 @@ int forward_impl(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_de
         const char* skip = aslot + st->plan.layers[add.skip_layer].x_off + row0 * add.in_elems * es;
         void* add_a = (l + 1 == L - 1) ? y_dev : (void*)(aslot + st->plan.layers[l + 2].x_off + row0 * add.out_elems * es);
         if ((((uintptr_t)skip | (uintptr_t)add_a) & 15) == 0) {
-          HIP_TRY(tp::launch_fprop(st->stream, d.dtype, d.mb * lp.tokens, lp.d.out_features, lp.d.in_features, x_in,
+          HIP_TRY(tp::launch_fprop(fs, d.dtype, d.mb * lp.tokens, lp.d.out_features, lp.d.in_features, x_in,
                                    wcopy + lp.w_off * es, master + lp.b_off, lp.d.act, z_out, add_a,
                                    need_copy ? x_saved : nullptr, skip));
           ++l;  // the add is done
           continue;
         }
       }
-      HIP_TRY(tp::launch_fprop(st->stream, d.dtype, d.mb * lp.tokens, lp.d.out_features, lp.d.in_features, x_in,
+      HIP_TRY(tp::launch_fprop(fs, d.dtype, d.mb * lp.tokens, lp.d.out_features, lp.d.in_features, x_in,
                                wcopy + lp.w_off * es, master + lp.b_off, lp.d.act, z_out, a_out,
                                need_copy ? x_saved : nullptr));
       continue;
@@ -800,27 +865,27 @@ int forward_impl(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_de
       uint16_t* x8 = (uint16_t*)(aslot + lp.xpad_off) + row0 * px * 8;
       {
         ProfScope ps(st, TP_K_COPY);
-        HIP_TRY(tp::conv_c8_pad(st->stream, d.mb * px, lp.d.in_features, (const uint16_t*)x_in, x8));
+        HIP_TRY(tp::conv_c8_pad(fs, d.mb * px, lp.d.in_features, (const uint16_t*)x_in, x8));
       }
       ProfScope ps(st, TP_K_FPROP);
       if (lp.d.geom[2] == 7)
-        HIP_TRY(tp::conv_stem_fprop(st->stream, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, lp.d.out_features, x8,
+        HIP_TRY(tp::conv_stem_fprop(fs, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, lp.d.out_features, x8,
                                     (const uint16_t*)(wcopy + lp.w_off * es), master + lp.b_off, lp.d.act, (uint16_t*)z_out,
                                     (uint16_t*)a_out, (const uint16_t*)st->zeros()));
       else
-        HIP_TRY(tp::conv_c8_fprop(st->stream, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, lp.d.out_features, x8,
+        HIP_TRY(tp::conv_c8_fprop(fs, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, lp.d.out_features, x8,
                                   (const uint16_t*)(wcopy + lp.w_off * es), master + lp.b_off, lp.d.act, (uint16_t*)z_out,
                                   (uint16_t*)a_out, (const uint16_t*)st->zeros()));
       continue;
     }
     if (need_copy) {
       ProfScope ps(st, TP_K_COPY);
-      HIP_TRY(tp::launch_copy(st->stream, x_dev, x_saved, (size_t)d.mb * lp.in_elems * es));
+      HIP_TRY(tp::launch_copy(fs, x_dev, x_saved, (size_t)d.mb * lp.in_elems * es));
     }
     if (lp.d.type == TP_LAYER_LAYERNORM) {
       ProfScope ps(st, TP_K_NORM);
       float* stats = (float*)(aslot + lp.stat_off) + row0 * lp.stat_elems;
-      HIP_TRY(tp::launch_layernorm_fwd(st->stream, d.dtype, (size_t)d.mb * lp.tokens, lp.d.in_features, x_saved,
+      HIP_TRY(tp::launch_layernorm_fwd(fs, d.dtype, (size_t)d.mb * lp.tokens, lp.d.in_features, x_saved,
                                        master + lp.w_off, master + lp.b_off, a_out, stats));
       continue;
     }
@@ -828,7 +893,7 @@ int forward_impl(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_de
       ProfScope ps(st, TP_K_ATTN);
       float* lse = (float*)(aslot + lp.stat_off) + row0 * lp.stat_elems;
       const int heads = lp.d.geom[1];
-      HIP_TRY(tp::launch_attention_fwd(st->stream, d.dtype, d.mb, lp.tokens, heads, lp.d.out_features / heads, x_saved, a_out,
+      HIP_TRY(tp::launch_attention_fwd(fs, d.dtype, d.mb, lp.tokens, heads, lp.d.out_features / heads, x_saved, a_out,
                                        lse, st->attn_scratch(), st->plan.attn_scratch_bytes));
       continue;
     }
@@ -838,9 +903,9 @@ int forward_impl(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_de
       ProfScope ps(st, TP_K_ADD);
       const char* skip = aslot + st->plan.layers[lp.skip_layer].x_off + row0 * lp.in_elems * es;
       if (lp.d.act == TP_ACT_NONE)
-        HIP_TRY(tp::launch_add(st->stream, d.dtype, (size_t)d.mb * lp.in_elems, x_saved, skip, a_out));
+        HIP_TRY(tp::launch_add(fs, d.dtype, (size_t)d.mb * lp.in_elems, x_saved, skip, a_out));
       else
-        HIP_TRY(tp::launch_add_act(st->stream, d.dtype, (size_t)d.mb * lp.in_elems, x_saved, skip, lp.d.act, a_out, z_out));
+        HIP_TRY(tp::launch_add_act(fs, d.dtype, (size_t)d.mb * lp.in_elems, x_saved, skip, lp.d.act, a_out, z_out));
       continue;
     }
     if (lp.d.type == TP_LAYER_BATCHNORM) {
@@ -856,31 +921,31 @@ int forward_impl(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_de
         void* add_z = add.z_off == UINT64_MAX ? nullptr : aslot + add.z_off + row0 * add.out_elems * es;
         void* add_a = (l + 1 == L - 1) ? y_dev : (void*)(aslot + st->plan.layers[l + 2].x_off + row0 * add.out_elems * es);
         if ((((uintptr_t)x_saved | (uintptr_t)skip | (uintptr_t)add_a | (uintptr_t)add_z) & 15) == 0) {
-          HIP_TRY(tp::launch_batchnorm_fwd(st->stream, d.dtype, (size_t)d.mb * lp.tokens, C, x_saved, master + lp.w_off,
+          HIP_TRY(tp::launch_batchnorm_fwd(fs, d.dtype, (size_t)d.mb * lp.tokens, C, x_saved, master + lp.w_off,
                                            master + lp.b_off, add.d.act, add_a, add_z, stats, st->partials(), skip));
           ++l;  // the add is done
           continue;
         }
       }
-      HIP_TRY(tp::launch_batchnorm_fwd(st->stream, d.dtype, (size_t)d.mb * lp.tokens, C, x_saved, master + lp.w_off,
+      HIP_TRY(tp::launch_batchnorm_fwd(fs, d.dtype, (size_t)d.mb * lp.tokens, C, x_saved, master + lp.w_off,
                                        master + lp.b_off, lp.d.act, a_out, z_out, stats, st->partials()));
       continue;
     }
     if (lp.d.type == TP_LAYER_CONV2D) {
       ProfScope ps(st, TP_K_FPROP);
-      HIP_TRY(tp::launch_conv_fprop(st->stream, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.geom[2], lp.d.geom[3],
+      HIP_TRY(tp::launch_conv_fprop(fs, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.geom[2], lp.d.geom[3],
                                     lp.d.in_features, lp.d.out_features, x_saved, wcopy + lp.w_off * es, master + lp.b_off,
                                     lp.d.act, z_out, a_out, st->zeros()));
     } else if (lp.d.type == TP_LAYER_AVGPOOL) {
       ProfScope ps(st, TP_K_POOL);
-      HIP_TRY(tp::launch_avgpool_fwd(st->stream, d.dtype, d.mb, lp.tokens, lp.d.in_features, x_saved, a_out));
+      HIP_TRY(tp::launch_avgpool_fwd(fs, d.dtype, d.mb, lp.tokens, lp.d.in_features, x_saved, a_out));
     } else if (lp.d.type == TP_LAYER_SUBSAMPLE2) {
       ProfScope ps(st, TP_K_POOL);
-      HIP_TRY(tp::launch_subsample_fwd(st->stream, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, x_saved,
+      HIP_TRY(tp::launch_subsample_fwd(fs, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, x_saved,
                                        a_out));
     } else {
       ProfScope ps(st, TP_K_POOL);
-      HIP_TRY(tp::launch_maxpool_fwd(st->stream, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, x_saved,
+      HIP_TRY(tp::launch_maxpool_fwd(fs, d.dtype, d.mb, lp.d.geom[0], lp.d.geom[1], lp.d.in_features, x_saved,
                                      a_out));
     }
   }
@@ -910,6 +975,7 @@ int stage_loss_softmax_ce(tp_stage* st, uint64_t mb_id, const void* logits_dev, 
     return fail(TP_ESTATE, "loss of mini-batch %llu needs all %d forwards", (unsigned long long)mb_id, st->desc.n);
   if (st->dry) return TP_OK;
   if (!logits_dev || !labels_dev || !dlogits_dev || !loss_dev) return fail(TP_EINVAL, "null pointer");
+  if (int rc = join_forwards(st)) return rc;
   const int rows = st->desc.mb * st->desc.n;
   if (st->plan.layers.back().d.type != TP_LAYER_DENSE) return fail(TP_EINVAL, "the loss needs a dense last layer");
   const int classes = st->plan.layers.back().d.out_features;
@@ -945,6 +1011,7 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
   if (delta_used) *delta_used = delta;
 
   if (!st->dry) {
+    if (int rc = join_forwards(st)) return rc;
     const size_t es = st->plan.elt_size;
     const uint64_t P = st->plan.sizes.param_count;
     const char* wb;
@@ -1329,6 +1396,7 @@ int blend_update_impl(tp_stage* st, uint64_t mb_id_done, uint64_t mb_id_next_bwd
     blend = slot_stale != slot_new;                    // never read the slot being overwritten
   }
   if (!st->dry) {
+    if (int rc = join_forwards(st)) return rc;  // forwards on the second stream still read the weights being replaced
     tp::UpdateArgs u;
     u.count = st->plan.sizes.param_count;
     u.g = (const float*)st->bufs.grad_dev;
@@ -1412,6 +1480,7 @@ int stage_export_params(tp_stage* st, uint64_t version, void* dst_dev) {
   if (s < 0) return fail(TP_ENOVERSION, "version %llu is not in the ring", (unsigned long long)version);
   if (st->dry) return TP_OK;
   if (!dst_dev) return fail(TP_EINVAL, "null destination");
+  if (int rc = join_forwards(st)) return rc;
   HIP_TRY(hipMemcpyAsync(dst_dev, st->ring(s), st->plan.sizes.param_count * 4, hipMemcpyDeviceToDevice, st->stream));
   return TP_OK;
 }
@@ -1420,6 +1489,7 @@ int stage_profile_begin(tp_stage* st, uint32_t max_launches) {
   if (!st) return fail(TP_EINVAL, "null stage");
   if (st->dry) return fail(TP_ESTATE, "a stage without device buffers launches nothing");
   if (st->prof_on) return fail(TP_ESTATE, "profiling is already on");
+  if (int rc = join_forwards(st)) return rc;
   while (st->prof_pool.size() < max_launches) {
     ProfEntry e{};
     HIP_TRY(hipEventCreate(&e.start));

@@ -49,7 +49,10 @@ class GpuStage:
     def __init__(self, layers: Sequence[tuple], params: Optional[List[np.ndarray]], *, dtype: str, mb: int, n: int,
                  stage_index: int, num_stages: int, policy: str, lam: float, lr: float, momentum: float,
                  ring_capacity: Optional[int] = None, max_in_flight: Optional[int] = None,
-                 needs_dx: Optional[bool] = None, device="cuda:0", stream: Optional[torch.cuda.Stream] = None):
+                 needs_dx: Optional[bool] = None, device="cuda:0", stream: Optional[torch.cuda.Stream] = None,
+                 forward_stream: bool = False):
+        """forward_stream: hand the stage a second stream (default priority) for the forward passes of odd
+        micro-batches; their outputs are ordered on the stage's stream by forward_join() or any later call."""
         self.layers = [tuple(l) for l in layers]
         self.in_elems = B.layer_in_elems(self.layers[0])      # values per sample in / out of the stage
         self.out_elems = B.layer_out_elems(self.layers[-1])
@@ -93,6 +96,10 @@ class GpuStage:
                             self.scratch.data_ptr(), self.diag.data_ptr())
         with torch.cuda.stream(self.stream):
             self.handle = B.stage_init(self.desc, bufs, self.stream.cuda_stream)
+        self.fwd_stream = None
+        if forward_stream:
+            self.fwd_stream = torch.cuda.Stream(self.device)
+            B.stage_set_forward_stream(self.handle, self.fwd_stream.cuda_stream, True)
 
     # -- parameter arena <-> per-layer arrays (pure indexing) -----------------
     def pack(self, params: List[np.ndarray]) -> np.ndarray:
@@ -131,6 +138,9 @@ class GpuStage:
         assert y.shape[0] == self.mb and y.numel() == self.mb * self.out_elems
         v = B.stage_forward(self.handle, mb_id, ub, x.data_ptr(), y.data_ptr())
         return y, v
+
+    def forward_join(self):
+        B.stage_forward_join(self.handle)
 
     def forward_on(self, mb_id: int, ub: int, version: int, x: torch.Tensor, y: torch.Tensor):
         """Forward on a retained version (TP_TIMEPREST)."""

@@ -65,7 +65,7 @@ def fix_relu_masks(specs, params, x, margin=4.0):
 
 def run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, depth=2, needs_dx=True, lr=None,
               lam=0.4, params=None, mean_loss_dy=False, fixed_masks=False, pure_oracle=False, stage_index=0,
-              check_saved=True, storage_floor=False):
+              check_saved=True, storage_floor=False, forward_stream=False):
     """Steady schedule of a stage of pipeline depth `depth`: forwards run `depth` mini-batches ahead.
 
     The fp32 runs take large steps (lr 0.05): at tolerance 1e-4 any mix-up of weight versions in the
@@ -84,7 +84,10 @@ def run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, depth
     ORACLES on that tensor (times sqrt 2) -- what storing every activation in bf16 does to the exact result, by the
     oracle's own account.  The GPU's bf16 execution then has to sit as close to the bf16-storing oracle as two
     independent bf16 executions of the exact computation sit to each other; on stacks where that distance is below
-    the tolerance nothing changes."""
+    the tolerance nothing changes.
+
+    forward_stream: the stage gets a second stream for the forward passes of odd micro-batches; their results are
+    read after stage_forward_join."""
     if lr is None:
         lr = 0.05 if dtype == "f32" else 0.002
     import torch
@@ -111,7 +114,8 @@ def run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, depth
     ost = Stage(specs, params, policy=policy, lam=lam, lr=lr, momentum=0.9, n=n, first_stage=not needs_dx,
                 storage=W.round_bf16 if (bf16 and not pure_oracle) else None)
     st = GpuStage([layer_tuple(l) for l in specs], params, dtype=dtype, mb=mb, n=n, stage_index=stage_index,
-                  num_stages=stage_index + depth, policy=policy, lam=lam, lr=lr, momentum=0.9, needs_dx=needs_dx)
+                  num_stages=stage_index + depth, policy=policy, lam=lam, lr=lr, momentum=0.9, needs_dx=needs_dx,
+                  forward_stream=forward_stream)
     opure = Stage(specs, params, policy=policy, lam=lam, lr=lr, momentum=0.9, n=n, first_stage=not needs_dx) \
         if storage_floor else None
     tol = TOL[dtype]
@@ -211,6 +215,8 @@ def run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, depth
                 pref.append(opure.forward(j, ub, x[ub * mb:(ub + 1) * mb]))
             _, v = st.forward(j, ub, xt[ub * mb:(ub + 1) * mb], y[ub * mb:(ub + 1) * mb])
             assert v == ost.inflight[j]["v_f"]
+        if forward_stream:
+            st.forward_join()
         if opure is not None:
             floor_of("y", np.concatenate(ref).reshape(n * mb, -1), np.concatenate(pref).reshape(n * mb, -1))
         ey = rel_err(to_np(y), np.concatenate(ref).reshape(n * mb, -1))

@@ -1,0 +1,109 @@
+"""The forward passes of a mini-batch's micro-batches on two streams (stage_set_forward_stream): the same bits as on
+one stream, parity with the oracle, the joins that order the second stream's results, and the refusals."""
+import numpy as np
+import pytest
+
+from synth_inputs import workloads as W
+from stage_parity import run_stage as _run_stage
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_dense_stage_parity_with_second_forward_stream(dtype):
+    # five micro-batches (the last even one has no partner), ragged widths in fp32 and matrix-core shapes in bf16
+    dims = (72, 200, 48) if dtype == "f32" else (256, 512, 128)
+    specs = (W.Dense(dims[0], dims[1], "gelu"), W.Dense(dims[1], dims[1], "relu"), W.Dense(dims[1], dims[2], "none"))
+    print(dtype, _run_stage(specs, f"fwd2_mlp_{dtype}", dtype, mb=64, n=5, depth=3, minibatches=4, forward_stream=True))
+
+
+def test_conv_pool_stage_parity_with_second_forward_stream():
+    w = W.vgg_stage0(mb=4, n=4, size=16, c1=64, c2=64)
+    print(_run_stage(w.stages[0], "fwd2_vgg", "bf16", mb=w.mb, n=w.n, depth=2, minibatches=3, needs_dx=False,
+                     mean_loss_dy=True, lr=0.01, forward_stream=True))
+
+
+def _drive(st, w, s, steps, join_before_read):
+    import torch
+    rows = w.n * w.mb
+    depth = w.K - s
+    outs = []
+    xs = [torch.from_numpy(W.stage_input(w, s, j).reshape(rows, -1)).cuda().to(st.tdtype) for j in range(steps + depth)]
+    dys = [torch.from_numpy(W.stage_upstream_grad(w, s, j, mean_loss=True).reshape(rows, -1)).cuda().to(st.tdtype)
+           for j in range(steps)]
+    torch.cuda.synchronize()
+
+    def forward(j):
+        y = torch.empty(rows, st.out_elems, dtype=st.tdtype, device="cuda")
+        for ub in range(w.n):
+            st.forward(j, ub, xs[j][ub * w.mb:(ub + 1) * w.mb], y[ub * w.mb:(ub + 1) * w.mb])
+        if join_before_read:
+            st.forward_join()
+        outs.append(y.float().cpu().numpy())
+
+    for j in range(depth):
+        forward(j)
+    for j in range(steps):
+        dx, _ = st.backward(j, dys[j])                      # joins by itself
+        outs.append(dx.float().cpu().numpy())
+        outs.append(st.grad.cpu().numpy().copy())
+        st.blend_update(j, j + 1)
+        outs.append(st.export(j + 1).cpu().numpy())
+        forward(j + depth)
+    return outs
+
+
+def test_two_streams_give_the_bits_of_one():
+    from paper_2509_23241_amd.runner import GpuStage, layer_tuple
+    w = W.mlp_wide(width=512, mb=128, n=8)
+    s = 1
+    layers = [layer_tuple(l) for l in w.stages[s]]
+    results = []
+    for two in (False, True):
+        st = GpuStage(layers, W.init_params(w, s), dtype=w.dtype, mb=w.mb, n=w.n, stage_index=s, num_stages=w.K,
+                      policy="convex", lam=w.lam, lr=w.lr, momentum=w.momentum, forward_stream=two)
+        results.append(_drive(st, w, s, steps=4, join_before_read=two))
+        st.close()
+    assert len(results[0]) == len(results[1])
+    for a, b in zip(*results):
+        assert np.array_equal(a, b)
+
+
+def test_saved_inputs_of_odd_micro_batches_are_ordered_by_the_accessor():
+    import torch
+    from paper_2509_23241_amd.runner import GpuStage, layer_tuple
+    w = W.mlp_wide(width=256, mb=64, n=4)
+    layers = [layer_tuple(l) for l in w.stages[1]]
+    st = GpuStage(layers, W.init_params(w, 1), dtype=w.dtype, mb=w.mb, n=w.n, stage_index=1, num_stages=w.K,
+                  policy="convex", lam=w.lam, lr=w.lr, momentum=w.momentum, forward_stream=True)
+    x = torch.from_numpy(W.stage_input(w, 1, 0).reshape(w.n * w.mb, -1)).cuda().to(st.tdtype)
+    torch.cuda.synchronize()
+    for ub in range(w.n):
+        st.forward(0, ub, x[ub * w.mb:(ub + 1) * w.mb])
+    for ub in range(w.n):                                  # the stage's own copy of what each micro-batch came in with
+        assert torch.equal(st.saved_input(0, ub, 0).reshape(w.mb, -1), x[ub * w.mb:(ub + 1) * w.mb])
+    st.close()
+
+
+def test_second_forward_stream_refusals():
+    import torch
+    from paper_2509_23241_amd import binding as B
+    from paper_2509_23241_amd.runner import GpuStage, layer_tuple
+    mk = dict(dtype="bf16", mb=4, n=2, stage_index=0, num_stages=2, lam=0.1, lr=0.01, momentum=0.9)
+    dense = [(64, 64, "relu")]
+    side = torch.cuda.Stream()
+    st = GpuStage(dense, None, policy="convex", **mk)
+    for bad in (0, st.stream.cuda_stream):                 # null, the stage's own
+        with pytest.raises(B.StageLibError) as ei:
+            B.stage_set_forward_stream(st.handle, bad, True)
+        assert ei.value.code == B.TP_EINVAL
+    B.stage_set_forward_stream(st.handle, side.cuda_stream, True)
+    B.stage_set_forward_stream(st.handle, 0, False)        # taken away again
+    B.stage_forward_join(st.handle)
+    st.close()
+    for layers, policy in (([layer_tuple(l) for l in W.bottleneck_block(16, 8, 2, 2)], "convex"), (dense, "timeprest")):
+        st = GpuStage(layers, None, policy=policy, **mk)
+        with pytest.raises(B.StageLibError) as ei:
+            B.stage_set_forward_stream(st.handle, side.cuda_stream, True)
+        assert ei.value.code == B.TP_EINVAL
+        st.close()
