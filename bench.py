@@ -59,9 +59,9 @@ def parse():
     ap.add_argument("--n", type=int, default=None, help="micro-batches per mini-batch (default 8 mlp, 4 vgg, 4 tfm)")
     ap.add_argument("--repeats", type=int, default=5,
                     help="timed blocks of --steps steps each; the line reports the median block (and all of them)")
-    ap.add_argument("--forward-streams", type=int, default=2, choices=[1, 2],
-                    help="2: the forward passes of odd micro-batches run on a second stream beside the even ones "
-                         "(stages without batch-normalisation and attention layers; elsewhere one stream is used)")
+    ap.add_argument("--forward-streams", type=int, default=None, choices=[1, 2, 3, 4],
+                    help="streams the micro-batch forward passes of a mini-batch are spread over (the stage's own and "
+                         "up to three more; default 2 for mlp and vgg, 4 for bneck; stages with attention layers use one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-minibatches", type=int, default=3)
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
@@ -277,10 +277,13 @@ def main():
     depth = w.K - s
     layers = [layer_tuple(l) for l in w.stages[s]]
     # micro-batch forwards on two streams where the stage's forward kernels share no scratch memory
-    two_streams = args.forward_streams == 2 and not any(l.kind in ("bn", "attn") for l in w.stages[s])
+    fstreams = args.forward_streams or {"mlp": 2, "vgg": 2, "bneck": 4}.get(args.workload, 1)
+    if any(l.kind == "attn" for l in w.stages[s]):
+        fstreams = 1
+    two_streams = fstreams > 1
     st = GpuStage(layers, W.init_params(w, s), dtype=w.dtype, mb=w.mb, n=w.n, stage_index=s, num_stages=w.K,
                   policy=args.policy, lam=w.lam, lr=w.lr, momentum=w.momentum, needs_dx=(s > 0), device=dev,
-                  forward_stream=two_streams)
+                  forward_stream=fstreams - 1)
     tdt = st.tdtype
     rows = w.n * w.mb
     nbuf = 2                                       # distinct synthetic mini-batches, resident in HBM
@@ -396,9 +399,9 @@ def main():
                                f"fp32 master weights, micro-batch {w.mb} x {w.n}, policy {args.policy}, "
                                f"lambda {w.lam}, staleness {delta_steady}, one step = 1 backward + 1 fused update/blend "
                                f"+ {w.n} micro-batch forwards"
-                               + (" (odd micro-batches on a second stream beside the even ones; the per-kernel "
-                                  "durations below are taken with all of them on one stream)" if two_streams else ""),
-                   "params_per_stage": int(st.P), "ring_slots": int(st.C), "forward_streams": 2 if two_streams else 1},
+                               + (f" (spread over {fstreams} streams; the per-kernel durations below are taken with "
+                                  "all of them on one stream)" if two_streams else ""),
+                   "params_per_stage": int(st.P), "ring_slots": int(st.C), "forward_streams": fstreams},
         "roofline": roofline,
         "kernels": kernels,
         "mfma_util_pct": {c: round(100 * kernels[c]["tflops"] / PEAK_BF16_TFLOPS, 2)

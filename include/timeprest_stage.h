@@ -27,7 +27,7 @@
  *     copies, activation workspace, scratch) and passes them in tp_buffers; sizes come
  *     from stage_workspace_query.  The library allocates no device memory, creates no
  *     stream, and enqueues work only on the stream given to stage_init (and on the one given
- *     to stage_set_forward_stream, if any).  Buffers must
+ *     to stage_set_forward_streams, if any).  Buffers must
  *     stay alive, and must not be written by the caller, until stage_destroy -- except
  *     ring slot 0, which the caller fills with the initial weights (version 0), and the
  *     momentum buffer, which the caller zeroes, both before stage_init.
@@ -234,22 +234,24 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
 int stage_forward_on(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, uint64_t version, const void* x_dev,
                      void* y_dev);
 
-/* Optional: a second stream of the caller's for the forward passes (a hipStream_t of default priority that is
- * neither NULL nor the stage's own and does not synchronise with it implicitly; enable = 0 takes it away again).
- * The micro-batch forward passes of a mini-batch do not depend on one another (Section "Methodology": they run one
- * after another through the pipeline on the same weights), so while a second stream is set stage_forward and
- * stage_forward_on enqueue micro-batches with an odd ub_idx there, beside the even ones on the stage's stream; the
- * kernels and their results are the same bits.  Ordering, kept with events of the library's own:
- *   - a forward pass on either stream starts behind everything the stage's stream held when the most recent call
- *     other than a forward returned (weights, reuse of the activation slot).  x_dev of an odd micro-batch must be
- *     complete, or ordered before that point, when the call is made;
- *   - what odd micro-batches produce (y_dev, saved activations) is ordered on the stage's stream by the next call
- *     that is not a forward -- every such call first makes the stage's stream wait for the second one -- or by
- *     stage_forward_join.  Read y_dev of an odd micro-batch on the stage's stream only after one of them.
- * Refused (TP_EINVAL) for stages with batch-normalisation or attention layers, whose forward kernels share scratch
- * memory, and under TP_TIMEPREST.  Not used while profiling is on.  The stream must outlive the stage or be taken
- * away first; stage_destroy waits for it. */
-int stage_set_forward_stream(tp_stage* st, void* hip_stream, int32_t enable);
+/* Optional: up to TP_MAX_FORWARD_STREAMS further streams of the caller's for the forward passes (hipStream_t of
+ * default priority, none of them NULL or the stage's own, none synchronising with it implicitly; count = 0 takes
+ * them away again).  The micro-batch forward passes of a mini-batch do not depend on one another (Section
+ * "Methodology": they run one after another through the pipeline on the same weights), so with S such streams
+ * stage_forward and stage_forward_on enqueue micro-batch ub on the stage's stream if ub % (S + 1) is 0 and on
+ * hip_streams[ub % (S + 1) - 1] otherwise; the kernels and their results are the same bits.  Ordering, kept with events
+ * of the library's own:
+ *   - a forward pass on any stream starts behind everything the stage's stream held when the most recent call other
+ *     than a forward returned (weights, reuse of the activation slot).  x_dev of a micro-batch that runs on a forward
+ *     stream must be complete, or ordered before that point, when the call is made;
+ *   - what those micro-batches produce (y_dev, saved activations) is ordered on the stage's stream by the next call
+ *     that is not a forward -- every such call first makes the stage's stream wait for the forward streams -- or by
+ *     stage_forward_join.  Read their y_dev on the stage's stream only after one of them.
+ * Refused (TP_EINVAL) for stages with attention layers, whose forward kernels share their scratch memory, and under
+ * TP_TIMEPREST.  Not used while profiling is on.  The streams must outlive the stage or be taken away first;
+ * stage_destroy waits for them. */
+#define TP_MAX_FORWARD_STREAMS 3
+int stage_set_forward_streams(tp_stage* st, void* const* hip_streams, int32_t count);
 int stage_forward_join(tp_stage* st);
 
 /* Where the stage wants the input of (mb_id, ub_idx) to be written so that

@@ -22,7 +22,7 @@ POLICY = {"latest": TP_LATEST, "eq1": TP_INTERMEDIATE_EQ1, "convex": TP_INTERMED
 ACT = {"none": TP_ACT_NONE, "relu": TP_ACT_RELU, "gelu": TP_ACT_GELU}
 DTYPE = {"f32": TP_F32, "bf16": TP_BF16}
 
-EXPORTS = ["stage_workspace_query", "stage_init", "stage_destroy", "stage_set_forward_stream", "stage_forward_join", "stage_forward", "stage_forward_on", "stage_backward_on", "stage_input_ptr", "stage_saved_input_ptr",
+EXPORTS = ["stage_workspace_query", "stage_init", "stage_destroy", "stage_set_forward_streams", "stage_forward_join", "stage_forward", "stage_forward_on", "stage_backward_on", "stage_input_ptr", "stage_saved_input_ptr",
            "stage_loss_softmax_ce", "stage_backward", "stage_blend_update", "stage_blend_update_noalloc", "stash_push", "stash_evict",
            "stage_query", "stage_export_params", "tp_blend_coefficients", "tp_schedule_events", "tp_schedule_microbatch_events",
            "stage_profile_begin", "stage_profile_end", "tp_last_error"]
@@ -102,7 +102,7 @@ lib.stage_forward.argtypes = [_vp, _u64, _u32, _vp, _vp, C.POINTER(_u64)]
 lib.stage_forward_on.argtypes = [_vp, _u64, _u32, _u64, _vp, _vp]
 lib.stage_backward_on.argtypes = [_vp, _u64, _u64, _vp, _vp]
 lib.stage_input_ptr.argtypes = [_vp, _u64, _u32, C.POINTER(_vp)]
-lib.stage_set_forward_stream.argtypes = [_vp, _vp, _i32]
+lib.stage_set_forward_streams.argtypes = [_vp, C.POINTER(_vp), _i32]
 lib.stage_forward_join.argtypes = [_vp]
 lib.stage_saved_input_ptr.argtypes = [_vp, _u64, _u32, _i32, C.POINTER(_vp), C.POINTER(_u64)]
 lib.stage_loss_softmax_ce.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp]
@@ -282,8 +282,13 @@ def stage_backward_on(st, mb_id: int, version: int, dy_dev: int, dx_dev: int):
     _check(lib.stage_backward_on(st, mb_id, version, _vp(dy_dev), _vp(dx_dev)))
 
 
-def stage_set_forward_stream(st, hip_stream: int, enable: bool = True):
-    _check(lib.stage_set_forward_stream(st, _vp(hip_stream), 1 if enable else 0))
+TP_MAX_FORWARD_STREAMS = 3
+
+
+def stage_set_forward_streams(st, hip_streams):
+    """hip_streams: sequence of stream handles (integers); empty takes the forward streams away."""
+    arr = (_vp * max(len(hip_streams), 1))(*[_vp(h) for h in hip_streams])
+    _check(lib.stage_set_forward_streams(st, arr, len(hip_streams)))
 
 
 def stage_forward_join(st):

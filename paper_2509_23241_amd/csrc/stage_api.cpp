@@ -70,6 +70,7 @@ struct Plan {
   uint64_t dz_bytes = 0;       // one backward temporary
   uint64_t partial_floats = 0; // reduction partials
   uint64_t deferred_floats = 0; // behind them: partials of the backward pass's sums, which one launch forms at its end
+  uint64_t fwd2_floats = 0;     // behind those: scratch of the normalisation forward kernels on a second forward stream
   uint64_t attn_scratch_bytes = 0;  // transient score matrices of the matrix-core attention
   size_t elt_size = 4;
 };
@@ -260,6 +261,8 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
       lp.stat_bytes = (uint64_t)d->n * 2 * L.in_features * 4;   // (mean, 1/std) per channel and micro-batch
       norm_scratch = std::max<uint64_t>(norm_scratch, tp::batchnorm_scratch_floats((size_t)d->mb * lp.tokens, L.in_features, d->n) +
                                                           (uint64_t)d->n * 2 * L.in_features);
+      p->fwd2_floats = std::max<uint64_t>(p->fwd2_floats,
+                                          round_up(tp::batchnorm_scratch_floats((size_t)d->mb * lp.tokens, L.in_features, 1), 64));
     } else if (L.type == TP_LAYER_ATTENTION) {
       lp.tokens = L.geom[0];
       lp.in_elems = (uint64_t)lp.tokens * L.in_features;
@@ -370,7 +373,7 @@ int make_plan(const tp_stage_desc* d, Plan* p) {
   s.wfwd_bytes = d->dtype == TP_BF16 ? P * 2 : 0;
   s.wbwd_bytes = d->policy == TP_LATEST ? 0 : P * p->elt_size;  // V-TiMePReSt never builds intermediate weights
   s.act_bytes = (uint64_t)d->max_in_flight * act;
-  s.scratch_bytes = 3 * p->dz_bytes + (p->partial_floats + p->deferred_floats) * 4 + 512 + p->attn_scratch_bytes;  // + an aligned block of 256 zero bytes (conv padding)
+  s.scratch_bytes = 3 * p->dz_bytes + (p->partial_floats + p->deferred_floats + TP_MAX_FORWARD_STREAMS * p->fwd2_floats) * 4 + 512 + p->attn_scratch_bytes;  // + an aligned block of 256 zero bytes (conv padding)
   s.diag_bytes = TP_DIAG_COUNT * sizeof(double);
   return TP_OK;
 }
@@ -410,10 +413,12 @@ struct tp_stage {
   bool copy_valid = false;
   uint64_t copy_version = 0;
   // Optional second stream of the caller's: the forward passes of odd micro-batches run there, beside the even ones.
-  hipStream_t fwd_stream = nullptr;
-  hipEvent_t ev_main = nullptr, ev_fwd = nullptr;  // "the stage's stream is ready for forwards" / "the second stream is done"
-  bool main_dirty = true;    // the stage's stream got work other than forwards since ev_main was recorded
-  bool fwd_pending = false;  // the second stream holds forwards the stage's stream has not waited for yet
+  int fwd_streams = 0;                                    // how many the caller gave
+  hipStream_t fwd_stream[TP_MAX_FORWARD_STREAMS] = {};
+  hipEvent_t ev_main = nullptr;                           // "the stage's stream is ready for forwards"
+  hipEvent_t ev_fwd[TP_MAX_FORWARD_STREAMS] = {};         // "this forward stream is done"
+  bool main_dirty = true;                                 // the stage's stream got work other than forwards since ev_main was recorded
+  bool fwd_pending[TP_MAX_FORWARD_STREAMS] = {};          // the stream holds forwards the stage's stream has not waited for yet
 
   int find_slot(uint64_t v) const {
     const Slot& s = slots[v % desc.ring_capacity];
@@ -429,9 +434,10 @@ struct tp_stage {
   char* dz_buf(int i) const { return (char*)bufs.scratch_dev + (uint64_t)i * plan.dz_bytes; }
   float* partials() const { return (float*)((char*)bufs.scratch_dev + 3 * plan.dz_bytes); }
   float* deferred_partials() const { return partials() + plan.partial_floats; }
+  float* fwd2_scratch(int k) const { return deferred_partials() + plan.deferred_floats + (uint64_t)k * plan.fwd2_floats; }
   std::vector<tp::SumJob> sum_jobs;  // the backward pass under way: sums still to be formed
   const void* zeros() const {  // 256-byte aligned, behind the partial sums
-    const uintptr_t p = (uintptr_t)bufs.scratch_dev + 3 * plan.dz_bytes + (plan.partial_floats + plan.deferred_floats) * 4;
+    const uintptr_t p = (uintptr_t)bufs.scratch_dev + 3 * plan.dz_bytes + (plan.partial_floats + plan.deferred_floats + TP_MAX_FORWARD_STREAMS * plan.fwd2_floats) * 4;
     return (const void*)((p + 255) & ~(uintptr_t)255);
   }
   void* attn_scratch() const { return plan.attn_scratch_bytes ? (char*)zeros() + 256 : nullptr; }
@@ -469,10 +475,12 @@ struct ProfScope {
 // behind what this call enqueues.
 int join_forwards(tp_stage* st) {
   st->main_dirty = true;
-  if (!st->fwd_pending) return TP_OK;
-  HIP_TRY(hipEventRecord(st->ev_fwd, st->fwd_stream));
-  HIP_TRY(hipStreamWaitEvent(st->stream, st->ev_fwd, 0));
-  st->fwd_pending = false;
+  for (int k = 0; k < TP_MAX_FORWARD_STREAMS; ++k) {
+    if (!st->fwd_pending[k]) continue;
+    HIP_TRY(hipEventRecord(st->ev_fwd[k], st->fwd_stream[k]));
+    HIP_TRY(hipStreamWaitEvent(st->stream, st->ev_fwd[k], 0));
+    st->fwd_pending[k] = false;
+  }
   return TP_OK;
 }
 
@@ -645,9 +653,11 @@ int stage_init(const tp_stage_desc* desc, const tp_buffers* bufs, void* hip_stre
 
 int stage_destroy(tp_stage* st) {
   if (!st) return fail(TP_EINVAL, "null stage");
-  if (st->fwd_stream) (void)hipStreamSynchronize(st->fwd_stream);  // nothing of this stage is left on the caller's stream
+  for (int k = 0; k < TP_MAX_FORWARD_STREAMS; ++k) {
+    if (st->fwd_stream[k]) (void)hipStreamSynchronize(st->fwd_stream[k]);  // nothing of this stage is left on the caller's streams
+    if (st->ev_fwd[k]) (void)hipEventDestroy(st->ev_fwd[k]);
+  }
   if (st->ev_main) (void)hipEventDestroy(st->ev_main);
-  if (st->ev_fwd) (void)hipEventDestroy(st->ev_fwd);
   for (ProfEntry& e : st->prof_pool) {
     (void)hipEventDestroy(e.start);
     (void)hipEventDestroy(e.stop);
@@ -656,25 +666,30 @@ int stage_destroy(tp_stage* st) {
   return TP_OK;
 }
 
-int stage_set_forward_stream(tp_stage* st, void* hip_stream, int32_t enable) {
+int stage_set_forward_streams(tp_stage* st, void* const* hip_streams, int32_t count) {
   if (!st) return fail(TP_EINVAL, "null stage");
   if (st->dry) return fail(TP_ESTATE, "a stage without device buffers launches nothing");
-  if (!enable) {
-    if (int rc = join_forwards(st)) return rc;
-    st->fwd_stream = nullptr;
-    return TP_OK;
+  if (count < 0 || count > TP_MAX_FORWARD_STREAMS) return fail(TP_EINVAL, "0 .. %d forward streams", TP_MAX_FORWARD_STREAMS);
+  if (count > 0 && !hip_streams) return fail(TP_EINVAL, "null stream list");
+  for (int k = 0; k < count; ++k) {
+    if (!hip_streams[k] || (hipStream_t)hip_streams[k] == st->stream)
+      return fail(TP_EINVAL, "a forward stream must be a stream of its own, not null and not the stage's");
+    for (int q = 0; q < k; ++q)
+      if (hip_streams[q] == hip_streams[k]) return fail(TP_EINVAL, "forward streams %d and %d are the same", q, k);
   }
-  if (!hip_stream || (hipStream_t)hip_stream == st->stream)
-    return fail(TP_EINVAL, "the second stream must be a stream of its own, not null and not the stage's");
-  if (st->desc.policy == TP_TIMEPREST)
-    return fail(TP_EINVAL, "forward passes on versions other than the latest share one compute copy: one stream only");
-  for (const LayerPlan& lp : st->plan.layers)
-    if (lp.d.type == TP_LAYER_BATCHNORM || lp.d.type == TP_LAYER_ATTENTION)
-      return fail(TP_EINVAL, "the forward kernels of batch normalisation and attention layers share scratch memory: one stream only");
-  if (int rc = join_forwards(st)) return rc;  // a stream given earlier is drained into the stage's first
-  if (!st->ev_main) HIP_TRY(hipEventCreateWithFlags(&st->ev_main, hipEventDisableTiming));
-  if (!st->ev_fwd) HIP_TRY(hipEventCreateWithFlags(&st->ev_fwd, hipEventDisableTiming));
-  st->fwd_stream = (hipStream_t)hip_stream;
+  if (count > 0) {
+    if (st->desc.policy == TP_TIMEPREST)
+      return fail(TP_EINVAL, "forward passes on versions other than the latest share one compute copy: one stream only");
+    for (const LayerPlan& lp : st->plan.layers)
+      if (lp.d.type == TP_LAYER_ATTENTION)
+        return fail(TP_EINVAL, "the forward kernels of attention layers share their scratch memory: one stream only");
+  }
+  if (int rc = join_forwards(st)) return rc;  // streams given earlier are drained into the stage's first
+  if (count > 0 && !st->ev_main) HIP_TRY(hipEventCreateWithFlags(&st->ev_main, hipEventDisableTiming));
+  for (int k = 0; k < count; ++k)
+    if (!st->ev_fwd[k]) HIP_TRY(hipEventCreateWithFlags(&st->ev_fwd[k], hipEventDisableTiming));
+  for (int k = 0; k < TP_MAX_FORWARD_STREAMS; ++k) st->fwd_stream[k] = k < count ? (hipStream_t)hip_streams[k] : nullptr;
+  st->fwd_streams = count;
   st->main_dirty = true;
   return TP_OK;
 }
@@ -813,18 +828,21 @@ int forward_impl(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_de
       if (int rc = old_version_copy(st, v, slot, &wcopy)) return rc;
   }
   char* aslot = st->act_slot(f->act_slot);
-  // micro-batches with an odd index go to the second stream, if the caller gave one (not while kernels are timed one
-  // by one).  Either stream's forwards start behind everything the stage's stream held before this run of forwards.
+  // With S forward streams of the caller's, micro-batch ub runs on the stage's stream if ub % (S + 1) is 0 and on
+  // forward stream ub % (S + 1) - 1 otherwise (not while kernels are timed one by one).  Every stream's forwards start
+  // behind everything the stage's stream held before this run of forwards.
   hipStream_t fs = st->stream;
-  if (st->fwd_stream && !st->prof_on) {
+  int fsk = -1;  // index of the forward stream in use
+  if (st->fwd_streams > 0 && !st->prof_on) {
     if (st->main_dirty) {
       HIP_TRY(hipEventRecord(st->ev_main, st->stream));
       st->main_dirty = false;
     }
-    if (ub_idx & 1) {
-      HIP_TRY(hipStreamWaitEvent(st->fwd_stream, st->ev_main, 0));
-      fs = st->fwd_stream;
-      st->fwd_pending = true;
+    fsk = (int)(ub_idx % (uint32_t)(st->fwd_streams + 1)) - 1;
+    if (fsk >= 0) {
+      HIP_TRY(hipStreamWaitEvent(st->fwd_stream[fsk], st->ev_main, 0));
+      fs = st->fwd_stream[fsk];
+      st->fwd_pending[fsk] = true;
     }
   }
   const uint64_t row0 = (uint64_t)ub_idx * d.mb;
@@ -922,13 +940,13 @@ int forward_impl(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_de
         void* add_a = (l + 1 == L - 1) ? y_dev : (void*)(aslot + st->plan.layers[l + 2].x_off + row0 * add.out_elems * es);
         if ((((uintptr_t)x_saved | (uintptr_t)skip | (uintptr_t)add_a | (uintptr_t)add_z) & 15) == 0) {
           HIP_TRY(tp::launch_batchnorm_fwd(fs, d.dtype, (size_t)d.mb * lp.tokens, C, x_saved, master + lp.w_off,
-                                           master + lp.b_off, add.d.act, add_a, add_z, stats, st->partials(), skip));
+                                           master + lp.b_off, add.d.act, add_a, add_z, stats, fsk < 0 ? st->partials() : st->fwd2_scratch(fsk), skip));
           ++l;  // the add is done
           continue;
         }
       }
       HIP_TRY(tp::launch_batchnorm_fwd(fs, d.dtype, (size_t)d.mb * lp.tokens, C, x_saved, master + lp.w_off,
-                                       master + lp.b_off, lp.d.act, a_out, z_out, stats, st->partials()));
+                                       master + lp.b_off, lp.d.act, a_out, z_out, stats, fsk < 0 ? st->partials() : st->fwd2_scratch(fsk)));
       continue;
     }
     if (lp.d.type == TP_LAYER_CONV2D) {

@@ -50,9 +50,10 @@ class GpuStage:
                  stage_index: int, num_stages: int, policy: str, lam: float, lr: float, momentum: float,
                  ring_capacity: Optional[int] = None, max_in_flight: Optional[int] = None,
                  needs_dx: Optional[bool] = None, device="cuda:0", stream: Optional[torch.cuda.Stream] = None,
-                 forward_stream: bool = False):
-        """forward_stream: hand the stage a second stream (default priority) for the forward passes of odd
-        micro-batches; their outputs are ordered on the stage's stream by forward_join() or any later call."""
+                 forward_stream=False):
+        """forward_stream: False / 0, or how many further streams (default priority; True = 1) the stage gets for the
+        forward passes of a mini-batch's micro-batches; what runs there is ordered on the stage's stream by
+        forward_join() or any later call other than a forward."""
         self.layers = [tuple(l) for l in layers]
         self.in_elems = B.layer_in_elems(self.layers[0])      # values per sample in / out of the stage
         self.out_elems = B.layer_out_elems(self.layers[-1])
@@ -96,10 +97,9 @@ class GpuStage:
                             self.scratch.data_ptr(), self.diag.data_ptr())
         with torch.cuda.stream(self.stream):
             self.handle = B.stage_init(self.desc, bufs, self.stream.cuda_stream)
-        self.fwd_stream = None
-        if forward_stream:
-            self.fwd_stream = torch.cuda.Stream(self.device)
-            B.stage_set_forward_stream(self.handle, self.fwd_stream.cuda_stream, True)
+        self.fwd_streams = [torch.cuda.Stream(self.device) for _ in range(int(forward_stream))]
+        if self.fwd_streams:
+            B.stage_set_forward_streams(self.handle, [q.cuda_stream for q in self.fwd_streams])
 
     # -- parameter arena <-> per-layer arrays (pure indexing) -----------------
     def pack(self, params: List[np.ndarray]) -> np.ndarray:

@@ -1,5 +1,5 @@
-"""The forward passes of a mini-batch's micro-batches on two streams (stage_set_forward_stream): the same bits as on
-one stream, parity with the oracle, the joins that order the second stream's results, and the refusals."""
+"""The forward passes of a mini-batch's micro-batches on several streams (stage_set_forward_streams): the same bits
+as on one stream, parity with the oracle, the joins that order the forward streams' results, and the refusals."""
 import numpy as np
 import pytest
 
@@ -21,6 +21,21 @@ def test_conv_pool_stage_parity_with_second_forward_stream():
     w = W.vgg_stage0(mb=4, n=4, size=16, c1=64, c2=64)
     print(_run_stage(w.stages[0], "fwd2_vgg", "bf16", mb=w.mb, n=w.n, depth=2, minibatches=3, needs_dx=False,
                      mean_loss_dy=True, lr=0.01, forward_stream=True))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_bottleneck_stage_parity_with_four_forward_streams(dtype):
+    # batch normalisation per micro-batch on both streams at once (each with scratch of its own), strided block
+    # with projection shortcut, identity block
+    specs = W.bottleneck_down_block(16, 16, 32, 8, 8, "gelu") + W.bottleneck_block(32, 16, 4, 4, "gelu")
+    print(dtype, _run_stage(specs, f"fwd2_bneck_{dtype}", dtype, mb=4, n=4, depth=3, minibatches=3, forward_stream=3))
+
+
+def test_streaming_normalisation_on_both_streams_bf16():
+    # 9000 rows per micro-batch: statistics, finalize and normalise kernels with partial sums in scratch memory
+    specs = (W.Dense(8, 16, "none", tokens=3000), W.BatchNorm(16, 3000, "gelu"),
+             W.Dense(16, 8, "none", tokens=3000), W.BatchNorm(8, 3000, "none"))
+    print(_run_stage(specs, "fwd2_bn_rows", "bf16", mb=3, n=4, forward_stream=True))
 
 
 def _drive(st, w, s, steps, join_before_read):
@@ -59,14 +74,31 @@ def test_two_streams_give_the_bits_of_one():
     s = 1
     layers = [layer_tuple(l) for l in w.stages[s]]
     results = []
-    for two in (False, True):
+    for extra in (0, 1, 3):
         st = GpuStage(layers, W.init_params(w, s), dtype=w.dtype, mb=w.mb, n=w.n, stage_index=s, num_stages=w.K,
-                      policy="convex", lam=w.lam, lr=w.lr, momentum=w.momentum, forward_stream=two)
-        results.append(_drive(st, w, s, steps=4, join_before_read=two))
+                      policy="convex", lam=w.lam, lr=w.lr, momentum=w.momentum, forward_stream=extra)
+        results.append(_drive(st, w, s, steps=4, join_before_read=extra > 0))
         st.close()
-    assert len(results[0]) == len(results[1])
-    for a, b in zip(*results):
-        assert np.array_equal(a, b)
+    for other in results[1:]:
+        assert len(results[0]) == len(other)
+        for a, b in zip(results[0], other):
+            assert np.array_equal(a, b)
+
+
+def test_two_streams_give_the_bits_of_one_bottleneck_stage():
+    from paper_2509_23241_amd.runner import GpuStage, layer_tuple
+    w = W.bottleneck_stage(c=256, mid=64, h=4, w=4, blocks=1, mb=16, n=4, down=True)
+    s = 1
+    layers = [layer_tuple(l) for l in w.stages[s]]
+    results = []
+    for extra in (0, 2, 3):
+        st = GpuStage(layers, W.init_params(w, s), dtype=w.dtype, mb=w.mb, n=w.n, stage_index=s, num_stages=w.K,
+                      policy="convex", lam=w.lam, lr=w.lr, momentum=w.momentum, forward_stream=extra)
+        results.append(_drive(st, w, s, steps=3, join_before_read=extra > 0))
+        st.close()
+    for other in results[1:]:
+        for a, b in zip(results[0], other):
+            assert np.array_equal(a, b)
 
 
 def test_saved_inputs_of_odd_micro_batches_are_ordered_by_the_accessor():
@@ -85,25 +117,27 @@ def test_saved_inputs_of_odd_micro_batches_are_ordered_by_the_accessor():
     st.close()
 
 
-def test_second_forward_stream_refusals():
+def test_forward_stream_refusals():
     import torch
     from paper_2509_23241_amd import binding as B
     from paper_2509_23241_amd.runner import GpuStage, layer_tuple
     mk = dict(dtype="bf16", mb=4, n=2, stage_index=0, num_stages=2, lam=0.1, lr=0.01, momentum=0.9)
     dense = [(64, 64, "relu")]
-    side = torch.cuda.Stream()
+    side = [torch.cuda.Stream() for _ in range(4)]
+    h = [q.cuda_stream for q in side]
     st = GpuStage(dense, None, policy="convex", **mk)
-    for bad in (0, st.stream.cuda_stream):                 # null, the stage's own
+    for bad in ([0], [st.stream.cuda_stream] if st.stream.cuda_stream else [0], [h[0], h[0]], h):   # null, the stage's own, twice the same, too many
         with pytest.raises(B.StageLibError) as ei:
-            B.stage_set_forward_stream(st.handle, bad, True)
+            B.stage_set_forward_streams(st.handle, bad)
         assert ei.value.code == B.TP_EINVAL
-    B.stage_set_forward_stream(st.handle, side.cuda_stream, True)
-    B.stage_set_forward_stream(st.handle, 0, False)        # taken away again
+    B.stage_set_forward_streams(st.handle, h[:3])
+    B.stage_set_forward_streams(st.handle, [])             # taken away again
     B.stage_forward_join(st.handle)
     st.close()
-    for layers, policy in (([layer_tuple(l) for l in W.bottleneck_block(16, 8, 2, 2)], "convex"), (dense, "timeprest")):
+    attn = [layer_tuple(l) for l in W.transformer_block(64, 2, 128, 8)]
+    for layers, policy in ((attn, "convex"), (dense, "timeprest")):
         st = GpuStage(layers, None, policy=policy, **mk)
         with pytest.raises(B.StageLibError) as ei:
-            B.stage_set_forward_stream(st.handle, side.cuda_stream, True)
+            B.stage_set_forward_streams(st.handle, h[:1])
         assert ei.value.code == B.TP_EINVAL
         st.close()
