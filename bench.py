@@ -59,9 +59,10 @@ def parse():
     ap.add_argument("--n", type=int, default=None, help="micro-batches per mini-batch (default 8 mlp, 4 vgg, 4 tfm)")
     ap.add_argument("--repeats", type=int, default=5,
                     help="timed blocks of --steps steps each; the line reports the median block (and all of them)")
-    ap.add_argument("--forward-streams", type=int, default=None, choices=[1, 2, 3, 4],
-                    help="streams the micro-batch forward passes of a mini-batch are spread over (the stage's own and "
-                         "up to three more; default 2 for mlp and vgg, 4 for bneck; stages with attention layers use one)")
+    ap.add_argument("--forward-streams", type=int, default=None, choices=[0, 1, 2, 3],
+                    help="streams of their own for the forward passes: micro-batch ub runs on stream ub mod N, beside the "
+                         "backward pass of an earlier mini-batch on the stage's stream; 0: everything on the stage's "
+                         "stream (default 2; 3 for a last stage, whose own stream takes a turn; stages with attention layers: 0)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-minibatches", type=int, default=3)
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
@@ -277,13 +278,16 @@ def main():
     depth = w.K - s
     layers = [layer_tuple(l) for l in w.stages[s]]
     # micro-batch forwards on two streams where the stage's forward kernels share no scratch memory
-    fstreams = args.forward_streams or {"mlp": 2, "vgg": 2, "bneck": 4}.get(args.workload, 1)
+    # a stage that holds one mini-batch at a time (the last one) cannot run forwards beside a backward pass; its own
+    # stream then takes a turn with the forward streams: three of them make four in all
+    fstreams = args.forward_streams if args.forward_streams is not None else \
+        (3 if w.K - s == 1 else {"mlp": 2, "vgg": 2, "bneck": 2}.get(args.workload, 0))
     if any(l.kind == "attn" for l in w.stages[s]):
-        fstreams = 1
-    two_streams = fstreams > 1
+        fstreams = 0
+    two_streams = fstreams > 0
     st = GpuStage(layers, W.init_params(w, s), dtype=w.dtype, mb=w.mb, n=w.n, stage_index=s, num_stages=w.K,
                   policy=args.policy, lam=w.lam, lr=w.lr, momentum=w.momentum, needs_dx=(s > 0), device=dev,
-                  forward_stream=fstreams - 1)
+                  forward_stream=fstreams)
     tdt = st.tdtype
     rows = w.n * w.mb
     nbuf = 2                                       # distinct synthetic mini-batches, resident in HBM
@@ -399,8 +403,9 @@ def main():
                                f"fp32 master weights, micro-batch {w.mb} x {w.n}, policy {args.policy}, "
                                f"lambda {w.lam}, staleness {delta_steady}, one step = 1 backward + 1 fused update/blend "
                                f"+ {w.n} micro-batch forwards"
-                               + (f" (spread over {fstreams} streams; the per-kernel durations below are taken with "
-                                  "all of them on one stream)" if two_streams else ""),
+                               + (f" (the forwards on {fstreams} streams of their own, beside the backward pass of the "
+                                  "next mini-batch on the stage's stream; the per-kernel durations below are taken with "
+                                  "everything on the stage's stream)" if two_streams else ""),
                    "params_per_stage": int(st.P), "ring_slots": int(st.C), "forward_streams": fstreams},
         "roofline": roofline,
         "kernels": kernels,

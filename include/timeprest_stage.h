@@ -234,19 +234,25 @@ int stage_forward(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_d
 int stage_forward_on(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, uint64_t version, const void* x_dev,
                      void* y_dev);
 
-/* Optional: up to TP_MAX_FORWARD_STREAMS further streams of the caller's for the forward passes (hipStream_t of
- * default priority, none of them NULL or the stage's own, none synchronising with it implicitly; count = 0 takes
- * them away again).  The micro-batch forward passes of a mini-batch do not depend on one another (Section
- * "Methodology": they run one after another through the pipeline on the same weights), so with S such streams
- * stage_forward and stage_forward_on enqueue micro-batch ub on the stage's stream if ub % (S + 1) is 0 and on
- * hip_streams[ub % (S + 1) - 1] otherwise; the kernels and their results are the same bits.  Ordering, kept with events
- * of the library's own:
- *   - a forward pass on any stream starts behind everything the stage's stream held when the most recent call other
- *     than a forward returned (weights, reuse of the activation slot).  x_dev of a micro-batch that runs on a forward
- *     stream must be complete, or ordered before that point, when the call is made;
- *   - what those micro-batches produce (y_dev, saved activations) is ordered on the stage's stream by the next call
- *     that is not a forward -- every such call first makes the stage's stream wait for the forward streams -- or by
- *     stage_forward_join.  Read their y_dev on the stage's stream only after one of them.
+/* Optional: up to TP_MAX_FORWARD_STREAMS streams of the caller's for the forward passes (hipStream_t of default
+ * priority, none of them NULL or the stage's own, none synchronising with it implicitly; count = 0 takes them away
+ * again).  The micro-batch forward passes of a mini-batch do not depend on one another (Section "Methodology": they
+ * run one after another through the pipeline on the same weights), and the forward passes of a later mini-batch do
+ * not depend on the backward pass of an earlier one, only on the update before it (Sections "V-TiMePReSt",
+ * "I-TiMePReSt": a forward reads the latest version).  With S such streams stage_forward and stage_forward_on enqueue
+ * micro-batch ub on hip_streams[ub % S] and nothing of a forward on the stage's own stream (a stage with
+ * max_in_flight = 1, whose backward pass always needs the forwards just enqueued, lets its own stream take a turn:
+ * ub % (S + 1) == 0 runs there, the others on hip_streams[ub % (S + 1) - 1]); the kernels and their results are the
+ * same bits.  Ordering, kept with events of the library's own:
+ *   - a forward pass starts behind everything the stage's stream held when the most recent call other than a forward
+ *     returned (the update that made its weights, the backward pass that freed its activation slot).  x_dev must be
+ *     complete, or ordered before that point, when the call is made;
+ *   - stage_backward / stage_backward_on make the stage's stream wait for the forward passes of THEIR mini-batch
+ *     and for no others: forwards of later mini-batches enqueued before the call keep running beside the backward
+ *     pass;
+ *   - every other call that enqueues work or hands out results (stage_blend_update[_noalloc], stage_loss_softmax_ce,
+ *     stage_saved_input_ptr, stage_export_params, stage_profile_begin, stage_forward_join) first makes the stage's
+ *     stream wait for all forward streams.  Read y_dev on the stage's stream only after one of them.
  * Refused (TP_EINVAL) for stages with attention layers, whose forward kernels share their scratch memory, and under
  * TP_TIMEPREST.  Not used while profiling is on.  The streams must outlive the stage or be taken away first;
  * stage_destroy waits for them. */

@@ -419,6 +419,10 @@ struct tp_stage {
   hipEvent_t ev_fwd[TP_MAX_FORWARD_STREAMS] = {};         // "this forward stream is done"
   bool main_dirty = true;                                 // the stage's stream got work other than forwards since ev_main was recorded
   bool fwd_pending[TP_MAX_FORWARD_STREAMS] = {};          // the stream holds forwards the stage's stream has not waited for yet
+  // per activation slot (= mini-batch in flight) and forward stream: the last forward of that mini-batch there, which
+  // its backward pass waits for -- and for no other, so that forwards of later mini-batches run beside it
+  hipEvent_t ev_slot[TP_MAX_IN_FLIGHT][TP_MAX_FORWARD_STREAMS] = {};
+  bool slot_fwd[TP_MAX_IN_FLIGHT][TP_MAX_FORWARD_STREAMS] = {};
 
   int find_slot(uint64_t v) const {
     const Slot& s = slots[v % desc.ring_capacity];
@@ -480,6 +484,7 @@ int join_forwards(tp_stage* st) {
     HIP_TRY(hipEventRecord(st->ev_fwd[k], st->fwd_stream[k]));
     HIP_TRY(hipStreamWaitEvent(st->stream, st->ev_fwd[k], 0));
     st->fwd_pending[k] = false;
+    for (int q = 0; q < TP_MAX_IN_FLIGHT; ++q) st->slot_fwd[q][k] = false;  // ordered with everything else on the stream
   }
   return TP_OK;
 }
@@ -656,6 +661,8 @@ int stage_destroy(tp_stage* st) {
   for (int k = 0; k < TP_MAX_FORWARD_STREAMS; ++k) {
     if (st->fwd_stream[k]) (void)hipStreamSynchronize(st->fwd_stream[k]);  // nothing of this stage is left on the caller's streams
     if (st->ev_fwd[k]) (void)hipEventDestroy(st->ev_fwd[k]);
+    for (int q = 0; q < TP_MAX_IN_FLIGHT; ++q)
+      if (st->ev_slot[q][k]) (void)hipEventDestroy(st->ev_slot[q][k]);
   }
   if (st->ev_main) (void)hipEventDestroy(st->ev_main);
   for (ProfEntry& e : st->prof_pool) {
@@ -686,8 +693,11 @@ int stage_set_forward_streams(tp_stage* st, void* const* hip_streams, int32_t co
   }
   if (int rc = join_forwards(st)) return rc;  // streams given earlier are drained into the stage's first
   if (count > 0 && !st->ev_main) HIP_TRY(hipEventCreateWithFlags(&st->ev_main, hipEventDisableTiming));
-  for (int k = 0; k < count; ++k)
+  for (int k = 0; k < count; ++k) {
     if (!st->ev_fwd[k]) HIP_TRY(hipEventCreateWithFlags(&st->ev_fwd[k], hipEventDisableTiming));
+    for (int q = 0; q < st->desc.max_in_flight; ++q)
+      if (!st->ev_slot[q][k]) HIP_TRY(hipEventCreateWithFlags(&st->ev_slot[q][k], hipEventDisableTiming));
+  }
   for (int k = 0; k < TP_MAX_FORWARD_STREAMS; ++k) st->fwd_stream[k] = k < count ? (hipStream_t)hip_streams[k] : nullptr;
   st->fwd_streams = count;
   st->main_dirty = true;
@@ -806,6 +816,7 @@ int forward_impl(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_de
       nf.pinned = true;
     }
     st->act_used[q] = true;
+    for (int k = 0; k < TP_MAX_FORWARD_STREAMS; ++k) st->slot_fwd[q][k] = false;
     st->inflight.push_back(nf);
     f = &st->inflight.back();
   }
@@ -828,23 +839,34 @@ int forward_impl(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_de
       if (int rc = old_version_copy(st, v, slot, &wcopy)) return rc;
   }
   char* aslot = st->act_slot(f->act_slot);
-  // With S forward streams of the caller's, micro-batch ub runs on the stage's stream if ub % (S + 1) is 0 and on
-  // forward stream ub % (S + 1) - 1 otherwise (not while kernels are timed one by one).  Every stream's forwards start
-  // behind everything the stage's stream held before this run of forwards.
+  // With S forward streams of the caller's, micro-batch ub runs on forward stream ub % S and the stage's own stream
+  // runs no forward, so that the backward pass of an earlier mini-batch can go on there meanwhile (not while kernels
+  // are timed one by one).  A stage that holds one mini-batch at a time has no such backward pass: there the stage's
+  // own stream takes a turn too (ub % (S + 1) == 0).  Every stream's forwards start behind everything the stage's
+  // stream held before this run of forwards.
   hipStream_t fs = st->stream;
   int fsk = -1;  // index of the forward stream in use
+  const int act_q = f->act_slot;
   if (st->fwd_streams > 0 && !st->prof_on) {
     if (st->main_dirty) {
       HIP_TRY(hipEventRecord(st->ev_main, st->stream));
       st->main_dirty = false;
     }
-    fsk = (int)(ub_idx % (uint32_t)(st->fwd_streams + 1)) - 1;
+    fsk = d.max_in_flight == 1 ? (int)(ub_idx % (uint32_t)(st->fwd_streams + 1)) - 1 : (int)(ub_idx % (uint32_t)st->fwd_streams);
     if (fsk >= 0) {
       HIP_TRY(hipStreamWaitEvent(st->fwd_stream[fsk], st->ev_main, 0));
       fs = st->fwd_stream[fsk];
       st->fwd_pending[fsk] = true;
     }
   }
+  // however the call ends, what it enqueued on a forward stream is what the mini-batch's backward pass waits for
+  struct MarkForward {
+    tp_stage* st; int q, k; hipStream_t s;
+    ~MarkForward() {
+      if (k < 0) return;
+      if (hipEventRecord(st->ev_slot[q][k], s) == hipSuccess) st->slot_fwd[q][k] = true;
+    }
+  } mark_forward{st, act_q, fsk, fs};
   const uint64_t row0 = (uint64_t)ub_idx * d.mb;
   const int L = d.num_layers;
   for (int l = 0; l < L; ++l) {
@@ -1029,7 +1051,14 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
   if (delta_used) *delta_used = delta;
 
   if (!st->dry) {
-    if (int rc = join_forwards(st)) return rc;
+    // The stage's stream waits for the forwards of THIS mini-batch only: forwards of later mini-batches may still be
+    // running on the forward streams and go on beside this pass (they share no buffer with it).
+    st->main_dirty = true;
+    for (int k = 0; k < TP_MAX_FORWARD_STREAMS; ++k)
+      if (st->slot_fwd[f->act_slot][k]) {
+        HIP_TRY(hipStreamWaitEvent(st->stream, st->ev_slot[f->act_slot][k], 0));
+        st->slot_fwd[f->act_slot][k] = false;
+      }
     const size_t es = st->plan.elt_size;
     const uint64_t P = st->plan.sizes.param_count;
     const char* wb;

@@ -51,9 +51,9 @@ class GpuStage:
                  ring_capacity: Optional[int] = None, max_in_flight: Optional[int] = None,
                  needs_dx: Optional[bool] = None, device="cuda:0", stream: Optional[torch.cuda.Stream] = None,
                  forward_stream=False):
-        """forward_stream: False / 0, or how many further streams (default priority; True = 1) the stage gets for the
-        forward passes of a mini-batch's micro-batches; what runs there is ordered on the stage's stream by
-        forward_join() or any later call other than a forward."""
+        """forward_stream: False / 0, or how many streams (default priority; True = 1) the stage gets for the forward
+        passes; what runs there is ordered on the stage's stream by forward_join() or any later call other than a
+        forward or a backward (a backward waits for the forwards of its own mini-batch only)."""
         self.layers = [tuple(l) for l in layers]
         self.in_elems = B.layer_in_elems(self.layers[0])      # values per sample in / out of the stage
         self.out_elems = B.layer_out_elems(self.layers[-1])

@@ -276,7 +276,8 @@ def run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, depth
             for pi, (a, b) in enumerate(zip(ost.m, opure.m)):
                 if np.linalg.norm(b) > 0:
                     floor_of(f"m[{pi}]", a, b)
-        assert st.blend_update(j, j + 1) == ost.latest
+        # with one mini-batch in flight the next one has not been forwarded yet: no look-ahead blend
+        assert (st.blend_update(j, j + 1) if depth > 1 else st.blend_update(j)) == ost.latest
         m_rms = float(np.sqrt(np.mean(np.concatenate([r.reshape(-1) for r in ost.m]) ** 2)))
         for pi, (got, ref, mg, mr) in enumerate(zip(st.unpack(to_np(st.export(ost.latest))), ost.weights[ost.latest],
                                                     st.unpack(to_np(st.momentum)), ost.m)):

@@ -1,5 +1,6 @@
-"""The forward passes of a mini-batch's micro-batches on several streams (stage_set_forward_streams): the same bits
-as on one stream, parity with the oracle, the joins that order the forward streams' results, and the refusals."""
+"""The forward passes on streams of their own (stage_set_forward_streams) -- the micro-batches of a mini-batch side by
+side, and beside the backward pass of an earlier mini-batch on the stage's stream: the same bits as with everything
+on one stream, parity with the oracle, the joins that order the forward streams' results, and the refusals."""
 import numpy as np
 import pytest
 
@@ -14,13 +15,13 @@ def test_dense_stage_parity_with_second_forward_stream(dtype):
     # five micro-batches (the last even one has no partner), ragged widths in fp32 and matrix-core shapes in bf16
     dims = (72, 200, 48) if dtype == "f32" else (256, 512, 128)
     specs = (W.Dense(dims[0], dims[1], "gelu"), W.Dense(dims[1], dims[1], "relu"), W.Dense(dims[1], dims[2], "none"))
-    print(dtype, _run_stage(specs, f"fwd2_mlp_{dtype}", dtype, mb=64, n=5, depth=3, minibatches=4, forward_stream=True))
+    print(dtype, _run_stage(specs, f"fwd2_mlp_{dtype}", dtype, mb=64, n=5, depth=3, minibatches=4, forward_stream=2))
 
 
 def test_conv_pool_stage_parity_with_second_forward_stream():
     w = W.vgg_stage0(mb=4, n=4, size=16, c1=64, c2=64)
     print(_run_stage(w.stages[0], "fwd2_vgg", "bf16", mb=w.mb, n=w.n, depth=2, minibatches=3, needs_dx=False,
-                     mean_loss_dy=True, lr=0.01, forward_stream=True))
+                     mean_loss_dy=True, lr=0.01, forward_stream=2))
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -31,18 +32,28 @@ def test_bottleneck_stage_parity_with_four_forward_streams(dtype):
     print(dtype, _run_stage(specs, f"fwd2_bneck_{dtype}", dtype, mb=4, n=4, depth=3, minibatches=3, forward_stream=3))
 
 
+def test_last_stage_own_stream_takes_a_turn_bf16():
+    # one mini-batch in flight (pipeline depth 1): the backward pass needs the forwards just enqueued, so the stage's
+    # own stream runs micro-batches 0 and 4, three forward streams the others; loss-free head: pooling + classifier
+    specs = W.resnet_head_stage(c=96, mid=24, h=2, blocks=1, classes=10, act="gelu")
+    print(_run_stage(specs, "fwd_last_stage", "bf16", mb=16, n=5, depth=1, minibatches=3, stage_index=3,
+                     storage_floor=True, forward_stream=3))
+
+
 def test_streaming_normalisation_on_both_streams_bf16():
     # 9000 rows per micro-batch: statistics, finalize and normalise kernels with partial sums in scratch memory
     specs = (W.Dense(8, 16, "none", tokens=3000), W.BatchNorm(16, 3000, "gelu"),
              W.Dense(16, 8, "none", tokens=3000), W.BatchNorm(8, 3000, "none"))
-    print(_run_stage(specs, "fwd2_bn_rows", "bf16", mb=3, n=4, forward_stream=True))
+    print(_run_stage(specs, "fwd2_bn_rows", "bf16", mb=3, n=4, forward_stream=3))
 
 
 def _drive(st, w, s, steps, join_before_read):
+    """bench.py's order of calls: backward, update, then the forwards of a later mini-batch -- whose outputs are read
+    only at the end, so that with forward streams they are still under way when the next backward pass is enqueued."""
     import torch
     rows = w.n * w.mb
     depth = w.K - s
-    outs = []
+    outs, ys = [], []
     xs = [torch.from_numpy(W.stage_input(w, s, j).reshape(rows, -1)).cuda().to(st.tdtype) for j in range(steps + depth)]
     dys = [torch.from_numpy(W.stage_upstream_grad(w, s, j, mean_loss=True).reshape(rows, -1)).cuda().to(st.tdtype)
            for j in range(steps)]
@@ -52,19 +63,20 @@ def _drive(st, w, s, steps, join_before_read):
         y = torch.empty(rows, st.out_elems, dtype=st.tdtype, device="cuda")
         for ub in range(w.n):
             st.forward(j, ub, xs[j][ub * w.mb:(ub + 1) * w.mb], y[ub * w.mb:(ub + 1) * w.mb])
-        if join_before_read:
-            st.forward_join()
-        outs.append(y.float().cpu().numpy())
+        ys.append(y)
 
     for j in range(depth):
         forward(j)
     for j in range(steps):
-        dx, _ = st.backward(j, dys[j])                      # joins by itself
+        dx, _ = st.backward(j, dys[j])                      # waits for the forwards of mini-batch j, not for the later ones
         outs.append(dx.float().cpu().numpy())
         outs.append(st.grad.cpu().numpy().copy())
-        st.blend_update(j, j + 1)
+        st.blend_update(j, j + 1)                           # waits for every forward
         outs.append(st.export(j + 1).cpu().numpy())
         forward(j + depth)
+    if join_before_read:
+        st.forward_join()
+    outs.extend(y.float().cpu().numpy() for y in ys)
     return outs
 
 
