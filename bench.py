@@ -35,8 +35,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 #            profiles/bench_mlp4096_stage1_kernel_stats.md
 MEASURED_TRAFFIC_BYTES = {"fprop": 56.1e6, "dgrad": 159.5e6, "wgrad": 168.0e6, "update": 940.1e6,
                           "act_bwd": 52.5e6, "colsum": 19.0e6}
-ROCPROF_AVG_US = {"fprop": 18.69, "dgrad": 64.16, "wgrad": 63.88, "update": 164.18, "act_bwd": 12.83}
-PROFILED_AT = "02ef2bf"
+ROCPROF_AVG_US = {"fprop": 18.51, "dgrad": 68.31, "wgrad": 66.57, "update": 162.72, "act_bwd": 12.89}
+PROFILED_AT = "8a38374"
 
 
 def parse():
