@@ -423,6 +423,7 @@ struct tp_stage {
   // its backward pass waits for -- and for no other, so that forwards of later mini-batches run beside it
   hipEvent_t ev_slot[TP_MAX_IN_FLIGHT][TP_MAX_FORWARD_STREAMS] = {};
   bool slot_fwd[TP_MAX_IN_FLIGHT][TP_MAX_FORWARD_STREAMS] = {};
+  bool slot_event_lost = false;  // such an event could not be recorded: the next backward pass waits for every forward stream
 
   int find_slot(uint64_t v) const {
     const Slot& s = slots[v % desc.ring_capacity];
@@ -865,6 +866,7 @@ int forward_impl(tp_stage* st, uint64_t mb_id, uint32_t ub_idx, const void* x_de
     ~MarkForward() {
       if (k < 0) return;
       if (hipEventRecord(st->ev_slot[q][k], s) == hipSuccess) st->slot_fwd[q][k] = true;
+      else st->slot_event_lost = true;
     }
   } mark_forward{st, act_q, fsk, fs};
   const uint64_t row0 = (uint64_t)ub_idx * d.mb;
@@ -1054,6 +1056,10 @@ int backward_impl(tp_stage* st, uint64_t mb_id, const void* dy_dev, void* dx_dev
     // The stage's stream waits for the forwards of THIS mini-batch only: forwards of later mini-batches may still be
     // running on the forward streams and go on beside this pass (they share no buffer with it).
     st->main_dirty = true;
+    if (st->slot_event_lost) {
+      if (int rc = join_forwards(st)) return rc;
+      st->slot_event_lost = false;
+    }
     for (int k = 0; k < TP_MAX_FORWARD_STREAMS; ++k)
       if (st->slot_fwd[f->act_slot][k]) {
         HIP_TRY(hipStreamWaitEvent(st->stream, st->ev_slot[f->act_slot][k], 0));

@@ -347,6 +347,15 @@ def test_stem_and_head_descriptions():
     B.stage_workspace_query(B.make_desc([("avg", 8, 4), (8, 4, "none")], **good))
 
 
+def test_forward_streams_need_a_stage_that_launches():
+    h = _dry_stage(2, 0, "convex")
+    with pytest.raises(B.StageLibError) as ei:
+        B.stage_set_forward_streams(h, [1234])
+    assert ei.value.code == B.TP_ESTATE
+    B.stage_forward_join(h)                                   # nothing to wait for: accepted
+    B.stage_destroy(h)
+
+
 def test_workspace_layout():
     d = B.make_desc([(256, 512, "relu"), (512, 10, "none")], dtype="bf16", mb=32, n=4, stage_index=0, num_stages=2,
                     ring_capacity=2, max_in_flight=2, policy="convex", needs_dx=False, lam=0.1, lr=0.01, momentum=0.9)
