@@ -399,19 +399,22 @@ def resnet_head_stage(c: int = 2048, mid: int = 512, h: int = 2, blocks: int = 2
 
 
 def resnet_stages(mb: int = 128, n: int = 4, dtype: str = "bf16", scale: int = 1, size: int = 64, classes: int = 200,
-                  act: str = "relu") -> Workload:
+                  act: str = "relu", identity: tuple = (2, 3, 5, 2)) -> Workload:
     """All four stages of a ResNet-50-style bottleneck net on size x size x 3 images: {stem, conv2_x}, {conv3_x},
-    {conv4_x}, {conv5_x, average pooling, classifier}.  scale divides every channel count (reduced copies the CPU
-    oracle finishes in seconds keep the structure: 3 + 4 + 6 + 3 bottlenecks, strides, projection shortcuts)."""
+    {conv4_x}, {conv5_x, average pooling, classifier}.  scale divides every channel count and `identity` gives the
+    identity bottlenecks behind the first (projection) bottleneck of each group -- reduced copies the CPU oracle
+    finishes in seconds keep the structure: strides, projection shortcuts, 3 + 4 + 6 + 3 bottlenecks by default."""
     c = 64 // scale
     q = size // 4
-    s0 = resnet_stem_stage(size, c, c, 4 * c, 2, act)
+    s0 = resnet_stem_stage(size, c, c, 4 * c, identity[0], act)
     s1 = bottleneck_down_block(4 * c, 2 * c, 8 * c, q, q, act) + tuple(
-        l for _ in range(3) for l in bottleneck_block(8 * c, 2 * c, q // 2, q // 2, act))
+        l for _ in range(identity[1]) for l in bottleneck_block(8 * c, 2 * c, q // 2, q // 2, act))
     s2 = bottleneck_down_block(8 * c, 4 * c, 16 * c, q // 2, q // 2, act) + tuple(
-        l for _ in range(5) for l in bottleneck_block(16 * c, 4 * c, q // 4, q // 4, act))
-    s3 = resnet_head_stage(32 * c, 8 * c, q // 8, 2, classes, act)
-    return Workload(name=f"resnet{size}_c{c}_{dtype}_k4", dtype=dtype, stages=(s0, s1, s2, s3), mb=mb, n=n, classes=classes)
+        l for _ in range(identity[2]) for l in bottleneck_block(16 * c, 4 * c, q // 4, q // 4, act))
+    s3 = resnet_head_stage(32 * c, 8 * c, q // 8, identity[3], classes, act)
+    tag = "" if tuple(identity) == (2, 3, 5, 2) else "_i" + "".join(str(i) for i in identity)
+    return Workload(name=f"resnet{size}_c{c}{tag}_{dtype}_k4", dtype=dtype, stages=(s0, s1, s2, s3), mb=mb, n=n,
+                    classes=classes)
 
 
 def transformer_block(d: int, heads: int, ffn: int, tokens: int) -> tuple:

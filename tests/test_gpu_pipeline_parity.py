@@ -32,8 +32,16 @@ def _run_and_compare(w, policy, num_mb, fuse=True, tol=None):
         """The whole arena and every weight matrix and bias vector in it on its own (a wrong bias vector is a few
         thousand of millions of values: invisible in the norm of the whole arena)."""
         note(name, rel_err(got_arena, ref_arena))
+        # A gradient tensor whose true value is zero -- a bias in front of a batch normalisation: the mean subtraction
+        # removes it, what is left is the cancellation noise of a sum of terms that add up to zero -- has no scale of
+        # its own, and neither have the momentum and the bias built from it (zero plus steps of noise): such tensors are
+        # measured against the typical entry of the whole arena instead.
+        rms = float(np.sqrt(np.mean(np.asarray(ref_arena, dtype=np.float64) ** 2)))
         for pi, (got, ref) in enumerate(zip(st.unpack(got_arena), st.unpack(ref_arena))):
-            if np.linalg.norm(ref) > 0:
+            floor = rms * np.sqrt(ref.size)
+            if 0 < np.linalg.norm(ref) < 0.05 * floor:
+                note(f"{name}[{pi}]", float(np.linalg.norm(np.asarray(got, dtype=np.float64).reshape(-1) - ref.reshape(-1)) / floor))
+            elif np.linalg.norm(ref) > 0:
                 note(f"{name}[{pi}]", rel_err(got, ref))
             else:
                 assert np.linalg.norm(got) == 0, (name, pi)
@@ -135,3 +143,16 @@ def test_single_sample_single_microbatch():
     w = W.Workload(name="one", dtype="f32", stages=((W.Dense(3, 4, "relu"),), (W.Dense(4, 2, "none"),)),
                    mb=1, n=1, classes=2)
     _run_and_compare(w, "eq1", 4)
+
+
+@pytest.mark.parametrize("policy", ["convex", "latest"])
+def test_resnet_reduced_fp32_four_stage_pipeline(policy):
+    # every stage of the ResNet-style net at an eighth of its channels on 64x64x3 images: 7x7 stride-2 stem, pooling,
+    # conv2_x | conv3_x | conv4_x | conv5_x, global average pooling, classifier, softmax-CE loss; per group the first
+    # bottleneck with its stride and projection shortcut and one identity bottleneck (with the full 3 + 4 + 6 + 3 the
+    # fp32 rounding of ~150 layers with batch statistics over a few hundred values reaches 1.5e-4 on a gradient
+    # tensor or two), batch normalisation per micro-batch, staleness up to 3.  GELU in place of the ReLUs: at fp32
+    # tolerance a pre-activation within rounding distance of a kink would decide
+    w = W.resnet_stages(mb=16, n=2, dtype="f32", scale=8, size=64, classes=10, act="gelu", identity=(1, 1, 1, 1))
+    worst = _run_and_compare(w, policy, 6)
+    print(policy, {k: v for k, v in worst.items() if "[" not in k})
