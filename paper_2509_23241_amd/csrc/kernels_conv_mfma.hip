@@ -15,7 +15,8 @@
 // Needs: image height and width powers of two (pixel -> (h, w) by shift and mask), channel counts
 // that are multiples of 64, pixel count a multiple of 64.  Everything else goes to the generic
 // kernels of kernels_conv.hip.  Stride 2 runs on the gather kernels only: the rows (fprop, wgrad:
-// output pixels; dgrad: input pixels) and the pixels they read live on grids of different size.
+// output pixels; dgrad: input pixels, one parity class at a time) and the pixels they read live on grids of
+// different size.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -46,17 +47,10 @@ struct GatherDesc {
   int SH, SW;             // image size of the source grid (= H, W at stride 1)
 };
 
-// Source pixel of grid position (h, w) moved by (dh, dw), for stride S.  Forward (fprop, wgrad): the
-// position is an output pixel and reads the input at S*(h, w) + (dh, dw).  Backward (dgrad): the
-// position is an input pixel and reads dz at ((h, w) + (dh, dw)) / S where that is whole.
-template <int S, bool BACKWARD>
+// Source pixel of output position (h, w) for tap offset (dh, dw) at stride S (fprop, wgrad): the input at
+// S*(h, w) + (dh, dw).  (The input gradient at stride 2 goes by parity class of the input pixels: RowGatherS2.)
+template <int S>
 __device__ __forceinline__ bool source_pixel(int h, int w, int dh, int dw, int SH, int SW, int& sh, int& sw) {
-  if (BACKWARD) {
-    const int nh = h + dh, nw = w + dw;
-    sh = nh / S;
-    sw = nw / S;
-    return nh >= 0 && nw >= 0 && nh % S == 0 && nw % S == 0 && sh < SH && sw < SW;
-  }
   sh = h * S + dh;
   sw = w * S + dw;
   return (unsigned)sh < (unsigned)SH && (unsigned)sw < (unsigned)SW;
@@ -105,7 +99,8 @@ struct RowGather {
       off = (long)pix_off[t] + ((long)(dh * d.W + dw) * d.C + c0) * 2;
     } else {
       int sh, sw;
-      valid = source_pixel<S, BACKWARD>(hw[t] >> 16, hw[t] & 0xffff, dh, dw, d.SH, d.SW, sh, sw);
+      static_assert(!BACKWARD || S == 1, "the stride-2 input gradient runs on RowGatherS2");
+      valid = source_pixel<S>(hw[t] >> 16, hw[t] & 0xffff, dh, dw, d.SH, d.SW, sh, sw);
       off = (long)pix_off[t] + ((long)(sh * d.SW + sw) * d.C + c0) * 2;
     }
     const char* src = valid ? (const char*)d.base + off : (const char*)d.zeros + zoff;
@@ -215,7 +210,7 @@ struct ColGather {
       off = ((long)p + dh * d.W + dw) * d.C * 2 + coff[t];
     } else {
       int sh, sw;
-      valid = source_pixel<S, false>((p >> d.lw) & (d.H - 1), p & (d.W - 1), dh, dw, d.SH, d.SW, sh, sw);
+      valid = source_pixel<S>((p >> d.lw) & (d.H - 1), p & (d.W - 1), dh, dw, d.SH, d.SW, sh, sw);
       const int img = p / (d.H * d.W);
       off = (((long)img * d.SH + sh) * d.SW + sw) * d.C * 2 + coff[t];
     }
