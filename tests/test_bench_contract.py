@@ -44,6 +44,24 @@ def test_algorithmic_work_of_a_strided_convolution():
     assert bench.layer_work("wgrad", W.Subsample2(256, 8, 8), 512, 128) == (0.0, 0.0)
 
 
+def test_algorithmic_work_of_the_stem_and_head_layers():
+    import bench
+    from synth_inputs import workloads as W
+    stem = W.Conv2d(3, 64, 64, 64, "none", k=7, stride=2, pad=3)
+    fl, by = bench.layer_work("fprop", stem, rows=512, mb=128)
+    assert fl == 2.0 * 128 * 1024 * (49 * 3) * 64                                    # 32 x 32 output pixels, 49 taps
+    assert by == 2.0 * (128 * 4096 * 3 + 49 * 3 * 64 + 2 * 128 * 1024 * 64)
+    fl, _ = bench.layer_work("wgrad", stem, rows=512, mb=128)
+    assert fl == 2.0 * 512 * 1024 * 147 * 64
+    assert bench.layer_work("fprop", W.AvgPool(2048, 4), 512, 128) == (0.0, 0.0)
+    w = W.resnet_stages()
+    _, by = bench.kernel_work("pool", w, 3, True)                                    # stage 3: one subsampling, the average pooling
+    sub = 2.0 * 512 * (1024 * 16 / 2) + 2.0 * 512 * (1024 * 16 / 4 + 1024 * 16)
+    avg = 2 * 2.0 * 512 * (2048 * 4 + 2048)
+    assert by == sub + avg
+    assert bench.kernel_work("dgrad", w, 0, False)[0] < bench.kernel_work("dgrad", w, 0, True)[0]   # no input gradient of the stem
+
+
 @pytest.mark.gpu
 def test_bench_prints_one_json_line_with_the_contract_keys():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "3", "--warmup", "1", "--width", "512",
