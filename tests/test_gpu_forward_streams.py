@@ -47,6 +47,24 @@ def test_streaming_normalisation_on_both_streams_bf16():
     print(_run_stage(specs, "fwd2_bn_rows", "bf16", mb=3, n=4, forward_stream=3))
 
 
+_INPUTS = {}
+
+
+def _inputs(st, w, s, steps):
+    """Synthetic inputs and upstream gradients of the run, on the device and complete; made once per workload."""
+    import torch
+    key = (w.name, s, steps, st.tdtype)
+    if key not in _INPUTS:
+        _INPUTS.clear()
+        rows, depth = w.n * w.mb, w.K - s
+        xs = [torch.from_numpy(W.stage_input(w, s, j).reshape(rows, -1)).cuda().to(st.tdtype) for j in range(steps + depth)]
+        dys = [torch.from_numpy(W.stage_upstream_grad(w, s, j, mean_loss=True).reshape(rows, -1)).cuda().to(st.tdtype)
+               for j in range(steps)]
+        torch.cuda.synchronize()
+        _INPUTS[key] = (xs, dys)
+    return _INPUTS[key]
+
+
 def _drive(st, w, s, steps, join_before_read):
     """bench.py's order of calls: backward, update, then the forwards of a later mini-batch -- whose outputs are read
     only at the end, so that with forward streams they are still under way when the next backward pass is enqueued."""
@@ -54,10 +72,7 @@ def _drive(st, w, s, steps, join_before_read):
     rows = w.n * w.mb
     depth = w.K - s
     outs, ys = [], []
-    xs = [torch.from_numpy(W.stage_input(w, s, j).reshape(rows, -1)).cuda().to(st.tdtype) for j in range(steps + depth)]
-    dys = [torch.from_numpy(W.stage_upstream_grad(w, s, j, mean_loss=True).reshape(rows, -1)).cuda().to(st.tdtype)
-           for j in range(steps)]
-    torch.cuda.synchronize()
+    xs, dys = _inputs(st, w, s, steps)
 
     def forward(j):
         y = torch.empty(rows, st.out_elems, dtype=st.tdtype, device="cuda")
@@ -71,7 +86,10 @@ def _drive(st, w, s, steps, join_before_read):
         dx, _ = st.backward(j, dys[j])                      # waits for the forwards of mini-batch j, not for the later ones
         outs.append(dx.float().cpu().numpy())
         outs.append(st.grad.cpu().numpy().copy())
-        st.blend_update(j, j + 1)                           # waits for every forward
+        if depth > 1:
+            st.blend_update(j, j + 1)                       # waits for every forward
+        else:
+            st.blend_update(j)                              # one mini-batch in flight: the next one is not there yet
         outs.append(st.export(j + 1).cpu().numpy())
         forward(j + depth)
     if join_before_read:
@@ -111,6 +129,32 @@ def test_two_streams_give_the_bits_of_one_bottleneck_stage():
     for other in results[1:]:
         for a, b in zip(results[0], other):
             assert np.array_equal(a, b)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("which", ["mlp", "conv4_x", "head"])
+def test_full_size_stages_in_the_order_of_calls_of_the_benchmark(which):
+    # the stages bench.py times, at their full sizes and with its streams, in its order of calls (the forwards of a
+    # later mini-batch still under way when the next backward pass is enqueued): every output, input gradient,
+    # gradient arena and weight version bit for bit what the same calls give on the stage's stream alone
+    from paper_2509_23241_amd.runner import GpuStage, layer_tuple
+    if which == "mlp":
+        w, s, streams = W.mlp_wide(width=4096, mb=256, n=8), 1, 2
+    elif which == "conv4_x":
+        w, s, streams = W.resnet_middle_stages(mb=128, n=4), 2, 2
+    else:
+        w, s, streams = W.resnet_stages(mb=128, n=4), 3, 3
+    layers = [layer_tuple(l) for l in w.stages[s]]
+    results = []
+    for extra in (0, streams):
+        st = GpuStage(layers, W.init_params(w, s), dtype=w.dtype, mb=w.mb, n=w.n, stage_index=s, num_stages=w.K,
+                      policy="convex", lam=w.lam, lr=w.lr, momentum=w.momentum, forward_stream=extra)
+        results.append(_drive(st, w, s, steps=2, join_before_read=extra > 0))
+        st.close()
+    _INPUTS.clear()
+    assert len(results[0]) == len(results[1])
+    for a, b in zip(*results):
+        assert np.array_equal(a, b)
 
 
 def test_saved_inputs_of_odd_micro_batches_are_ordered_by_the_accessor():

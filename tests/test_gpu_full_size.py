@@ -1,4 +1,6 @@
-"""GPU parity at the full sizes that bench.py times, in its launch configuration: the interior
+"""GPU parity at the full sizes that bench.py times, in its launch configuration (the forwards on two streams of
+their own; what differs from bench.py is that the outputs are read after every mini-batch's forwards, so the next
+backward pass starts behind them -- tests/test_gpu_forward_streams.py covers forwards still under way beside it): the interior
 stage of the width-4096 GELU MLP (micro-batch 256 x 8, pipeline depth 3) and stage 0 of the
 VGG-style net on 32x32x3 images (micro-batch 64 x 4, depth 4).  The fp64 oracle is small enough at
 these sizes to run whole (a few seconds per mini-batch on the host), so every output element is
@@ -20,7 +22,7 @@ def test_mlp4096_interior_stage_full_size():
     w = W.mlp_wide(width=4096, mb=256, n=8)
     t0 = time.time()
     worst = _run_stage(w.stages[1], "mlp4096_full", "bf16", mb=w.mb, n=w.n, policy="convex", depth=3, minibatches=3,
-                       needs_dx=True, lr=w.lr)
+                       needs_dx=True, lr=w.lr, forward_stream=2)
     print(f"{time.time() - t0:.1f} s", worst)
 
 
@@ -31,7 +33,7 @@ def test_vgg_stage0_full_size():
     w = W.vgg_stage0(mb=64, n=4)
     t0 = time.time()
     worst = _run_stage(w.stages[0], "vgg32_full", "bf16", mb=w.mb, n=w.n, policy="convex", depth=4, minibatches=5,
-                       needs_dx=False, lr=w.lr, lam=w.lam, mean_loss_dy=True)
+                       needs_dx=False, lr=w.lr, lam=w.lam, mean_loss_dy=True, forward_stream=2)
     print(f"{time.time() - t0:.1f} s", worst)
 
 
@@ -58,7 +60,7 @@ def test_conv4_group_whole_full_geometry(act, fixed):
     t0 = time.time()
     worst = _run_stage(w.stages[1], f"conv4x_whole_{act}", "bf16", mb=w.mb, n=w.n, policy="convex", depth=2, minibatches=2,
                        needs_dx=True, lr=w.lr, lam=w.lam, mean_loss_dy=True, fixed_masks=fixed, stage_index=2,
-                       storage_floor=(act == "gelu"))
+                       storage_floor=(act == "gelu"), forward_stream=2)
     print(f"{time.time() - t0:.1f} s", {k: v for k, v in worst.items() if "[" not in k})
 
 
@@ -100,7 +102,8 @@ def test_stem_stage_full_geometry(act, fixed):
     t0 = time.time()
     n = w.n if act == "gelu" else 2      # the second form on half the mini-batch: the oracle's time goes with it
     worst = _run_stage(specs, f"stem_full_{act}", "bf16", mb=w.mb, n=n, policy="convex", depth=2, minibatches=2,
-                       needs_dx=False, lr=w.lr, lam=w.lam, mean_loss_dy=True, fixed_masks=fixed, storage_floor=True)
+                       needs_dx=False, lr=w.lr, lam=w.lam, mean_loss_dy=True, fixed_masks=fixed, storage_floor=True,
+                       forward_stream=2)
     print(f"{time.time() - t0:.1f} s", {k: v for k, v in worst.items() if "[" not in k})
 
 
@@ -116,7 +119,8 @@ def test_head_stage_full_geometry(act):
     specs = W.resnet_head_stage(2048, 512, 2, 2, 200, act)
     t0 = time.time()
     worst = _run_stage(specs, f"head_full_{act}", "bf16", mb=w.mb, n=w.n, policy="convex", depth=2, minibatches=2,
-                       needs_dx=True, lr=w.lr, lam=w.lam, mean_loss_dy=True, stage_index=2, storage_floor=(act == "gelu"))
+                       needs_dx=True, lr=w.lr, lam=w.lam, mean_loss_dy=True, stage_index=2, storage_floor=(act == "gelu"),
+                       forward_stream=2)
     print(f"{time.time() - t0:.1f} s", {k: v for k, v in worst.items() if "[" not in k})
 
 
