@@ -25,3 +25,13 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def progress(capsys):
+    """A callable for tests that take a minute or more: progress("step") writes a short note past pytest's capture
+    when a step of the test is done, so that a long test is not silent from start to end."""
+    def say(msg):
+        with capsys.disabled():
+            print(f" [{msg}]", end="", flush=True)
+    return say

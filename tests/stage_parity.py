@@ -65,7 +65,7 @@ def fix_relu_masks(specs, params, x, margin=4.0):
 
 def run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, depth=2, needs_dx=True, lr=None,
               lam=0.4, params=None, mean_loss_dy=False, fixed_masks=False, pure_oracle=False, stage_index=0,
-              check_saved=True, storage_floor=False, forward_stream=False):
+              check_saved=True, storage_floor=False, forward_stream=False, progress=None):
     """Steady schedule of a stage of pipeline depth `depth`: forwards run `depth` mini-batches ahead.
 
     The fp32 runs take large steps (lr 0.05): at tolerance 1e-4 any mix-up of weight versions in the
@@ -87,7 +87,10 @@ def run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, depth
     the tolerance nothing changes.
 
     forward_stream: the stage gets a second stream for the forward passes of odd micro-batches; their results are
-    read after stage_forward_join."""
+    read after stage_forward_join.
+
+    progress: called with a short text after every forward, backward and update of a mini-batch (the tests that take
+    a minute or more at full size report through it)."""
     if lr is None:
         lr = 0.05 if dtype == "f32" else 0.002
     import torch
@@ -235,8 +238,10 @@ def run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, depth
         else:
             flipped[j] = 0.0 if smooth else 1.0
 
+    progress = progress or (lambda msg: None)
     for j in range(depth):
         forward(j)
+        progress(f"{w_name} forward {j}")
     for j in range(minibatches):
         dy = W.stage_upstream_grad(w, 0, j, mean_loss=mean_loss_dy)
         dx_ref = ost.backward(j, dy)
@@ -250,6 +255,7 @@ def run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, depth
                     floor_of(f"g[{pi}]", a, b)
         dx, delta = st.backward(j, torch.from_numpy(dy.reshape(n * mb, -1)).cuda().to(st.tdtype))
         assert delta == ost.trace[-1][4]
+        progress(f"{w_name} backward {j}")
         # gradient tensors of a mini-batch in which a fraction e of the decisions differed: TOL + 4 sqrt(e)
         e = flipped.pop(j) if bf16 else 0.0
         gtol = min(0.25, tol + 4.0 * np.sqrt(e)) if e > 0 else tol
@@ -288,7 +294,9 @@ def run_stage(specs, w_name, dtype, mb, n, policy="convex", minibatches=3, depth
             else:
                 note(f"m[{pi}]", rel_err(mg, mr), limit=gtol_m[0])
         note("W_new", rel_err(to_np(st.export(ost.latest)), oracle_flat_to_arena(st, ost.flat(ost.weights[ost.latest]))))
+        progress(f"{w_name} update {j}")
         forward(j + depth)
+        progress(f"{w_name} forward {j + depth}")
     st.close()
     assert not failures, (failures, worst)
     return worst

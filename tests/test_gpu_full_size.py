@@ -18,37 +18,37 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.timeout(900)
-def test_mlp4096_interior_stage_full_size():
+def test_mlp4096_interior_stage_full_size(progress):
     w = W.mlp_wide(width=4096, mb=256, n=8)
     t0 = time.time()
     worst = _run_stage(w.stages[1], "mlp4096_full", "bf16", mb=w.mb, n=w.n, policy="convex", depth=3, minibatches=3,
-                       needs_dx=True, lr=w.lr, forward_stream=2)
+                       needs_dx=True, lr=w.lr, forward_stream=2, progress=progress)
     print(f"{time.time() - t0:.1f} s", worst)
 
 
 @pytest.mark.timeout(900)
-def test_vgg_stage0_full_size():
+def test_vgg_stage0_full_size(progress):
     # the workload's own optimiser settings (lr 0.01, momentum 0.9); the synthetic upstream gradient is scaled like
     # that of a loss averaged over the mini-batch, the scale at which such a step is a training step
     w = W.vgg_stage0(mb=64, n=4)
     t0 = time.time()
     worst = _run_stage(w.stages[0], "vgg32_full", "bf16", mb=w.mb, n=w.n, policy="convex", depth=4, minibatches=5,
-                       needs_dx=False, lr=w.lr, lam=w.lam, mean_loss_dy=True, forward_stream=2)
+                       needs_dx=False, lr=w.lr, lam=w.lam, mean_loss_dy=True, forward_stream=2, progress=progress)
     print(f"{time.time() - t0:.1f} s", worst)
 
 
 @pytest.mark.timeout(900)
-def test_vgg_stage0_full_size_fixed_masks():
+def test_vgg_stage0_full_size_fixed_masks(progress):
     w = W.vgg_stage0(mb=64, n=4)
     t0 = time.time()
     worst = _run_stage(w.stages[0], "vgg32_full_fixed", "bf16", mb=w.mb, n=w.n, policy="convex", depth=4, minibatches=4,
-                       needs_dx=False, lr=w.lr, lam=w.lam, mean_loss_dy=True, fixed_masks=True)
+                       needs_dx=False, lr=w.lr, lam=w.lam, mean_loss_dy=True, fixed_masks=True, progress=progress)
     print(f"{time.time() - t0:.1f} s", worst)
 
 
 @pytest.mark.timeout(1200)
 @pytest.mark.parametrize("act,fixed", [("gelu", False), ("relu", True)])
-def test_conv4_group_whole_full_geometry(act, fixed):
+def test_conv4_group_whole_full_geometry(act, fixed, progress):
     # the stage bench.py --workload bneck times, whole: the strided first bottleneck [8, 8, 512] -> [4, 4, 1024] with
     # its projection shortcut and the five identity bottlenecks 1024-256-256-1024, micro-batch 128 x 4, the workload's
     # lr 0.01; two mini-batches in flight, so the second backward runs on blended weights (delta 1).  Every tensor,
@@ -60,37 +60,37 @@ def test_conv4_group_whole_full_geometry(act, fixed):
     t0 = time.time()
     worst = _run_stage(w.stages[1], f"conv4x_whole_{act}", "bf16", mb=w.mb, n=w.n, policy="convex", depth=2, minibatches=2,
                        needs_dx=True, lr=w.lr, lam=w.lam, mean_loss_dy=True, fixed_masks=fixed, stage_index=2,
-                       storage_floor=(act == "gelu"), forward_stream=2)
+                       storage_floor=(act == "gelu"), forward_stream=2, progress=progress)
     print(f"{time.time() - t0:.1f} s", {k: v for k, v in worst.items() if "[" not in k})
 
 
 @pytest.mark.timeout(900)
-def test_conv4_group_first_blocks_full_geometry_centred_relu():
+def test_conv4_group_first_blocks_full_geometry_centred_relu(progress):
     # the strided first bottleneck and one identity bottleneck at the real geometry with the workload's own ReLUs on
     # centred pre-activations: the mask decisions that differ between the two sides are counted, each must lie within
     # the rounding noise of zero, and their share bounds the gradient tolerance
     w = W.bottleneck_stage(blocks=1, down=True)
     t0 = time.time()
     worst = _run_stage(w.stages[1], "conv4x_first2_relu", "bf16", mb=w.mb, n=w.n, policy="convex", depth=3, minibatches=3,
-                       needs_dx=True, lr=w.lr, lam=w.lam, mean_loss_dy=True, stage_index=1)
+                       needs_dx=True, lr=w.lr, lam=w.lam, mean_loss_dy=True, stage_index=1, progress=progress)
     print(f"{time.time() - t0:.1f} s", {k: v for k, v in worst.items() if "[" not in k})
 
 
 @pytest.mark.timeout(900)
-def test_conv3_group_first_block_full_geometry():
+def test_conv3_group_first_block_full_geometry(progress):
     # the first block of the conv3_x group at its real geometry: [16, 16, 256] -> [8, 8, 512] with 128 middle
     # channels (32768 rows per micro-batch in front of the stride: the streaming normalisation kernels), one
     # identity block behind it
     w = W.bottleneck_stage(c=512, mid=128, h=8, w=8, blocks=1, down=True)
     t0 = time.time()
     worst = _run_stage(w.stages[1], "conv3_down_full", "bf16", mb=w.mb, n=w.n, policy="convex", depth=3, minibatches=2,
-                       needs_dx=True, lr=2e-4)
+                       needs_dx=True, lr=2e-4, progress=progress)
     print(f"{time.time() - t0:.1f} s", worst)
 
 
 @pytest.mark.timeout(1200)
 @pytest.mark.parametrize("act,fixed", [("gelu", False), ("relu", True)])
-def test_stem_stage_full_geometry(act, fixed):
+def test_stem_stage_full_geometry(act, fixed, progress):
     # stage 0 of the ResNet-style net as bench.py --workload bneck --stage 0 runs it: 64x64x3 images, 7x7 stride-2 stem
     # to 64 channels (matrix-core kernels on the padded input), batch normalisation over 131072 positions per
     # micro-batch, pooling to 16x16, then the first bottleneck of conv2_x with its projection shortcut and one
@@ -103,13 +103,13 @@ def test_stem_stage_full_geometry(act, fixed):
     n = w.n if act == "gelu" else 2      # the second form on half the mini-batch: the oracle's time goes with it
     worst = _run_stage(specs, f"stem_full_{act}", "bf16", mb=w.mb, n=n, policy="convex", depth=2, minibatches=2,
                        needs_dx=False, lr=w.lr, lam=w.lam, mean_loss_dy=True, fixed_masks=fixed, storage_floor=True,
-                       forward_stream=2)
+                       forward_stream=2, progress=progress)
     print(f"{time.time() - t0:.1f} s", {k: v for k, v in worst.items() if "[" not in k})
 
 
 @pytest.mark.timeout(1200)
 @pytest.mark.parametrize("act", ["gelu", "relu"])
-def test_head_stage_full_geometry(act):
+def test_head_stage_full_geometry(act, progress):
     # stage 3 as bench.py --workload bneck --stage 3 runs it, whole: conv5_x ([4, 4, 1024] -> [2, 2, 2048], 512 middle
     # channels: strided bottleneck with projection shortcut and two identity bottlenecks, 3x3 convolutions on 2x2
     # maps), global average pooling, classifier 2048 -> 200; micro-batch 128 x 4.  With GELU every tensor is held to
@@ -120,7 +120,7 @@ def test_head_stage_full_geometry(act):
     t0 = time.time()
     worst = _run_stage(specs, f"head_full_{act}", "bf16", mb=w.mb, n=w.n, policy="convex", depth=2, minibatches=2,
                        needs_dx=True, lr=w.lr, lam=w.lam, mean_loss_dy=True, stage_index=2, storage_floor=(act == "gelu"),
-                       forward_stream=2)
+                       forward_stream=2, progress=progress)
     print(f"{time.time() - t0:.1f} s", {k: v for k, v in worst.items() if "[" not in k})
 
 
